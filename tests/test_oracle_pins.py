@@ -1,0 +1,322 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test names the plausible oracle mistake it would catch.  Independent re-statements used here are
+written in numpy / pure Python / exact rationals and never call back into the oracle for the expected
+value.
+"""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2509_23410_amd import synth
+
+
+def bits(vals):
+    """decimal (or '-0.0') -> bf16 bit patterns; all fixture numbers are exactly representable."""
+    a = np.array([[float(v) for v in row] for row in vals], dtype=np.float32)
+    b = synth.f32_to_bf16_bits(a)
+    assert np.array_equal(synth.bf16_bits_to_f32(b), a)
+    return b
+
+
+def load(golden_dir, name):
+    with open(os.path.join(golden_dir, name)) as fh:
+        return json.load(fh)
+
+
+def relF(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+# ---------------------------------------------------------------- hand-worked example
+def test_hand_worked_pack(golden_dir):
+    """Catches: nibble order inside a byte, pos0/pos1 order, padding rule for <2 nonzeros, -0 handling,
+    tile-map polarity (the dense tile violates 2:4, so a flipped polarity cannot pack)."""
+    d = load(golden_dir, "hand_pack_example.json")
+    W = bits(d["W_hat"])
+    tm = np.array(d["tile_map"], np.uint8)
+    vals, meta = oracle.pack(W, tm, d["tile"])
+    exp_sparse = bits(d["sparse_tile_vals"]).reshape(-1)
+    exp_dense = W[:, 8:16].reshape(-1)
+    assert np.array_equal(vals, np.concatenate([exp_sparse, exp_dense]))
+    assert [f"{b:02X}" for b in meta] == d["meta_bytes_hex"]
+    # the kept -0 keeps its sign bit
+    assert vals[8] == 0x8000
+
+
+def test_hand_worked_gemm(golden_dir):
+    """Catches: transposed operand (N != K here), dropped tile, wrong K offset of a tile."""
+    d = load(golden_dir, "hand_pack_example.json")
+    W = bits(d["W_hat"])
+    tm = np.array(d["tile_map"], np.uint8)
+    vals, meta = oracle.pack(W, tm, d["tile"])
+    Y = oracle.gemm(bits(d["X"]), vals, meta, d["N"], d["K"], tm, d["tile"])
+    assert np.array_equal(Y, np.array(d["Y"], np.float64))
+
+
+def test_polarity_flip_is_rejected(golden_dir):
+    d = load(golden_dir, "hand_pack_example.json")
+    W = bits(d["W_hat"])
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.pack(W, np.array([[1, 0]], np.uint8), d["tile"])
+    assert e.value.code == oracle.ERR_NOT_24
+    assert e.value.where == (0, 8)  # first violating group: row 0, columns 8..11 = [1,1,1,1]
+
+
+# ---------------------------------------------------------------- six patterns, exact rationals
+def _six_pattern_case(golden_dir):
+    pats = load(golden_dir, "patterns_2of4.json")["patterns"]
+    N, K, t = 16, 24, 8  # 2 x 3 tiles, non-square, asymmetric map
+    tm = np.array([[0, 1, 0], [1, 0, 0]], np.uint8)
+    rng = np.random.default_rng(7)
+    # small dyadic values: every product and sum below is exact in binary64
+    Wf = rng.integers(-8, 9, size=(N, K)).astype(np.float32) / 4
+    Wf[Wf == 0] = 0.25
+    mask24 = np.zeros((N, K), np.uint8)
+    which = np.zeros((N, K // 4), np.int64)
+    for n in range(N):
+        for g in range(K // 4):
+            p = (n * 5 + g * 7 + (n // 3)) % 6
+            which[n, g] = p
+            mask24[n, 4 * g:4 * g + 4] = pats[p]["mask"]
+    assert set(which.reshape(-1)) == set(range(6))
+    Xf = rng.integers(-6, 7, size=(3, K)).astype(np.float32) / 2
+    return pats, N, K, t, tm, synth.f32_to_bf16_bits(Wf), mask24, which, synth.f32_to_bf16_bits(Xf), Wf, Xf
+
+
+def test_mask_merge_and_product_against_exact_rationals(golden_dir):
+    """Brute force from the definition Y = X (W . M*)^T, M* = M_tile + (1 - M_tile) . M_24, with
+    Python Fractions.  Catches: wrong merge formula, tile-map index transposition, any dropped term."""
+    pats, N, K, t, tm, W, mask24, which, X, Wf, Xf = _six_pattern_case(golden_dir)
+    W_hat = oracle.apply_mask(W, tm, mask24, t)
+    vals, meta = oracle.pack(W_hat, tm, t)
+    Y = oracle.gemm(X, vals, meta, N, K, tm, t)
+    for m in range(X.shape[0]):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                m_tile = int(tm[n // t, k // t])
+                m_star = m_tile + (1 - m_tile) * int(mask24[n, k])
+                acc += Fraction(float(Xf[m, k])) * Fraction(float(Wf[n, k])) * m_star
+            assert Fraction(float(Y[m, n])) == acc, (m, n)
+
+
+def test_nibbles_match_pattern_table(golden_dir):
+    """Each of the six candidate patterns must encode to the fixture's nibble (all values nonzero here)."""
+    pats, N, K, t, tm, W, mask24, which, X, Wf, Xf = _six_pattern_case(golden_dir)
+    W_hat = oracle.apply_mask(W, tm, mask24, t)
+    vals, meta = oracle.pack(W_hat, tm, t)
+    nibs = np.stack([meta & 0xF, meta >> 4], axis=1).reshape(-1)
+    i = 0
+    for tn in range(N // t):
+        for tk in range(K // t):
+            if tm[tn, tk]:
+                continue
+            for r in range(t):
+                for g in range(t // 4):
+                    p = which[tn * t + r, (tk * t) // 4 + g]
+                    assert nibs[i] == pats[p]["nibble"], (tn, tk, r, g)
+                    i += 1
+    assert i == nibs.size
+
+
+# ---------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("N,K,t,f", [(512, 512, 64, 0.5), (896, 896, 128, 0.5), (4096, 4096, 128, 0.25),
+                                      (4096, 4096, 128, 0.75), (11008, 4096, 128, 0.6), (4864, 896, 128, 1.0)])
+def test_closed_form_size(N, K, t, f):
+    """bytes = 2 N K (1 - (7/16) n_sparse / T): 2 B per dense element, 1 + 1/8 B per 2:4-tile element."""
+    tm = synth.tile_map(0, N // t, K // t, f, "size")
+    T = tm.size
+    ns = int((tm == 0).sum())
+    assert ns == int(np.floor(f * T + 0.5))
+    nv, nm = oracle.packed_sizes(N, K, t, tm)
+    assert Fraction(2 * nv + nm) == Fraction(2 * N * K) * (1 - Fraction(7, 16) * Fraction(ns, T))
+
+
+def test_size_ratio_table_and_paper_band(golden_dir):
+    for f, ratio in [(0.0, 1.0), (0.25, 0.890625), (0.5, 0.78125), (0.75, 0.671875), (1.0, 0.5625)]:
+        tm = synth.tile_map(0, 32, 32, f, "ratio")
+        nv, nm = oracle.packed_sizes(4096, 4096, 128, tm)
+        assert (2 * nv + nm) / (2 * 4096 * 4096) == ratio
+    d = load(golden_dir, "paper_memory_footprint.json")
+    for s, fp in zip(d["sparsity"], d["footprint_vs_dense"]):
+        tm = synth.tile_map(0, 32, 32, 2 * s, "band")
+        nv, nm = oracle.packed_sizes(4096, 4096, 128, tm)
+        assert abs((2 * nv + nm) / (2 * 4096 * 4096) - fp) <= d["band"]
+
+
+# ---------------------------------------------------------------- round trip and invariants
+def _special_matrix(N, K, seed):
+    c = synth.make_case("rt", N, K, 4, 64, 0.5, seed)
+    W = c.W.copy()
+    rng = np.random.default_rng(seed)
+    flat = W.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 8, replace=False)
+    specials = np.array([0x0000, 0x8000, 0x7FC0, 0x7F80, 0xFF80, 0x0001, 0x8001, 0x7F7F], np.uint16)
+    flat[idx] = specials[rng.integers(0, len(specials), size=idx.size)]
+    return c, W
+
+
+@pytest.mark.parametrize("N,K,t,f,seed", [(128, 192, 64, 0.5, 0), (256, 128, 128, 1.0, 1), (192, 320, 64, 0.3, 2)])
+def test_round_trip_bitwise(N, K, t, f, seed):
+    """unpack(pack(W_hat)) == W_hat on bits at kept positions and as values (-0 == +0) at dropped ones,
+    with zeros, negative zeros, NaN, Inf and denormals sprinkled in."""
+    c, W = _special_matrix(N, K, seed)
+    tm = synth.tile_map(seed, N // t, K // t, f, "rt")
+    m24 = synth.mask24_magnitude(W)
+    W_hat = oracle.apply_mask(W, tm, m24, t)
+    vals, meta = oracle.pack(W_hat, tm, t)
+    back = oracle.unpack(vals, meta, N, K, tm, t)
+    diff = back != W_hat
+    # the only allowed bit difference: a -0 that was not kept comes back as +0
+    assert np.all(W_hat[diff] == 0x8000) and np.all(back[diff] == 0x0000)
+    dense_elems = np.kron(tm, np.ones((t, t), np.uint8)).astype(bool)
+    assert not diff[dense_elems].any()
+    # invariants: every group of a 2:4 tile has at most two nonzeros; nnz bound
+    grp = ((back & 0x7FFF) != 0).reshape(N, K // 4, 4).sum(2)
+    sparse_grp = ~dense_elems.reshape(N, K // 4, 4)[:, :, 0]
+    assert grp[sparse_grp].max() <= 2
+    ns = int((tm == 0).sum())
+    assert int(((back & 0x7FFF) != 0).sum()) <= N * K - ns * t * t // 2
+
+
+def test_round_trip_config_shapes():
+    for (N, K), t, f in [((512, 512), 64, 0.5), ((896, 896), 128, 0.5), ((896, 4864), 128, 1.0)]:
+        c = synth.make_case("cfg", N, K, 1, t, f, 0)
+        W_hat = oracle.apply_mask(c.W, c.tile_map, c.mask24, t)
+        vals, meta = oracle.pack(W_hat, c.tile_map, t)
+        assert np.array_equal(oracle.unpack(vals, meta, N, K, c.tile_map, t), W_hat)
+        nnz = int(((W_hat & 0x7FFF) != 0).sum())
+        assert nnz <= N * K * (1 - synth.n_sparse_tiles(c.tile_map.size, f) / c.tile_map.size / 2)
+
+
+def test_unmasked_sparse_tile_rejected():
+    c = synth.make_case("rej", 128, 128, 1, 64, 0.5, 3)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.pack(c.W, c.tile_map, 64)  # W not masked: 2:4 tiles hold 4 nonzeros per group
+    assert e.value.code == oracle.ERR_NOT_24
+
+
+def test_shape_errors():
+    tm = np.ones((1, 1), np.uint8)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.packed_sizes(100, 128, 64, tm)
+    assert e.value.code == oracle.ERR_SHAPE
+
+
+# ---------------------------------------------------------------- GEMM special cases
+def _naive_dense_f64(X, W):
+    """Independent naive product, k ascending per output (same order as the definition)."""
+    Xd, Wd = synth.bf16_bits_to_f64(X), synth.bf16_bits_to_f64(W)
+    acc = np.zeros((X.shape[0], W.shape[0]), np.float64)
+    for k in range(X.shape[1]):
+        acc += Xd[:, k, None] * Wd[None, :, k]
+    return acc
+
+
+def test_all_dense_map_equals_naive_dense_bitwise():
+    """tile_map == 1 everywhere: the oracle must be the plain dense product, bit for bit."""
+    c = synth.make_case("dense", 192, 320, 5, 64, 0.0, 4)
+    assert c.tile_map.all()
+    vals, meta = oracle.pack(c.W, c.tile_map, 64)
+    Y = oracle.gemm(c.X, vals, meta, c.N, c.K, c.tile_map, 64)
+    assert np.array_equal(Y, _naive_dense_f64(c.X, c.W))
+
+
+def test_all_dense_map_equals_library_gemm():
+    c = synth.make_case("dense_lib", 256, 384, 7, 128, 0.0, 5)
+    vals, meta = oracle.pack(c.W, c.tile_map, 128)
+    Y = oracle.gemm(c.X, vals, meta, c.N, c.K, c.tile_map, 128)
+    Xt = torch.from_numpy(synth.bf16_bits_to_f64(c.X))
+    Wt = torch.from_numpy(synth.bf16_bits_to_f64(c.W))
+    assert relF(Y, torch.matmul(Xt, Wt.T).numpy()) <= 1e-12
+
+
+def _direct_24_gemm(X, vals, meta, N, K, t):
+    """All-2:4 map: product written directly on (values, positions) without decompressing:
+    Y[m, n] = sum_g sum_{j<2} v[n, g, j] * X[m, 4 g + pos_j].  Independent decode of the canonical order."""
+    Tn, Tk = N // t, K // t
+    v = synth.bf16_bits_to_f64(vals).reshape(Tn, Tk, t, t // 4, 2)
+    nib = np.stack([meta & 0xF, meta >> 4], axis=1).reshape(Tn, Tk, t, t // 4)
+    pos = np.stack([nib & 3, nib >> 2], axis=-1).astype(np.int64)       # (Tn, Tk, t, t/4, 2)
+    Xd = synth.bf16_bits_to_f64(X)
+    Y = np.zeros((X.shape[0], N))
+    for tn in range(Tn):
+        for tk in range(Tk):
+            kidx = tk * t + 4 * np.arange(t // 4)[None, :, None] + pos[tn, tk]     # (t, t/4, 2)
+            Xg = Xd[:, kidx.reshape(-1)].reshape(X.shape[0], t, -1)               # (M, t, t/2)
+            Y[:, tn * t:(tn + 1) * t] += np.einsum("mrj,rj->mr", Xg, v[tn, tk].reshape(t, -1))
+    return Y
+
+
+def test_all_sparse_map_equals_direct_24_gemm():
+    c = synth.make_case("sparse", 256, 384, 6, 128, 1.0, 6)
+    assert not c.tile_map.any()
+    W_hat = oracle.apply_mask(c.W, c.tile_map, c.mask24, 128)
+    vals, meta = oracle.pack(W_hat, c.tile_map, 128)
+    Y = oracle.gemm(c.X, vals, meta, c.N, c.K, c.tile_map, 128)
+    assert relF(Y, _direct_24_gemm(c.X, vals, meta, c.N, c.K, 128)) <= 1e-12
+
+
+def test_mixed_map_against_masked_library_gemm():
+    """Mixed map, masks applied independently in numpy (np.where on the Kronecker-expanded tile map)."""
+    c = synth.make_case("mixed", 384, 256, 9, 64, 0.4, 8)
+    W_hat = oracle.apply_mask(c.W, c.tile_map, c.mask24, 64)
+    vals, meta = oracle.pack(W_hat, c.tile_map, 64)
+    Y = oracle.gemm(c.X, vals, meta, c.N, c.K, c.tile_map, 64)
+    Mtile = np.kron(c.tile_map, np.ones((64, 64), np.uint8))
+    Mstar = Mtile + (1 - Mtile) * c.mask24
+    Wd = synth.bf16_bits_to_f64(c.W) * Mstar
+    assert relF(Y, synth.bf16_bits_to_f64(c.X) @ Wd.T) <= 1e-12
+    # sparsity is f/2 up to rounding of the tile count
+    ns = int((c.tile_map == 0).sum())
+    assert int((Mstar == 0).sum()) == ns * 64 * 64 // 2
+
+
+def test_linearity_and_map_invariance():
+    """gemm(a X1 + X2) = a gemm(X1) + gemm(X2) (exactly representable inputs), and re-labelling a tile
+    whose content already is 2:4 from sparse to dense does not change Y."""
+    c = synth.make_case("lin", 128, 256, 4, 64, 1.0, 9)
+    W_hat = oracle.apply_mask(c.W, c.tile_map, c.mask24, 64)
+    vals, meta = oracle.pack(W_hat, c.tile_map, 64)
+    rng = np.random.default_rng(0)
+    X1 = rng.integers(-4, 5, size=(4, 256)).astype(np.float32)
+    X2 = rng.integers(-4, 5, size=(4, 256)).astype(np.float32)
+    g = lambda Xf: oracle.gemm(synth.f32_to_bf16_bits(Xf), vals, meta, 128, 256, c.tile_map, 64)
+    assert relF(g(2 * X1 + X2), 2 * g(X1) + g(X2)) <= 1e-13
+    tm2 = c.tile_map.copy()
+    tm2[0, 1] = 1
+    tm2[1, 2] = 1
+    vals2, meta2 = oracle.pack(W_hat, tm2, 64)
+    Y1 = oracle.gemm(c.X, vals, meta, 128, 256, c.tile_map, 64)
+    Y2 = oracle.gemm(c.X, vals2, meta2, 128, 256, tm2, 64)
+    assert np.array_equal(Y1, Y2)
+
+
+def test_gemm_points_matches_full():
+    c = synth.make_case("pts", 128, 192, 8, 64, 0.5, 10)
+    W_hat = oracle.apply_mask(c.W, c.tile_map, c.mask24, 64)
+    vals, meta = oracle.pack(W_hat, c.tile_map, 64)
+    Y = oracle.gemm(c.X, vals, meta, 128, 192, c.tile_map, 64)
+    mn = np.array([[0, 0], [7, 127], [3, 64], [5, 1]], np.int64)
+    pts = oracle.gemm_points(c.X, oracle.unpack(vals, meta, 128, 192, c.tile_map, 64), mn)
+    assert np.array_equal(pts, Y[mn[:, 0], mn[:, 1]])
+    assert np.array_equal(pts, _naive_dense_f64(c.X, W_hat)[mn[:, 0], mn[:, 1]])
+
+
+# ---------------------------------------------------------------- generator checks
+def test_magnitude_mask_keeps_top2_with_low_index_ties():
+    W = bits([[1, 1, 1, 1, 3, -3, 2, 3, 0, 0, 0, 5, -2, 1, 2, -1]])
+    m = synth.mask24_magnitude(W)
+    assert m.tolist() == [[1, 1, 0, 0, 1, 1, 0, 0, 1, 0, 0, 1, 1, 0, 1, 0]]
+
+
+def test_tile_map_exact_count():
+    assert int((synth.tile_map(0, 7, 7, 0.5) == 0).sum()) == 25       # round-half-up(24.5)
+    assert int((synth.tile_map(0, 32, 32, 0.25) == 0).sum()) == 256
+    assert int((synth.tile_map(0, 86, 32, 0.6) == 0).sum()) == 1651
