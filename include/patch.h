@@ -1,0 +1,122 @@
+/*
+ * patch.h -- C ABI of the MI355X (gfx950) library for the inference linear layer of PATCH
+ * (arXiv 2509.23410): Y = X * W_hat^T where W_hat (N x K = d1 x d2, out x in features) is cut into
+ * tile x tile blocks and every block is either dense or 2:4 sparse along K.
+ *
+ * Conventions
+ *   - All matrices are row-major.  bf16 = IEEE bfloat16 (upper 16 bits of binary32).
+ *   - "DEVICE" pointers are HIP device memory of the current device; "HOST" pointers are ordinary host
+ *     memory.  The caller owns every buffer it passes in; the library owns a patch_packed until
+ *     patch_free.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - No exception crosses this boundary: every failure is a patch_status.  Argument and shape errors
+ *     are detected on the host before any device work.
+ *   - tile_map is HOST memory, row-major (N/tile) x (K/tile) bytes: nonzero = the tile is dense,
+ *     0 = the tile is 2:4 sparse.  This is the hard tile mask 1[P_tile > 0] of Algorithm 1 (first
+ *     line after the training loop); a positive logit means "dense" (Section 3, "Inference").
+ *   - 2:4: in every group of four consecutive elements along K (the input-feature dimension) at most
+ *     two are nonzero (Section 1; Section 2, "Learnable 2:4 Mask").  An element is "zero" when its
+ *     bit pattern & 0x7FFF is 0.
+ */
+#ifndef PATCH_H_
+#define PATCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct patch_packed patch_packed; /* opaque: compressed weight + tables + split-K workspace */
+
+typedef enum {
+    PATCH_OK = 0,
+    PATCH_ERR_ARG = 1,    /* null pointer, non-positive size, unknown option                         */
+    PATCH_ERR_SHAPE = 2,  /* tile not in {64, 128}, or N / K not a multiple of tile                  */
+    PATCH_ERR_NOT_24 = 3, /* a group of four in a tile flagged 2:4 holds more than two nonzeros      */
+    PATCH_ERR_ALLOC = 4,  /* device or host allocation failed                                        */
+    PATCH_ERR_HIP = 5,    /* a HIP runtime call failed (patch_last_hip_error gives the code)         */
+    PATCH_ERR_SIZE = 6    /* a caller-provided host buffer is too small                              */
+} patch_status;
+
+/* Which kernel family patch_gemm_ex uses.  AUTO: decode for M <= 16, prefill otherwise. */
+typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
+
+/* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and
+ * schedule, e.g. split-K).  A zero field means "library default". */
+typedef struct {
+    int path;    /* patch_path                                                                      */
+    int split_k; /* decode: number of K slices whose fp32 partials are reduced (1..64), 0 = auto    */
+    int variant; /* kernel variant index within the path, 0 = default                               */
+} patch_gemm_opts;
+
+/*
+ * Merge of the hard masks and pruning of the weights (Algorithm 1, last three lines; Eq. 4 with hard
+ * masks):  M* = M_tile + (1 - M_tile) (.) M_24,  W_hat = W (.) M*.
+ *   W      DEVICE, N x K bf16
+ *   mask24 DEVICE, N x K bytes, nonzero = keep (used only inside tiles whose tile_map entry is 0)
+ *   W_hat  DEVICE, N x K bf16 (may alias W); pruned entries are written as +0
+ * Asynchronous on `stream` except for one small host-to-device copy of the tile map.
+ */
+patch_status patch_apply_mask(const void* W, const void* mask24, const uint8_t* tile_map, int64_t N,
+                              int64_t K, int tile, void* W_hat, void* stream);
+
+/*
+ * Compression (Appendix A: "matrix compression and metadata generation are determined by the chosen
+ * tile size"): 2:4 tiles become kept values + 2-bit positions laid out for the gfx950 sparse matrix
+ * instructions; dense tiles are re-ordered into matrix-instruction operand order.
+ *   W_hat  DEVICE, N x K bf16, already pruned.
+ *   tile   64 or 128; N and K must be multiples of it.
+ *   *out   receives a new patch_packed on success, untouched otherwise.
+ * Kept positions of a group with fewer than two nonzeros: its nonzeros plus the lowest-index zeros.
+ * Synchronises `stream` once (to learn whether the 2:4 check failed).  Returns PATCH_ERR_NOT_24 if it did.
+ */
+patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile,
+                        void* stream, patch_packed** out);
+
+/*
+ * The product (Section 4; Appendix A decode input BS x K and prefill input BS*SL x K):
+ *   Y[m, n] = sum_k X[m, k] * W_hat[n, k],   bf16 x bf16 products accumulated in fp32.
+ *   X  DEVICE, M x K bf16;  Y  DEVICE, M x N fp32;  M >= 1 arbitrary.
+ * Asynchronous on `stream`; allocates nothing and never synchronises.  Calls that use the same
+ * patch_packed concurrently (different streams) race on its split-K workspace: not supported.
+ * Results are bit-reproducible from call to call (fixed reduction order).
+ */
+patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream);
+patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream,
+                           const patch_gemm_opts* opts);
+
+/* Decompression back to a row-major N x K bf16 matrix (DEVICE).  Dropped positions become +0. */
+patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream);
+
+/*
+ * Test hook: the compressed matrix in the layout-independent canonical order.
+ *   vals (HOST, uint16): tiles in row-major tile order; dense tile = its tile*tile elements row-major;
+ *                        2:4 tile = per row, per group along K, the two kept elements, ascending position.
+ *   meta (HOST, bytes) : 2:4 tiles only, same order; per group one nibble pos0 | pos1 << 2 (pos0 < pos1),
+ *                        two nibbles per byte, earlier group in the low nibble.
+ * Sizes come from patch_canonical_sizes; smaller buffers give PATCH_ERR_SIZE.  Synchronous.
+ */
+patch_status patch_canonical_sizes(const patch_packed* P, size_t* vals_bytes, size_t* meta_bytes);
+patch_status patch_export_canonical(const patch_packed* P, void* vals, size_t vals_bytes, void* meta,
+                                    size_t meta_bytes);
+
+/* Compressed weight bytes (values + positions; tables excluded): 2NK (1 - 7/16 * n_sparse / T). */
+size_t patch_packed_bytes(const patch_packed* P);
+/* Bytes of the per-tile tables the kernels read in addition (offset / type table). */
+size_t patch_table_bytes(const patch_packed* P);
+patch_status patch_packed_dims(const patch_packed* P, int64_t* N, int64_t* K, int* tile,
+                               int64_t* n_sparse_tiles);
+/* HOST copy of the tile map held by P (N/tile * K/tile bytes). */
+patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, size_t bytes);
+
+void patch_free(patch_packed* P);
+const char* patch_strerror(patch_status s);
+int patch_last_hip_error(void); /* hipError_t of the most recent PATCH_ERR_HIP on this thread */
+const char* patch_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PATCH_H_ */

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of the C-ABI library declared in include/patch.h (argument marshalling only).
+
+Every function takes raw device pointers (ints, e.g. ``tensor.data_ptr()``) or torch tensors and a stream
+handle (``torch.cuda.current_stream().cuda_stream``); all computation happens inside the library's HIP
+kernels.  Loading fails loudly if the library has not been built (``python -m paper_2509_23410_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpatch_hip.so")
+
+OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
+PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
+
+EXPORTS = [
+    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_unpack", "patch_canonical_sizes",
+    "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
+    "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
+]
+
+
+class GemmOpts(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int)]
+
+
+class PatchError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_23410_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        L.patch_apply_mask.argtypes = [vp, vp, vp, i64, i64, ci, vp, vp]
+        L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
+        L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
+        L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
+        L.patch_unpack.argtypes = [vp, vp, vp]
+        L.patch_canonical_sizes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.patch_export_canonical.argtypes = [vp, vp, sz, vp, sz]
+        L.patch_packed_bytes.argtypes = [vp]
+        L.patch_packed_bytes.restype = sz
+        L.patch_table_bytes.argtypes = [vp]
+        L.patch_table_bytes.restype = sz
+        L.patch_packed_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ci), ctypes.POINTER(i64)]
+        L.patch_packed_tile_map.argtypes = [vp, vp, sz]
+        L.patch_free.argtypes = [vp]
+        L.patch_free.restype = None
+        L.patch_strerror.argtypes = [ci]
+        L.patch_strerror.restype = ctypes.c_char_p
+        L.patch_last_hip_error.restype = ci
+        L.patch_version.restype = ctypes.c_char_p
+        for f in ("patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_unpack", "patch_canonical_sizes",
+                  "patch_export_canonical", "patch_packed_dims", "patch_packed_tile_map"):
+            getattr(L, f).restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    raise TypeError(type(x))
+
+
+def _check(st: int, what: str):
+    if st != OK:
+        msg = lib().patch_strerror(st).decode()
+        if st == ERR_HIP:
+            msg += f" (hipError {lib().patch_last_hip_error()})"
+        raise PatchError(st, f"{what}: {msg}")
+
+
+def strerror(st: int) -> str:
+    return lib().patch_strerror(st).decode()
+
+
+def version() -> str:
+    return lib().patch_version().decode()
+
+
+def _map_host(tile_map) -> np.ndarray:
+    return np.ascontiguousarray(tile_map, dtype=np.uint8)
+
+
+def patch_apply_mask(W, mask24, tile_map, N: int, K: int, tile: int, W_hat, stream: int = 0) -> None:
+    tm = _map_host(tile_map)
+    _check(lib().patch_apply_mask(_ptr(W), _ptr(mask24), tm.ctypes.data, N, K, tile, _ptr(W_hat), stream), "patch_apply_mask")
+
+
+class Packed:
+    """Owner of a ``patch_packed*``; freed on ``close()`` or garbage collection."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def close(self):
+        if self.handle:
+            lib().patch_free(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def nbytes(self) -> int:
+        return int(lib().patch_packed_bytes(self.handle))
+
+    @property
+    def table_bytes(self) -> int:
+        return int(lib().patch_table_bytes(self.handle))
+
+    def dims(self):
+        N, K, t, ns = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int64()
+        _check(lib().patch_packed_dims(self.handle, ctypes.byref(N), ctypes.byref(K), ctypes.byref(t), ctypes.byref(ns)),
+               "patch_packed_dims")
+        return int(N.value), int(K.value), int(t.value), int(ns.value)
+
+    def tile_map(self) -> np.ndarray:
+        N, K, t, _ = self.dims()
+        out = np.empty((N // t, K // t), np.uint8)
+        _check(lib().patch_packed_tile_map(self.handle, out.ctypes.data, out.size), "patch_packed_tile_map")
+        return out
+
+
+def patch_pack(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> Packed:
+    tm = _map_host(tile_map)
+    if N > 0 and K > 0 and tile > 0 and N % tile == 0 and K % tile == 0 and tm.size != (N // tile) * (K // tile):
+        raise PatchError(ERR_ARG, "patch_pack: tile_map has the wrong number of entries")
+    out = ctypes.c_void_p(0)
+    _check(lib().patch_pack(_ptr(W_hat), N, K, tm.ctypes.data, tile, stream, ctypes.byref(out)), "patch_pack")
+    return Packed(out.value)
+
+
+def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> None:
+    if path == PATH_AUTO and split_k == 0 and variant == 0:
+        st = lib().patch_gemm(_ptr(X), M, P.handle, _ptr(Y), stream)
+    else:
+        o = GemmOpts(path, split_k, variant)
+        st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
+    _check(st, "patch_gemm")
+
+
+def patch_unpack(P: Packed, W_out, stream: int = 0) -> None:
+    _check(lib().patch_unpack(P.handle, _ptr(W_out), stream), "patch_unpack")
+
+
+def patch_export_canonical(P: Packed):
+    """-> (vals uint16[...], meta uint8[...]) in the canonical order described in include/patch.h."""
+    vb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().patch_canonical_sizes(P.handle, ctypes.byref(vb), ctypes.byref(mb)), "patch_canonical_sizes")
+    vals = np.empty(vb.value // 2, np.uint16)
+    meta = np.zeros(max(mb.value, 1), np.uint8)
+    _check(lib().patch_export_canonical(P.handle, vals.ctypes.data, vb.value, meta.ctypes.data, mb.value), "patch_export_canonical")
+    return vals, meta[:mb.value]

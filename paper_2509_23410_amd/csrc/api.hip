@@ -1,0 +1,300 @@
+// C ABI of the library (see include/patch.h): argument checks, the patch_packed object, host-side table
+// construction and kernel dispatch.  No device arithmetic here.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/patch.h"
+#include "kernels.h"
+#include "layout.h"
+
+using namespace patch;
+
+struct patch_packed {
+    int64_t N = 0, K = 0;
+    int tile = 0;
+    int Tn = 0, Tk = 0;
+    int64_t n_sparse = 0;
+    size_t payload_bytes = 0;   // sum of tile payloads (no alignment slack: tiles are granule multiples)
+    uint8_t* d_payload = nullptr;
+    uint32_t* d_table = nullptr;
+    std::vector<uint8_t> tile_map;   // host copy, 1 = dense
+    std::vector<uint32_t> table;     // host copy of the offset / type table
+    float* d_ws = nullptr;
+    size_t ws_floats = 0;
+    unsigned* d_counters = nullptr;
+    int device = 0;
+    int n_cus = 256;
+};
+
+static thread_local int g_last_hip_error = 0;
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) {                         \
+            g_last_hip_error = (int)e_;                 \
+            return PATCH_ERR_HIP;                       \
+        }                                               \
+    } while (0)
+
+static patch_status check_shape(int64_t N, int64_t K, int tile) {
+    if (N <= 0 || K <= 0) return PATCH_ERR_ARG;
+    if (tile != 64 && tile != 128) return PATCH_ERR_SHAPE;
+    if (N % tile != 0 || K % tile != 0) return PATCH_ERR_SHAPE;
+    if (N / tile > (1 << 20) || K / tile > (1 << 20)) return PATCH_ERR_SHAPE;
+    return PATCH_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" {
+
+const char* patch_version(void) { return "patch-mi355x 0.1 (gfx950)"; }
+
+int patch_last_hip_error(void) { return g_last_hip_error; }
+
+const char* patch_strerror(patch_status s) {
+    switch (s) {
+        case PATCH_OK: return "ok";
+        case PATCH_ERR_ARG: return "invalid argument (null or misaligned pointer, non-positive size, unknown option)";
+        case PATCH_ERR_SHAPE: return "unsupported shape (tile must be 64 or 128 and divide N and K)";
+        case PATCH_ERR_NOT_24: return "a group of four in a 2:4 tile holds more than two nonzeros";
+        case PATCH_ERR_ALLOC: return "allocation failed";
+        case PATCH_ERR_HIP: return "HIP runtime error";
+        case PATCH_ERR_SIZE: return "caller buffer too small";
+    }
+    return "unknown status";
+}
+
+patch_status patch_apply_mask(const void* W, const void* mask24, const uint8_t* tile_map, int64_t N, int64_t K, int tile,
+                              void* W_hat, void* stream) {
+    if (!W || !mask24 || !tile_map || !W_hat) return PATCH_ERR_ARG;
+    patch_status st = check_shape(N, K, tile);
+    if (st != PATCH_OK) return st;
+    if (!aligned16(W) || !aligned16(W_hat) || (reinterpret_cast<uintptr_t>(mask24) & 7u)) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t T = (size_t)(N / tile) * (size_t)(K / tile);
+    uint8_t* d_map = nullptr;
+    if (hipMalloc(&d_map, T) != hipSuccess) { (void)hipGetLastError(); return PATCH_ERR_ALLOC; }
+    hipError_t e = hipMemcpyAsync(d_map, tile_map, T, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) {
+        launch_apply_mask(static_cast<const uint16_t*>(W), static_cast<const uint8_t*>(mask24), d_map, N, K, tile,
+                          static_cast<uint16_t*>(W_hat), s);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(d_map);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return PATCH_ERR_HIP; }
+    return PATCH_OK;
+}
+
+void patch_free(patch_packed* P) {
+    if (!P) return;
+    if (P->d_payload) (void)hipFree(P->d_payload);
+    if (P->d_table) (void)hipFree(P->d_table);
+    if (P->d_ws) (void)hipFree(P->d_ws);
+    if (P->d_counters) (void)hipFree(P->d_counters);
+    delete P;
+}
+
+patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
+                        patch_packed** out) {
+    if (!W_hat || !tile_map || !out) return PATCH_ERR_ARG;
+    patch_status st = check_shape(N, K, tile);
+    if (st != PATCH_OK) return st;
+    if (!aligned16(W_hat)) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    patch_packed* P = new (std::nothrow) patch_packed();
+    if (!P) return PATCH_ERR_ALLOC;
+    P->N = N; P->K = K; P->tile = tile;
+    P->Tn = (int)(N / tile); P->Tk = (int)(K / tile);
+    const size_t T = (size_t)P->Tn * (size_t)P->Tk;
+    try {
+        P->tile_map.resize(T);
+        P->table.resize(T);
+    } catch (...) { delete P; return PATCH_ERR_ALLOC; }
+    uint64_t off = 0;
+    for (size_t i = 0; i < T; ++i) {
+        const bool sparse = tile_map[i] == 0;
+        P->tile_map[i] = sparse ? 0 : 1;
+        P->table[i] = make_entry(off, sparse);
+        off += sparse ? sparse_tile_bytes(tile) : dense_tile_bytes(tile);
+        if (sparse) ++P->n_sparse;
+    }
+    P->payload_bytes = off;
+    if ((off / kGranule) >> 31) { delete P; return PATCH_ERR_SHAPE; }
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        g_last_hip_error = (int)hipGetLastError();
+        delete P;
+        return PATCH_ERR_HIP;
+    }
+    P->device = dev;
+    P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    const int smax = decode_max_split(N, P->Tk);
+    P->ws_floats = (size_t)smax * 16 * (size_t)N;
+    const size_t n_counters = (size_t)(N / 64);
+    int* d_err = nullptr;
+    // one extra granule after the payload: kernels may prefetch the start of a next tile that does not exist
+    bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kGranule) == hipSuccess &&
+              hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&P->d_ws, P->ws_floats * sizeof(float)) == hipSuccess &&
+              hipMalloc(&P->d_counters, n_counters * sizeof(unsigned)) == hipSuccess &&
+              hipMalloc(&d_err, sizeof(int)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (d_err) (void)hipFree(d_err);
+        patch_free(P);
+        return PATCH_ERR_ALLOC;
+    }
+    hipError_t e = hipMemcpyAsync(P->d_table, P->table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemsetAsync(P->d_counters, 0, n_counters * sizeof(unsigned), s);
+    if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
+    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload + P->payload_bytes, 0, kGranule, s);
+    if (e == hipSuccess) {
+        launch_pack(static_cast<const uint16_t*>(W_hat), K, P->d_table, (int)T, P->Tk, tile, P->d_payload, d_err, s);
+        e = hipGetLastError();
+    }
+    int h_err = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(d_err);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        patch_free(P);
+        return PATCH_ERR_HIP;
+    }
+    if (h_err) {
+        patch_free(P);
+        return PATCH_ERR_NOT_24;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream, const patch_gemm_opts* opts) {
+    if (!X || !P || !Y || M <= 0) return PATCH_ERR_ARG;
+    if (!aligned16(X) || !aligned16(Y)) return PATCH_ERR_ARG;
+    int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
+    if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
+    if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 64 || variant < 0) return PATCH_ERR_ARG;
+    if (path == PATCH_PATH_AUTO) path = (M <= 16) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs a;
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.N = P->N; a.K = P->K;
+    a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
+    a.payload = P->d_payload; a.table = P->d_table;
+    a.Y = static_cast<float*>(Y);
+    a.ws = P->d_ws; a.ws_floats = P->ws_floats; a.counters = P->d_counters;
+    a.n_cus = P->n_cus;
+    if (path == PATCH_PATH_DECODE) {
+        for (int64_t m0 = 0; m0 < M; m0 += 16) {
+            const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
+            launch_decode(a, m0, rows, split_k, variant, s);
+        }
+    } else {
+        launch_prefill(a, variant, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return PATCH_OK;
+}
+
+patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream) {
+    return patch_gemm_ex(X, M, P, Y, stream, nullptr);
+}
+
+patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream) {
+    if (!P || !W_out || !aligned16(W_out)) return PATCH_ERR_ARG;
+    launch_unpack(P->d_payload, P->d_table, P->Tn * P->Tk, P->Tk, P->tile, P->K, static_cast<uint16_t*>(W_out),
+                  static_cast<hipStream_t>(stream));
+    HIP_TRY(hipGetLastError());
+    return PATCH_OK;
+}
+
+size_t patch_packed_bytes(const patch_packed* P) { return P ? P->payload_bytes : 0; }
+size_t patch_table_bytes(const patch_packed* P) { return P ? P->table.size() * sizeof(uint32_t) : 0; }
+
+patch_status patch_packed_dims(const patch_packed* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles) {
+    if (!P) return PATCH_ERR_ARG;
+    if (N) *N = P->N;
+    if (K) *K = P->K;
+    if (tile) *tile = P->tile;
+    if (n_sparse_tiles) *n_sparse_tiles = P->n_sparse;
+    return PATCH_OK;
+}
+
+patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, size_t bytes) {
+    if (!P || !tile_map) return PATCH_ERR_ARG;
+    if (bytes < P->tile_map.size()) return PATCH_ERR_SIZE;
+    memcpy(tile_map, P->tile_map.data(), P->tile_map.size());
+    return PATCH_OK;
+}
+
+patch_status patch_canonical_sizes(const patch_packed* P, size_t* vals_bytes, size_t* meta_bytes) {
+    if (!P) return PATCH_ERR_ARG;
+    const size_t t2 = (size_t)P->tile * P->tile;
+    const size_t n_dense = P->tile_map.size() - (size_t)P->n_sparse;
+    if (vals_bytes) *vals_bytes = 2 * (n_dense * t2 + (size_t)P->n_sparse * t2 / 2);
+    if (meta_bytes) *meta_bytes = (size_t)P->n_sparse * t2 / 8;
+    return PATCH_OK;
+}
+
+// Host-side re-ordering of the device layout into the canonical order (test hook; not a hot path).
+patch_status patch_export_canonical(const patch_packed* P, void* vals, size_t vals_bytes, void* meta, size_t meta_bytes) {
+    if (!P || !vals || (!meta && P->n_sparse)) return PATCH_ERR_ARG;
+    size_t need_v = 0, need_m = 0;
+    patch_canonical_sizes(P, &need_v, &need_m);
+    if (vals_bytes < need_v || meta_bytes < need_m) return PATCH_ERR_SIZE;
+    std::vector<uint8_t> host;
+    try { host.resize(P->payload_bytes); } catch (...) { return PATCH_ERR_ALLOC; }
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host.data(), P->d_payload, P->payload_bytes, hipMemcpyDeviceToHost));
+    const int t = P->tile, KPT = t / kStepCols;
+    uint16_t* v = static_cast<uint16_t*>(vals);
+    uint8_t* mt = static_cast<uint8_t*>(meta);
+    if (need_m) memset(mt, 0, need_m);
+    size_t vi = 0, nib = 0;
+    for (size_t ti = 0; ti < P->table.size(); ++ti) {
+        const uint32_t e = P->table[ti];
+        const uint8_t* base = host.data() + entry_offset(e);
+        for (int r = 0; r < t; ++r) {
+            const int s = r / 16, i = r % 16;
+            if (!entry_sparse(e)) {
+                for (int c = 0; c < t; ++c) {
+                    const int j = c / 64, h = (c % 64) / 32, q = (c % 32) / 8, el = c % 8;
+                    const size_t byte = (size_t)(((s * KPT + j) * 2 + h) * 64 + (16 * q + i)) * 16 + 2 * el;
+                    uint16_t x;
+                    memcpy(&x, base + byte, 2);
+                    v[vi++] = x;
+                }
+            } else {
+                for (int g = 0; g < t / 4; ++g) {
+                    const int c = 4 * g, j = c / 64, qa = (c % 64) / 16, gl = (c % 16) / 4;
+                    const int lane = 16 * qa + i;
+                    const size_t byte = (size_t)((s * KPT + j) * 64 + lane) * 16 + 4 * gl;
+                    uint16_t x[2];
+                    memcpy(x, base + byte, 4);
+                    v[vi++] = x[0];
+                    v[vi++] = x[1];
+                    uint16_t idx;
+                    memcpy(&idx, base + sparse_vals_bytes(t) + (size_t)((s * 64 + lane) * KPT + j) * 2, 2);
+                    const uint8_t nibble = (uint8_t)((idx >> (4 * gl)) & 0xF);
+                    mt[nib >> 1] |= (uint8_t)(nibble << (4 * (nib & 1)));
+                    ++nib;
+                }
+            }
+        }
+    }
+    return PATCH_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and rejects bad arguments before any device work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2509_23410_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    src = open(os.path.join(ROOT, "include", "patch.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(patch_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported():
+    names = header_functions()
+    assert "patch_pack" in names and "patch_gemm" in names and len(names) >= 12
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in patch.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror_and_version():
+    assert B.strerror(B.OK) == "ok"
+    assert "2:4" in B.strerror(B.ERR_NOT_24)
+    assert "gfx950" in B.version()
+
+
+def test_argument_errors_without_device():
+    L = B.lib()
+    tm = np.ones((2, 2), np.uint8)
+    out = ctypes.c_void_p(0)
+    fake = 0x1000  # never dereferenced: all of these fail on the host first
+    assert L.patch_pack(0, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack(fake, 128, 128, 0, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack(fake, -1, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack(fake, 128, 128, tm.ctypes.data, 32, 0, ctypes.byref(out)) == B.ERR_SHAPE
+    assert L.patch_pack(fake, 100, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_SHAPE
+    assert L.patch_pack(fake + 2, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG  # misaligned
+    assert out.value is None
+    assert L.patch_gemm(fake, 1, 0, fake, 0) == B.ERR_ARG
+    assert L.patch_gemm(0, 1, fake, fake, 0) == B.ERR_ARG
+    assert L.patch_apply_mask(fake, fake, tm.ctypes.data, 128, 128, 48, fake, 0) == B.ERR_SHAPE
+    assert L.patch_unpack(0, fake, 0) == B.ERR_ARG
+    assert L.patch_packed_bytes(0) == 0
+    L.patch_free(0)
+    with pytest.raises(B.PatchError):
+        B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)
