@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-typedef struct patch_packed patch_packed; /* opaque: compressed weight + tables + split-K workspace */
+typedef struct patch_packed patch_packed; /* opaque: compressed weight + per-tile tables */
 
 typedef enum {
     PATCH_OK = 0,
@@ -47,7 +47,8 @@ typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 
  * schedule, e.g. split-K).  A zero field means "library default". */
 typedef struct {
     int path;    /* patch_path                                                                      */
-    int split_k; /* decode: number of K slices whose fp32 partials are reduced (1..64), 0 = auto    */
+    int split_k; /* decode: K slices (one wavefront each) per workgroup whose fp32 partials are     */
+                 /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto       */
     int variant; /* kernel variant index within the path, 0 = default                               */
 } patch_gemm_opts;
 
@@ -57,7 +58,7 @@ typedef struct {
  *   W      DEVICE, N x K bf16
  *   mask24 DEVICE, N x K bytes, nonzero = keep (used only inside tiles whose tile_map entry is 0)
  *   W_hat  DEVICE, N x K bf16 (may alias W); pruned entries are written as +0
- * Asynchronous on `stream` except for one small host-to-device copy of the tile map.
+ * Synchronous: uploads the tile map, runs on `stream` and waits for it (a one-off conversion step).
  */
 patch_status patch_apply_mask(const void* W, const void* mask24, const uint8_t* tile_map, int64_t N,
                               int64_t K, int tile, void* W_hat, void* stream);
@@ -79,9 +80,9 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
  * The product (Section 4; Appendix A decode input BS x K and prefill input BS*SL x K):
  *   Y[m, n] = sum_k X[m, k] * W_hat[n, k],   bf16 x bf16 products accumulated in fp32.
  *   X  DEVICE, M x K bf16;  Y  DEVICE, M x N fp32;  M >= 1 arbitrary.
- * Asynchronous on `stream`; allocates nothing and never synchronises.  Calls that use the same
- * patch_packed concurrently (different streams) race on its split-K workspace: not supported.
- * Results are bit-reproducible from call to call (fixed reduction order).
+ * Asynchronous on `stream`; allocates nothing and never synchronises.  A patch_packed is read-only for
+ * patch_gemm, so concurrent calls on different streams are allowed as long as their Y buffers differ.
+ * Results are bit-reproducible from call to call (fixed reduction order, no atomics).
  */
 patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream);
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream,

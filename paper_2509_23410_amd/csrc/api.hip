@@ -23,9 +23,6 @@ struct patch_packed {
     uint32_t* d_table = nullptr;
     std::vector<uint8_t> tile_map;   // host copy, 1 = dense
     std::vector<uint32_t> table;     // host copy of the offset / type table
-    float* d_ws = nullptr;
-    size_t ws_floats = 0;
-    unsigned* d_counters = nullptr;
     int device = 0;
     int n_cus = 256;
 };
@@ -96,8 +93,6 @@ void patch_free(patch_packed* P) {
     if (!P) return;
     if (P->d_payload) (void)hipFree(P->d_payload);
     if (P->d_table) (void)hipFree(P->d_table);
-    if (P->d_ws) (void)hipFree(P->d_ws);
-    if (P->d_counters) (void)hipFree(P->d_counters);
     delete P;
 }
 
@@ -139,15 +134,10 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     P->device = dev;
     P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-    const int smax = decode_max_split(N, P->Tk);
-    P->ws_floats = (size_t)smax * 16 * (size_t)N;
-    const size_t n_counters = (size_t)(N / 64);
     int* d_err = nullptr;
-    // one extra granule after the payload: kernels may prefetch the start of a next tile that does not exist
-    bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kGranule) == hipSuccess &&
+    // a kilobyte of slack behind the payload keeps any over-read of the last tile inside the allocation
+    bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kZeroPad) == hipSuccess &&
               hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&P->d_ws, P->ws_floats * sizeof(float)) == hipSuccess &&
-              hipMalloc(&P->d_counters, n_counters * sizeof(unsigned)) == hipSuccess &&
               hipMalloc(&d_err, sizeof(int)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -156,9 +146,8 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
         return PATCH_ERR_ALLOC;
     }
     hipError_t e = hipMemcpyAsync(P->d_table, P->table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMemsetAsync(P->d_counters, 0, n_counters * sizeof(unsigned), s);
     if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
-    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload + P->payload_bytes, 0, kGranule, s);
+    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload + P->payload_bytes, 0, kZeroPad, s);
     if (e == hipSuccess) {
         launch_pack(static_cast<const uint16_t*>(W_hat), K, P->d_table, (int)T, P->Tk, tile, P->d_payload, d_err, s);
         e = hipGetLastError();
@@ -185,7 +174,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     if (!aligned16(X) || !aligned16(Y)) return PATCH_ERR_ARG;
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
-    if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 64 || variant < 0) return PATCH_ERR_ARG;
+    if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
     if (path == PATCH_PATH_AUTO) path = (M <= 16) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a;
@@ -194,7 +183,6 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
     a.payload = P->d_payload; a.table = P->d_table;
     a.Y = static_cast<float*>(Y);
-    a.ws = P->d_ws; a.ws_floats = P->ws_floats; a.counters = P->d_counters;
     a.n_cus = P->n_cus;
     if (path == PATCH_PATH_DECODE) {
         for (int64_t m0 = 0; m0 < M; m0 += 16) {

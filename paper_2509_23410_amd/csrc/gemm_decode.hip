@@ -1,17 +1,19 @@
-// Decode-shaped hybrid GEMM (at most 16 rows of X per launch), split-K with an in-kernel, fixed-order
-// reduction.  This is the product Y = X * W_hat^T of Section 4 / Appendix A of the paper for the decoding
-// input (batch x K), with "split-K" as the schedule Appendix A names.
+// Decode-shaped hybrid GEMM (at most 16 rows of X per launch) with split-K across the wavefronts of a
+// workgroup and a fixed-order fp32 reduction through LDS.  This is the product Y = X * W_hat^T of Section 4 /
+// Appendix A of the paper for the decoding input (batch x K), with "split-K" as the schedule Appendix A names.
 //
 // Mapping.  The weight is the A operand (the sparse operand of the gfx950 sparse matrix instruction is A),
-// so the kernel computes Y^T = W_hat * X^T: a wavefront owns a strip of 16 output features and walks along
-// K; the up-to-16 rows of X are the 16 columns of the instruction.  Weight fragments go HBM -> registers
-// directly (every weight byte is used exactly once; layout.h gives the register-order storage); X is staged
-// once per workgroup in LDS.  Per tile the wavefront takes ONE scalar branch on the tile type:
-//   dense : 2 x v_mfma_f32_16x16x32_bf16 per 64 columns
-//   2:4   : 1 x v_smfmac_f32_16x16x64_bf16 per 64 columns
-// Workgroup = 4 wavefronts = 4 adjacent strips (64 output features) x one K slice.  Slices write fp32
-// partials; the last-arriving workgroup of each 64-feature block sums them in slice order (deterministic)
-// and resets the arrival counter.
+// so the kernel computes Y^T = W_hat * X^T.  A workgroup owns one strip of 16 output features; its
+// wavefronts split K into contiguous slices of NK 64-column steps.  The path is HBM-bound, so it is built
+// around the memory system: a wavefront first issues ALL weight loads of its slice (128-bit, non-temporal,
+// register-order storage from layout.h, so every byte is requested exactly once and as early as possible),
+// interleaved with the loads of its slice of X (L2 hits), and only then runs its matrix instructions.
+// Fewer, fatter wavefronts (16 KB of weights in flight each) measured faster than many thin ones.
+// Per 64-column step the wavefront takes ONE scalar branch on the tile type:
+//   dense : 2 x v_mfma_f32_16x16x32_bf16
+//   2:4   : 1 x v_smfmac_f32_16x16x64_bf16
+// The partial accumulators of the wavefronts meet in LDS and are summed in slice order, so results are
+// bit-reproducible; there is no global workspace, no atomics and no second launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,144 +27,166 @@ typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kDecodeChunkK = 1024;  // columns of X staged in LDS at a time
-constexpr int kXsStride = kDecodeChunkK + 8;
-
 union AFrag { u32x4 raw; bf16x8 v; };
 union BFrag { u32x4 raw[2]; bf16x8 h[2]; bf16x16 v; };
 
-template <int TILE>
-__global__ __launch_bounds__(256) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K,
-                                                     const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                     int Tk, int tiles_per_split, int S, float* __restrict__ ws,
-                                                     unsigned* __restrict__ counters, float* __restrict__ Y, int64_t N) {
-    constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows, TC = kDecodeChunkK / TILE;
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[16 * kXsStride];
-    __shared__ int s_is_last;
+template <int TILE, int NK, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K,
+                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
+                                                           int Tk, float* __restrict__ Y, int64_t N) {
+    constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
+    __shared__ f32x4 red[MAXW][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int strip = blockIdx.x * 4 + w;
+    const int KW = blockDim.x >> 6;
+    const int strip = blockIdx.x;
     const int tn = strip / SPT, s = strip % SPT;
-    const int split = blockIdx.y;
-    const int tk0 = split * tiles_per_split;
-    const int tk1 = (tk0 + tiles_per_split < Tk) ? tk0 + tiles_per_split : Tk;
     const int col = lane & 15, q = lane >> 4;
+    const bool xvalid = col < rows;
+    const uint32_t* trow = table + (int64_t)tn * Tk;
+    const int total = Tk * KPT;
+    // per-lane byte offsets, fixed for the whole kernel; every address below is a scalar base plus one of these
+    const uint32_t voff = lane * 16, voffm = lane * KPT * 2;
+    const uint32_t voffx = (uint32_t)(((xvalid ? col : 0) * K + 8 * q) * 2);
+    const uint8_t* xbase = reinterpret_cast<const uint8_t*>(X + m0 * K);
+    // lanes whose column is a row of X; the other lanes never load X and never store
+    const uint64_t xmask = __builtin_amdgcn_ballot_w64(xvalid);
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = w * NK; base < total; base += KW * NK) {
+        const int n = (total - base < NK) ? total - base : NK;
+        uint32_t ent[NK];
+#pragma unroll
+        for (int g = 0; g < NK; ++g) ent[g] = trow[((g < n) ? base + g : base) / KPT];
 
-    for (int tkc = tk0; tkc < tk1; tkc += TC) {
-        const int ntile = (tk1 - tkc < TC) ? tk1 - tkc : TC;
-        const int klen = ntile * TILE;
-        const int64_t kbase = (int64_t)tkc * TILE;
-        __syncthreads();
-        {
-            const int cpr = klen / 8;  // 16-byte chunks per row
-            for (int c = tid; c < 16 * cpr; c += 256) {
-                const int r = c / cpr, kk = (c % cpr) * 8;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (r < rows) v = *reinterpret_cast<const u32x4*>(X + (m0 + r) * K + kbase + kk);
-                *reinterpret_cast<u32x4*>(&Xs[r * kXsStride + kk]) = v;
+        // ---- every byte of the slice is requested now, weights and X interleaved step by step (issuing the X
+        // loads after all the weight loads measured 1.2 us slower).  One asm block per step: the compiler can
+        // neither sink these loads into the branches that consume them nor wait for them one by one.  A load
+        // the step does not need (second half of a 2:4 step, positions of a dense step, anything past the end of
+        // K, X for a lane without a row) is issued with an empty EXEC mask: it moves no data and leaves the zero
+        // its destination was initialised with.
+        u32x4 a[NK][2], b[NK][2];
+        uint32_t idx[NK];
+#pragma unroll
+        for (int g = 0; g < NK; ++g) {
+            const int k = (g < n) ? base + g : base;
+            const int j = k % KPT;
+            const uint32_t e = ent[g];
+            const int kind = (g < n) ? (int)(e & 1u) + 1 : 0;  // 0 = past the end, 1 = dense, 2 = 2:4
+            const uint8_t* tb = payload + entry_offset(e);
+            const uint8_t* sb0 = tb + (size_t)(s * KPT + j) * ((e & 1u) ? kSparseFragBytes : kDenseFragBytes);
+            // positions: one 16-bit word per lane and step; with two steps per tile the even step fetches the
+            // lane's dword for both (a fully used 256-byte row) and the odd step takes its upper half
+            const uint8_t* sbm = tb + sparse_vals_bytes(TILE) + (s * 64 * KPT) * 2;
+            const int mkind = (KPT == 2 && (g & 1)) ? 0 : kind;
+            const uint8_t* sbx = xbase + (size_t)k * (kStepCols * 2);
+            u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u}, x0 = {0u, 0u, 0u, 0u}, x1 = {0u, 0u, 0u, 0u};
+            uint32_t vi = 0;
+            uint64_t saved;
+// One step's loads.  LDM is the mnemonic of the positions load (16 or 32 bits per lane).
+#define PATCH_DECODE_STEP_LOADS(LDM)                                                                              \
+    asm volatile(                                                                                                 \
+        "s_mov_b64 %[sv], exec\n\t"                                                                               \
+        "s_cmp_lg_u32 %[kind], 0\n\t"                                                                             \
+        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "global_load_dwordx4 %[v0], %[vo], %[sb0] nt\n\t"                                                         \
+        "s_cmp_eq_u32 %[kind], 1\n\t"                                                                             \
+        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "global_load_dwordx4 %[v1], %[vo], %[sb0] offset:1024 nt\n\t"                                             \
+        "s_cmp_eq_u32 %[mkind], 2\n\t"                                                                            \
+        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        LDM " %[vi], %[vm], %[sbm] nt\n\t"                                                                        \
+        "s_cmp_lg_u32 %[kind], 0\n\t"                                                                             \
+        "s_cselect_b64 exec, %[xm], 0\n\t"                                                                        \
+        "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"                                                            \
+        "global_load_dwordx4 %[x1], %[vx], %[sbx] offset:64\n\t"                                                  \
+        "s_mov_b64 exec, %[sv]"                                                                                    \
+        : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi), [x0] "+v"(x0), [x1] "+v"(x1), [sv] "=&s"(saved)            \
+        : [vo] "v"(voff), [vm] "v"(voffm), [vx] "v"(voffx), [sb0] "s"(sb0), [sbm] "s"(sbm), [sbx] "s"(sbx),       \
+          [kind] "s"(kind), [mkind] "s"(mkind), [xm] "s"(xmask)                                                   \
+        : "memory", "scc")
+            if constexpr (KPT == 2) { PATCH_DECODE_STEP_LOADS("global_load_dword"); }
+            else { PATCH_DECODE_STEP_LOADS("global_load_ushort"); }
+#undef PATCH_DECODE_STEP_LOADS
+            a[g][0] = v0;
+            a[g][1] = v1;
+            idx[g] = vi;
+            b[g][0] = x0;
+            b[g][1] = x1;
+        }
+        // ---- wait for the loads (the compiler does not know about them), then tie every destination to this
+        // point so that no use can be scheduled above the wait
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int g = 0; g < NK; ++g)
+            asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(idx[g]), "+v"(b[g][0]), "+v"(b[g][1]));
+
+#pragma unroll
+        for (int g = 0; g < NK; ++g) {
+            BFrag bb;
+            bb.raw[0] = b[g][0];
+            bb.raw[1] = b[g][1];
+            AFrag a0, a1;
+            a0.raw = a[g][0];
+            a1.raw = a[g][1];
+            if (g < n) {
+                if (entry_sparse(ent[g])) {
+                    // two steps per tile: the even step's dword holds both position words
+                    const uint32_t pos = (KPT == 2 && (g & 1)) ? (idx[g - 1] >> 16) : idx[g];
+                    acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0.v, bb.v, acc, (int)pos, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, bb.h[0], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, bb.h[1], acc, 0, 0, 0);
+                }
             }
         }
-        __syncthreads();
-
-        for (int ti = 0; ti < ntile; ++ti) {
-            const uint32_t e = table[(int64_t)tn * Tk + tkc + ti];
-            const uint8_t* base = payload + entry_offset(e);
-            const uint16_t* xs = &Xs[col * kXsStride + ti * TILE + 8 * q];
-            if (entry_sparse(e)) {
-                const uint8_t* vals = base + (size_t)s * KPT * kSparseFragBytes + lane * 16;
-                const uint16_t* meta = reinterpret_cast<const uint16_t*>(base + sparse_vals_bytes(TILE)) + (s * 64 + lane) * KPT;
-                AFrag a[KPT];
-                uint32_t idx;
-#pragma unroll
-                for (int j = 0; j < KPT; ++j) a[j].raw = *reinterpret_cast<const u32x4*>(vals + j * kSparseFragBytes);
-                if constexpr (KPT == 2) idx = *reinterpret_cast<const uint32_t*>(meta);
-                else idx = *meta;
-#pragma unroll
-                for (int j = 0; j < KPT; ++j) {
-                    BFrag b;
-                    b.raw[0] = *reinterpret_cast<const u32x4*>(xs + 64 * j);
-                    b.raw[1] = *reinterpret_cast<const u32x4*>(xs + 64 * j + 32);
-                    if (j == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a[j].v, b.v, acc, (int)idx, 0, 0);
-                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a[j].v, b.v, acc, (int)idx, 0, 1);
-                }
-            } else {
-                const uint8_t* frag = base + (size_t)s * KPT * kDenseFragBytes + lane * 16;
-                AFrag a[KPT * 2];
-#pragma unroll
-                for (int jh = 0; jh < KPT * 2; ++jh) a[jh].raw = *reinterpret_cast<const u32x4*>(frag + jh * 1024);
-#pragma unroll
-                for (int j = 0; j < KPT; ++j) {
-                    BFrag b;
-                    b.raw[0] = *reinterpret_cast<const u32x4*>(xs + 64 * j);
-                    b.raw[1] = *reinterpret_cast<const u32x4*>(xs + 64 * j + 32);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[2 * j].v, b.h[0], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[2 * j + 1].v, b.h[1], acc, 0, 0, 0);
-                }
-            }
-        }
     }
 
-    // acc[r] = Y^T[strip*16 + 4 q + r][col]  ->  Y[m0 + col][strip*16 + 4 q + r]
-    const int64_t n = (int64_t)strip * 16 + 4 * q;
-    if (S == 1) {
-        if (col < rows) *reinterpret_cast<f32x4*>(Y + (m0 + col) * N + n) = acc;
-        return;
-    }
-    if (col < rows) *reinterpret_cast<f32x4*>(ws + ((int64_t)split * 16 + col) * N + n) = acc;
-    __threadfence();
+    // fixed-order reduction of the partials; acc[r] = Y^T[strip*16 + 4 q + r][col]
+    red[w][lane] = acc;
     __syncthreads();
-    if (tid == 0) {
-        const unsigned old = atomicAdd(&counters[blockIdx.x], 1u);
-        s_is_last = (old == (unsigned)(S - 1));
-    }
-    __syncthreads();
-    if (!s_is_last) return;
-    __threadfence();
-    {
-        const int c = tid & 63;
-        const int64_t nn = (int64_t)blockIdx.x * 64 + c;
-        for (int r = tid >> 6; r < rows; r += 4) {
-            float sum = 0.f;
-            for (int sp = 0; sp < S; ++sp)
-                sum += __hip_atomic_load(ws + ((int64_t)sp * 16 + r) * N + nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            Y[(m0 + r) * N + nn] = sum;
+    if (w == 0) {
+        f32x4 sum = red[0][lane];
+        for (int i = 1; i < KW; ++i) {
+            const f32x4 v = red[i][lane];
+            sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
+        if (xvalid) *reinterpret_cast<f32x4*>(Y + (m0 + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
     }
-    if (tid == 0) atomicExch(&counters[blockIdx.x], 0u);
 }
 
-int decode_max_split(int64_t N, int Tk) {
-    int64_t cap = 8192 / (N / 16);
-    if (cap < 1) cap = 1;
-    if (cap > 64) cap = 64;
-    return (int)(cap < Tk ? cap : Tk);
-}
-
-int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
-    (void)variant;
-    const int strips = (int)(a.N / 16);
-    int S = split_k;
-    if (S <= 0) {
-        const int target_waves = a.n_cus * 16;
-        S = (target_waves + strips / 2) / strips;
-        if (S < 1) S = 1;
-    }
-    const int smax = decode_max_split(a.N, a.Tk);
-    if (S > smax) S = smax;
-    while (S > 1 && (size_t)S * 16 * (size_t)a.N > a.ws_floats) --S;
-    int tps = (a.Tk + S - 1) / S;
-    S = (a.Tk + tps - 1) / tps;
-    dim3 grid((unsigned)(a.N / 64), (unsigned)S), block(256);
-    if (a.tile == 128)
-        hipLaunchKernelGGL(decode_kernel<128>, grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, tps, S, a.ws,
-                           a.counters, a.Y, a.N);
+template <int TILE>
+static void launch_decode_t(const GemmArgs& a, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
+    dim3 grid((unsigned)(a.N / 16)), block((unsigned)(kw * 64));
+    if (nk == 8)
+        hipLaunchKernelGGL((decode_kernel<TILE, 8, 8>), grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, a.Y, a.N);
     else
-        hipLaunchKernelGGL(decode_kernel<64>, grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, tps, S, a.ws,
-                           a.counters, a.Y, a.N);
-    return S;
+        hipLaunchKernelGGL((decode_kernel<TILE, 4, 16>), grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, a.Y, a.N);
+}
+
+// Schedule: NK = 64-column steps per wavefront and pass (8 or 4), KW = wavefronts per workgroup.
+// split_k > 0 forces KW; variant 2 / 3 forces NK = 8 / 4.
+// Default: NK = 8 if that still leaves about four wavefronts per compute unit, else 4.
+int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
+    const int64_t strips = a.N / 16;
+    const int total = a.Tk * (a.tile / kStepCols);
+    int nk = 0;
+    if (variant == 2) nk = 8;
+    else if (variant == 3) nk = 4;
+    if (nk == 0 && split_k > 0) nk = ((total + split_k - 1) / split_k > 4) ? 8 : 4;
+    if (nk == 0) {
+        int kw8 = (total + 7) / 8;
+        if (kw8 > 8) kw8 = 8;
+        nk = (strips * kw8 >= (int64_t)a.n_cus * 4) ? 8 : 4;
+    }
+    const int maxw = (nk == 4) ? 16 : 8;
+    int kw = split_k > 0 ? split_k : (total + nk - 1) / nk;
+    if (kw > maxw) kw = maxw;
+    if (kw < 1) kw = 1;
+    if (a.tile == 128) launch_decode_t<128>(a, m0, rows, nk, kw, stream);
+    else launch_decode_t<64>(a, m0, rows, nk, kw, stream);
+    return kw;
 }
 
 }  // namespace patch

@@ -20,15 +20,12 @@ struct GemmArgs {
     const uint8_t* payload;
     const uint32_t* table;  // Tn x Tk entries
     float* Y;               // M x N fp32
-    float* ws;              // split-K workspace, ws_floats floats
-    size_t ws_floats;
-    unsigned* counters;     // one per 64-row block of N, all zero between calls
     int n_cus;
 };
 
-// M <= 16 rows of X starting at row m0 (decode shape).  split_k = 0 picks a default.  Returns the split used.
+// M <= 16 rows of X starting at row m0 (decode shape).  split_k = K slices (wavefronts) per workgroup,
+// 0 picks a default.  Returns the number used.
 int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
-int decode_max_split(int64_t N, int Tk);
 
 // Any M (prefill shape).
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream);

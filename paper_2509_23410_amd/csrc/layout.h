@@ -37,6 +37,7 @@ namespace patch {
 constexpr int kGranule = 256;        // tile start alignment / unit of the offset table
 constexpr int kStripRows = 16;       // rows of a fragment
 constexpr int kStepCols = 64;        // columns of a fragment
+constexpr int kZeroPad = 1024;       // zeroed slack kept behind the payload
 constexpr int kDenseFragBytes = 2048;
 constexpr int kSparseFragBytes = 1024;
 

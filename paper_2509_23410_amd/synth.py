@@ -70,11 +70,20 @@ def mask24_magnitude(W_bits: np.ndarray) -> np.ndarray:
     W_bits = np.ascontiguousarray(W_bits, dtype=np.uint16)
     N, K = W_bits.shape
     assert K % 4 == 0
-    mag = (W_bits & np.uint16(0x7FFF)).astype(np.int32).reshape(N, K // 4, 4)
-    # stable sort on descending magnitude: ties keep ascending index
-    order = np.argsort(-mag, axis=2, kind="stable")
-    keep = np.zeros((N, K // 4, 4), np.uint8)
-    np.put_along_axis(keep, order[:, :, :2], 1, axis=2)
+    mag = (W_bits & np.uint16(0x7FFF)).reshape(N, K // 4, 4)
+    # rank of element p = number of elements that beat it (larger magnitude, or equal magnitude at a
+    # lower index); keep the elements of rank 0 and 1
+    keep = np.empty((N, K // 4, 4), np.uint8)
+    for p in range(4):
+        beaten = np.zeros((N, K // 4), np.uint8)
+        for o in range(4):
+            if o == p:
+                continue
+            if o < p:
+                beaten += mag[:, :, o] >= mag[:, :, p]
+            else:
+                beaten += mag[:, :, o] > mag[:, :, p]
+        keep[:, :, p] = beaten < 2
     return keep.reshape(N, K)
 
 
