@@ -158,8 +158,219 @@ __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restr
     }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Main prefill kernel (tile = 128): 256 features x 256 rows per workgroup, 8 wavefronts, 64-column K-steps,
+// LDS double buffer filled by direct global->LDS loads.
+//
+//   wavefront w < 4 : tile row 0 of the block (features 0..127),   rows 64 w .. 64 w + 63
+//   wavefront w >= 4: tile row 1 of the block (features 128..255), rows 64 (w-4) ..
+// The two wavefronts that share a SIMD (w and w + 4) thus always own DIFFERENT tile rows, so every SIMD
+// carries cost(tile row 0) + cost(tile row 1) matrix cycles per K-step whatever the tile types are: the
+// dense/2:4 mix cannot unbalance the workgroup between two barriers.
+//
+// LDS per stage: weight fragments [tile row][strip][2048 B] (a 2:4 strip uses the first 1024 B), X tile
+// 256 rows x 128 B with the XOR swizzle of xs_off(); plus the position words of the current 2:4 tiles.
+// ------------------------------------------------------------------------------------------------------
+constexpr int kPfBN = 256, kPfBM = 256;
+constexpr int kPfAStage = 2 * 8 * kDenseFragBytes;   // 32 KB
+constexpr int kPfBStage = kPfBM * 128;               // 32 KB
+constexpr int kPfMetaBuf = 2 * 2048;                 // two tile rows x 2 KB of position words (tile 128)
+constexpr int kPfLds = 2 * kPfAStage + 2 * kPfBStage + 2 * kPfMetaBuf;
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ __forceinline__ void g2l16(const void* g, void* l) {
+    // 16 bytes per lane, global -> LDS, no registers: LDS address = (wave-uniform) l + lane * 16
+    __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
+}
+
+// One 32-column half-step of a 32-feature block against two 32-row blocks, in place:
+//   2:4   : c0 += A0 (*) B0, c1 += A0 (*) B1                         (v_smfmac_f32_32x32x32_bf16, positions idx)
+//   dense : c0 += A0 B0.lo + A1 B0.hi, c1 += A0 B1.lo + A1 B1.hi     (v_mfma_f32_32x32x16_bf16)
+// The wavefront-uniform choice is a scalar branch INSIDE the asm block.  Written with the compiler builtins
+// and an if/else, the accumulators of the two arms end up in different registers (the register allocator
+// splits the 16-register tuples at the branch), which doubles the accumulator footprint and spills to
+// scratch; here the compiler sees straight-line code and every accumulator tile stays in one place.
+// It does not see the matrix instructions either: the epilogue pads the matrix-pipe -> memory read hazard.
+__device__ __forceinline__ void mma_step(f32x16& c0, f32x16& c1, const bf16x8& a0, const bf16x8& a1, const B16& b0,
+                                         const B16& b1, int idx, int sparse) {
+    asm volatile(
+        "s_cmp_eq_u32 %[sp], 0\n\t"
+        "s_cbranch_scc1 .Ldense%=\n\t"
+        "v_smfmac_f32_32x32x32_bf16 %[c0], %[a0], %[b0], %[idx]\n\t"
+        "v_smfmac_f32_32x32x32_bf16 %[c1], %[a0], %[b1], %[idx]\n\t"
+        "s_branch .Ldone%=\n"
+        ".Ldense%=:\n\t"
+        "v_mfma_f32_32x32x16_bf16 %[c0], %[a0], %[b0lo], %[c0]\n\t"
+        "v_mfma_f32_32x32x16_bf16 %[c1], %[a0], %[b1lo], %[c1]\n\t"
+        "v_mfma_f32_32x32x16_bf16 %[c0], %[a1], %[b0hi], %[c0]\n\t"
+        "v_mfma_f32_32x32x16_bf16 %[c1], %[a1], %[b1hi], %[c1]\n"
+        ".Ldone%=:"
+        : [c0] "+v"(c0), [c1] "+v"(c1)
+        : [a0] "v"(a0), [a1] "v"(a1), [b0] "v"(b0.v), [b1] "v"(b1.v), [b0lo] "v"(b0.h[0]), [b0hi] "v"(b0.h[1]),
+          [b1lo] "v"(b1.h[0]), [b1hi] "v"(b1.h[1]), [idx] "v"(idx), [sp] "s"(sparse)
+        : "scc");
+}
+
+__global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
+                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
+                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y) {
+    constexpr int TILE = 128, KPT = 2;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint8_t* const As = lds;                                  // [stage][tile row][strip][2048]
+    uint8_t* const Bs = lds + 2 * kPfAStage;                  // [stage][256 rows][128 B] swizzled
+    uint8_t* const Ms = lds + 2 * kPfAStage + 2 * kPfBStage;  // [tile parity][tile row][2048]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = w >> 2, wm = w & 3;  // tile row of the block, 64-row group
+
+    // ---- block -> (n, m) tile of the output; consecutive blocks go to different XCDs (hardware round-robin),
+    // so give each of the 8 XCDs a contiguous run of tiles walking M first: they share weight fragments in L2
+    const int nblk = tiles_n * tiles_m;
+    int bid = blockIdx.x;
+    {
+        const int per = (nblk + 7) / 8;
+        const int x = bid & 7, i = bid >> 3;
+        const int t = x * per + i;
+        bid = (i < per && t < nblk) ? t : -1;
+    }
+    if (bid < 0) return;
+    const int bn = bid / tiles_m, bm = bid % tiles_m;
+    const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * kPfBM;
+    const bool row_live = n0 + 128 * r < N;  // N is a multiple of 128, not necessarily of 256
+    const int tn = (int)(n0 / TILE) + (row_live ? r : 0);
+    const uint32_t* trow0 = table + (int64_t)(n0 / TILE) * Tk;
+    const bool two_rows = n0 + 128 < N;
+    const uint32_t* trow1 = trow0 + (two_rows ? Tk : 0);
+    const uint32_t* trow_mine = table + (int64_t)tn * Tk;
+
+    // ---- per-lane source pointers for the X tile copy: wavefront w copies 1 KB pieces w, w+8, w+16, w+24
+    const uint8_t* xsrc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = (w + 8 * i) * 64 + lane;       // physical 16-byte chunk of the tile
+        const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
+        int64_t row = m0 + m;
+        if (row >= M) row = M - 1;                     // rows past M: any valid row, their outputs are not stored
+        xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8);
+    }
+
+    auto prefetch = [&](int ks, int stage) {
+        const int tk = ks >> 1, j = ks & 1;
+        // weights: wavefront w copies strip w of both tile rows
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            if (rr == 1 && !two_rows) break;
+            const uint32_t e = (rr ? trow1 : trow0)[tk];
+            const uint8_t* tb = payload + entry_offset(e);
+            uint8_t* dst = As + stage * kPfAStage + (rr * 8 + w) * kDenseFragBytes;
+            if (entry_sparse(e)) {
+                g2l16(tb + (size_t)(w * KPT + j) * kSparseFragBytes + lane * 16, dst);
+                if (j == 0 && w < 2) {  // the tile's 2 KB of position words, once per tile
+                    g2l16(tb + sparse_vals_bytes(TILE) + w * 1024 + lane * 16, Ms + (tk & 1) * kPfMetaBuf + rr * 2048 + w * 1024);
+                }
+            } else {
+                const uint8_t* f = tb + (size_t)(w * KPT + j) * kDenseFragBytes + lane * 16;
+                g2l16(f, dst);
+                g2l16(f + 1024, dst + 1024);
+            }
+        }
+        // X tile
+#pragma unroll
+        for (int i = 0; i < 4; ++i) g2l16(xsrc[i] + (size_t)ks * 128, Bs + stage * kPfBStage + (w + 8 * i) * 1024);
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int i32 = lane & 31, q = lane >> 5;
+    const int ksteps = (int)(K / kStepCols);
+    // LDS byte offsets of this lane inside a strip's fragment; a 32-feature block a covers strips 2a, 2a+1
+    const int lane_frag = ((i32 >> 4) * kDenseFragBytes) + (16 * q + (i32 & 15)) * 16;
+    const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * 4;
+    prefetch(0, 0);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const int stage = ks & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        // always issued (the last step re-fetches itself into the idle stage): no branch around the loads
+        prefetch((ks + 1 < ksteps) ? ks + 1 : ks, stage ^ 1);
+
+        const int tk = ks >> 1, j = ks & 1;
+        const uint32_t e = __builtin_amdgcn_readfirstlane(trow_mine[tk]);
+        const int sp = (int)(e & 1u);
+        const uint8_t* as = As + stage * kPfAStage + r * 8 * kDenseFragBytes + lane_frag;
+        const uint8_t* bs = Bs + stage * kPfBStage;
+        const uint8_t* ms = Ms + (tk & 1) * kPfMetaBuf + r * 2048 + lane_meta;
+        // half-step u of a strip: 2:4 fragment half at u * 512, dense operand pair at u * 1024 and + 512
+        const int ustride = sp ? 512 : 1024;
+
+        // X fragments as 8-register pairs: a 2:4 instruction takes a pair, a dense one either half
+        B16 xb[2][2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int m = wm * 64 + b * 32 + i32;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) xb[b][c >> 1].raw[c & 1] = *reinterpret_cast<const u32x4*>(bs + xs_off(m, 2 * c + q));
+        }
+        // All LDS reads are unconditional: a 2:4 half-step reads one fragment it does not use, a dense one a
+        // position word it does not use (LDS bandwidth has that slack, the register allocator has none).
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                A8 a0, a1;
+                a0.raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride);
+                a1.raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride + 512);
+                const uint32_t pw = *reinterpret_cast<const uint32_t*>(ms + a * 2 * 64 * 4 + u * 32 * 4);
+                const int idx = (int)(pw >> (16 * j));
+                mma_step(acc[a][0], acc[a][1], a0.v, a1.v, xb[0][u], xb[1][u], idx, sp);
+            }
+        }
+    }
+
+    // the idle-stage loads of the last step must land before this workgroup's LDS can be handed on
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // rows of the block past N computed on whatever was in LDS; nothing of theirs is stored
+    if (!row_live) return;
+    // the last matrix instructions may still be writing their accumulators: 16-pass results need up to 18 wait
+    // states before another unit may read them
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // acc[a][b][i]: feature n0 + 128 r + 32 a + 8 (i/4) + 4 q + i%4, row m0 + 64 wm + 32 b + i32
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int64_t m = m0 + 64 * wm + 32 * b + i32;
+        if (m >= M) continue;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                *reinterpret_cast<f32x4*>(Y + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q) = v;
+            }
+    }
+}
+
+// variant 0: tile 128 -> prefill_kernel_t128, tile 64 -> prefill_kernel_v0; variant 1 forces prefill_kernel_v0.
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream) {
-    (void)variant;
+    if (a.tile == 128 && variant == 0) {
+        static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_t128),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+        (void)granted;
+        const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kPfBM - 1) / kPfBM);
+        const int nblk = tiles_n * tiles_m;
+        const int grid = ((nblk + 7) / 8) * 8;
+        hipLaunchKernelGGL(prefill_kernel_t128, dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk,
+                           tiles_n, tiles_m, a.Y);
+        return;
+    }
     dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);
     if (a.tile == 128)
         hipLaunchKernelGGL((prefill_kernel_v0<128, 128>), grid, block, 0, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, a.Y);
