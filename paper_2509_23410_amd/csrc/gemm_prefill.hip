@@ -257,13 +257,14 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8);
     }
 
-    auto prefetch = [&](int ks, int stage) {
+    // Fill one LDS stage with K-step ks; e0 / e1 are the table entries of the two tile rows at that step.
+    auto prefetch = [&](int ks, int stage, uint32_t e0, uint32_t e1) {
         const int tk = ks >> 1, j = ks & 1;
         // weights: wavefront w copies strip w of both tile rows
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             if (rr == 1 && !two_rows) break;
-            const uint32_t e = (rr ? trow1 : trow0)[tk];
+            const uint32_t e = rr ? e1 : e0;
             const uint8_t* tb = payload + entry_offset(e);
             uint8_t* dst = As + stage * kPfAStage + (rr * 8 + w) * kDenseFragBytes;
             if (entry_sparse(e)) {
@@ -291,21 +292,20 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
     const int i32 = lane & 31, q = lane >> 5;
-    const int ksteps = (int)(K / kStepCols);
     // LDS byte offsets of this lane inside a strip's fragment; a 32-feature block a covers strips 2a, 2a+1
     const int lane_frag = ((i32 >> 4) * kDenseFragBytes) + (16 * q + (i32 & 15)) * 16;
     const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * 4;
-    prefetch(0, 0);
-    for (int ks = 0; ks < ksteps; ++ks) {
+    // One K-step: wait for the stage, refill the other one, multiply.  e_mine: table entry of this wavefront's
+    // tile at step ks; (pf_ks, pf_e0, pf_e1): the step to fetch into the idle stage and its entries.
+    auto step = [&](int ks, uint32_t e_mine, int pf_ks, uint32_t pf_e0, uint32_t pf_e1) {
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        // always issued (the last step re-fetches itself into the idle stage): no branch around the loads
-        prefetch((ks + 1 < ksteps) ? ks + 1 : ks, stage ^ 1);
-
+#ifndef LAB_NO_LOADS
+        prefetch(pf_ks, stage ^ 1, pf_e0, pf_e1);
+#endif
         const int tk = ks >> 1, j = ks & 1;
-        const uint32_t e = __builtin_amdgcn_readfirstlane(trow_mine[tk]);
-        const int sp = (int)(e & 1u);
+        const int sp = (int)(e_mine & 1u);
         const uint8_t* as = As + stage * kPfAStage + r * 8 * kDenseFragBytes + lane_frag;
         const uint8_t* bs = Bs + stage * kPfBStage;
         const uint8_t* ms = Ms + (tk & 1) * kPfMetaBuf + r * 2048 + lane_meta;
@@ -322,18 +322,41 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         }
         // All LDS reads are unconditional: a 2:4 half-step reads one fragment it does not use, a dense one a
         // position word it does not use (LDS bandwidth has that slack, the register allocator has none).
+        // The operands of a (block, half) are fetched two positions ahead of the matrix instructions that use
+        // them: an LDS round trip is longer than the 64-128 matrix cycles of one position.
+        A8 fa0[3], fa1[3];
+        uint32_t fpw[3];
+        auto fetch = [&](int pos, int buf) {
+            const int a = pos >> 1, u = pos & 1;
+            fa0[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride);
+            fa1[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride + 512);
+            fpw[buf] = *reinterpret_cast<const uint32_t*>(ms + a * 2 * 64 * 4 + u * 32 * 4);
+        };
+        fetch(0, 0);
+        fetch(1, 1);
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                A8 a0, a1;
-                a0.raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride);
-                a1.raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride + 512);
-                const uint32_t pw = *reinterpret_cast<const uint32_t*>(ms + a * 2 * 64 * 4 + u * 32 * 4);
-                const int idx = (int)(pw >> (16 * j));
-                mma_step(acc[a][0], acc[a][1], a0.v, a1.v, xb[0][u], xb[1][u], idx, sp);
-            }
+        for (int pos = 0; pos < 8; ++pos) {
+            if (pos + 2 < 8) fetch(pos + 2, (pos + 2) % 3);
+            const int a = pos >> 1, u = pos & 1, buf = pos % 3;
+            const int idx = (int)(fpw[buf] >> (16 * j));
+#ifndef LAB_NO_MMA
+            mma_step(acc[a][0], acc[a][1], fa0[buf].v, fa1[buf].v, xb[0][u], xb[1][u], idx, sp);
+#else
+            acc[a][0][0] += (float)(fa0[buf].raw[0] + fa1[buf].raw[1] + xb[0][u].raw[0][0] + xb[1][u].raw[1][1] + idx);
+#endif
         }
+    };
+
+    // Table entries are read one tile ahead of their first use, so no step starts by waiting for a scalar load.
+    uint32_t e0 = trow0[0], e1 = trow1[0], em = trow_mine[0];
+    prefetch(0, 0, e0, e1);
+    for (int tk = 0; tk < Tk; ++tk) {
+        const int tkn = (tk + 1 < Tk) ? tk + 1 : tk;
+        const uint32_t e0n = trow0[tkn], e1n = trow1[tkn], emn = trow_mine[tkn];
+        step(2 * tk, em, 2 * tk + 1, e0, e1);
+        // the very last step re-fetches itself into the idle stage: no branch around the loads
+        step(2 * tk + 1, em, (tk + 1 < Tk) ? 2 * tk + 2 : 2 * tk + 1, e0n, e1n);
+        e0 = e0n; e1 = e1n; em = emn;
     }
 
     // the idle-stage loads of the last step must land before this workgroup's LDS can be handed on
@@ -353,6 +376,9 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+#ifdef LAB_NO_STORE
+                if (v[0] == 1.2345f)
+#endif
                 *reinterpret_cast<f32x4*>(Y + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q) = v;
             }
     }
