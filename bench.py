@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (known traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -81,6 +83,12 @@ def main():
         return e0.elapsed_time(e1) * 1e-3  # seconds
 
     out = {}
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # ------------------------------------------------------------------ headline: 7B MLP prefill
     M, f, t = args.m, args.f, 128
     shapes = [("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
@@ -112,9 +120,16 @@ def main():
     value = dense_flop / (ms_per_step * 1e-3) / 1e12
     n_launch = len(layers)
     avg_launch_s = ms_per_step * 1e-3 / n_launch
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "prefill_traffic.json")
+    if os.path.exists(tpath) and M == 4096 and f == 0.6:
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch")   # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
     roof = dict(bound="mfma", achieved=issued_flop / n_launch / avg_launch_s / 1e12, peak=PEAK_MFMA_BF16_TF, unit="TFLOP/s",
-                traffic=None, kernel="prefill_kernel", avg_launch_us=avg_launch_s * 1e6,
-                note="achieved = issued matrix flops M N K (2 - f) per launch / average launch duration (HIP events)")
+                traffic=traffic, kernel="prefill_kernel_t128", avg_launch_us=avg_launch_s * 1e6,
+                algorithmic_flop_per_launch=issued_flop / n_launch,
+                note="achieved = issued matrix flops M N K (2 - f) per launch / average launch duration (HIP events); "
+                     "traffic = measured HBM bytes per launch (profiles/)")
     roof["frac"] = roof["achieved"] / roof["peak"]
 
     # ------------------------------------------------------------------ same shapes, all-dense tile map
@@ -180,6 +195,10 @@ def main():
             for P_ in Ps:
                 P_.close()
             del W_hat
+        m1 = [r_ for r_ in dec if r_["M"] == 1 and r_["f"] == 0.0][0]
+        out["decode_roofline"] = dict(bound="hbm", achieved=m1["GBps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=m1["frac_hbm"],
+                                      traffic=None, kernel="decode_kernel", workload="4096x4096 f=0 M=1",
+                                      note="compressed weight bytes per launch / average launch duration")
         out["decode"] = dict(workload="llama7b_attn_decode 4096x4096 tile128", peak_GBps=PEAK_HBM_GBS, rows=dec,
                              note="us = median of 5 batches of back-to-back launches over rotating packed copies (HBM-resident)")
 

@@ -40,7 +40,8 @@ typedef enum {
     PATCH_ERR_SIZE = 6    /* a caller-provided host buffer is too small                              */
 } patch_status;
 
-/* Which kernel family patch_gemm_ex uses.  AUTO: decode for M <= 16, prefill otherwise. */
+/* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of 16 rows, PREFILL in 256-row
+ * tiles.  AUTO: decode for M <= 128 (measured crossover), prefill otherwise. */
 typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
 
 /* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and

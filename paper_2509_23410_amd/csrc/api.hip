@@ -175,7 +175,9 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
-    if (path == PATCH_PATH_AUTO) path = (M <= 16) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    // measured crossover: up to 128 rows, 16-row decode passes beat the 256 x 256-tile prefill kernel, whose
+    // grid is too small to fill the chip at that M
+    if (path == PATCH_PATH_AUTO) path = (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a;
     a.X = static_cast<const uint16_t*>(X);

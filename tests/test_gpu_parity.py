@@ -221,3 +221,67 @@ def test_full_size_decode_sampled(dev):
             got = Y[mn[:, 0], mn[:, 1]].astype(np.float64)
             assert float(np.linalg.norm(got - ref) / np.linalg.norm(ref)) <= TIGHT
         p.P.close()
+
+
+def _sampled_checks(p, c, Xb, Y, rng, n_points=2048, n_rows=32):
+    """Checks at sizes where the full fp64 product is too slow on a CPU: (1) sampled outputs computed one by
+    one from the definition, (2) a seeded sample of whole rows, (3) a Freivalds projection over the full
+    output: r^T Y = (r^T X) W_hat^T for a random sign vector r."""
+    M = Xb.shape[0]
+    assert np.isfinite(Y).all(), "unwritten outputs"
+    mn = np.stack([rng.integers(0, M, n_points), rng.integers(0, c.N, n_points)], axis=1)
+    ref = oracle.gemm_points(Xb, p.W_hat_o, mn)
+    got = Y[mn[:, 0], mn[:, 1]].astype(np.float64)
+    assert float(np.linalg.norm(got - ref) / np.linalg.norm(ref)) <= TIGHT
+    rows = np.sort(rng.choice(M, size=min(n_rows, M), replace=False))
+    Yo = oracle.gemm(np.ascontiguousarray(Xb[rows]), p.vals_o, p.meta_o, c.N, c.K, c.tile_map, c.tile)
+    assert relF(Y[rows], Yo) <= TIGHT
+    r = rng.choice(np.array([-1.0, 1.0]), size=M)
+    lhs = r @ Y.astype(np.float64)
+    rhs = (r @ synth.bf16_bits_to_f64(Xb)) @ synth.bf16_bits_to_f64(p.W_hat_o).T
+    assert float(np.linalg.norm(lhs - rhs) / np.linalg.norm(rhs)) <= 1e-4
+
+
+@pytest.mark.parametrize("N,K,M", [(11008, 4096, 4096), (4096, 11008, 2048)])
+def test_full_size_prefill_sampled(dev, N, K, M):
+    """7B MLP prefill at full size, in the launch configuration the benchmark times (tile 128, 60 % 2:4 tiles)."""
+    print(f"prefill N={N} K={K} M={M}", flush=True)
+    c = synth.make_case("mlp_prefill", N, K, M, 128, 0.6, seed=7)
+    p = Prepared(c, dev)
+    vals, meta = B.patch_export_canonical(p.P)
+    assert np.array_equal(vals, p.vals_o) and np.array_equal(meta, p.meta_o)
+    Y = p.gemm(c.X)
+    _sampled_checks(p, c, c.X, Y, np.random.default_rng(2))
+    # ragged M on the same weights: last row block partly empty
+    Mr = M - 77
+    Yr = p.gemm(c.X[:Mr])
+    assert np.array_equal(Yr, Y[:Mr]), "rows must not depend on how many rows follow them"
+    p.P.close()
+
+
+def test_13b_layer_shapes_sampled(dev):
+    """One decoder layer of the 13B stack (q/k/v/o 5120^2, gate/up 13824 x 5120, down 5120 x 13824) with the
+    layer's 2:4 fraction drawn U[0,1), at M = 1 and M = 512."""
+    fr = synth.layer_fractions(0, 40)
+    for li, (N, K) in [(3, (5120, 5120)), (17, (13824, 5120)), (29, (5120, 13824))]:
+        f = float(fr[li])
+        print(f"13B layer {li} N={N} K={K} f={f:.3f}", flush=True)
+        c = synth.make_case(f"l13b_{li}", N, K, 512, 128, f, seed=8)
+        p = Prepared(c, dev)
+        rng = np.random.default_rng(li)
+        for M in (1, 512):
+            Y = p.gemm(c.X[:M])
+            _sampled_checks(p, c, c.X[:M], Y, rng, n_points=1024, n_rows=8)
+        p.P.close()
+
+
+def test_mid_m_paths_agree(dev):
+    """M around the decode / prefill crossover: both paths must give the oracle's result."""
+    c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
+    p = Prepared(c, dev)
+    for M in (17, 100, 128, 129, 256, 257, 300):
+        Yo = p.oracle_gemm(c.X[:M])
+        for path in (B.PATH_AUTO, B.PATH_DECODE, B.PATH_PREFILL):
+            print(f"mid M={M} path={path}", flush=True)
+            assert relF(p.gemm(c.X[:M], path=path), Yo) <= TIGHT
+    p.P.close()
