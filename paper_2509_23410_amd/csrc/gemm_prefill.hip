@@ -403,6 +403,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
 // variant 0: tile 128 -> prefill_kernel_t128, tile 64 -> prefill_kernel_v0; variant 1 forces prefill_kernel_v0.
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream) {
     if (a.tile == 128 && variant == 3) { launch_prefill_ring(a, stream); return; }
+    if (a.tile == 128 && variant == 4) { launch_prefill_wreg(a, stream); return; }
     if (a.tile == 128 && (variant == 0 || variant == 2)) {
         static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_t128),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);

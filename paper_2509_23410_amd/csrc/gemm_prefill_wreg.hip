@@ -1,0 +1,379 @@
+// Prefill-shaped hybrid GEMM for tile = 128 with the weights loaded straight into registers (Section 4 /
+// Appendix A of the paper: the product for the prefill input, dense and 2:4 tiles mixed inside one launch).
+//
+// Workgroup = 256 output features (two tile rows) x 256 rows of X, 4 wavefronts (one per SIMD).  Wavefront w owns
+// 64 features (4 strips of tile row w / 2) x ALL 256 rows of X: its weight fragments are private, so they go
+// global -> registers in the stored register order (layout.h) with no LDS traffic, no transposition and no barrier
+// between producer and consumer, two 64-column steps ahead.  X is shared by the four wavefronts and goes
+// global -> LDS directly (no registers) in whole 128-byte rows, three steps ahead, through a ring of four 32 KB
+// stages.  Every row of X in a step is one full cache line: a 32-column step would use half of each line it
+// pulls through the vector L1 and was measured to cost 1.5x the L1 <- L2 requests.
+//
+// A step is 16 "column blocks" (16 rows of X each).  Per column block and wavefront:
+//   dense: 8 x v_mfma_f32_16x16x32_bf16   or   2:4: 4 x v_smfmac_f32_16x16x64_bf16
+// plus the two LDS reads of the column block three ahead (across step boundaries: the LDS pipeline never drains)
+// and at most one global load.  With one wavefront per SIMD nothing hides an instruction that is not a matrix
+// instruction, and a taken branch is a bubble in the matrix pipe, so the dense / 2:4 decision is ONE scalar branch
+// per step (a wavefront works on one tile at a time) around two branch-free instruction streams.
+//
+// Registers.  Everything that is loaded asynchronously or lives across that branch is addressed BY NAME in the asm
+// statements and never seen by the compiler as a value:
+//   a[0:255]     the 64 accumulator tiles (strip s, column block cb) at a[4 (16 s + cb) .. + 3]
+//   v[128:223]   weights of three steps in rotation, 8 x 4 registers each (see PATCH_WR_VA)
+//   v[224:255]   X operands of four column blocks in rotation, 8 registers each
+// As compiler values they would meet at the branch (and at the loop edge) as phi nodes, where the register
+// allocator may insert copies - it did: it split the accumulators and spilled, and it copied X operands whose
+// LDS reads were still in flight.  Every asm statement declares all of these registers clobbered, so the compiler
+// keeps nothing of its own there; its own values fit below v128 and it uses no accumulation register, which
+// tests/test_abi_host.py checks on the generated assembly.
+// The loads are counted, not tracked: every step issues exactly 16 vector-memory loads per wavefront (8 for the
+// weights whatever the tile type, 8 for X) and 32 LDS reads, so every s_waitcnt below is a compile-time constant.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+#include "layout.h"
+
+namespace patch {
+
+typedef float wr_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWrBN = 256, kWrBM = 256;
+constexpr int kWrStage = kWrBM * 128;   // 256 rows of X x 64 columns, swizzled
+constexpr int kWrLds = 4 * kWrStage;    // 128 KB
+
+typedef const __attribute__((address_space(1))) void* wr_gptr_t;
+typedef __attribute__((address_space(3))) void* wr_lptr_t;
+
+__device__ __forceinline__ void wr_g2l16(const void* g, void* l) {
+    // 16 bytes per lane, global -> LDS, no registers: LDS address = (wave-uniform) l + lane * 16
+    __builtin_amdgcn_global_load_lds((wr_gptr_t)g, (wr_lptr_t)l, 16, 0, 0);
+}
+
+// ---- register names (the assembler evaluates the index expressions)
+// accumulator tile of strip S, column block CB
+#define PATCH_WR_C(S, CB) "a[4*(16*" #S "+" #CB "):4*(16*" #S "+" #CB ")+3]"
+// weight register I (0..7) of step buffer AB (0..2):
+//   dense: I = 2 s + h: operand h of strip s;   2:4: I = s: values of strip s, I = 4 + s: position dword in its first register
+#define PATCH_WR_VA(AB, I) "v[128+32*" #AB "+4*" #I ":128+32*" #AB "+4*" #I "+3]"
+#define PATCH_WR_VI(AB, S) "v[128+32*" #AB "+16+4*" #S "]"
+// X operand set SET (0..3): low / high half (the two dense operands) and the pair (the 2:4 operand)
+#define PATCH_WR_VBL(SET) "v[224+8*" #SET ":224+8*" #SET "+3]"
+#define PATCH_WR_VBH(SET) "v[228+8*" #SET ":228+8*" #SET "+3]"
+#define PATCH_WR_VB(SET) "v[224+8*" #SET ":224+8*" #SET "+7]"
+#define PATCH_WR_R8(r, p) r #p "0", r #p "1", r #p "2", r #p "3", r #p "4", r #p "5", r #p "6", r #p "7"
+#define PATCH_WR_R10(r, p) PATCH_WR_R8(r, p), r #p "8", r #p "9"
+#define PATCH_WR_CLOBBER                                                                                           \
+    "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", PATCH_WR_R10("a", 1), PATCH_WR_R10("a", 2),          \
+        PATCH_WR_R10("a", 3), PATCH_WR_R10("a", 4), PATCH_WR_R10("a", 5), PATCH_WR_R10("a", 6), PATCH_WR_R10("a", 7),  \
+        PATCH_WR_R10("a", 8), PATCH_WR_R10("a", 9), PATCH_WR_R10("a", 10), PATCH_WR_R10("a", 11), PATCH_WR_R10("a", 12), \
+        PATCH_WR_R10("a", 13), PATCH_WR_R10("a", 14), PATCH_WR_R10("a", 15), PATCH_WR_R10("a", 16),                  \
+        PATCH_WR_R10("a", 17), PATCH_WR_R10("a", 18), PATCH_WR_R10("a", 19), PATCH_WR_R10("a", 20),                  \
+        PATCH_WR_R10("a", 21), PATCH_WR_R10("a", 22), PATCH_WR_R10("a", 23), PATCH_WR_R10("a", 24), "a250", "a251",  \
+        "a252", "a253", "a254", "a255", "v128", "v129", PATCH_WR_R10("v", 13), PATCH_WR_R10("v", 14),                \
+        PATCH_WR_R10("v", 15), PATCH_WR_R10("v", 16), PATCH_WR_R10("v", 17), PATCH_WR_R10("v", 18),                  \
+        PATCH_WR_R10("v", 19), PATCH_WR_R10("v", 20), PATCH_WR_R10("v", 21), PATCH_WR_R10("v", 22),                  \
+        PATCH_WR_R10("v", 23), PATCH_WR_R10("v", 24), "v250", "v251", "v252", "v253", "v254", "v255"
+
+// ---- one column block CB of X (operand set SET) against the wavefront's four strips (weights of step buffer AB),
+// after waiting for its operands, plus the two LDS reads of the column block three ahead into set NSET.
+#define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, al_, ah_, OFF)                                                     \
+    asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
+                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:%[off]\n\t"                                    \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
+                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:%[off]\n\t"                                    \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 4) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 6) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 5) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
+                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB)          \
+                 :                                                                                                 \
+                 : [al] "v"(al_), [ah] "v"(ah_), [off] "n"(OFF)                                                    \
+                 : PATCH_WR_CLOBBER)
+// J selects the K-step's half of the position dwords
+#define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, J, al_, ah_, OFF)                                                 \
+    asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
+                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:%[off]\n\t"                                    \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
+                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:%[off]\n\t"                                    \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J          \
+                 :                                                                                                 \
+                 : [al] "v"(al_), [ah] "v"(ah_), [off] "n"(OFF)                                                    \
+                 : PATCH_WR_CLOBBER)
+// weight load I of a step into buffer AB: 16 bytes per lane, asynchronous
+#define PATCH_WR_LOAD_A(AB, I, voff_, base_)                                                                       \
+    asm volatile("global_load_dwordx4 " PATCH_WR_VA(AB, I) ", %0, %1" : : "v"(voff_), "s"(base_) : PATCH_WR_CLOBBER)
+// first LDS reads of the kernel (column block CB of stage 0 into set CB)
+#define PATCH_WR_LDS_FIRST(CB, al_, ah_)                                                                           \
+    asm volatile("ds_read_b128 " PATCH_WR_VBL(CB) ", %0 offset:2048*" #CB "\n\t"                                   \
+                 "ds_read_b128 " PATCH_WR_VBH(CB) ", %1 offset:2048*" #CB                                          \
+                 :                                                                                                 \
+                 : "v"(al_), "v"(ah_)                                                                              \
+                 : PATCH_WR_CLOBBER)
+// column blocks of a step with their operand sets: P(CB, SET, NSET)
+#define PATCH_WR_16(P)                                                                                             \
+    P(0, 0, 3) P(1, 1, 0) P(2, 2, 1) P(3, 3, 2) P(4, 0, 3) P(5, 1, 0) P(6, 2, 1) P(7, 3, 2) P(8, 0, 3) P(9, 1, 0)   \
+    P(10, 2, 1) P(11, 3, 2) P(12, 0, 3) P(13, 1, 0) P(14, 2, 1) P(15, 3, 2)
+
+__global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
+                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
+                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y) {
+    constexpr int TILE = 128;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tr = w >> 1, sh = w & 1;  // tile row of the block, half (4 strips) of the tile
+    const int col = lane & 15, q = lane >> 4;
+
+    // ---- block -> (n, m) tile of the output.  Consecutive blocks go to different XCDs (hardware round-robin),
+    // each with its own L2, so every XCD gets a contiguous run of the tile order below, and that order walks
+    // groups of 4 row blocks x all feature blocks: the workgroups an XCD runs at a time then cover about
+    // 8 feature blocks x 4 row blocks and share both operands in L2.
+    const int nblk = tiles_n * tiles_m;
+    int bid = blockIdx.x;
+    {
+        const int per = (nblk + 7) / 8;
+        const int x = bid & 7, i = bid >> 3;
+        const int t = x * per + i;
+        bid = (i < per && t < nblk) ? t : -1;
+    }
+    if (bid < 0) return;
+    int bn, bm;
+    {
+        constexpr int GM = 4;
+        const int full = (tiles_m / GM) * GM * tiles_n;
+        if (bid < full) {
+            const int g = bid / (GM * tiles_n), rem = bid % (GM * tiles_n);
+            bn = rem / GM;
+            bm = g * GM + rem % GM;
+        } else {
+            const int gm = tiles_m % GM, rem = bid - full;
+            bn = rem / gm;
+            bm = (tiles_m / GM) * GM + rem % gm;
+        }
+    }
+    const int64_t n0 = (int64_t)bn * kWrBN, m0 = (int64_t)bm * kWrBM;
+    // N is a multiple of 128, not necessarily of 256: the wavefronts of a missing second tile row copy X and meet
+    // the barriers like the others, read the first tile row's weights (valid addresses) and multiply nothing
+    const bool live = n0 + (int64_t)tr * TILE < N;
+    const uint32_t* trow = table + (n0 / TILE + (live ? tr : 0)) * Tk;
+
+    // ---- per-lane sources of the X copy: wavefront w copies the 1 KB pieces w, w+4, ..., w+28 of the 32 KB stage.
+    // LDS chunk c (16 bytes) = row c / 8, physical chunk c % 8, which holds logical chunk (c % 8) ^ ((row / 2) % 8):
+    // 16 consecutive rows reading the same logical chunk then hit 16 distinct 16-byte bank groups.
+    // Byte offsets from X + step * 128 (a scalar base); the host keeps M * K * 2 below 4 GB for this kernel.
+    uint32_t xoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int c = (w + 4 * i) * 64 + lane;
+        const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
+        int64_t row = m0 + m;
+        if (row >= M) row = M - 1;  // rows past M: any valid row, their outputs are not stored
+        xoff[i] = (uint32_t)((row * K + pl * 8) * 2);
+    }
+    const uint8_t* const xbase = reinterpret_cast<const uint8_t*>(X);
+    // ---- per-lane LDS read addresses of a column block's two operands (+ stage * 32 KB + block * 2 KB)
+    const uint32_t lds0 = (uint32_t)(size_t)((wr_lptr_t)lds);
+    const int swz = (col >> 1) & 7;
+    const uint32_t bl0 = lds0 + col * 128 + ((q ^ swz) << 4);
+    const uint32_t bh0 = lds0 + col * 128 + (((4 + q) ^ swz) << 4);
+    // ---- weight loads of one step: 8 instructions ("slots") per wavefront whatever the tile type, each 16 bytes per
+    // lane from a scalar address that is selected, not branched on:
+    //   dense slot i    : operand i % 2 of strip i / 2 at K-step j
+    //   2:4 slot i < 4  : values of strip i at K-step j
+    //   2:4 slot 4 + s  : 16 bytes starting at the lane's position dword of strip s (the first register is the
+    //                     dword, the rest is ignored; the last lanes read up to 12 bytes into the next tile or the
+    //                     zeroed slack behind the payload)
+    const uint32_t vlane16 = lane * 16, vlane4 = lane * 4;
+    auto a_base = [&](int slot, int j, uint32_t e) -> const uint8_t* {
+        const int cd = sh * 4 * 2 * kDenseFragBytes + (slot >> 1) * 2 * kDenseFragBytes + j * kDenseFragBytes + (slot & 1) * 1024;
+        const int cs = slot < 4 ? sh * 4 * 2 * kSparseFragBytes + slot * 2 * kSparseFragBytes + j * kSparseFragBytes
+                                : sparse_vals_bytes(TILE) + (4 * sh + slot - 4) * 64 * 4;
+        return payload + entry_offset(e) + (entry_sparse(e) ? cs : cd);
+    };
+    auto a_voff = [&](int slot, uint32_t e) { return (slot >= 4 && entry_sparse(e)) ? vlane4 : vlane16; };
+#define PATCH_WR_LOAD_STEP(AB, j_, e_)                                                                             \
+    PATCH_WR_LOAD_A(AB, 0, a_voff(0, e_), a_base(0, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 1, a_voff(1, e_), a_base(1, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 2, a_voff(2, e_), a_base(2, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 3, a_voff(3, e_), a_base(3, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 4, a_voff(4, e_), a_base(4, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 5, a_voff(5, e_), a_base(5, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 6, a_voff(6, e_), a_base(6, j_, e_));                                                      \
+    PATCH_WR_LOAD_A(AB, 7, a_voff(7, e_), a_base(7, j_, e_));
+    // X loads of one step (8 instructions) into a ring stage
+    auto load_x_slot = [&](int slot, int s, int stage) {
+        wr_g2l16(xbase + (size_t)s * 128 + xoff[slot], lds + stage * kWrStage + (w + 4 * slot) * 1024);
+    };
+
+    const int S = 2 * Tk;  // 64-column steps
+    auto entry = [&](int t) { return trow[t < Tk ? t : Tk - 1]; };
+
+    // accumulators: zero
+#define PATCH_WR_ZERO(CB, SET, NSET)                                                                               \
+    asm volatile("v_accvgpr_write_b32 a[16*" #CB "+0], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+1], 0\n\t"            \
+                 "v_accvgpr_write_b32 a[16*" #CB "+2], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+3], 0\n\t"            \
+                 "v_accvgpr_write_b32 a[16*" #CB "+4], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+5], 0\n\t"            \
+                 "v_accvgpr_write_b32 a[16*" #CB "+6], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+7], 0\n\t"            \
+                 "v_accvgpr_write_b32 a[16*" #CB "+8], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+9], 0\n\t"            \
+                 "v_accvgpr_write_b32 a[16*" #CB "+10], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+11], 0\n\t"          \
+                 "v_accvgpr_write_b32 a[16*" #CB "+12], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+13], 0\n\t"          \
+                 "v_accvgpr_write_b32 a[16*" #CB "+14], 0\n\tv_accvgpr_write_b32 a[16*" #CB "+15], 0" ::: PATCH_WR_CLOBBER);
+    PATCH_WR_16(PATCH_WR_ZERO)
+#undef PATCH_WR_ZERO
+
+    // ---- prologue, in the order the steady state would have produced: X(0) | A(0) X(1) | A(1) X(2)
+    uint32_t ec[3] = {entry(0), entry(1), entry(2)};
+    {
+        const int s1 = S > 1 ? 1 : 0, s2 = S > 2 ? 2 : S - 1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_x_slot(i, 0, 0);
+        asm volatile("" ::: "memory");
+        PATCH_WR_LOAD_STEP(0, 0, ec[0])
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_x_slot(i, s1, 1);
+        asm volatile("" ::: "memory");
+        PATCH_WR_LOAD_STEP(1, 1, ec[0])
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_x_slot(i, s2, 2);
+#ifdef LAB_NO_LOADS
+        asm volatile("" ::: "memory");
+        PATCH_WR_LOAD_STEP(2, 0, ec[1])
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_x_slot(i, s2, 3);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    }
+    asm volatile("s_waitcnt vmcnt(24)" ::: "memory");  // X(0) (and A(0)) landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // X operands: column block cb lives in set cb % 4 and is requested three blocks ahead.  Before block cb the
+    // reads of blocks cb, cb+1, cb+2 (two each) are in flight; waiting until four are left completes block cb.
+    PATCH_WR_LDS_FIRST(0, bl0, bh0);
+    PATCH_WR_LDS_FIRST(1, bl0, bh0);
+    PATCH_WR_LDS_FIRST(2, bl0, bh0);
+
+#ifdef LAB_NO_LOADS
+#define PATCH_WR_LAB_LOADS(...) (void)e2; (void)s3;
+#else
+#define PATCH_WR_LAB_LOADS(...) __VA_ARGS__
+#endif
+// Everything of a column block but its matrix instructions.  Blocks 0-7: one weight load of step s+2.  Block 13:
+// this wavefront's share of X(s+1) has landed (after it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is
+// visible and every read of stage (s-1) % 4 has completed, so the loads of X(s+3) (blocks 13-15) may overwrite it.
+#define PATCH_WR_PRE(CB, ABN)                                                                                      \
+    if (CB == 13) {                                                                                                \
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
+        __builtin_amdgcn_s_barrier();                                                                              \
+        asm volatile("" ::: "memory");                                                                             \
+    }                                                                                                              \
+    PATCH_WR_LAB_LOADS(if (CB < 8) PATCH_WR_LOAD_A(ABN, CB, a_voff(CB, e2), a_base(CB, j, e2));                    \
+                       if (CB >= 13) {                                                                             \
+                           load_x_slot(3 * (CB - 13), s3, (s + 3) & 3);                                            \
+                           load_x_slot(3 * (CB - 13) + 1, s3, (s + 3) & 3);                                        \
+                           if (CB < 15) load_x_slot(3 * (CB - 13) + 2, s3, (s + 3) & 3);                           \
+                       })
+#define PATCH_WR_OFF(CB) (((CB + 3) % 16) * 2048)
+#define PATCH_WR_RDA(CB) const uint32_t ral = CB < 13 ? al : aln, rah = CB < 13 ? ah : ahn;
+// One step: SS = position in the round of six, AB / ABN = weight buffers of steps s / s+2, J = K-step in the tile.
+// One scalar branch.  A wavefront without a tile row (N % 256 = 128) multiplies the first tile row's weights as
+// dense data into accumulators that are never stored.
+#define PATCH_WR_STEP(SS, AB, ABN, J)                                                                              \
+    {                                                                                                              \
+        const int s = 6 * it + SS;                                                                                 \
+        if (s >= S) break;                                                                                         \
+        constexpr int j = J, tt = SS >> 1, tt2 = (SS + 2) >> 1;                                                    \
+        /* A(s) has landed: the loads issued after it are X(s+1), A(s+1), X(s+2) */                                \
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
+        const uint32_t al = bl0 + (s & 3) * kWrStage, ah = bh0 + (s & 3) * kWrStage;                               \
+        const uint32_t aln = bl0 + ((s + 1) & 3) * kWrStage, ahn = bh0 + ((s + 1) & 3) * kWrStage;                 \
+        const uint32_t e2 = tt2 < 3 ? ec[tt2 % 3] : en[tt2 % 3];                                                   \
+        const int s3 = (s + 3 < S) ? s + 3 : S - 1;                                                                \
+        if (live && entry_sparse(ec[tt])) {                                                                        \
+            PATCH_WR_16(PATCH_WR_SPARSE_##AB##_##ABN##_##J)                                                        \
+        } else {                                                                                                   \
+            PATCH_WR_16(PATCH_WR_DENSE_##AB##_##ABN)                                                               \
+        }                                                                                                          \
+    }
+#define PATCH_WR_DENSE_0_2(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_DENSE_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_DENSE_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 0, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 1, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 0, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 1, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_SPARSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, ral, rah, PATCH_WR_OFF(CB)); }
+
+    // a round = six steps = three tiles: step buffer = step % 3 and K-step = step % 2 are then compile-time constants
+    for (int it = 0;; ++it) {
+        const uint32_t en[3] = {entry(3 * it + 3), entry(3 * it + 4), entry(3 * it + 5)};  // next round's tiles
+        PATCH_WR_STEP(0, 0, 2, 0)
+        PATCH_WR_STEP(1, 1, 0, 1)
+        PATCH_WR_STEP(2, 2, 1, 0)
+        PATCH_WR_STEP(3, 0, 2, 1)
+        PATCH_WR_STEP(4, 1, 0, 0)
+        PATCH_WR_STEP(5, 2, 1, 1)
+        ec[0] = en[0];
+        ec[1] = en[1];
+        ec[2] = en[2];
+    }
+#undef PATCH_WR_STEP
+#undef PATCH_WR_PRE
+#undef PATCH_WR_LAB_LOADS
+
+    // outstanding (re-fetched) loads and the reads requested for a step that does not exist must land before this
+    // workgroup's LDS and registers can be handed on; the last matrix instructions may still be writing
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory", PATCH_WR_CLOBBER);
+
+    // accumulator (s, cb), register r: feature n0 + 128 tr + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col
+    if (live) {
+#define PATCH_WR_READ(S, CB)                                                                                       \
+    asm volatile("v_accvgpr_read_b32 %0, a[4*(16*" #S "+" #CB ")+0]\n\tv_accvgpr_read_b32 %1, a[4*(16*" #S "+" #CB ")+1]\n\t" \
+                 "v_accvgpr_read_b32 %2, a[4*(16*" #S "+" #CB ")+2]\n\tv_accvgpr_read_b32 %3, a[4*(16*" #S "+" #CB ")+3]"       \
+                 : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]))
+#ifdef LAB_NO_STORE
+#define PATCH_WR_LAB_STORE(c) ((c) && v[0] == 1.2345f)
+#else
+#define PATCH_WR_LAB_STORE(c) (c)
+#endif
+#define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
+    {                                                                                                              \
+        const int64_t m = m0 + 16 * CB + col;                                                                      \
+        float* yrow = Y + m * N + n0 + 128 * tr + 64 * sh + 4 * q;                                                 \
+        float v[4];                                                                                                \
+        PATCH_WR_READ(0, CB);                                                                                      \
+        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};      \
+        PATCH_WR_READ(1, CB);                                                                                      \
+        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        PATCH_WR_READ(2, CB);                                                                                      \
+        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        PATCH_WR_READ(3, CB);                                                                                      \
+        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+    }
+        PATCH_WR_16(PATCH_WR_STORE)
+#undef PATCH_WR_LAB_STORE
+#undef PATCH_WR_STORE
+#undef PATCH_WR_READ
+    }
+}
+
+void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream) {
+    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
+    (void)granted;
+    const int tiles_n = (int)((a.N + kWrBN - 1) / kWrBN), tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
+    const int nblk = tiles_n * tiles_m;
+    const int grid = ((nblk + 7) / 8) * 8;
+    hipLaunchKernelGGL(prefill_kernel_wreg, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, tiles_n,
+                       tiles_m, a.Y);
+}
+
+}  // namespace patch

@@ -287,11 +287,11 @@ def test_mid_m_paths_agree(dev):
     p.P.close()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
 def test_prefill_kernel_variants(dev, variant):
     """Every prefill kernel variant (patch_gemm_opts.variant) against the oracle: odd tile-row count (N % 256 = 128),
     ragged M, K of several tiles, all-dense / mixed / all-2:4 maps."""
-    for N, K, f in [(384, 640, 0.5), (512, 1024, 0.0), (256, 512, 1.0), (640, 384, 0.3)]:
+    for N, K, f in [(384, 640, 0.5), (512, 1024, 0.0), (256, 512, 1.0), (640, 384, 0.3), (128, 128, 0.5), (256, 256, 0.5)]:
         c = synth.make_case("variants", N, K, 300, 128, f, seed=10)
         p = Prepared(c, dev)
         for M in (300, 256, 17):
