@@ -50,7 +50,10 @@ typedef struct {
     int path;    /* patch_path                                                                      */
     int split_k; /* decode: K slices (one wavefront each) per workgroup whose fp32 partials are     */
                  /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto       */
-    int variant; /* kernel variant index within the path, 0 = default                               */
+    int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
+                 /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
+                 /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
+                 /* K-steps per wavefront.  A variant that does not apply falls back to the default.     */
 } patch_gemm_opts;
 
 /*

@@ -40,3 +40,12 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
 if __name__ == "__main__":
     print(build_lib(verbose=True))
     sys.exit(0)
+
+
+def device_asm(source: str, out_path: str) -> str:
+    """gfx950 assembly of one source file (what the compiler generated around the inline asm), for checks."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *[f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")], "-S", "--cuda-device-only", "-I",
+           os.path.join(ROOT, "include"), "-I", CSRC, "-o", out_path, os.path.join(CSRC, source)]
+    subprocess.run(cmd, check=True, capture_output=True)
+    return out_path

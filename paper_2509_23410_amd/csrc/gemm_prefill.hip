@@ -317,9 +317,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-#ifndef LAB_NO_LOADS
         prefetch(pf_ks, stage ^ 1, pf_e0, pf_e1);
-#endif
         const int tk = ks >> 1, j = ks & 1;
         const int sp = (int)(e_mine & 1u);
         const uint8_t* as = As + stage * kPfAStage + r * 8 * kDenseFragBytes + lane_frag;
@@ -355,11 +353,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
             if (pos + 2 < 8) fetch(pos + 2, (pos + 2) % 3);
             const int a = pos >> 1, u = pos & 1, buf = pos % 3;
             const int idx = (int)(fpw[buf] >> (16 * j));
-#ifndef LAB_NO_MMA
             mma_step(acc[a][0], acc[a][1], fa0[buf].v, fa1[buf].v, xb[0][u], xb[1][u], idx, sp);
-#else
-            acc[a][0][0] += (float)(fa0[buf].raw[0] + fa1[buf].raw[1] + xb[0][u].raw[0][0] + xb[1][u].raw[1][1] + idx);
-#endif
         }
     };
 
@@ -392,19 +386,17 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-#ifdef LAB_NO_STORE
-                if (v[0] == 1.2345f)
-#endif
                 *reinterpret_cast<f32x4*>(Y + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q) = v;
             }
     }
 }
 
-// variant 0: tile 128 -> prefill_kernel_t128, tile 64 -> prefill_kernel_v0; variant 1 forces prefill_kernel_v0.
+// Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_t128;
+// tile 64 -> prefill_kernel_v0.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_t128, 3 prefill_kernel_wreg
+// (each falling back to the default choice where it does not apply).
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream) {
-    if (a.tile == 128 && variant == 3) { launch_prefill_ring(a, stream); return; }
-    if (a.tile == 128 && variant == 4) { launch_prefill_wreg(a, stream); return; }
-    if (a.tile == 128 && (variant == 0 || variant == 2)) {
+    if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, stream); return; }
+    if (a.tile == 128 && variant != 1) {
         static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_t128),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
         (void)granted;

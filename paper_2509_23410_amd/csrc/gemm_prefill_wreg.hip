@@ -42,13 +42,7 @@ constexpr int kWrBN = 256, kWrBM = 256;
 constexpr int kWrStage = kWrBM * 128;   // 256 rows of X x 64 columns, swizzled
 constexpr int kWrLds = 4 * kWrStage;    // 128 KB
 
-typedef const __attribute__((address_space(1))) void* wr_gptr_t;
 typedef __attribute__((address_space(3))) void* wr_lptr_t;
-
-__device__ __forceinline__ void wr_g2l16(const void* g, void* l) {
-    // 16 bytes per lane, global -> LDS, no registers: LDS address = (wave-uniform) l + lane * 16
-    __builtin_amdgcn_global_load_lds((wr_gptr_t)g, (wr_lptr_t)l, 16, 0, 0);
-}
 
 // ---- register names (the assembler evaluates the index expressions)
 // accumulator tile of strip S, column block CB
@@ -75,35 +69,94 @@ __device__ __forceinline__ void wr_g2l16(const void* g, void* l) {
         PATCH_WR_R10("v", 19), PATCH_WR_R10("v", 20), PATCH_WR_R10("v", 21), PATCH_WR_R10("v", 22),                  \
         PATCH_WR_R10("v", 23), PATCH_WR_R10("v", 24), "v250", "v251", "v252", "v253", "v254", "v255"
 
+// ---- weight load of slot I (0..7) of the step two ahead (buffer ABN, K-step J), as asm text for the middle of a
+// column block: 16 bytes per lane from tile base + lane offset + slot offset, the slot offset selected by the tile
+// type through a mask (0 dense, -1 2:4), not branched on:
+//   dense slot I    : operand I % 2 of strip I / 2          offset (I / 2) 4096 + (I % 2) 1024 + J 2048
+//   2:4 slot I < 4  : values of strip I                      offset I 2048 + J 1024
+//   2:4 slot 4 + s  : 16 bytes starting at the lane's position dword of strip s   offset 16384 + s 256
+//                     (the first register is the dword, the rest is ignored; the last lanes read up to 12 bytes
+//                     into the next tile or the zeroed slack behind the payload)
+#define PATCH_WR_CD(I, J) "((" #I ">>1)*4096+(" #I "&1)*1024+" #J "*2048)"
+#define PATCH_WR_CS_VAL(I, J) "(" #I "*2048+" #J "*1024)"
+#define PATCH_WR_CS_POS(I, J) "(16384+(" #I "-4)*256)"
+// The four instructions of a load are spread over four gaps between matrix instructions (LD1..LD4): one light
+// instruction per gap issues in the shadow of the matrix instruction before it.
+#define PATCH_WR_A1(ABN, I, J, CS, VSEL) "s_and_b32 %[t], %[mask], " CS "-" PATCH_WR_CD(I, J) "\n\t"
+#define PATCH_WR_A2(ABN, I, J, CS, VSEL) "s_add_i32 %[t], %[t], " PATCH_WR_CD(I, J) "\n\t"
+#define PATCH_WR_A3(ABN, I, J, CS, VSEL) "v_add_u32 %[vt], %[t], " VSEL "\n\t"
+#define PATCH_WR_A4(ABN, I, J, CS, VSEL) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", %[vt], %[tb]\n\t"
+// X load SLOT (0..7) of the step three ahead: 16 bytes per lane, global -> LDS at m0 + lane * 16
+#define PATCH_WR_X3(SLOT) "s_add_u32 m0, %[m0b], 4096*" #SLOT "\n\t"
+#define PATCH_WR_X4(SLOT) "global_load_lds_dwordx4 %[xo], %[xb]\n\t"
+#define PATCH_WR_LDV(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_VAL(I, J), "%[v03]")
+#define PATCH_WR_LDP(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_POS(I, J), "%[v47]")
+// load part N (1..4) of column block CB
+#define PATCH_WR_LD_0(N, ABN, J) PATCH_WR_LDV(N, ABN, 0, J)
+#define PATCH_WR_LD_1(N, ABN, J) PATCH_WR_LDV(N, ABN, 1, J)
+#define PATCH_WR_LD_2(N, ABN, J) PATCH_WR_LDV(N, ABN, 2, J)
+#define PATCH_WR_LD_3(N, ABN, J) PATCH_WR_LDV(N, ABN, 3, J)
+#define PATCH_WR_LD_4(N, ABN, J) PATCH_WR_LDP(N, ABN, 4, J)
+#define PATCH_WR_LD_5(N, ABN, J) PATCH_WR_LDP(N, ABN, 5, J)
+#define PATCH_WR_LD_6(N, ABN, J) PATCH_WR_LDP(N, ABN, 6, J)
+#define PATCH_WR_LD_7(N, ABN, J) PATCH_WR_LDP(N, ABN, 7, J)
+#define PATCH_WR_XN1(SLOT) ""
+#define PATCH_WR_XN2(SLOT) ""
+#define PATCH_WR_XN3(SLOT) PATCH_WR_X3(SLOT)
+#define PATCH_WR_XN4(SLOT) PATCH_WR_X4(SLOT)
+#define PATCH_WR_LD_8(N, ABN, J) PATCH_WR_XN##N(0)
+#define PATCH_WR_LD_9(N, ABN, J) PATCH_WR_XN##N(1)
+#define PATCH_WR_LD_10(N, ABN, J) PATCH_WR_XN##N(2)
+#define PATCH_WR_LD_11(N, ABN, J) PATCH_WR_XN##N(3)
+#define PATCH_WR_LD_12(N, ABN, J) PATCH_WR_XN##N(4)
+#define PATCH_WR_LD_13(N, ABN, J) PATCH_WR_XN##N(5)
+#define PATCH_WR_LD_14(N, ABN, J) PATCH_WR_XN##N(6)
+#define PATCH_WR_LD_15(N, ABN, J) PATCH_WR_XN##N(7)
+// operands of every column-block statement (cu, scr, xo: see the step loop).  The statements of blocks 8-15 write m0,
+// which the compiler does not use in this kernel (every LDS-DMA load is issued from asm).
+#define PATCH_WR_PIECE_OPS                                                                                         \
+    : [t] "=&s"(scr.t), [vt] "=&v"(scr.vt)                                                                         \
+    : [al] "v"(ral), [ah] "v"(rah), [mask] "s"(cu.mask), [v03] "v"(cu.v03), [v47] "v"(cu.v47), [tb] "s"(cu.tb),    \
+      [m0b] "s"(cu.m0b), [xb] "s"(cu.xb), [xo] "v"(xo)
+
 // ---- one column block CB of X (operand set SET) against the wavefront's four strips (weights of step buffer AB),
-// after waiting for its operands, plus the two LDS reads of the column block three ahead into set NSET.
-#define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, al_, ah_, OFF)                                                     \
+// after waiting for its operands, plus the two LDS reads of the column block three ahead into set NSET (LDS byte
+// offset OFF from the lane addresses) and one global load: blocks 0-7 a weight load of step s+2 (buffer ABN),
+// blocks 8-15 an X load of step s+3.  J = K-step inside the tile.
+#define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)
+#define PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                      \
     asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:%[off]\n\t"                                    \
+                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:%[off]\n\t"                                    \
+                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:" #OFF "\n\t"                                  \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 4) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
+                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 6) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
+                 PATCH_WR_LD_##CB(2, ABN, J)                                                                       \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
+                 PATCH_WR_LD_##CB(3, ABN, J)                                                                       \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
+                 PATCH_WR_LD_##CB(4, ABN, J)                                                                       \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 5) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB)          \
-                 :                                                                                                 \
-                 : [al] "v"(al_), [ah] "v"(ah_), [off] "n"(OFF)                                                    \
-                 : PATCH_WR_CLOBBER)
-// J selects the K-step's half of the position dwords
-#define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, J, al_, ah_, OFF)                                                 \
+                 PATCH_WR_PIECE_OPS                                                                                \
+                 : "scc", PATCH_WR_CLOBBER)
+#define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)
+#define PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                     \
     asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:%[off]\n\t"                                    \
+                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
+                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:%[off]\n\t"                                    \
+                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:" #OFF "\n\t"                                  \
+                 PATCH_WR_LD_##CB(2, ABN, J)                                                                       \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
+                 PATCH_WR_LD_##CB(3, ABN, J)                                                                       \
+                 PATCH_WR_LD_##CB(4, ABN, J)                                                                       \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J          \
-                 :                                                                                                 \
-                 : [al] "v"(al_), [ah] "v"(ah_), [off] "n"(OFF)                                                    \
-                 : PATCH_WR_CLOBBER)
+                 PATCH_WR_PIECE_OPS                                                                                \
+                 : "scc", PATCH_WR_CLOBBER)
 // weight load I of a step into buffer AB: 16 bytes per lane, asynchronous
 #define PATCH_WR_LOAD_A(AB, I, voff_, base_)                                                                       \
     asm volatile("global_load_dwordx4 " PATCH_WR_VA(AB, I) ", %0, %1" : : "v"(voff_), "s"(base_) : PATCH_WR_CLOBBER)
@@ -206,13 +259,37 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     PATCH_WR_LOAD_A(AB, 5, a_voff(5, e_), a_base(5, j_, e_));                                                      \
     PATCH_WR_LOAD_A(AB, 6, a_voff(6, e_), a_base(6, j_, e_));                                                      \
     PATCH_WR_LOAD_A(AB, 7, a_voff(7, e_), a_base(7, j_, e_));
-    // X loads of one step (8 instructions) into a ring stage
+    // X loads of one step (8 instructions) into a ring stage: prologue only, the loop issues them from the
+    // column-block statements.  m0 = LDS byte address of the wavefront's 1 KB piece.
     auto load_x_slot = [&](int slot, int s, int stage) {
-        wr_g2l16(xbase + (size_t)s * 128 + xoff[slot], lds + stage * kWrStage + (w + 4 * slot) * 1024);
+        const uint8_t* xb = xbase + (size_t)s * 128;
+        const uint32_t m0v = lds0 + stage * kWrStage + (w + 4 * slot) * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(xoff[slot]), "s"(xb) : "memory");
     };
 
     const int S = 2 * Tk;  // 64-column steps
-    auto entry = [&](int t) { return trow[t < Tk ? t : Tk - 1]; };
+    // the tile row's table entries: lane l of ent[i] holds tile 64 i + l; fetched with v_readlane (a scalar load in
+    // the loop would be waited for with lgkmcnt(0), i.e. together with every LDS read in flight).  Tk <= 256.
+    uint32_t ent[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = 64 * i + lane;
+        ent[i] = trow[t < Tk ? t : Tk - 1];
+    }
+    // a use right here: the compiler waits for these loads now, not with a vmcnt(0) inside the loop
+    asm volatile("" : "+v"(ent[0]), "+v"(ent[1]), "+v"(ent[2]), "+v"(ent[3]));
+    auto entry = [&](int t) {
+        t = t < Tk ? t : Tk - 1;
+        uint32_t r = __builtin_amdgcn_readlane(ent[0], t & 63);
+        if (Tk > 64) {
+#pragma unroll
+            for (int i = 1; i < 4; ++i) {
+                const uint32_t v = __builtin_amdgcn_readlane(ent[i], t & 63);
+                r = (t >> 6) == i ? v : r;
+            }
+        }
+        return r;
+    };
 
     // accumulators: zero
 #define PATCH_WR_ZERO(CB, SET, NSET)                                                                               \
@@ -243,13 +320,6 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_x_slot(i, s2, 2);
-#ifdef LAB_NO_LOADS
-        asm volatile("" ::: "memory");
-        PATCH_WR_LOAD_STEP(2, 0, ec[1])
-#pragma unroll
-        for (int i = 0; i < 8; ++i) load_x_slot(i, s2, 3);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
     }
     asm volatile("s_waitcnt vmcnt(24)" ::: "memory");  // X(0) (and A(0)) landed
     __builtin_amdgcn_s_barrier();
@@ -260,59 +330,107 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     PATCH_WR_LDS_FIRST(1, bl0, bh0);
     PATCH_WR_LDS_FIRST(2, bl0, bh0);
 
-#ifdef LAB_NO_LOADS
-#define PATCH_WR_LAB_LOADS(...) (void)e2; (void)s3;
-#else
-#define PATCH_WR_LAB_LOADS(...) __VA_ARGS__
-#endif
-// Everything of a column block but its matrix instructions.  Blocks 0-7: one weight load of step s+2.  Block 13:
-// this wavefront's share of X(s+1) has landed (after it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is
-// visible and every read of stage (s-1) % 4 has completed, so the loads of X(s+3) (blocks 13-15) may overwrite it.
-#define PATCH_WR_PRE(CB, ABN)                                                                                      \
-    if (CB == 13) {                                                                                                \
+    // lane offsets of the weight loads inside a tile: dense operands, 2:4 values, 2:4 position dwords
+    const uint32_t vd = lane * 16 + sh * 4 * 2 * kDenseFragBytes, vs = lane * 16 + sh * 4 * 2 * kSparseFragBytes;
+    const uint32_t vm = lane * 4 + sh * 4 * 64 * 4;
+    // ---- what a step needs besides its operands, computed during the step before (in the shadow of its matrix
+    // instructions) so that a step starts with nothing but a wait and a branch
+    struct StepVars {
+        uint32_t al, ah;     // lane LDS addresses of the X operands in stage s % 4 ...
+        uint32_t aln, ahn;   // ... and in stage (s+1) % 4
+        const uint8_t* tb;   // tile of step s+2 (weight loads)
+        int mask;            // its type: 0 dense, -1 2:4
+        uint32_t v03, v47;   // lane offsets of load slots 0-3 / 4-7 for that type
+        const uint8_t* xb;   // X + 128 (step s+3)
+        uint32_t m0b;        // LDS byte address of this wavefront's first 1 KB piece of stage (s+3) % 4
+        int sparse;          // type of the tile this step multiplies
+    };
+    const int live_i = __builtin_amdgcn_readfirstlane(live ? 1 : 0);
+    auto step_vars = [&](int s, uint32_t e, uint32_t e2) {
+        StepVars v;
+        v.al = bl0 + (s & 3) * kWrStage;
+        v.ah = bh0 + (s & 3) * kWrStage;
+        v.aln = bl0 + ((s + 1) & 3) * kWrStage;
+        v.ahn = bh0 + ((s + 1) & 3) * kWrStage;
+        v.tb = payload + entry_offset(e2);
+        v.mask = -(int)(e2 & 1u);
+        v.v03 = entry_sparse(e2) ? vs : vd;
+        v.v47 = entry_sparse(e2) ? vm : vd;
+        const int s3 = (s + 3 < S) ? s + 3 : S - 1;
+        v.xb = xbase + (size_t)s3 * 128;
+        v.m0b = lds0 + ((s + 3) & 3) * kWrStage + w * 1024;
+        v.sparse = (int)(e & 1u) & live_i;
+        return v;
+    };
+    struct { uint32_t t, vt; } scr;  // scratch registers of the asm
+// Everything of a column block but its asm statement.  Block 8: this wavefront's share of X(s+1) has landed (after
+// it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 13) and every read of
+// stage (s-1) % 4 has completed, so the loads of X(s+3) (one per block 8-15) may overwrite it.
+#define PATCH_WR_PRE(CB, SS)                                                                                         \
+    if (CB == 8) {                                                                                                 \
         asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
         __builtin_amdgcn_s_barrier();                                                                              \
         asm volatile("" ::: "memory");                                                                             \
     }                                                                                                              \
-    PATCH_WR_LAB_LOADS(if (CB < 8) PATCH_WR_LOAD_A(ABN, CB, a_voff(CB, e2), a_base(CB, j, e2));                    \
-                       if (CB >= 13) {                                                                             \
-                           load_x_slot(3 * (CB - 13), s3, (s + 3) & 3);                                            \
-                           load_x_slot(3 * (CB - 13) + 1, s3, (s + 3) & 3);                                        \
-                           if (CB < 15) load_x_slot(3 * (CB - 13) + 2, s3, (s + 3) & 3);                           \
-                       })
-#define PATCH_WR_OFF(CB) (((CB + 3) % 16) * 2048)
-#define PATCH_WR_RDA(CB) const uint32_t ral = CB < 13 ? al : aln, rah = CB < 13 ? ah : ahn;
+    if (CB == 9) {                                                                                                 \
+        int sn = s + 1;                                                                                            \
+        asm volatile("" : "+s"(sn)); /* not before this point */                                                   \
+        nx = step_vars(sn, PATCH_WR_ENT((SS + 1) >> 1), PATCH_WR_ENT((SS + 3) >> 1));                              \
+    }                                                                                                              \
+    if (CB == 12) { /* ... and not after this one */                                                               \
+        asm volatile("" : "+v"(nx.al), "+v"(nx.ah), "+v"(nx.aln), "+v"(nx.ahn), "+v"(nx.v03), "+v"(nx.v47));      \
+        asm volatile("" : "+s"(nx.tb), "+s"(nx.mask), "+s"(nx.xb), "+s"(nx.m0b), "+s"(nx.sparse));                \
+    }                                                                                                              \
+    const uint32_t ral = CB < 13 ? cu.al : cu.aln, rah = CB < 13 ? cu.ah : cu.ahn, xo = xoff[CB < 8 ? 0 : CB - 8];
+// LDS offset of the column block three ahead
+#define PATCH_WR_OFF_0 6144
+#define PATCH_WR_OFF_1 8192
+#define PATCH_WR_OFF_2 10240
+#define PATCH_WR_OFF_3 12288
+#define PATCH_WR_OFF_4 14336
+#define PATCH_WR_OFF_5 16384
+#define PATCH_WR_OFF_6 18432
+#define PATCH_WR_OFF_7 20480
+#define PATCH_WR_OFF_8 22528
+#define PATCH_WR_OFF_9 24576
+#define PATCH_WR_OFF_10 26624
+#define PATCH_WR_OFF_11 28672
+#define PATCH_WR_OFF_12 30720
+#define PATCH_WR_OFF_13 0
+#define PATCH_WR_OFF_14 2048
+#define PATCH_WR_OFF_15 4096
 // One step: SS = position in the round of six, AB / ABN = weight buffers of steps s / s+2, J = K-step in the tile.
 // One scalar branch.  A wavefront without a tile row (N % 256 = 128) multiplies the first tile row's weights as
 // dense data into accumulators that are never stored.
+#define PATCH_WR_ENT(k) ((k) < 3 ? ec[(k) % 3] : en[(k) % 3]) /* entry of tile k of this round (3, 4: next round) */
 #define PATCH_WR_STEP(SS, AB, ABN, J)                                                                              \
     {                                                                                                              \
         const int s = 6 * it + SS;                                                                                 \
         if (s >= S) break;                                                                                         \
-        constexpr int j = J, tt = SS >> 1, tt2 = (SS + 2) >> 1;                                                    \
+        const StepVars cu = nx;                                                                                    \
         /* A(s) has landed: the loads issued after it are X(s+1), A(s+1), X(s+2) */                                \
         asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
-        const uint32_t al = bl0 + (s & 3) * kWrStage, ah = bh0 + (s & 3) * kWrStage;                               \
-        const uint32_t aln = bl0 + ((s + 1) & 3) * kWrStage, ahn = bh0 + ((s + 1) & 3) * kWrStage;                 \
-        const uint32_t e2 = tt2 < 3 ? ec[tt2 % 3] : en[tt2 % 3];                                                   \
-        const int s3 = (s + 3 < S) ? s + 3 : S - 1;                                                                \
-        if (live && entry_sparse(ec[tt])) {                                                                        \
+        if (cu.sparse) {                                                                                           \
             PATCH_WR_16(PATCH_WR_SPARSE_##AB##_##ABN##_##J)                                                        \
         } else {                                                                                                   \
-            PATCH_WR_16(PATCH_WR_DENSE_##AB##_##ABN)                                                               \
+            PATCH_WR_16(PATCH_WR_DENSE_##AB##_##ABN##_##J)                                                         \
         }                                                                                                          \
     }
-#define PATCH_WR_DENSE_0_2(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_DENSE_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_DENSE_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 0, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 1, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 0, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 1, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, ral, rah, PATCH_WR_OFF(CB)); }
-#define PATCH_WR_SPARSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_RDA(CB) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, ral, rah, PATCH_WR_OFF(CB)); }
+#define PATCH_WR_DENSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_DENSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 1, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_DENSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_DENSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 3) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 1, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_DENSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 4) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_DENSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 5) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 1, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 1, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 3) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 1, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 4) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 0, PATCH_WR_OFF_##CB); }
+#define PATCH_WR_SPARSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 5) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 1, PATCH_WR_OFF_##CB); }
 
     // a round = six steps = three tiles: step buffer = step % 3 and K-step = step % 2 are then compile-time constants
+    StepVars nx = step_vars(0, ec[0], ec[1]);
     for (int it = 0;; ++it) {
         const uint32_t en[3] = {entry(3 * it + 3), entry(3 * it + 4), entry(3 * it + 5)};  // next round's tiles
         PATCH_WR_STEP(0, 0, 2, 0)
@@ -327,7 +445,6 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     }
 #undef PATCH_WR_STEP
 #undef PATCH_WR_PRE
-#undef PATCH_WR_LAB_LOADS
 
     // outstanding (re-fetched) loads and the reads requested for a step that does not exist must land before this
     // workgroup's LDS and registers can be handed on; the last matrix instructions may still be writing
@@ -339,30 +456,29 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     asm volatile("v_accvgpr_read_b32 %0, a[4*(16*" #S "+" #CB ")+0]\n\tv_accvgpr_read_b32 %1, a[4*(16*" #S "+" #CB ")+1]\n\t" \
                  "v_accvgpr_read_b32 %2, a[4*(16*" #S "+" #CB ")+2]\n\tv_accvgpr_read_b32 %3, a[4*(16*" #S "+" #CB ")+3]"       \
                  : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]))
-#ifdef LAB_NO_STORE
-#define PATCH_WR_LAB_STORE(c) ((c) && v[0] == 1.2345f)
-#else
-#define PATCH_WR_LAB_STORE(c) (c)
-#endif
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
         const int64_t m = m0 + 16 * CB + col;                                                                      \
         float* yrow = Y + m * N + n0 + 128 * tr + 64 * sh + 4 * q;                                                 \
         float v[4];                                                                                                \
         PATCH_WR_READ(0, CB);                                                                                      \
-        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};      \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};      \
         PATCH_WR_READ(1, CB);                                                                                      \
-        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
         PATCH_WR_READ(2, CB);                                                                                      \
-        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
         PATCH_WR_READ(3, CB);                                                                                      \
-        if (PATCH_WR_LAB_STORE(m < M)) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
     }
         PATCH_WR_16(PATCH_WR_STORE)
-#undef PATCH_WR_LAB_STORE
 #undef PATCH_WR_STORE
 #undef PATCH_WR_READ
     }
+}
+
+// Limits of the kernel: 32-bit lane offsets into X, four registers of table entries per tile row.
+bool prefill_wreg_supports(const GemmArgs& a) {
+    return a.tile == 128 && a.M > 0 && a.K <= 256 * 128 && (uint64_t)a.M * (uint64_t)a.K * 2 < (1ull << 32);
 }
 
 void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream) {

@@ -29,7 +29,7 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
 
 // Any M (prefill shape).
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream);
-void launch_prefill_ring(const GemmArgs& a, hipStream_t stream);  // tile 128 only
-void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream);  // tile 128 only
+bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB
+void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream);
 
 }  // namespace patch

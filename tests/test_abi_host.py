@@ -53,3 +53,36 @@ def test_argument_errors_without_device():
     L.patch_free(0)
     with pytest.raises(B.PatchError):
         B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)
+
+
+def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
+    """prefill_kernel_wreg addresses a[0:255] and v[128:255] by name inside its asm statements; the code the
+    compiler generates around them must not touch those registers, nor m0 (written by the asm for LDS-DMA)."""
+    import re
+    from paper_2509_23410_amd import build
+    text = open(build.device_asm("gemm_prefill_wreg.hip", str(tmp_path / "wreg.s"))).read()
+    m = re.search(r"^_ZN5patch19prefill_kernel_wreg\w*:[^\n]*\n(.*?)s_endpgm", text, re.S | re.M)
+    assert m, "kernel not found in the assembly"
+    inasm, max_v, n_asm = False, -1, 0
+    for line in m.group(1).splitlines():
+        if "#ASMSTART" in line:
+            inasm, n_asm = True, n_asm + 1
+            continue
+        if "#ASMEND" in line:
+            inasm = False
+            continue
+        code = line.split(";")[0]
+        if inasm or not code.strip() or code.strip().startswith("."):
+            continue
+        assert not re.search(r"\ba\[?\d", code) and "accvgpr" not in code, f"compiler touched an accumulation register: {line}"
+        assert not re.search(r"\bm0\b", code), f"compiler uses m0: {line}"
+        for g in re.finditer(r"\bv(\d+)\b", code):
+            max_v = max(max_v, int(g.group(1)))
+        for g in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
+            max_v = max(max_v, int(g.group(2)))
+    assert n_asm > 200, "inline asm markers missing from the assembly"
+    assert 0 <= max_v < 128, f"compiler allocated v{max_v}, inside the range the asm owns"
+    meta = re.search(r"\.name:\s+_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
+    spills = re.search(r"_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
+    assert (meta or spills) and int((meta or spills).group(1)) == 0
+    assert re.search(r"\.agpr_count:\s+256", text)

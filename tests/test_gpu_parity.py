@@ -287,7 +287,17 @@ def test_mid_m_paths_agree(dev):
     p.P.close()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+def test_prefill_long_k(dev):
+    """K beyond the weights-in-registers kernel's limit (256 tiles): the default choice must fall back."""
+    c = synth.make_case("longk", 128, 258 * 128, 40, 128, 0.5, seed=12)
+    p = Prepared(c, dev)
+    for variant in (0, 3):
+        print(f"long K variant={variant}", flush=True)
+        assert relF(p.gemm(c.X, path=B.PATH_PREFILL, variant=variant), p.oracle_gemm(c.X)) <= TIGHT
+    p.P.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_prefill_kernel_variants(dev, variant):
     """Every prefill kernel variant (patch_gemm_opts.variant) against the oracle: odd tile-row count (N % 256 = 128),
     ragged M, K of several tiles, all-dense / mixed / all-2:4 maps."""
