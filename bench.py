@@ -126,7 +126,7 @@ def main():
         with open(tpath) as fh:
             traffic = json.load(fh).get("hbm_bytes_per_launch")   # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
     roof = dict(bound="mfma", achieved=issued_flop / n_launch / avg_launch_s / 1e12, peak=PEAK_MFMA_BF16_TF, unit="TFLOP/s",
-                traffic=traffic, kernel="prefill_kernel_t128", avg_launch_us=avg_launch_s * 1e6,
+                traffic=traffic, kernel="prefill_kernel_wreg" if args.variant in (0, 3) else "variant %d" % args.variant, avg_launch_us=avg_launch_s * 1e6,
                 algorithmic_flop_per_launch=issued_flop / n_launch,
                 note="achieved = issued matrix flops M N K (2 - f) per launch / average launch duration (HIP events); "
                      "traffic = measured HBM bytes per launch (profiles/)")
