@@ -171,6 +171,7 @@ def main():
         Xd = dev_bf16(cd.X)
         Yd = torch.empty((16, N), device=dev, dtype=torch.float32)
         base_us = {}
+        fused = []
         for fd in (0.0, 0.25, 0.5, 0.75, 1.0):
             tm = synth.tile_map(0, N // t, K // t, fd, "llama7b_attn", N, K, t, fd)
             W_hat, P0 = masked_packed(cd, tm)
@@ -192,6 +193,20 @@ def main():
                                 speedup_vs_all_dense=round(base_us[Md] / us, 4), us_cache_resident=round(us_res, 3),
                                 packed_MB=round(P0.nbytes / 1e6, 3), copies=R,
                                 dense_equiv_TFLOPs=round(2.0 * Md * N * K / (us * 1e-6) / 1e12, 3)))
+            if fd in (0.0, 0.5):
+                # q / k / v: three projections sharing X in one launch (patch_gemm_many)
+                nq = 3
+                Rq = max(2, R // nq)
+                sets = [Ps[i * nq:(i + 1) * nq] for i in range(Rq)]
+                Yq = [torch.empty((16, N), device=dev, dtype=torch.float32) for _ in range(nq)]
+                def launch_q(i):
+                    B.patch_gemm_many(Xd, 1, sets[i % Rq], Yq, stream)
+                timed(launch_q, 20)
+                nl = max(1, args.decode_launches // nq)
+                us = sorted(timed(launch_q, nl) / nl for _ in range(5))[2] * 1e6
+                gbs = nq * P0.nbytes / (us * 1e-6) / 1e9
+                fused.append(dict(f=fd, M=1, weights=nq, us=round(us, 3), GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4),
+                                  speedup_vs_single_launches=round(nq * [r_ for r_ in dec if r_["M"] == 1 and r_["f"] == fd][0]["us"] / us, 4)))
             for P_ in Ps:
                 P_.close()
             del W_hat
@@ -199,6 +214,7 @@ def main():
         out["decode_roofline"] = dict(bound="hbm", achieved=m1["GBps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=m1["frac_hbm"],
                                       traffic=None, kernel="decode_kernel", workload="4096x4096 f=0 M=1",
                                       note="compressed weight bytes per launch / average launch duration")
+        out["decode_fused_qkv"] = dict(rows=fused, note="three 4096x4096 projections sharing X in one patch_gemm_many launch, rotating packed copies")
         out["decode"] = dict(workload="llama7b_attn_decode 4096x4096 tile128", peak_GBps=PEAK_HBM_GBS, rows=dec,
                              note="us = median of 5 batches of back-to-back launches over rotating packed copies (HBM-resident)")
 

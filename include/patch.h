@@ -92,6 +92,22 @@ patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream,
                            const patch_gemm_opts* opts);
 
+/*
+ * The same product for several weights that share one input: Y[i] = X * W_hat[i]^T, i < count (the q / k / v
+ * projections of an attention block, the gate / up projections of an MLP; Appendix A times the layer's products
+ * for one decode input and one prefill input).  On the decode path all weights run in ONE launch per 16 rows of
+ * X, which amortises launch and ramp-up over all their bytes; on the prefill path it is one launch per weight.
+ *   P      HOST array of count handles; all with the same K and the same tile, N may differ
+ *   Y      HOST array of count DEVICE pointers, Y[i] is M x N[i] fp32 row-major, 16-byte aligned, distinct
+ *   count  1 .. PATCH_MAX_MANY
+ *   opts   as for patch_gemm_ex, NULL = defaults
+ * Errors: PATCH_ERR_ARG (null, count out of range, misaligned), PATCH_ERR_SHAPE (K or tile differ).  Same
+ * asynchrony, ownership and reproducibility as patch_gemm; both arrays are read before the call returns.
+ */
+#define PATCH_MAX_MANY 8
+patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count,
+                             void* stream, const patch_gemm_opts* opts);
+
 /* Decompression back to a row-major N x K bf16 matrix (DEVICE).  Dropped positions become +0. */
 patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream);
 

@@ -18,7 +18,7 @@ OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_unpack", "patch_canonical_sizes",
+    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_unpack", "patch_canonical_sizes",
     "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -49,6 +49,7 @@ def lib() -> ctypes.CDLL:
         L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
+        L.patch_gemm_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp, ctypes.POINTER(GemmOpts)]
         L.patch_unpack.argtypes = [vp, vp, vp]
         L.patch_canonical_sizes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.patch_export_canonical.argtypes = [vp, vp, sz, vp, sz]
@@ -64,7 +65,7 @@ def lib() -> ctypes.CDLL:
         L.patch_strerror.restype = ctypes.c_char_p
         L.patch_last_hip_error.restype = ci
         L.patch_version.restype = ctypes.c_char_p
-        for f in ("patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_unpack", "patch_canonical_sizes",
+        for f in ("patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_unpack", "patch_canonical_sizes",
                   "patch_export_canonical", "patch_packed_dims", "patch_packed_tile_map"):
             getattr(L, f).restype = ci
         _lib = L
@@ -160,6 +161,17 @@ def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, 
         o = GemmOpts(path, split_k, variant)
         st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
     _check(st, "patch_gemm")
+
+
+def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> None:
+    """Y[i] = X * W_hat[i]^T for weights that share X (same K, same tile); one decode launch for all of them."""
+    n = len(Ps)
+    if n != len(Ys):
+        raise PatchError(ERR_ARG, "patch_gemm_many: as many outputs as weights")
+    hp = (ctypes.c_void_p * max(n, 1))(*[p.handle for p in Ps])
+    yp = (ctypes.c_void_p * max(n, 1))(*[_ptr(y) for y in Ys])
+    o = GemmOpts(path, split_k, variant)
+    _check(lib().patch_gemm_many(_ptr(X), M, hp, yp, n, stream, ctypes.byref(o)), "patch_gemm_many")
 
 
 def patch_unpack(P: Packed, W_out, stream: int = 0) -> None:

@@ -198,6 +198,53 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     return PATCH_OK;
 }
 
+patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count, void* stream,
+                             const patch_gemm_opts* opts) {
+    if (!X || !P || !Y || M <= 0 || count < 1 || count > PATCH_MAX_MANY) return PATCH_ERR_ARG;
+    static_assert(PATCH_MAX_MANY == kMaxMany, "header and kernels disagree");
+    if (!aligned16(X)) return PATCH_ERR_ARG;
+    for (int i = 0; i < count; ++i) {
+        if (!P[i] || !Y[i] || !aligned16(Y[i])) return PATCH_ERR_ARG;
+        if (P[i]->K != P[0]->K || P[i]->tile != P[0]->tile) return PATCH_ERR_SHAPE;
+    }
+    int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
+    if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
+    if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
+    if (path == PATCH_PATH_AUTO) path = (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (path == PATCH_PATH_PREFILL || count == 1) {
+        patch_gemm_opts o = {path, split_k, variant};
+        for (int i = 0; i < count; ++i) {
+            const patch_status st = patch_gemm_ex(X, M, P[i], Y[i], stream, &o);
+            if (st != PATCH_OK) return st;
+        }
+        return PATCH_OK;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs a = {};
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = P[0]->K;
+    a.tile = P[0]->tile; a.Tk = P[0]->Tk;
+    a.n_cus = P[0]->n_cus;
+    DecodeSet set = {};
+    int strips = 0;
+    for (int i = 0; i < count; ++i) {
+        set.payload[i] = P[i]->d_payload;
+        set.table[i] = P[i]->d_table;
+        set.Y[i] = static_cast<float*>(Y[i]);
+        set.N[i] = P[i]->N;
+        set.first_strip[i] = strips;
+        strips += (int)(P[i]->N / 16);
+    }
+    set.count = count;
+    set.strips = strips;
+    for (int64_t m0 = 0; m0 < M; m0 += 16) {
+        const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
+        launch_decode_set(a, set, m0, rows, split_k, variant, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return PATCH_OK;
+}
+
 patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream) {
     return patch_gemm_ex(X, M, P, Y, stream, nullptr);
 }

@@ -30,17 +30,43 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 union AFrag { u32x4 raw; bf16x8 v; };
 union BFrag { u32x4 raw[2]; bf16x8 h[2]; bf16x16 v; };
 
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
 template <int TILE, int NK, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K,
-                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                           int Tk, float* __restrict__ Y, int64_t N) {
+__global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
+                                                           const DecodeSet set) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
     __shared__ f32x4 red[MAXW][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KW = blockDim.x >> 6;
-    const int strip = blockIdx.x;
+    // which weight of the set this strip belongs to: scalar selects over the (at most 8) candidates, so that every
+    // pointer stays in scalar registers
+    const uint8_t* __restrict__ payload = set.payload[0];
+    const uint32_t* __restrict__ table = set.table[0];
+    float* __restrict__ Y = set.Y[0];
+    int64_t N = set.N[0];
+    int first = 0;
+    if (set.count > 1)
+#pragma unroll
+    for (int i = 1; i < kMaxMany; ++i) {
+        const bool here = i < set.count && (int)blockIdx.x >= set.first_strip[i];
+        payload = here ? set.payload[i] : payload;
+        table = here ? set.table[i] : table;
+        Y = here ? set.Y[i] : Y;
+        N = here ? set.N[i] : N;
+        first = here ? set.first_strip[i] : first;
+    }
+    // the selects above are wavefront-uniform; say so (the weight addresses below must be scalar)
+    payload = reinterpret_cast<const uint8_t*>(uniform64(reinterpret_cast<uint64_t>(payload)));
+    table = reinterpret_cast<const uint32_t*>(uniform64(reinterpret_cast<uint64_t>(table)));
+    Y = reinterpret_cast<float*>(uniform64(reinterpret_cast<uint64_t>(Y)));
+    N = (int64_t)uniform64((uint64_t)N);
+    const int strip = (int)blockIdx.x - __builtin_amdgcn_readfirstlane(first);
     const int tn = strip / SPT, s = strip % SPT;
     const int col = lane & 15, q = lane >> 4;
     const bool xvalid = col < rows;
@@ -58,7 +84,15 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         const int n = (total - base < NK) ? total - base : NK;
         uint32_t ent[NK];
 #pragma unroll
-        for (int g = 0; g < NK; ++g) ent[g] = trow[((g < n) ? base + g : base) / KPT];
+        for (int g = 0; g < NK; ++g) {
+            // scalar load by hand: the table pointer comes out of a select, and the compiler would fall back to
+            // vector loads (and vector registers for everything derived from the entries)
+            const uint32_t off = (uint32_t)(((g < n) ? base + g : base) / KPT) * 4u;
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(ent[g]) : "s"(trow), "s"(off));
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int g = 0; g < NK; ++g) asm volatile("" : "+s"(ent[g]));
 
         // ---- every byte of the slice is requested now, weights and X interleaved step by step (issuing the X
         // loads after all the weight loads measured 1.2 us slower).  One asm block per step: the compiler can
@@ -157,19 +191,28 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
 }
 
 template <int TILE>
-static void launch_decode_t(const GemmArgs& a, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
-    dim3 grid((unsigned)(a.N / 16)), block((unsigned)(kw * 64));
-    if (nk == 8)
-        hipLaunchKernelGGL((decode_kernel<TILE, 8, 8>), grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, a.Y, a.N);
-    else
-        hipLaunchKernelGGL((decode_kernel<TILE, 4, 16>), grid, block, 0, stream, a.X, m0, rows, a.K, a.payload, a.table, a.Tk, a.Y, a.N);
+static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
+    dim3 grid((unsigned)set.strips), block((unsigned)(kw * 64));
+    if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
 }
 
 // Schedule: NK = 64-column steps per wavefront and pass (8 or 4), KW = wavefronts per workgroup.
 // split_k > 0 forces KW; variant 2 / 3 forces NK = 8 / 4.
 // Default: NK = 8 if that still leaves about four wavefronts per compute unit, else 4.
 int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
-    const int64_t strips = a.N / 16;
+    DecodeSet set = {};
+    set.payload[0] = a.payload;
+    set.table[0] = a.table;
+    set.Y[0] = a.Y;
+    set.N[0] = a.N;
+    set.count = 1;
+    set.strips = (int)(a.N / 16);
+    return launch_decode_set(a, set, m0, rows, split_k, variant, stream);
+}
+
+int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
+    const int64_t strips = set.strips;
     const int total = a.Tk * (a.tile / kStepCols);
     int nk = 0;
     if (variant == 2) nk = 8;
@@ -184,8 +227,8 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
     int kw = split_k > 0 ? split_k : (total + nk - 1) / nk;
     if (kw > maxw) kw = maxw;
     if (kw < 1) kw = 1;
-    if (a.tile == 128) launch_decode_t<128>(a, m0, rows, nk, kw, stream);
-    else launch_decode_t<64>(a, m0, rows, nk, kw, stream);
+    if (a.tile == 128) launch_decode_t<128>(a, set, m0, rows, nk, kw, stream);
+    else launch_decode_t<64>(a, set, m0, rows, nk, kw, stream);
     return kw;
 }
 

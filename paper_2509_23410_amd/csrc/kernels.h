@@ -23,9 +23,22 @@ struct GemmArgs {
     int n_cus;
 };
 
+// Up to kMaxMany weights that share one X (same K, same tile), multiplied in one decode launch.
+constexpr int kMaxMany = 8;
+struct DecodeSet {
+    const uint8_t* payload[kMaxMany];
+    const uint32_t* table[kMaxMany];
+    float* Y[kMaxMany];          // M x N[i] fp32
+    int64_t N[kMaxMany];
+    int first_strip[kMaxMany];   // index of the weight's first 16-feature strip in the launch
+    int count, strips;           // weights, strips in total
+};
+
 // M <= 16 rows of X starting at row m0 (decode shape).  split_k = K slices (wavefronts) per workgroup,
 // 0 picks a default.  Returns the number used.
 int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
+// The same for a set of weights; a supplies X, K, tile, Tk, n_cus (its payload / table / Y / N are ignored).
+int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
 
 // Any M (prefill shape).
 void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream);

@@ -46,6 +46,10 @@ def test_argument_errors_without_device():
     assert L.patch_pack(fake + 2, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG  # misaligned
     assert out.value is None
     assert L.patch_gemm(fake, 1, 0, fake, 0) == B.ERR_ARG
+    two = (ctypes.c_void_p * 2)(0, 0)
+    assert L.patch_gemm_many(fake, 1, two, two, 2, 0, None) == B.ERR_ARG   # null handles
+    assert L.patch_gemm_many(fake, 1, two, two, 0, 0, None) == B.ERR_ARG   # count out of range
+    assert L.patch_gemm_many(fake, 1, two, two, 9, 0, None) == B.ERR_ARG
     assert L.patch_gemm(0, 1, fake, fake, 0) == B.ERR_ARG
     assert L.patch_apply_mask(fake, fake, tm.ctypes.data, 128, 128, 48, fake, 0) == B.ERR_SHAPE
     assert L.patch_unpack(0, fake, 0) == B.ERR_ARG

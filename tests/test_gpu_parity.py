@@ -287,6 +287,33 @@ def test_mid_m_paths_agree(dev):
     p.P.close()
 
 
+def test_gemm_many_matches_single_calls(dev):
+    """patch_gemm_many: several weights sharing X (different N, different maps) in one decode launch per 16 rows,
+    bit-equal to the single calls and within tolerance of the oracle; prefill path: one launch per weight."""
+    K, t = 1024, 128
+    cases = [synth.make_case(f"many{i}", N, K, 40, t, f, seed=20) for i, (N, f) in enumerate([(512, 0.5), (128, 1.0), (384, 0.0)])]
+    X = cases[0].X                       # shared input
+    preps = [Prepared(c, dev) for c in cases]
+    Xd = to_dev_bf16(X, dev)
+    for M, path in [(1, B.PATH_AUTO), (16, B.PATH_DECODE), (40, B.PATH_DECODE), (40, B.PATH_PREFILL)]:
+        print(f"many M={M} path={path}", flush=True)
+        Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=path)
+        for p, Y in zip(preps, Ys):
+            single = torch.empty_like(Y)
+            B.patch_gemm(Xd, M, p.P, single, stream(), path=path)
+            torch.cuda.synchronize()
+            assert torch.equal(Y, single), "fused launch differs from the single call"
+            assert relF(Y.cpu().numpy(), p.oracle_gemm(X[:M])) <= TIGHT
+    other = Prepared(synth.make_case("manyk", 128, 512, 4, t, 0.5, seed=21), dev)
+    with pytest.raises(B.PatchError):   # K differs
+        B.patch_gemm_many(Xd, 1, [preps[0].P, other.P],
+                          [torch.empty((1, 512), device=dev), torch.empty((1, 128), device=dev)], stream())
+    other.P.close()
+    for p in preps:
+        p.P.close()
+
+
 def test_prefill_long_k(dev):
     """K beyond the weights-in-registers kernel's limit (256 tiles): the default choice must fall back."""
     c = synth.make_case("longk", 128, 258 * 128, 40, 128, 0.5, seed=12)
