@@ -11,7 +11,8 @@
 //
 // A step is 16 "column blocks" (16 rows of X each).  Per column block and wavefront:
 //   dense: 8 x v_mfma_f32_16x16x32_bf16   or   2:4: 4 x v_smfmac_f32_16x16x64_bf16
-// plus the two LDS reads of the column block three ahead (across step boundaries: the LDS pipeline never drains)
+// plus the two LDS reads of the column block seven ahead (across step boundaries: the LDS pipeline never drains;
+// a 2:4 column block lasts 64 cycles, and three blocks ahead did not cover the LDS latency)
 // and at most one global load.  With one wavefront per SIMD nothing hides an instruction that is not a matrix
 // instruction, and a taken branch is a bubble in the matrix pipe, so the dense / 2:4 decision is ONE scalar branch
 // per step (a wavefront works on one tile at a time) around two branch-free instruction streams.
@@ -20,11 +21,11 @@
 // statements and never seen by the compiler as a value:
 //   a[0:255]     the 64 accumulator tiles (strip s, column block cb) at a[4 (16 s + cb) .. + 3]
 //   v[128:223]   weights of three steps in rotation, 8 x 4 registers each (see PATCH_WR_VA)
-//   v[224:255]   X operands of four column blocks in rotation, 8 registers each
+//   v[64:127]    X operands of eight column blocks in rotation, 8 registers each
 // As compiler values they would meet at the branch (and at the loop edge) as phi nodes, where the register
 // allocator may insert copies - it did: it split the accumulators and spilled, and it copied X operands whose
 // LDS reads were still in flight.  Every asm statement declares all of these registers clobbered, so the compiler
-// keeps nothing of its own there; its own values fit below v128 and it uses no accumulation register, which
+// keeps nothing of its own there; its own values fit below v64 and it uses no accumulation register, which
 // tests/test_abi_host.py checks on the generated assembly.
 // The loads are counted, not tracked: every step issues exactly 16 vector-memory loads per wavefront (8 for the
 // weights whatever the tile type, 8 for X) and 32 LDS reads, so every s_waitcnt below is a compile-time constant.
@@ -52,9 +53,9 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 #define PATCH_WR_VA(AB, I) "v[128+32*" #AB "+4*" #I ":128+32*" #AB "+4*" #I "+3]"
 #define PATCH_WR_VI(AB, S) "v[128+32*" #AB "+16+4*" #S "]"
 // X operand set SET (0..3): low / high half (the two dense operands) and the pair (the 2:4 operand)
-#define PATCH_WR_VBL(SET) "v[224+8*" #SET ":224+8*" #SET "+3]"
-#define PATCH_WR_VBH(SET) "v[228+8*" #SET ":228+8*" #SET "+3]"
-#define PATCH_WR_VB(SET) "v[224+8*" #SET ":224+8*" #SET "+7]"
+#define PATCH_WR_VBL(SET) "v[64+8*" #SET ":64+8*" #SET "+3]"
+#define PATCH_WR_VBH(SET) "v[68+8*" #SET ":68+8*" #SET "+3]"
+#define PATCH_WR_VB(SET) "v[64+8*" #SET ":64+8*" #SET "+7]"
 #define PATCH_WR_R8(r, p) r #p "0", r #p "1", r #p "2", r #p "3", r #p "4", r #p "5", r #p "6", r #p "7"
 #define PATCH_WR_R10(r, p) PATCH_WR_R8(r, p), r #p "8", r #p "9"
 #define PATCH_WR_CLOBBER                                                                                           \
@@ -64,10 +65,10 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
         PATCH_WR_R10("a", 13), PATCH_WR_R10("a", 14), PATCH_WR_R10("a", 15), PATCH_WR_R10("a", 16),                  \
         PATCH_WR_R10("a", 17), PATCH_WR_R10("a", 18), PATCH_WR_R10("a", 19), PATCH_WR_R10("a", 20),                  \
         PATCH_WR_R10("a", 21), PATCH_WR_R10("a", 22), PATCH_WR_R10("a", 23), PATCH_WR_R10("a", 24), "a250", "a251",  \
-        "a252", "a253", "a254", "a255", "v128", "v129", PATCH_WR_R10("v", 13), PATCH_WR_R10("v", 14),                \
+        "a252", "a253", "a254", "a255", "v64", "v65", "v66", "v67", "v68", "v69", PATCH_WR_R10("v", 7), PATCH_WR_R10("v", 8), PATCH_WR_R10("v", 9),      \
+        PATCH_WR_R10("v", 10), PATCH_WR_R10("v", 11), PATCH_WR_R10("v", 12), PATCH_WR_R10("v", 13), PATCH_WR_R10("v", 14),                \
         PATCH_WR_R10("v", 15), PATCH_WR_R10("v", 16), PATCH_WR_R10("v", 17), PATCH_WR_R10("v", 18),                  \
-        PATCH_WR_R10("v", 19), PATCH_WR_R10("v", 20), PATCH_WR_R10("v", 21), PATCH_WR_R10("v", 22),                  \
-        PATCH_WR_R10("v", 23), PATCH_WR_R10("v", 24), "v250", "v251", "v252", "v253", "v254", "v255"
+        PATCH_WR_R10("v", 19), PATCH_WR_R10("v", 20), PATCH_WR_R10("v", 21), "v220", "v221", "v222", "v223"
 
 // ---- weight load of slot I (0..7) of the step two ahead (buffer ABN, K-step J), as asm text for the middle of a
 // column block: 16 bytes per lane from tile base + lane offset + slot offset, the slot offset selected by the tile
@@ -120,12 +121,12 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
       [m0b] "s"(cu.m0b), [xb] "s"(cu.xb), [xo] "v"(xo)
 
 // ---- one column block CB of X (operand set SET) against the wavefront's four strips (weights of step buffer AB),
-// after waiting for its operands, plus the two LDS reads of the column block three ahead into set NSET (LDS byte
+// after waiting for its operands, plus the two LDS reads of the column block seven ahead into set NSET (LDS byte
 // offset OFF from the lane addresses) and one global load: blocks 0-7 a weight load of step s+2 (buffer ABN),
 // blocks 8-15 an X load of step s+3.  J = K-step inside the tile.
 #define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)
 #define PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                      \
-    asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
+    asm volatile("s_waitcnt lgkmcnt(12)\n\t"                                                                        \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
                  "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
                  "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
@@ -144,7 +145,7 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
                  : "scc", PATCH_WR_CLOBBER)
 #define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)
 #define PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                     \
-    asm volatile("s_waitcnt lgkmcnt(4)\n\t"                                                                        \
+    asm volatile("s_waitcnt lgkmcnt(12)\n\t"                                                                        \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
                  "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
                  PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
@@ -168,9 +169,7 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
                  : "v"(al_), "v"(ah_)                                                                              \
                  : PATCH_WR_CLOBBER)
 // column blocks of a step with their operand sets: P(CB, SET, NSET)
-#define PATCH_WR_16(P)                                                                                             \
-    P(0, 0, 3) P(1, 1, 0) P(2, 2, 1) P(3, 3, 2) P(4, 0, 3) P(5, 1, 0) P(6, 2, 1) P(7, 3, 2) P(8, 0, 3) P(9, 1, 0)   \
-    P(10, 2, 1) P(11, 3, 2) P(12, 0, 3) P(13, 1, 0) P(14, 2, 1) P(15, 3, 2)
+#define PATCH_WR_16(P) P(0, 0, 7) P(1, 1, 0) P(2, 2, 1) P(3, 3, 2) P(4, 4, 3) P(5, 5, 4) P(6, 6, 5) P(7, 7, 6) P(8, 0, 7) P(9, 1, 0) P(10, 2, 1) P(11, 3, 2) P(12, 4, 3) P(13, 5, 4) P(14, 6, 5) P(15, 7, 6)
 
 __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                            const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
@@ -324,11 +323,15 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     asm volatile("s_waitcnt vmcnt(24)" ::: "memory");  // X(0) (and A(0)) landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // X operands: column block cb lives in set cb % 4 and is requested three blocks ahead.  Before block cb the
-    // reads of blocks cb, cb+1, cb+2 (two each) are in flight; waiting until four are left completes block cb.
+    // X operands: column block cb lives in set cb % 8 and is requested seven blocks ahead.  Before block cb the
+    // reads of blocks cb .. cb+6 (two each) are in flight; waiting until twelve are left completes block cb.
     PATCH_WR_LDS_FIRST(0, bl0, bh0);
     PATCH_WR_LDS_FIRST(1, bl0, bh0);
     PATCH_WR_LDS_FIRST(2, bl0, bh0);
+    PATCH_WR_LDS_FIRST(3, bl0, bh0);
+    PATCH_WR_LDS_FIRST(4, bl0, bh0);
+    PATCH_WR_LDS_FIRST(5, bl0, bh0);
+    PATCH_WR_LDS_FIRST(6, bl0, bh0);
 
     // lane offsets of the weight loads inside a tile: dense operands, 2:4 values, 2:4 position dwords
     const uint32_t vd = lane * 16 + sh * 4 * 2 * kDenseFragBytes, vs = lane * 16 + sh * 4 * 2 * kSparseFragBytes;
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     };
     struct { uint32_t t, vt; } scr;  // scratch registers of the asm
 // Everything of a column block but its asm statement.  Block 8: this wavefront's share of X(s+1) has landed (after
-// it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 13) and every read of
+// it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 9) and every read of
 // stage (s-1) % 4 has completed, so the loads of X(s+3) (one per block 8-15) may overwrite it.
 #define PATCH_WR_PRE(CB, SS)                                                                                         \
     if (CB == 8) {                                                                                                 \
@@ -381,24 +384,24 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
         asm volatile("" : "+v"(nx.al), "+v"(nx.ah), "+v"(nx.aln), "+v"(nx.ahn), "+v"(nx.v03), "+v"(nx.v47));      \
         asm volatile("" : "+s"(nx.tb), "+s"(nx.mask), "+s"(nx.xb), "+s"(nx.m0b), "+s"(nx.sparse));                \
     }                                                                                                              \
-    const uint32_t ral = CB < 13 ? cu.al : cu.aln, rah = CB < 13 ? cu.ah : cu.ahn, xo = xoff[CB < 8 ? 0 : CB - 8];
-// LDS offset of the column block three ahead
-#define PATCH_WR_OFF_0 6144
-#define PATCH_WR_OFF_1 8192
-#define PATCH_WR_OFF_2 10240
-#define PATCH_WR_OFF_3 12288
-#define PATCH_WR_OFF_4 14336
-#define PATCH_WR_OFF_5 16384
-#define PATCH_WR_OFF_6 18432
-#define PATCH_WR_OFF_7 20480
-#define PATCH_WR_OFF_8 22528
-#define PATCH_WR_OFF_9 24576
-#define PATCH_WR_OFF_10 26624
-#define PATCH_WR_OFF_11 28672
-#define PATCH_WR_OFF_12 30720
-#define PATCH_WR_OFF_13 0
-#define PATCH_WR_OFF_14 2048
-#define PATCH_WR_OFF_15 4096
+    const uint32_t ral = CB < 9 ? cu.al : cu.aln, rah = CB < 9 ? cu.ah : cu.ahn, xo = xoff[CB < 8 ? 0 : CB - 8];
+// LDS offset of the column block seven ahead
+#define PATCH_WR_OFF_0 14336
+#define PATCH_WR_OFF_1 16384
+#define PATCH_WR_OFF_2 18432
+#define PATCH_WR_OFF_3 20480
+#define PATCH_WR_OFF_4 22528
+#define PATCH_WR_OFF_5 24576
+#define PATCH_WR_OFF_6 26624
+#define PATCH_WR_OFF_7 28672
+#define PATCH_WR_OFF_8 30720
+#define PATCH_WR_OFF_9 0
+#define PATCH_WR_OFF_10 2048
+#define PATCH_WR_OFF_11 4096
+#define PATCH_WR_OFF_12 6144
+#define PATCH_WR_OFF_13 8192
+#define PATCH_WR_OFF_14 10240
+#define PATCH_WR_OFF_15 12288
 // One step: SS = position in the round of six, AB / ABN = weight buffers of steps s / s+2, J = K-step in the tile.
 // One scalar branch.  A wavefront without a tile row (N % 256 = 128) multiplies the first tile row's weights as
 // dense data into accumulators that are never stored.
