@@ -163,6 +163,30 @@ def main():
         out["pack"] = dict(shape=[c.N, c.K], ms=(time.time() - tp) / 3 * 1e3,
                            note="patch_pack wall time incl. allocation and the status read-back")
 
+    # ------------------------------------------------------------------ mid M: 13B layer shapes at M = 512, 7B MLP at M = 2048
+    if "mid" not in skip:
+        rows = []
+        for name, N_, K_, Mm in (("13b_attn", 5120, 5120, 512), ("13b_gate", 13824, 5120, 512), ("13b_down", 5120, 13824, 512),
+                                 ("7b_gate", 11008, 4096, 2048), ("7b_attn", 4096, 4096, 64), ("7b_attn", 4096, 4096, 256)):
+            cm = synth.make_case("mid_" + name, N_, K_, Mm, t, 0.5, seed=0)
+            W_hat, Pm = masked_packed(cm)
+            Xm = dev_bf16(cm.X)
+            Ym = torch.empty((Mm, N_), device=dev, dtype=torch.float32)
+            need = B.patch_gemm_workspace_bytes(Mm, Pm)
+            ws = torch.empty(max(need, 16) // 4, device=dev, dtype=torch.float32)
+            res = {}
+            for label, kw in (("unsplit", dict()), ("with_workspace", dict(workspace=ws))):
+                fn = lambda i, kw=kw: B.patch_gemm(Xm, Mm, Pm, Ym, stream, **kw)
+                timed(fn, 10)
+                res[label] = sorted(timed(fn, 50) / 50 for _ in range(3))[1] * 1e6
+            rows.append(dict(shape=[N_, K_], M=Mm, f=0.5, us_without_workspace=round(res["unsplit"], 2),
+                             us=round(res["with_workspace"], 2), workspace_MB=round(need / 1e6, 1),
+                             dense_equiv_TFLOPs=round(2.0 * Mm * N_ * K_ / res["with_workspace"] / 1e6, 1)))
+            Pm.close()
+            del W_hat, Xm, Ym, ws
+        out["mid_m"] = dict(rows=rows, note="patch_gemm, automatic path; with a workspace the prefill launch splits K over "
+                                            "otherwise idle compute units (partials summed in slice order)")
+
     # ------------------------------------------------------------------ decode: 7B attention projection
     if "decode" not in skip:
         dec = []

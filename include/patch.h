@@ -41,7 +41,8 @@ typedef enum {
 } patch_status;
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of 16 rows, PREFILL in 256-row
- * tiles.  AUTO: decode for M <= 128 (measured crossover), prefill otherwise. */
+ * tiles.  AUTO (measured crossovers): without a workspace decode for M <= 128, prefill above; with a workspace for
+ * at least two slices (see patch_gemm_opts) decode for M <= 16, and for M <= 32 if the weight is below 64 MB. */
 typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
 
 /* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and
@@ -49,11 +50,19 @@ typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 
 typedef struct {
     int path;    /* patch_path                                                                      */
     int split_k; /* decode: K slices (one wavefront each) per workgroup whose fp32 partials are     */
-                 /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto       */
+                 /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto.       */
+                 /* prefill (tile 128): K slices per output tile, one workgroup each, whose partial  */
+                 /* products go to `workspace` and are summed in slice order by a second launch;     */
+                 /* 0 = auto (1 unless the tile grid would leave a third of the chip idle), 1 = no   */
+                 /* split.  Never more slices than the workspace holds: without one, no split.       */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
                  /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
                  /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
                  /* K-steps per wavefront.  A variant that does not apply falls back to the default.     */
+    void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for split prefill launches, */
+                            /* or NULL.  The library never allocates in a product call.  Launches that   */
+                            /* may run concurrently need distinct workspaces.                            */
+    size_t workspace_bytes; /* its size; patch_gemm_workspace_bytes says what a launch would use         */
 } patch_gemm_opts;
 
 /*
@@ -91,6 +100,10 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
 patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream);
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream,
                            const patch_gemm_opts* opts);
+
+/* Bytes of patch_gemm_opts.workspace the product with these M, P and opts (path, split_k; NULL = defaults) would
+ * use if it were given enough: slices x M x N x 4 for a split prefill launch, else 0. */
+size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts);
 
 /*
  * The same product for several weights that share one input: Y[i] = X * W_hat[i]^T, i < count (the q / k / v

@@ -18,14 +18,15 @@ OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_unpack", "patch_canonical_sizes",
-    "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
+    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_unpack",
+    "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
 
 class GemmOpts(ctypes.Structure):
-    _fields_ = [("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int)]
+    _fields_ = [("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 class PatchError(RuntimeError):
@@ -49,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
+        L.patch_gemm_workspace_bytes.argtypes = [i64, vp, ctypes.POINTER(GemmOpts)]
+        L.patch_gemm_workspace_bytes.restype = sz
         L.patch_gemm_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp, ctypes.POINTER(GemmOpts)]
         L.patch_unpack.argtypes = [vp, vp, vp]
         L.patch_canonical_sizes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
@@ -154,23 +157,37 @@ def patch_pack(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> P
     return Packed(out.value)
 
 
-def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> None:
-    if path == PATH_AUTO and split_k == 0 and variant == 0:
+def _opts(path, split_k, variant, workspace, workspace_bytes):
+    if workspace is not None and workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return GemmOpts(path, split_k, variant, _ptr(workspace) if workspace is not None else None, workspace_bytes or 0)
+
+
+def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0,
+               workspace=None, workspace_bytes=None) -> None:
+    """workspace: a device tensor (or pointer + workspace_bytes) for split prefill launches, see patch.h."""
+    if path == PATH_AUTO and split_k == 0 and variant == 0 and workspace is None:
         st = lib().patch_gemm(_ptr(X), M, P.handle, _ptr(Y), stream)
     else:
-        o = GemmOpts(path, split_k, variant)
+        o = _opts(path, split_k, variant, workspace, workspace_bytes)
         st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
     _check(st, "patch_gemm")
 
 
-def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> None:
+def patch_gemm_workspace_bytes(M: int, P: Packed, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> int:
+    o = GemmOpts(path, split_k, variant, None, 0)
+    return int(lib().patch_gemm_workspace_bytes(M, P.handle, ctypes.byref(o)))
+
+
+def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0,
+                    workspace=None, workspace_bytes=None) -> None:
     """Y[i] = X * W_hat[i]^T for weights that share X (same K, same tile); one decode launch for all of them."""
     n = len(Ps)
     if n != len(Ys):
         raise PatchError(ERR_ARG, "patch_gemm_many: as many outputs as weights")
     hp = (ctypes.c_void_p * max(n, 1))(*[p.handle for p in Ps])
     yp = (ctypes.c_void_p * max(n, 1))(*[_ptr(y) for y in Ys])
-    o = GemmOpts(path, split_k, variant)
+    o = _opts(path, split_k, variant, workspace, workspace_bytes)
     _check(lib().patch_gemm_many(_ptr(X), M, hp, yp, n, stream, ctypes.byref(o)), "patch_gemm_many")
 
 

@@ -169,15 +169,27 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     return PATCH_OK;
 }
 
+// Measured crossover between 16-row decode passes (every pass streams the whole weight) and the 256 x 256-tile
+// prefill kernel.  Unsplit, the prefill grid is too small to fill the chip at small M and loses up to M = 128.
+// With a workspace the prefill launch splits K over the idle compute units and costs about 20 us + the weight
+// stream, which two decode passes only beat on small weights (4096 x 4096: 16 vs 20 us at M = 32).
+static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
+    const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float) &&
+                    P->tile == 128;
+    if (!ws) return (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (M <= 16) return PATCH_PATH_DECODE;
+    if (M <= 32 && P->payload_bytes < ((size_t)64 << 20)) return PATCH_PATH_DECODE;
+    return PATCH_PATH_PREFILL;
+}
+
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream, const patch_gemm_opts* opts) {
     if (!X || !P || !Y || M <= 0) return PATCH_ERR_ARG;
     if (!aligned16(X) || !aligned16(Y)) return PATCH_ERR_ARG;
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
-    // measured crossover: up to 128 rows, 16-row decode passes beat the 256 x 256-tile prefill kernel, whose
-    // grid is too small to fill the chip at that M
-    if (path == PATCH_PATH_AUTO) path = (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
+    if (path == PATCH_PATH_AUTO) path = auto_path(M, P, opts);
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a;
     a.X = static_cast<const uint16_t*>(X);
@@ -186,16 +198,36 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.payload = P->d_payload; a.table = P->d_table;
     a.Y = static_cast<float*>(Y);
     a.n_cus = P->n_cus;
+    if (opts && opts->workspace) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_DECODE) {
         for (int64_t m0 = 0; m0 < M; m0 += 16) {
             const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
             launch_decode(a, m0, rows, split_k, variant, s);
         }
     } else {
-        launch_prefill(a, variant, s);
+        launch_prefill(a, variant, split_k, s);
     }
     HIP_TRY(hipGetLastError());
     return PATCH_OK;
+}
+
+size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
+    if (!P || M <= 0) return 0;
+    int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
+    if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
+    patch_gemm_opts enough = {path, split_k, variant, reinterpret_cast<void*>(16), ~(size_t)0};  // the choice given enough
+    if (path == PATCH_PATH_AUTO) path = auto_path(M, P, &enough);
+    if (path != PATCH_PATH_PREFILL || (variant != 0 && variant != 3)) return 0;
+    GemmArgs a;
+    a.X = nullptr; a.M = M; a.N = P->N; a.K = P->K;
+    a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
+    a.payload = nullptr; a.table = nullptr; a.Y = nullptr;
+    a.n_cus = P->n_cus;
+    if (!prefill_wreg_supports(a)) return 0;
+    a.ws = reinterpret_cast<float*>(16);  // "enough": ask for the unconstrained choice
+    a.ws_bytes = ~(size_t)0;
+    const int s = prefill_wreg_split(a, split_k);
+    return s > 1 ? (size_t)s * (size_t)M * (size_t)P->N * sizeof(float) : 0;
 }
 
 patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count, void* stream,
@@ -210,9 +242,9 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
-    if (path == PATCH_PATH_AUTO) path = (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (path == PATCH_PATH_AUTO) path = auto_path(M, P[0], opts);
     if (path == PATCH_PATH_PREFILL || count == 1) {
-        patch_gemm_opts o = {path, split_k, variant};
+        patch_gemm_opts o = {path, split_k, variant, opts ? opts->workspace : nullptr, opts ? opts->workspace_bytes : 0};
         for (int i = 0; i < count; ++i) {
             const patch_status st = patch_gemm_ex(X, M, P[i], Y[i], stream, &o);
             if (st != PATCH_OK) return st;

@@ -394,8 +394,8 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
 // Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_t128;
 // tile 64 -> prefill_kernel_v0.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_t128, 3 prefill_kernel_wreg
 // (each falling back to the default choice where it does not apply).
-void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream) {
-    if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, stream); return; }
+void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream) {
+    if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, split_k, stream); return; }
     if (a.tile == 128 && variant != 1) {
         static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_t128),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);

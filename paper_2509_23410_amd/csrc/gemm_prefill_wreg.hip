@@ -171,9 +171,25 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 // column blocks of a step with their operand sets: P(CB, SET, NSET)
 #define PATCH_WR_16(P) P(0, 0, 7) P(1, 1, 0) P(2, 2, 1) P(3, 3, 2) P(4, 4, 3) P(5, 5, 4) P(6, 6, 5) P(7, 7, 6) P(8, 0, 7) P(9, 1, 0) P(10, 2, 1) P(11, 3, 2) P(12, 4, 3) P(13, 5, 4) P(14, 6, 5) P(15, 7, 6)
 
+// Y = sum over the slices of the partial products, slice 0 first: a fixed order, so the result is reproducible.
+// (Adding the partials to Y with fp32 atomics instead was 2-3x slower than this second launch.)
+__global__ __launch_bounds__(256) void wr_reduce_kernel(const wr_f32x4* __restrict__ ws, size_t n4, int slices, wr_f32x4* __restrict__ Y) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+        wr_f32x4 acc = ws[i];
+        for (int s = 1; s < slices; ++s) {
+            const wr_f32x4 v = ws[(size_t)s * n4 + i];
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        Y[i] = acc;
+    }
+}
+
+// SPLIT: the launch splits K over gridDim.y workgroups per output tile (a grid of tiles alone would leave most of the
+// chip idle); slice y writes its partial product to Y + y * M * N (a workspace), wr_reduce_kernel sums the slices.
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                            const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y) {
+                                                           int Tk_all, int tiles_n, int tiles_m, float* __restrict__ Y) {
     constexpr int TILE = 128;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
@@ -213,7 +229,10 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     // N is a multiple of 128, not necessarily of 256: the wavefronts of a missing second tile row copy X and meet
     // the barriers like the others, read the first tile row's weights (valid addresses) and multiply nothing
     const bool live = n0 + (int64_t)tr * TILE < N;
-    const uint32_t* trow = table + (n0 / TILE + (live ? tr : 0)) * Tk;
+    // this workgroup's K slice, in tiles: to the rest of the kernel it is a product with a shorter K
+    const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
+    const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
+    const uint32_t* trow = table + (n0 / TILE + (live ? tr : 0)) * Tk_all + t_begin;
 
     // ---- per-lane sources of the X copy: wavefront w copies the 1 KB pieces w, w+4, ..., w+28 of the 32 KB stage.
     // LDS chunk c (16 bytes) = row c / 8, physical chunk c % 8, which holds logical chunk (c % 8) ^ ((row / 2) % 8):
@@ -228,7 +247,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
         if (row >= M) row = M - 1;  // rows past M: any valid row, their outputs are not stored
         xoff[i] = (uint32_t)((row * K + pl * 8) * 2);
     }
-    const uint8_t* const xbase = reinterpret_cast<const uint8_t*>(X);
+    const uint8_t* const xbase = reinterpret_cast<const uint8_t*>(X) + (size_t)t_begin * (TILE * 2);
     // ---- per-lane LDS read addresses of a column block's two operands (+ stage * 32 KB + block * 2 KB)
     const uint32_t lds0 = (uint32_t)(size_t)((wr_lptr_t)lds);
     const int swz = (col >> 1) & 7;
@@ -462,16 +481,16 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
         const int64_t m = m0 + 16 * CB + col;                                                                      \
-        float* yrow = Y + m * N + n0 + 128 * tr + 64 * sh + 4 * q;                                                 \
+        float* yrow = Y + (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + 128 * tr + 64 * sh + 4 * q;                                                 \
         float v[4];                                                                                                \
         PATCH_WR_READ(0, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};      \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(1, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(2, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(3, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]}; \
+        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
     }
         PATCH_WR_16(PATCH_WR_STORE)
 #undef PATCH_WR_STORE
@@ -484,15 +503,49 @@ bool prefill_wreg_supports(const GemmArgs& a) {
     return a.tile == 128 && a.M > 0 && a.K <= 256 * 128 && (uint64_t)a.M * (uint64_t)a.K * 2 < (1ull << 32);
 }
 
-void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream) {
-    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg),
-                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
-    (void)granted;
+// K slices per output tile: as many as the workspace a.ws holds partial products for (M N fp32 each), at most
+// `requested` if > 0, else as many as fill the chip when the tile grid covers less than about two thirds of it -
+// each slice at least four tiles (eight steps) long, at most 8.  1 = no split (no workspace needed).
+int prefill_wreg_split(const GemmArgs& a, int requested) {
+    const int tiles = (int)(((a.N + kWrBN - 1) / kWrBN) * ((a.M + kWrBM - 1) / kWrBM));
+    int s = requested;
+    if (s <= 0) {
+        s = 1;
+        if (tiles < (a.n_cus * 2) / 3) {
+            s = a.n_cus / tiles;
+            if (s > a.Tk / 4) s = a.Tk / 4;
+            if (s > 8) s = 8;
+        }
+    }
+    if (s > a.Tk) s = a.Tk;
+    const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
+    const size_t fit = (a.ws && per_slice) ? a.ws_bytes / per_slice : 0;
+    if ((size_t)s > fit) s = (int)fit;
+    return s < 2 ? 1 : s;
+}
+
+void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
+    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<false>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
+    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<true>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
+    (void)granted0;
+    (void)granted1;
     const int tiles_n = (int)((a.N + kWrBN - 1) / kWrBN), tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    hipLaunchKernelGGL(prefill_kernel_wreg, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, tiles_n,
-                       tiles_m, a.Y);
+    const int split = prefill_wreg_split(a, split_k);
+    if (split == 1) {
+        hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
+                           a.Tk, tiles_n, tiles_m, a.Y);
+    } else {
+        hipLaunchKernelGGL(prefill_kernel_wreg<true>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload,
+                           a.table, a.Tk, tiles_n, tiles_m, a.ws);
+        const size_t n4 = (size_t)a.M * (size_t)a.N / 4;
+        const size_t blocks = (n4 + 255) / 256;
+        hipLaunchKernelGGL(wr_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
+                           reinterpret_cast<const wr_f32x4*>(a.ws), n4, split, reinterpret_cast<wr_f32x4*>(a.Y));
+    }
 }
 
 }  // namespace patch

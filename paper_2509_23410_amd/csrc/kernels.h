@@ -20,6 +20,8 @@ struct GemmArgs {
     const uint8_t* payload;
     const uint32_t* table;  // Tn x Tk entries
     float* Y;               // M x N fp32
+    float* ws = nullptr;    // caller's workspace for split-K partial products (prefill), may be null
+    size_t ws_bytes = 0;
     int n_cus;
 };
 
@@ -41,8 +43,9 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
 int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
 
 // Any M (prefill shape).
-void launch_prefill(const GemmArgs& a, int variant, hipStream_t stream);
+void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream);
 bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB
-void launch_prefill_wreg(const GemmArgs& a, hipStream_t stream);
+int prefill_wreg_split(const GemmArgs& a, int requested);       // K slices per output tile the launch will use
+void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream);
 
 }  // namespace patch

@@ -314,6 +314,32 @@ def test_gemm_many_matches_single_calls(dev):
         p.P.close()
 
 
+def test_prefill_split_k(dev):
+    """Prefill with K split over workgroups (partial products in a caller workspace, summed in slice order): every
+    slice count, slices that do not divide the tile count, ragged M, an odd tile-row count; auto picks a split for
+    this small grid; a workspace that is too small or absent degrades to fewer slices / no split; reproducible."""
+    c = synth.make_case("splitk", 384, 2048, 300, 128, 0.5, seed=13)
+    p = Prepared(c, dev)
+    ws = torch.empty(16 * 300 * 384, device=dev, dtype=torch.float32)
+    for M in (300, 40):
+        Yo = p.oracle_gemm(c.X[:M])
+        need = B.patch_gemm_workspace_bytes(M, p.P, path=B.PATH_PREFILL)
+        assert need > 0 and need % (M * 384 * 4) == 0, "auto must split this 2- or 4-tile grid"
+        for sk in (0, 1, 2, 3, 5, 16):
+            print(f"prefill split_k={sk} M={M}", flush=True)
+            Y = p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=sk, workspace=ws)
+            assert np.isfinite(Y).all()
+            assert relF(Y, Yo) <= TIGHT
+            assert np.array_equal(Y, p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=sk, workspace=ws)), "not reproducible"
+        small = ws[: 2 * M * 384 + 5]            # room for two slices only
+        assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5, workspace=small), Yo) <= TIGHT
+        assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5), Yo) <= TIGHT   # none: unsplit
+    assert B.patch_gemm_workspace_bytes(1, p.P) == 0            # decode path
+    assert B.patch_gemm_workspace_bytes(40, p.P) > 0            # auto: prefill, split, once a workspace is there
+    assert relF(p.gemm(c.X[:40], workspace=ws), p.oracle_gemm(c.X[:40])) <= TIGHT
+    p.P.close()
+
+
 def test_prefill_long_k(dev):
     """K beyond the weights-in-registers kernel's limit (256 tiles): the default choice must fall back."""
     c = synth.make_case("longk", 128, 258 * 128, 40, 128, 0.5, seed=12)
