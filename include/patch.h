@@ -101,6 +101,22 @@ patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream,
                            const patch_gemm_opts* opts);
 
+/*
+ * Schedule autotuner (Appendix A leaves tile shape and schedule - e.g. split-K - to an autotuner run per layer
+ * and input shape, decode first).  Times the candidate schedules of patch_gemm_ex for this M and P on the device,
+ * on real operands, and returns the fastest.  Candidates: both paths where they apply (decode passes up to
+ * M = 128), the kernel variants of the path, and for prefill the K-split counts the workspace allows.
+ *   X, Y       as for patch_gemm (Y is overwritten several times; on return it holds the product)
+ *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
+ *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1
+ *   best       OUT: the options to pass to patch_gemm_ex / patch_gemm_many (workspace fields included)
+ *   best_us    OUT, may be NULL: its average time per launch in microseconds
+ * Not a hot-path call: it creates and destroys two HIP events and synchronises `stream` after every candidate.
+ * Errors as patch_gemm_ex, plus PATCH_ERR_ARG for reps < 1 or a NULL `best`.
+ */
+patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
+                        void* stream, int reps, patch_gemm_opts* best, float* best_us);
+
 /* Bytes of patch_gemm_opts.workspace the product with these M, P and opts (path, split_k; NULL = defaults) would
  * use if it were given enough: slices x M x N x 4 for a split prefill launch, else 0. */
 size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts);

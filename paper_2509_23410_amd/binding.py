@@ -18,7 +18,7 @@ OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_unpack",
+    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
+        L.patch_tune.argtypes = [vp, i64, vp, vp, vp, sz, vp, ci, ctypes.POINTER(GemmOpts), ctypes.POINTER(ctypes.c_float)]
+        L.patch_tune.restype = ci
         L.patch_gemm_workspace_bytes.argtypes = [i64, vp, ctypes.POINTER(GemmOpts)]
         L.patch_gemm_workspace_bytes.restype = sz
         L.patch_gemm_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp, ctypes.POINTER(GemmOpts)]
@@ -172,6 +174,17 @@ def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, 
         o = _opts(path, split_k, variant, workspace, workspace_bytes)
         st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
     _check(st, "patch_gemm")
+
+
+def patch_tune(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, stream: int = 0, reps: int = 20):
+    """-> (dict(path, split_k, variant), microseconds per launch) of the fastest schedule; pass the dict (and the same
+    workspace) to patch_gemm."""
+    if workspace is not None and workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    o, us = GemmOpts(), ctypes.c_float(0)
+    _check(lib().patch_tune(_ptr(X), M, P.handle, _ptr(Y), _ptr(workspace) if workspace is not None else None,
+                            workspace_bytes or 0, stream, reps, ctypes.byref(o), ctypes.byref(us)), "patch_tune")
+    return dict(path=o.path, split_k=o.split_k, variant=o.variant), float(us.value)
 
 
 def patch_gemm_workspace_bytes(M: int, P: Packed, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> int:

@@ -211,6 +211,57 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     return PATCH_OK;
 }
 
+patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
+                        void* stream, int reps, patch_gemm_opts* best, float* best_us) {
+    if (!X || !P || !Y || !best || M <= 0 || reps < 1) return PATCH_ERR_ARG;
+    if (!aligned16(X) || !aligned16(Y) || (workspace && !aligned16(workspace))) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<patch_gemm_opts> cand;
+    auto add = [&](int path, int split_k, int variant, bool ws) {
+        cand.push_back(patch_gemm_opts{path, split_k, variant, ws ? workspace : nullptr, ws ? workspace_bytes : 0});
+    };
+    if (M <= 128) {  // every 16-row pass streams the whole weight again: no contender beyond that
+        add(PATCH_PATH_DECODE, 0, 0, false);
+        add(PATCH_PATH_DECODE, 0, 2, false);
+        add(PATCH_PATH_DECODE, 0, 3, false);
+    }
+    if (P->tile == 128) {
+        add(PATCH_PATH_PREFILL, 1, 0, false);
+        add(PATCH_PATH_PREFILL, 1, 2, false);
+        const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+        if (workspace)
+            for (int sk : {2, 3, 4, 6, 8, 12, 16})
+                if ((size_t)sk * per_slice <= workspace_bytes && sk * 2 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
+    } else {
+        add(PATCH_PATH_PREFILL, 1, 1, false);
+    }
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); g_last_hip_error = (int)e; return PATCH_ERR_HIP; }
+    patch_status st = PATCH_OK;
+    float best_ms = 0.f;
+    int best_i = -1;
+    for (size_t i = 0; i < cand.size() && st == PATCH_OK; ++i) {
+        for (int r = 0; r < 2 && st == PATCH_OK; ++r) st = patch_gemm_ex(X, M, P, Y, stream, &cand[i]);
+        if (st != PATCH_OK) break;
+        hipError_t e = hipEventRecord(e0, s);
+        for (int r = 0; r < reps && st == PATCH_OK; ++r) st = patch_gemm_ex(X, M, P, Y, stream, &cand[i]);
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; st = PATCH_ERR_HIP; break; }
+        if (best_i < 0 || ms < best_ms) { best_ms = ms; best_i = (int)i; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != PATCH_OK) return st;
+    *best = cand[best_i];
+    if (best_us) *best_us = best_ms * 1000.f / (float)reps;
+    // leave the product of the chosen schedule in Y
+    return patch_gemm_ex(X, M, P, Y, stream, best);
+}
+
 size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
     if (!P || M <= 0) return 0;
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;

@@ -55,6 +55,7 @@ def test_argument_errors_without_device():
     assert L.patch_unpack(0, fake, 0) == B.ERR_ARG
     assert L.patch_packed_bytes(0) == 0
     assert L.patch_gemm_workspace_bytes(256, 0, None) == 0
+    assert L.patch_tune(fake, 1, 0, fake, None, 0, None, 5, None, None) == B.ERR_ARG
     L.patch_free(0)
     with pytest.raises(B.PatchError):
         B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)

@@ -340,6 +340,33 @@ def test_prefill_split_k(dev):
     p.P.close()
 
 
+def test_tune_returns_a_valid_fast_schedule(dev):
+    """patch_tune: the schedule it returns reproduces the oracle result, with and without a workspace, for a decode
+    and a mid-M shape; its time is not worse than the default schedule's measured the same way."""
+    c = synth.make_case("tune", 512, 2048, 200, 128, 0.5, seed=14)
+    p = Prepared(c, dev)
+    ws = torch.empty(8 * 200 * 512, device=dev, dtype=torch.float32)
+    for M, w in [(4, None), (200, None), (200, ws), (48, ws)]:
+        X = to_dev_bf16(c.X[:M], dev)
+        Y = torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32)
+        opts, us = B.patch_tune(X, M, p.P, Y, workspace=w, stream=stream(), reps=5)
+        print(f"tune M={M} workspace={w is not None}: {opts} {us:.1f} us", flush=True)
+        assert us > 0 and opts["path"] in (B.PATH_DECODE, B.PATH_PREFILL)
+        torch.cuda.synchronize()
+        Yo = p.oracle_gemm(c.X[:M])
+        assert relF(Y.cpu().numpy(), Yo) <= TIGHT               # Y holds the chosen schedule's product
+        assert relF(p.gemm(c.X[:M], workspace=w, **opts), Yo) <= TIGHT
+    p.P.close()
+    c64 = synth.make_case("tune64", 256, 512, 150, 64, 0.5, seed=15)   # tile 64: one prefill candidate
+    p64 = Prepared(c64, dev)
+    X = to_dev_bf16(c64.X, dev)
+    Y = torch.empty((150, 256), device=dev, dtype=torch.float32)
+    opts, us = B.patch_tune(X, 150, p64.P, Y, stream=stream(), reps=3)
+    torch.cuda.synchronize()
+    assert opts["path"] == B.PATH_PREFILL and relF(Y.cpu().numpy(), p64.oracle_gemm(c64.X)) <= TIGHT
+    p64.P.close()
+
+
 def test_prefill_long_k(dev):
     """K beyond the weights-in-registers kernel's limit (256 tiles): the default choice must fall back."""
     c = synth.make_case("longk", 128, 258 * 128, 40, 128, 0.5, seed=12)
