@@ -125,7 +125,9 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
  * The same product for several weights that share one input: Y[i] = X * W_hat[i]^T, i < count (the q / k / v
  * projections of an attention block, the gate / up projections of an MLP; Appendix A times the layer's products
  * for one decode input and one prefill input).  On the decode path all weights run in ONE launch per 16 rows of
- * X, which amortises launch and ramp-up over all their bytes; on the prefill path it is one launch per weight.
+ * X, which amortises launch and ramp-up over all their bytes; on the prefill path (tile 128) one launch covers the
+ * output tiles of all weights - one tail instead of one per weight - unless they are so few that splitting K pays
+ * (a workspace is given, split_k = 0), or opts ask for a kernel variant or split: then one launch per weight.
  *   P      HOST array of count handles; all with the same K and the same tile, N may differ
  *   Y      HOST array of count DEVICE pointers, Y[i] is M x N[i] fp32 row-major, 16-byte aligned, distinct
  *   count  1 .. PATCH_MAX_MANY

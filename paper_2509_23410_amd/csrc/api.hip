@@ -294,6 +294,35 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
     if (path == PATCH_PATH_AUTO) path = auto_path(M, P[0], opts);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs a = {};
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = P[0]->K; a.N = P[0]->N;
+    a.tile = P[0]->tile; a.Tk = P[0]->Tk;
+    a.n_cus = P[0]->n_cus;
+    if (path == PATCH_PATH_PREFILL && count > 1 && (variant == 0 || variant == 3) && split_k <= 1 && prefill_wreg_supports(a)) {
+        // one launch over the feature blocks of all weights - unless the blocks are so few that splitting K pays
+        // (then one split launch per weight, below)
+        int blocks = 0;
+        WeightSet set = {};
+        for (int i = 0; i < count; ++i) {
+            set.payload[i] = P[i]->d_payload;
+            set.table[i] = P[i]->d_table;
+            set.Y[i] = static_cast<float*>(Y[i]);
+            set.N[i] = P[i]->N;
+            set.first[i] = blocks;
+            blocks += (int)((P[i]->N + 255) / 256);
+        }
+        set.count = count;
+        set.units = blocks;
+        const int64_t tiles = (int64_t)blocks * ((M + 255) / 256);
+        const bool have_ws = opts && opts->workspace && split_k == 0;
+        if (!have_ws || tiles >= (a.n_cus * 2) / 3) {
+            launch_prefill_wreg_set(a, set, s);
+            HIP_TRY(hipGetLastError());
+            return PATCH_OK;
+        }
+    }
     if (path == PATCH_PATH_PREFILL || count == 1) {
         patch_gemm_opts o = {path, split_k, variant, opts ? opts->workspace : nullptr, opts ? opts->workspace_bytes : 0};
         for (int i = 0; i < count; ++i) {
@@ -302,12 +331,6 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
         }
         return PATCH_OK;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    GemmArgs a = {};
-    a.X = static_cast<const uint16_t*>(X);
-    a.M = M; a.K = P[0]->K;
-    a.tile = P[0]->tile; a.Tk = P[0]->Tk;
-    a.n_cus = P[0]->n_cus;
     DecodeSet set = {};
     int strips = 0;
     for (int i = 0; i < count; ++i) {
@@ -315,11 +338,11 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
         set.table[i] = P[i]->d_table;
         set.Y[i] = static_cast<float*>(Y[i]);
         set.N[i] = P[i]->N;
-        set.first_strip[i] = strips;
+        set.first[i] = strips;
         strips += (int)(P[i]->N / 16);
     }
     set.count = count;
-    set.strips = strips;
+    set.units = strips;
     for (int64_t m0 = 0; m0 < M; m0 += 16) {
         const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
         launch_decode_set(a, set, m0, rows, split_k, variant, s);

@@ -54,12 +54,12 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
     if (set.count > 1)
 #pragma unroll
     for (int i = 1; i < kMaxMany; ++i) {
-        const bool here = i < set.count && (int)blockIdx.x >= set.first_strip[i];
+        const bool here = i < set.count && (int)blockIdx.x >= set.first[i];
         payload = here ? set.payload[i] : payload;
         table = here ? set.table[i] : table;
         Y = here ? set.Y[i] : Y;
         N = here ? set.N[i] : N;
-        first = here ? set.first_strip[i] : first;
+        first = here ? set.first[i] : first;
     }
     // the selects above are wavefront-uniform; say so (the weight addresses below must be scalar)
     payload = reinterpret_cast<const uint8_t*>(uniform64(reinterpret_cast<uint64_t>(payload)));
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
 
 template <int TILE>
 static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
-    dim3 grid((unsigned)set.strips), block((unsigned)(kw * 64));
+    dim3 grid((unsigned)set.units), block((unsigned)(kw * 64));
     if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
     else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
 }
@@ -207,12 +207,12 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
     set.Y[0] = a.Y;
     set.N[0] = a.N;
     set.count = 1;
-    set.strips = (int)(a.N / 16);
+    set.units = (int)(a.N / 16);
     return launch_decode_set(a, set, m0, rows, split_k, variant, stream);
 }
 
 int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
-    const int64_t strips = set.strips;
+    const int64_t strips = set.units;
     const int total = a.Tk * (a.tile / kStepCols);
     int nk = 0;
     if (variant == 2) nk = 8;

@@ -184,12 +184,16 @@ __global__ __launch_bounds__(256) void wr_reduce_kernel(const wr_f32x4* __restri
     }
 }
 
+__device__ __forceinline__ uint64_t wr_uniform64(uint64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
 // SPLIT: the launch splits K over gridDim.y workgroups per output tile (a grid of tiles alone would leave most of the
 // chip idle); slice y writes its partial product to Y + y * M * N (a workspace), wr_reduce_kernel sums the slices.
 template <bool SPLIT>
-__global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
-                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                           int Tk_all, int tiles_n, int tiles_m, float* __restrict__ Y) {
+__global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t K, int Tk_all, int tiles_n,
+                                                           int tiles_m, const WeightSet set) {
     constexpr int TILE = 128;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
@@ -225,6 +229,29 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
             bm = (tiles_m / GM) * GM + rem % gm;
         }
     }
+    // which weight of the set the feature block belongs to: scalar selects, made explicitly uniform, so that the
+    // weight addresses stay in scalar registers
+    const uint8_t* __restrict__ payload = set.payload[0];
+    const uint32_t* __restrict__ table = set.table[0];
+    float* __restrict__ Y = set.Y[0];
+    int64_t N = set.N[0];
+    if (set.count > 1) {
+        int first = 0;
+#pragma unroll
+        for (int i = 1; i < kMaxMany; ++i) {
+            const bool here = i < set.count && bn >= set.first[i];
+            payload = here ? set.payload[i] : payload;
+            table = here ? set.table[i] : table;
+            Y = here ? set.Y[i] : Y;
+            N = here ? set.N[i] : N;
+            first = here ? set.first[i] : first;
+        }
+        bn -= __builtin_amdgcn_readfirstlane(first);
+    }
+    payload = reinterpret_cast<const uint8_t*>(wr_uniform64(reinterpret_cast<uint64_t>(payload)));
+    table = reinterpret_cast<const uint32_t*>(wr_uniform64(reinterpret_cast<uint64_t>(table)));
+    Y = reinterpret_cast<float*>(wr_uniform64(reinterpret_cast<uint64_t>(Y)));
+    N = (int64_t)wr_uniform64((uint64_t)N);
     const int64_t n0 = (int64_t)bn * kWrBN, m0 = (int64_t)bm * kWrBM;
     // N is a multiple of 128, not necessarily of 256: the wavefronts of a missing second tile row copy X and meet
     // the barriers like the others, read the first tile row's weights (valid addresses) and multiply nothing
@@ -524,28 +551,47 @@ int prefill_wreg_split(const GemmArgs& a, int requested) {
     return s < 2 ? 1 : s;
 }
 
-void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
+static void wr_grant_lds() {
     static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<false>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
     static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<true>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
     (void)granted0;
     (void)granted1;
+}
+
+void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
+    wr_grant_lds();
     const int tiles_n = (int)((a.N + kWrBN - 1) / kWrBN), tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
     const int split = prefill_wreg_split(a, split_k);
+    WeightSet set = {};
+    set.payload[0] = a.payload;
+    set.table[0] = a.table;
+    set.N[0] = a.N;
+    set.count = 1;
+    set.units = tiles_n;
     if (split == 1) {
-        hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
-                           a.Tk, tiles_n, tiles_m, a.Y);
+        set.Y[0] = a.Y;
+        hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n, tiles_m, set);
     } else {
-        hipLaunchKernelGGL(prefill_kernel_wreg<true>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.N, a.K, a.payload,
-                           a.table, a.Tk, tiles_n, tiles_m, a.ws);
+        set.Y[0] = a.ws;
+        hipLaunchKernelGGL(prefill_kernel_wreg<true>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
+                           tiles_m, set);
         const size_t n4 = (size_t)a.M * (size_t)a.N / 4;
         const size_t blocks = (n4 + 255) / 256;
         hipLaunchKernelGGL(wr_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
                            reinterpret_cast<const wr_f32x4*>(a.ws), n4, split, reinterpret_cast<wr_f32x4*>(a.Y));
     }
+}
+
+void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_t stream) {
+    wr_grant_lds();
+    const int tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
+    const int nblk = set.units * tiles_m;
+    const int grid = ((nblk + 7) / 8) * 8;
+    hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, set.units, tiles_m, set);
 }
 
 }  // namespace patch

@@ -25,16 +25,19 @@ struct GemmArgs {
     int n_cus;
 };
 
-// Up to kMaxMany weights that share one X (same K, same tile), multiplied in one decode launch.
+// Up to kMaxMany weights that share one X (same K, same tile), multiplied in one launch.  The launch numbers its
+// units of features (decode: 16-feature strips; prefill: 256-feature blocks, each weight rounded up) across all
+// weights; first[i] is the first unit of weight i.
 constexpr int kMaxMany = 8;
-struct DecodeSet {
+struct WeightSet {
     const uint8_t* payload[kMaxMany];
     const uint32_t* table[kMaxMany];
     float* Y[kMaxMany];          // M x N[i] fp32
     int64_t N[kMaxMany];
-    int first_strip[kMaxMany];   // index of the weight's first 16-feature strip in the launch
-    int count, strips;           // weights, strips in total
+    int first[kMaxMany];
+    int count, units;            // weights, units in total
 };
+typedef WeightSet DecodeSet;
 
 // M <= 16 rows of X starting at row m0 (decode shape).  split_k = K slices (wavefronts) per workgroup,
 // 0 picks a default.  Returns the number used.
@@ -47,5 +50,8 @@ void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t str
 bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB
 int prefill_wreg_split(const GemmArgs& a, int requested);       // K slices per output tile the launch will use
 void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream);
+// The same for a set of weights, never split; a supplies X, M, K, tile, Tk, n_cus.  All of the set must pass
+// prefill_wreg_supports with these M, K.
+void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_t stream);
 
 }  // namespace patch

@@ -291,11 +291,11 @@ def test_gemm_many_matches_single_calls(dev):
     """patch_gemm_many: several weights sharing X (different N, different maps) in one decode launch per 16 rows,
     bit-equal to the single calls and within tolerance of the oracle; prefill path: one launch per weight."""
     K, t = 1024, 128
-    cases = [synth.make_case(f"many{i}", N, K, 40, t, f, seed=20) for i, (N, f) in enumerate([(512, 0.5), (128, 1.0), (384, 0.0)])]
+    cases = [synth.make_case(f"many{i}", N, K, 300, t, f, seed=20) for i, (N, f) in enumerate([(512, 0.5), (128, 1.0), (384, 0.0)])]
     X = cases[0].X                       # shared input
     preps = [Prepared(c, dev) for c in cases]
     Xd = to_dev_bf16(X, dev)
-    for M, path in [(1, B.PATH_AUTO), (16, B.PATH_DECODE), (40, B.PATH_DECODE), (40, B.PATH_PREFILL)]:
+    for M, path in [(1, B.PATH_AUTO), (16, B.PATH_DECODE), (40, B.PATH_DECODE), (40, B.PATH_PREFILL), (300, B.PATH_AUTO)]:
         print(f"many M={M} path={path}", flush=True)
         Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
         B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=path)
@@ -305,6 +305,13 @@ def test_gemm_many_matches_single_calls(dev):
             torch.cuda.synchronize()
             assert torch.equal(Y, single), "fused launch differs from the single call"
             assert relF(Y.cpu().numpy(), p.oracle_gemm(X[:M])) <= TIGHT
+    # with a workspace the few output tiles of this set are better split: one split launch per weight
+    ws = torch.empty(8 * 40 * 512, device=dev, dtype=torch.float32)
+    Ys = [torch.full((40, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+    B.patch_gemm_many(Xd, 40, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, workspace=ws)
+    torch.cuda.synchronize()
+    for p, Y in zip(preps, Ys):
+        assert relF(Y.cpu().numpy(), p.oracle_gemm(X[:40])) <= TIGHT
     other = Prepared(synth.make_case("manyk", 128, 512, 4, t, 0.5, seed=21), dev)
     with pytest.raises(B.PatchError):   # K differs
         B.patch_gemm_many(Xd, 1, [preps[0].P, other.P],
