@@ -44,6 +44,7 @@ def _load():
         L = ctypes.CDLL(_LIB)
         i64, ci, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         L.patch_oracle_apply_mask.argtypes = [vp, vp, vp, i64, i64, ci, vp]
+        L.patch_oracle_hard_masks.argtypes = [vp, vp, i64, i64, ci, vp, vp]
         L.patch_oracle_packed_sizes.argtypes = [i64, i64, ci, vp, vp, vp]
         L.patch_oracle_pack.argtypes = [vp, i64, i64, vp, ci, vp, vp, vp]
         L.patch_oracle_unpack.argtypes = [vp, vp, i64, i64, vp, ci, vp]
@@ -88,6 +89,19 @@ def apply_mask(W, tile_map, mask24, t):
     if rc:
         raise OracleError(rc)
     return out
+
+
+def hard_masks(P_tile, P_24, N, K, t):
+    """-> (tile_map (N/t, K/t) uint8, mask24 (N, K) uint8) from the logits (Algorithm 1, hard masks)."""
+    pt = np.ascontiguousarray(P_tile, dtype=np.float32)
+    p24 = np.ascontiguousarray(P_24, dtype=np.float32)
+    assert pt.shape == (N // t, K // t) and p24.shape == (6, N * K // 4)
+    tm = np.empty((N // t, K // t), np.uint8)
+    m24 = np.empty((N, K), np.uint8)
+    rc = _load().patch_oracle_hard_masks(_p(pt), _p(p24), N, K, t, _p(tm), _p(m24))
+    if rc:
+        raise OracleError(rc)
+    return tm, m24
 
 
 def packed_sizes(N, K, t, tile_map):

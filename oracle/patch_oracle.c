@@ -77,6 +77,31 @@ int patch_oracle_apply_mask(const uint16_t* W, const uint8_t* tile_map, const ui
     return PO_OK;
 }
 
+/* Hard masks from the learned logits (Algorithm 1, first two lines after the training loop; Section 3,
+ * "Inference"; Section 2, "Learnable 2:4 Mask"):
+ *   tile_map[i] = 1[P_tile[i] > 0]            (a positive logit keeps the tile dense; the sparse class is the
+ *                                              concatenated zero logit, so 0 and NaN mean "2:4")
+ *   mask24      = for every group of four consecutive elements (row-major, along K) the candidate pattern with
+ *                 the largest of its six logits.  P_24 is 6 x (N K / 4), row c = logits of candidate c for all
+ *                 groups; the candidates are the rows of S: all 4-vectors with two ones, here in lexicographic
+ *                 order of the kept positions (0,1) (0,2) (0,3) (1,2) (1,3) (2,3).  Ties: the first candidate.
+ */
+int patch_oracle_hard_masks(const float* P_tile, const float* P_24, int64_t N, int64_t K, int t,
+                            uint8_t* tile_map, uint8_t* mask24) {
+    static const uint8_t S[6][4] = {{1, 1, 0, 0}, {1, 0, 1, 0}, {1, 0, 0, 1}, {0, 1, 1, 0}, {0, 1, 0, 1}, {0, 0, 1, 1}};
+    int rc = check_shape(N, K, t);
+    if (rc) return rc;
+    int64_t T = (N / t) * (K / t), G = N * K / 4;
+    for (int64_t i = 0; i < T; ++i) tile_map[i] = (P_tile[i] > 0.0f) ? 1 : 0;
+    for (int64_t g = 0; g < G; ++g) {
+        int best = 0;
+        for (int c = 1; c < 6; ++c)
+            if (P_24[c * G + g] > P_24[best * G + g]) best = c;
+        for (int j = 0; j < 4; ++j) mask24[4 * g + j] = S[best][j];
+    }
+    return PO_OK;
+}
+
 /* Element counts of the canonical arrays: values (uint16) and meta (bytes). */
 int patch_oracle_packed_sizes(int64_t N, int64_t K, int t, const uint8_t* tile_map,
                               int64_t* n_vals, int64_t* n_meta) {

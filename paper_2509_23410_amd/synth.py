@@ -122,6 +122,24 @@ CONFIGS = {
 }
 
 
+def mask_logits(seed: int, N: int, K: int, tile: int, *tags):
+    """Seeded stand-ins for learned mask logits: P_tile (N/tile, K/tile) and P_24 (6, N K / 4), fp32 N(0, 1), with a few
+    exact ties, zeros and NaNs planted so that the tie and sign rules are exercised."""
+    r = _rng(seed, "logits", N, K, tile, *tags)
+    pt = r.standard_normal((N // tile, K // tile)).astype(np.float32)
+    p24 = r.standard_normal((6, N * K // 4)).astype(np.float32)
+    G = p24.shape[1]
+    idx = r.integers(0, G, size=max(4, G // 50))
+    p24[2, idx] = p24[4, idx] = np.maximum(p24[:, idx].max(axis=0), 0) + 1.0      # a tie for the maximum
+    idx0 = r.integers(0, G, size=max(2, G // 200))
+    p24[:, idx0] = 0.0                                                              # all six equal
+    p24[r.integers(0, 6, size=3), r.integers(0, G, size=3)] = np.nan
+    flat = pt.reshape(-1)
+    flat[r.integers(0, flat.size, size=max(1, flat.size // 8))] = 0.0              # zero logit: the sparse class
+    flat[r.integers(0, flat.size)] = np.nan
+    return pt, p24
+
+
 def layer_fractions(seed: int, n_layers: int = 40) -> np.ndarray:
     """One 2:4-tile fraction per decoder layer, U[0, 1) (non-uniform allocation across layers)."""
     return _rng(seed, "layer_fractions", n_layers).random(n_layers)

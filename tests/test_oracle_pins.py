@@ -320,3 +320,47 @@ def test_tile_map_exact_count():
     assert int((synth.tile_map(0, 7, 7, 0.5) == 0).sum()) == 25       # round-half-up(24.5)
     assert int((synth.tile_map(0, 32, 32, 0.25) == 0).sum()) == 256
     assert int((synth.tile_map(0, 86, 32, 0.6) == 0).sum()) == 1651
+
+
+# ---------------------------------------------------------------- hard masks from logits (Algorithm 1)
+
+def test_hard_masks_hand_example(golden_dir):
+    """One row of 8 columns (two groups), one 4 x 4 tile grid of 1 x 2 ... by hand: group 0 has its largest logit on
+    candidate 3 = kept positions (1, 2); group 1 ties candidates 1 and 5 -> the first, (0, 2).  Candidates and their
+    order: the six 2-of-4 patterns of the golden file (Section 2, Learnable 2:4 Mask)."""
+    pats = [p["mask"] for p in json.load(open(os.path.join(golden_dir, "patterns_2of4.json")))["patterns"]]
+    assert sorted(pats) == sorted([list(m) for m in {(1, 1, 0, 0), (1, 0, 1, 0), (1, 0, 0, 1), (0, 1, 1, 0), (0, 1, 0, 1), (0, 0, 1, 1)}])
+    N, K, t = 4, 8, 4
+    p24 = np.full((6, N * K // 4), -1.0, np.float32)
+    p24[3, 0] = 2.0
+    p24[1, 1] = p24[5, 1] = 0.5
+    pt = np.array([[0.25, -0.25]], np.float32)
+    tm, m24 = oracle.hard_masks(pt, p24, N, K, t)
+    assert tm.tolist() == [[1, 0]]
+    assert m24[0].tolist() == pats[3] + pats[1] == [0, 1, 1, 0, 1, 0, 1, 0]
+    assert (m24[1:].reshape(-1, 4) == np.array(pats[0])).all()      # all equal -> candidate 0
+
+
+def test_hard_masks_against_numpy_argmax_and_invariants():
+    """Library special case: numpy's argmax (first maximum) over the six logits, without NaNs; sign rule on the tile
+    logits including the zero logit; every group keeps exactly two."""
+    N, K, t = 64, 128, 32
+    pt, p24 = synth.mask_logits(3, N, K, t)
+    tm, m24 = oracle.hard_masks(pt, p24, N, K, t)
+    assert ((m24.reshape(-1, 4).sum(axis=1)) == 2).all()
+    ok = ~np.isnan(p24).any(axis=0)
+    S = np.array([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]], np.uint8)
+    ref = S[np.argmax(p24[:, ok], axis=0)]
+    assert (m24.reshape(-1, 4)[ok] == ref).all()
+    assert ((pt > 0).astype(np.uint8) == tm).all() and tm[pt == 0].sum() == 0 and tm[np.isnan(pt)].sum() == 0
+    # feeding the hard masks into the mask merge keeps dense tiles whole and sparse tiles 2:4
+    c = synth.make_case("hm", N, K, 4, t, 0.5, seed=3)
+    W_hat = oracle.apply_mask(c.W, tm, m24, t)
+    for tn in range(N // t):
+        for tk in range(K // t):
+            blk = W_hat[tn * t:(tn + 1) * t, tk * t:(tk + 1) * t]
+            src = c.W[tn * t:(tn + 1) * t, tk * t:(tk + 1) * t]
+            if tm[tn, tk]:
+                assert (blk == src).all()
+            else:
+                assert (((blk & 0x7FFF) != 0).reshape(-1, 4).sum(axis=1) <= 2).all()
