@@ -66,6 +66,22 @@ typedef struct {
 } patch_gemm_opts;
 
 /*
+ * Hard masks from the learned logits (Algorithm 1, the two lines after the training loop; Section 3, "Inference";
+ * Section 2, "Learnable 2:4 Mask"):
+ *   tile_map[i] = 1[P_tile[i] > 0]   a positive logit keeps the tile dense; 0 and NaN give the 2:4 class
+ *   mask24      for every group of four consecutive elements (row-major, along K) the candidate pattern with the
+ *               largest of its six logits; ties: the first.  Candidates = the six 4-vectors with two ones, in
+ *               lexicographic order of the kept positions (0,1) (0,2) (0,3) (1,2) (1,3) (2,3).
+ *   P_tile   HOST, (N/tile) x (K/tile) fp32, row-major        tile_map  HOST out, same shape, bytes (for patch_pack)
+ *   P_24     DEVICE, 6 x (N K / 4) fp32, row c = logits of candidate c for all groups, 4-byte aligned
+ *   mask24   DEVICE out, N x K bytes, 1 = keep, 4-byte aligned (input of patch_apply_mask)
+ * tile_map is complete on return; mask24 is written asynchronously on `stream`.  Errors: PATCH_ERR_ARG,
+ * PATCH_ERR_SHAPE (as patch_apply_mask), PATCH_ERR_HIP.
+ */
+patch_status patch_hard_masks(const float* P_tile, const void* P_24, int64_t N, int64_t K, int tile, uint8_t* tile_map,
+                              void* mask24, void* stream);
+
+/*
  * Merge of the hard masks and pruning of the weights (Algorithm 1, last three lines; Eq. 4 with hard
  * masks):  M* = M_tile + (1 - M_tile) (.) M_24,  W_hat = W (.) M*.
  *   W      DEVICE, N x K bf16

@@ -18,7 +18,7 @@ OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
+    "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.patch_apply_mask.argtypes = [vp, vp, vp, i64, i64, ci, vp, vp]
         L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
+        L.patch_hard_masks.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
+        L.patch_hard_masks.restype = ci
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
         L.patch_tune.argtypes = [vp, i64, vp, vp, vp, sz, vp, ci, ctypes.POINTER(GemmOpts), ctypes.POINTER(ctypes.c_float)]
         L.patch_tune.restype = ci
@@ -190,6 +192,16 @@ def patch_tune(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, st
 def patch_gemm_workspace_bytes(M: int, P: Packed, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> int:
     o = GemmOpts(path, split_k, variant, None, 0)
     return int(lib().patch_gemm_workspace_bytes(M, P.handle, ctypes.byref(o)))
+
+
+def patch_hard_masks(P_tile, P_24, N: int, K: int, tile: int, mask24, stream: int = 0) -> np.ndarray:
+    """-> tile_map (N/tile, K/tile) uint8 on the host; mask24 (device, N x K bytes) is written on the stream."""
+    pt = np.ascontiguousarray(P_tile, dtype=np.float32)
+    if N > 0 and K > 0 and tile > 0 and N % tile == 0 and K % tile == 0 and pt.size != (N // tile) * (K // tile):
+        raise PatchError(ERR_ARG, "patch_hard_masks: P_tile has the wrong number of entries")
+    tm = np.empty(max(pt.size, 1), np.uint8)
+    _check(lib().patch_hard_masks(pt.ctypes.data, _ptr(P_24), N, K, tile, tm.ctypes.data, _ptr(mask24), stream), "patch_hard_masks")
+    return tm[: pt.size].reshape(pt.shape)
 
 
 def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0,

@@ -89,6 +89,19 @@ patch_status patch_apply_mask(const void* W, const void* mask24, const uint8_t* 
     return PATCH_OK;
 }
 
+patch_status patch_hard_masks(const float* P_tile, const void* P_24, int64_t N, int64_t K, int tile, uint8_t* tile_map,
+                              void* mask24, void* stream) {
+    if (!P_tile || !P_24 || !tile_map || !mask24) return PATCH_ERR_ARG;
+    patch_status st = check_shape(N, K, tile);
+    if (st != PATCH_OK) return st;
+    if ((reinterpret_cast<uintptr_t>(P_24) & 3u) || (reinterpret_cast<uintptr_t>(mask24) & 3u)) return PATCH_ERR_ARG;
+    const size_t T = (size_t)(N / tile) * (size_t)(K / tile);
+    for (size_t i = 0; i < T; ++i) tile_map[i] = (P_tile[i] > 0.0f) ? 1 : 0;   // NaN and 0: the 2:4 class
+    launch_hard_mask24(static_cast<const float*>(P_24), N * K / 4, static_cast<uint8_t*>(mask24), static_cast<hipStream_t>(stream));
+    HIP_TRY(hipGetLastError());
+    return PATCH_OK;
+}
+
 void patch_free(patch_packed* P) {
     if (!P) return;
     if (P->d_payload) (void)hipFree(P->d_payload);

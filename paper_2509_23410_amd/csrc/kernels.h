@@ -7,6 +7,8 @@ namespace patch {
 
 void launch_apply_mask(const uint16_t* W, const uint8_t* mask24, const uint8_t* d_tile_map, int64_t N, int64_t K, int tile,
                        uint16_t* W_hat, hipStream_t stream);
+// mask24 (N x K keep bytes, 4-byte aligned) from the 6 x G pattern logits, G = N K / 4 groups
+void launch_hard_mask24(const float* P24, int64_t G, uint8_t* mask24, hipStream_t stream);
 void launch_pack(const uint16_t* W, int64_t K, const uint32_t* d_table, int n_tiles, int Tk, int tile, uint8_t* payload, int* d_err,
                  hipStream_t stream);
 void launch_unpack(const uint8_t* payload, const uint32_t* d_table, int n_tiles, int Tk, int tile, int64_t K, uint16_t* W_out,

@@ -47,6 +47,33 @@ void launch_apply_mask(const uint16_t* W, const uint8_t* mask24, const uint8_t* 
     hipLaunchKernelGGL(apply_mask_kernel, dim3(blocks), dim3(256), 0, stream, W, mask24, d_tile_map, N, K, tile, W_hat);
 }
 
+// ------------------------------------------------------------------ hard 2:4 mask from the pattern logits
+// One thread per group of four consecutive elements: the candidate with the largest of the six logits (first one on
+// ties; a NaN never wins a comparison), written as four keep bytes.  Candidates in lexicographic order of the kept
+// positions: (0,1) (0,2) (0,3) (1,2) (1,3) (2,3).
+__global__ __launch_bounds__(256) void hard_mask24_kernel(const float* __restrict__ P24, int64_t G, uint32_t* __restrict__ mask24) {
+    // keep bytes of candidate c, little endian: byte j = element j of the group
+    constexpr uint32_t kPattern[6] = {0x00000101u, 0x00010001u, 0x01000001u, 0x00010100u, 0x01000100u, 0x01010000u};
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+        float best = P24[g];
+        uint32_t pat = kPattern[0];
+#pragma unroll
+        for (int c = 1; c < 6; ++c) {
+            const float v = P24[(int64_t)c * G + g];
+            const bool better = v > best;
+            best = better ? v : best;
+            pat = better ? kPattern[c] : pat;
+        }
+        mask24[g] = pat;
+    }
+}
+
+void launch_hard_mask24(const float* P24, int64_t G, uint8_t* mask24, hipStream_t stream) {
+    int blocks = (int)((G + 255) / 256);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(hard_mask24_kernel, dim3(blocks), dim3(256), 0, stream, P24, G, reinterpret_cast<uint32_t*>(mask24));
+}
+
 // ------------------------------------------------------------------ compression
 __device__ __forceinline__ bool bf16_nonzero(uint16_t h) { return (h & 0x7FFFu) != 0; }
 

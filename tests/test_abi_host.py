@@ -52,6 +52,9 @@ def test_argument_errors_without_device():
     assert L.patch_gemm_many(fake, 1, two, two, 9, 0, None) == B.ERR_ARG
     assert L.patch_gemm(0, 1, fake, fake, 0) == B.ERR_ARG
     assert L.patch_apply_mask(fake, fake, tm.ctypes.data, 128, 128, 48, fake, 0) == B.ERR_SHAPE
+    assert L.patch_hard_masks(None, fake, 128, 128, 64, tm.ctypes.data, fake, 0) == B.ERR_ARG
+    assert L.patch_hard_masks(fake, fake, 128, 100, 64, tm.ctypes.data, fake, 0) == B.ERR_SHAPE
+    assert L.patch_hard_masks(fake, fake + 2, 128, 128, 64, tm.ctypes.data, fake, 0) == B.ERR_ARG
     assert L.patch_unpack(0, fake, 0) == B.ERR_ARG
     assert L.patch_packed_bytes(0) == 0
     assert L.patch_gemm_workspace_bytes(256, 0, None) == 0

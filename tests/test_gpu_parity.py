@@ -95,6 +95,28 @@ def test_mask_merge_pack_unpack_bit_exact(dev, name, N, K, t, f):
     p.P.close()
 
 
+@pytest.mark.parametrize("N,K,t", [(128, 256, 64), (384, 640, 128), (64, 64, 64)])
+def test_hard_masks_bit_exact_and_feed_the_pipeline(dev, N, K, t):
+    """patch_hard_masks against the oracle, byte for byte, on logits with planted ties, zeros and NaNs; then the whole
+    front end on both sides: logits -> hard masks -> mask merge -> pack, compared in canonical form."""
+    pt, p24 = synth.mask_logits(5, N, K, t)
+    tm_o, m24_o = oracle.hard_masks(pt, p24, N, K, t)
+    m24 = torch.full((N, K), 7, device=dev, dtype=torch.uint8)
+    tm = B.patch_hard_masks(pt, torch.from_numpy(p24).to(dev), N, K, t, m24, stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(tm, tm_o)
+    assert np.array_equal(m24.cpu().numpy(), m24_o)
+    c = synth.make_case("hardmask", N, K, 4, t, 0.5, seed=5)
+    W = to_dev_bf16(c.W, dev)
+    W_hat = torch.empty_like(W)
+    B.patch_apply_mask(W, m24, tm, N, K, t, W_hat, stream())
+    P = B.patch_pack(W_hat, N, K, tm, t, stream())
+    vals, meta = B.patch_export_canonical(P)
+    vo, mo = oracle.pack(oracle.apply_mask(c.W, tm_o, m24_o, t), tm_o, t)
+    assert np.array_equal(vals, vo) and np.array_equal(meta[: mo.size], mo)
+    P.close()
+
+
 def test_pack_special_values_and_padding_rule(dev):
     """Zeros, negative zeros, NaN, Inf, denormals; groups with 0 or 1 nonzeros exercise the padding rule."""
     c = synth.make_case("special", 256, 256, 1, 64, 0.6, seed=2)
