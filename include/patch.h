@@ -40,9 +40,10 @@ typedef enum {
     PATCH_ERR_SIZE = 6    /* a caller-provided host buffer is too small                              */
 } patch_status;
 
-/* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of 16 rows, PREFILL in 256-row
- * tiles.  AUTO (measured crossovers): without a workspace decode for M <= 128, prefill above; with a workspace for
- * at least two slices (see patch_gemm_opts) decode for M <= 16, and for M <= 32 if the weight is below 64 MB. */
+/* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
+ * once per pass), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a workspace
+ * for at least two slices (see patch_gemm_opts) up to M = 48 for weights below 64 MB and M = 24 above, without one up
+ * to M = 192 and M = 64; prefill beyond. */
 typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
 
 /* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and
@@ -121,7 +122,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
  * Schedule autotuner (Appendix A leaves tile shape and schedule - e.g. split-K - to an autotuner run per layer
  * and input shape, decode first).  Times the candidate schedules of patch_gemm_ex for this M and P on the device,
  * on real operands, and returns the fastest.  Candidates: both paths where they apply (decode passes up to
- * M = 128), the kernel variants of the path, and for prefill the K-split counts the workspace allows.
+ * M = 256), the kernel variants of the path, and for prefill the K-split counts the workspace allows.
  *   X, Y       as for patch_gemm (Y is overwritten several times; on return it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1

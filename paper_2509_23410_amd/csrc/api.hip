@@ -182,17 +182,19 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     return PATCH_OK;
 }
 
-// Measured crossover between 16-row decode passes (every pass streams the whole weight) and the 256 x 256-tile
-// prefill kernel.  Unsplit, the prefill grid is too small to fill the chip at small M and loses up to M = 128.
-// With a workspace the prefill launch splits K over the idle compute units and costs about 20 us + the weight
-// stream, which two decode passes only beat on small weights (4096 x 4096: 16 vs 20 us at M = 32).
+// Measured crossovers between decode passes (up to 64 rows each; every pass streams the whole weight) and the
+// 256 x 256-tile prefill kernel.  Unsplit, the prefill grid is too small to fill the chip at small M.  With a
+// workspace the prefill launch splits K over the idle compute units and costs about 20 us + the weight stream:
+//   4096 x 4096 (34 MB): decode 12 / 18 / 20 / 41 / 83 us at M = 32 / 48 / 64 / 128 / 256, split prefill 20 / 21 /
+//   21 / 24 / 30 us, unsplit prefill 66 - 71 us;  13824 x 5120 (113 MB at f = 0.5): decode 32 / 46 / 94 / 188 us
+//   at M = 17 / 32 / 64 / 128, split prefill 34 / 35 / 38 / 42 us, unsplit prefill about 93 us.
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
     const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float) &&
                     P->tile == 128;
-    if (!ws) return (M <= 128) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    const bool small = P->payload_bytes < ((size_t)64 << 20);
     if (M <= 16) return PATCH_PATH_DECODE;
-    if (M <= 32 && P->payload_bytes < ((size_t)64 << 20)) return PATCH_PATH_DECODE;
-    return PATCH_PATH_PREFILL;
+    if (ws) return M <= (small ? 48 : 24) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    return M <= (small ? 192 : 64) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
 }
 
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream, const patch_gemm_opts* opts) {
@@ -213,8 +215,8 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.n_cus = P->n_cus;
     if (opts && opts->workspace) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_DECODE) {
-        for (int64_t m0 = 0; m0 < M; m0 += 16) {
-            const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
+        for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
+            const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
             launch_decode(a, m0, rows, split_k, variant, s);
         }
     } else {
@@ -233,7 +235,7 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
     auto add = [&](int path, int split_k, int variant, bool ws) {
         cand.push_back(patch_gemm_opts{path, split_k, variant, ws ? workspace : nullptr, ws ? workspace_bytes : 0});
     };
-    if (M <= 128) {  // every 16-row pass streams the whole weight again: no contender beyond that
+    if (M <= 256) {  // every pass of 64 rows streams the whole weight again: no contender beyond that
         add(PATCH_PATH_DECODE, 0, 0, false);
         add(PATCH_PATH_DECODE, 0, 2, false);
         add(PATCH_PATH_DECODE, 0, 3, false);
@@ -356,8 +358,8 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     }
     set.count = count;
     set.units = strips;
-    for (int64_t m0 = 0; m0 < M; m0 += 16) {
-        const int rows = (int)((M - m0 < 16) ? M - m0 : 16);
+    for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
+        const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
         launch_decode_set(a, set, m0, rows, split_k, variant, s);
     }
     HIP_TRY(hipGetLastError());

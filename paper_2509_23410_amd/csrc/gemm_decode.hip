@@ -35,11 +35,12 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-template <int TILE, int NK, int MAXW>
+// RB = blocks of 16 rows of X per launch (1, 2 or 4): the weights are streamed once for up to 64 rows.
+template <int TILE, int NK, int MAXW, int RB>
 __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
                                                            const DecodeSet set) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
-    __shared__ f32x4 red[MAXW][64];
+    __shared__ f32x4 red[MAXW][RB][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
     const int strip = (int)blockIdx.x - __builtin_amdgcn_readfirstlane(first);
     const int tn = strip / SPT, s = strip % SPT;
     const int col = lane & 15, q = lane >> 4;
-    const bool xvalid = col < rows;
+    const bool xvalid = col < rows;   // row block 0; block rb holds rows 16 rb + col
     const uint32_t* trow = table + (int64_t)tn * Tk;
     const int total = Tk * KPT;
     // per-lane byte offsets, fixed for the whole kernel; every address below is a scalar base plus one of these
@@ -79,7 +80,18 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
     // lanes whose column is a row of X; the other lanes never load X and never store
     const uint64_t xmask = __builtin_amdgcn_ballot_w64(xvalid);
 
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    // the same for the further row blocks (RB > 1)
+    uint32_t voffx_r[RB];
+    uint64_t xmask_r[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const bool v = 16 * rb + col < rows;
+        voffx_r[rb] = (uint32_t)(((v ? 16 * rb + col : 0) * K + 8 * q) * 2);
+        xmask_r[rb] = __builtin_amdgcn_ballot_w64(v);
+    }
+    f32x4 acc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int base = w * NK; base < total; base += KW * NK) {
         const int n = (total - base < NK) ? total - base : NK;
         uint32_t ent[NK];
@@ -100,7 +112,7 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         // the step does not need (second half of a 2:4 step, positions of a dense step, anything past the end of
         // K, X for a lane without a row) is issued with an empty EXEC mask: it moves no data and leaves the zero
         // its destination was initialised with.
-        u32x4 a[NK][2], b[NK][2];
+        u32x4 a[NK][2], b[NK][RB][2];
         uint32_t idx[NK];
 #pragma unroll
         for (int g = 0; g < NK; ++g) {
@@ -146,55 +158,86 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
             a[g][0] = v0;
             a[g][1] = v1;
             idx[g] = vi;
-            b[g][0] = x0;
-            b[g][1] = x1;
+            b[g][0][0] = x0;
+            b[g][0][1] = x1;
+            // X of the further row blocks: same step, same scalar base, the block's own lanes and rows
+#pragma unroll
+            for (int rb = 1; rb < RB; ++rb) {
+                u32x4 y0 = {0u, 0u, 0u, 0u}, y1 = {0u, 0u, 0u, 0u};
+                asm volatile(
+                    "s_mov_b64 %[sv], exec\n\t"
+                    "s_cmp_lg_u32 %[kind], 0\n\t"
+                    "s_cselect_b64 exec, %[xm], 0\n\t"
+                    "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"
+                    "global_load_dwordx4 %[x1], %[vx], %[sbx] offset:64\n\t"
+                    "s_mov_b64 exec, %[sv]"
+                    : [x0] "+v"(y0), [x1] "+v"(y1), [sv] "=&s"(saved)
+                    : [vx] "v"(voffx_r[rb]), [sbx] "s"(sbx), [kind] "s"(kind), [xm] "s"(xmask_r[rb])
+                    : "memory", "scc");
+                b[g][rb][0] = y0;
+                b[g][rb][1] = y1;
+            }
         }
         // ---- wait for the loads (the compiler does not know about them), then tie every destination to this
         // point so that no use can be scheduled above the wait
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int g = 0; g < NK; ++g)
-            asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(idx[g]), "+v"(b[g][0]), "+v"(b[g][1]));
+        {
+            asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(idx[g]));
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(b[g][rb][0]), "+v"(b[g][rb][1]));
+        }
 
 #pragma unroll
         for (int g = 0; g < NK; ++g) {
-            BFrag bb;
-            bb.raw[0] = b[g][0];
-            bb.raw[1] = b[g][1];
             AFrag a0, a1;
             a0.raw = a[g][0];
             a1.raw = a[g][1];
             if (g < n) {
-                if (entry_sparse(ent[g])) {
-                    // two steps per tile: the even step's dword holds both position words
-                    const uint32_t pos = (KPT == 2 && (g & 1)) ? (idx[g - 1] >> 16) : idx[g];
-                    acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0.v, bb.v, acc, (int)pos, 0, 0);
-                } else {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, bb.h[0], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, bb.h[1], acc, 0, 0, 0);
+                // two steps per tile: the even step's dword holds both position words
+                const uint32_t pos = (KPT == 2 && (g & 1)) ? (idx[g - 1] >> 16) : idx[g];
+                const bool sp = entry_sparse(ent[g]);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    BFrag bb;
+                    bb.raw[0] = b[g][rb][0];
+                    bb.raw[1] = b[g][rb][1];
+                    if (sp) {
+                        acc[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0.v, bb.v, acc[rb], (int)pos, 0, 0);
+                    } else {
+                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, bb.h[0], acc[rb], 0, 0, 0);
+                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, bb.h[1], acc[rb], 0, 0, 0);
+                    }
                 }
             }
         }
     }
 
-    // fixed-order reduction of the partials; acc[r] = Y^T[strip*16 + 4 q + r][col]
-    red[w][lane] = acc;
+    // fixed-order reduction of the partials; acc[rb][r] = Y^T[strip*16 + 4 q + r][16 rb + col]
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) red[w][rb][lane] = acc[rb];
     __syncthreads();
     if (w == 0) {
-        f32x4 sum = red[0][lane];
-        for (int i = 1; i < KW; ++i) {
-            const f32x4 v = red[i][lane];
-            sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            f32x4 sum = red[0][rb][lane];
+            for (int i = 1; i < KW; ++i) {
+                const f32x4 v = red[i][rb][lane];
+                sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+            }
+            if (16 * rb + col < rows) *reinterpret_cast<f32x4*>(Y + (m0 + 16 * rb + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
         }
-        if (xvalid) *reinterpret_cast<f32x4*>(Y + (m0 + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
     }
 }
 
 template <int TILE>
 static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
     dim3 grid((unsigned)set.units), block((unsigned)(kw * 64));
-    if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    if (rows > 32) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 4>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    else if (rows > 16) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 2>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    else if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
 }
 
 // Schedule: NK = 64-column steps per wavefront and pass (8 or 4), KW = wavefronts per workgroup.
@@ -223,7 +266,8 @@ int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int r
         if (kw8 > 8) kw8 = 8;
         nk = (strips * kw8 >= (int64_t)a.n_cus * 4) ? 8 : 4;
     }
-    const int maxw = (nk == 4) ? 16 : 8;
+    if (rows > 16) nk = 4;   // 17 .. 64 rows: 4 steps and 8 wavefronts (registers hold X for up to four row blocks)
+    const int maxw = (nk == 4 && rows <= 16) ? 16 : 8;
     int kw = split_k > 0 ? split_k : (total + nk - 1) / nk;
     if (kw > maxw) kw = maxw;
     if (kw < 1) kw = 1;

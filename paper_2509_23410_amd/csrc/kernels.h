@@ -41,7 +41,9 @@ struct WeightSet {
 };
 typedef WeightSet DecodeSet;
 
-// M <= 16 rows of X starting at row m0 (decode shape).  split_k = K slices (wavefronts) per workgroup,
+// Up to kDecodeRows rows of X starting at row m0 (decode shape; 16-row blocks, the weights streamed once per launch).
+constexpr int kDecodeRows = 64;
+//  split_k = K slices (wavefronts) per workgroup,
 // 0 picks a default.  Returns the number used.
 int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
 // The same for a set of weights; a supplies X, K, tile, Tk, n_cus (its payload / table / Y / N are ignored).

@@ -301,11 +301,19 @@ def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
     p = Prepared(c, dev)
-    for M in (17, 100, 128, 129, 256, 257, 300):
+    for M in (17, 31, 32, 33, 48, 64, 65, 100, 128, 129, 256, 257, 300):
         Yo = p.oracle_gemm(c.X[:M])
         for path in (B.PATH_AUTO, B.PATH_DECODE, B.PATH_PREFILL):
             print(f"mid M={M} path={path}", flush=True)
             assert relF(p.gemm(c.X[:M], path=path), Yo) <= TIGHT
+    p.P.close()
+    # decode passes of up to 64 rows (1, 2 or 4 blocks of 16) on tile 64 and with forced wavefront counts
+    c = synth.make_case("mid64", 192, 640, 70, 64, 0.5, seed=9)
+    p = Prepared(c, dev)
+    for M in (20, 40, 64, 70):
+        Yo = p.oracle_gemm(c.X[:M])
+        for sk in (0, 1, 3, 8):
+            assert relF(p.gemm(c.X[:M], path=B.PATH_DECODE, split_k=sk), Yo) <= TIGHT
     p.P.close()
 
 
