@@ -372,8 +372,9 @@ def test_prefill_split_k(dev):
         assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5, workspace=small), Yo) <= TIGHT
         assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5), Yo) <= TIGHT   # none: unsplit
     assert B.patch_gemm_workspace_bytes(1, p.P) == 0            # decode path
-    assert B.patch_gemm_workspace_bytes(40, p.P) > 0            # auto: prefill, split, once a workspace is there
-    assert relF(p.gemm(c.X[:40], workspace=ws), p.oracle_gemm(c.X[:40])) <= TIGHT
+    assert B.patch_gemm_workspace_bytes(40, p.P) == 0           # auto: still decode at this M for a small weight
+    assert B.patch_gemm_workspace_bytes(100, p.P) > 0           # auto: prefill, split, once a workspace is there
+    assert relF(p.gemm(c.X[:100], workspace=ws), p.oracle_gemm(c.X[:100])) <= TIGHT
     p.P.close()
 
 
