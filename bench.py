@@ -234,6 +234,27 @@ def main():
             for P_ in Ps:
                 P_.close()
             del W_hat
+        # the MLP projections of the same model at M = 1 (two thirds of a decoder layer's weight bytes)
+        mlp = []
+        for name, N_, K_ in (("gate", 11008, 4096), ("down", 4096, 11008)):
+            for fd in (0.0, 0.5):
+                cm = synth.make_case("llama7b_mlp_dec_" + name, N_, K_, 1, t, fd, seed=0)
+                W_hat, P0 = masked_packed(cm)
+                Rm = max(2, int(np.ceil(1.1e9 / P0.nbytes)))
+                Pm = [P0] + [B.patch_pack(W_hat, N_, K_, cm.tile_map, t, stream) for _ in range(Rm - 1)]
+                Xm = dev_bf16(cm.X)
+                Ym = torch.empty((1, N_), device=dev, dtype=torch.float32)
+                fn = lambda i: B.patch_gemm(Xm, 1, Pm[i % Rm], Ym, stream)
+                timed(fn, 20)
+                nl = max(1, args.decode_launches // 2)
+                us = sorted(timed(fn, nl) / nl for _ in range(5))[2] * 1e6
+                gbs = P0.nbytes / (us * 1e-6) / 1e9
+                mlp.append(dict(shape=[N_, K_], f=fd, M=1, us=round(us, 3), GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4),
+                                packed_MB=round(P0.nbytes / 1e6, 3), copies=Rm))
+                for P_ in Pm:
+                    P_.close()
+                del W_hat
+        out["decode_mlp"] = dict(rows=mlp, note="7B MLP projections, M = 1, rotating packed copies")
         m1 = [r_ for r_ in dec if r_["M"] == 1 and r_["f"] == 0.0][0]
         out["decode_roofline"] = dict(bound="hbm", achieved=m1["GBps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=m1["frac_hbm"],
                                       traffic=None, kernel="decode_kernel", workload="4096x4096 f=0 M=1",

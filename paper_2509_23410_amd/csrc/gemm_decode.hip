@@ -242,7 +242,13 @@ static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0,
 
 // Schedule: NK = 64-column steps per wavefront and pass (8 or 4), KW = wavefronts per workgroup.
 // split_k > 0 forces KW; variant 2 / 3 forces NK = 8 / 4.
-// Default: NK = 8 if that still leaves about four wavefronts per compute unit, else 4.
+// Default (measured, M = 1):
+//   two or more workgroups per compute unit (N >= 8192): NK = 8, KW = 4 - three small workgroups share a compute unit
+//     and overlap one's reduction and exit with the others' loads (11008 x 4096: 17.6 vs 19.9 us; 13824 x 5120:
+//     25.8 vs 26.9 us);
+//   about one workgroup per compute unit and a long K (>= 128 steps): NK = 4, KW = 16 - more, shorter passes per
+//     wavefront (4096 x 11008: 16.3 vs 17.7 us);
+//   else NK = 8 if that still leaves about four wavefronts per compute unit, else 4.
 int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int variant, hipStream_t stream) {
     DecodeSet set = {};
     set.payload[0] = a.payload;
@@ -261,6 +267,11 @@ int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int r
     if (variant == 2) nk = 8;
     else if (variant == 3) nk = 4;
     if (nk == 0 && split_k > 0) nk = ((total + split_k - 1) / split_k > 4) ? 8 : 4;
+    int kw_default = 0;
+    if (nk == 0 && rows <= 16) {
+        if (strips >= 2 * (int64_t)a.n_cus) { nk = 8; kw_default = 4; }
+        else if (total >= 128) nk = 4;
+    }
     if (nk == 0) {
         int kw8 = (total + 7) / 8;
         if (kw8 > 8) kw8 = 8;
@@ -268,7 +279,7 @@ int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int r
     }
     if (rows > 16) nk = 4;   // 17 .. 64 rows: 4 steps and 8 wavefronts (registers hold X for up to four row blocks)
     const int maxw = (nk == 4 && rows <= 16) ? 16 : 8;
-    int kw = split_k > 0 ? split_k : (total + nk - 1) / nk;
+    int kw = split_k > 0 ? split_k : kw_default > 0 ? kw_default : (total + nk - 1) / nk;
     if (kw > maxw) kw = maxw;
     if (kw < 1) kw = 1;
     if (a.tile == 128) launch_decode_t<128>(a, set, m0, rows, nk, kw, stream);

@@ -395,13 +395,13 @@ def test_tune_returns_a_valid_fast_schedule(dev):
         assert relF(Y.cpu().numpy(), Yo) <= TIGHT               # Y holds the chosen schedule's product
         assert relF(p.gemm(c.X[:M], workspace=w, **opts), Yo) <= TIGHT
     p.P.close()
-    c64 = synth.make_case("tune64", 256, 512, 150, 64, 0.5, seed=15)   # tile 64: one prefill candidate
+    c64 = synth.make_case("tune64", 256, 512, 150, 64, 0.5, seed=15)   # tile 64: decode passes or the simple prefill kernel
     p64 = Prepared(c64, dev)
     X = to_dev_bf16(c64.X, dev)
     Y = torch.empty((150, 256), device=dev, dtype=torch.float32)
     opts, us = B.patch_tune(X, 150, p64.P, Y, stream=stream(), reps=3)
     torch.cuda.synchronize()
-    assert opts["path"] == B.PATH_PREFILL and relF(Y.cpu().numpy(), p64.oracle_gemm(c64.X)) <= TIGHT
+    assert opts["path"] in (B.PATH_DECODE, B.PATH_PREFILL) and relF(Y.cpu().numpy(), p64.oracle_gemm(c64.X)) <= TIGHT
     p64.P.close()
 
 
