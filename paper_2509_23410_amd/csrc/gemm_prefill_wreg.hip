@@ -455,8 +455,9 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_STEP(SS, AB, ABN, J)                                                                              \
     {                                                                                                              \
         const int s = 6 * it + SS;                                                                                 \
-        if (s >= S) break;                                                                                         \
-        const StepVars cu = nx;                                                                                    \
+        if ((SS & 1) == 0 && s >= S) break; /* S is even */                                                        \
+        StepVars& cu = (SS & 1) ? sv1 : sv0; /* this step's variables; the next step's go to the other set */    \
+        StepVars& nx = (SS & 1) ? sv0 : sv1;                                                                       \
         /* A(s) has landed: the loads issued after it are X(s+1), A(s+1), X(s+2) */                                \
         asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
         if (cu.sparse) {                                                                                           \
@@ -479,7 +480,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_SPARSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 5) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 1, PATCH_WR_OFF_##CB); }
 
     // a round = six steps = three tiles: step buffer = step % 3 and K-step = step % 2 are then compile-time constants
-    StepVars nx = step_vars(0, ec[0], ec[1]);
+    StepVars sv0 = step_vars(0, ec[0], ec[1]), sv1 = sv0;
     for (int it = 0;; ++it) {
         const uint32_t en[3] = {entry(3 * it + 3), entry(3 * it + 4), entry(3 * it + 5)};  // next round's tiles
         PATCH_WR_STEP(0, 0, 2, 0)
