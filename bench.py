@@ -38,11 +38,11 @@ PAPER_CONTEXT = "paper: 1.18x-1.38x end-to-end LLaMA-2 7B speedup on an A6000 at
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -162,6 +162,30 @@ def main():
         torch.cuda.synchronize()
         out["pack"] = dict(shape=[c.N, c.K], ms=(time.time() - tp) / 3 * 1e3,
                            note="patch_pack wall time incl. allocation and the status read-back")
+
+    # ------------------------------------------------------------------ prefill time against the 2:4 tile fraction (gate projection)
+    if "sweep" not in skip:
+        c0 = layers[0]["c"]
+        fr = (0.0, 0.25, 0.5, 0.75, 1.0)
+        Pf = []
+        for ff in fr:
+            cf = synth.make_case("llama7b_mlp_gate", c0.N, c0.K, M, t, ff, seed=0)
+            W_hat_f, P_f = masked_packed(cf)
+            Pf.append(P_f)
+            del W_hat_f
+        Xf, Yf = layers[0]["X"], layers[0]["Y"]
+        us = [[] for _ in fr]
+        for _r in range(3):   # the fractions in turn, three rounds: the clock drifts by a few per cent over a run
+            for i, P_f in enumerate(Pf):
+                fn = lambda _i, P_f=P_f: B.patch_gemm(Xf, M, P_f, Yf, stream, **opts)
+                timed(fn, 3)
+                us[i].append(timed(fn, 10) / 10 * 1e6)
+        med = [sorted(u)[1] for u in us]
+        out["prefill_f_sweep"] = dict(shape=[c0.N, c0.K], M=M, f=list(fr), us=[round(u, 1) for u in med],
+                                      speedup_over_all_dense=[round(med[0] / u, 3) for u in med],
+                                      note="median of three interleaved rounds of 10 launches each")
+        for P_f in Pf:
+            P_f.close()
 
     # ------------------------------------------------------------------ mid M: 13B layer shapes at M = 512, 7B MLP at M = 2048
     if "mid" not in skip:
