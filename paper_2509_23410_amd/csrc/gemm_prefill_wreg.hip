@@ -148,12 +148,12 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
     asm volatile("s_waitcnt lgkmcnt(12)\n\t"                                                                        \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
                  "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
-                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
                  "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:" #OFF "\n\t"                                  \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
+                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
                  PATCH_WR_LD_##CB(2, ABN, J)                                                                       \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
                  PATCH_WR_LD_##CB(3, ABN, J)                                                                       \
+                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
                  PATCH_WR_LD_##CB(4, ABN, J)                                                                       \
                  "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J          \
                  PATCH_WR_PIECE_OPS                                                                                \
