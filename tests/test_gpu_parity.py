@@ -428,3 +428,29 @@ def test_prefill_kernel_variants(dev, variant):
             assert np.isfinite(Y).all(), "unwritten outputs"
             assert relF(Y, p.oracle_gemm(c.X[:M])) <= TIGHT
         p.P.close()
+
+
+def test_random_shapes_and_schedules(dev):
+    """Seeded sweep: random (N, K, M, tile, f) within the ABI's limits, every path and kernel variant, with and
+    without a workspace and a forced K split; every result against the oracle."""
+    rng = np.random.default_rng(2024)
+    ws = torch.empty(16 << 20, device=dev, dtype=torch.float32)
+    for case in range(24):
+        t = int(rng.choice([64, 128]))
+        N = t * int(rng.integers(1, 7))
+        K = t * int(rng.integers(1, 9))
+        M = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 130, 255, 256, 257, 400]))
+        f = float(rng.choice([0.0, 0.3, 0.5, 1.0]))
+        c = synth.make_case("rnd%d" % case, N, K, M, t, f, seed=100 + case)
+        p = Prepared(c, dev)
+        Yo = p.oracle_gemm(c.X)
+        scheds = [dict(), dict(path=B.PATH_DECODE), dict(path=B.PATH_PREFILL), dict(path=B.PATH_PREFILL, variant=1 if t == 64 else 2),
+                  dict(workspace=ws), dict(path=B.PATH_PREFILL, workspace=ws, split_k=int(rng.integers(2, 5))),
+                  dict(path=B.PATH_DECODE, split_k=int(rng.integers(1, 9)))]
+        for kw in scheds:
+            print(f"random case {case}: N={N} K={K} M={M} tile={t} f={f} " + str({k: v for k, v in kw.items() if k != 'workspace'})
+                  + (" +workspace" if "workspace" in kw else ""), flush=True)
+            Y = p.gemm(c.X, **kw)
+            assert np.isfinite(Y).all(), "unwritten outputs"
+            assert relF(Y, Yo) <= TIGHT, (case, kw.get("path"), kw.get("variant"), kw.get("split_k"))
+        p.P.close()
