@@ -109,7 +109,8 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
 /*
  * The product (Section 4; Appendix A decode input BS x K and prefill input BS*SL x K):
  *   Y[m, n] = sum_k X[m, k] * W_hat[n, k],   bf16 x bf16 products accumulated in fp32.
- *   X  DEVICE, M x K bf16;  Y  DEVICE, M x N fp32;  M >= 1 arbitrary.
+ *   X  DEVICE, M x K bf16;  Y  DEVICE, M x N fp32;  M >= 0 arbitrary (M = 0: PATCH_OK, nothing is launched;
+ *   the pointers must still be non-null and aligned).
  * Asynchronous on `stream`; allocates nothing and never synchronises.  A patch_packed is read-only for
  * patch_gemm, so concurrent calls on different streams are allowed as long as their Y buffers differ.
  * Results are bit-reproducible from call to call (fixed reduction order, no atomics).

@@ -198,12 +198,13 @@ static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* op
 }
 
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream, const patch_gemm_opts* opts) {
-    if (!X || !P || !Y || M <= 0) return PATCH_ERR_ARG;
+    if (!X || !P || !Y || M < 0) return PATCH_ERR_ARG;
     if (!aligned16(X) || !aligned16(Y)) return PATCH_ERR_ARG;
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
     if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
+    if (M == 0) return PATCH_OK;  // an empty batch: nothing to launch, Y has no rows
     if (path == PATCH_PATH_AUTO) path = auto_path(M, P, opts);
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a;
@@ -298,7 +299,7 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
 
 patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count, void* stream,
                              const patch_gemm_opts* opts) {
-    if (!X || !P || !Y || M <= 0 || count < 1 || count > PATCH_MAX_MANY) return PATCH_ERR_ARG;
+    if (!X || !P || !Y || M < 0 || count < 1 || count > PATCH_MAX_MANY) return PATCH_ERR_ARG;
     static_assert(PATCH_MAX_MANY == kMaxMany, "header and kernels disagree");
     if (!aligned16(X)) return PATCH_ERR_ARG;
     for (int i = 0; i < count; ++i) {
@@ -308,6 +309,7 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
+    if (M == 0) return PATCH_OK;
     if (path == PATCH_PATH_AUTO) path = auto_path(M, P[0], opts);
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a = {};

@@ -454,3 +454,19 @@ def test_random_shapes_and_schedules(dev):
             assert np.isfinite(Y).all(), "unwritten outputs"
             assert relF(Y, Yo) <= TIGHT, (case, kw.get("path"), kw.get("variant"), kw.get("split_k"))
         p.P.close()
+
+
+def test_empty_batch_is_a_no_op(dev):
+    """M = 0: PATCH_OK, nothing launched, Y untouched; a negative M is an argument error."""
+    c = synth.make_case("empty", 256, 256, 4, 128, 0.5, seed=3)
+    p = Prepared(c, dev)
+    X = to_dev_bf16(c.X, dev)
+    Y = torch.full((4, c.N), 7.0, device=dev, dtype=torch.float32)
+    for path in (B.PATH_AUTO, B.PATH_DECODE, B.PATH_PREFILL):
+        B.patch_gemm(X, 0, p.P, Y, stream(), path=path)
+    B.patch_gemm_many(X, 0, [p.P, p.P], [Y, Y], stream())
+    torch.cuda.synchronize()
+    assert bool((Y == 7.0).all())
+    with pytest.raises(B.PatchError):
+        B.patch_gemm(X, -1, p.P, Y, stream())
+    p.P.close()
