@@ -191,7 +191,8 @@ def main():
     if "mid" not in skip:
         rows = []
         for name, N_, K_, Mm in (("13b_attn", 5120, 5120, 512), ("13b_gate", 13824, 5120, 512), ("13b_down", 5120, 13824, 512),
-                                 ("7b_gate", 11008, 4096, 2048), ("7b_attn", 4096, 4096, 64), ("7b_attn", 4096, 4096, 256)):
+                                 ("7b_gate", 11008, 4096, 2048), ("7b_attn", 4096, 4096, 32), ("7b_attn", 4096, 4096, 64), ("7b_attn", 4096, 4096, 256),
+                                 ("13b_gate", 13824, 5120, 32), ("13b_gate", 13824, 5120, 64), ("13b_down", 5120, 13824, 64)):
             cm = synth.make_case("mid_" + name, N_, K_, Mm, t, 0.5, seed=0)
             W_hat, Pm = masked_packed(cm)
             Xm = dev_bf16(cm.X)
@@ -208,8 +209,9 @@ def main():
                              dense_equiv_TFLOPs=round(2.0 * Mm * N_ * K_ / res["with_workspace"] / 1e6, 1)))
             Pm.close()
             del W_hat, Xm, Ym, ws
-        out["mid_m"] = dict(rows=rows, note="patch_gemm, automatic path; with a workspace the prefill launch splits K over "
-                                            "otherwise idle compute units (partials summed in slice order)")
+        out["mid_m"] = dict(rows=rows, note="patch_gemm, automatic path; with a workspace the launch splits K over otherwise idle "
+                                            "compute units (partials summed in slice order): M <= 64 one decode-path pass with 64 "
+                                            "features per wavefront, beyond that the prefill kernel")
 
     # ------------------------------------------------------------------ decode: 7B attention projection
     if "decode" not in skip:

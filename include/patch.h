@@ -41,9 +41,11 @@ typedef enum {
 } patch_status;
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
- * once per pass), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a workspace
- * for at least two slices (see patch_gemm_opts) up to M = 48 for weights below 64 MB and M = 24 above, without one up
- * to M = 192 and M = 64; prefill beyond. */
+ * once per pass: 16-feature strips per workgroup for up to 16 rows, 64 features per wavefront for 17 .. 64 rows where
+ * that fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a
+ * workspace for at least two slices (see patch_gemm_opts) up to M = 64 (tile 64, which has no split prefill: 192);
+ * without one up to M = 128 for N >= 5120, else up to M = 192 for weights below 64 MB and M = 64 above; prefill
+ * beyond. */
 typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
 
 /* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and
@@ -59,10 +61,14 @@ typedef struct {
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
                  /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
                  /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
-                 /* K-steps per wavefront.  A variant that does not apply falls back to the default.     */
-    void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for split prefill launches, */
-                            /* or NULL.  The library never allocates in a product call.  Launches that   */
-                            /* may run concurrently need distinct workspaces.                            */
+                 /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
+                 /* features per wavefront for passes of 17 .. 64 rows (its split_k = K chunks over      */
+                 /* `workspace`, 0 = auto; the default for such passes when a workspace allows chunks    */
+                 /* or N >= 5120).  A variant that does not apply falls back to the default.             */
+    void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for launches that split K   */
+                            /* over workgroups (prefill; decode passes of 17 .. 64 rows), or NULL.  The  */
+                            /* library never allocates in a product call.  Launches that may run         */
+                            /* concurrently need distinct workspaces.                                    */
     size_t workspace_bytes; /* its size; patch_gemm_workspace_bytes says what a launch would use         */
 } patch_gemm_opts;
 
@@ -123,7 +129,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
  * Schedule autotuner (Appendix A leaves tile shape and schedule - e.g. split-K - to an autotuner run per layer
  * and input shape, decode first).  Times the candidate schedules of patch_gemm_ex for this M and P on the device,
  * on real operands, and returns the fastest.  Candidates: both paths where they apply (decode passes up to
- * M = 256), the kernel variants of the path, and for prefill the K-split counts the workspace allows.
+ * M = 256), the kernel variants of the path, and the K-split counts the workspace allows.
  *   X, Y       as for patch_gemm (Y is overwritten several times; on return it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1
@@ -136,14 +142,15 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
                         void* stream, int reps, patch_gemm_opts* best, float* best_us);
 
 /* Bytes of patch_gemm_opts.workspace the product with these M, P and opts (path, split_k; NULL = defaults) would
- * use if it were given enough: slices x M x N x 4 for a split prefill launch, else 0. */
+ * use if it were given enough: slices x M x N x 4 for a split prefill launch, chunks x min(M, 64) x N x 4 for
+ * decode passes of 17 .. 64 rows, else 0. */
 size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts);
 
 /*
  * The same product for several weights that share one input: Y[i] = X * W_hat[i]^T, i < count (the q / k / v
  * projections of an attention block, the gate / up projections of an MLP; Appendix A times the layer's products
- * for one decode input and one prefill input).  On the decode path all weights run in ONE launch per 16 rows of
- * X, which amortises launch and ramp-up over all their bytes; on the prefill path (tile 128) one launch covers the
+ * for one decode input and one prefill input).  On the decode path all weights run in ONE launch per pass of up
+ * to 64 rows of X, which amortises launch and ramp-up over all their bytes; on the prefill path (tile 128) one launch covers the
  * output tiles of all weights - one tail instead of one per weight - unless they are so few that splitting K pays
  * (a workspace is given, split_k = 0), or opts ask for a kernel variant or split: then one launch per weight.
  *   P      HOST array of count handles; all with the same K and the same tile, N may differ

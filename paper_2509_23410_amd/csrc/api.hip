@@ -182,18 +182,31 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     return PATCH_OK;
 }
 
-// Measured crossovers between decode passes (up to 64 rows each; every pass streams the whole weight) and the
-// 256 x 256-tile prefill kernel.  Unsplit, the prefill grid is too small to fill the chip at small M.  With a
-// workspace the prefill launch splits K over the idle compute units and costs about 20 us + the weight stream:
-//   4096 x 4096 (34 MB): decode 12 / 18 / 20 / 41 / 83 us at M = 32 / 48 / 64 / 128 / 256, split prefill 20 / 21 /
-//   21 / 24 / 30 us, unsplit prefill 66 - 71 us;  13824 x 5120 (113 MB at f = 0.5): decode 32 / 46 / 94 / 188 us
-//   at M = 17 / 32 / 64 / 128, split prefill 34 / 35 / 38 / 42 us, unsplit prefill about 93 us.
+// A pass of 17 .. 64 rows on the decode path runs the 64-features-per-wavefront kernel (gemm_mid.hip) when asked for
+// (variant 4) or, by default, when it can fill the chip: with K-chunks over a workspace, or with at least 80 groups
+// of 64 features (measured at M = 32, unsplit: 4096 x 4096, 64 groups, 19.6 us against 12.9 for the strip kernel;
+// 5120 x 5120, 80 groups, 24.1 against 25.2; 13824 x 5120 25.7 against 46.3).
+static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, int64_t groups) {
+    if (rows <= 16) return false;
+    if (variant == 4) return true;
+    return variant == 0 && split_k == 0 && (mid_chunks > 1 || groups >= 80);
+}
+
+// Measured crossovers between decode-path passes (up to 64 rows each; every pass streams the whole weight) and the
+// 256 x 256-tile prefill kernel, f = 0.5, us at M = 32 / 64 / 128:
+//   with a workspace (K split over otherwise idle compute units on either path):
+//     4096 x 4096    passes 12.4 / 16.1 / 31.3    split prefill 21.1 / 21.7 / 24.4
+//     5120 x 5120    passes 15.9 / 21.5 / 42.5    split prefill 23.4 / 25.2 / 28.2
+//     13824 x 5120   passes 25.7 / 34.6 / 69.9    split prefill 35.2 / 39.6 / 42.9
+//     5120 x 13824   passes 27.8 / 36.8 / 72.5    split prefill 42.1 / 43.0 / 45.9
+//   without one the prefill grid is too small to fill the chip (66 - 93 us on these shapes) and the passes cost
+//     4096 x 4096 12.9 / 20.7 / 41.2 (strip kernel), 5120 x 5120 24.1 / 32.9 / 66.1, 13824 x 5120 25.7 / 34.8 / 70.3.
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
-    const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float) &&
-                    P->tile == 128;
+    const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
     const bool small = P->payload_bytes < ((size_t)64 << 20);
     if (M <= 16) return PATCH_PATH_DECODE;
-    if (ws) return M <= (small ? 48 : 24) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (ws) return (M <= kDecodeRows || P->tile != 128) && M <= 192 ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (P->N / 64 >= 80) return M <= 128 ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
     return M <= (small ? 192 : 64) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
 }
 
@@ -216,9 +229,15 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.n_cus = P->n_cus;
     if (opts && opts->workspace) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_DECODE) {
+        WeightSet one = {};
+        one.payload[0] = a.payload; one.table[0] = a.table; one.Y[0] = a.Y; one.N[0] = a.N;
+        one.count = 1;
+        one.units = (int)(a.N / 64);
         for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
             const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
-            launch_decode(a, m0, rows, split_k, variant, s);
+            const int chunks = rows > 16 ? mid_split(a, rows, variant == 4 ? split_k : 0) : 1;
+            if (use_mid_kernel(rows, variant, split_k, chunks, a.N / 64)) launch_mid_set(a, one, m0, rows, chunks, s);
+            else launch_decode(a, m0, rows, split_k, variant, s);
         }
     } else {
         launch_prefill(a, variant, split_k, s);
@@ -240,6 +259,13 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
         add(PATCH_PATH_DECODE, 0, 0, false);
         add(PATCH_PATH_DECODE, 0, 2, false);
         add(PATCH_PATH_DECODE, 0, 3, false);
+        if (M > 16) {  // the 64-features-per-wavefront kernel, unsplit and with K-chunks over the workspace
+            add(PATCH_PATH_DECODE, 0, 4, false);
+            const size_t per_slice = (size_t)(M < kDecodeRows ? M : kDecodeRows) * (size_t)P->N * sizeof(float);
+            if (workspace)
+                for (int sk : {2, 3, 4, 6, 8})
+                    if ((size_t)sk * per_slice <= workspace_bytes && sk <= P->Tk) add(PATCH_PATH_DECODE, sk, 4, true);
+        }
     }
     if (P->tile == 128) {
         add(PATCH_PATH_PREFILL, 1, 0, false);
@@ -284,15 +310,23 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     patch_gemm_opts enough = {path, split_k, variant, reinterpret_cast<void*>(16), ~(size_t)0};  // the choice given enough
     if (path == PATCH_PATH_AUTO) path = auto_path(M, P, &enough);
-    if (path != PATCH_PATH_PREFILL || (variant != 0 && variant != 3)) return 0;
     GemmArgs a;
     a.X = nullptr; a.M = M; a.N = P->N; a.K = P->K;
     a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
     a.payload = nullptr; a.table = nullptr; a.Y = nullptr;
     a.n_cus = P->n_cus;
-    if (!prefill_wreg_supports(a)) return 0;
     a.ws = reinterpret_cast<float*>(16);  // "enough": ask for the unconstrained choice
     a.ws_bytes = ~(size_t)0;
+    if (path == PATCH_PATH_DECODE) {
+        // passes of 17 .. 64 rows may cut K into chunks over the workspace (the largest pass decides)
+        const int rows = (int)(M < kDecodeRows ? M : kDecodeRows);
+        if (rows <= 16) return 0;
+        const int chunks = mid_split(a, rows, variant == 4 ? split_k : 0);
+        if (!use_mid_kernel(rows, variant, split_k, chunks, a.N / 64) || chunks < 2) return 0;
+        return (size_t)chunks * (size_t)rows * (size_t)P->N * sizeof(float);
+    }
+    if (variant != 0 && variant != 3) return 0;
+    if (!prefill_wreg_supports(a)) return 0;
     const int s = prefill_wreg_split(a, split_k);
     return s > 1 ? (size_t)s * (size_t)M * (size_t)P->N * sizeof(float) : 0;
 }
@@ -360,9 +394,18 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     }
     set.count = count;
     set.units = strips;
+    // the same set in units of 64-feature groups, for passes of more than 16 rows
+    WeightSet wide = set;
+    int groups = 0;
+    for (int i = 0; i < count; ++i) {
+        wide.first[i] = groups;
+        groups += (int)(P[i]->N / 64);
+    }
+    wide.units = groups;
     for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
         const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
-        launch_decode_set(a, set, m0, rows, split_k, variant, s);
+        if (use_mid_kernel(rows, variant, split_k, 1, groups)) launch_mid_set(a, wide, m0, rows, 1, s);
+        else launch_decode_set(a, set, m0, rows, split_k, variant, s);
     }
     HIP_TRY(hipGetLastError());
     return PATCH_OK;

@@ -561,6 +561,12 @@ static void wr_grant_lds() {
     (void)granted1;
 }
 
+void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t stream) {
+    const size_t blocks = (n4 + 255) / 256;
+    hipLaunchKernelGGL(wr_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
+                       reinterpret_cast<const wr_f32x4*>(ws), n4, slices, reinterpret_cast<wr_f32x4*>(Y));
+}
+
 void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
     wr_grant_lds();
     const int tiles_n = (int)((a.N + kWrBN - 1) / kWrBN), tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
@@ -580,10 +586,7 @@ void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
         set.Y[0] = a.ws;
         hipLaunchKernelGGL(prefill_kernel_wreg<true>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
                            tiles_m, set);
-        const size_t n4 = (size_t)a.M * (size_t)a.N / 4;
-        const size_t blocks = (n4 + 255) / 256;
-        hipLaunchKernelGGL(wr_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
-                           reinterpret_cast<const wr_f32x4*>(a.ws), n4, split, reinterpret_cast<wr_f32x4*>(a.Y));
+        wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, stream);
     }
 }
 

@@ -49,6 +49,14 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
 // The same for a set of weights; a supplies X, K, tile, Tk, n_cus (its payload / table / Y / N are ignored).
 int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
 
+// 17 .. kDecodeRows rows of X starting at row m0 (batched decode): 64 features per wavefront, so X is read once per
+// four strips.  set.units / first[] count 64-feature groups.  split > 1 (single weight only, a.ws must hold
+// split x rows x N floats) cuts K into chunks over more workgroups; mid_split picks the count (1 without a.ws).
+int mid_split(const GemmArgs& a, int rows, int requested);
+void launch_mid_set(const GemmArgs& a, const WeightSet& set, int64_t m0, int rows, int split, hipStream_t stream);
+// Y[i] = sum over the slices of ws[slice * n4 + i] (float4 units), slice 0 first
+void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t stream);
+
 // Any M (prefill shape).
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream);
 bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB

@@ -306,6 +306,13 @@ def test_mid_m_paths_agree(dev):
         for path in (B.PATH_AUTO, B.PATH_DECODE, B.PATH_PREFILL):
             print(f"mid M={M} path={path}", flush=True)
             assert relF(p.gemm(c.X[:M], path=path), Yo) <= TIGHT
+    # the 64-features-per-wavefront kernel for 17 .. 64 rows per pass, unsplit and with K-chunks over a workspace
+    ws = torch.empty(8 * 64 * 1024, device=dev, dtype=torch.float32)
+    for M in (17, 32, 33, 48, 64, 65, 100, 130):
+        Yo = p.oracle_gemm(c.X[:M])
+        for kw in (dict(), dict(workspace=ws), dict(workspace=ws, split_k=3), dict(workspace=ws, split_k=6)):
+            print(f"mid kernel M={M} split_k={kw.get('split_k')} workspace={'workspace' in kw}", flush=True)
+            assert relF(p.gemm(c.X[:M], path=B.PATH_DECODE, variant=4, **kw), Yo) <= TIGHT
     p.P.close()
     # decode passes of up to 64 rows (1, 2 or 4 blocks of 16) on tile 64 and with forced wavefront counts
     c = synth.make_case("mid64", 192, 640, 70, 64, 0.5, seed=9)
@@ -314,6 +321,8 @@ def test_mid_m_paths_agree(dev):
         Yo = p.oracle_gemm(c.X[:M])
         for sk in (0, 1, 3, 8):
             assert relF(p.gemm(c.X[:M], path=B.PATH_DECODE, split_k=sk), Yo) <= TIGHT
+        for kw in (dict(), dict(workspace=ws), dict(workspace=ws, split_k=4)):
+            assert relF(p.gemm(c.X[:M], path=B.PATH_DECODE, variant=4, **kw), Yo) <= TIGHT
     p.P.close()
 
 
@@ -325,13 +334,14 @@ def test_gemm_many_matches_single_calls(dev):
     X = cases[0].X                       # shared input
     preps = [Prepared(c, dev) for c in cases]
     Xd = to_dev_bf16(X, dev)
-    for M, path in [(1, B.PATH_AUTO), (16, B.PATH_DECODE), (40, B.PATH_DECODE), (40, B.PATH_PREFILL), (300, B.PATH_AUTO)]:
-        print(f"many M={M} path={path}", flush=True)
+    for M, path, variant in [(1, B.PATH_AUTO, 0), (16, B.PATH_DECODE, 0), (40, B.PATH_DECODE, 0), (40, B.PATH_PREFILL, 0),
+                             (300, B.PATH_AUTO, 0), (24, B.PATH_DECODE, 4), (100, B.PATH_DECODE, 4)]:
+        print(f"many M={M} path={path} variant={variant}", flush=True)
         Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
-        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=path)
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=path, variant=variant)
         for p, Y in zip(preps, Ys):
             single = torch.empty_like(Y)
-            B.patch_gemm(Xd, M, p.P, single, stream(), path=path)
+            B.patch_gemm(Xd, M, p.P, single, stream(), path=path, variant=variant)
             torch.cuda.synchronize()
             assert torch.equal(Y, single), "fused launch differs from the single call"
             assert relF(Y.cpu().numpy(), p.oracle_gemm(X[:M])) <= TIGHT
@@ -372,7 +382,9 @@ def test_prefill_split_k(dev):
         assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5, workspace=small), Yo) <= TIGHT
         assert relF(p.gemm(c.X[:M], path=B.PATH_PREFILL, split_k=5), Yo) <= TIGHT   # none: unsplit
     assert B.patch_gemm_workspace_bytes(1, p.P) == 0            # decode path
-    assert B.patch_gemm_workspace_bytes(40, p.P) == 0           # auto: still decode at this M for a small weight
+    need40 = B.patch_gemm_workspace_bytes(40, p.P)              # auto: a decode pass of 40 rows, K in chunks
+    assert need40 > 0 and need40 % (40 * 384 * 4) == 0
+    assert relF(p.gemm(c.X[:40], workspace=ws), p.oracle_gemm(c.X[:40])) <= TIGHT
     assert B.patch_gemm_workspace_bytes(100, p.P) > 0           # auto: prefill, split, once a workspace is there
     assert relF(p.gemm(c.X[:100], workspace=ws), p.oracle_gemm(c.X[:100])) <= TIGHT
     p.P.close()
