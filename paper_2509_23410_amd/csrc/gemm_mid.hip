@@ -7,7 +7,7 @@
 // loads is used by four strips, so X costs as many bytes as the weights, not four times as many.
 //
 // Mapping.  Workgroup (g, c) = 64-feature group g x K-chunk c (whole tiles).  Its four wavefronts take the chunk's
-// steps in turn, one or two 64-column steps per pass; per pass a wavefront issues all its loads first (weights straight
+// steps in turn, two 64-column steps per pass; per pass a wavefront issues all its loads first (weights straight
 // into registers in the stored register order, X from L2), then the matrix instructions: per strip one scalar
 // branch on the tile type, dense 2 x v_mfma_f32_16x16x32_bf16 or 2:4 1 x v_smfmac_f32_16x16x64_bf16 per row block.
 // The wavefronts' partial sums meet in LDS and are added in wavefront order.  With one chunk (gridDim.y = 1) the
@@ -30,6 +30,7 @@ union MidA { mid_u32x4 raw; mid_bf16x8 v; };
 union MidB { mid_u32x4 raw[2]; mid_bf16x8 h[2]; mid_bf16x16 v; };
 
 constexpr int kMidSB = 4;   // strips (16 features) per wavefront
+constexpr int kMidNK = 2;   // 64-column steps per pass
 constexpr int kMidKW = 4;   // wavefronts per workgroup
 
 __device__ __forceinline__ uint64_t mid_uniform64(uint64_t v) {
@@ -37,14 +38,14 @@ __device__ __forceinline__ uint64_t mid_uniform64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// RB = 16-row blocks of X (2: up to 32 rows, 4: up to 64).  NK = 64-column steps per pass (all of a pass's loads
-// are in flight together: 2 with RB = 2, 1 with RB = 4 keep the kernel at two wavefronts per SIMD).
-// SPLIT: gridDim.y K-chunks, partial sums to a workspace.
-template <int TILE, int RB, int NK, bool SPLIT>
-__global__ __launch_bounds__(kMidKW * 64) void mid_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
+// RB = 16-row blocks of X (2: up to 32 rows, 4: up to 64).  SPLIT: gridDim.y K-chunks, partial sums to a workspace.
+// Two 64-column steps per pass, all their loads in flight together; the register budget is held to two wavefronts
+// per SIMD (243 registers at RB = 4), so a second workgroup's loads overlap this one's matrix instructions.
+template <int TILE, int RB, bool SPLIT>
+__global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void mid_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
                                                           const WeightSet set) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows, GPT = SPT / kMidSB;  // groups per tile row
-    constexpr int SB = kMidSB, KW = kMidKW;
+    constexpr int SB = kMidSB, NK = kMidNK, KW = kMidKW;
     __shared__ mid_f32x4 red[KW][SB * RB][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -252,22 +253,17 @@ int mid_split(const GemmArgs& a, int rows, int requested) {
 template <int TILE>
 static void launch_mid_t(const GemmArgs& a, const WeightSet& set, int64_t m0, int rows, int split, hipStream_t stream) {
     const dim3 block(kMidKW * 64);
-    // 33 .. 64 rows: two steps in flight per wavefront need more than half of a SIMD's registers, so only one
-    // workgroup fits a compute unit - right when the grid has about one per compute unit, else one step
-    const bool deep = (int64_t)set.units * (split > 1 ? split : 1) <= (int64_t)a.n_cus * 5 / 4;
     if (split > 1) {
         WeightSet part = set;
         part.Y[0] = a.ws;
         const dim3 grid((unsigned)set.units, (unsigned)split);
-        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
-        else if (deep) hipLaunchKernelGGL((mid_kernel<TILE, 4, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
-        else hipLaunchKernelGGL((mid_kernel<TILE, 4, 1, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
+        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
+        else hipLaunchKernelGGL((mid_kernel<TILE, 4, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
         wr_reduce(a.ws, (size_t)rows * (size_t)set.N[0] / 4, split, set.Y[0] + m0 * set.N[0], stream);
     } else {
         const dim3 grid((unsigned)set.units);
-        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-        else if (deep) hipLaunchKernelGGL((mid_kernel<TILE, 4, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-        else hipLaunchKernelGGL((mid_kernel<TILE, 4, 1, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+        else hipLaunchKernelGGL((mid_kernel<TILE, 4, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
     }
 }
 
