@@ -41,8 +41,8 @@ typedef enum {
 } patch_status;
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
- * once per pass: 16-feature strips per workgroup for up to 16 rows, 64 features per wavefront for 17 .. 64 rows where
- * that fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a
+ * once per pass: 16-feature strips per workgroup for few rows, 64 features per wavefront for more rows where that
+ * fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a
  * workspace for at least two slices (see patch_gemm_opts) up to M = 64 (tile 64, which has no split prefill: 192);
  * without one up to M = 128 for N >= 5120, else up to M = 192 for weights below 64 MB and M = 64 above; prefill
  * beyond. */
@@ -62,9 +62,10 @@ typedef struct {
                  /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
                  /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
-                 /* features per wavefront for passes of 17 .. 64 rows (its split_k = K chunks over      */
-                 /* `workspace`, 0 = auto; the default for such passes when a workspace allows chunks    */
-                 /* or N >= 5120).  A variant that does not apply falls back to the default.             */
+                 /* features per wavefront (its split_k = K chunks over `workspace`, 0 = auto; the       */
+                 /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 5120, and */
+                 /* for 12 .. 16 rows when N >= 10240).  A variant that does not apply falls back to the */
+                 /* default.                                                                             */
     void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for launches that split K   */
                             /* over workgroups (prefill; decode passes of 17 .. 64 rows), or NULL.  The  */
                             /* library never allocates in a product call.  Launches that may run         */

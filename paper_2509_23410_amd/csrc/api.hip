@@ -182,14 +182,18 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     return PATCH_OK;
 }
 
-// A pass of 17 .. 64 rows on the decode path runs the 64-features-per-wavefront kernel (gemm_mid.hip) when asked for
-// (variant 4) or, by default, when it can fill the chip: with K-chunks over a workspace, or with at least 80 groups
-// of 64 features (measured at M = 32, unsplit: 4096 x 4096, 64 groups, 19.6 us against 12.9 for the strip kernel;
-// 5120 x 5120, 80 groups, 24.1 against 25.2; 13824 x 5120 25.7 against 46.3).
+// A pass on the decode path runs the 64-features-per-wavefront kernel (gemm_mid.hip) when asked for (variant 4) or,
+// by default, when it can fill the chip and X is a large part of the traffic:
+//   17 .. 64 rows: with K-chunks over a workspace, or with at least 80 groups of 64 features (measured at M = 32,
+//     unsplit: 4096 x 4096, 64 groups, 19.6 us against 12.9 for the strip kernel; 5120 x 5120, 80 groups, 24.1
+//     against 25.2; 13824 x 5120 25.7 against 46.3);
+//   12 .. 16 rows: with at least 160 groups (M = 16: 11008 x 4096 17.9 us against 19.9, 13824 x 5120 22.4 against
+//     29.8; M = 8: 18.2 against 15.9 and 22.9 against 24.3; 4096 x 4096: the strip kernel at every M <= 16).
 static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, int64_t groups) {
-    if (rows <= 16) return false;
     if (variant == 4) return true;
-    return variant == 0 && split_k == 0 && (mid_chunks > 1 || groups >= 80);
+    if (variant != 0 || split_k != 0) return false;
+    if (rows <= 16) return rows >= 12 && groups >= 160;
+    return mid_chunks > 1 || groups >= 80;
 }
 
 // Measured crossovers between decode-path passes (up to 64 rows each; every pass streams the whole weight) and the
@@ -235,7 +239,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
         one.units = (int)(a.N / 64);
         for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
             const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
-            const int chunks = rows > 16 ? mid_split(a, rows, variant == 4 ? split_k : 0) : 1;
+            const int chunks = (rows > 16 || variant == 4) ? mid_split(a, rows, variant == 4 ? split_k : 0) : 1;
             if (use_mid_kernel(rows, variant, split_k, chunks, a.N / 64)) launch_mid_set(a, one, m0, rows, chunks, s);
             else launch_decode(a, m0, rows, split_k, variant, s);
         }
@@ -320,7 +324,7 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
     if (path == PATCH_PATH_DECODE) {
         // passes of 17 .. 64 rows may cut K into chunks over the workspace (the largest pass decides)
         const int rows = (int)(M < kDecodeRows ? M : kDecodeRows);
-        if (rows <= 16) return 0;
+        if (rows <= 16 && variant != 4) return 0;
         const int chunks = mid_split(a, rows, variant == 4 ? split_k : 0);
         if (!use_mid_kernel(rows, variant, split_k, chunks, a.N / 64) || chunks < 2) return 0;
         return (size_t)chunks * (size_t)rows * (size_t)P->N * sizeof(float);

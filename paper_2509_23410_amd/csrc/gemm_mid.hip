@@ -1,5 +1,6 @@
-// Hybrid GEMM for middle-sized batches: 17 .. 64 rows of X per launch (the product Y = X * W_hat^T of Section 4 /
-// Appendix A of the paper between its decoding input, a few rows, and its prefill input, thousands).
+// Hybrid GEMM for batched decoding: up to 64 rows of X per launch, meant for 12 and more (the product
+// Y = X * W_hat^T of Section 4 / Appendix A of the paper between its decoding input, a few rows, and its prefill
+// input, thousands).
 //
 // With more than 16 rows the decode mapping (one 16-feature strip per workgroup) re-reads X once per strip: at 64
 // rows that is four times the weight bytes through every vector L1, and the L1 fill rate is what bounds these
@@ -38,7 +39,7 @@ __device__ __forceinline__ uint64_t mid_uniform64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// RB = 16-row blocks of X (2: up to 32 rows, 4: up to 64).  SPLIT: gridDim.y K-chunks, partial sums to a workspace.
+// RB = 16-row blocks of X (1: up to 16 rows, 2: up to 32, 4: up to 64).  SPLIT: gridDim.y K-chunks, partial sums to a workspace.
 // Two 64-column steps per pass, all their loads in flight together; the register budget is held to two wavefronts
 // per SIMD (243 registers at RB = 4), so a second workgroup's loads overlap this one's matrix instructions.
 template <int TILE, int RB, bool SPLIT>
@@ -257,17 +258,19 @@ static void launch_mid_t(const GemmArgs& a, const WeightSet& set, int64_t m0, in
         WeightSet part = set;
         part.Y[0] = a.ws;
         const dim3 grid((unsigned)set.units, (unsigned)split);
-        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
+        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
+        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
         else hipLaunchKernelGGL((mid_kernel<TILE, 4, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
         wr_reduce(a.ws, (size_t)rows * (size_t)set.N[0] / 4, split, set.Y[0] + m0 * set.N[0], stream);
     } else {
         const dim3 grid((unsigned)set.units);
-        if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
         else hipLaunchKernelGGL((mid_kernel<TILE, 4, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
     }
 }
 
-// 17 .. 64 rows of X starting at row m0.  set.units / first[] count 64-feature groups.  A K split (split > 1) needs
+// Up to 64 rows of X starting at row m0.  set.units / first[] count 64-feature groups.  A K split (split > 1) needs
 // a single weight and a.ws with room for split x rows x N floats.
 void launch_mid_set(const GemmArgs& a, const WeightSet& set, int64_t m0, int rows, int split, hipStream_t stream) {
     if (set.count != 1) split = 1;

@@ -49,7 +49,7 @@ int launch_decode(const GemmArgs& a, int64_t m0, int rows, int split_k, int vari
 // The same for a set of weights; a supplies X, K, tile, Tk, n_cus (its payload / table / Y / N are ignored).
 int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int split_k, int variant, hipStream_t stream);
 
-// 17 .. kDecodeRows rows of X starting at row m0 (batched decode): 64 features per wavefront, so X is read once per
+// Up to kDecodeRows rows of X starting at row m0 (batched decode): 64 features per wavefront, so X is read once per
 // four strips.  set.units / first[] count 64-feature groups.  split > 1 (single weight only, a.ws must hold
 // split x rows x N floats) cuts K into chunks over more workgroups; mid_split picks the count (1 without a.ws).
 int mid_split(const GemmArgs& a, int rows, int requested);

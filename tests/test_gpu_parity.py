@@ -283,7 +283,9 @@ def test_full_size_prefill_sampled(dev, N, K, M):
 
 def test_13b_layer_shapes_sampled(dev):
     """One decoder layer of the 13B stack (q/k/v/o 5120^2, gate/up 13824 x 5120, down 5120 x 13824) with the
-    layer's 2:4 fraction drawn U[0,1), at M = 1 and M = 512."""
+    layer's 2:4 fraction drawn U[0,1), at M = 1, a batched-decode M = 16 and 48 (the wide-wavefront kernel on the
+    13824-feature weight, alone and with K-chunks over a workspace on the others) and M = 512."""
+    ws = torch.empty(8 * 64 * 13824, device=dev, dtype=torch.float32)
     fr = synth.layer_fractions(0, 40)
     for li, (N, K) in [(3, (5120, 5120)), (17, (13824, 5120)), (29, (5120, 13824))]:
         f = float(fr[li])
@@ -293,6 +295,9 @@ def test_13b_layer_shapes_sampled(dev):
         rng = np.random.default_rng(li)
         for M in (1, 512):
             Y = p.gemm(c.X[:M])
+            _sampled_checks(p, c, c.X[:M], Y, rng, n_points=1024, n_rows=8)
+        for M, kw in ((16, dict()), (48, dict()), (48, dict(workspace=ws))):
+            Y = p.gemm(c.X[:M], **kw)
             _sampled_checks(p, c, c.X[:M], Y, rng, n_points=1024, n_rows=8)
         p.P.close()
 
@@ -308,7 +313,7 @@ def test_mid_m_paths_agree(dev):
             assert relF(p.gemm(c.X[:M], path=path), Yo) <= TIGHT
     # the 64-features-per-wavefront kernel for 17 .. 64 rows per pass, unsplit and with K-chunks over a workspace
     ws = torch.empty(8 * 64 * 1024, device=dev, dtype=torch.float32)
-    for M in (17, 32, 33, 48, 64, 65, 100, 130):
+    for M in (1, 7, 16, 17, 32, 33, 48, 64, 65, 100, 130):
         Yo = p.oracle_gemm(c.X[:M])
         for kw in (dict(), dict(workspace=ws), dict(workspace=ws, split_k=3), dict(workspace=ws, split_k=6)):
             print(f"mid kernel M={M} split_k={kw.get('split_k')} workspace={'workspace' in kw}", flush=True)
