@@ -7,7 +7,7 @@
 // kernels.  Here a wavefront owns FOUR strips (64 features) and up to four 16-row blocks of X: every X operand it
 // loads is used by four strips, so X costs as many bytes as the weights, not four times as many.
 //
-// Mapping.  Workgroup (g, c) = 64-feature group g x K-chunk c (whole tiles).  Its four wavefronts take the chunk's
+// Mapping.  Workgroup (g, c) = 64-feature group g x K-chunk c (whole tiles).  Its eight wavefronts take the chunk's
 // steps in turn, two 64-column steps per pass; per pass a wavefront issues all its loads first (weights straight
 // into registers in the stored register order, X from L2), then the matrix instructions: per strip one scalar
 // branch on the tile type, dense 2 x v_mfma_f32_16x16x32_bf16 or 2:4 1 x v_smfmac_f32_16x16x64_bf16 per row block.
@@ -32,7 +32,7 @@ union MidB { mid_u32x4 raw[2]; mid_bf16x8 h[2]; mid_bf16x16 v; };
 
 constexpr int kMidSB = 4;   // strips (16 features) per wavefront
 constexpr int kMidNK = 2;   // 64-column steps per pass
-constexpr int kMidKW = 4;   // wavefronts per workgroup
+constexpr int kMidKW = 8;   // wavefronts per workgroup: two per SIMD, one's loads overlap the other's matrix instructions
 
 __device__ __forceinline__ uint64_t mid_uniform64(uint64_t v) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
@@ -47,7 +47,8 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
                                                           const WeightSet set) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows, GPT = SPT / kMidSB;  // groups per tile row
     constexpr int SB = kMidSB, NK = kMidNK, KW = kMidKW;
-    __shared__ mid_f32x4 red[KW][SB * RB][64];
+    constexpr int KH = KW / 2;
+    __shared__ mid_f32x4 red[KH][SB * RB][64];  // 64 KB at RB = 4: half of the wavefronts at a time
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -213,18 +214,32 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
     }
 
     // fixed-order sum of the wavefronts' partials; acc[sb][rb][r] = Y^T[64 grp + 16 sb + 4 q + r][16 rb + col].
-    // Wavefront w adds and stores the accumulator tiles t = w, w + KW, ... (t = sb * RB + rb).
+    // First wavefront w + KH hands its partials to wavefront w, then the KH sums meet in LDS again and wavefront w
+    // adds and stores the accumulator tiles t = w, w + KW, ... (t = sb * RB + rb): ((p0 + p4) + (p1 + p5)) + ...
+    if (w >= KH) {
 #pragma unroll
-    for (int sb = 0; sb < SB; ++sb)
+        for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) red[w][sb * RB + rb][lane] = acc[sb][rb];
+            for (int rb = 0; rb < RB; ++rb) red[w - KH][sb * RB + rb][lane] = acc[sb][rb];
+    }
+    __syncthreads();
+    if (w < KH) {
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const mid_f32x4 v = red[w][sb * RB + rb][lane];
+                acc[sb][rb][0] += v[0]; acc[sb][rb][1] += v[1]; acc[sb][rb][2] += v[2]; acc[sb][rb][3] += v[3];
+                red[w][sb * RB + rb][lane] = acc[sb][rb];  // the same lane wrote and reads this slot: no barrier between
+            }
+    }
     __syncthreads();
     float* dst = SPLIT ? Y + (int64_t)blockIdx.y * rows * N : Y + m0 * N;  // SPLIT: Y is the workspace, slices of rows x N
     for (int t = w; t < SB * RB; t += KW) {
         const int sb = t / RB, rb = t % RB;
         mid_f32x4 sum = red[0][t][lane];
 #pragma unroll
-        for (int i = 1; i < KW; ++i) {
+        for (int i = 1; i < KH; ++i) {
             const mid_f32x4 v = red[i][t][lane];
             sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
