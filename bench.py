@@ -282,9 +282,16 @@ def main():
                 del W_hat
         out["decode_mlp"] = dict(rows=mlp, note="7B MLP projections, M = 1, rotating packed copies")
         m1 = [r_ for r_ in dec if r_["M"] == 1 and r_["f"] == 0.0][0]
+        dtraffic = None
+        dpath = os.path.join(ROOT, "profiles", "decode_traffic.json")
+        if os.path.exists(dpath):
+            with open(dpath) as fh:
+                dtraffic = json.load(fh).get("hbm_bytes_per_launch")   # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
         out["decode_roofline"] = dict(bound="hbm", achieved=m1["GBps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=m1["frac_hbm"],
-                                      traffic=None, kernel="decode_kernel", workload="4096x4096 f=0 M=1",
-                                      note="compressed weight bytes per launch / average launch duration")
+                                      traffic=dtraffic, kernel="decode_kernel", workload="4096x4096 f=0 M=1",
+                                      algorithmic_bytes_per_launch=m1["packed_MB"] * 1e6,
+                                      note="achieved = compressed weight bytes per launch / average launch duration; "
+                                           "traffic = measured HBM bytes per launch (profiles/)")
         out["decode_fused_qkv"] = dict(rows=fused, note="three 4096x4096 projections sharing X in one patch_gemm_many launch, rotating packed copies")
         out["decode"] = dict(workload="llama7b_attn_decode 4096x4096 tile128", peak_GBps=PEAK_HBM_GBS, rows=dec,
                              note="us = median of 5 batches of back-to-back launches over rotating packed copies (HBM-resident)")
