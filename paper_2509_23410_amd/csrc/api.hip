@@ -263,7 +263,7 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
         add(PATCH_PATH_DECODE, 0, 0, false);
         add(PATCH_PATH_DECODE, 0, 2, false);
         add(PATCH_PATH_DECODE, 0, 3, false);
-        if (M > 16) {  // the 64-features-per-wavefront kernel, unsplit and with K-chunks over the workspace
+        if (M >= 12) {  // the 64-features-per-wavefront kernel, unsplit and with K-chunks over the workspace
             add(PATCH_PATH_DECODE, 0, 4, false);
             const size_t per_slice = (size_t)(M < kDecodeRows ? M : kDecodeRows) * (size_t)P->N * sizeof(float);
             if (workspace)
