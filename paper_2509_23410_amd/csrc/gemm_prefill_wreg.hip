@@ -309,7 +309,8 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     auto load_x_slot = [&](int slot, int s, int stage) {
         const uint8_t* xb = xbase + (size_t)s * 128;
         const uint32_t m0v = lds0 + stage * kWrStage + (w + 4 * slot) * 1024;
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(xoff[slot]), "s"(xb) : "memory");
+        // (one wait state between the write of m0 and the load that reads it as its LDS base)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(xoff[slot]), "s"(xb) : "memory");
     };
 
     const int S = 2 * Tk;  // 64-column steps
