@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -23,6 +24,7 @@ struct patch_packed {
     uint32_t* d_table = nullptr;
     std::vector<uint8_t> tile_map;   // host copy, 1 = dense
     std::vector<uint32_t> table;     // host copy of the offset / type table
+    std::vector<int32_t> pairs;      // tile rows two by two (see pair_tile_rows); behind the table on the device
     int device = 0;
     int n_cus = 256;
 };
@@ -44,6 +46,70 @@ static patch_status check_shape(int64_t N, int64_t K, int tile) {
     if (N % tile != 0 || K % tile != 0) return PATCH_ERR_SHAPE;
     if (N / tile > (1 << 20) || K / tile > (1 << 20)) return PATCH_ERR_SHAPE;
     return PATCH_OK;
+}
+
+// Which two tile rows share a prefill workgroup (tile-map-driven schedule; the paper leaves the schedule to the
+// implementation).  The workgroup's wavefronts meet at a barrier every 64-column step, so a step in which one tile row
+// is dense and the other 2:4 lasts as long as a dense one.  Rows are therefore paired by the similarity of their
+// dense / 2:4 patterns along K: within windows of 256 rows, the most similar free pair first (ties: lowest row
+// indices).  Returns 2 * ceil(Tn / 2) entries, pair p = rows out[2 p], out[2 p + 1]; -1 = no second row.
+static std::vector<int32_t> pair_tile_rows(const std::vector<uint8_t>& tile_map, int Tn, int Tk) {
+    std::vector<int32_t> out;
+    out.reserve((size_t)Tn + 1);
+    std::vector<int> carry;  // rows left single by earlier windows
+    constexpr int kWindow = 256;
+    struct Cand { int agree, a, b; };
+    for (int w0 = 0; w0 < Tn; w0 += kWindow) {
+        std::vector<int> rows = carry;
+        carry.clear();
+        for (int r = w0; r < Tn && r < w0 + kWindow; ++r) rows.push_back(r);
+        const int n = (int)rows.size();
+        std::vector<Cand> cand;
+        cand.reserve((size_t)n * (size_t)(n - 1) / 2);
+        for (int i = 0; i < n; ++i)
+            for (int j = i + 1; j < n; ++j) {
+                const uint8_t* ra = &tile_map[(size_t)rows[i] * Tk];
+                const uint8_t* rb = &tile_map[(size_t)rows[j] * Tk];
+                int agree = 0;
+                for (int k = 0; k < Tk; ++k) agree += ra[k] == rb[k];
+                cand.push_back(Cand{agree, i, j});
+            }
+        std::stable_sort(cand.begin(), cand.end(), [](const Cand& x, const Cand& y) { return x.agree > y.agree; });
+        std::vector<char> used((size_t)n, 0);
+        for (const Cand& c : cand) {
+            if (used[c.a] || used[c.b]) continue;
+            used[c.a] = used[c.b] = 1;
+            out.push_back(rows[c.a]);
+            out.push_back(rows[c.b]);
+        }
+        for (int i = 0; i < n; ++i)
+            if (!used[i]) carry.push_back(rows[i]);
+    }
+    for (size_t i = 0; i + 1 < carry.size(); i += 2) { out.push_back(carry[i]); out.push_back(carry[i + 1]); }
+    if (carry.size() % 2) { out.push_back(carry.back()); out.push_back(-1); }
+    // Order of the pairs = order of the feature blocks in the launch, of which every XCD runs a contiguous piece
+    // (a half, a quarter, ... depending on M).  A pair costs about Tk - 0.3 x (steps in which both rows are 2:4);
+    // heaviest and lightest pairs alternate, so that every contiguous piece carries about the average cost.
+    const size_t np = out.size() / 2;
+    std::vector<std::pair<int, size_t>> cost(np);
+    for (size_t p = 0; p < np; ++p) {
+        const int a = out[2 * p], b2 = out[2 * p + 1];
+        int both = 0;
+        for (int k = 0; k < Tk; ++k) both += tile_map[(size_t)a * Tk + k] == 0 && (b2 < 0 || tile_map[(size_t)b2 * Tk + k] == 0);
+        cost[p] = {both, p};  // more common 2:4 steps = lighter
+    }
+    std::stable_sort(cost.begin(), cost.end(), [](const auto& x, const auto& y) { return x.first < y.first; });
+    std::vector<int32_t> ordered;
+    ordered.reserve(out.size());
+    for (size_t lo = 0, hi = np; lo < hi;) {
+        const size_t h = cost[lo++].second;
+        ordered.push_back(out[2 * h]); ordered.push_back(out[2 * h + 1]);
+        if (lo < hi) {
+            const size_t l = cost[--hi].second;
+            ordered.push_back(out[2 * l]); ordered.push_back(out[2 * l + 1]);
+        }
+    }
+    return ordered;
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -136,6 +202,9 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     }
     P->payload_bytes = off;
     if ((off / kGranule) >> 31) { delete P; return PATCH_ERR_SHAPE; }
+    try {
+        P->pairs = pair_tile_rows(P->tile_map, P->Tn, P->Tk);
+    } catch (...) { delete P; return PATCH_ERR_ALLOC; }
 
     int dev = 0;
     hipDeviceProp_t prop;
@@ -150,7 +219,7 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     int* d_err = nullptr;
     // a kilobyte of slack behind the payload keeps any over-read of the last tile inside the allocation
     bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kZeroPad) == hipSuccess &&
-              hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&P->d_table, (T + P->pairs.size()) * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&d_err, sizeof(int)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -159,6 +228,8 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
         return PATCH_ERR_ALLOC;
     }
     hipError_t e = hipMemcpyAsync(P->d_table, P->table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(P->d_table + T, P->pairs.data(), P->pairs.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
     if (e == hipSuccess) e = hipMemsetAsync(P->d_payload + P->payload_bytes, 0, kZeroPad, s);
     if (e == hipSuccess) {

@@ -252,14 +252,20 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     table = reinterpret_cast<const uint32_t*>(wr_uniform64(reinterpret_cast<uint64_t>(table)));
     Y = reinterpret_cast<float*>(wr_uniform64(reinterpret_cast<uint64_t>(Y)));
     N = (int64_t)wr_uniform64((uint64_t)N);
-    const int64_t n0 = (int64_t)bn * kWrBN, m0 = (int64_t)bm * kWrBM;
-    // N is a multiple of 128, not necessarily of 256: the wavefronts of a missing second tile row copy X and meet
-    // the barriers like the others, read the first tile row's weights (valid addresses) and multiply nothing
-    const bool live = n0 + (int64_t)tr * TILE < N;
+    const int64_t m0 = (int64_t)bm * kWrBM;
+    // The two tile rows of feature block bn: rows pairs[2 bn], pairs[2 bn + 1] of the list behind the table, chosen
+    // by the packer so that their dense / 2:4 patterns along K agree as often as possible (the wavefronts meet at a
+    // barrier every step: a step with one dense and one 2:4 tile row lasts as long as a dense one).
+    // With an odd number of tile rows the last block has no second row (-1): its wavefronts copy X and meet the
+    // barriers like the others, read the first row's weights (valid addresses) and multiply nothing.
+    const int32_t* pairs = reinterpret_cast<const int32_t*>(table) + (N / TILE) * (int64_t)Tk_all;
+    const int row0 = pairs[2 * bn], row1 = pairs[2 * bn + 1];
+    const bool live = tr == 0 || row1 >= 0;
+    const int64_t nrow = (int64_t)__builtin_amdgcn_readfirstlane((tr == 0 || row1 < 0) ? row0 : row1) * TILE;  // first feature of this wavefront's tile row
     // this workgroup's K slice, in tiles: to the rest of the kernel it is a product with a shorter K
     const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
     const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
-    const uint32_t* trow = table + (n0 / TILE + (live ? tr : 0)) * Tk_all + t_begin;
+    const uint32_t* trow = table + (nrow / TILE) * Tk_all + t_begin;
 
     // ---- per-lane sources of the X copy: wavefront w copies the 1 KB pieces w, w+4, ..., w+28 of the 32 KB stage.
     // LDS chunk c (16 bytes) = row c / 8, physical chunk c % 8, which holds logical chunk (c % 8) ^ ((row / 2) % 8):
@@ -501,7 +507,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     // workgroup's LDS and registers can be handed on; the last matrix instructions may still be writing
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory", PATCH_WR_CLOBBER);
 
-    // accumulator (s, cb), register r: feature n0 + 128 tr + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col
+    // accumulator (s, cb), register r: feature nrow + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col
     if (live) {
 #define PATCH_WR_READ(S, CB)                                                                                       \
     asm volatile("v_accvgpr_read_b32 %0, a[4*(16*" #S "+" #CB ")+0]\n\tv_accvgpr_read_b32 %1, a[4*(16*" #S "+" #CB ")+1]\n\t" \
@@ -510,7 +516,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
         const int64_t m = m0 + 16 * CB + col;                                                                      \
-        float* yrow = Y + (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + 128 * tr + 64 * sh + 4 * q;                                                 \
+        float* yrow = Y + (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;                                                 \
         float v[4];                                                                                                \
         PATCH_WR_READ(0, CB);                                                                                      \
         if (m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \

@@ -487,3 +487,38 @@ def test_empty_batch_is_a_no_op(dev):
     with pytest.raises(B.PatchError):
         B.patch_gemm(X, -1, p.P, Y, stream())
     p.P.close()
+
+
+@pytest.mark.parametrize("pattern", ["row_bands", "alternating_rows", "columns", "one_sparse_row"])
+def test_prefill_structured_tile_maps(dev, pattern):
+    """Tile maps with structure (whole tile rows of one type, bands, columns): the packer pairs tile rows by pattern
+    and reorders the feature blocks; every tile row must still be multiplied exactly once.  Odd tile-row count."""
+    N, K, M, t = 1664, 768, 300, 128       # 13 tile rows x 6 tile columns
+    c = synth.make_case("structured", N, K, M, t, 0.5, seed=17)
+    Tn, Tk = N // t, K // t
+    tm = np.ones((Tn, Tk), np.uint8)
+    if pattern == "row_bands":
+        tm[: Tn // 2] = 0
+    elif pattern == "alternating_rows":
+        tm[::2] = 0
+    elif pattern == "columns":
+        tm[:, : Tk // 2] = 0
+    else:
+        tm[Tn - 1] = 0
+    W_hat_o = oracle.apply_mask(c.W, tm, c.mask24, t)
+    vals_o, meta_o = oracle.pack(W_hat_o, tm, t)
+    W = to_dev_bf16(c.W, dev)
+    W_hat = torch.empty_like(W)
+    B.patch_apply_mask(W, torch.from_numpy(c.mask24).to(dev), tm, N, K, t, W_hat, stream())
+    P = B.patch_pack(W_hat, N, K, tm, t, stream())
+    X = to_dev_bf16(c.X, dev)
+    Yo = oracle.gemm(c.X, vals_o, meta_o, N, K, tm, t)
+    ws = torch.empty(4 * M * N, device=dev, dtype=torch.float32)
+    for kw in (dict(path=B.PATH_PREFILL), dict(path=B.PATH_PREFILL, workspace=ws, split_k=3), dict(path=B.PATH_PREFILL, variant=2)):
+        Y = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+        B.patch_gemm(X, M, P, Y, stream(), **kw)
+        torch.cuda.synchronize()
+        Yh = Y.cpu().numpy()
+        assert np.isfinite(Yh).all(), "a tile row was not written"
+        assert relF(Yh, Yo) <= TIGHT
+    P.close()
