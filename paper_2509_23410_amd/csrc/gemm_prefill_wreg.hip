@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     N = (int64_t)wr_uniform64((uint64_t)N);
     const int64_t m0 = (int64_t)bm * kWrBM;
     // The two tile rows of feature block bn: rows pairs[2 bn], pairs[2 bn + 1] of the list behind the table, chosen
-    // by the packer so that their dense / 2:4 patterns along K agree as often as possible (the wavefronts meet at a
-    // barrier every step: a step with one dense and one 2:4 tile row lasts as long as a dense one).
+    // by the packer so that both are 2:4 in as many steps as possible (the wavefronts meet at a barrier every step:
+    // a step with one dense and one 2:4 tile row lasts as long as a dense one).
     // With an odd number of tile rows the last block has no second row (-1): its wavefronts copy X and meet the
     // barriers like the others, read the first row's weights (valid addresses) and multiply nothing.
     const int32_t* pairs = reinterpret_cast<const int32_t*>(table) + (N / TILE) * (int64_t)Tk_all;
