@@ -205,7 +205,7 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     P->payload_bytes = off;
     if ((off / kGranule) >> 31) { delete P; return PATCH_ERR_SHAPE; }
     try {
-        P->pairs = pair_tile_rows(P->tile_map, P->Tn, P->Tk);
+        if (tile == 128) P->pairs = pair_tile_rows(P->tile_map, P->Tn, P->Tk);  // read by prefill_kernel_wreg only
     } catch (...) { delete P; return PATCH_ERR_ALLOC; }
 
     int dev = 0;
