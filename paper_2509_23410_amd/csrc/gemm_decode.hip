@@ -110,8 +110,9 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         // loads after all the weight loads measured 1.2 us slower).  One asm block per step: the compiler can
         // neither sink these loads into the branches that consume them nor wait for them one by one.  A load
         // the step does not need (second half of a 2:4 step, positions of a dense step, anything past the end of
-        // K, X for a lane without a row) is issued with an empty EXEC mask: it moves no data and leaves the zero
-        // its destination was initialised with.
+        // K) is jumped over by a scalar branch inside the block and leaves the zero its destination was initialised
+        // with (issuing it with an empty EXEC mask instead still costs an instruction's turn in the memory pipeline:
+        // all-2:4 maps at M = 1 went from 6.5 to 6.0 us on 4096 x 4096 and from 13.4 to 11.6 us on 11008 x 4096); X is loaded by the lanes that have a row only.
         u32x4 a[NK][2], b[NK][RB][2];
         uint32_t idx[NK];
 #pragma unroll
@@ -133,21 +134,23 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
 // One step's loads.  LDM is the mnemonic of the positions load (16 or 32 bits per lane).
 #define PATCH_DECODE_STEP_LOADS(LDM)                                                                              \
     asm volatile(                                                                                                 \
-        "s_mov_b64 %[sv], exec\n\t"                                                                               \
-        "s_cmp_lg_u32 %[kind], 0\n\t"                                                                             \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_cmp_eq_u32 %[kind], 0\n\t"                                                                             \
+        "s_cbranch_scc1 3f\n\t"                                                                                   \
         "global_load_dwordx4 %[v0], %[vo], %[sb0] nt\n\t"                                                         \
         "s_cmp_eq_u32 %[kind], 1\n\t"                                                                             \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_cbranch_scc0 1f\n\t"                                                                                   \
         "global_load_dwordx4 %[v1], %[vo], %[sb0] offset:1024 nt\n\t"                                             \
+        "1:\n\t"                                                                                                  \
         "s_cmp_eq_u32 %[mkind], 2\n\t"                                                                            \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_cbranch_scc0 2f\n\t"                                                                                   \
         LDM " %[vi], %[vm], %[sbm] nt\n\t"                                                                        \
-        "s_cmp_lg_u32 %[kind], 0\n\t"                                                                             \
-        "s_cselect_b64 exec, %[xm], 0\n\t"                                                                        \
+        "2:\n\t"                                                                                                  \
+        "s_mov_b64 %[sv], exec\n\t"                                                                               \
+        "s_mov_b64 exec, %[xm]\n\t"                                                                               \
         "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"                                                            \
         "global_load_dwordx4 %[x1], %[vx], %[sbx] offset:64\n\t"                                                  \
-        "s_mov_b64 exec, %[sv]"                                                                                    \
+        "s_mov_b64 exec, %[sv]\n\t"                                                                               \
+        "3:"                                                                                                       \
         : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi), [x0] "+v"(x0), [x1] "+v"(x1), [sv] "=&s"(saved)            \
         : [vo] "v"(voff), [vm] "v"(voffm), [vx] "v"(voffx), [sb0] "s"(sb0), [sbm] "s"(sbm), [sbx] "s"(sbx),       \
           [kind] "s"(kind), [mkind] "s"(mkind), [xm] "s"(xmask)                                                   \

@@ -112,8 +112,9 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
         for (int g = 0; g < NK; ++g) asm volatile("" : "+s"(ent[g]));
 
         // ---- every byte of the pass is requested now.  A load the step does not need (second half of a 2:4 step,
-        // positions of a dense step, anything past the end of the chunk, X for a lane without a row) is issued with
-        // an empty EXEC mask: it moves no data and leaves the zero its destination was initialised with.
+        // positions of a dense step, anything past the end of the chunk) is jumped over by a scalar branch inside
+        // the asm block and leaves the zero its destination was initialised with; X is loaded by the lanes that
+        // have a row only.
         mid_u32x4 a[NK][SB][2], b[NK][RB][2];
         uint32_t idx[NK][SB];
 #pragma unroll
@@ -135,18 +136,17 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
                 uint32_t vi = 0;
 #define PATCH_MID_WEIGHT_LOADS(LDM)                                                                               \
     asm volatile(                                                                                                 \
-        "s_mov_b64 %[sv], exec\n\t"                                                                               \
-        "s_cmp_lg_u32 %[kind], 0\n\t"                                                                             \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_cmp_eq_u32 %[kind], 0\n\t"                                                                             \
+        "s_cbranch_scc1 3f\n\t"                                                                                   \
         "global_load_dwordx4 %[v0], %[vo], %[sbw] nt\n\t"                                                         \
         "s_cmp_eq_u32 %[kind], 1\n\t"                                                                             \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_cbranch_scc0 1f\n\t"                                                                                   \
         "global_load_dwordx4 %[v1], %[vo], %[sbw] offset:1024 nt\n\t"                                             \
-        "s_cmp_eq_u32 %[kind], 2\n\t"                                                                             \
-        "s_cselect_b64 exec, %[sv], 0\n\t"                                                                        \
+        "s_branch 3f\n\t"                                                                                         \
+        "1:\n\t"                                                                                                  \
         LDM " %[vi], %[vm], %[sbm] nt\n\t"                                                                        \
-        "s_mov_b64 exec, %[sv]"                                                                                    \
-        : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi), [sv] "=&s"(saved)                                          \
+        "3:"                                                                                                       \
+        : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi)                                                             \
         : [vo] "v"(voff), [vm] "v"(voffm), [sbw] "s"(sbw), [sbm] "s"(sbm), [kind] "s"(kind)                       \
         : "memory", "scc")
                 if constexpr (KPT == 2) { PATCH_MID_WEIGHT_LOADS("global_load_dword"); }
@@ -161,12 +161,14 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
             for (int rb = 0; rb < RB; ++rb) {
                 mid_u32x4 x0 = {0u, 0u, 0u, 0u}, x1 = {0u, 0u, 0u, 0u};
                 asm volatile(
+                    "s_cmp_eq_u32 %[kind], 0\n\t"
+                    "s_cbranch_scc1 1f\n\t"
                     "s_mov_b64 %[sv], exec\n\t"
-                    "s_cmp_lg_u32 %[kind], 0\n\t"
-                    "s_cselect_b64 exec, %[xm], 0\n\t"
+                    "s_mov_b64 exec, %[xm]\n\t"
                     "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"
                     "global_load_dwordx4 %[x1], %[vx], %[sbx] offset:64\n\t"
-                    "s_mov_b64 exec, %[sv]"
+                    "s_mov_b64 exec, %[sv]\n\t"
+                    "1:"
                     : [x0] "+v"(x0), [x1] "+v"(x1), [sv] "=&s"(saved)
                     : [vx] "v"(voffx[rb]), [sbx] "s"(sbx), [kind] "s"(kind), [xm] "s"(xmask[rb])
                     : "memory", "scc");
