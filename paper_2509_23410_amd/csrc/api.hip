@@ -262,10 +262,11 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
 //     against 25.2; 13824 x 5120 25.7 against 46.3);
 //   12 .. 16 rows: with at least 160 groups (M = 16: 11008 x 4096 17.9 us against 19.9, 13824 x 5120 22.4 against
 //     29.8; M = 8: 18.2 against 15.9 and 22.9 against 24.3; 4096 x 4096: the strip kernel at every M <= 16).
-static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, int64_t groups) {
+//     (a set of three 4096 x 4096 weights, 192 groups: from 8 rows, 20.0 us against 20.5; equal at M = 1)
+static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, int64_t groups, bool set = false) {
     if (variant == 4) return true;
     if (variant != 0 || split_k != 0) return false;
-    if (rows <= 16) return rows >= 12 && groups >= 160;
+    if (rows <= 16) return rows >= (set ? 8 : 12) && groups >= 160;
     return mid_chunks > 1 || groups >= 80;
 }
 
@@ -481,7 +482,7 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     wide.units = groups;
     for (int64_t m0 = 0; m0 < M; m0 += kDecodeRows) {
         const int rows = (int)((M - m0 < kDecodeRows) ? M - m0 : kDecodeRows);
-        if (use_mid_kernel(rows, variant, split_k, 1, groups)) launch_mid_set(a, wide, m0, rows, 1, s);
+        if (use_mid_kernel(rows, variant, split_k, 1, groups, true)) launch_mid_set(a, wide, m0, rows, 1, s);
         else launch_decode_set(a, set, m0, rows, split_k, variant, s);
     }
     HIP_TRY(hipGetLastError());
