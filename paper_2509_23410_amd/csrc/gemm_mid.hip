@@ -123,8 +123,9 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
             const int j = k % KPT;
             const uint32_t e = ent[g];
             const int kind = (g < n) ? (int)(e & 1u) + 1 : 0;  // 0 = past the end, 1 = dense, 2 = 2:4
-            // positions: one 16-bit word per lane and step; with two steps per tile a lane's dword holds both and
-            // the odd step takes the upper half
+            // positions: one 16-bit word per lane and step; with two steps per tile the even step fetches the
+            // lane's dword for both and the odd step of the pass takes its upper half (a pass starts on an even step)
+            const int mkind = (KPT == 2 && (g & 1)) ? 0 : kind;
             const uint8_t* tb = payload + entry_offset(e);
             uint64_t saved;
 #pragma unroll
@@ -144,10 +145,12 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
         "global_load_dwordx4 %[v1], %[vo], %[sbw] offset:1024 nt\n\t"                                             \
         "s_branch 3f\n\t"                                                                                         \
         "1:\n\t"                                                                                                  \
+        "s_cmp_eq_u32 %[mkind], 2\n\t"                                                                            \
+        "s_cbranch_scc0 3f\n\t"                                                                                   \
         LDM " %[vi], %[vm], %[sbm] nt\n\t"                                                                        \
         "3:"                                                                                                       \
         : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi)                                                             \
-        : [vo] "v"(voff), [vm] "v"(voffm), [sbw] "s"(sbw), [sbm] "s"(sbm), [kind] "s"(kind)                       \
+        : [vo] "v"(voff), [vm] "v"(voffm), [sbw] "s"(sbw), [sbm] "s"(sbm), [kind] "s"(kind), [mkind] "s"(mkind)   \
         : "memory", "scc")
                 if constexpr (KPT == 2) { PATCH_MID_WEIGHT_LOADS("global_load_dword"); }
                 else { PATCH_MID_WEIGHT_LOADS("global_load_ushort"); }
@@ -196,8 +199,7 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
                     MidA a0, a1;
                     a0.raw = a[g][sb][0];
                     a1.raw = a[g][sb][1];
-                    const int jg = (base + g) % KPT;
-                    const uint32_t pos = (KPT == 2 && jg) ? (idx[g][sb] >> 16) : idx[g][sb];
+                    const uint32_t pos = (KPT == 2 && (g & 1)) ? (idx[g - 1][sb] >> 16) : idx[g][sb];
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         MidB bb;
