@@ -182,12 +182,17 @@ patch_status patch_export_canonical(const patch_packed* P, void* vals, size_t va
 
 /* Compressed weight bytes (values + positions; tables excluded): 2NK (1 - 7/16 * n_sparse / T). */
 size_t patch_packed_bytes(const patch_packed* P);
-/* Bytes of the per-tile tables the kernels read in addition (offset / type table). */
+/* Bytes of the per-tile tables the kernels read in addition (offset / type table, row order of the prefill launch). */
 size_t patch_table_bytes(const patch_packed* P);
 patch_status patch_packed_dims(const patch_packed* P, int64_t* N, int64_t* K, int* tile,
                                int64_t* n_sparse_tiles);
 /* HOST copy of the tile map held by P (N/tile * K/tile bytes). */
 patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, size_t bytes);
+/* The prefill launch order chosen from the tile map (tile 128; the schedule is left to the implementation by
+ * Appendix A): `order` (HOST) receives 2 * ceil(N / 256) tile-row indices, two per workgroup of 256 features, in
+ * launch order; -1 marks a missing second row.  *count = entries written (0 for tile 64); `cap` = entries `order`
+ * can hold, PATCH_ERR_SIZE if too few. */
+patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_t cap, size_t* count);
 
 void patch_free(patch_packed* P);
 const char* patch_strerror(patch_status s);

@@ -20,7 +20,7 @@ PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
-    "patch_packed_tile_map", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
+    "patch_packed_tile_map", "patch_packed_row_order", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
 
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.patch_table_bytes.restype = sz
         L.patch_packed_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ci), ctypes.POINTER(i64)]
         L.patch_packed_tile_map.argtypes = [vp, vp, sz]
+        L.patch_packed_row_order.argtypes = [vp, vp, sz, ctypes.POINTER(sz)]
         L.patch_free.argtypes = [vp]
         L.patch_free.restype = None
         L.patch_strerror.argtypes = [ci]
@@ -73,7 +74,7 @@ def lib() -> ctypes.CDLL:
         L.patch_last_hip_error.restype = ci
         L.patch_version.restype = ctypes.c_char_p
         for f in ("patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_unpack", "patch_canonical_sizes",
-                  "patch_export_canonical", "patch_packed_dims", "patch_packed_tile_map"):
+                  "patch_export_canonical", "patch_packed_dims", "patch_packed_tile_map", "patch_packed_row_order"):
             getattr(L, f).restype = ci
         _lib = L
     return _lib
@@ -150,6 +151,14 @@ class Packed:
         out = np.empty((N // t, K // t), np.uint8)
         _check(lib().patch_packed_tile_map(self.handle, out.ctypes.data, out.size), "patch_packed_tile_map")
         return out
+
+    def row_order(self) -> np.ndarray:
+        """(workgroups, 2) tile-row indices in prefill launch order, -1 = no second row; empty for tile 64."""
+        N, K, t, _ = self.dims()
+        out = np.empty(2 * ((N // t + 1) // 2), np.int32)
+        n = ctypes.c_size_t(0)
+        _check(lib().patch_packed_row_order(self.handle, out.ctypes.data, out.size, ctypes.byref(n)), "patch_packed_row_order")
+        return out[: n.value].reshape(-1, 2)
 
 
 def patch_pack(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> Packed:

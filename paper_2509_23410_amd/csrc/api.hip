@@ -502,7 +502,7 @@ patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream) {
 }
 
 size_t patch_packed_bytes(const patch_packed* P) { return P ? P->payload_bytes : 0; }
-size_t patch_table_bytes(const patch_packed* P) { return P ? P->table.size() * sizeof(uint32_t) : 0; }
+size_t patch_table_bytes(const patch_packed* P) { return P ? (P->table.size() + P->pairs.size()) * sizeof(uint32_t) : 0; }
 
 patch_status patch_packed_dims(const patch_packed* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles) {
     if (!P) return PATCH_ERR_ARG;
@@ -517,6 +517,14 @@ patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, siz
     if (!P || !tile_map) return PATCH_ERR_ARG;
     if (bytes < P->tile_map.size()) return PATCH_ERR_SIZE;
     memcpy(tile_map, P->tile_map.data(), P->tile_map.size());
+    return PATCH_OK;
+}
+
+patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_t cap, size_t* count) {
+    if (!P || !order || !count) return PATCH_ERR_ARG;
+    if (cap < P->pairs.size()) return PATCH_ERR_SIZE;
+    if (!P->pairs.empty()) memcpy(order, P->pairs.data(), P->pairs.size() * sizeof(int32_t));
+    *count = P->pairs.size();
     return PATCH_OK;
 }
 

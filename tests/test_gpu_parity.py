@@ -522,3 +522,40 @@ def test_prefill_structured_tile_maps(dev, pattern):
         assert np.isfinite(Yh).all(), "a tile row was not written"
         assert relF(Yh, Yo) <= TIGHT
     P.close()
+
+
+def test_row_order_is_a_permutation_and_pairs_common_24_steps(dev):
+    """The prefill launch order the packer derives from the tile map: every tile row exactly once, -1 only as the
+    partner of the one unpaired row of an odd count; on a random map the chosen pairs share more 2:4 steps than
+    adjacent rows do; on a banded map every pair is of one kind."""
+    t = 128
+    for N, K, f in [(1664, 1024, 0.6), (1536, 4096, 0.5), (128, 256, 0.5)]:
+        c = synth.make_case("order", N, K, 1, t, f, seed=23)
+        p = Prepared(c, dev)
+        order = p.P.row_order()
+        Tn = N // t
+        assert order.shape == ((Tn + 1) // 2, 2)
+        rows = order[order >= 0]
+        assert sorted(rows.tolist()) == list(range(Tn))
+        assert int((order < 0).sum()) == Tn % 2 and (order[:, 0] >= 0).all()
+        sp = c.tile_map == 0
+        both = lambda a, b: int((sp[a] & sp[b]).sum())
+        chosen = sum(both(a, b) for a, b in order if b >= 0)
+        adjacent = sum(both(2 * i, 2 * i + 1) for i in range(Tn // 2))
+        print(f"row order N={N} K={K}: common 2:4 steps chosen {chosen} adjacent {adjacent}", flush=True)
+        assert chosen >= adjacent
+        p.P.close()
+    tm = np.ones((12, 8), np.uint8)
+    tm[[0, 3, 4, 7, 9, 10]] = 0                      # six tile rows all 2:4, six all dense, interleaved
+    c = synth.make_case("order_bands", 12 * t, 8 * t, 1, t, 0.5, seed=24)
+    W = to_dev_bf16(c.W, dev)
+    W_hat = torch.empty_like(W)
+    B.patch_apply_mask(W, torch.from_numpy(c.mask24).to(dev), tm, 12 * t, 8 * t, t, W_hat, stream())
+    P = B.patch_pack(W_hat, 12 * t, 8 * t, tm, t, stream())
+    for a, b in P.row_order():
+        assert tm[a, 0] == tm[b, 0], "a 2:4 row was paired with a dense one although an equal partner existed"
+    P.close()
+    c64 = synth.make_case("order64", 256, 256, 1, 64, 0.5, seed=25)
+    p64 = Prepared(c64, dev)
+    assert p64.P.row_order().size == 0                # tile 64: no prefill row order
+    p64.P.close()
