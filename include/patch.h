@@ -56,8 +56,9 @@ typedef struct {
                  /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto.       */
                  /* prefill (tile 128): K slices per output tile, one workgroup each, whose partial  */
                  /* products go to `workspace` and are summed in slice order by a second launch;     */
-                 /* 0 = auto (1 unless the tile grid would leave a third of the chip idle), 1 = no   */
-                 /* split.  Never more slices than the workspace holds: without one, no split.       */
+                 /* 0 = auto (1 unless the tile grid would leave a third of the chip idle; with a    */
+                 /* workspace a part-filled last round of at most half the chip is split on its own), */
+                 /* 1 = no split.  Never more slices than the workspace holds: without one, no split. */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
                  /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
                  /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
@@ -143,8 +144,9 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
                         void* stream, int reps, patch_gemm_opts* best, float* best_us);
 
 /* Bytes of patch_gemm_opts.workspace the product with these M, P and opts (path, split_k; NULL = defaults) would
- * use if it were given enough: slices x M x N x 4 for a split prefill launch, chunks x min(M, 64) x N x 4 for
- * decode passes of 17 .. 64 rows, else 0. */
+ * use if it were given enough: slices x M x N x 4 for a split prefill launch, slices x tiles x 256 KB when only the
+ * part-filled last round of a prefill launch is split, chunks x min(M, 64) x N x 4 for decode passes of 17 .. 64
+ * rows, else 0. */
 size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts);
 
 /*

@@ -406,7 +406,11 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
     if (variant != 0 && variant != 3) return 0;
     if (!prefill_wreg_supports(a)) return 0;
     const int s = prefill_wreg_split(a, split_k);
-    return s > 1 ? (size_t)s * (size_t)M * (size_t)P->N * sizeof(float) : 0;
+    if (s > 1) return (size_t)s * (size_t)M * (size_t)P->N * sizeof(float);
+    if (split_k != 0) return 0;
+    int tail = 0;
+    const int ts = prefill_wreg_tail(a, &tail);   // K slices for the part-filled last round only
+    return ts > 1 ? (size_t)ts * (size_t)tail * 256 * 256 * sizeof(float) : 0;
 }
 
 patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count, void* stream,

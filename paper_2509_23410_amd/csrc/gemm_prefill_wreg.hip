@@ -189,11 +189,61 @@ __device__ __forceinline__ uint64_t wr_uniform64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// SPLIT: the launch splits K over gridDim.y workgroups per output tile (a grid of tiles alone would leave most of the
-// chip idle); slice y writes its partial product to Y + y * M * N (a workspace), wr_reduce_kernel sums the slices.
-template <bool SPLIT>
+// Tile t of the launch order -> feature block bn (256 features), row block bm (256 rows): groups of 4 row blocks x
+// all feature blocks, so that the workgroups an XCD runs at a time cover about 8 feature blocks x 4 row blocks
+// and share both operands in its L2.
+__device__ __forceinline__ void wr_tile_of(int t, int tiles_n, int tiles_m, int& bn, int& bm) {
+    constexpr int GM = 4;
+    const int full = (tiles_m / GM) * GM * tiles_n;
+    if (t < full) {
+        const int g = t / (GM * tiles_n), rem = t % (GM * tiles_n);
+        bn = rem / GM;
+        bm = g * GM + rem % GM;
+    } else {
+        const int gm = tiles_m % GM, rem = t - full;
+        bn = rem / gm;
+        bm = (tiles_m / GM) * GM + rem % gm;
+    }
+}
+
+// Sum of the partial tiles of a MODE 2 launch (slot (t - t0) * slices + y, 256 rows x 256 features each, slice 0
+// first) into Y.  Block = 16 rows of one tile; thread = 4 x 4 features of one row.
+__global__ __launch_bounds__(256) void wr_tail_reduce_kernel(const float* __restrict__ ws, int slices, int t0, int tiles_n, int tiles_m,
+                                                             int64_t M, int64_t N, const uint32_t* __restrict__ table, int Tk_all,
+                                                             float* __restrict__ Y) {
+    const int j = blockIdx.x >> 4, chunk = blockIdx.x & 15;
+    int bn, bm;
+    wr_tile_of(t0 + j, tiles_n, tiles_m, bn, bm);
+    const int32_t* pairs = reinterpret_cast<const int32_t*>(table) + (N / 128) * (int64_t)Tk_all;
+    const int r = 16 * chunk + (threadIdx.x >> 4);
+    const int64_t m = (int64_t)bm * kWrBM + r;
+    if (m >= M) return;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int f = (threadIdx.x & 15) * 4 + 64 * u;   // feature inside the 256-feature block
+        const int row = pairs[2 * bn + (f >> 7)];
+        if (row < 0) continue;                           // no second tile row
+        const float* src = ws + (int64_t)j * slices * (kWrBM * kWrBN) + r * kWrBN + f;
+        wr_f32x4 acc = *reinterpret_cast<const wr_f32x4*>(src);
+        for (int y = 1; y < slices; ++y) {
+            const wr_f32x4 v = *reinterpret_cast<const wr_f32x4*>(src + (int64_t)y * (kWrBM * kWrBN));
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        *reinterpret_cast<wr_f32x4*>(Y + m * N + (int64_t)row * 128 + (f & 127)) = acc;
+    }
+}
+
+// The launch covers tiles t0 .. t0 + cnt - 1 of the order above.
+// MODE 0: whole K, results to Y.
+// MODE 1: K split over gridDim.y workgroups per output tile (a grid of tiles alone would leave most of the chip
+//         idle); slice y writes its partial product to Y + y * M * N (a workspace), wr_reduce_kernel sums the slices.
+// MODE 2: the same split for the last few tiles of a launch whose tile count is a little more than a multiple of the
+//         CU count (a part-filled last round): slice y of tile t writes a 256 x 256 partial tile to slot
+//         (t - t0) * gridDim.y + y of the workspace, wr_tail_reduce_kernel sums the slots into Y.
+template <int MODE>
 __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t K, int Tk_all, int tiles_n,
-                                                           int tiles_m, const WeightSet set) {
+                                                           int tiles_m, int t0, int cnt, const WeightSet set) {
+    constexpr bool SPLIT = MODE != 0;
     constexpr int TILE = 128;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
@@ -202,33 +252,18 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     const int tr = w >> 1, sh = w & 1;  // tile row of the block, half (4 strips) of the tile
     const int col = lane & 15, q = lane >> 4;
 
-    // ---- block -> (n, m) tile of the output.  Consecutive blocks go to different XCDs (hardware round-robin),
-    // each with its own L2, so every XCD gets a contiguous run of the tile order below, and that order walks
-    // groups of 4 row blocks x all feature blocks: the workgroups an XCD runs at a time then cover about
-    // 8 feature blocks x 4 row blocks and share both operands in L2.
-    const int nblk = tiles_n * tiles_m;
+    // ---- block -> tile of the launch order.  Consecutive blocks go to different XCDs (hardware round-robin), each
+    // with its own L2, so every XCD gets a contiguous run of this launch's part of the order.
     int bid = blockIdx.x;
     {
-        const int per = (nblk + 7) / 8;
+        const int per = (cnt + 7) / 8;
         const int x = bid & 7, i = bid >> 3;
         const int t = x * per + i;
-        bid = (i < per && t < nblk) ? t : -1;
+        bid = (i < per && t < cnt) ? t0 + t : -1;
     }
     if (bid < 0) return;
     int bn, bm;
-    {
-        constexpr int GM = 4;
-        const int full = (tiles_m / GM) * GM * tiles_n;
-        if (bid < full) {
-            const int g = bid / (GM * tiles_n), rem = bid % (GM * tiles_n);
-            bn = rem / GM;
-            bm = g * GM + rem % GM;
-        } else {
-            const int gm = tiles_m % GM, rem = bid - full;
-            bn = rem / gm;
-            bm = (tiles_m / GM) * GM + rem % gm;
-        }
-    }
+    wr_tile_of(bid, tiles_n, tiles_m, bn, bm);
     // which weight of the set the feature block belongs to: scalar selects, made explicitly uniform, so that the
     // weight addresses stay in scalar registers
     const uint8_t* __restrict__ payload = set.payload[0];
@@ -516,16 +551,17 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
         const int64_t m = m0 + 16 * CB + col;                                                                      \
-        float* yrow = Y + (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;                                                 \
+        float* yrow = MODE == 2 ? Y + ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + col) * kWrBN + 128 * tr + 64 * sh + 4 * q \
+                                : Y + (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;         \
         float v[4];                                                                                                \
         PATCH_WR_READ(0, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(1, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(2, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
         PATCH_WR_READ(3, CB);                                                                                      \
-        if (m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
     }
         PATCH_WR_16(PATCH_WR_STORE)
 #undef PATCH_WR_STORE
@@ -559,13 +595,40 @@ int prefill_wreg_split(const GemmArgs& a, int requested) {
     return s < 2 ? 1 : s;
 }
 
+// A launch whose tile count is a little more than a multiple of the CU count ends with a part-filled round that
+// lasts as long as a full one.  With a workspace the last `tail` tiles (at most half a round) are cut into K slices
+// that fill the chip once: returns the slice count (1 = no such split) and sets *tail.  It pays when the part of a
+// round it saves outweighs writing and re-reading the partial tiles (an estimate from measured rates: 1.3 us per
+// step, 3 TB/s for the partials, 8 us for the two extra launches).
+int prefill_wreg_tail(const GemmArgs& a, int* tail) {
+    const int tiles = (int)(((a.N + kWrBN - 1) / kWrBN) * ((a.M + kWrBM - 1) / kWrBM));
+    const int t = tiles % a.n_cus;
+    *tail = 0;
+    if (!a.ws || tiles < a.n_cus || t == 0 || 2 * t > a.n_cus) return 1;
+    int s = a.n_cus / t;
+    if (s > 8) s = 8;
+    if (s > a.Tk / 4) s = a.Tk / 4;
+    const size_t per_slot = (size_t)kWrBM * kWrBN * sizeof(float);
+    while (s >= 2 && (size_t)t * (size_t)s * per_slot > a.ws_bytes) --s;
+    if (s < 2) return 1;
+    const double round_us = 2.0 * a.Tk * 1.3;
+    const double gain_us = round_us * (1.0 - 1.0 / s);
+    const double cost_us = 2.0 * (double)t * s * per_slot / 3.0e6 + 8.0;
+    if (gain_us <= cost_us) return 1;
+    *tail = t;
+    return s;
+}
+
 static void wr_grant_lds() {
-    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<false>),
+    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<0>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
-    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<true>),
+    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<1>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
+    static const hipError_t granted2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_wreg<2>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWrLds);
     (void)granted0;
     (void)granted1;
+    (void)granted2;
 }
 
 void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t stream) {
@@ -586,13 +649,27 @@ void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
     set.N[0] = a.N;
     set.count = 1;
     set.units = tiles_n;
-    if (split == 1) {
+    int tail = 0;
+    const int tail_split = (split == 1 && split_k == 0) ? prefill_wreg_tail(a, &tail) : 1;
+    if (split == 1 && tail_split > 1) {
+        // all full rounds unsplit, then the part-filled round in K slices over the whole chip, then their sum
+        const int body = nblk - tail;
         set.Y[0] = a.Y;
-        hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n, tiles_m, set);
+        hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(((body + 7) / 8) * 8), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
+                           tiles_m, 0, body, set);
+        set.Y[0] = a.ws;
+        hipLaunchKernelGGL(prefill_kernel_wreg<2>, dim3(((tail + 7) / 8) * 8, tail_split), dim3(256), kWrLds, stream, a.X, a.M, a.K,
+                           a.Tk, tiles_n, tiles_m, body, tail, set);
+        hipLaunchKernelGGL(wr_tail_reduce_kernel, dim3(tail * 16), dim3(256), 0, stream, a.ws, tail_split, body, tiles_n, tiles_m, a.M,
+                           a.N, a.table, a.Tk, a.Y);
+    } else if (split == 1) {
+        set.Y[0] = a.Y;
+        hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n, tiles_m, 0, nblk,
+                           set);
     } else {
         set.Y[0] = a.ws;
-        hipLaunchKernelGGL(prefill_kernel_wreg<true>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
-                           tiles_m, set);
+        hipLaunchKernelGGL(prefill_kernel_wreg<1>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
+                           tiles_m, 0, nblk, set);
         wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, stream);
     }
 }
@@ -602,7 +679,8 @@ void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_
     const int tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
     const int nblk = set.units * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    hipLaunchKernelGGL(prefill_kernel_wreg<false>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, set.units, tiles_m, set);
+    hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, set.units, tiles_m, 0, nblk,
+                       set);
 }
 
 }  // namespace patch

@@ -61,6 +61,8 @@ void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t str
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream);
 bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB
 int prefill_wreg_split(const GemmArgs& a, int requested);       // K slices per output tile the launch will use
+// K slices for the last *tail tiles of an unsplit launch with a part-filled last round (needs a.ws); 1 = none
+int prefill_wreg_tail(const GemmArgs& a, int* tail);
 void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream);
 // The same for a set of weights, never split; a supplies X, M, K, tile, Tk, n_cus.  All of the set must pass
 // prefill_wreg_supports with these M, K.

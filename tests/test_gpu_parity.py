@@ -559,3 +559,27 @@ def test_row_order_is_a_permutation_and_pairs_common_24_steps(dev):
     p64 = Prepared(c64, dev)
     assert p64.P.row_order().size == 0                # tile 64: no prefill row order
     p64.P.close()
+
+
+def test_prefill_part_filled_last_round_is_split(dev):
+    """270 output tiles on 256 compute units: with a workspace the last 14 tiles are cut into K slices of their own
+    (partial tiles in workspace slots, summed by a third launch).  Sampled checks against the oracle, with and
+    without the workspace; rows outside the tail tiles are bit-equal between the two."""
+    N, K, M, t = 2560, 2048, 6912 - 40, 128       # 10 feature blocks x 27 row blocks (the last one ragged)
+    c = synth.make_case("tail", N, K, M, t, 0.5, seed=31)
+    p = Prepared(c, dev)
+    need = B.patch_gemm_workspace_bytes(M, p.P, path=B.PATH_PREFILL)
+    print(f"tail split workspace: {need} bytes", flush=True)
+    assert need > 0 and need % (256 * 256 * 4) == 0
+    ws = torch.empty(need // 4, device=dev, dtype=torch.float32)
+    Y0 = p.gemm(c.X, path=B.PATH_PREFILL)
+    Y1 = p.gemm(c.X, path=B.PATH_PREFILL, workspace=ws)
+    rng = np.random.default_rng(5)
+    _sampled_checks(p, c, c.X, Y0, rng, n_points=1024, n_rows=8)
+    _sampled_checks(p, c, c.X, Y1, rng, n_points=1024, n_rows=8)
+    same = (Y0 == Y1).all(axis=1)
+    assert same.mean() > 0.5 and relF(Y1, Y0.astype(np.float64)) <= TIGHT
+    assert np.array_equal(Y1, p.gemm(c.X, path=B.PATH_PREFILL, workspace=ws)), "not reproducible"
+    small = ws[: (need // 4) // 2 + 3]           # room for fewer slices: still correct
+    assert relF(p.gemm(c.X, path=B.PATH_PREFILL, workspace=small), Y0.astype(np.float64)) <= TIGHT
+    p.P.close()
