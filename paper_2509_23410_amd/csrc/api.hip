@@ -349,6 +349,7 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
         add(PATCH_PATH_PREFILL, 1, 0, false);
         add(PATCH_PATH_PREFILL, 1, 2, false);
         const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+        if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic: may split a part-filled last round only
         if (workspace)
             for (int sk : {2, 3, 4, 6, 8, 12, 16})
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 2 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
