@@ -434,6 +434,8 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     a.M = M; a.K = P[0]->K; a.N = P[0]->N;
     a.tile = P[0]->tile; a.Tk = P[0]->Tk;
     a.n_cus = P[0]->n_cus;
+    if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
+    if (opts && opts->workspace && split_k == 0) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_PREFILL && count > 1 && (variant == 0 || variant == 3) && split_k <= 1 && prefill_wreg_supports(a)) {
         // one launch over the feature blocks of all weights - unless the blocks are so few that splitting K pays
         // (then one split launch per weight, below)

@@ -63,9 +63,11 @@ bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <
 int prefill_wreg_split(const GemmArgs& a, int requested);       // K slices per output tile the launch will use
 // K slices for the last *tail tiles of an unsplit launch with a part-filled last round (needs a.ws); 1 = none
 int prefill_wreg_tail(const GemmArgs& a, int* tail);
+int prefill_wreg_tail_of(int tiles, const GemmArgs& a, int* tail);   // the same for a given tile count (sets of weights)
 void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream);
-// The same for a set of weights, never split; a supplies X, M, K, tile, Tk, n_cus.  All of the set must pass
-// prefill_wreg_supports with these M, K.
+// The same for a set of weights; a supplies X, M, K, tile, Tk, n_cus and, optionally, ws / ws_bytes (then a
+// part-filled last round is split as in launch_prefill_wreg).  All of the set must pass prefill_wreg_supports with
+// these M, K.
 void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_t stream);
 
 }  // namespace patch

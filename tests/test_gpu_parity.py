@@ -583,3 +583,29 @@ def test_prefill_part_filled_last_round_is_split(dev):
     small = ws[: (need // 4) // 2 + 3]           # room for fewer slices: still correct
     assert relF(p.gemm(c.X, path=B.PATH_PREFILL, workspace=small), Y0.astype(np.float64)) <= TIGHT
     p.P.close()
+
+
+def test_prefill_set_with_split_last_round(dev):
+    """Two weights sharing X in one prefill launch whose 270 tiles end in a part-filled round: with a workspace the
+    last tiles (of both weights) are split in K; every output against the oracle on samples, and equal to the
+    unsplit set launch within rounding."""
+    K, M, t = 2048, 6912 - 40, 128
+    cases = [synth.make_case(f"tailset{i}", N, K, M, t, f, seed=33) for i, (N, f) in enumerate([(1280, 0.5), (1280, 0.8)])]
+    X = cases[0].X
+    preps = [Prepared(c, dev) for c in cases]
+    Xd = to_dev_bf16(X, dev)
+    ws = torch.empty(8 * 16 * 256 * 256, device=dev, dtype=torch.float32)
+    outs = {}
+    for label, kw in (("plain", dict()), ("workspace", dict(workspace=ws))):
+        Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, **kw)
+        torch.cuda.synchronize()
+        outs[label] = [Y.cpu().numpy() for Y in Ys]
+    rng = np.random.default_rng(6)
+    for i, (p, c) in enumerate(zip(preps, cases)):
+        _sampled_checks(p, c, X, outs["workspace"][i], rng, n_points=1024, n_rows=8)
+        assert relF(outs["workspace"][i], outs["plain"][i].astype(np.float64)) <= TIGHT
+    # the last tiles of the launch order belong to the second weight: its sums were formed in a different order
+    assert any(not np.array_equal(a_, b_) for a_, b_ in zip(outs["workspace"], outs["plain"])), "the last round was not split"
+    for p in preps:
+        p.P.close()
