@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -281,6 +281,53 @@ def main():
                     P_.close()
                 del W_hat
         out["decode_mlp"] = dict(rows=mlp, note="7B MLP projections, M = 1, rotating packed copies")
+        # one 7B decoder layer's seven projections at M = 1 (q/k/v in one launch, o, gate/up in one launch, down),
+        # eager and as a captured HIP graph, rotating over copies of the layer so that no cache holds the weights
+        if "layer" not in skip:
+            lrows = []
+            for fd in (0.0, 0.5):
+                shapes7 = [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o", 4096, 4096),
+                           ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
+                copies, nbytes = 3, 0
+                layer = [dict() for _ in range(copies)]
+                for name, N_, K_ in shapes7:
+                    cl = synth.make_case("llama7b_layer_" + name, N_, K_, 1, t, fd, seed=0)
+                    W_hat, P0 = masked_packed(cl)
+                    nbytes += P0.nbytes
+                    for ci in range(copies):
+                        layer[ci][name] = P0 if ci == 0 else B.patch_pack(W_hat, N_, K_, cl.tile_map, t, stream)
+                    del W_hat
+                x4, x11 = dev_bf16(synth.make_case("llama7b_layer_x", 128, 4096, 1, t, 0.0, seed=1).X), None
+                x11 = dev_bf16(synth.make_case("llama7b_layer_x2", 128, 11008, 1, t, 0.0, seed=2).X)
+                y = {n: torch.empty((1, N_), device=dev, dtype=torch.float32) for n, N_, _ in shapes7}
+
+                def layer_pass(L, st):
+                    B.patch_gemm_many(x4, 1, [L["q"], L["k"], L["v"]], [y["q"], y["k"], y["v"]], st)
+                    B.patch_gemm(x4, 1, L["o"], y["o"], st)
+                    B.patch_gemm_many(x4, 1, [L["gate"], L["up"]], [y["gate"], y["up"]], st)
+                    B.patch_gemm(x11, 1, L["down"], y["down"], st)
+
+                fn = lambda i: layer_pass(layer[i % copies], stream)
+                timed(fn, 12)
+                eager_us = sorted(timed(fn, 60) / 60 for _ in range(3))[1] * 1e6
+                side = torch.cuda.Stream()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(graph, stream=side):
+                        for ci in range(copies):
+                            layer_pass(layer[ci], side.cuda_stream)
+                timed(lambda i: graph.replay(), 4)
+                graph_us = sorted(timed(lambda i: graph.replay(), 20) / (20 * copies) for _ in range(3))[1] * 1e6
+                lrows.append(dict(f=fd, M=1, packed_MB=round(nbytes / 1e6, 1), launches=4, us_eager=round(eager_us, 2),
+                                  us_graph=round(graph_us, 2), GBps_graph=round(nbytes / (graph_us * 1e-6) / 1e9, 1),
+                                  frac_hbm_graph=round(nbytes / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
+                del graph
+                for L in layer:
+                    for P_ in L.values():
+                        P_.close()
+            out["decode_layer_7b"] = dict(rows=lrows, note="the seven projections of one 7B decoder layer at M = 1 in four launches "
+                                          "(q/k/v fused, o, gate/up fused, down), per layer; graph = one captured HIP graph of three "
+                                          "layer copies replayed")
         m1 = [r_ for r_ in dec if r_["M"] == 1 and r_["f"] == 0.0][0]
         dtraffic = None
         dpath = os.path.join(ROOT, "profiles", "decode_traffic.json")

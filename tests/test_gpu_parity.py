@@ -609,3 +609,39 @@ def test_prefill_set_with_split_last_round(dev):
     assert any(not np.array_equal(a_, b_) for a_, b_ in zip(outs["workspace"], outs["plain"])), "the last round was not split"
     for p in preps:
         p.P.close()
+
+
+def test_hip_graph_replay_matches_eager(dev):
+    """The product calls allocate nothing, never synchronise and record no memset: a HIP graph captured over a decode
+    launch, a batched-decode pass with K chunks (two launches), a split prefill launch (two launches) and a plain one
+    replays bit-equal to the eager results, several times, with eager work between the replays."""
+    c = synth.make_case("graph", 768, 1024, 300, 128, 0.5, seed=41)
+    p = Prepared(c, dev)
+    X = to_dev_bf16(c.X, dev)
+    ws = torch.empty(8 * 300 * 768, device=dev, dtype=torch.float32)
+    jobs = [(1, dict()), (40, dict(path=B.PATH_DECODE, workspace=ws)), (300, dict(path=B.PATH_PREFILL, workspace=ws)),
+            (300, dict(path=B.PATH_PREFILL))]
+    eager = []
+    for M, kw in jobs:                         # also the warm-up every kernel needs before a capture
+        Y = torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32)
+        B.patch_gemm(X, M, p.P, Y, stream(), **kw)
+        eager.append(Y)
+    torch.cuda.synchronize()
+    outs = [torch.full_like(Y, float("nan")) for Y in eager]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for (M, kw), Y in zip(jobs, outs):
+                B.patch_gemm(X, M, p.P, Y, side.cuda_stream, **kw)
+    for rep in range(3):
+        for Y in outs:
+            Y.fill_(float("nan"))
+        scratch = p.gemm(c.X[:7])               # eager work (and a synchronisation) between the replays
+        assert np.isfinite(scratch).all()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (M, kw), Y, E in zip(jobs, outs, eager):
+            assert torch.equal(Y, E), f"replay {rep}: M={M} differs from the eager launch"
+    assert relF(outs[2].cpu().numpy(), p.oracle_gemm(c.X)) <= TIGHT
+    p.P.close()
