@@ -83,7 +83,8 @@ typedef struct {
  *               lexicographic order of the kept positions (0,1) (0,2) (0,3) (1,2) (1,3) (2,3).
  *   P_tile   HOST, (N/tile) x (K/tile) fp32, row-major        tile_map  HOST out, same shape, bytes (for patch_pack)
  *   P_24     DEVICE, 6 x (N K / 4) fp32, row c = logits of candidate c for all groups, 4-byte aligned
- *   mask24   DEVICE out, N x K bytes, 1 = keep, 4-byte aligned (input of patch_apply_mask)
+ *   mask24   DEVICE out, N x K bytes, 1 = keep, 8-byte aligned (the input of patch_apply_mask, which reads it in
+ *            8-byte pieces)
  * tile_map is complete on return; mask24 is written asynchronously on `stream`.  Errors: PATCH_ERR_ARG,
  * PATCH_ERR_SHAPE (as patch_apply_mask), PATCH_ERR_HIP.
  */
@@ -93,18 +94,20 @@ patch_status patch_hard_masks(const float* P_tile, const void* P_24, int64_t N, 
 /*
  * Merge of the hard masks and pruning of the weights (Algorithm 1, last three lines; Eq. 4 with hard
  * masks):  M* = M_tile + (1 - M_tile) (.) M_24,  W_hat = W (.) M*.
- *   W      DEVICE, N x K bf16
- *   mask24 DEVICE, N x K bytes, nonzero = keep (used only inside tiles whose tile_map entry is 0)
- *   W_hat  DEVICE, N x K bf16 (may alias W); pruned entries are written as +0
+ *   W      DEVICE, N x K bf16, 16-byte aligned
+ *   mask24 DEVICE, N x K bytes, nonzero = keep (used only inside tiles whose tile_map entry is 0), 8-byte aligned
+ *   W_hat  DEVICE, N x K bf16, 16-byte aligned; either W itself (in place) or a buffer that does not overlap W;
+ *          pruned entries are written as +0
+ * Misaligned pointers: PATCH_ERR_ARG.
  * Synchronous: uploads the tile map, runs on `stream` and waits for it (a one-off conversion step).
  */
 patch_status patch_apply_mask(const void* W, const void* mask24, const uint8_t* tile_map, int64_t N,
                               int64_t K, int tile, void* W_hat, void* stream);
 
 /*
- * Compression (Appendix A: "matrix compression and metadata generation are determined by the chosen
- * tile size"): 2:4 tiles become kept values + 2-bit positions laid out for the gfx950 sparse matrix
- * instructions; dense tiles are re-ordered into matrix-instruction operand order.
+ * Compression (Appendix A: the compressed values and the position metadata depend on the tile size, which is
+ * therefore fixed at pack time): 2:4 tiles become kept values + 2-bit positions laid out for the gfx950 sparse
+ * matrix instructions; dense tiles are re-ordered into matrix-instruction operand order.
  *   W_hat  DEVICE, N x K bf16, already pruned.
  *   tile   64 or 128; N and K must be multiples of it.
  *   *out   receives a new patch_packed on success, untouched otherwise.
@@ -167,11 +170,13 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
 patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const* P, void* const* Y, int count,
                              void* stream, const patch_gemm_opts* opts);
 
-/* Decompression back to a row-major N x K bf16 matrix (DEVICE).  Dropped positions become +0. */
+/* Decompression back to a row-major N x K bf16 matrix (DEVICE, 16-byte aligned).  Dropped positions become +0.
+ * This project's hook for round-trip tests (the inverse of the Appendix A compression step); the paper defines no
+ * such call. */
 patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream);
 
 /*
- * Test hook: the compressed matrix in the layout-independent canonical order.
+ * Test hook (this project's; no passage of the paper): the compressed matrix in the layout-independent canonical order.
  *   vals (HOST, uint16): tiles in row-major tile order; dense tile = its tile*tile elements row-major;
  *                        2:4 tile = per row, per group along K, the two kept elements, ascending position.
  *   meta (HOST, bytes) : 2:4 tiles only, same order; per group one nibble pos0 | pos1 << 2 (pos0 < pos1),
@@ -182,7 +187,8 @@ patch_status patch_canonical_sizes(const patch_packed* P, size_t* vals_bytes, si
 patch_status patch_export_canonical(const patch_packed* P, void* vals, size_t vals_bytes, void* meta,
                                     size_t meta_bytes);
 
-/* Compressed weight bytes (values + positions; tables excluded): 2NK (1 - 7/16 * n_sparse / T). */
+/* Getters, lifetime and diagnostics below are this project's (no passage of the paper).
+ * Compressed weight bytes (values + positions; tables excluded): 2NK (1 - 7/16 * n_sparse / T). */
 size_t patch_packed_bytes(const patch_packed* P);
 /* Bytes of the per-tile tables the kernels read in addition (offset / type table, row order of the prefill launch). */
 size_t patch_table_bytes(const patch_packed* P);

@@ -112,6 +112,8 @@ def _map_host(tile_map) -> np.ndarray:
 
 def patch_apply_mask(W, mask24, tile_map, N: int, K: int, tile: int, W_hat, stream: int = 0) -> None:
     tm = _map_host(tile_map)
+    if N > 0 and K > 0 and tile > 0 and N % tile == 0 and K % tile == 0 and tm.size != (N // tile) * (K // tile):
+        raise PatchError(ERR_ARG, "patch_apply_mask: tile_map has the wrong number of entries")
     _check(lib().patch_apply_mask(_ptr(W), _ptr(mask24), tm.ctypes.data, N, K, tile, _ptr(W_hat), stream), "patch_apply_mask")
 
 
@@ -188,14 +190,21 @@ def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, 
 
 
 def patch_tune(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, stream: int = 0, reps: int = 20):
-    """-> (dict(path, split_k, variant), microseconds per launch) of the fastest schedule; pass the dict (and the same
-    workspace) to patch_gemm."""
+    """-> (dict(path, split_k, variant, uses_workspace), microseconds per launch) of the fastest schedule.  Run it with
+    run_tuned(): the winner is either a schedule timed with the workspace (pass the same one again) or one timed without
+    (pass none: with a workspace the library might pick K chunks the tuner never timed)."""
     if workspace is not None and workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size()
     o, us = GemmOpts(), ctypes.c_float(0)
     _check(lib().patch_tune(_ptr(X), M, P.handle, _ptr(Y), _ptr(workspace) if workspace is not None else None,
                             workspace_bytes or 0, stream, reps, ctypes.byref(o), ctypes.byref(us)), "patch_tune")
-    return dict(path=o.path, split_k=o.split_k, variant=o.variant), float(us.value)
+    return dict(path=o.path, split_k=o.split_k, variant=o.variant, uses_workspace=bool(o.workspace)), float(us.value)
+
+
+def run_tuned(X, M: int, P: Packed, Y, tuned: dict, workspace=None, stream: int = 0) -> None:
+    """patch_gemm with exactly the schedule patch_tune returned."""
+    patch_gemm(X, M, P, Y, stream, path=tuned["path"], split_k=tuned["split_k"], variant=tuned["variant"],
+               workspace=workspace if tuned["uses_workspace"] else None)
 
 
 def patch_gemm_workspace_bytes(M: int, P: Packed, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> int:

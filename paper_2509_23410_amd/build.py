@@ -23,9 +23,7 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_lib(verbose: bool = False, extra_flags=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -34,6 +32,22 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out:
         print(out)
+
+
+def build_lib(verbose: bool = False, extra_flags=()) -> str:
+    """Compile every source (each to an object of its own, side by side) and link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    jobs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        jobs.append((obj, [hipcc, *flags, *extra_flags, "-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", obj, src]))
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+        list(pool.map(lambda j: _run(j[1], verbose), jobs))
+    _run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *[j[0] for j in jobs]], verbose)
     return LIB
 
 

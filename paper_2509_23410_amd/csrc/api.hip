@@ -162,7 +162,7 @@ patch_status patch_hard_masks(const float* P_tile, const void* P_24, int64_t N, 
     if (!P_tile || !P_24 || !tile_map || !mask24) return PATCH_ERR_ARG;
     patch_status st = check_shape(N, K, tile);
     if (st != PATCH_OK) return st;
-    if ((reinterpret_cast<uintptr_t>(P_24) & 3u) || (reinterpret_cast<uintptr_t>(mask24) & 3u)) return PATCH_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(P_24) & 3u) || (reinterpret_cast<uintptr_t>(mask24) & 7u)) return PATCH_ERR_ARG;
     const size_t T = (size_t)(N / tile) * (size_t)(K / tile);
     for (size_t i = 0; i < T; ++i) tile_map[i] = (P_tile[i] > 0.0f) ? 1 : 0;   // NaN and 0: the 2:4 class
     launch_hard_mask24(static_cast<const float*>(P_24), N * K / 4, static_cast<uint8_t*>(mask24), static_cast<hipStream_t>(stream));

@@ -15,9 +15,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ mask merge
 // One thread per 8 consecutive elements of a row (16 bytes of W, 8 bytes of mask).
-__global__ __launch_bounds__(256) void apply_mask_kernel(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask24,
+// W_hat may be W itself (in place): neither is declared restrict.
+__global__ __launch_bounds__(256) void apply_mask_kernel(const uint16_t* W, const uint8_t* __restrict__ mask24,
                                                          const uint8_t* __restrict__ tile_map, int64_t N, int64_t K, int tile,
-                                                         uint16_t* __restrict__ W_hat) {
+                                                         uint16_t* W_hat) {
     const int64_t chunks_per_row = K / 8;
     const int64_t total = N * chunks_per_row;
     const int64_t Tk = K / tile;

@@ -95,3 +95,30 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
     spills = re.search(r"_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
     assert (meta or spills) and int((meta or spills).group(1)) == 0
     assert re.search(r"\.agpr_count:\s+256", text)
+
+
+@pytest.mark.parametrize("source,kernel", [("gemm_decode.hip", "decode_kernel"), ("gemm_mid.hip", "mid_kernel")])
+def test_kernels_with_untracked_loads_do_not_spill(source, kernel):
+    """decode_kernel and mid_kernel issue their loads from asm statements and wait for them in a later one; until
+    that wait the destinations must stay where the loads write them.  A spill (or any scratch use) of such a register
+    would store a value that is still in flight, so every instantiation must report none."""
+    import subprocess
+    from paper_2509_23410_amd import build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *[f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")], "-c", "--cuda-device-only",
+           "-Rpass-analysis=kernel-resource-usage", "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+           "-o", os.devnull, os.path.join(build.CSRC, source)]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout[-2000:]
+    blocks = re.split(r"remark: Function Name: ", r.stdout)[1:]
+    seen = 0
+    for b in blocks:
+        name = b.split()[0]
+        if kernel not in name:
+            continue
+        seen += 1
+        get = lambda key: int(re.search(re.escape(key) + r":\s*(\d+)", b).group(1))
+        assert get("VGPRs Spill") == 0 and get("SGPRs Spill") == 0, f"{name} spills"
+        assert get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory"
+        assert get("VGPRs") <= 256 and get("AGPRs") == 0, name
+    assert seen >= 4, f"expected several instantiations of {kernel}, saw {seen}"
