@@ -131,6 +131,24 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
                            const patch_gemm_opts* opts);
 
 /*
+ * The same product for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): patch_gemm_ex with the automatic schedule and,
+ * in place of patch_gemm_opts.workspace, a scratch array of PATCH_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (one copy per GPU, held until the process ends).  Calls no hipMalloc / hipFree and no
+ * allocating routine; the first call on a device looks the array's address up (hipGetSymbolAddress).
+ *   X, M, P, Y, stream   as for patch_gemm
+ * The schedule is the one patch_gemm_ex picks when given a workspace of that size, so results are bit-equal to
+ * patch_gemm_ex with such a caller workspace.  Returns PATCH_ERR_SIZE - nothing is launched - when that schedule
+ * would want more scratch than the array holds (patch_gemm_workspace_bytes(M, P, NULL) > PATCH_STATIC_SCRATCH_BYTES;
+ * e.g. split launches of large M x N); use patch_gemm_ex with a workspace of your own then.  Every partial sum the
+ * kernels read from the scratch is written by the same call first, so nothing needs clearing between calls, but
+ * all calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or
+ * threads) race on it.  Errors otherwise as patch_gemm_ex.
+ */
+#define PATCH_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream);
+
+/*
  * Schedule autotuner (Appendix A leaves tile shape and schedule - e.g. split-K - to an autotuner run per layer
  * and input shape, decode first).  Times the candidate schedules of patch_gemm_ex for this M and P on the device,
  * on real operands, and returns the fastest.  Candidates: both paths where they apply (decode passes up to

@@ -18,7 +18,7 @@ OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
+    "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.patch_apply_mask.argtypes = [vp, vp, vp, i64, i64, ci, vp, vp]
         L.patch_pack.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_gemm.argtypes = [vp, i64, vp, vp, vp]
+        L.patch_gemm_static.argtypes = [vp, i64, vp, vp, vp]
+        L.patch_gemm_static.restype = ci
         L.patch_hard_masks.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
         L.patch_hard_masks.restype = ci
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
@@ -187,6 +189,14 @@ def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, 
         o = _opts(path, split_k, variant, workspace, workspace_bytes)
         st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
     _check(st, "patch_gemm")
+
+
+def patch_gemm_static(X, M: int, P: Packed, Y, stream: int = 0) -> None:
+    """patch_gemm with the library's own static scratch array in place of a caller workspace (allocates nothing)."""
+    _check(lib().patch_gemm_static(_ptr(X), M, P.handle, _ptr(Y), stream), "patch_gemm_static")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 def patch_tune(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, stream: int = 0, reps: int = 20):

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -115,6 +116,31 @@ static std::vector<int32_t> pair_tile_rows(const std::vector<uint8_t>& tile_map,
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Library-side scratch for patch_gemm_static (callers that cannot allocate): split-K partial products live here
+// instead of a caller workspace.  One copy per GPU, held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = PATCH_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static patch_status static_scratch(void** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return PATCH_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { g_last_hip_error = (int)hipErrorInvalidSymbol; return PATCH_ERR_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PATCH_OK;
+}
 
 extern "C" {
 
@@ -498,6 +524,18 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
 
 patch_status patch_gemm(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream) {
     return patch_gemm_ex(X, M, P, Y, stream, nullptr);
+}
+
+patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream) {
+    if (!X || !P || !Y || M < 0) return PATCH_ERR_ARG;
+    // what the automatic schedule would use given any amount of workspace: beyond the static array, refuse
+    const size_t need = patch_gemm_workspace_bytes(M, P, nullptr);
+    if (need > kStaticScratchBytes) return PATCH_ERR_SIZE;
+    void* ws = nullptr;
+    const patch_status st = static_scratch(&ws);
+    if (st != PATCH_OK) return st;
+    const patch_gemm_opts o = {PATCH_PATH_AUTO, 0, 0, ws, kStaticScratchBytes};
+    return patch_gemm_ex(X, M, P, Y, stream, &o);
 }
 
 patch_status patch_unpack(const patch_packed* P, void* W_out, void* stream) {
