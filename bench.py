@@ -14,7 +14,15 @@ Also reported on the same JSON line:
                 to defeat the 256 MB last-level cache
   speedup_vs_all_dense   same shapes with an all-dense tile map through the same library
   pack          compression throughput (one-off conversion; not part of a step)
+  ceilings      measured ceilings from kernels of this library (register-resident loops of the two matrix
+                instructions, streaming reads) and the vendor dense GEMM on the same shapes (context)
+  stack_13b     the 13B decoder stack: 40 layers x 7 matrices, one 2:4 fraction per layer drawn U[0,1),
+                M in {1, 512, 4096}, time = sum over the layers
+  qwen_0p5b     the 0.5B-scale layer set (launch-latency-bound)
   cpu_baseline  the CPU oracle timed on a bounded sample of the headline workload
+
+Before every timed region the workload runs until two consecutive batches agree within 1 % (the clock of
+the part needs some tens of launches after idle to settle); `settle_steps` says how many steps that took.
 """
 from __future__ import annotations
 
@@ -35,14 +43,87 @@ PEAK_MFMA_BF16_TF = 2500.0  # MI355X published dense bf16 matrix peak
 PAPER_CONTEXT = "paper: 1.18x-1.38x end-to-end LLaMA-2 7B speedup on an A6000 at 25-45% sparsity (context, not a target)"
 
 
+def stack_13b(torch, B, synth, dev, stream, timed, t):
+    """The 13B decoder stack: 40 layers x {q, k, v, o 5120 x 5120; gate, up 13824 x 5120; down 5120 x 13824}, one 2:4
+    tile fraction per layer drawn U[0, 1), every GEMM with its own X, M in {1, 512, 4096}; time = sum over the layers.
+    A layer runs as four launches (q / k / v share X, gate / up share X).  Weights are packed layer by layer and freed;
+    they are drawn on the device (N(0, 0.02^2), magnitude 2:4 mask) - the parity tests cover these shapes with the
+    host-drawn inputs.  Every layer is also run with an all-dense map of the same weights."""
+    H, F = 5120, 13824
+    shapes = [("q", H, H), ("k", H, H), ("v", H, H), ("o", H, H), ("gate", F, H), ("up", F, H), ("down", H, F)]
+    fr = synth.layer_fractions(0, 40)
+    Ms = (1, 512, 4096)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(13)
+    xH = torch.randn(4096, H, device=dev, generator=gen).to(torch.bfloat16)
+    xF = torch.randn(4096, F, device=dev, generator=gen).to(torch.bfloat16)
+    y = {n: torch.empty((4096, N_), device=dev, dtype=torch.float32) for n, N_, _ in shapes}
+    ws = torch.empty(96 << 20, device=dev, dtype=torch.float32)     # 384 MB: room for every split the launcher picks
+    tot = {M_: dict(mix=0.0, dense=0.0) for M_ in Ms}
+    packed_bytes, dense_bytes, flop_w, ideal_s = 0, 0, 0.0, {M_: 0.0 for M_ in Ms}
+    per_layer = []
+
+    def layer_pass(L, M_):
+        B.patch_gemm_many(xH, M_, [L["q"], L["k"], L["v"]], [y["q"], y["k"], y["v"]], stream, workspace=ws)
+        B.patch_gemm(xH, M_, L["o"], y["o"], stream, workspace=ws)
+        B.patch_gemm_many(xH, M_, [L["gate"], L["up"]], [y["gate"], y["up"]], stream, workspace=ws)
+        B.patch_gemm(xF, M_, L["down"], y["down"], stream, workspace=ws)
+
+    for li in range(40):
+        f = float(fr[li])
+        layer, dense = {}, {}
+        for name, N_, K_ in shapes:
+            W = (torch.randn(N_, K_, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+            keep = torch.zeros((N_ * K_ // 4, 4), device=dev, dtype=torch.uint8)
+            keep.scatter_(1, W.abs().float().view(-1, 4).topk(2, dim=1).indices, 1)
+            tm = synth.tile_map(li, N_ // t, K_ // t, f, "stack13b", name)
+            W_hat = torch.empty_like(W)
+            B.patch_apply_mask(W, keep.view(N_, K_), tm, N_, K_, t, W_hat, stream)
+            layer[name] = B.patch_pack(W_hat, N_, K_, tm, t, stream)
+            dense[name] = B.patch_pack(W_hat, N_, K_, np.ones_like(tm), t, stream)
+            packed_bytes += layer[name].nbytes
+            dense_bytes += dense[name].nbytes
+            del W, keep, W_hat
+        row = dict(layer=li, f=round(f, 3))
+        for M_ in Ms:
+            reps = 10 if M_ == 1 else 4 if M_ == 512 else 2
+            for key, L in (("mix", layer), ("dense", dense)):
+                timed(lambda _i: layer_pass(L, M_), 2)
+                s_ = min(timed(lambda _i: layer_pass(L, M_), reps) / reps for _ in range(2))
+                tot[M_][key] += s_
+                row[f"us_M{M_}" + ("" if key == "mix" else "_all_dense")] = round(s_ * 1e6, 1)
+        per_layer.append(row)
+        for L in (layer, dense):
+            for P_ in L.values():
+                P_.close()
+    layer_flop = sum(2.0 * N_ * K_ for _, N_, K_ in shapes)            # per row of X
+    f_mean = float(np.mean(fr))
+    rows = []
+    for M_ in Ms:
+        secs = tot[M_]["mix"]
+        issued = sum(layer_flop * M_ * (2.0 - float(f)) / 2.0 for f in fr)
+        r_ = dict(M=M_, ms_total=round(secs * 1e3, 3), ms_total_all_dense=round(tot[M_]["dense"] * 1e3, 3),
+                  speedup_vs_all_dense=round(tot[M_]["dense"] / secs, 4),
+                  dense_equiv_TFLOPs=round(40 * layer_flop * M_ / secs / 1e12, 1),
+                  issued_TFLOPs=round(issued / secs / 1e12, 1), frac_mfma_peak=round(issued / secs / 1e12 / PEAK_MFMA_BF16_TF, 4),
+                  GBps_compressed=round(packed_bytes / secs / 1e9, 1), frac_hbm_peak=round(packed_bytes / secs / 1e9 / PEAK_HBM_GBS, 4))
+        rows.append(r_)
+    return dict(layers=40, launches_per_layer=4, packed_GB=round(packed_bytes / 1e9, 3), dense_GB=round(dense_bytes / 1e9, 3),
+                f_mean=round(f_mean, 4), rows=rows, per_layer=per_layer,
+                note="time = sum over the 40 layers of the layer's four launches (q/k/v fused, o, gate/up fused, down), each layer "
+                     "timed on its own after two warm-up passes with a caller workspace; frac_mfma_peak = issued matrix flops "
+                     "(flop-weighted over the layers' fractions) / time / 2.5 PFLOP/s, the bound at M = 4096; frac_hbm_peak = "
+                     "compressed weight bytes / time / 8 TB/s, the bound at M = 1; M = 512 sits near the ridge: both are given")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,qwen")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -82,6 +163,17 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3  # seconds
 
+    def settle(fn, batch=10, max_batches=12, tol=0.01):
+        """Run fn in batches until two consecutive batch means agree within tol; -> steps run."""
+        prev, n = None, 0
+        for _ in range(max_batches):
+            t = timed(fn, batch)
+            n += batch
+            if prev is not None and abs(t - prev) <= tol * prev:
+                break
+            prev = t
+        return n
+
     out = {}
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -107,6 +199,7 @@ def main():
         for L in layers:
             B.patch_gemm(L["X"], M, L["P"], L["Y"], stream, **opts)
 
+    settle_steps = settle(step)
     timed(step, args.warmup)
     secs = timed(step, args.steps)
     Y_sample = {L["name"]: L["Y"].cpu().numpy() for L in layers[:1]} if "cpu" not in skip else {}
@@ -145,6 +238,7 @@ def main():
             for X, P0, Y in dl:
                 B.patch_gemm(X, M, P0, Y, stream, **opts)
 
+        settle(dstep)
         timed(dstep, args.warmup)
         dsecs = timed(dstep, args.steps)
         speedup = dsecs / secs
@@ -175,6 +269,7 @@ def main():
             del W_hat_f
         Xf, Yf = layers[0]["X"], layers[0]["Y"]
         us = [[] for _ in fr]
+        settle(lambda _i: B.patch_gemm(Xf, M, Pf[2], Yf, stream, **opts), batch=30)
         for _r in range(3):   # the fractions in turn, three rounds: the clock drifts by a few per cent over a run
             for i, P_f in enumerate(Pf):
                 fn = lambda _i, P_f=P_f: B.patch_gemm(Xf, M, P_f, Yf, stream, **opts)
@@ -343,6 +438,101 @@ def main():
         out["decode"] = dict(workload="llama7b_attn_decode 4096x4096 tile128", peak_GBps=PEAK_HBM_GBS, rows=dec,
                              note="us = median of 5 batches of back-to-back launches over rotating packed copies (HBM-resident)")
 
+    # ------------------------------------------------------------------ measured ceilings (kernels of this library)
+    if "ceilings" not in skip:
+        n_cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        ceil = dict(compute_units=n_cus)
+        res = torch.empty(2 * n_cus * 256, device=dev, dtype=torch.float32)
+        iters = 12000
+        best_rate = {}
+        for label, ops in (("random_operands", torch.randn(B.PROBE_OPERAND_BYTES // 2, device=dev).to(torch.bfloat16)),
+                           ("zero_operands", torch.zeros(B.PROBE_OPERAND_BYTES // 2, device=dev, dtype=torch.bfloat16))):
+            for kind, name, flop in ((0, "dense_mfma_16x16x32_bf16", 16384.0), (1, "sparse_smfmac_16x16x64_bf16", 32768.0)):
+                for wps in (1, 2):      # wavefronts per SIMD
+                    fn = lambda _i, kind=kind, ops=ops, wps=wps: B.patch_probe_matrix_rate(kind, ops, wps * n_cus, iters, res, stream)
+                    timed(fn, 2)
+                    t_best = min(timed(fn, 3) / 3 for _ in range(3))
+                    rate = round(wps * n_cus * 4 * iters * 16 * flop / t_best / 1e12, 1)
+                    ceil[f"{name}_{label}_{wps}_per_simd_TFLOPs"] = rate
+                    best_rate[(kind, label)] = max(best_rate.get((kind, label), 0.0), rate)
+        P_d, P_s = best_rate[(0, "random_operands")], best_rate[(1, "random_operands")]
+        fa = 1.0 - issued_flop / dense_flop * 2.0 + 1.0     # f of the headline set: issued = dense (2 - f) / 2
+        p_mix = 1.0 / ((1.0 - fa) / P_d + fa / P_s)
+        ceil["headline_mix_weighted_measured_peak_TFLOPs"] = round(p_mix, 1)
+        ceil["headline_frac_of_measured_mix_peak"] = round(value / p_mix, 4)
+        ceil["matrix_note"] = ("register-resident loops, one or two wavefronts per SIMD on every compute unit, no memory traffic; 2:4 in "
+                               "dense-equivalent flops; the clock under matrix load depends on the operand data, hence both figures; the "
+                               "mix-weighted peak uses the better random-operand figure of each instruction")
+        big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        big.random_(0, 255)
+        sink = torch.empty(4096 * 1024, dtype=torch.int32, device=dev)
+        best = None
+        for wg, th in ((n_cus * 8, 256), (n_cus * 4, 512), (n_cus * 2, 1024), (n_cus * 16, 256)):
+            fn = lambda _i, wg=wg, th=th: B.patch_probe_stream_read(big, big.numel(), wg, th, sink, stream)
+            timed(fn, 2)
+            t_ = min(timed(fn, 5) / 5 for _ in range(3))
+            if best is None or t_ < best[0]:
+                best = (t_, wg, th)
+        ceil["stream_read_2GiB_GBps"] = round(big.numel() / best[0] / 1e9, 1)
+        ceil["stream_read_2GiB_launch"] = [best[1], best[2]]
+        # the decode launch shape of the 4096 x 4096 projection (256 workgroups of 16 wavefronts) over 33.5 MB pieces,
+        # rotating through the 2 GiB buffer so that no cache holds a piece when its turn comes again
+        piece, n_piece = 4096 * 4096 * 2, (2 << 30) // (4096 * 4096 * 2)
+        fn = lambda i: B.patch_probe_stream_read(big.data_ptr() + (i % n_piece) * piece, piece, 256, 1024, sink, stream)
+        timed(fn, 20)
+        t_ = sorted(timed(fn, 200) / 200 for _ in range(5))[2]
+        ceil["stream_read_33MB_decode_launch_shape_us"] = round(t_ * 1e6, 2)
+        ceil["stream_read_33MB_decode_launch_shape_GBps"] = round(piece / t_ / 1e9, 1)
+        fn = lambda i: B.patch_probe_stream_read(big.data_ptr(), 16, 1, 64, sink, stream)
+        timed(fn, 20)
+        ceil["empty_launch_us"] = round(sorted(timed(fn, 200) / 200 for _ in range(5))[2] * 1e6, 2)
+        del big, sink
+        # vendor dense GEMM (bf16 output) on the headline shapes, for context: same macro tile class, same part
+        vend = []
+        for name, N_, K_ in (("gate", 11008, 4096), ("down", 4096, 11008)):
+            Xv = torch.randn(M, K_, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            Wv = (torch.randn(N_, K_, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            Yv = torch.empty(M, N_, device=dev, dtype=torch.bfloat16)
+            fn = lambda _i: torch.matmul(Xv, Wv.t(), out=Yv)
+            settle(fn, batch=20)
+            t_ = min(timed(fn, 20) / 20 for _ in range(3))
+            P0 = B.patch_pack(Wv, N_, K_, np.ones((N_ // t, K_ // t), np.uint8), t, stream)
+            Yo_ = torch.empty(M, N_, device=dev, dtype=torch.float32)
+            fo = lambda _i: B.patch_gemm(Xv, M, P0, Yo_, stream)
+            settle(fo, batch=20)
+            t_o = min(timed(fo, 20) / 20 for _ in range(3))
+            vend.append(dict(shape=[N_, K_], M=M, vendor_us=round(t_ * 1e6, 1), vendor_TFLOPs=round(2.0 * M * N_ * K_ / t_ / 1e12, 1),
+                             this_library_all_dense_us=round(t_o * 1e6, 1), this_library_all_dense_TFLOPs=round(2.0 * M * N_ * K_ / t_o / 1e12, 1)))
+            P0.close()
+            del Xv, Wv, Yv, Yo_
+        ceil["vendor_dense_gemm"] = dict(rows=vend, note="torch.matmul (the vendor library), bf16 in / bf16 out, random data; this library: "
+                                         "all-dense tile map, fp32 out.  Context only.")
+        out["ceilings"] = ceil
+
+    # ------------------------------------------------------------------ 0.5B-scale layer set (launch-latency-bound)
+    if "qwen" not in skip:
+        rows = []
+        for N_, K_ in ((896, 896), (4864, 896), (896, 4864)):
+            for fd in (0.0, 0.5, 1.0):
+                cq = synth.make_case("qwen0p5b", N_, K_, 64, t, fd, seed=0)
+                W_hat, Pq = masked_packed(cq)
+                Xq = dev_bf16(cq.X)
+                Yq = torch.empty((64, N_), device=dev, dtype=torch.float32)
+                r_ = dict(shape=[N_, K_], f=fd, packed_MB=round(Pq.nbytes / 1e6, 2))
+                for Mq in (1, 64):
+                    fn = lambda _i, Mq=Mq: B.patch_gemm(Xq, Mq, Pq, Yq, stream)
+                    timed(fn, 20)
+                    r_[f"us_M{Mq}"] = round(sorted(timed(fn, 200) / 200 for _ in range(3))[1] * 1e6, 2)
+                rows.append(r_)
+                Pq.close()
+                del W_hat, Xq, Yq
+        out["qwen_0p5b"] = dict(rows=rows, note="0.5B-scale set, tile 128, cache-resident (1.6 - 8.7 MB): bounded by launch latency "
+                                "(an empty launch is in ceilings.empty_launch_us), not by a roofline")
+
+    # ------------------------------------------------------------------ 13B decoder stack
+    if "stack" not in skip:
+        out["stack_13b"] = stack_13b(torch, B, synth, dev, stream, timed, t)
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None
     if "cpu" not in skip:
@@ -364,7 +554,7 @@ def main():
     line = {
         "metric": "hybrid GEMM dense-equiv TFLOP/s + GB/s vs roofline; speedup over all-dense",
         "value": value, "unit": "TFLOP/s (dense-equivalent)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "settle_steps": settle_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "llama7b_mlp_prefill", "shapes": [[n, k] for _, n, k in shapes], "M": M, "tile": t,
                    "f_2to4_tiles": f, "launches_per_step": n_launch, "variant": args.variant},

@@ -220,6 +220,28 @@ patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, siz
  * can hold, PATCH_ERR_SIZE if too few. */
 patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_t cap, size_t* count);
 
+/*
+ * Measurement probes (this project's; no passage of the paper): kernels that run nothing of the method, for the
+ * measured ceilings the benchmark prints beside the product kernels.  Both are asynchronous on `stream` and
+ * allocate nothing; the caller times them with events.
+ *   patch_probe_matrix_rate  `workgroups` workgroups of 4 wavefronts each run `iters` rounds of 16 independent matrix
+ *                            instructions on register operands: kind 0 = v_mfma_f32_16x16x32_bf16 (16384 flop each),
+ *                            kind 1 = v_smfmac_f32_16x16x64_bf16 (32768 dense-equivalent flop each).  Total instructions
+ *                            = workgroups * 4 * iters * 16.  operands: DEVICE, 16-byte aligned, at least
+ *                            PATCH_PROBE_OPERAND_BYTES of bf16 data (random data gives the rate under realistic
+ *                            switching activity; zeros give the clock-unconstrained rate); out: DEVICE,
+ *                            workgroups * 256 floats (keeps the results alive).
+ *   patch_probe_stream_read  reads `bytes` (16-byte aligned, multiple of 16) at src with 128-bit loads, grid-stride
+ *                            over workgroups x threads (threads a multiple of 64, at most 1024); out: DEVICE,
+ *                            workgroups * threads 32-bit words.
+ * Errors: PATCH_ERR_ARG, PATCH_ERR_SIZE (a buffer too small), PATCH_ERR_HIP.
+ */
+#define PATCH_PROBE_OPERAND_BYTES ((size_t)12 * 256 * 16)
+patch_status patch_probe_matrix_rate(int kind, const void* operands, size_t operand_bytes, int workgroups, int iters, void* out,
+                                     size_t out_bytes, void* stream);
+patch_status patch_probe_stream_read(const void* src, size_t bytes, int workgroups, int threads, void* out, size_t out_bytes,
+                                     void* stream);
+
 void patch_free(patch_packed* P);
 const char* patch_strerror(patch_status s);
 int patch_last_hip_error(void); /* hipError_t of the most recent PATCH_ERR_HIP on this thread */

@@ -20,7 +20,7 @@ PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
-    "patch_packed_tile_map", "patch_packed_row_order", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
+    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
 
@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.patch_packed_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ci), ctypes.POINTER(i64)]
         L.patch_packed_tile_map.argtypes = [vp, vp, sz]
         L.patch_packed_row_order.argtypes = [vp, vp, sz, ctypes.POINTER(sz)]
+        L.patch_probe_matrix_rate.argtypes = [ci, vp, sz, ci, ci, vp, sz, vp]
+        L.patch_probe_matrix_rate.restype = ci
+        L.patch_probe_stream_read.argtypes = [vp, sz, ci, ci, vp, sz, vp]
+        L.patch_probe_stream_read.restype = ci
         L.patch_free.argtypes = [vp]
         L.patch_free.restype = None
         L.patch_strerror.argtypes = [ci]
@@ -242,6 +246,21 @@ def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, s
     yp = (ctypes.c_void_p * max(n, 1))(*[_ptr(y) for y in Ys])
     o = _opts(path, split_k, variant, workspace, workspace_bytes)
     _check(lib().patch_gemm_many(_ptr(X), M, hp, yp, n, stream, ctypes.byref(o)), "patch_gemm_many")
+
+
+PROBE_OPERAND_BYTES = 12 * 256 * 16
+
+
+def patch_probe_matrix_rate(kind: int, operands, workgroups: int, iters: int, out, stream: int = 0) -> None:
+    """Register-resident loop of the dense (kind 0) or 2:4 (kind 1) matrix instruction; see patch.h."""
+    _check(lib().patch_probe_matrix_rate(kind, _ptr(operands), operands.numel() * operands.element_size(), workgroups, iters,
+                                         _ptr(out), out.numel() * out.element_size(), stream), "patch_probe_matrix_rate")
+
+
+def patch_probe_stream_read(src, nbytes: int, workgroups: int, threads: int, out, stream: int = 0) -> None:
+    """128-bit streaming read of nbytes at src (a tensor or a device address); see patch.h."""
+    _check(lib().patch_probe_stream_read(_ptr(src), nbytes, workgroups, threads, _ptr(out), out.numel() * out.element_size(), stream),
+           "patch_probe_stream_read")
 
 
 def patch_unpack(P: Packed, W_out, stream: int = 0) -> None:
