@@ -72,6 +72,10 @@ typedef struct {
                             /* library never allocates in a product call.  Launches that may run         */
                             /* concurrently need distinct workspaces.                                    */
     size_t workspace_bytes; /* its size; patch_gemm_workspace_bytes says what a launch would use         */
+    int y_bf16;             /* nonzero: Y (every Y of patch_gemm_many) is M x N bf16 instead of fp32: the fp32  */
+                            /* accumulator - after the sum over K slices, where K is split - rounded to nearest, */
+                            /* ties to even.  The paper fixes no output type; half-precision inference feeds the */
+                            /* product to the next layer in 16 bits.  Same alignment (16 bytes) as the fp32 Y.   */
 } patch_gemm_opts;
 
 /*

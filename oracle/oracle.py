@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (no -march flags, no fast-math, no FP contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC]
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -50,6 +50,8 @@ def _load():
         L.patch_oracle_unpack.argtypes = [vp, vp, i64, i64, vp, ci, vp]
         L.patch_oracle_gemm.argtypes = [vp, i64, vp, vp, i64, i64, vp, ci, vp]
         L.patch_oracle_gemm_points.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
+        L.patch_oracle_round_bf16.argtypes = [vp, i64, vp]
+        L.patch_oracle_round_bf16.restype = ci
         for f in ("apply_mask", "packed_sizes", "pack", "unpack", "gemm", "gemm_points", "num_threads"):
             getattr(L, "patch_oracle_" + f).restype = ci
         _lib = L
@@ -155,6 +157,16 @@ def gemm(X, vals, meta, N, K, tile_map, t):
     if rc:
         raise OracleError(rc)
     return Y
+
+
+def round_bf16(Y):
+    """float64 array -> bf16 bit patterns (uint16, same shape): one rounding, to nearest, ties to even."""
+    Y = np.ascontiguousarray(Y, dtype=np.float64)
+    out = np.empty(Y.shape, np.uint16)
+    rc = _load().patch_oracle_round_bf16(_p(Y), Y.size, _p(out))
+    if rc:
+        raise OracleError(rc)
+    return out
 
 
 def gemm_points(X, W_hat_dense, mn):

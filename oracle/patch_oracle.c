@@ -26,6 +26,11 @@
  * All bf16 data are passed as uint16_t bit patterns.  The product is evaluated in IEEE double with
  * k ascending, one independent dot product per output element (no blocking, no reordering).
  *
+ * Output in bf16 (an option of this project's library; the paper fixes no output type): the exact product,
+ * here the double, rounded ONCE to the nearest bf16 value, ties to the even significand
+ * (patch_oracle_round_bf16).  The library rounds its fp32 accumulator instead, so the two may differ by one
+ * unit in the last place; the tests allow exactly that.
+ *
  * Parity pins (see tests/test_oracle_*.py): hand-worked packed example, closed-form sizes, round trip,
  * naive dense GEMM (bit-equal), library dense GEMM, direct 2:4 GEMM on (values, positions), exact
  * rational brute force over all six patterns, linearity and tile-map invariance.
@@ -243,6 +248,35 @@ int patch_oracle_gemm_points(const uint16_t* X, int64_t M, const uint16_t* W_hat
         double acc = 0.0;
         for (int64_t k = 0; k < K; ++k) acc += bf16_to_double(X[m * K + k]) * bf16_to_double(W_hat_dense[n * K + k]);
         out[i] = acc;
+    }
+    return PO_OK;
+}
+
+/* y[i] (double) -> nearest bf16 value (8 significand bits, exponent range of binary32), ties to even, as a
+ * bit pattern.  Written on the value, with frexp / nearbyint in the default rounding mode, not on bit patterns:
+ *   |y| = m 2^e, 0.5 <= m < 1  ->  quantum q = 2^(e - 8) (2^-133 below the normal range), result = rint(|y| / q) q.
+ * Overflow past the largest finite bf16 gives infinity; NaN gives a quiet NaN. */
+#include <math.h>
+int patch_oracle_round_bf16(const double* y, int64_t n, uint16_t* out) {
+    if (!y || !out || n < 0) return PO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        const double v = y[i];
+        uint16_t sign = signbit(v) ? 0x8000u : 0u;
+        if (isnan(v)) { out[i] = (uint16_t)(sign | 0x7FC0u); continue; }
+        const double a = fabs(v);
+        if (isinf(a)) { out[i] = (uint16_t)(sign | 0x7F80u); continue; }
+        if (a == 0.0) { out[i] = sign; continue; }
+        int e;
+        (void)frexp(a, &e);                 /* a = m 2^e with 0.5 <= m < 1: the leading bit has weight 2^(e-1) */
+        int qe = e - 8;                     /* 8 significand bits: the last one has weight 2^(e-8) */
+        if (qe < -133) qe = -133;           /* subnormal range: fixed quantum 2^-133 */
+        const double r = nearbyint(ldexp(a, -qe));   /* an integer <= 256, ties to even */
+        const double rounded = ldexp(r, qe);
+        if (rounded > 3.3895313892515355e38) { out[i] = (uint16_t)(sign | 0x7F80u); continue; }  /* > max finite bf16 */
+        const float f = (float)rounded;     /* exact: 8 significant bits within the binary32 range */
+        uint32_t u;
+        memcpy(&u, &f, sizeof u);
+        out[i] = (uint16_t)(sign | (uint16_t)(u >> 16));
     }
     return PO_OK;
 }

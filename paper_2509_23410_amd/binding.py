@@ -26,7 +26,7 @@ EXPORTS = [
 
 class GemmOpts(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("y_bf16", ctypes.c_int)]
 
 
 class PatchError(RuntimeError):
@@ -178,19 +178,19 @@ def patch_pack(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> P
     return Packed(out.value)
 
 
-def _opts(path, split_k, variant, workspace, workspace_bytes):
+def _opts(path, split_k, variant, workspace, workspace_bytes, y_bf16=False):
     if workspace is not None and workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size()
-    return GemmOpts(path, split_k, variant, _ptr(workspace) if workspace is not None else None, workspace_bytes or 0)
+    return GemmOpts(path, split_k, variant, _ptr(workspace) if workspace is not None else None, workspace_bytes or 0, 1 if y_bf16 else 0)
 
 
 def patch_gemm(X, M: int, P: Packed, Y, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0,
-               workspace=None, workspace_bytes=None) -> None:
-    """workspace: a device tensor (or pointer + workspace_bytes) for split prefill launches, see patch.h."""
-    if path == PATH_AUTO and split_k == 0 and variant == 0 and workspace is None:
+               workspace=None, workspace_bytes=None, y_bf16: bool = False) -> None:
+    """workspace: a device tensor (or pointer + workspace_bytes) for split prefill launches; y_bf16: Y is bf16; see patch.h."""
+    if path == PATH_AUTO and split_k == 0 and variant == 0 and workspace is None and not y_bf16:
         st = lib().patch_gemm(_ptr(X), M, P.handle, _ptr(Y), stream)
     else:
-        o = _opts(path, split_k, variant, workspace, workspace_bytes)
+        o = _opts(path, split_k, variant, workspace, workspace_bytes, y_bf16)
         st = lib().patch_gemm_ex(_ptr(X), M, P.handle, _ptr(Y), stream, ctypes.byref(o))
     _check(st, "patch_gemm")
 
@@ -222,7 +222,7 @@ def run_tuned(X, M: int, P: Packed, Y, tuned: dict, workspace=None, stream: int 
 
 
 def patch_gemm_workspace_bytes(M: int, P: Packed, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0) -> int:
-    o = GemmOpts(path, split_k, variant, None, 0)
+    o = GemmOpts(path, split_k, variant, None, 0, 0)
     return int(lib().patch_gemm_workspace_bytes(M, P.handle, ctypes.byref(o)))
 
 
@@ -237,14 +237,14 @@ def patch_hard_masks(P_tile, P_24, N: int, K: int, tile: int, mask24, stream: in
 
 
 def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, split_k: int = 0, variant: int = 0,
-                    workspace=None, workspace_bytes=None) -> None:
+                    workspace=None, workspace_bytes=None, y_bf16: bool = False) -> None:
     """Y[i] = X * W_hat[i]^T for weights that share X (same K, same tile); one decode launch for all of them."""
     n = len(Ps)
     if n != len(Ys):
         raise PatchError(ERR_ARG, "patch_gemm_many: as many outputs as weights")
     hp = (ctypes.c_void_p * max(n, 1))(*[p.handle for p in Ps])
     yp = (ctypes.c_void_p * max(n, 1))(*[_ptr(y) for y in Ys])
-    o = _opts(path, split_k, variant, workspace, workspace_bytes)
+    o = _opts(path, split_k, variant, workspace, workspace_bytes, y_bf16)
     _check(lib().patch_gemm_many(_ptr(X), M, hp, yp, n, stream, ctypes.byref(o)), "patch_gemm_many")
 
 

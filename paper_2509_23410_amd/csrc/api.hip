@@ -332,6 +332,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.Y = static_cast<float*>(Y);
     a.n_cus = P->n_cus;
     if (opts && opts->workspace) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
+    a.ybf16 = (opts && opts->y_bf16) ? 1 : 0;
     if (path == PATCH_PATH_DECODE) {
         WeightSet one = {};
         one.payload[0] = a.payload; one.table[0] = a.table; one.Y[0] = a.Y; one.N[0] = a.N;
@@ -357,7 +358,7 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<patch_gemm_opts> cand;
     auto add = [&](int path, int split_k, int variant, bool ws) {
-        cand.push_back(patch_gemm_opts{path, split_k, variant, ws ? workspace : nullptr, ws ? workspace_bytes : 0});
+        cand.push_back(patch_gemm_opts{path, split_k, variant, ws ? workspace : nullptr, ws ? workspace_bytes : 0, 0});
     };
     if (M <= 256) {  // every pass of 64 rows streams the whole weight again: no contender beyond that
         add(PATCH_PATH_DECODE, 0, 0, false);
@@ -413,7 +414,7 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
     if (!P || M <= 0) return 0;
     int path = PATCH_PATH_AUTO, split_k = 0, variant = 0;
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
-    patch_gemm_opts enough = {path, split_k, variant, reinterpret_cast<void*>(16), ~(size_t)0};  // the choice given enough
+    patch_gemm_opts enough = {path, split_k, variant, reinterpret_cast<void*>(16), ~(size_t)0, 0};  // the choice given enough
     if (path == PATCH_PATH_AUTO) path = auto_path(M, P, &enough);
     GemmArgs a;
     a.X = nullptr; a.M = M; a.N = P->N; a.K = P->K;
@@ -460,6 +461,7 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     a.M = M; a.K = P[0]->K; a.N = P[0]->N;
     a.tile = P[0]->tile; a.Tk = P[0]->Tk;
     a.n_cus = P[0]->n_cus;
+    a.ybf16 = (opts && opts->y_bf16) ? 1 : 0;
     if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
     if (opts && opts->workspace && split_k == 0) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_PREFILL && count > 1 && (variant == 0 || variant == 3) && split_k <= 1 && prefill_wreg_supports(a)) {
@@ -486,7 +488,7 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
         }
     }
     if (path == PATCH_PATH_PREFILL || count == 1) {
-        patch_gemm_opts o = {path, split_k, variant, opts ? opts->workspace : nullptr, opts ? opts->workspace_bytes : 0};
+        patch_gemm_opts o = {path, split_k, variant, opts ? opts->workspace : nullptr, opts ? opts->workspace_bytes : 0, a.ybf16};
         for (int i = 0; i < count; ++i) {
             const patch_status st = patch_gemm_ex(X, M, P[i], Y[i], stream, &o);
             if (st != PATCH_OK) return st;
@@ -534,7 +536,7 @@ patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, 
     void* ws = nullptr;
     const patch_status st = static_scratch(&ws);
     if (st != PATCH_OK) return st;
-    const patch_gemm_opts o = {PATCH_PATH_AUTO, 0, 0, ws, kStaticScratchBytes};
+    const patch_gemm_opts o = {PATCH_PATH_AUTO, 0, 0, ws, kStaticScratchBytes, 0};
     return patch_gemm_ex(X, M, P, Y, stream, &o);
 }
 

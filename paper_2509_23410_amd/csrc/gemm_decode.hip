@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "epilogue.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -36,9 +37,11 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
 }
 
 // RB = blocks of 16 rows of X per launch (1, 2 or 4): the weights are streamed once for up to 64 rows.
-template <int TILE, int NK, int MAXW, int RB>
+// SetT = DecodeSet (up to 8 weights sharing X) or WeightOne (a single weight: short kernel arguments, no selection).
+template <int TILE, int NK, int MAXW, int RB, typename SetT>
 __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
-                                                           const DecodeSet set) {
+                                                           const SetT set, int ybf16) {
+    constexpr bool kOne = sizeof(SetT) == sizeof(WeightOne);
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
     __shared__ f32x4 red[MAXW][RB][64];
 
@@ -47,26 +50,37 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
     const int KW = blockDim.x >> 6;
     // which weight of the set this strip belongs to: scalar selects over the (at most 8) candidates, so that every
     // pointer stays in scalar registers
-    const uint8_t* __restrict__ payload = set.payload[0];
-    const uint32_t* __restrict__ table = set.table[0];
-    float* __restrict__ Y = set.Y[0];
-    int64_t N = set.N[0];
+    const uint8_t* __restrict__ payload;
+    const uint32_t* __restrict__ table;
+    float* __restrict__ Y;
+    int64_t N;
     int first = 0;
-    if (set.count > 1)
+    if constexpr (kOne) {
+        payload = set.payload;
+        table = set.table;
+        Y = set.Y;
+        N = set.N;
+    } else {
+        payload = set.payload[0];
+        table = set.table[0];
+        Y = set.Y[0];
+        N = set.N[0];
+        if (set.count > 1)
 #pragma unroll
-    for (int i = 1; i < kMaxMany; ++i) {
-        const bool here = i < set.count && (int)blockIdx.x >= set.first[i];
-        payload = here ? set.payload[i] : payload;
-        table = here ? set.table[i] : table;
-        Y = here ? set.Y[i] : Y;
-        N = here ? set.N[i] : N;
-        first = here ? set.first[i] : first;
+        for (int i = 1; i < kMaxMany; ++i) {
+            const bool here = i < set.count && (int)blockIdx.x >= set.first[i];
+            payload = here ? set.payload[i] : payload;
+            table = here ? set.table[i] : table;
+            Y = here ? set.Y[i] : Y;
+            N = here ? set.N[i] : N;
+            first = here ? set.first[i] : first;
+        }
+        // the selects above are wavefront-uniform; say so (the weight addresses below must be scalar)
+        payload = reinterpret_cast<const uint8_t*>(uniform64(reinterpret_cast<uint64_t>(payload)));
+        table = reinterpret_cast<const uint32_t*>(uniform64(reinterpret_cast<uint64_t>(table)));
+        Y = reinterpret_cast<float*>(uniform64(reinterpret_cast<uint64_t>(Y)));
+        N = (int64_t)uniform64((uint64_t)N);
     }
-    // the selects above are wavefront-uniform; say so (the weight addresses below must be scalar)
-    payload = reinterpret_cast<const uint8_t*>(uniform64(reinterpret_cast<uint64_t>(payload)));
-    table = reinterpret_cast<const uint32_t*>(uniform64(reinterpret_cast<uint64_t>(table)));
-    Y = reinterpret_cast<float*>(uniform64(reinterpret_cast<uint64_t>(Y)));
-    N = (int64_t)uniform64((uint64_t)N);
     const int strip = (int)blockIdx.x - __builtin_amdgcn_readfirstlane(first);
     const int tn = strip / SPT, s = strip % SPT;
     const int col = lane & 15, q = lane >> 4;
@@ -229,18 +243,28 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
                 const f32x4 v = red[i][rb][lane];
                 sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
             }
-            if (16 * rb + col < rows) *reinterpret_cast<f32x4*>(Y + (m0 + 16 * rb + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
+            if (16 * rb + col < rows) store4(Y, (m0 + 16 * rb + col) * N + (int64_t)strip * 16 + 4 * q, sum, ybf16);
         }
     }
 }
 
+template <int TILE, typename SetT>
+static void launch_decode_s(const GemmArgs& a, const SetT& set, int units, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
+    dim3 grid((unsigned)units), block((unsigned)(kw * 64));
+    if (rows > 32) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 4, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    else if (rows > 16) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 2, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    else if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+}
+
 template <int TILE>
 static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
-    dim3 grid((unsigned)set.units), block((unsigned)(kw * 64));
-    if (rows > 32) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 4>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-    else if (rows > 16) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 2>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-    else if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+    if (set.count == 1) {
+        const WeightOne one = {set.payload[0], set.table[0], set.Y[0], set.N[0]};
+        launch_decode_s<TILE>(a, one, set.units, m0, rows, nk, kw, stream);
+    } else {
+        launch_decode_s<TILE>(a, set, set.units, m0, rows, nk, kw, stream);
+    }
 }
 
 // Schedule: NK = 64-column steps per wavefront and pass (8 or 4), KW = wavefronts per workgroup.

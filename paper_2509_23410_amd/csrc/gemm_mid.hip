@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "epilogue.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -44,7 +45,7 @@ __device__ __forceinline__ uint64_t mid_uniform64(uint64_t v) {
 // per SIMD (243 registers at RB = 4), so a second workgroup's loads overlap this one's matrix instructions.
 template <int TILE, int RB, bool SPLIT>
 __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void mid_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
-                                                          const WeightSet set) {
+                                                          const WeightSet set, int ybf16) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows, GPT = SPT / kMidSB;  // groups per tile row
     constexpr int SB = kMidSB, NK = kMidNK, KW = kMidKW;
     constexpr int KH = KW / 2;
@@ -238,7 +239,8 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
             }
     }
     __syncthreads();
-    float* dst = SPLIT ? Y + (int64_t)blockIdx.y * rows * N : Y + m0 * N;  // SPLIT: Y is the workspace, slices of rows x N
+    // SPLIT: Y is the workspace, slices of rows x N fp32; else row m0 of Y (fp32 or bf16 elements)
+    float* dst = SPLIT ? Y + (int64_t)blockIdx.y * rows * N : ybf16 ? reinterpret_cast<float*>(reinterpret_cast<uint16_t*>(Y) + m0 * N) : Y + m0 * N;
     for (int t = w; t < SB * RB; t += KW) {
         const int sb = t / RB, rb = t % RB;
         mid_f32x4 sum = red[0][t][lane];
@@ -247,8 +249,8 @@ __global__ __launch_bounds__(kMidKW * 64) __attribute__((amdgpu_waves_per_eu(2, 
             const mid_f32x4 v = red[i][t][lane];
             sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
-        if (16 * rb + col < rows)
-            *reinterpret_cast<mid_f32x4*>(dst + (int64_t)(16 * rb + col) * N + (int64_t)grp * 64 + 16 * sb + 4 * q) = sum;
+        if (16 * rb + col < rows)   // partial sums of a K-chunk stay fp32; the sum over the chunks is rounded
+            store4(dst, (int64_t)(16 * rb + col) * N + (int64_t)grp * 64 + 16 * sb + 4 * q, sum, SPLIT ? 0 : ybf16);
     }
 }
 
@@ -277,15 +279,16 @@ static void launch_mid_t(const GemmArgs& a, const WeightSet& set, int64_t m0, in
         WeightSet part = set;
         part.Y[0] = a.ws;
         const dim3 grid((unsigned)set.units, (unsigned)split);
-        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
-        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
-        else hipLaunchKernelGGL((mid_kernel<TILE, 4, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part);
-        wr_reduce(a.ws, (size_t)rows * (size_t)set.N[0] / 4, split, set.Y[0] + m0 * set.N[0], stream);
+        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part, 0);
+        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part, 0);
+        else hipLaunchKernelGGL((mid_kernel<TILE, 4, true>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, part, 0);
+        float* y0 = a.ybf16 ? reinterpret_cast<float*>(reinterpret_cast<uint16_t*>(set.Y[0]) + m0 * set.N[0]) : set.Y[0] + m0 * set.N[0];
+        wr_reduce(a.ws, (size_t)rows * (size_t)set.N[0] / 4, split, y0, a.ybf16, stream);
     } else {
         const dim3 grid((unsigned)set.units);
-        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
-        else hipLaunchKernelGGL((mid_kernel<TILE, 4, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set);
+        if (rows <= 16) hipLaunchKernelGGL((mid_kernel<TILE, 1, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+        else if (rows <= 32) hipLaunchKernelGGL((mid_kernel<TILE, 2, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+        else hipLaunchKernelGGL((mid_kernel<TILE, 4, false>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
     }
 }
 

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "epilogue.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -33,7 +34,7 @@ __device__ __forceinline__ int xs_off(int m, int p) { return m * 128 + ((p ^ ((m
 template <int TILE, int BM>
 __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                          const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                         int Tk, float* __restrict__ Y) {
+                                                         int Tk, float* __restrict__ Y, int ybf16) {
     static_assert(BM == 128, "wave layout below assumes a 128 x 128 workgroup tile");
     constexpr int KPT = TILE / kStepCols;
     __shared__ __attribute__((aligned(16))) uint8_t As[2 * 4 * kDenseFragBytes];  // [half][strip][fragment]
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restr
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                *reinterpret_cast<f32x4*>(Y + m * N + n0 + 64 * wn + 32 * a + 8 * g + 4 * q) = v;
+                store4(Y, m * N + n0 + 64 * wn + 32 * a + 8 * g + 4 * q, v, ybf16);
             }
     }
 }
@@ -215,7 +216,7 @@ __device__ __forceinline__ void mma_step(f32x16& c0, f32x16& c1, const bf16x8& a
 
 __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                            const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y) {
+                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
     constexpr int TILE = 128, KPT = 2;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* const As = lds;                                  // [stage][tile row][strip][2048]
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                *reinterpret_cast<f32x4*>(Y + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q) = v;
+                store4(Y, m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q, v, ybf16);
             }
     }
 }
@@ -404,14 +405,14 @@ void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t str
         const int nblk = tiles_n * tiles_m;
         const int grid = ((nblk + 7) / 8) * 8;
         hipLaunchKernelGGL(prefill_kernel_t128, dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk,
-                           tiles_n, tiles_m, a.Y);
+                           tiles_n, tiles_m, a.Y, a.ybf16);
         return;
     }
     dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);
     if (a.tile == 128)
-        hipLaunchKernelGGL((prefill_kernel_v0<128, 128>), grid, block, 0, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, a.Y);
+        hipLaunchKernelGGL((prefill_kernel_v0<128, 128>), grid, block, 0, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, a.Y, a.ybf16);
     else
-        hipLaunchKernelGGL((prefill_kernel_v0<64, 128>), grid, block, 0, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, a.Y);
+        hipLaunchKernelGGL((prefill_kernel_v0<64, 128>), grid, block, 0, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, a.Y, a.ybf16);
 }
 
 }  // namespace patch

@@ -32,6 +32,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "epilogue.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -173,14 +174,14 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 
 // Y = sum over the slices of the partial products, slice 0 first: a fixed order, so the result is reproducible.
 // (Adding the partials to Y with fp32 atomics instead was 2-3x slower than this second launch.)
-__global__ __launch_bounds__(256) void wr_reduce_kernel(const wr_f32x4* __restrict__ ws, size_t n4, int slices, wr_f32x4* __restrict__ Y) {
+__global__ __launch_bounds__(256) void wr_reduce_kernel(const wr_f32x4* __restrict__ ws, size_t n4, int slices, float* __restrict__ Y, int ybf16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
         wr_f32x4 acc = ws[i];
         for (int s = 1; s < slices; ++s) {
             const wr_f32x4 v = ws[(size_t)s * n4 + i];
             acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
         }
-        Y[i] = acc;
+        store4(Y, (int64_t)(4 * i), acc, ybf16);
     }
 }
 
@@ -209,7 +210,7 @@ __device__ __forceinline__ void wr_tile_of(int t, int tiles_n, int tiles_m, int&
 // Sum of the partial tiles of a MODE 2 launch (slot (t - t0) * slices + y, 256 rows x 256 features each, slice 0
 // first) into Y.  Block = 16 rows of one tile; thread = 4 x 4 features of one row.
 __global__ __launch_bounds__(256) void wr_tail_reduce_kernel(const float* __restrict__ ws, int slices, int t0, int tiles_n, int tiles_m,
-                                                             int64_t M, int Tk_all, const WeightSet set) {
+                                                             int64_t M, int Tk_all, const WeightSet set, int ybf16) {
     const int j = blockIdx.x >> 4, chunk = blockIdx.x & 15;
     int bn, bm;
     wr_tile_of(t0 + j, tiles_n, tiles_m, bn, bm);
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256) void wr_tail_reduce_kernel(const float* __rest
             const wr_f32x4 v = *reinterpret_cast<const wr_f32x4*>(src + (int64_t)y * (kWrBM * kWrBN));
             acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
         }
-        *reinterpret_cast<wr_f32x4*>(Y + m * N + (int64_t)row * 128 + (f & 127)) = acc;
+        store4(Y, m * N + (int64_t)row * 128 + (f & 127), acc, ybf16);
     }
 }
 
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(256) void wr_tail_reduce_kernel(const float* __rest
 //         (t - t0) * gridDim.y + y of the workspace, wr_tail_reduce_kernel sums the slots into Y.
 template <int MODE>
 __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __restrict__ X, int64_t M, int64_t K, int Tk_all, int tiles_n,
-                                                           int tiles_m, int t0, int cnt, const WeightSet set) {
+                                                           int tiles_m, int t0, int cnt, const WeightSet set, int ybf16) {
     constexpr bool SPLIT = MODE != 0;
     constexpr int TILE = 128;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -557,17 +558,19 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
         const int64_t m = m0 + 16 * CB + col;                                                                      \
-        float* yrow = MODE == 2 ? Y + ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + col) * kWrBN + 128 * tr + 64 * sh + 4 * q \
-                                : Y + (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;         \
+        /* element offset of this lane's first four features: a workspace slot (MODE 2), a workspace slice (MODE 1), Y */ \
+        const int64_t ye = MODE == 2 ? ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + col) * kWrBN + 128 * tr + 64 * sh + 4 * q \
+                                     : (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;      \
+        const int yb = MODE == 0 ? ybf16 : 0; /* partial products stay fp32; their sum is rounded by the reduction */  \
         float v[4];                                                                                                \
         PATCH_WR_READ(0, CB);                                                                                      \
-        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) store4(Y, ye, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                               \
         PATCH_WR_READ(1, CB);                                                                                      \
-        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 16) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) store4(Y, ye + 16, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
         PATCH_WR_READ(2, CB);                                                                                      \
-        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 32) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) store4(Y, ye + 32, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
         PATCH_WR_READ(3, CB);                                                                                      \
-        if (MODE == 2 || m < M) *reinterpret_cast<wr_f32x4*>(yrow + 48) = wr_f32x4{v[0], v[1], v[2], v[3]};                                        \
+        if (MODE == 2 || m < M) store4(Y, ye + 48, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
     }
         PATCH_WR_16(PATCH_WR_STORE)
 #undef PATCH_WR_STORE
@@ -642,10 +645,10 @@ static void wr_grant_lds() {
     (void)granted2;
 }
 
-void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t stream) {
+void wr_reduce(const float* ws, size_t n4, int slices, float* Y, int ybf16, hipStream_t stream) {
     const size_t blocks = (n4 + 255) / 256;
     hipLaunchKernelGGL(wr_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
-                       reinterpret_cast<const wr_f32x4*>(ws), n4, slices, reinterpret_cast<wr_f32x4*>(Y));
+                       reinterpret_cast<const wr_f32x4*>(ws), n4, slices, Y, ybf16);
 }
 
 void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
@@ -667,22 +670,22 @@ void launch_prefill_wreg(const GemmArgs& a, int split_k, hipStream_t stream) {
         const int body = nblk - tail;
         set.Y[0] = a.Y;
         hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(((body + 7) / 8) * 8), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
-                           tiles_m, 0, body, set);
+                           tiles_m, 0, body, set, a.ybf16);
         set.Y[0] = a.ws;
         hipLaunchKernelGGL(prefill_kernel_wreg<2>, dim3(((tail + 7) / 8) * 8, tail_split), dim3(256), kWrLds, stream, a.X, a.M, a.K,
-                           a.Tk, tiles_n, tiles_m, body, tail, set);
+                           a.Tk, tiles_n, tiles_m, body, tail, set, 0);
         set.Y[0] = a.Y;
         hipLaunchKernelGGL(wr_tail_reduce_kernel, dim3(tail * 16), dim3(256), 0, stream, a.ws, tail_split, body, tiles_n, tiles_m, a.M,
-                           a.Tk, set);
+                           a.Tk, set, a.ybf16);
     } else if (split == 1) {
         set.Y[0] = a.Y;
         hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n, tiles_m, 0, nblk,
-                           set);
+                           set, a.ybf16);
     } else {
         set.Y[0] = a.ws;
         hipLaunchKernelGGL(prefill_kernel_wreg<1>, dim3(grid, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, tiles_n,
-                           tiles_m, 0, nblk, set);
-        wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, stream);
+                           tiles_m, 0, nblk, set, 0);
+        wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, a.ybf16, stream);
     }
 }
 
@@ -695,18 +698,18 @@ void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_
     if (tail_split > 1) {
         const int body = nblk - tail;
         hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(((body + 7) / 8) * 8), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, set.units,
-                           tiles_m, 0, body, set);
+                           tiles_m, 0, body, set, a.ybf16);
         WeightSet part = set;
         for (int i = 0; i < kMaxMany; ++i) part.Y[i] = a.ws;   // partial tiles go to workspace slots, whatever the weight
         hipLaunchKernelGGL(prefill_kernel_wreg<2>, dim3(((tail + 7) / 8) * 8, tail_split), dim3(256), kWrLds, stream, a.X, a.M, a.K,
-                           a.Tk, set.units, tiles_m, body, tail, part);
+                           a.Tk, set.units, tiles_m, body, tail, part, 0);
         hipLaunchKernelGGL(wr_tail_reduce_kernel, dim3(tail * 16), dim3(256), 0, stream, a.ws, tail_split, body, set.units, tiles_m, a.M,
-                           a.Tk, set);
+                           a.Tk, set, a.ybf16);
         return;
     }
     const int grid = ((nblk + 7) / 8) * 8;
     hipLaunchKernelGGL(prefill_kernel_wreg<0>, dim3(grid), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk, set.units, tiles_m, 0, nblk,
-                       set);
+                       set, a.ybf16);
 }
 
 }  // namespace patch

@@ -25,6 +25,7 @@ struct GemmArgs {
     float* ws = nullptr;    // caller's workspace for split-K partial products (prefill), may be null
     size_t ws_bytes = 0;
     int n_cus;
+    int ybf16 = 0;          // nonzero: Y (and every Y of a set) is bf16, the accumulator rounded to nearest even
 };
 
 // Up to kMaxMany weights that share one X (same K, same tile), multiplied in one launch.  The launch numbers its
@@ -40,6 +41,15 @@ struct WeightSet {
     int count, units;            // weights, units in total
 };
 typedef WeightSet DecodeSet;
+// A set of one, for the kernels' single-weight instantiations: 32 bytes of kernel arguments instead of 300.  Every
+// wavefront reads its arguments before it can request anything else, the set's arrays in several dependent rounds
+// (which weight? then that weight's pointers), and a decode launch is short enough for that to show.
+struct WeightOne {
+    const uint8_t* payload;
+    const uint32_t* table;
+    float* Y;
+    int64_t N;
+};
 
 // Up to kDecodeRows rows of X starting at row m0 (decode shape; 16-row blocks, the weights streamed once per launch).
 constexpr int kDecodeRows = 64;
@@ -55,7 +65,7 @@ int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int r
 int mid_split(const GemmArgs& a, int rows, int requested);
 void launch_mid_set(const GemmArgs& a, const WeightSet& set, int64_t m0, int rows, int split, hipStream_t stream);
 // Y[i] = sum over the slices of ws[slice * n4 + i] (float4 units), slice 0 first
-void wr_reduce(const float* ws, size_t n4, int slices, float* Y, hipStream_t stream);
+void wr_reduce(const float* ws, size_t n4, int slices, float* Y, int ybf16, hipStream_t stream);
 
 // Any M (prefill shape).
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream);

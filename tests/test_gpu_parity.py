@@ -105,6 +105,17 @@ class Prepared:
         torch.cuda.synchronize()
         return Y.cpu().numpy()
 
+    def gemm_bf16(self, X_bits, **kw):
+        """The same product with a bf16 Y (patch_gemm_opts.y_bf16): bit patterns, uint16."""
+        M = X_bits.shape[0]
+        X = to_dev_bf16(X_bits, self.dev)
+        Y = torch.full((M, self.c.N), float("nan"), device=self.dev, dtype=torch.bfloat16)
+        if kw.get("workspace") is not None:
+            kw["workspace"].fill_(float("nan"))
+        B.patch_gemm(X, M, self.P, Y, stream(), y_bf16=True, **kw)
+        torch.cuda.synchronize()
+        return bits_of(Y)
+
     def check(self, X_bits, Y, Yo=None, what=""):
         """Full-output comparison with the oracle: relF and every element."""
         if Yo is None:
@@ -562,6 +573,79 @@ def test_random_shapes_and_schedules(dev):
             Y = p.gemm(c.X, **kw)
             p.check(c.X, Y, Yo, f"random case {case}")
         p.P.close()
+
+
+def _bf16_order(bits):
+    """bf16 bit patterns -> integers whose difference counts representable values between two numbers."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b)
+
+
+def check_bf16(bits, Yo, xn, wn, K, what=""):
+    """bf16 output against the oracle's exact product rounded once (round_bf16): every element within one unit in
+    the last place of it - or, where the product nearly cancels and an ulp of the result is smaller than the
+    accumulation error allowed to the fp32 output, within that bound plus one ulp."""
+    want = oracle.round_bf16(Yo)
+    assert not ((bits & 0x7FFF) > 0x7F80).any(), f"{what}: NaN in the output (unwritten?)"
+    dist = np.abs(_bf16_order(bits) - _bf16_order(want))
+    got = synth.bf16_bits_to_f64(bits)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(Yo), 2.0 ** -126))) - 7)
+    bound = elem_bound(xn[:, None], wn[None, :], K) + ulp
+    ok = (dist <= 1) | (np.abs(got - Yo) <= bound)
+    print(f"  bf16 parity {what}: exact {float((dist == 0).mean()):.4f}, one ulp off {float((dist == 1).mean()):.4f}, "
+          f"by the absolute bound {int(((dist > 1) & ok).sum())} of {dist.size}", flush=True)
+    assert ok.all(), f"{what}: element {np.unravel_index(np.argmax(~ok), ok.shape)} is more than one ulp off"
+    assert (dist == 0).mean() > 0.98, "double rounding can cost an ulp only rarely"
+
+
+def test_bf16_output_is_the_rounded_product(dev):
+    """patch_gemm_opts.y_bf16 on every kernel and schedule that writes Y: within one ulp of the oracle's product
+    rounded once, and bit-equal to the fp32 output of the same schedule rounded to nearest even (the same
+    accumulator goes through the same rounding)."""
+    ws = torch.empty(16 << 20, device=dev, dtype=torch.float32)
+    for name, N, K, t, f, M in [("b128", 384, 1024, 128, 0.5, 300), ("b64", 192, 320, 64, 0.4, 130)]:
+        c = synth.make_case("bf16out_" + name, N, K, M, t, f, seed=61)
+        p = Prepared(c, dev)
+        scheds = [(1, dict()), (16, dict(path=B.PATH_DECODE)), (40, dict(path=B.PATH_DECODE)), (40, dict(path=B.PATH_DECODE, variant=4)),
+                  (40, dict(path=B.PATH_DECODE, variant=4, workspace=ws, split_k=2)), (M, dict(path=B.PATH_PREFILL)),
+                  (M - 33, dict(path=B.PATH_PREFILL, variant=1 if t == 64 else 2)), (M, dict(workspace=ws))]
+        if t == 128:
+            scheds += [(M, dict(path=B.PATH_PREFILL, workspace=ws, split_k=3)), (70, dict(path=B.PATH_DECODE))]
+        for Mi, kw in scheds:
+            what = f"{name} M={Mi} " + str({k: v for k, v in kw.items() if k != "workspace"}) + (" +workspace" if "workspace" in kw else "")
+            print("bf16 out: " + what, flush=True)
+            Xb = c.X[:Mi]
+            bits = p.gemm_bf16(Xb, **kw)
+            Y32 = p.gemm(Xb, **kw)
+            assert np.array_equal(bits, synth.f32_to_bf16_bits(Y32)), what + ": not the fp32 output rounded to nearest even"
+            check_bf16(bits, p.oracle_gemm(Xb), row_norms(Xb), p.wn, K, what)
+        p.P.close()
+    # a set of weights sharing X, decode and prefill launches
+    cases = [synth.make_case(f"bf16many{i}", N, 1024, 300, 128, f, seed=62) for i, (N, f) in enumerate([(512, 0.5), (256, 1.0)])]
+    preps = [Prepared(c, dev) for c in cases]
+    Xd = to_dev_bf16(cases[0].X, dev)
+    for M in (1, 300):
+        Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.bfloat16) for c in cases]
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), y_bf16=True)
+        torch.cuda.synchronize()
+        for p, Y in zip(preps, Ys):
+            check_bf16(bits_of(Y), p.oracle_gemm(cases[0].X[:M]), row_norms(cases[0].X[:M]), p.wn, 1024, f"set M={M}")
+    for p in preps:
+        p.P.close()
+
+
+def test_bf16_output_full_size_prefill_sampled(dev):
+    """The headline gate projection (11008 x 4096, M = 4096, 60 % 2:4 tiles) with a bf16 Y: a seeded sample of rows
+    against the oracle's rounded product, and bit-equal to the rounded fp32 output everywhere."""
+    N, K, M = 11008, 4096, 4096
+    c = synth.make_case("mlp_prefill", N, K, M, 128, 0.6, seed=7)
+    p = Prepared(c, dev)
+    bits = p.gemm_bf16(c.X)
+    assert np.array_equal(bits, synth.f32_to_bf16_bits(p.gemm(c.X)))
+    rows = np.sort(np.random.default_rng(3).choice(M, size=16, replace=False))
+    Xr = np.ascontiguousarray(c.X[rows])
+    check_bf16(bits[rows], p.oracle_gemm(Xr), row_norms(Xr), p.wn, K, "gate projection, 16 sampled rows")
+    p.P.close()
 
 
 def test_empty_batch_is_a_no_op(dev):

@@ -364,3 +364,69 @@ def test_hard_masks_against_numpy_argmax_and_invariants():
                 assert (blk == src).all()
             else:
                 assert (((blk & 0x7FFF) != 0).reshape(-1, 4).sum(axis=1) <= 2).all()
+
+
+# ---------------------------------------------------------------------------------------------------------
+# bf16 output rounding (an option of the library; the oracle rounds the exact product once, to nearest even)
+
+def test_round_bf16_is_the_identity_on_every_bf16_value():
+    """All 65536 bit patterns: a value that already is a bf16 number rounds to itself (NaNs stay NaNs)."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = synth.bf16_bits_to_f64(bits)
+    out = oracle.round_bf16(vals)
+    nan = np.isnan(vals)
+    assert np.array_equal(out[~nan], bits[~nan])
+    assert ((out[nan] & 0x7F80) == 0x7F80).all() and ((out[nan] & 0x007F) != 0).all()
+
+
+def test_round_bf16_ties_halfway_cases_and_range_ends():
+    """Hand-worked cases.  bf16 spacing in [1, 2) is 2^-7: 1 + 2^-8 lies halfway between 1 (even significand) and
+    1 + 2^-7 (odd) and goes down; 1 + 3 * 2^-8 lies halfway between 1 + 2^-7 (odd) and 1 + 2^-6 (even) and goes up;
+    anything past the halfway point goes to the nearer neighbour."""
+    one = 0x3F80
+    cases = [
+        (1.0 + 2.0 ** -8, one),                      # tie -> even (down)
+        (1.0 + 3 * 2.0 ** -8, one + 2),              # tie -> even (up)
+        (1.0 + 2.0 ** -8 + 2.0 ** -40, one + 1),     # just above the tie: up (a float32 detour would lose the 2^-40)
+        (1.0 + 2.0 ** -8 - 2.0 ** -40, one),         # just below: down
+        (-(1.0 + 3 * 2.0 ** -8), 0x8000 | (one + 2)),
+        (2.0 - 2.0 ** -9, 0x4000),                   # rounds up into the next binade: 2.0
+        (0.0, 0x0000), (-0.0, 0x8000),
+        (2.0 ** -133, 0x0001),                       # smallest subnormal
+        (2.0 ** -134, 0x0000),                       # half of it: tie -> even (zero)
+        (3 * 2.0 ** -134, 0x0002),                   # 1.5 subnormal quanta: tie -> even (2)
+        (2.0 ** -126, 0x0080),                       # smallest normal
+        ((2.0 - 2.0 ** -7) * 2.0 ** 127, 0x7F7F),    # largest finite
+        ((2.0 - 2.0 ** -8) * 2.0 ** 127, 0x7F80),    # halfway to 2^128: tie -> even = overflow -> inf
+        (1e39, 0x7F80), (-1e39, 0xFF80), (float("inf"), 0x7F80),
+    ]
+    got = oracle.round_bf16(np.array([c[0] for c in cases]))
+    for (v, want), g in zip(cases, got):
+        assert int(g) == want, (v, hex(int(g)), hex(want))
+
+
+def test_round_bf16_agrees_with_library_rounding_of_float32():
+    """On values that are float32 numbers the single rounding equals the library's float32 -> bf16 conversion
+    (torch, round to nearest even) and the integer-trick rounding of the input generator."""
+    import torch
+    rng = np.random.default_rng(77)
+    x = np.concatenate([rng.standard_normal(200000).astype(np.float32) * np.float32(10.0 ** rng.integers(-30, 30)),
+                        rng.standard_normal(100000).astype(np.float32)])
+    got = oracle.round_bf16(x.astype(np.float64))
+    lib = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, lib)
+    assert np.array_equal(got, synth.f32_to_bf16_bits(x))
+
+
+def test_round_bf16_is_the_nearest_value_by_brute_force():
+    """For random doubles: among all finite bf16 values none is closer than the one returned."""
+    rng = np.random.default_rng(78)
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    allv = synth.bf16_bits_to_f64(bits)
+    fin = np.isfinite(allv)
+    grid = np.sort(allv[fin])
+    y = rng.standard_normal(2000) * 10.0 ** rng.uniform(-3, 3, 2000)
+    got = synth.bf16_bits_to_f64(oracle.round_bf16(y))
+    j = np.searchsorted(grid, y)
+    best = np.minimum(np.abs(grid[np.clip(j, 0, grid.size - 1)] - y), np.abs(grid[np.clip(j - 1, 0, grid.size - 1)] - y))
+    assert np.array_equal(np.abs(got - y), best)
