@@ -37,7 +37,8 @@ typedef enum {
     PATCH_ERR_NOT_24 = 3, /* a group of four in a tile flagged 2:4 holds more than two nonzeros      */
     PATCH_ERR_ALLOC = 4,  /* device or host allocation failed                                        */
     PATCH_ERR_HIP = 5,    /* a HIP runtime call failed (patch_last_hip_error gives the code)         */
-    PATCH_ERR_SIZE = 6    /* a caller-provided host buffer is too small                              */
+    PATCH_ERR_SIZE = 6,   /* a caller-provided host buffer is too small                              */
+    PATCH_ERR_NOT_FOUND = 7 /* patch_tune_table_get: no schedule stored for this key                       */
 } patch_status;
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
@@ -153,20 +154,63 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
 patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream);
 
 /*
- * Schedule autotuner (Appendix A leaves tile shape and schedule - e.g. split-K - to an autotuner run per layer
- * and input shape, decode first).  Times the candidate schedules of patch_gemm_ex for this M and P on the device,
- * on real operands, and returns the fastest.  Candidates: both paths where they apply (decode passes up to
- * M = 256), the kernel variants of the path, and the K-split counts the workspace allows.
- *   X, Y       as for patch_gemm (Y is overwritten several times; on return it holds the product)
+ * Schedule autotuner (Appendix A leaves the execution tile and the schedule - e.g. split-K - to an autotuner that is
+ * run per layer and input shape, on the decode input first).  patch_tune_all times every candidate schedule of
+ * patch_gemm_ex for this M and P on the device, on real operands; patch_tune returns the fastest.  Candidates:
+ *   decode path (M <= 256): 16-feature-strip kernel with 8 or 4 K-steps per wavefront (variants 2 / 3) and 2 .. 16
+ *     wavefronts per workgroup (split_k: the wavefronts-per-compute-unit dimension), the 64-features-per-wavefront
+ *     kernel (variant 4) unsplit and with K chunks over the workspace;
+ *   prefill path, tile 128: the execution tiles 256 x 256 with one wavefront per SIMD (default), 256 x 256 with two
+ *     (variant 2) and the small 128 x 128 tile (variant 1; Appendix O reports that small execution tiles under-use
+ *     the matrix units - it is timed so that the report shows it), and the K-split counts the workspace allows;
+ *   prefill path, tile 64: the 128 x 128 kernel.
+ *   X, Y       as for patch_gemm (Y is overwritten several times; after patch_tune it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1
- *   best       OUT: the options to pass to patch_gemm_ex / patch_gemm_many (workspace fields included)
+ *   results    HOST array of `cap` entries; receives min(*count, cap) candidates in candidate order, each with its
+ *              average time per launch; *count = number of candidates timed
+ *   best       OUT: the options to pass to patch_gemm_ex / patch_gemm_many (workspace fields included: NULL when the
+ *              winner was timed without one - then run it without one)
  *   best_us    OUT, may be NULL: its average time per launch in microseconds
- * Not a hot-path call: it creates and destroys two HIP events and synchronises `stream` after every candidate.
- * Errors as patch_gemm_ex, plus PATCH_ERR_ARG for reps < 1 or a NULL `best`.
+ * Not hot-path calls: they create and destroy two HIP events and synchronise `stream` after every candidate.
+ * Errors as patch_gemm_ex, plus PATCH_ERR_ARG for reps < 1 or a NULL `best` / `results` / `count`.
  */
+typedef struct {
+    patch_gemm_opts opts;
+    float us;
+} patch_tune_result;
+patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
+                            void* stream, int reps, patch_tune_result* results, size_t cap, size_t* count);
 patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
                         void* stream, int reps, patch_gemm_opts* best, float* best_us);
+
+/*
+ * Table of tuned schedules (host memory; Appendix A: the tuner's choice is kept per layer shape and input shape and
+ * reused).  Key = (M bucket, N, K, tile, number of 2:4 tiles); the M bucket is the smallest power of two >= M
+ * (patch_tune_bucket).  A stored schedule remembers whether it was timed with a workspace, not the pointer.
+ *   patch_tune_table_put  stores / replaces; opts->workspace != NULL marks "uses a workspace"
+ *   patch_tune_table_get  PATCH_OK and *out filled (its workspace fields = the arguments when the schedule uses a
+ *                         workspace, else NULL / 0); PATCH_ERR_NOT_FOUND if no entry, or if the entry uses a
+ *                         workspace and none is given
+ *   patch_tune_layer      the paper's order for one layer: tunes the decode input first, then the prefill input, and
+ *                         stores both.  What the decode choice pins for prefill in the paper - the mask tile and with
+ *                         it the compressed layout - is fixed when P is packed here, and both inputs run from the one
+ *                         P; the kernels' execution tiles are independent of the layout, so the second search is not
+ *                         narrowed by the first.  Y must hold max(M_decode, M_prefill) x N floats.
+ * The table is internally locked; entries are plain values.  Errors: PATCH_ERR_ARG, PATCH_ERR_ALLOC, and those of
+ * patch_tune.
+ */
+typedef struct patch_tune_table patch_tune_table;
+int64_t patch_tune_bucket(int64_t M);
+patch_status patch_tune_table_create(patch_tune_table** out);
+void patch_tune_table_destroy(patch_tune_table* t);
+size_t patch_tune_table_size(const patch_tune_table* t);
+patch_status patch_tune_table_put(patch_tune_table* t, int64_t M, int64_t N, int64_t K, int tile, int64_t n_sparse_tiles,
+                                  const patch_gemm_opts* opts);
+patch_status patch_tune_table_get(const patch_tune_table* t, int64_t M, int64_t N, int64_t K, int tile, int64_t n_sparse_tiles,
+                                  void* workspace, size_t workspace_bytes, patch_gemm_opts* out);
+patch_status patch_tune_layer(patch_tune_table* t, const void* X_decode, int64_t M_decode, const void* X_prefill, int64_t M_prefill,
+                              const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes, void* stream, int reps);
 
 /* Bytes of patch_gemm_opts.workspace the product with these M, P and opts (path, split_k; NULL = defaults) would
  * use if it were given enough: slices x M x N x 4 for a split prefill launch, slices x tiles x 256 KB when only the

@@ -14,11 +14,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpatch_hip.so")
 
-OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE = range(7)
+OK, ERR_ARG, ERR_SHAPE, ERR_NOT_24, ERR_ALLOC, ERR_HIP, ERR_SIZE, ERR_NOT_FOUND = range(8)
 PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 
 EXPORTS = [
-    "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_unpack",
+    "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_tune_all",
+    "patch_tune_bucket", "patch_tune_table_create", "patch_tune_table_destroy", "patch_tune_table_size", "patch_tune_table_put",
+    "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -27,6 +29,10 @@ EXPORTS = [
 class GemmOpts(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("y_bf16", ctypes.c_int)]
+
+
+class TuneResult(ctypes.Structure):
+    _fields_ = [("opts", GemmOpts), ("us", ctypes.c_float)]
 
 
 class PatchError(RuntimeError):
@@ -56,6 +62,22 @@ def lib() -> ctypes.CDLL:
         L.patch_gemm_ex.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(GemmOpts)]
         L.patch_tune.argtypes = [vp, i64, vp, vp, vp, sz, vp, ci, ctypes.POINTER(GemmOpts), ctypes.POINTER(ctypes.c_float)]
         L.patch_tune.restype = ci
+        L.patch_tune_all.argtypes = [vp, i64, vp, vp, vp, sz, vp, ci, ctypes.POINTER(TuneResult), sz, ctypes.POINTER(sz)]
+        L.patch_tune_all.restype = ci
+        L.patch_tune_bucket.argtypes = [i64]
+        L.patch_tune_bucket.restype = i64
+        L.patch_tune_table_create.argtypes = [ctypes.POINTER(vp)]
+        L.patch_tune_table_create.restype = ci
+        L.patch_tune_table_destroy.argtypes = [vp]
+        L.patch_tune_table_destroy.restype = None
+        L.patch_tune_table_size.argtypes = [vp]
+        L.patch_tune_table_size.restype = sz
+        L.patch_tune_table_put.argtypes = [vp, i64, i64, i64, ci, i64, ctypes.POINTER(GemmOpts)]
+        L.patch_tune_table_put.restype = ci
+        L.patch_tune_table_get.argtypes = [vp, i64, i64, i64, ci, i64, vp, sz, ctypes.POINTER(GemmOpts)]
+        L.patch_tune_table_get.restype = ci
+        L.patch_tune_layer.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, sz, vp, ci]
+        L.patch_tune_layer.restype = ci
         L.patch_gemm_workspace_bytes.argtypes = [i64, vp, ctypes.POINTER(GemmOpts)]
         L.patch_gemm_workspace_bytes.restype = sz
         L.patch_gemm_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp, ctypes.POINTER(GemmOpts)]
@@ -213,6 +235,74 @@ def patch_tune(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, st
     _check(lib().patch_tune(_ptr(X), M, P.handle, _ptr(Y), _ptr(workspace) if workspace is not None else None,
                             workspace_bytes or 0, stream, reps, ctypes.byref(o), ctypes.byref(us)), "patch_tune")
     return dict(path=o.path, split_k=o.split_k, variant=o.variant, uses_workspace=bool(o.workspace)), float(us.value)
+
+
+def _sched(o: GemmOpts) -> dict:
+    return dict(path=o.path, split_k=o.split_k, variant=o.variant, uses_workspace=bool(o.workspace))
+
+
+def patch_tune_all(X, M: int, P: Packed, Y, workspace=None, workspace_bytes=None, stream: int = 0, reps: int = 20):
+    """-> list of (schedule dict, microseconds per launch) for every candidate the tuner times, in candidate order."""
+    if workspace is not None and workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    cap = 64
+    res, n = (TuneResult * cap)(), ctypes.c_size_t(0)
+    _check(lib().patch_tune_all(_ptr(X), M, P.handle, _ptr(Y), _ptr(workspace) if workspace is not None else None,
+                                workspace_bytes or 0, stream, reps, res, cap, ctypes.byref(n)), "patch_tune_all")
+    return [(_sched(res[i].opts), float(res[i].us)) for i in range(min(n.value, cap))]
+
+
+class TuneTable:
+    """Owner of a patch_tune_table*: tuned schedules keyed by (M bucket, N, K, tile, 2:4 tile count)."""
+
+    def __init__(self):
+        h = ctypes.c_void_p(0)
+        _check(lib().patch_tune_table_create(ctypes.byref(h)), "patch_tune_table_create")
+        self.handle = h.value
+
+    def close(self):
+        if self.handle:
+            lib().patch_tune_table_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __len__(self):
+        return int(lib().patch_tune_table_size(self.handle))
+
+    def put(self, M: int, N: int, K: int, tile: int, n_sparse: int, path=PATH_AUTO, split_k=0, variant=0, uses_workspace=False):
+        o = GemmOpts(path, split_k, variant, 16 if uses_workspace else None, 0, 0)
+        _check(lib().patch_tune_table_put(self.handle, M, N, K, tile, n_sparse, ctypes.byref(o)), "patch_tune_table_put")
+
+    def get(self, M: int, N: int, K: int, tile: int, n_sparse: int, workspace=None, workspace_bytes=None):
+        """-> schedule dict, or None when nothing usable is stored for the key."""
+        if workspace is not None and workspace_bytes is None:
+            workspace_bytes = workspace.numel() * workspace.element_size()
+        o = GemmOpts()
+        st = lib().patch_tune_table_get(self.handle, M, N, K, tile, n_sparse, _ptr(workspace) if workspace is not None else None,
+                                        workspace_bytes or 0, ctypes.byref(o))
+        if st == ERR_NOT_FOUND:
+            return None
+        _check(st, "patch_tune_table_get")
+        return _sched(o)
+
+    def get_for(self, M: int, P: Packed, workspace=None):
+        N, K, t, ns = P.dims()
+        return self.get(M, N, K, t, ns, workspace)
+
+    def tune_layer(self, X_decode, M_decode: int, X_prefill, M_prefill: int, P: Packed, Y, workspace=None, stream: int = 0, reps: int = 10):
+        """Decode input first, then the prefill input; both schedules are stored."""
+        wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        _check(lib().patch_tune_layer(self.handle, _ptr(X_decode), M_decode, _ptr(X_prefill), M_prefill, P.handle, _ptr(Y),
+                                      _ptr(workspace) if workspace is not None else None, wb, stream, reps), "patch_tune_layer")
+
+
+def tune_bucket(M: int) -> int:
+    return int(lib().patch_tune_bucket(M))
 
 
 def run_tuned(X, M: int, P: Packed, Y, tuned: dict, workspace=None, stream: int = 0) -> None:

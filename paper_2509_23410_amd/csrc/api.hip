@@ -5,8 +5,10 @@
 #include <string.h>
 
 #include <algorithm>
+#include <map>
 #include <mutex>
 #include <new>
+#include <tuple>
 #include <vector>
 
 #include "../../include/patch.h"
@@ -157,6 +159,7 @@ const char* patch_strerror(patch_status s) {
         case PATCH_ERR_ALLOC: return "allocation failed";
         case PATCH_ERR_HIP: return "HIP runtime error";
         case PATCH_ERR_SIZE: return "caller buffer too small";
+        case PATCH_ERR_NOT_FOUND: return "no tuned schedule stored for this key";
     }
     return "unknown status";
 }
@@ -351,19 +354,23 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     return PATCH_OK;
 }
 
-patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
-                        void* stream, int reps, patch_gemm_opts* best, float* best_us) {
-    if (!X || !P || !Y || !best || M <= 0 || reps < 1) return PATCH_ERR_ARG;
+patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
+                            void* stream, int reps, patch_tune_result* results, size_t cap, size_t* count) {
+    if (!X || !P || !Y || !results || !count || M <= 0 || reps < 1) return PATCH_ERR_ARG;
     if (!aligned16(X) || !aligned16(Y) || (workspace && !aligned16(workspace))) return PATCH_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<patch_gemm_opts> cand;
     auto add = [&](int path, int split_k, int variant, bool ws) {
         cand.push_back(patch_gemm_opts{path, split_k, variant, ws ? workspace : nullptr, ws ? workspace_bytes : 0, 0});
     };
+    const int steps = P->Tk * (P->tile / kStepCols);
     if (M <= 256) {  // every pass of 64 rows streams the whole weight again: no contender beyond that
         add(PATCH_PATH_DECODE, 0, 0, false);
-        add(PATCH_PATH_DECODE, 0, 2, false);
-        add(PATCH_PATH_DECODE, 0, 3, false);
+        add(PATCH_PATH_DECODE, 0, 2, false);   // 8 K-steps per wavefront
+        add(PATCH_PATH_DECODE, 0, 3, false);   // 4 K-steps per wavefront
+        for (int kw : {2, 4, 8, 16})           // wavefronts per workgroup
+            for (int v : {2, 3})
+                if (kw * (v == 2 ? 8 : 4) <= 2 * steps && (kw <= 8 || v == 3)) add(PATCH_PATH_DECODE, kw, v, false);
         if (M >= 12) {  // the 64-features-per-wavefront kernel, unsplit and with K-chunks over the workspace
             add(PATCH_PATH_DECODE, 0, 4, false);
             const size_t per_slice = (size_t)(M < kDecodeRows ? M : kDecodeRows) * (size_t)P->N * sizeof(float);
@@ -373,8 +380,9 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
         }
     }
     if (P->tile == 128) {
-        add(PATCH_PATH_PREFILL, 1, 0, false);
-        add(PATCH_PATH_PREFILL, 1, 2, false);
+        add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, one wavefront per SIMD
+        add(PATCH_PATH_PREFILL, 1, 2, false);   // 256 x 256, two wavefronts per SIMD
+        add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
         const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
         if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic: may split a part-filled last round only
         if (workspace)
@@ -387,8 +395,6 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
     HIP_TRY(hipEventCreate(&e0));
     if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); g_last_hip_error = (int)e; return PATCH_ERR_HIP; }
     patch_status st = PATCH_OK;
-    float best_ms = 0.f;
-    int best_i = -1;
     for (size_t i = 0; i < cand.size() && st == PATCH_OK; ++i) {
         for (int r = 0; r < 2 && st == PATCH_OK; ++r) st = patch_gemm_ex(X, M, P, Y, stream, &cand[i]);
         if (st != PATCH_OK) break;
@@ -399,15 +405,113 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
         if (e != hipSuccess) { g_last_hip_error = (int)e; st = PATCH_ERR_HIP; break; }
-        if (best_i < 0 || ms < best_ms) { best_ms = ms; best_i = (int)i; }
+        if (i < cap) results[i] = patch_tune_result{cand[i], ms * 1000.f / (float)reps};
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (st != PATCH_OK) return st;
-    *best = cand[best_i];
-    if (best_us) *best_us = best_ms * 1000.f / (float)reps;
+    *count = cand.size();
+    return PATCH_OK;
+}
+
+patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes,
+                        void* stream, int reps, patch_gemm_opts* best, float* best_us) {
+    if (!best) return PATCH_ERR_ARG;
+    constexpr size_t kCap = 64;
+    patch_tune_result res[kCap];
+    size_t n = 0;
+    const patch_status st = patch_tune_all(X, M, P, Y, workspace, workspace_bytes, stream, reps, res, kCap, &n);
+    if (st != PATCH_OK) return st;
+    if (n > kCap) n = kCap;
+    size_t bi = 0;
+    for (size_t i = 1; i < n; ++i)
+        if (res[i].us < res[bi].us) bi = i;
+    *best = res[bi].opts;
+    if (best_us) *best_us = res[bi].us;
     // leave the product of the chosen schedule in Y
     return patch_gemm_ex(X, M, P, Y, stream, best);
+}
+
+// ---- table of tuned schedules
+struct TuneKey {
+    int64_t bucket, N, K, n_sparse;
+    int tile;
+    bool operator<(const TuneKey& o) const {
+        return std::tie(bucket, N, K, n_sparse, tile) < std::tie(o.bucket, o.N, o.K, o.n_sparse, o.tile);
+    }
+};
+struct TuneEntry { int path, split_k, variant, y_bf16; bool uses_ws; };
+struct patch_tune_table {
+    mutable std::mutex mu;
+    std::map<TuneKey, TuneEntry> entries;
+};
+
+int64_t patch_tune_bucket(int64_t M) {
+    if (M <= 1) return 1;
+    int64_t b = 1;
+    while (b < M && b < ((int64_t)1 << 62)) b <<= 1;
+    return b;
+}
+
+patch_status patch_tune_table_create(patch_tune_table** out) {
+    if (!out) return PATCH_ERR_ARG;
+    patch_tune_table* t = new (std::nothrow) patch_tune_table();
+    if (!t) return PATCH_ERR_ALLOC;
+    *out = t;
+    return PATCH_OK;
+}
+
+void patch_tune_table_destroy(patch_tune_table* t) { delete t; }
+
+size_t patch_tune_table_size(const patch_tune_table* t) {
+    if (!t) return 0;
+    std::lock_guard<std::mutex> lock(t->mu);
+    return t->entries.size();
+}
+
+static bool tune_key_ok(int64_t M, int64_t N, int64_t K, int tile, int64_t ns) {
+    return M >= 1 && ns >= 0 && check_shape(N, K, tile) == PATCH_OK && ns <= (N / tile) * (K / tile);
+}
+
+patch_status patch_tune_table_put(patch_tune_table* t, int64_t M, int64_t N, int64_t K, int tile, int64_t n_sparse_tiles,
+                                  const patch_gemm_opts* opts) {
+    if (!t || !opts || !tune_key_ok(M, N, K, tile, n_sparse_tiles)) return PATCH_ERR_ARG;
+    if (opts->path < PATCH_PATH_AUTO || opts->path > PATCH_PATH_PREFILL || opts->split_k < 0 || opts->split_k > 16 || opts->variant < 0)
+        return PATCH_ERR_ARG;
+    const TuneKey k{patch_tune_bucket(M), N, K, n_sparse_tiles, tile};
+    const TuneEntry e{opts->path, opts->split_k, opts->variant, opts->y_bf16 ? 1 : 0, opts->workspace != nullptr};
+    std::lock_guard<std::mutex> lock(t->mu);
+    try { t->entries[k] = e; } catch (...) { return PATCH_ERR_ALLOC; }
+    return PATCH_OK;
+}
+
+patch_status patch_tune_table_get(const patch_tune_table* t, int64_t M, int64_t N, int64_t K, int tile, int64_t n_sparse_tiles,
+                                  void* workspace, size_t workspace_bytes, patch_gemm_opts* out) {
+    if (!t || !out || !tune_key_ok(M, N, K, tile, n_sparse_tiles)) return PATCH_ERR_ARG;
+    const TuneKey k{patch_tune_bucket(M), N, K, n_sparse_tiles, tile};
+    std::lock_guard<std::mutex> lock(t->mu);
+    const auto it = t->entries.find(k);
+    if (it == t->entries.end()) return PATCH_ERR_NOT_FOUND;
+    const TuneEntry& e = it->second;
+    if (e.uses_ws && !workspace) return PATCH_ERR_NOT_FOUND;
+    *out = patch_gemm_opts{e.path, e.split_k, e.variant, e.uses_ws ? workspace : nullptr, e.uses_ws ? workspace_bytes : 0, e.y_bf16};
+    return PATCH_OK;
+}
+
+patch_status patch_tune_layer(patch_tune_table* t, const void* X_decode, int64_t M_decode, const void* X_prefill, int64_t M_prefill,
+                              const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes, void* stream, int reps) {
+    if (!t || !P || !X_decode || !X_prefill || M_decode < 1 || M_prefill < 1) return PATCH_ERR_ARG;
+    // the decode input first, then the prefill input, both from the one packed weight
+    const void* xs[2] = {X_decode, X_prefill};
+    const int64_t ms[2] = {M_decode, M_prefill};
+    for (int i = 0; i < 2; ++i) {
+        patch_gemm_opts best;
+        patch_status st = patch_tune(xs[i], ms[i], P, Y, workspace, workspace_bytes, stream, reps, &best, nullptr);
+        if (st != PATCH_OK) return st;
+        st = patch_tune_table_put(t, ms[i], P->N, P->K, P->tile, P->n_sparse, &best);
+        if (st != PATCH_OK) return st;
+    }
+    return PATCH_OK;
 }
 
 size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {

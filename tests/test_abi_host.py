@@ -59,9 +59,43 @@ def test_argument_errors_without_device():
     assert L.patch_packed_bytes(0) == 0
     assert L.patch_gemm_workspace_bytes(256, 0, None) == 0
     assert L.patch_tune(fake, 1, 0, fake, None, 0, None, 5, None, None) == B.ERR_ARG
+    assert L.patch_tune_all(fake, 1, 0, fake, None, 0, None, 5, None, 0, None) == B.ERR_ARG
+    assert L.patch_gemm_static(fake, 1, 0, fake, 0) == B.ERR_ARG
+    assert L.patch_probe_matrix_rate(2, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_probe_stream_read(fake, 1024, 1, 100, fake, 1 << 20, 0) == B.ERR_ARG
     L.patch_free(0)
     with pytest.raises(B.PatchError):
         B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)
+
+
+def test_tune_table_host_logic():
+    """The table of tuned schedules is host memory only: buckets, put / get / replace, misses, the workspace rule."""
+    assert [B.tune_bucket(m) for m in (1, 2, 3, 4, 5, 16, 17, 512, 513, 4096)] == [1, 2, 4, 4, 8, 16, 32, 512, 1024, 4096]
+    tab = B.TuneTable()
+    assert len(tab) == 0 and tab.get(1, 4096, 4096, 128, 512) is None
+    tab.put(1, 4096, 4096, 128, 512, path=B.PATH_DECODE, split_k=8, variant=3)
+    tab.put(3000, 4096, 4096, 128, 512, path=B.PATH_PREFILL, split_k=1, variant=0)
+    tab.put(40, 4096, 4096, 128, 512, path=B.PATH_DECODE, split_k=4, variant=4, uses_workspace=True)
+    assert len(tab) == 3
+    assert tab.get(1, 4096, 4096, 128, 512) == dict(path=B.PATH_DECODE, split_k=8, variant=3, uses_workspace=False)
+    assert tab.get(4096, 4096, 4096, 128, 512)["path"] == B.PATH_PREFILL        # 3000 and 4096 share the bucket
+    assert tab.get(2048, 4096, 4096, 128, 512) is None                           # another bucket
+    assert tab.get(1, 4096, 4096, 128, 511) is None and tab.get(1, 4096, 4096, 64, 512) is None   # another map / tile
+    assert tab.get(40, 4096, 4096, 128, 512) is None                             # stored with a workspace, none given
+    got = tab.get(40, 4096, 4096, 128, 512, workspace=0x1000, workspace_bytes=1 << 20)
+    assert got == dict(path=B.PATH_DECODE, split_k=4, variant=4, uses_workspace=True)
+    tab.put(1, 4096, 4096, 128, 512, path=B.PATH_DECODE, split_k=2, variant=2)   # replace
+    assert len(tab) == 3 and tab.get(1, 4096, 4096, 128, 512)["split_k"] == 2
+    L = B.lib()
+    o = B.GemmOpts()
+    assert L.patch_tune_table_get(tab.handle, 0, 4096, 4096, 128, 512, None, 0, ctypes.byref(o)) == B.ERR_ARG      # M < 1
+    assert L.patch_tune_table_get(tab.handle, 1, 4096, 4000, 128, 512, None, 0, ctypes.byref(o)) == B.ERR_ARG      # K % tile
+    assert L.patch_tune_table_get(tab.handle, 1, 4096, 4096, 128, 5000, None, 0, ctypes.byref(o)) == B.ERR_ARG     # more 2:4 tiles than tiles
+    bad = B.GemmOpts(7, 0, 0, None, 0, 0)
+    assert L.patch_tune_table_put(tab.handle, 1, 4096, 4096, 128, 512, ctypes.byref(bad)) == B.ERR_ARG
+    assert L.patch_tune_table_create(None) == B.ERR_ARG and L.patch_tune_table_size(None) == 0
+    assert L.patch_tune_layer(None, 0x1000, 1, 0x1000, 64, None, 0x1000, None, 0, None, 3) == B.ERR_ARG
+    tab.close()
 
 
 def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):

@@ -526,6 +526,43 @@ def test_tune_returns_a_valid_fast_schedule(dev):
     p64.P.close()
 
 
+def test_tune_report_table_and_small_execution_tile(dev):
+    """patch_tune_all reports every candidate; the small 128 x 128 execution tile must not beat the 256 x 256 default
+    on a compute-bound shape (the paper's Appendix O finds small execution tiles under-use the matrix units; times are
+    printed, only their order is asserted).  patch_tune_layer tunes the decode input first, then the prefill input,
+    and both stored schedules reproduce the oracle's result."""
+    N, K, Mp = 2048, 2048, 2048
+    c = synth.make_case("tune_layer", N, K, Mp, 128, 0.5, seed=16)
+    p = Prepared(c, dev)
+    X = to_dev_bf16(c.X, dev)
+    Y = torch.full((Mp, N), float("nan"), device=dev, dtype=torch.float32)
+    ws = torch.full((8 << 20,), float("nan"), device=dev, dtype=torch.float32)
+    rep = B.patch_tune_all(X, Mp, p.P, Y, workspace=ws, stream=stream(), reps=5)
+    for sch, us in rep:
+        print(f"  candidate {sch}: {us:.1f} us", flush=True)
+    pre = {sch["variant"]: us for sch, us in rep if sch["path"] == B.PATH_PREFILL and sch["split_k"] == 1}
+    assert set(pre) == {0, 1, 2}, "the three execution tiles of the prefill path must all be timed"
+    assert pre[1] > pre[0], f"128 x 128 execution tile {pre[1]:.1f} us is not slower than 256 x 256 {pre[0]:.1f} us"
+    assert all(sch["path"] == B.PATH_PREFILL for sch, _ in rep), "decode passes are no contenders at M = 2048"
+    rep1 = B.patch_tune_all(X, 1, p.P, Y, stream=stream(), reps=5)
+    assert len({(s_["split_k"], s_["variant"]) for s_, _ in rep1 if s_["path"] == B.PATH_DECODE}) >= 8, "wavefront counts not swept"
+    tab = B.TuneTable()
+    tab.tune_layer(X, 4, X, Mp, p.P, Y, workspace=ws, stream=stream(), reps=5)
+    assert len(tab) == 2
+    for M in (4, 3, Mp, Mp - 500):                      # 3 shares the decode bucket, Mp - 500 the prefill bucket
+        sch = tab.get_for(M, p.P, workspace=ws)
+        print(f"  stored for M={M}: {sch}", flush=True)
+        assert sch is not None and sch["path"] == (B.PATH_DECODE if M <= 4 else B.PATH_PREFILL)
+        Y2 = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+        ws.fill_(float("nan"))
+        B.run_tuned(X, M, p.P, Y2, sch, workspace=ws, stream=stream())
+        torch.cuda.synchronize()
+        p.check(c.X[:M], Y2.cpu().numpy(), None, f"stored schedule M={M}")
+    assert tab.get_for(64, p.P, workspace=ws) is None   # nothing tuned for that bucket
+    tab.close()
+    p.P.close()
+
+
 def test_prefill_long_k(dev):
     """K beyond the weights-in-registers kernel's limit (256 tiles): the default choice must fall back."""
     c = synth.make_case("longk", 128, 258 * 128, 40, 128, 0.5, seed=12)
