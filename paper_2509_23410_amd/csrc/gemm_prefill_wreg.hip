@@ -71,6 +71,23 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
         PATCH_WR_R10("v", 15), PATCH_WR_R10("v", 16), PATCH_WR_R10("v", 17), PATCH_WR_R10("v", 18),                  \
         PATCH_WR_R10("v", 19), PATCH_WR_R10("v", 20), PATCH_WR_R10("v", 21), "v220", "v221", "v222", "v223"
 
+// ---- registers of the step loop.  The loop is ONE asm statement (no compiler-generated instruction inside it: with one
+// wavefront per SIMD every instruction that is not issued in the shadow of a matrix instruction stalls the matrix pipe,
+// and the code the compiler placed between the column blocks - the next step's addresses, the loop control, its
+// hazard nops - cost about 300 cycles of a 2048-cycle dense step).  Besides the accumulators, the weight buffers and
+// the X operand sets it owns, by name:
+//   s80       step index s                          s81  scratch of the weight-load addresses
+//   s[82:83]  X + 128 min(s + 3, S - 1): source of the X loads issued in step s
+//   s[84:85]  tile of the weight loads issued in step s (the tile of step s + 2), s86 its type as a mask (0 dense, -1 2:4)
+//   s87       type of the tile the NEXT step multiplies (0 dense, 1 2:4; 0 for a wavefront without a tile row)
+//   s88-s90   scratch of the control code           s91  LDS address of this wavefront's first 1 KB piece of stage (s + 3) % 4
+//   s[92:93]  lane mask of the selects              s[94:95] 64-bit scratch
+//   v224 / v225  lane LDS addresses (low / high X operand) of the stage an EVEN step reads in column blocks 0-8 and an odd
+//                step reads in column blocks 9-15; v226 / v227 the other way round
+//   v228 / v229  lane offsets of weight-load slots 0-3 / 4-7 for the type of the tile being loaded;  v230 address scratch
+// Every step updates them in "control slots": three light instructions per column block, each placed behind a matrix
+// instruction (K1, K2, K3 below), so that they issue while the matrix pipe is busy.
+//
 // ---- weight load of slot I (0..7) of the step two ahead (buffer ABN, K-step J), as asm text for the middle of a
 // column block: 16 bytes per lane from tile base + lane offset + slot offset, the slot offset selected by the tile
 // type through a mask (0 dense, -1 2:4), not branched on:
@@ -82,17 +99,16 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 #define PATCH_WR_CD(I, J) "((" #I ">>1)*4096+(" #I "&1)*1024+" #J "*2048)"
 #define PATCH_WR_CS_VAL(I, J) "(" #I "*2048+" #J "*1024)"
 #define PATCH_WR_CS_POS(I, J) "(16384+(" #I "-4)*256)"
-// The four instructions of a load are spread over four gaps between matrix instructions (LD1..LD4): one light
-// instruction per gap issues in the shadow of the matrix instruction before it.
-#define PATCH_WR_A1(ABN, I, J, CS, VSEL) "s_and_b32 %[t], %[mask], " CS "-" PATCH_WR_CD(I, J) "\n\t"
-#define PATCH_WR_A2(ABN, I, J, CS, VSEL) "s_add_i32 %[t], %[t], " PATCH_WR_CD(I, J) "\n\t"
-#define PATCH_WR_A3(ABN, I, J, CS, VSEL) "v_add_u32 %[vt], %[t], " VSEL "\n\t"
-#define PATCH_WR_A4(ABN, I, J, CS, VSEL) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", %[vt], %[tb]\n\t"
+// The four instructions of a load are spread over the gaps between matrix instructions (LD1..LD4).
+#define PATCH_WR_A1(ABN, I, J, CS, VSEL) "s_and_b32 s81, s86, " CS "-" PATCH_WR_CD(I, J) "\n\t"
+#define PATCH_WR_A2(ABN, I, J, CS, VSEL) "s_add_i32 s81, s81, " PATCH_WR_CD(I, J) "\n\t"
+#define PATCH_WR_A3(ABN, I, J, CS, VSEL) "v_add_u32 v230, s81, " VSEL "\n\t"
+#define PATCH_WR_A4(ABN, I, J, CS, VSEL) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", v230, s[84:85]\n\t"
 // X load SLOT (0..7) of the step three ahead: 16 bytes per lane, global -> LDS at m0 + lane * 16
-#define PATCH_WR_X3(SLOT) "s_add_u32 m0, %[m0b], 4096*" #SLOT "\n\t"
-#define PATCH_WR_X4(SLOT) "global_load_lds_dwordx4 %[xo], %[xb]\n\t"
-#define PATCH_WR_LDV(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_VAL(I, J), "%[v03]")
-#define PATCH_WR_LDP(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_POS(I, J), "%[v47]")
+#define PATCH_WR_X3(SLOT) "s_add_u32 m0, s91, 4096*" #SLOT "\n\t"
+#define PATCH_WR_X4(SLOT) "global_load_lds_dwordx4 %[xo" #SLOT "], s[82:83]\n\t"
+#define PATCH_WR_LDV(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_VAL(I, J), "v228")
+#define PATCH_WR_LDP(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_POS(I, J), "v229")
 // load part N (1..4) of column block CB
 #define PATCH_WR_LD_0(N, ABN, J) PATCH_WR_LDV(N, ABN, 0, J)
 #define PATCH_WR_LD_1(N, ABN, J) PATCH_WR_LDV(N, ABN, 1, J)
@@ -114,51 +130,169 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 #define PATCH_WR_LD_13(N, ABN, J) PATCH_WR_XN##N(5)
 #define PATCH_WR_LD_14(N, ABN, J) PATCH_WR_XN##N(6)
 #define PATCH_WR_LD_15(N, ABN, J) PATCH_WR_XN##N(7)
-// operands of every column-block statement (cu, scr, xo: see the step loop).  The statements of blocks 8-15 write m0,
-// which the compiler does not use in this kernel (every LDS-DMA load is issued from asm).
-#define PATCH_WR_PIECE_OPS                                                                                         \
-    : [t] "=&s"(scr.t), [vt] "=&v"(scr.vt)                                                                         \
-    : [al] "v"(ral), [ah] "v"(rah), [mask] "s"(cu.mask), [v03] "v"(cu.v03), [v47] "v"(cu.v47), [tb] "s"(cu.tb),    \
-      [m0b] "s"(cu.m0b), [xb] "s"(cu.xb), [xo] "v"(xo)
+
+// ---- lane LDS addresses by step parity PAR: column blocks 0-8 read ahead inside the step's own stage (address pair
+// "cur"), column blocks 9-15 into the next stage ("nxt")
+#define PATCH_WR_CURL_0 "v224"
+#define PATCH_WR_CURH_0 "v225"
+#define PATCH_WR_NXTL_0 "v226"
+#define PATCH_WR_NXTH_0 "v227"
+#define PATCH_WR_CURL_1 "v226"
+#define PATCH_WR_CURH_1 "v227"
+#define PATCH_WR_NXTL_1 "v224"
+#define PATCH_WR_NXTH_1 "v225"
+
+// ---- control slots K1, K2, K3 of column block CB in a step of parity PAR.  In order (s = this step):
+//   blocks 0-2    s[82:83] = X + 128 min(s + 3, S - 1);  s91 = LDS address of stage (s + 3) % 4     (used by blocks 8-15)
+//   blocks 3-5    s87 = type of tile (s + 1) / 2, the tile the next step multiplies
+//   blocks 9-10   "cur" lane addresses = stage (s + 2) % 4: the next step's "nxt" (last read in block 8)
+//   blocks 10-15  tile (s + 3) / 2, which the next step's weight loads fetch: s[84:85], s86, v228, v229 (last used in
+//                 block 7);  s80 = s + 1
+// A scalar compare and the select that reads its result share a slot (the weight-load address arithmetic in the gaps
+// between them writes SCC too); so do the two halves of a 64-bit add.
+#define PATCH_WR_K1_0(PAR) "s_add_i32 s88, s80, 3\n\t"
+#define PATCH_WR_K2_0(PAR) "s_min_i32 s89, s88, %[sm1]\n\t"
+#define PATCH_WR_K3_0(PAR) "s_lshl_b32 s89, s89, 7\n\t"
+#define PATCH_WR_K1_1(PAR) "s_add_u32 s82, %[xlo], s89\n\ts_addc_u32 s83, %[xhi], 0\n\t"
+#define PATCH_WR_K2_1(PAR) "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_1(PAR) "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_2(PAR) "s_add_u32 s91, %[ldsw], s88\n\t"
+#define PATCH_WR_K2_2(PAR) ""
+#define PATCH_WR_K3_2(PAR) ""
+#define PATCH_WR_K1_3(PAR) "s_add_i32 s88, s80, 1\n\t"
+#define PATCH_WR_K2_3(PAR) "s_lshr_b32 s88, s88, 1\n\t"
+#define PATCH_WR_K3_3(PAR) "s_min_u32 s88, s88, %[tkm1]\n\t"
+#define PATCH_WR_K1_4(PAR) "v_readlane_b32 s89, %[ent0], s88\n\t"
+#define PATCH_WR_K2_4(PAR) "v_readlane_b32 s90, %[ent1], s88\n\t"
+#define PATCH_WR_K3_4(PAR) "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s89, s89, s90\n\t"
+#define PATCH_WR_K1_5(PAR) "s_and_b32 s87, s89, %[live]\n\t"
+#define PATCH_WR_K2_5(PAR) ""
+#define PATCH_WR_K3_5(PAR) ""
+#define PATCH_WR_K1_6(PAR) ""
+#define PATCH_WR_K2_6(PAR) ""
+#define PATCH_WR_K3_6(PAR) ""
+#define PATCH_WR_K1_7(PAR) ""
+#define PATCH_WR_K2_7(PAR) ""
+#define PATCH_WR_K3_7(PAR) ""
+#define PATCH_WR_K1_8(PAR) ""
+#define PATCH_WR_K2_8(PAR) ""
+#define PATCH_WR_K3_8(PAR) ""
+#define PATCH_WR_K1_9(PAR) "s_add_i32 s88, s80, 2\n\t"
+#define PATCH_WR_K2_9(PAR) "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_9(PAR) "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_10(PAR) "v_add_u32 " PATCH_WR_CURL_##PAR ", s88, %[bl0]\n\t"
+#define PATCH_WR_K2_10(PAR) "v_add_u32 " PATCH_WR_CURH_##PAR ", s88, %[bh0]\n\t"
+#define PATCH_WR_K3_10(PAR) "s_add_i32 s88, s80, 3\n\t"
+#define PATCH_WR_K1_11(PAR) "s_lshr_b32 s88, s88, 1\n\t"
+#define PATCH_WR_K2_11(PAR) "s_min_u32 s88, s88, %[tkm1]\n\t"
+#define PATCH_WR_K3_11(PAR) "v_readlane_b32 s89, %[ent0], s88\n\t"
+#define PATCH_WR_K1_12(PAR) "v_readlane_b32 s90, %[ent1], s88\n\t"
+#define PATCH_WR_K2_12(PAR) "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s89, s89, s90\n\t"
+#define PATCH_WR_K3_12(PAR) "s_lshr_b32 s94, s89, 1\n\t"
+#define PATCH_WR_K1_13(PAR) "s_mov_b32 s95, 0\n\t"
+#define PATCH_WR_K2_13(PAR) "s_lshl_b64 s[94:95], s[94:95], 8\n\t"
+#define PATCH_WR_K3_13(PAR) "s_add_u32 s84, %[plo], s94\n\ts_addc_u32 s85, %[phi], s95\n\t"
+#define PATCH_WR_K1_14(PAR) "s_bitcmp1_b32 s89, 0\n\ts_cselect_b32 s86, -1, 0\n\t"
+#define PATCH_WR_K2_14(PAR) "s_bitcmp1_b32 s89, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
+#define PATCH_WR_K3_14(PAR) "v_cndmask_b32_e64 v228, %[vd], %[vs], s[92:93]\n\t"
+#define PATCH_WR_K1_15(PAR) "v_cndmask_b32_e64 v229, %[vd], %[vm], s[92:93]\n\t"
+#define PATCH_WR_K2_15(PAR) "s_add_i32 s80, s80, 1\n\t"
+#define PATCH_WR_K3_15(PAR) ""
+// block 8 starts with the step's barrier: this wavefront's share of X(s+1) has landed (the loads issued after it: A(s+1),
+// X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 9) and every read of stage (s-1) % 4
+// has completed, so the loads of X(s+3) (one per block 8-15) may overwrite it
+#define PATCH_WR_PRE_0 ""
+#define PATCH_WR_PRE_1 ""
+#define PATCH_WR_PRE_2 ""
+#define PATCH_WR_PRE_3 ""
+#define PATCH_WR_PRE_4 ""
+#define PATCH_WR_PRE_5 ""
+#define PATCH_WR_PRE_6 ""
+#define PATCH_WR_PRE_7 ""
+#define PATCH_WR_PRE_8 "s_waitcnt vmcnt(24)\n\ts_barrier\n\t"
+#define PATCH_WR_PRE_9 ""
+#define PATCH_WR_PRE_10 ""
+#define PATCH_WR_PRE_11 ""
+#define PATCH_WR_PRE_12 ""
+#define PATCH_WR_PRE_13 ""
+#define PATCH_WR_PRE_14 ""
+#define PATCH_WR_PRE_15 ""
+// which address pair column block CB reads ahead with
+#define PATCH_WR_RAL_0(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_1(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_2(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_3(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_4(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_5(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_6(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_7(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_8(PAR) PATCH_WR_CURL_##PAR
+#define PATCH_WR_RAL_9(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_10(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_11(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_12(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_13(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_14(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAL_15(PAR) PATCH_WR_NXTL_##PAR
+#define PATCH_WR_RAH_0(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_1(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_2(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_3(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_4(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_5(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_6(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_7(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_8(PAR) PATCH_WR_CURH_##PAR
+#define PATCH_WR_RAH_9(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_10(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_11(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_12(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_13(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_14(PAR) PATCH_WR_NXTH_##PAR
+#define PATCH_WR_RAH_15(PAR) PATCH_WR_NXTH_##PAR
 
 // ---- one column block CB of X (operand set SET) against the wavefront's four strips (weights of step buffer AB),
 // after waiting for its operands, plus the two LDS reads of the column block seven ahead into set NSET (LDS byte
-// offset OFF from the lane addresses) and one global load: blocks 0-7 a weight load of step s+2 (buffer ABN),
-// blocks 8-15 an X load of step s+3.  J = K-step inside the tile.
-#define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)
-#define PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                      \
-    asm volatile("s_waitcnt lgkmcnt(12)\n\t"                                                                        \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:" #OFF "\n\t"                                  \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 4) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
-                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 6) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
-                 PATCH_WR_LD_##CB(2, ABN, J)                                                                       \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
-                 PATCH_WR_LD_##CB(3, ABN, J)                                                                       \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
-                 PATCH_WR_LD_##CB(4, ABN, J)                                                                       \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 5) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
-                 "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB)          \
-                 PATCH_WR_PIECE_OPS                                                                                \
-                 : "scc", PATCH_WR_CLOBBER)
-#define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, ABN, J, OFF) PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)
-#define PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, OFF)                                                     \
-    asm volatile("s_waitcnt lgkmcnt(12)\n\t"                                                                        \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
-                 "ds_read_b128 " PATCH_WR_VBL(NSET) ", %[al] offset:" #OFF "\n\t"                                  \
-                 "ds_read_b128 " PATCH_WR_VBH(NSET) ", %[ah] offset:" #OFF "\n\t"                                  \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
-                 PATCH_WR_LD_##CB(1, ABN, J)                                                                       \
-                 PATCH_WR_LD_##CB(2, ABN, J)                                                                       \
-                 PATCH_WR_LD_##CB(3, ABN, J)                                                                       \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
-                 PATCH_WR_LD_##CB(4, ABN, J)                                                                       \
-                 "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J          \
-                 PATCH_WR_PIECE_OPS                                                                                \
-                 : "scc", PATCH_WR_CLOBBER)
+// offset OFF from the lane addresses), one global load - blocks 0-7 a weight load of step s+2 (buffer ABN), blocks
+// 8-15 an X load of step s+3 - and the block's control slots.  J = K-step inside the tile, PAR = parity of the step.
+#define PATCH_WR_PIECE_DENSE(CB, SET, NSET, AB, ABN, J, PAR, OFF) PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)
+#define PATCH_WR_PIECE_DENSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)                                                 \
+    PATCH_WR_PRE_##CB                                                                                              \
+    "s_waitcnt lgkmcnt(12)\n\t"                                                                                    \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
+    "ds_read_b128 " PATCH_WR_VBL(NSET) ", " PATCH_WR_RAL_##CB(PAR) " offset:" #OFF "\n\t"                          \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
+    "ds_read_b128 " PATCH_WR_VBH(NSET) ", " PATCH_WR_RAH_##CB(PAR) " offset:" #OFF "\n\t"                          \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 4) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
+    PATCH_WR_LD_##CB(1, ABN, J)                                                                                    \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 6) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
+    PATCH_WR_LD_##CB(2, ABN, J)                                                                                    \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
+    PATCH_WR_LD_##CB(3, ABN, J)                                                                                    \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
+    PATCH_WR_LD_##CB(4, ABN, J)                                                                                    \
+    PATCH_WR_K1_##CB(PAR)                                                                                          \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 5) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
+    PATCH_WR_K2_##CB(PAR)                                                                                          \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
+    PATCH_WR_K3_##CB(PAR)
+#define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, ABN, J, PAR, OFF) PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)
+#define PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)                                                \
+    PATCH_WR_PRE_##CB                                                                                              \
+    "s_waitcnt lgkmcnt(12)\n\t"                                                                                    \
+    "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 0) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 0) " abid:" #J "\n\t" \
+    "ds_read_b128 " PATCH_WR_VBL(NSET) ", " PATCH_WR_RAL_##CB(PAR) " offset:" #OFF "\n\t"                          \
+    "ds_read_b128 " PATCH_WR_VBH(NSET) ", " PATCH_WR_RAH_##CB(PAR) " offset:" #OFF "\n\t"                          \
+    "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
+    PATCH_WR_LD_##CB(1, ABN, J)                                                                                    \
+    PATCH_WR_LD_##CB(2, ABN, J)                                                                                    \
+    PATCH_WR_LD_##CB(3, ABN, J)                                                                                    \
+    "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
+    PATCH_WR_LD_##CB(4, ABN, J)                                                                                    \
+    PATCH_WR_K1_##CB(PAR)                                                                                          \
+    "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J "\n\t" \
+    PATCH_WR_K2_##CB(PAR)                                                                                          \
+    PATCH_WR_K3_##CB(PAR)
 // weight load I of a step into buffer AB: 16 bytes per lane, asynchronous
 #define PATCH_WR_LOAD_A(AB, I, voff_, base_)                                                                       \
     asm volatile("global_load_dwordx4 " PATCH_WR_VA(AB, I) ", %0, %1" : : "v"(voff_), "s"(base_) : PATCH_WR_CLOBBER)
@@ -171,6 +305,7 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
                  : PATCH_WR_CLOBBER)
 // column blocks of a step with their operand sets: P(CB, SET, NSET)
 #define PATCH_WR_16(P) P(0, 0, 7) P(1, 1, 0) P(2, 2, 1) P(3, 3, 2) P(4, 4, 3) P(5, 5, 4) P(6, 6, 5) P(7, 7, 6) P(8, 0, 7) P(9, 1, 0) P(10, 2, 1) P(11, 3, 2) P(12, 4, 3) P(13, 5, 4) P(14, 6, 5) P(15, 7, 6)
+
 
 // Y = sum over the slices of the partial products, slice 0 first: a fixed order, so the result is reproducible.
 // (Adding the partials to Y with fp32 atomics instead was 2-3x slower than this second launch.)
@@ -362,28 +497,17 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     };
 
     const int S = 2 * Tk;  // 64-column steps
-    // the tile row's table entries: lane l of ent[i] holds tile 64 i + l; fetched with v_readlane (a scalar load in
-    // the loop would be waited for with lgkmcnt(0), i.e. together with every LDS read in flight).  Tk <= 256.
-    uint32_t ent[4];
+    // the tile row's table entries: lane l of ent[i] holds tile 64 i + l; the loop fetches them with v_readlane (a
+    // scalar load in the loop would be waited for with lgkmcnt(0), i.e. together with every LDS read in flight).
+    // Tk <= 128 (prefill_wreg_supports).
+    uint32_t ent[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
         const int t = 64 * i + lane;
         ent[i] = trow[t < Tk ? t : Tk - 1];
     }
-    // a use right here: the compiler waits for these loads now, not with a vmcnt(0) inside the loop
-    asm volatile("" : "+v"(ent[0]), "+v"(ent[1]), "+v"(ent[2]), "+v"(ent[3]));
-    auto entry = [&](int t) {
-        t = t < Tk ? t : Tk - 1;
-        uint32_t r = __builtin_amdgcn_readlane(ent[0], t & 63);
-        if (Tk > 64) {
-#pragma unroll
-            for (int i = 1; i < 4; ++i) {
-                const uint32_t v = __builtin_amdgcn_readlane(ent[i], t & 63);
-                r = (t >> 6) == i ? v : r;
-            }
-        }
-        return r;
-    };
+    // a use right here: the compiler waits for these loads now
+    asm volatile("" : "+v"(ent[0]), "+v"(ent[1]));
 
     // accumulators: zero
 #define PATCH_WR_ZERO(CB, SET, NSET)                                                                               \
@@ -399,18 +523,18 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #undef PATCH_WR_ZERO
 
     // ---- prologue, in the order the steady state would have produced: X(0) | A(0) X(1) | A(1) X(2)
-    uint32_t ec[3] = {entry(0), entry(1), entry(2)};
     {
+        const uint32_t e0 = __builtin_amdgcn_readlane(ent[0], 0);   // tile 0: steps 0 and 1
         const int s1 = S > 1 ? 1 : 0, s2 = S > 2 ? 2 : S - 1;
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_x_slot(i, 0, 0);
         asm volatile("" ::: "memory");
-        PATCH_WR_LOAD_STEP(0, 0, ec[0])
+        PATCH_WR_LOAD_STEP(0, 0, e0)
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_x_slot(i, s1, 1);
         asm volatile("" ::: "memory");
-        PATCH_WR_LOAD_STEP(1, 1, ec[0])
+        PATCH_WR_LOAD_STEP(1, 1, e0)
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_x_slot(i, s2, 2);
@@ -431,55 +555,6 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     // lane offsets of the weight loads inside a tile: dense operands, 2:4 values, 2:4 position dwords
     const uint32_t vd = lane * 16 + sh * 4 * 2 * kDenseFragBytes, vs = lane * 16 + sh * 4 * 2 * kSparseFragBytes;
     const uint32_t vm = lane * 4 + sh * 4 * 64 * 4;
-    // ---- what a step needs besides its operands, computed during the step before (in the shadow of its matrix
-    // instructions) so that a step starts with nothing but a wait and a branch
-    struct StepVars {
-        uint32_t al, ah;     // lane LDS addresses of the X operands in stage s % 4 ...
-        uint32_t aln, ahn;   // ... and in stage (s+1) % 4
-        const uint8_t* tb;   // tile of step s+2 (weight loads)
-        int mask;            // its type: 0 dense, -1 2:4
-        uint32_t v03, v47;   // lane offsets of load slots 0-3 / 4-7 for that type
-        const uint8_t* xb;   // X + 128 (step s+3)
-        uint32_t m0b;        // LDS byte address of this wavefront's first 1 KB piece of stage (s+3) % 4
-        int sparse;          // type of the tile this step multiplies
-    };
-    const int live_i = __builtin_amdgcn_readfirstlane(live ? 1 : 0);
-    auto step_vars = [&](int s, uint32_t e, uint32_t e2) {
-        StepVars v;
-        v.al = bl0 + (s & 3) * kWrStage;
-        v.ah = bh0 + (s & 3) * kWrStage;
-        v.aln = bl0 + ((s + 1) & 3) * kWrStage;
-        v.ahn = bh0 + ((s + 1) & 3) * kWrStage;
-        v.tb = payload + entry_offset(e2);
-        v.mask = -(int)(e2 & 1u);
-        v.v03 = entry_sparse(e2) ? vs : vd;
-        v.v47 = entry_sparse(e2) ? vm : vd;
-        const int s3 = (s + 3 < S) ? s + 3 : S - 1;
-        v.xb = xbase + (size_t)s3 * 128;
-        v.m0b = lds0 + ((s + 3) & 3) * kWrStage + w * 1024;
-        v.sparse = (int)(e & 1u) & live_i;
-        return v;
-    };
-    struct { uint32_t t, vt; } scr;  // scratch registers of the asm
-// Everything of a column block but its asm statement.  Block 8: this wavefront's share of X(s+1) has landed (after
-// it: A(s+1), X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 9) and every read of
-// stage (s-1) % 4 has completed, so the loads of X(s+3) (one per block 8-15) may overwrite it.
-#define PATCH_WR_PRE(CB, SS)                                                                                         \
-    if (CB == 8) {                                                                                                 \
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
-        __builtin_amdgcn_s_barrier();                                                                              \
-        asm volatile("" ::: "memory");                                                                             \
-    }                                                                                                              \
-    if (CB == 9) {                                                                                                 \
-        int sn = s + 1;                                                                                            \
-        asm volatile("" : "+s"(sn)); /* not before this point */                                                   \
-        nx = step_vars(sn, PATCH_WR_ENT((SS + 1) >> 1), PATCH_WR_ENT((SS + 3) >> 1));                              \
-    }                                                                                                              \
-    if (CB == 12) { /* ... and not after this one */                                                               \
-        asm volatile("" : "+v"(nx.al), "+v"(nx.ah), "+v"(nx.aln), "+v"(nx.ahn), "+v"(nx.v03), "+v"(nx.v47));      \
-        asm volatile("" : "+s"(nx.tb), "+s"(nx.mask), "+s"(nx.xb), "+s"(nx.m0b), "+s"(nx.sparse));                \
-    }                                                                                                              \
-    const uint32_t ral = CB < 9 ? cu.al : cu.aln, rah = CB < 9 ? cu.ah : cu.ahn, xo = xoff[CB < 8 ? 0 : CB - 8];
 // LDS offset of the column block seven ahead
 #define PATCH_WR_OFF_0 14336
 #define PATCH_WR_OFF_1 16384
@@ -497,53 +572,70 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 #define PATCH_WR_OFF_13 8192
 #define PATCH_WR_OFF_14 10240
 #define PATCH_WR_OFF_15 12288
-// One step: SS = position in the round of six, AB / ABN = weight buffers of steps s / s+2, J = K-step in the tile.
-// One scalar branch.  A wavefront without a tile row (N % 256 = 128) multiplies the first tile row's weights as
-// dense data into accumulators that are never stored.
-#define PATCH_WR_ENT(k) ((k) < 3 ? ec[(k) % 3] : en[(k) % 3]) /* entry of tile k of this round (3, 4: next round) */
-#define PATCH_WR_STEP(SS, AB, ABN, J)                                                                              \
-    {                                                                                                              \
-        const int s = 6 * it + SS;                                                                                 \
-        if ((SS & 1) == 0 && s >= S) break; /* S is even */                                                        \
-        StepVars& cu = (SS & 1) ? sv1 : sv0; /* this step's variables; the next step's go to the other set */    \
-        StepVars& nx = (SS & 1) ? sv0 : sv1;                                                                       \
-        /* A(s) has landed: the loads issued after it are X(s+1), A(s+1), X(s+2) */                                \
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");                                                          \
-        if (cu.sparse) {                                                                                           \
-            PATCH_WR_16(PATCH_WR_SPARSE_##AB##_##ABN##_##J)                                                        \
-        } else {                                                                                                   \
-            PATCH_WR_16(PATCH_WR_DENSE_##AB##_##ABN##_##J)                                                         \
-        }                                                                                                          \
+// One step = 16 column blocks of one type.  SS = position in the round of six steps (three tiles: step buffer = SS % 3
+// and K-step = SS % 2 are then compile-time constants), AB / ABN = weight buffers of steps s / s+2, J = K-step in the
+// tile, PAR = SS % 2 = which lane address pair is "cur".
+#define PATCH_WR_BODY_D_0(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_D_1(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 1, 1, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_D_2(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_D_3(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 1, 1, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_D_4(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_D_5(CB, SET, NSET) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 1, 1, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_0(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_1(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 1, 1, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_2(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_3(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 1, 1, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_4(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 0, 0, PATCH_WR_OFF_##CB)
+#define PATCH_WR_BODY_S_5(CB, SET, NSET) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 1, 1, PATCH_WR_OFF_##CB)
+// The dense steps of a round lie one behind the other, and so do the 2:4 steps: a step whose tile has the type of
+// the one before is entered by falling through, and only a change of type (at most once per tile) takes a branch - a
+// taken branch is a bubble in the matrix pipe.  Head of step SS in either chain: an even step ends the loop when
+// s = S (S is even); A(s) has landed (the loads issued after it are X(s+1), A(s+1), X(s+2)); then the type check.
+#define PATCH_WR_END_CHECK_0 "s_cmp_ge_i32 s80, %[S]\n\ts_cbranch_scc1 WR_END_%=\n\t"
+#define PATCH_WR_END_CHECK_1 ""
+#define PATCH_WR_STEP_D(SS, EVEN)                                                                                  \
+    "WR_D" #SS "_%=:\n\t" PATCH_WR_END_CHECK_##EVEN "s_waitcnt vmcnt(24)\n\t"                                       \
+    "s_cmp_lg_u32 s87, 0\n\ts_cbranch_scc1 WR_SB" #SS "_%=\n\t"                                                    \
+    "WR_DB" #SS "_%=:\n\t" PATCH_WR_16(PATCH_WR_BODY_D_##SS)
+#define PATCH_WR_STEP_S(SS, EVEN)                                                                                  \
+    "WR_S" #SS "_%=:\n\t" PATCH_WR_END_CHECK_##EVEN "s_waitcnt vmcnt(24)\n\t"                                       \
+    "s_cmp_eq_u32 s87, 0\n\ts_cbranch_scc1 WR_DB" #SS "_%=\n\t"                                                    \
+    "WR_SB" #SS "_%=:\n\t" PATCH_WR_16(PATCH_WR_BODY_S_##SS)
+    {
+        const uint64_t xb64 = reinterpret_cast<uint64_t>(xbase), pl64 = reinterpret_cast<uint64_t>(payload);
+        const uint32_t xlo = (uint32_t)xb64, xhi = (uint32_t)(xb64 >> 32), plo = (uint32_t)pl64, phi = (uint32_t)(pl64 >> 32);
+        const uint32_t ldsw = lds0 + w * 1024;
+        const int sm1 = S - 1, tkm1 = Tk - 1;
+        const int live_i = __builtin_amdgcn_readfirstlane(live ? 1 : 0);
+        asm volatile(
+            // ---- state of step 0: stages 0 / 1, the weight loads fetch tile min(1, Tk - 1), tile 0 is multiplied
+            "s_mov_b32 s80, 0\n\t"
+            "v_mov_b32 v224, %[bl0]\n\tv_mov_b32 v225, %[bh0]\n\t"
+            "v_add_u32 v226, 0x8000, %[bl0]\n\tv_add_u32 v227, 0x8000, %[bh0]\n\t"
+            "s_min_u32 s88, 1, %[tkm1]\n\t"
+            "v_readlane_b32 s89, %[ent0], s88\n\t"
+            "s_lshr_b32 s94, s89, 1\n\ts_mov_b32 s95, 0\n\ts_lshl_b64 s[94:95], s[94:95], 8\n\t"
+            "s_add_u32 s84, %[plo], s94\n\ts_addc_u32 s85, %[phi], s95\n\t"
+            "s_bitcmp1_b32 s89, 0\n\ts_cselect_b32 s86, -1, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
+            "v_readlane_b32 s89, %[ent0], 0\n\t"
+            "s_and_b32 s87, s89, %[live]\n\t"
+            "v_cndmask_b32_e64 v228, %[vd], %[vs], s[92:93]\n\tv_cndmask_b32_e64 v229, %[vd], %[vm], s[92:93]\n\t"
+            // ---- the loop: a round of six dense steps, a round of six 2:4 steps, entered at step 0 of the dense chain
+            PATCH_WR_STEP_D(0, 0) PATCH_WR_STEP_D(1, 1) PATCH_WR_STEP_D(2, 0) PATCH_WR_STEP_D(3, 1) PATCH_WR_STEP_D(4, 0) PATCH_WR_STEP_D(5, 1)
+            "s_branch WR_D0_%=\n\t"
+            PATCH_WR_STEP_S(0, 0) PATCH_WR_STEP_S(1, 1) PATCH_WR_STEP_S(2, 0) PATCH_WR_STEP_S(3, 1) PATCH_WR_STEP_S(4, 0) PATCH_WR_STEP_S(5, 1)
+            "s_branch WR_S0_%=\n\t"
+            "WR_END_%=:"
+            :
+            : [S] "s"(S), [sm1] "s"(sm1), [tkm1] "s"(tkm1), [live] "s"(live_i), [xlo] "s"(xlo), [xhi] "s"(xhi), [plo] "s"(plo), [phi] "s"(phi),
+              [ldsw] "s"(ldsw), [bl0] "v"(bl0), [bh0] "v"(bh0), [vd] "v"(vd), [vs] "v"(vs), [vm] "v"(vm), [ent0] "v"(ent[0]), [ent1] "v"(ent[1]),
+              [xo0] "v"(xoff[0]), [xo1] "v"(xoff[1]), [xo2] "v"(xoff[2]), [xo3] "v"(xoff[3]), [xo4] "v"(xoff[4]), [xo5] "v"(xoff[5]),
+              [xo6] "v"(xoff[6]), [xo7] "v"(xoff[7])
+            : "memory", "scc", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
+              "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", PATCH_WR_CLOBBER);
     }
-#define PATCH_WR_DENSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_DENSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 1, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_DENSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_DENSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 3) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 0, 2, 1, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_DENSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 4) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 1, 0, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_DENSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 5) PATCH_WR_PIECE_DENSE(CB, SET, NSET, 2, 1, 1, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_0_2_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 0) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_1_0_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 1) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 1, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_2_1_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 2) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_0_2_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 3) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 0, 2, 1, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_1_0_0(CB, SET, NSET) { PATCH_WR_PRE(CB, 4) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 1, 0, 0, PATCH_WR_OFF_##CB); }
-#define PATCH_WR_SPARSE_2_1_1(CB, SET, NSET) { PATCH_WR_PRE(CB, 5) PATCH_WR_PIECE_SPARSE(CB, SET, NSET, 2, 1, 1, PATCH_WR_OFF_##CB); }
-
-    // a round = six steps = three tiles: step buffer = step % 3 and K-step = step % 2 are then compile-time constants
-    StepVars sv0 = step_vars(0, ec[0], ec[1]), sv1 = sv0;
-    for (int it = 0;; ++it) {
-        const uint32_t en[3] = {entry(3 * it + 3), entry(3 * it + 4), entry(3 * it + 5)};  // next round's tiles
-        PATCH_WR_STEP(0, 0, 2, 0)
-        PATCH_WR_STEP(1, 1, 0, 1)
-        PATCH_WR_STEP(2, 2, 1, 0)
-        PATCH_WR_STEP(3, 0, 2, 1)
-        PATCH_WR_STEP(4, 1, 0, 0)
-        PATCH_WR_STEP(5, 2, 1, 1)
-        ec[0] = en[0];
-        ec[1] = en[1];
-        ec[2] = en[2];
-    }
-#undef PATCH_WR_STEP
-#undef PATCH_WR_PRE
+#undef PATCH_WR_STEP_D
+#undef PATCH_WR_STEP_S
 
     // outstanding (re-fetched) loads and the reads requested for a step that does not exist must land before this
     // workgroup's LDS and registers can be handed on; the last matrix instructions may still be writing
@@ -578,9 +670,9 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     }
 }
 
-// Limits of the kernel: 32-bit lane offsets into X, four registers of table entries per tile row.
+// Limits of the kernel: 32-bit lane offsets into X, two registers of table entries per tile row (128 tiles).
 bool prefill_wreg_supports(const GemmArgs& a) {
-    return a.tile == 128 && a.M > 0 && a.K <= 256 * 128 && (uint64_t)a.M * (uint64_t)a.K * 2 < (1ull << 32);
+    return a.tile == 128 && a.M > 0 && a.K <= 128 * 128 && (uint64_t)a.M * (uint64_t)a.K * 2 < (1ull << 32);
 }
 
 // K slices per output tile: as many as the workspace a.ws holds partial products for (M N fp32 each), at most

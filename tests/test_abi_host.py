@@ -99,14 +99,15 @@ def test_tune_table_host_logic():
 
 
 def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
-    """prefill_kernel_wreg addresses a[0:255] and v[64:223] by name inside its asm statements; the code the
-    compiler generates around them must not touch those registers, nor m0 (written by the asm for LDS-DMA)."""
+    """prefill_kernel_wreg addresses a[0:255], v[64:230] and s[80:95] by name inside its asm statements (the whole step
+    loop is one statement); the code the compiler generates around them must not touch those registers, nor m0
+    (written by the asm for LDS-DMA)."""
     import re
     from paper_2509_23410_amd import build
     text = open(build.device_asm("gemm_prefill_wreg.hip", str(tmp_path / "wreg.s"))).read()
     m = re.search(r"^_ZN5patch19prefill_kernel_wreg\w*:[^\n]*\n(.*?)s_endpgm", text, re.S | re.M)
     assert m, "kernel not found in the assembly"
-    inasm, max_v, n_asm = False, -1, 0
+    inasm, max_v, max_s, n_asm = False, -1, -1, 0
     for line in m.group(1).splitlines():
         if "#ASMSTART" in line:
             inasm, n_asm = True, n_asm + 1
@@ -123,8 +124,15 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
             max_v = max(max_v, int(g.group(1)))
         for g in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
             max_v = max(max_v, int(g.group(2)))
-    assert n_asm > 200, "inline asm markers missing from the assembly"
+        for g in re.finditer(r"\bs(\d+)\b", code):
+            max_s = max(max_s, int(g.group(1)))
+        for g in re.finditer(r"\bs\[(\d+):(\d+)\]", code):
+            max_s = max(max_s, int(g.group(2)))
+    assert n_asm > 40, "inline asm markers missing from the assembly"
     assert 0 <= max_v < 64, f"compiler allocated v{max_v}, inside the range the asm owns"
+    assert 0 <= max_s < 80, f"compiler allocated s{max_s}, inside the range the asm owns"
+    loop = re.search(r"WR_D0_\d+:(.*?)WR_END_\d+:", m.group(1), re.S)
+    assert loop and "#ASMEND" not in loop.group(1), "the step loop must be a single asm statement"
     meta = re.search(r"\.name:\s+_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
     spills = re.search(r"_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
     assert (meta or spills) and int((meta or spills).group(1)) == 0

@@ -430,3 +430,20 @@ def test_round_bf16_is_the_nearest_value_by_brute_force():
     j = np.searchsorted(grid, y)
     best = np.minimum(np.abs(grid[np.clip(j, 0, grid.size - 1)] - y), np.abs(grid[np.clip(j - 1, 0, grid.size - 1)] - y))
     assert np.array_equal(np.abs(got - y), best)
+
+
+def test_oracle_runs_clean_under_address_and_undefined_sanitizers(tmp_path):
+    """The oracle's C source, compiled with -fsanitize=address,undefined together with a driver that walks every
+    routine over small seeded inputs (oracle/sanitize_check.c): any out-of-bounds access, leak or undefined
+    arithmetic aborts the run."""
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(oracle.__file__))
+    exe = str(tmp_path / "sanitize_check")
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan", os.path.join(here, "patch_oracle.c"),
+           os.path.join(here, "sanitize_check.c"), "-o", exe, "-lm"]
+    subprocess.run(cmd, check=True, capture_output=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "sanitize_check ok" in r.stdout, (r.stdout[-500:], r.stderr[-2000:])
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
