@@ -74,62 +74,70 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 // ---- registers of the step loop.  The loop is ONE asm statement (no compiler-generated instruction inside it: with one
 // wavefront per SIMD every instruction that is not issued in the shadow of a matrix instruction stalls the matrix pipe,
 // and the code the compiler placed between the column blocks - the next step's addresses, the loop control, its
-// hazard nops - cost about 300 cycles of a 2048-cycle dense step).  Besides the accumulators, the weight buffers and
-// the X operand sets it owns, by name:
-//   s80       step index s                          s81  scratch of the weight-load addresses
+// hazard nops - cost about 300 cycles of a 2048-cycle dense step).  A lone wavefront issues about one instruction
+// every five to six cycles, so a 2:4 step (64 matrix instructions in 1024 cycles) is bound by its instruction count:
+// a global load is ONE instruction (lane offsets and bases prepared once per tile), and what changes only with the
+// tile is computed in odd steps only.  Besides the accumulators, the weight buffers and the X operand sets the loop
+// owns, by name:
+//   s80       step index s
 //   s[82:83]  X + 128 min(s + 3, S - 1): source of the X loads issued in step s
-//   s[84:85]  tile of the weight loads issued in step s (the tile of step s + 2), s86 its type as a mask (0 dense, -1 2:4)
+//   s[74:75]  address of the tile the weight loads fetch (the tile of steps s + 2 / s + 3), s76 its table entry,
+//             s86 its type as a mask (0 dense, -1 2:4)
+//   s[84:85]  base of weight-load slots 0-3 of this step: the tile + K-step (s % 2) of the dense operands or 2:4 values
+//   s[96:97]  base of slots 4-7: the tile + K-step of the dense operands (the 2:4 position dwords hold both K-steps)
 //   s87       type of the tile the NEXT step multiplies (0 dense, 1 2:4; 0 for a wavefront without a tile row)
-//   s88-s90   scratch of the control code           s91  LDS address of this wavefront's first 1 KB piece of stage (s + 3) % 4
-//   s[92:93]  lane mask of the selects              s[94:95] 64-bit scratch
+//   s81, s88-s90, s[94:95] scratch     s91 LDS address of this wavefront's first 1 KB piece of stage (s + 3) % 4
+//   s[92:93]  lane mask of the selects
 //   v224 / v225  lane LDS addresses (low / high X operand) of the stage an EVEN step reads in column blocks 0-8 and an odd
 //                step reads in column blocks 9-15; v226 / v227 the other way round
-//   v228 / v229  lane offsets of weight-load slots 0-3 / 4-7 for the type of the tile being loaded;  v230 address scratch
-// Every step updates them in "control slots": three light instructions per column block, each placed behind a matrix
-// instruction (K1, K2, K3 below), so that they issue while the matrix pipe is busy.
+//   v228-v235    lane offsets of the eight weight-load slots for the type of the tile being loaded, selected from
+//   v236-v243    ... those of a dense tile: slot I = operand I % 2 of strip I / 2: lane * 16 + (I / 2) 4096 + (I % 2) 1024
+//   v244-v251    ... those of a 2:4 tile: slot I < 4 = values of strip I: lane * 16 + I 2048; slot 4 + s = 16 bytes starting
+//                at the lane's position dword of strip s: lane * 4 + 16384 + s 256 (the first register is the dword, the
+//                rest is ignored; the last lanes read up to 12 bytes into the next tile or the zeroed slack behind the payload)
+//   (each plus the offset of the wavefront's four strips inside the tile)
+// Every step updates them in "control slots": up to three light instructions per column block, each placed behind a
+// matrix instruction (K1, K2, K3 below), so that they issue while the matrix pipe is busy.
 //
-// ---- weight load of slot I (0..7) of the step two ahead (buffer ABN, K-step J), as asm text for the middle of a
-// column block: 16 bytes per lane from tile base + lane offset + slot offset, the slot offset selected by the tile
-// type through a mask (0 dense, -1 2:4), not branched on:
-//   dense slot I    : operand I % 2 of strip I / 2          offset (I / 2) 4096 + (I % 2) 1024 + J 2048
-//   2:4 slot I < 4  : values of strip I                      offset I 2048 + J 1024
-//   2:4 slot 4 + s  : 16 bytes starting at the lane's position dword of strip s   offset 16384 + s 256
-//                     (the first register is the dword, the rest is ignored; the last lanes read up to 12 bytes
-//                     into the next tile or the zeroed slack behind the payload)
-#define PATCH_WR_CD(I, J) "((" #I ">>1)*4096+(" #I "&1)*1024+" #J "*2048)"
-#define PATCH_WR_CS_VAL(I, J) "(" #I "*2048+" #J "*1024)"
-#define PATCH_WR_CS_POS(I, J) "(16384+(" #I "-4)*256)"
-// The four instructions of a load are spread over the gaps between matrix instructions (LD1..LD4).
-#define PATCH_WR_A1(ABN, I, J, CS, VSEL) "s_and_b32 s81, s86, " CS "-" PATCH_WR_CD(I, J) "\n\t"
-#define PATCH_WR_A2(ABN, I, J, CS, VSEL) "s_add_i32 s81, s81, " PATCH_WR_CD(I, J) "\n\t"
-#define PATCH_WR_A3(ABN, I, J, CS, VSEL) "v_add_u32 v230, s81, " VSEL "\n\t"
-#define PATCH_WR_A4(ABN, I, J, CS, VSEL) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", v230, s[84:85]\n\t"
+// ---- weight load of slot I (0..7) of the step two ahead into buffer ABN: one instruction in column block I
+#define PATCH_WR_WLOAD_03(ABN, I) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", v[228+" #I "], s[84:85]\n\t"
+#define PATCH_WR_WLOAD_47(ABN, I) "global_load_dwordx4 " PATCH_WR_VA(ABN, I) ", v[228+" #I "], s[96:97]\n\t"
 // X load SLOT (0..7) of the step three ahead: 16 bytes per lane, global -> LDS at m0 + lane * 16
 #define PATCH_WR_X3(SLOT) "s_add_u32 m0, s91, 4096*" #SLOT "\n\t"
 #define PATCH_WR_X4(SLOT) "global_load_lds_dwordx4 %[xo" #SLOT "], s[82:83]\n\t"
-#define PATCH_WR_LDV(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_VAL(I, J), "v228")
-#define PATCH_WR_LDP(N, ABN, I, J) PATCH_WR_A##N(ABN, I, J, PATCH_WR_CS_POS(I, J), "v229")
-// load part N (1..4) of column block CB
-#define PATCH_WR_LD_0(N, ABN, J) PATCH_WR_LDV(N, ABN, 0, J)
-#define PATCH_WR_LD_1(N, ABN, J) PATCH_WR_LDV(N, ABN, 1, J)
-#define PATCH_WR_LD_2(N, ABN, J) PATCH_WR_LDV(N, ABN, 2, J)
-#define PATCH_WR_LD_3(N, ABN, J) PATCH_WR_LDV(N, ABN, 3, J)
-#define PATCH_WR_LD_4(N, ABN, J) PATCH_WR_LDP(N, ABN, 4, J)
-#define PATCH_WR_LD_5(N, ABN, J) PATCH_WR_LDP(N, ABN, 5, J)
-#define PATCH_WR_LD_6(N, ABN, J) PATCH_WR_LDP(N, ABN, 6, J)
-#define PATCH_WR_LD_7(N, ABN, J) PATCH_WR_LDP(N, ABN, 7, J)
-#define PATCH_WR_XN1(SLOT) ""
-#define PATCH_WR_XN2(SLOT) ""
-#define PATCH_WR_XN3(SLOT) PATCH_WR_X3(SLOT)
-#define PATCH_WR_XN4(SLOT) PATCH_WR_X4(SLOT)
-#define PATCH_WR_LD_8(N, ABN, J) PATCH_WR_XN##N(0)
-#define PATCH_WR_LD_9(N, ABN, J) PATCH_WR_XN##N(1)
-#define PATCH_WR_LD_10(N, ABN, J) PATCH_WR_XN##N(2)
-#define PATCH_WR_LD_11(N, ABN, J) PATCH_WR_XN##N(3)
-#define PATCH_WR_LD_12(N, ABN, J) PATCH_WR_XN##N(4)
-#define PATCH_WR_LD_13(N, ABN, J) PATCH_WR_XN##N(5)
-#define PATCH_WR_LD_14(N, ABN, J) PATCH_WR_XN##N(6)
-#define PATCH_WR_LD_15(N, ABN, J) PATCH_WR_XN##N(7)
+// load parts of column block CB: LD3 (one matrix instruction before LD4: a write of m0 needs a wait state), LD4
+#define PATCH_WR_LD3_0(ABN) ""
+#define PATCH_WR_LD3_1(ABN) ""
+#define PATCH_WR_LD3_2(ABN) ""
+#define PATCH_WR_LD3_3(ABN) ""
+#define PATCH_WR_LD3_4(ABN) ""
+#define PATCH_WR_LD3_5(ABN) ""
+#define PATCH_WR_LD3_6(ABN) ""
+#define PATCH_WR_LD3_7(ABN) ""
+#define PATCH_WR_LD3_8(ABN) PATCH_WR_X3(0)
+#define PATCH_WR_LD3_9(ABN) PATCH_WR_X3(1)
+#define PATCH_WR_LD3_10(ABN) PATCH_WR_X3(2)
+#define PATCH_WR_LD3_11(ABN) PATCH_WR_X3(3)
+#define PATCH_WR_LD3_12(ABN) PATCH_WR_X3(4)
+#define PATCH_WR_LD3_13(ABN) PATCH_WR_X3(5)
+#define PATCH_WR_LD3_14(ABN) PATCH_WR_X3(6)
+#define PATCH_WR_LD3_15(ABN) PATCH_WR_X3(7)
+#define PATCH_WR_LD4_0(ABN) PATCH_WR_WLOAD_03(ABN, 0)
+#define PATCH_WR_LD4_1(ABN) PATCH_WR_WLOAD_03(ABN, 1)
+#define PATCH_WR_LD4_2(ABN) PATCH_WR_WLOAD_03(ABN, 2)
+#define PATCH_WR_LD4_3(ABN) PATCH_WR_WLOAD_03(ABN, 3)
+#define PATCH_WR_LD4_4(ABN) PATCH_WR_WLOAD_47(ABN, 4)
+#define PATCH_WR_LD4_5(ABN) PATCH_WR_WLOAD_47(ABN, 5)
+#define PATCH_WR_LD4_6(ABN) PATCH_WR_WLOAD_47(ABN, 6)
+#define PATCH_WR_LD4_7(ABN) PATCH_WR_WLOAD_47(ABN, 7)
+#define PATCH_WR_LD4_8(ABN) PATCH_WR_X4(0)
+#define PATCH_WR_LD4_9(ABN) PATCH_WR_X4(1)
+#define PATCH_WR_LD4_10(ABN) PATCH_WR_X4(2)
+#define PATCH_WR_LD4_11(ABN) PATCH_WR_X4(3)
+#define PATCH_WR_LD4_12(ABN) PATCH_WR_X4(4)
+#define PATCH_WR_LD4_13(ABN) PATCH_WR_X4(5)
+#define PATCH_WR_LD4_14(ABN) PATCH_WR_X4(6)
+#define PATCH_WR_LD4_15(ABN) PATCH_WR_X4(7)
 
 // ---- lane LDS addresses by step parity PAR: column blocks 0-8 read ahead inside the step's own stage (address pair
 // "cur"), column blocks 9-15 into the next stage ("nxt")
@@ -142,62 +150,113 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
 #define PATCH_WR_NXTL_1 "v224"
 #define PATCH_WR_NXTH_1 "v225"
 
-// ---- control slots K1, K2, K3 of column block CB in a step of parity PAR.  In order (s = this step):
+// ---- control slots: PATCH_WR_K<slot>_<column block>_<step parity>.  In order (s = this step):
 //   blocks 0-2    s[82:83] = X + 128 min(s + 3, S - 1);  s91 = LDS address of stage (s + 3) % 4     (used by blocks 8-15)
-//   blocks 3-5    s87 = type of tile (s + 1) / 2, the tile the next step multiplies
 //   blocks 9-10   "cur" lane addresses = stage (s + 2) % 4: the next step's "nxt" (last read in block 8)
-//   blocks 10-15  tile (s + 3) / 2, which the next step's weight loads fetch: s[84:85], s86, v228, v229 (last used in
-//                 block 7);  s80 = s + 1
-// A scalar compare and the select that reads its result share a slot (the weight-load address arithmetic in the gaps
-// between them writes SCC too); so do the two halves of a 64-bit add.
-#define PATCH_WR_K1_0(PAR) "s_add_i32 s88, s80, 3\n\t"
-#define PATCH_WR_K2_0(PAR) "s_min_i32 s89, s88, %[sm1]\n\t"
-#define PATCH_WR_K3_0(PAR) "s_lshl_b32 s89, s89, 7\n\t"
-#define PATCH_WR_K1_1(PAR) "s_add_u32 s82, %[xlo], s89\n\ts_addc_u32 s83, %[xhi], 0\n\t"
-#define PATCH_WR_K2_1(PAR) "s_and_b32 s88, s88, 3\n\t"
-#define PATCH_WR_K3_1(PAR) "s_lshl_b32 s88, s88, 15\n\t"
-#define PATCH_WR_K1_2(PAR) "s_add_u32 s91, %[ldsw], s88\n\t"
-#define PATCH_WR_K2_2(PAR) ""
-#define PATCH_WR_K3_2(PAR) ""
-#define PATCH_WR_K1_3(PAR) "s_add_i32 s88, s80, 1\n\t"
-#define PATCH_WR_K2_3(PAR) "s_lshr_b32 s88, s88, 1\n\t"
-#define PATCH_WR_K3_3(PAR) "s_min_u32 s88, s88, %[tkm1]\n\t"
-#define PATCH_WR_K1_4(PAR) "v_readlane_b32 s89, %[ent0], s88\n\t"
-#define PATCH_WR_K2_4(PAR) "v_readlane_b32 s90, %[ent1], s88\n\t"
-#define PATCH_WR_K3_4(PAR) "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s89, s89, s90\n\t"
-#define PATCH_WR_K1_5(PAR) "s_and_b32 s87, s89, %[live]\n\t"
-#define PATCH_WR_K2_5(PAR) ""
-#define PATCH_WR_K3_5(PAR) ""
-#define PATCH_WR_K1_6(PAR) ""
-#define PATCH_WR_K2_6(PAR) ""
-#define PATCH_WR_K3_6(PAR) ""
-#define PATCH_WR_K1_7(PAR) ""
-#define PATCH_WR_K2_7(PAR) ""
-#define PATCH_WR_K3_7(PAR) ""
-#define PATCH_WR_K1_8(PAR) ""
-#define PATCH_WR_K2_8(PAR) ""
-#define PATCH_WR_K3_8(PAR) ""
-#define PATCH_WR_K1_9(PAR) "s_add_i32 s88, s80, 2\n\t"
-#define PATCH_WR_K2_9(PAR) "s_and_b32 s88, s88, 3\n\t"
-#define PATCH_WR_K3_9(PAR) "s_lshl_b32 s88, s88, 15\n\t"
-#define PATCH_WR_K1_10(PAR) "v_add_u32 " PATCH_WR_CURL_##PAR ", s88, %[bl0]\n\t"
-#define PATCH_WR_K2_10(PAR) "v_add_u32 " PATCH_WR_CURH_##PAR ", s88, %[bh0]\n\t"
-#define PATCH_WR_K3_10(PAR) "s_add_i32 s88, s80, 3\n\t"
-#define PATCH_WR_K1_11(PAR) "s_lshr_b32 s88, s88, 1\n\t"
-#define PATCH_WR_K2_11(PAR) "s_min_u32 s88, s88, %[tkm1]\n\t"
-#define PATCH_WR_K3_11(PAR) "v_readlane_b32 s89, %[ent0], s88\n\t"
-#define PATCH_WR_K1_12(PAR) "v_readlane_b32 s90, %[ent1], s88\n\t"
-#define PATCH_WR_K2_12(PAR) "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s89, s89, s90\n\t"
-#define PATCH_WR_K3_12(PAR) "s_lshr_b32 s94, s89, 1\n\t"
-#define PATCH_WR_K1_13(PAR) "s_mov_b32 s95, 0\n\t"
-#define PATCH_WR_K2_13(PAR) "s_lshl_b64 s[94:95], s[94:95], 8\n\t"
-#define PATCH_WR_K3_13(PAR) "s_add_u32 s84, %[plo], s94\n\ts_addc_u32 s85, %[phi], s95\n\t"
-#define PATCH_WR_K1_14(PAR) "s_bitcmp1_b32 s89, 0\n\ts_cselect_b32 s86, -1, 0\n\t"
-#define PATCH_WR_K2_14(PAR) "s_bitcmp1_b32 s89, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
-#define PATCH_WR_K3_14(PAR) "v_cndmask_b32_e64 v228, %[vd], %[vs], s[92:93]\n\t"
-#define PATCH_WR_K1_15(PAR) "v_cndmask_b32_e64 v229, %[vd], %[vm], s[92:93]\n\t"
-#define PATCH_WR_K2_15(PAR) "s_add_i32 s80, s80, 1\n\t"
-#define PATCH_WR_K3_15(PAR) ""
+//   block 15      s80 = s + 1
+//   even steps (the next step is K-step 1 of the same tiles), blocks 10-12: the bases of its weight loads,
+//                 s[84:85] = tile + (2:4 ? 1024 : 2048), s[96:97] = tile + (2:4 ? 0 : 2048)
+//   odd steps (the next step starts new tiles): blocks 2-4 s87 = type of tile (s + 1) / 2, which the next step
+//                 multiplies; blocks 4-6 s76 = table entry of tile (s + 3) / 2, which the next two steps' weight loads fetch;
+//                 blocks 10-15, after this step's last weight load (block 7): its address s[74:75], its type s86, the
+//                 eight lane offsets v228-v235 for that type, both bases = the tile (K-step 0)
+// A scalar compare and the select that reads its result share a slot, and so do the two halves of a 64-bit add.
+#define PATCH_WR_K1_0_0 "s_add_i32 s88, s80, 3\n\t"
+#define PATCH_WR_K2_0_0 "s_min_i32 s89, s88, %[sm1]\n\t"
+#define PATCH_WR_K3_0_0 "s_lshl_b32 s89, s89, 7\n\t"
+#define PATCH_WR_K1_1_0 "s_add_u32 s82, %[xlo], s89\n\ts_addc_u32 s83, %[xhi], 0\n\t"
+#define PATCH_WR_K2_1_0 "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_1_0 "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_2_0 "s_add_u32 s91, %[ldsw], s88\n\t"
+#define PATCH_WR_K2_2_0 ""
+#define PATCH_WR_K3_2_0 ""
+#define PATCH_WR_K1_3_0 ""
+#define PATCH_WR_K2_3_0 ""
+#define PATCH_WR_K3_3_0 ""
+#define PATCH_WR_K1_4_0 ""
+#define PATCH_WR_K2_4_0 ""
+#define PATCH_WR_K3_4_0 ""
+#define PATCH_WR_K1_5_0 ""
+#define PATCH_WR_K2_5_0 ""
+#define PATCH_WR_K3_5_0 ""
+#define PATCH_WR_K1_6_0 ""
+#define PATCH_WR_K2_6_0 ""
+#define PATCH_WR_K3_6_0 ""
+#define PATCH_WR_K1_7_0 ""
+#define PATCH_WR_K2_7_0 ""
+#define PATCH_WR_K3_7_0 ""
+#define PATCH_WR_K1_8_0 ""
+#define PATCH_WR_K2_8_0 ""
+#define PATCH_WR_K3_8_0 ""
+#define PATCH_WR_K1_9_0 "s_add_i32 s88, s80, 2\n\t"
+#define PATCH_WR_K2_9_0 "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_9_0 "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_10_0 "v_add_u32 v224, s88, %[bl0]\n\t"
+#define PATCH_WR_K2_10_0 "v_add_u32 v225, s88, %[bh0]\n\t"
+#define PATCH_WR_K3_10_0 "s_and_b32 s81, s86, -1024\n\t"
+#define PATCH_WR_K1_11_0 "s_add_i32 s81, s81, 2048\n\t"
+#define PATCH_WR_K2_11_0 "s_add_u32 s84, s74, s81\n\ts_addc_u32 s85, s75, 0\n\t"
+#define PATCH_WR_K3_11_0 "s_andn2_b32 s81, 2048, s86\n\t"
+#define PATCH_WR_K1_12_0 "s_add_u32 s96, s74, s81\n\ts_addc_u32 s97, s75, 0\n\t"
+#define PATCH_WR_K2_12_0 ""
+#define PATCH_WR_K3_12_0 ""
+#define PATCH_WR_K1_13_0 ""
+#define PATCH_WR_K2_13_0 ""
+#define PATCH_WR_K3_13_0 ""
+#define PATCH_WR_K1_14_0 ""
+#define PATCH_WR_K2_14_0 ""
+#define PATCH_WR_K3_14_0 ""
+#define PATCH_WR_K1_15_0 ""
+#define PATCH_WR_K2_15_0 ""
+#define PATCH_WR_K3_15_0 "s_add_i32 s80, s80, 1\n\t"
+#define PATCH_WR_K1_0_1 "s_add_i32 s88, s80, 3\n\t"
+#define PATCH_WR_K2_0_1 "s_min_i32 s89, s88, %[sm1]\n\t"
+#define PATCH_WR_K3_0_1 "s_lshl_b32 s89, s89, 7\n\t"
+#define PATCH_WR_K1_1_1 "s_add_u32 s82, %[xlo], s89\n\ts_addc_u32 s83, %[xhi], 0\n\t"
+#define PATCH_WR_K2_1_1 "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_1_1 "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_2_1 "s_add_u32 s91, %[ldsw], s88\n\t"
+#define PATCH_WR_K2_2_1 "s_add_i32 s88, s80, 1\n\t"
+#define PATCH_WR_K3_2_1 "s_lshr_b32 s88, s88, 1\n\t"
+#define PATCH_WR_K1_3_1 "s_min_u32 s88, s88, %[tkm1]\n\t"
+#define PATCH_WR_K2_3_1 "v_readlane_b32 s89, %[ent0], s88\n\t"
+#define PATCH_WR_K3_3_1 "v_readlane_b32 s90, %[ent1], s88\n\t"
+#define PATCH_WR_K1_4_1 "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s89, s89, s90\n\t"
+#define PATCH_WR_K2_4_1 "s_and_b32 s87, s89, %[live]\n\t"
+#define PATCH_WR_K3_4_1 "s_add_i32 s88, s80, 3\n\t"
+#define PATCH_WR_K1_5_1 "s_lshr_b32 s88, s88, 1\n\t"
+#define PATCH_WR_K2_5_1 "s_min_u32 s88, s88, %[tkm1]\n\t"
+#define PATCH_WR_K3_5_1 "v_readlane_b32 s76, %[ent0], s88\n\t"
+#define PATCH_WR_K1_6_1 "v_readlane_b32 s90, %[ent1], s88\n\t"
+#define PATCH_WR_K2_6_1 "s_cmp_lt_u32 s88, 64\n\ts_cselect_b32 s76, s76, s90\n\t"
+#define PATCH_WR_K3_6_1 ""
+#define PATCH_WR_K1_7_1 ""
+#define PATCH_WR_K2_7_1 ""
+#define PATCH_WR_K3_7_1 ""
+#define PATCH_WR_K1_8_1 ""
+#define PATCH_WR_K2_8_1 ""
+#define PATCH_WR_K3_8_1 ""
+#define PATCH_WR_K1_9_1 "s_add_i32 s88, s80, 2\n\t"
+#define PATCH_WR_K2_9_1 "s_and_b32 s88, s88, 3\n\t"
+#define PATCH_WR_K3_9_1 "s_lshl_b32 s88, s88, 15\n\t"
+#define PATCH_WR_K1_10_1 "v_add_u32 v226, s88, %[bl0]\n\t"
+#define PATCH_WR_K2_10_1 "v_add_u32 v227, s88, %[bh0]\n\t"
+#define PATCH_WR_K3_10_1 "s_lshr_b32 s94, s76, 1\n\t"
+#define PATCH_WR_K1_11_1 "s_mov_b32 s95, 0\n\t"
+#define PATCH_WR_K2_11_1 "s_lshl_b64 s[94:95], s[94:95], 8\n\t"
+#define PATCH_WR_K3_11_1 "s_add_u32 s74, %[plo], s94\n\ts_addc_u32 s75, %[phi], s95\n\t"
+#define PATCH_WR_K1_12_1 "s_bitcmp1_b32 s76, 0\n\ts_cselect_b32 s86, -1, 0\n\t"
+#define PATCH_WR_K2_12_1 "s_bitcmp1_b32 s76, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
+#define PATCH_WR_K3_12_1 "v_cndmask_b32_e64 v228, v236, v244, s[92:93]\n\t"
+#define PATCH_WR_K1_13_1 "v_cndmask_b32_e64 v229, v237, v245, s[92:93]\n\t"
+#define PATCH_WR_K2_13_1 "v_cndmask_b32_e64 v230, v238, v246, s[92:93]\n\t"
+#define PATCH_WR_K3_13_1 "v_cndmask_b32_e64 v231, v239, v247, s[92:93]\n\t"
+#define PATCH_WR_K1_14_1 "v_cndmask_b32_e64 v232, v240, v248, s[92:93]\n\t"
+#define PATCH_WR_K2_14_1 "v_cndmask_b32_e64 v233, v241, v249, s[92:93]\n\t"
+#define PATCH_WR_K3_14_1 "v_cndmask_b32_e64 v234, v242, v250, s[92:93]\n\t"
+#define PATCH_WR_K1_15_1 "v_cndmask_b32_e64 v235, v243, v251, s[92:93]\n\t"
+#define PATCH_WR_K2_15_1 "s_mov_b64 s[84:85], s[74:75]\n\ts_mov_b64 s[96:97], s[74:75]\n\t"
+#define PATCH_WR_K3_15_1 "s_add_i32 s80, s80, 1\n\t"
 // block 8 starts with the step's barrier: this wavefront's share of X(s+1) has landed (the loads issued after it: A(s+1),
 // X(s+2), A(s+2)); past the barrier all of X(s+1) is visible (first read in block 9) and every read of stage (s-1) % 4
 // has completed, so the loads of X(s+3) (one per block 8-15) may overwrite it
@@ -264,18 +323,16 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
     "ds_read_b128 " PATCH_WR_VBH(NSET) ", " PATCH_WR_RAH_##CB(PAR) " offset:" #OFF "\n\t"                          \
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 4) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
-    PATCH_WR_LD_##CB(1, ABN, J)                                                                                    \
+    PATCH_WR_LD3_##CB(ABN)                                                                                         \
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 6) ", " PATCH_WR_VBL(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
-    PATCH_WR_LD_##CB(2, ABN, J)                                                                                    \
+    PATCH_WR_LD4_##CB(ABN)                                                                                         \
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(0, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(0, CB) "\n\t" \
-    PATCH_WR_LD_##CB(3, ABN, J)                                                                                    \
+    PATCH_WR_K1_##CB##_##PAR                                                                                       \
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(1, CB) "\n\t" \
-    PATCH_WR_LD_##CB(4, ABN, J)                                                                                    \
-    PATCH_WR_K1_##CB(PAR)                                                                                          \
+    PATCH_WR_K2_##CB##_##PAR                                                                                       \
     "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 5) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(2, CB) "\n\t" \
-    PATCH_WR_K2_##CB(PAR)                                                                                          \
-    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB) "\n\t" \
-    PATCH_WR_K3_##CB(PAR)
+    PATCH_WR_K3_##CB##_##PAR                                                                                       \
+    "v_mfma_f32_16x16x32_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 7) ", " PATCH_WR_VBH(SET) ", " PATCH_WR_C(3, CB) "\n\t"
 #define PATCH_WR_PIECE_SPARSE(CB, SET, NSET, AB, ABN, J, PAR, OFF) PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)
 #define PATCH_WR_PIECE_SPARSE_(CB, SET, NSET, AB, ABN, J, PAR, OFF)                                                \
     PATCH_WR_PRE_##CB                                                                                              \
@@ -284,15 +341,13 @@ typedef __attribute__((address_space(3))) void* wr_lptr_t;
     "ds_read_b128 " PATCH_WR_VBL(NSET) ", " PATCH_WR_RAL_##CB(PAR) " offset:" #OFF "\n\t"                          \
     "ds_read_b128 " PATCH_WR_VBH(NSET) ", " PATCH_WR_RAH_##CB(PAR) " offset:" #OFF "\n\t"                          \
     "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(1, CB) ", " PATCH_WR_VA(AB, 1) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 1) " abid:" #J "\n\t" \
-    PATCH_WR_LD_##CB(1, ABN, J)                                                                                    \
-    PATCH_WR_LD_##CB(2, ABN, J)                                                                                    \
-    PATCH_WR_LD_##CB(3, ABN, J)                                                                                    \
+    PATCH_WR_LD3_##CB(ABN)                                                                                         \
+    PATCH_WR_K1_##CB##_##PAR                                                                                       \
     "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(2, CB) ", " PATCH_WR_VA(AB, 2) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 2) " abid:" #J "\n\t" \
-    PATCH_WR_LD_##CB(4, ABN, J)                                                                                    \
-    PATCH_WR_K1_##CB(PAR)                                                                                          \
+    PATCH_WR_LD4_##CB(ABN)                                                                                         \
+    PATCH_WR_K2_##CB##_##PAR                                                                                       \
     "v_smfmac_f32_16x16x64_bf16 " PATCH_WR_C(3, CB) ", " PATCH_WR_VA(AB, 3) ", " PATCH_WR_VB(SET) ", " PATCH_WR_VI(AB, 3) " abid:" #J "\n\t" \
-    PATCH_WR_K2_##CB(PAR)                                                                                          \
-    PATCH_WR_K3_##CB(PAR)
+    PATCH_WR_K3_##CB##_##PAR
 // weight load I of a step into buffer AB: 16 bytes per lane, asynchronous
 #define PATCH_WR_LOAD_A(AB, I, voff_, base_)                                                                       \
     asm volatile("global_load_dwordx4 " PATCH_WR_VA(AB, I) ", %0, %1" : : "v"(voff_), "s"(base_) : PATCH_WR_CLOBBER)
@@ -608,18 +663,27 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
         const int sm1 = S - 1, tkm1 = Tk - 1;
         const int live_i = __builtin_amdgcn_readfirstlane(live ? 1 : 0);
         asm volatile(
-            // ---- state of step 0: stages 0 / 1, the weight loads fetch tile min(1, Tk - 1), tile 0 is multiplied
+            // ---- lane offsets of the eight weight-load slots for either tile type
+            "v_mov_b32 v236, %[vd]\n\tv_add_u32 v237, 1024, %[vd]\n\tv_add_u32 v238, 4096, %[vd]\n\tv_add_u32 v239, 5120, %[vd]\n\t"
+            "v_add_u32 v240, 8192, %[vd]\n\tv_add_u32 v241, 9216, %[vd]\n\tv_add_u32 v242, 12288, %[vd]\n\tv_add_u32 v243, 13312, %[vd]\n\t"
+            "v_mov_b32 v244, %[vs]\n\tv_add_u32 v245, 2048, %[vs]\n\tv_add_u32 v246, 4096, %[vs]\n\tv_add_u32 v247, 6144, %[vs]\n\t"
+            "v_add_u32 v248, 16384, %[vm]\n\tv_add_u32 v249, 16640, %[vm]\n\tv_add_u32 v250, 16896, %[vm]\n\tv_add_u32 v251, 17152, %[vm]\n\t"
+            // ---- state of step 0: stages 0 / 1, the weight loads fetch K-step 0 of tile min(1, Tk - 1), tile 0 is multiplied
             "s_mov_b32 s80, 0\n\t"
             "v_mov_b32 v224, %[bl0]\n\tv_mov_b32 v225, %[bh0]\n\t"
             "v_add_u32 v226, 0x8000, %[bl0]\n\tv_add_u32 v227, 0x8000, %[bh0]\n\t"
             "s_min_u32 s88, 1, %[tkm1]\n\t"
-            "v_readlane_b32 s89, %[ent0], s88\n\t"
-            "s_lshr_b32 s94, s89, 1\n\ts_mov_b32 s95, 0\n\ts_lshl_b64 s[94:95], s[94:95], 8\n\t"
-            "s_add_u32 s84, %[plo], s94\n\ts_addc_u32 s85, %[phi], s95\n\t"
-            "s_bitcmp1_b32 s89, 0\n\ts_cselect_b32 s86, -1, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
+            "v_readlane_b32 s76, %[ent0], s88\n\t"
+            "s_lshr_b32 s94, s76, 1\n\ts_mov_b32 s95, 0\n\ts_lshl_b64 s[94:95], s[94:95], 8\n\t"
+            "s_add_u32 s74, %[plo], s94\n\ts_addc_u32 s75, %[phi], s95\n\t"
+            "s_mov_b64 s[84:85], s[74:75]\n\ts_mov_b64 s[96:97], s[74:75]\n\t"
+            "s_bitcmp1_b32 s76, 0\n\ts_cselect_b32 s86, -1, 0\n\ts_cselect_b64 s[92:93], -1, 0\n\t"
             "v_readlane_b32 s89, %[ent0], 0\n\t"
             "s_and_b32 s87, s89, %[live]\n\t"
-            "v_cndmask_b32_e64 v228, %[vd], %[vs], s[92:93]\n\tv_cndmask_b32_e64 v229, %[vd], %[vm], s[92:93]\n\t"
+            "v_cndmask_b32_e64 v228, v236, v244, s[92:93]\n\tv_cndmask_b32_e64 v229, v237, v245, s[92:93]\n\t"
+            "v_cndmask_b32_e64 v230, v238, v246, s[92:93]\n\tv_cndmask_b32_e64 v231, v239, v247, s[92:93]\n\t"
+            "v_cndmask_b32_e64 v232, v240, v248, s[92:93]\n\tv_cndmask_b32_e64 v233, v241, v249, s[92:93]\n\t"
+            "v_cndmask_b32_e64 v234, v242, v250, s[92:93]\n\tv_cndmask_b32_e64 v235, v243, v251, s[92:93]\n\t"
             // ---- the loop: a round of six dense steps, a round of six 2:4 steps, entered at step 0 of the dense chain
             PATCH_WR_STEP_D(0, 0) PATCH_WR_STEP_D(1, 1) PATCH_WR_STEP_D(2, 0) PATCH_WR_STEP_D(3, 1) PATCH_WR_STEP_D(4, 0) PATCH_WR_STEP_D(5, 1)
             "s_branch WR_D0_%=\n\t"
@@ -631,8 +695,10 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
               [ldsw] "s"(ldsw), [bl0] "v"(bl0), [bh0] "v"(bh0), [vd] "v"(vd), [vs] "v"(vs), [vm] "v"(vm), [ent0] "v"(ent[0]), [ent1] "v"(ent[1]),
               [xo0] "v"(xoff[0]), [xo1] "v"(xoff[1]), [xo2] "v"(xoff[2]), [xo3] "v"(xoff[3]), [xo4] "v"(xoff[4]), [xo5] "v"(xoff[5]),
               [xo6] "v"(xoff[6]), [xo7] "v"(xoff[7])
-            : "memory", "scc", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
-              "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", PATCH_WR_CLOBBER);
+            : "memory", "scc", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237",
+              "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", "s74", "s75", "s76",
+              "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97",
+              PATCH_WR_CLOBBER);
     }
 #undef PATCH_WR_STEP_D
 #undef PATCH_WR_STEP_S
