@@ -43,6 +43,20 @@ PEAK_MFMA_BF16_TF = 2500.0  # MI355X published dense bf16 matrix peak
 PAPER_CONTEXT = "paper: 1.18x-1.38x end-to-end LLaMA-2 7B speedup on an A6000 at 25-45% sparsity (context, not a target)"
 
 
+def _keep_top2(torch, W):
+    """(N K / 4, 4) uint8 keep-mask of the two largest |w| of every four consecutive elements (lower index on ties), on
+    the device: an element is kept when fewer than two others beat it."""
+    mag = W.abs().float().view(-1, 4)
+    keep = torch.empty_like(mag, dtype=torch.uint8)
+    for p_ in range(4):
+        beaten = torch.zeros(mag.shape[0], device=W.device, dtype=torch.int32)
+        for o in range(4):
+            if o != p_:
+                beaten += (mag[:, o] >= mag[:, p_]) if o < p_ else (mag[:, o] > mag[:, p_])
+        keep[:, p_] = beaten < 2
+    return keep
+
+
 def stack_13b(torch, B, synth, dev, stream, timed, t):
     """The 13B decoder stack: 40 layers x {q, k, v, o 5120 x 5120; gate, up 13824 x 5120; down 5120 x 13824}, one 2:4
     tile fraction per layer drawn U[0, 1), every GEMM with its own X, M in {1, 512, 4096}; time = sum over the layers.
@@ -74,8 +88,7 @@ def stack_13b(torch, B, synth, dev, stream, timed, t):
         layer, dense = {}, {}
         for name, N_, K_ in shapes:
             W = (torch.randn(N_, K_, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
-            keep = torch.zeros((N_ * K_ // 4, 4), device=dev, dtype=torch.uint8)
-            keep.scatter_(1, W.abs().float().view(-1, 4).topk(2, dim=1).indices, 1)
+            keep = _keep_top2(torch, W)
             tm = synth.tile_map(li, N_ // t, K_ // t, f, "stack13b", name)
             W_hat = torch.empty_like(W)
             B.patch_apply_mask(W, keep.view(N_, K_), tm, N_, K_, t, W_hat, stream)
