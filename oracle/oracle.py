@@ -50,6 +50,12 @@ def _load():
         L.patch_oracle_unpack.argtypes = [vp, vp, i64, i64, vp, ci, vp]
         L.patch_oracle_gemm.argtypes = [vp, i64, vp, vp, i64, i64, vp, ci, vp]
         L.patch_oracle_gemm_points.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
+        L.patch_oracle_quantize4.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.patch_oracle_quantize4.restype = ci
+        L.patch_oracle_dequantize4.argtypes = [vp, vp, i64, i64, ci, vp]
+        L.patch_oracle_dequantize4.restype = ci
+        L.patch_oracle_packed4_sizes.argtypes = [i64, i64, ci, vp, vp, vp, vp]
+        L.patch_oracle_packed4_sizes.restype = ci
         L.patch_oracle_round_bf16.argtypes = [vp, i64, vp]
         L.patch_oracle_round_bf16.restype = ci
         for f in ("apply_mask", "packed_sizes", "pack", "unpack", "gemm", "gemm_points", "num_threads"):
@@ -167,6 +173,39 @@ def round_bf16(Y):
     if rc:
         raise OracleError(rc)
     return out
+
+
+def quantize4(W_hat, t):
+    """-> (codes int8 (N, K) in [-7, 7], scales uint16 bf16 bits (N, K / t)): symmetric 4-bit codes, one scale per row of a tile."""
+    W_hat = _u16(W_hat)
+    N, K = W_hat.shape
+    codes, scales = np.empty((N, K), np.int8), np.empty((N, K // t), np.uint16)
+    rc = _load().patch_oracle_quantize4(_p(W_hat), N, K, t, _p(codes), _p(scales))
+    if rc:
+        raise OracleError(rc)
+    return codes, scales
+
+
+def dequantize4(codes, scales, t):
+    """-> bf16 bit patterns (N, K) of bf16(code * scale)."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    N, K = codes.shape
+    scales = _u16(scales, (N, K // t))
+    out = np.empty((N, K), np.uint16)
+    rc = _load().patch_oracle_dequantize4(_p(codes), _p(scales), N, K, t, _p(out))
+    if rc:
+        raise OracleError(rc)
+    return out
+
+
+def packed4_sizes(N, K, t, tile_map):
+    """-> (code bytes, position bytes, scale bytes) of the 4-bit storage."""
+    tm = _map(tile_map, N, K, t)
+    a, b, c = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = _load().patch_oracle_packed4_sizes(N, K, t, _p(tm), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc:
+        raise OracleError(rc)
+    return int(a.value), int(b.value), int(c.value)
 
 
 def gemm_points(X, W_hat_dense, mn):

@@ -31,6 +31,16 @@
  * (patch_oracle_round_bf16).  The library rounds its fp32 accumulator instead, so the two may differ by one
  * unit in the last place; the tests allow exactly that.
  *
+ * 4-bit weight-only storage (Section 5.2, "Quantization", and the table of 4-bit results there: the pruned weights are
+ * stored in 4 bits; the table's compression ratios are 16 / (4 (1 - f) + 3 f) for a fraction f of 2:4 tiles, i.e. 4 bits
+ * per element of a dense tile and 2 x 4 + 4 bits per group of four of a 2:4 tile, scales not counted).  The paper
+ * names no quantizer; the reading taken (patch_oracle_quantize4): symmetric, 15 levels, one scale per row of a tile:
+ *     s = bf16( max|w| / 7 )  (float division, rounded to nearest even),   q = clamp( rint( w / s ), -7, 7 )  (float
+ *     division, ties to even),   s = 0 (an all-zero row) gives q = 0;
+ *     the weight the product then uses is  bf16( q s )  (exact product, one rounding): patch_oracle_dequantize4.
+ * A pruned weight is 0 and keeps code 0, so a 2:4 tile stays 2:4; its kept positions are those of the unquantized
+ * matrix.  Both decisions (s and q) are taken in float, the precision the library takes them in.
+ *
  * Parity pins (see tests/test_oracle_*.py): hand-worked packed example, closed-form sizes, round trip,
  * naive dense GEMM (bit-equal), library dense GEMM, direct 2:4 GEMM on (values, positions), exact
  * rational brute force over all six patterns, linearity and tile-map invariance.
@@ -278,6 +288,78 @@ int patch_oracle_round_bf16(const double* y, int64_t n, uint16_t* out) {
         memcpy(&u, &f, sizeof u);
         out[i] = (uint16_t)(sign | (uint16_t)(u >> 16));
     }
+    return PO_OK;
+}
+
+static uint16_t float_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/* codes[n][k] in [-7, 7] (0 where W_hat is zero), scales[n][k / t] as bf16 bit patterns: see the header. */
+int patch_oracle_quantize4(const uint16_t* W_hat, int64_t N, int64_t K, int t, int8_t* codes, uint16_t* scales) {
+    if (!W_hat || !codes || !scales) return PO_ERR_ARG;
+    int rc = check_shape(N, K, t);
+    if (rc) return rc;
+    const int64_t Tk = K / t;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g = 0; g < Tk; ++g) {
+            const uint16_t* w = W_hat + n * K + g * t;
+            float amax = 0.0f;
+            for (int k = 0; k < t; ++k) {
+                const float a = fabsf((float)bf16_to_double(w[k]));
+                if (a > amax) amax = a;
+            }
+            const uint16_t sb = float_to_bf16_rne(amax / 7.0f);
+            const float s = (float)bf16_to_double(sb);
+            scales[n * Tk + g] = sb;
+            for (int k = 0; k < t; ++k) {
+                int q = 0;
+                if (s > 0.0f) {
+                    float r = rintf((float)bf16_to_double(w[k]) / s);
+                    if (r > 7.0f) r = 7.0f;
+                    if (r < -7.0f) r = -7.0f;
+                    q = (int)r;
+                }
+                codes[n * K + g * t + k] = (int8_t)q;
+            }
+        }
+    return PO_OK;
+}
+
+/* W_deq[n][k] = bf16( codes[n][k] * scales[n][k / t] ), the exact product rounded once. */
+int patch_oracle_dequantize4(const int8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int t, uint16_t* W_deq) {
+    if (!codes || !scales || !W_deq) return PO_ERR_ARG;
+    int rc = check_shape(N, K, t);
+    if (rc) return rc;
+    const int64_t Tk = K / t;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const double v = (double)codes[n * K + k] * bf16_to_double(scales[n * Tk + k / t]);
+            rc = patch_oracle_round_bf16(&v, 1, &W_deq[n * K + k]);
+            if (rc) return rc;
+        }
+    return PO_OK;
+}
+
+/* Bytes of the 4-bit storage: codes (4 bits per element of a dense tile, per kept element of a 2:4 tile), positions
+ * (2 bits per kept element) and scales (one bf16 per row of a tile). */
+int patch_oracle_packed4_sizes(int64_t N, int64_t K, int t, const uint8_t* tile_map, int64_t* code_bytes, int64_t* meta_bytes,
+                               int64_t* scale_bytes) {
+    int rc = check_shape(N, K, t);
+    if (rc) return rc;
+    if (!tile_map || !code_bytes || !meta_bytes || !scale_bytes) return PO_ERR_ARG;
+    int64_t T = (N / t) * (K / t), c = 0, m = 0;
+    for (int64_t i = 0; i < T; ++i) {
+        if (tile_map[i]) c += (int64_t)t * t / 2;
+        else { c += (int64_t)t * t / 4; m += (int64_t)t * t / 8; }
+    }
+    *code_bytes = c;
+    *meta_bytes = m;
+    *scale_bytes = T * t * 2;
     return PO_OK;
 }
 

@@ -18,6 +18,9 @@ int patch_oracle_unpack(const uint16_t*, const uint8_t*, int64_t, int64_t, const
 int patch_oracle_gemm(const uint16_t*, int64_t, const uint16_t*, const uint8_t*, int64_t, int64_t, const uint8_t*, int, double*);
 int patch_oracle_gemm_points(const uint16_t*, int64_t, const uint16_t*, int64_t, int64_t, const int64_t*, int64_t, double*);
 int patch_oracle_round_bf16(const double*, int64_t, uint16_t*);
+int patch_oracle_quantize4(const uint16_t*, int64_t, int64_t, int, int8_t*, uint16_t*);
+int patch_oracle_dequantize4(const int8_t*, const uint16_t*, int64_t, int64_t, int, uint16_t*);
+int patch_oracle_packed4_sizes(int64_t, int64_t, int, const uint8_t*, int64_t*, int64_t*, int64_t*);
 
 static uint64_t state = 0x9E3779B97F4A7C15ull;
 static uint32_t rnd(void) {
@@ -68,6 +71,17 @@ static int one_case(int64_t N, int64_t K, int t, int64_t M, int map_kind) {
     REQUIRE(yp[0] == Y[0] && yp[1] == Y[(M - 1) * N + N - 1]);
     uint16_t* yb = malloc((size_t)(M * N) * 2);
     REQUIRE(yb && patch_oracle_round_bf16(Y, M * N, yb) == 0);
+    {   /* 4-bit storage of the pruned matrix */
+        int8_t* codes = malloc((size_t)(N * K));
+        uint16_t* scales = malloc((size_t)(N * (K / t)) * 2);
+        int64_t cb, mb, sb;
+        REQUIRE(codes && scales);
+        REQUIRE(patch_oracle_quantize4(W_hat, N, K, t, codes, scales) == 0);
+        REQUIRE(patch_oracle_dequantize4(codes, scales, N, K, t, W_back) == 0);
+        REQUIRE(patch_oracle_packed4_sizes(N, K, t, tm, &cb, &mb, &sb) == 0 && cb > 0 && sb == N * (K / t) * 2);
+        for (int64_t i = 0; i < N * K; ++i) REQUIRE(codes[i] >= -7 && codes[i] <= 7 && ((W_hat[i] & 0x7FFF) != 0 || codes[i] == 0));
+        free(codes); free(scales);
+    }
     if (map_kind != 0) {   /* an unmasked matrix under a map with 2:4 tiles must be rejected, without stray writes */
         int dense_enough = 0;
         for (int64_t i = 0; i < N * K && !dense_enough; i += 4)

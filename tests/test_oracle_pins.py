@@ -447,3 +447,89 @@ def test_oracle_runs_clean_under_address_and_undefined_sanitizers(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "sanitize_check ok" in r.stdout, (r.stdout[-500:], r.stderr[-2000:])
     assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
+
+
+# ---------------------------------------------------------------------------------------------------------
+# 4-bit weight-only storage (Section 5.2): symmetric 15-level codes, one scale per row of a tile
+
+def test_packed4_sizes_reproduce_the_papers_compression_ratios(golden_dir):
+    """Codes + positions of the 4-bit storage against the paper's theoretical compression ratios (scales are not
+    counted there): 16 bits / (4 (1 - f) + 3 f)."""
+    with open(os.path.join(golden_dir, "paper_4bit_compression.json")) as fh:
+        rows = json.load(fh)["rows"]
+    N, K, t = 1280, 1280, 128                      # 100 tiles: every fraction of the table is a whole number of tiles
+    for r in rows:
+        tm = synth.tile_map(3, N // t, K // t, r["tile_fraction_24"], "q4ratio")
+        c, m, s = oracle.packed4_sizes(N, K, t, tm)
+        assert abs(2 * N * K / (c + m) - r["ratio"]) < 0.006, (r, 2 * N * K / (c + m))
+        assert s == (N // t) * (K // t) * t * 2
+
+
+def test_quantize4_hand_worked_group_with_ties():
+    """One row of a tile (t = 8), scale a power of two: max|w| = 7 / 64 gives s = 1 / 64 exactly, so w / s is exact and
+    the halves show the tie rule (to the even code)."""
+    w = np.array([7, -3.5, 1, 0, 0.49, -0.5, 2.5, -7], np.float32) / 64
+    bits = synth.f32_to_bf16_bits(np.tile(w, (8, 1)))               # 8 x 8: one tile of t = 8
+    bits[1] = 0                                                       # an all-zero row: scale 0, codes 0
+    assert np.array_equal(synth.bf16_bits_to_f32(bits[0]), synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(w)))
+    codes, scales = oracle.quantize4(bits, 8)
+    wq = synth.bf16_bits_to_f32(bits[0]) * 64                         # 0.49 is not a bf16 number: take what was stored
+    assert abs(wq[4] - 0.49) < 0.004
+    assert codes[0].tolist() == [7, -4, 1, 0, 0, 0, 2, -7]
+    assert synth.bf16_bits_to_f32(scales[:, 0])[0] == 1 / 64 and scales[1, 0] == 0 and not codes[1].any()
+    deq = synth.bf16_bits_to_f32(oracle.dequantize4(codes, scales, 8))
+    assert deq[0].tolist() == [7 / 64, -4 / 64, 1 / 64, 0, 0, 0, 2 / 64, -7 / 64]
+
+
+def test_quantize4_scale_that_needs_rounding():
+    """max|w| = 1: 1 / 7 = 1.0010010 0100...b x 2^-3 rounds down to 1.0010010b x 2^-3 = 0.142578125 in bf16."""
+    w = np.zeros((8, 8), np.float32)
+    w[:, 0] = 1.0
+    w[:, 1] = -0.5
+    w[:, 2] = 0.07
+    codes, scales = oracle.quantize4(synth.f32_to_bf16_bits(w), 8)
+    assert synth.bf16_bits_to_f32(scales)[0, 0] == 0.142578125
+    # 1 / s = 7.0137 -> 7;  -0.5 / s = -3.507 -> -4;  bf16(0.07) = 0.06982 / s = 0.4897 -> 0
+    assert codes[0, :3].tolist() == [7, -4, 0]
+
+
+def test_quantize4_against_exact_rationals_and_library_float_ops():
+    """Seeded rows: the scale is bf16(max|w| / 7) as float32 library ops compute it; every code is the integer nearest
+    to w / s in exact rational arithmetic (unless w / s lies within 2^-20 of a half, where the float division decides),
+    |code| <= 7, zero keeps code 0, the largest element gets +-7; the dequantized value is the exact product rounded
+    once, and lies within half a step (plus its rounding) of the weight."""
+    from fractions import Fraction
+    t = 64
+    R = 64
+    bits = synth.normal_bf16(5, (R, 2 * t), 0.02, "q4")
+    bits[2, 5:40] = 0
+    bits[3, :t] = 0
+    codes, scales = oracle.quantize4(bits, t)
+    w = synth.bf16_bits_to_f32(bits)
+    s32 = synth.bf16_bits_to_f32(scales)
+    amax = np.abs(w.reshape(R, 2, t)).max(axis=2)
+    assert np.array_equal(scales, synth.f32_to_bf16_bits(amax / np.float32(7)))
+    lib = np.rint(np.divide(w.reshape(R, 2, t), np.where(s32 > 0, s32, 1)[:, :, None], dtype=np.float32)).astype(np.int64)
+    lib = np.clip(np.where(s32[:, :, None] > 0, lib, 0), -7, 7).reshape(R, 2 * t)
+    assert np.array_equal(codes, lib)
+    assert np.abs(codes).max() <= 7 and not codes[w == 0].any() and not codes[3, :t].any() and scales[3, 0] == 0
+    for n in range(0, R, 7):
+        for k in range(2 * t):
+            s = Fraction(float(s32[n, k // t]))
+            if s == 0:
+                continue
+            r = Fraction(float(w[n, k])) / s
+            q = int(codes[n, k])
+            near_half = abs(abs(r - int(r)) - Fraction(1, 2)) < Fraction(1, 1 << 20)
+            assert abs(r - q) <= Fraction(1, 2) or near_half or abs(r) > 7, (n, k, float(r), q)
+    big = np.abs(w.reshape(R, 2, t)).argmax(axis=2)
+    for n in range(R):
+        for g in range(2):
+            if s32[n, g] > 0:
+                assert abs(int(codes[n, g * t + big[n, g]])) == 7
+    deq_bits = oracle.dequantize4(codes, scales, t)
+    exact = codes.astype(np.float64) * np.repeat(s32.astype(np.float64), t, axis=1)
+    assert np.array_equal(deq_bits, oracle.round_bf16(exact))
+    deq = synth.bf16_bits_to_f64(deq_bits)
+    step = np.repeat(s32.astype(np.float64), t, axis=1)
+    assert (np.abs(deq - w) <= step * (0.5 + 7 * 2.0 ** -9 + 2.0 ** -8) + 1e-30).all()   # half a step, the rounding of up to 7 s, the rounded scale
