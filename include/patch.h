@@ -269,6 +269,32 @@ patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, siz
 patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_t cap, size_t* count);
 
 /*
+ * 4-bit weight-only storage of the pruned weight and its decode-shaped product (Section 5.2, "Quantization": the
+ * hybrid-sparse model composed with 4-bit weight-only quantization; its table counts 4 bits per element of a dense tile
+ * and 2 x 4 + 4 bits per group of four of a 2:4 tile).  The paper names no quantizer; this library's is symmetric with
+ * 15 levels and one scale per row of a tile:  s = bf16(max|w| / 7),  q = clamp(rint(w / s), -7, 7)  (fp32, ties to
+ * even; an all-zero row: s = 0, q = 0); the weight the product uses is bf16(q s).  A pruned weight keeps code 0, so a 2:4
+ * tile stays 2:4 (its kept positions are those of W_hat).
+ *   patch_pack4    W_hat, N, K, tile_map, tile, stream, *out as for patch_pack; synchronises `stream` once; returns
+ *                  PATCH_ERR_NOT_24 like patch_pack
+ *   patch_gemm4    Y[m, n] = sum_k X[m, k] * bf16(q s)[n, k]: X DEVICE M x K bf16, Y DEVICE M x N fp32, both 16-byte
+ *                  aligned; asynchronous, allocates nothing, bit-reproducible.  Decode-shaped: the weight is streamed
+ *                  once per 16 rows of X; for prefill shapes dequantize once (patch_unpack4) and patch_pack the result
+ *   patch_unpack4  any of: W_deq (DEVICE, N x K bf16, 16-byte aligned) = bf16(q s), 0 at pruned positions; codes
+ *                  (DEVICE, N x K int8, 0 at pruned positions); scales (DEVICE, N x (K / tile) bf16); NULL = not wanted
+ *   patch_packed4_bytes  codes + positions + scales, without alignment padding
+ * Errors as for their bf16 counterparts.
+ */
+typedef struct patch_packed4 patch_packed4;
+patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
+                         patch_packed4** out);
+patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream);
+patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream);
+size_t patch_packed4_bytes(const patch_packed4* P);
+patch_status patch_packed4_dims(const patch_packed4* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles);
+void patch_free4(patch_packed4* P);
+
+/*
  * Measurement probes (this project's; no passage of the paper): kernels that run nothing of the method, for the
  * measured ceilings the benchmark prints beside the product kernels.  Both are asynchronous on `stream` and
  * allocate nothing; the caller times them with events.

@@ -21,6 +21,7 @@ EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_tune_all",
     "patch_tune_bucket", "patch_tune_table_create", "patch_tune_table_destroy", "patch_tune_table_size", "patch_tune_table_put",
     "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
+    "patch_pack4", "patch_gemm4", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -95,6 +96,18 @@ def lib() -> ctypes.CDLL:
         L.patch_probe_matrix_rate.restype = ci
         L.patch_probe_stream_read.argtypes = [vp, sz, ci, ci, vp, sz, vp]
         L.patch_probe_stream_read.restype = ci
+        L.patch_pack4.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
+        L.patch_pack4.restype = ci
+        L.patch_gemm4.argtypes = [vp, i64, vp, vp, vp]
+        L.patch_gemm4.restype = ci
+        L.patch_unpack4.argtypes = [vp, vp, vp, vp, vp]
+        L.patch_unpack4.restype = ci
+        L.patch_packed4_bytes.argtypes = [vp]
+        L.patch_packed4_bytes.restype = sz
+        L.patch_packed4_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ci), ctypes.POINTER(i64)]
+        L.patch_packed4_dims.restype = ci
+        L.patch_free4.argtypes = [vp]
+        L.patch_free4.restype = None
         L.patch_free.argtypes = [vp]
         L.patch_free.restype = None
         L.patch_strerror.argtypes = [ci]
@@ -336,6 +349,51 @@ def patch_gemm_many(X, M: int, Ps, Ys, stream: int = 0, path: int = PATH_AUTO, s
     yp = (ctypes.c_void_p * max(n, 1))(*[_ptr(y) for y in Ys])
     o = _opts(path, split_k, variant, workspace, workspace_bytes, y_bf16)
     _check(lib().patch_gemm_many(_ptr(X), M, hp, yp, n, stream, ctypes.byref(o)), "patch_gemm_many")
+
+
+class Packed4:
+    """Owner of a ``patch_packed4*`` (4-bit weight-only storage); freed on ``close()`` or garbage collection."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def close(self):
+        if self.handle:
+            lib().patch_free4(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def nbytes(self) -> int:
+        return int(lib().patch_packed4_bytes(self.handle))
+
+    def dims(self):
+        N, K, t, ns = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int64()
+        _check(lib().patch_packed4_dims(self.handle, ctypes.byref(N), ctypes.byref(K), ctypes.byref(t), ctypes.byref(ns)), "patch_packed4_dims")
+        return int(N.value), int(K.value), int(t.value), int(ns.value)
+
+
+def patch_pack4(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> Packed4:
+    tm = _map_host(tile_map)
+    if N > 0 and K > 0 and tile > 0 and N % tile == 0 and K % tile == 0 and tm.size != (N // tile) * (K // tile):
+        raise PatchError(ERR_ARG, "patch_pack4: tile_map has the wrong number of entries")
+    out = ctypes.c_void_p(0)
+    _check(lib().patch_pack4(_ptr(W_hat), N, K, tm.ctypes.data, tile, stream, ctypes.byref(out)), "patch_pack4")
+    return Packed4(out.value)
+
+
+def patch_gemm4(X, M: int, P: Packed4, Y, stream: int = 0) -> None:
+    _check(lib().patch_gemm4(_ptr(X), M, P.handle, _ptr(Y), stream), "patch_gemm4")
+
+
+def patch_unpack4(P: Packed4, W_deq=None, codes=None, scales=None, stream: int = 0) -> None:
+    _check(lib().patch_unpack4(P.handle, _ptr(W_deq) if W_deq is not None else None, _ptr(codes) if codes is not None else None,
+                               _ptr(scales) if scales is not None else None, stream), "patch_unpack4")
 
 
 PROBE_OPERAND_BYTES = 12 * 256 * 16

@@ -33,6 +33,7 @@ struct patch_packed {
 };
 
 static thread_local int g_last_hip_error = 0;
+void patch_note_hip_error(int hip_error) { g_last_hip_error = hip_error; }
 
 #define HIP_TRY(expr)                                   \
     do {                                                \

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// records the hipError_t that patch_last_hip_error reports (thread-local, in api.hip)
+void patch_note_hip_error(int hip_error);
+
 namespace patch {
 
 void launch_apply_mask(const uint16_t* W, const uint8_t* mask24, const uint8_t* d_tile_map, int64_t N, int64_t K, int tile,

@@ -1,0 +1,403 @@
+// 4-bit weight-only storage of the hybrid dense / 2:4 weight and its decode-shaped product (Section 5.2 of the paper,
+// "Quantization": the pruned model is composed with 4-bit weight-only quantization; the table there counts 4 bits per
+// element of a dense tile and 2 x 4 + 4 bits per group of four of a 2:4 tile).  The paper names no quantizer; this
+// library's: symmetric, 15 levels, one scale per row of a tile,
+//     s = bf16(max|w| / 7),   q = clamp(rint(w / s), -7, 7)   (both in fp32, correctly rounded division, ties to even),
+// and the weight the product uses is bf16(q s): the exact product rounded once.  A pruned weight keeps code 0, so a
+// 2:4 tile stays 2:4; its kept positions are those of the unquantized matrix.
+//
+// Layout (tiles row-major, each on a 256-byte granule, table entry = offset / 256 << 1 | is 2:4, as for bf16):
+//   dense tile : code fragments in (strip, K-step) order, 512 B each: lane l holds two dwords, the 8 codes of
+//                W[row0 + l % 16][k0 + 8 (l / 16) + e] and those 32 columns further (the two operands of
+//                v_mfma_f32_16x16x32_bf16), code e in bits [4e+3 : 4e], two's complement;
+//                then the tile's `tile` scales (bf16, row order)
+//   2:4 tile   : code fragments of 256 B: lane l holds the 8 kept codes of W[row0 + l % 16][k0 + 16 (l / 16) .. + 15]
+//                (the operand of v_smfmac_f32_16x16x64_bf16); then the positions, uint16 [strip][lane][K-step] as in the
+//                bf16 layout; then the scales
+// The product kernel dequantizes in registers (8 codes -> 8 bf16 with integer rounding) and then runs the same matrix
+// instructions as the bf16 decode kernel: one workgroup per strip of 16 features, its wavefronts split K, partial sums
+// meet in LDS in wavefront order (bit-reproducible).  It is the decode-shaped path only - up to 16 rows per pass over
+// the weight; for prefill shapes dequantize once (patch_unpack4) and pack the result as bf16.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/patch.h"
+#include "epilogue.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace patch {
+
+typedef __bf16 q4_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 q4_bf16x16 __attribute__((ext_vector_type(16)));
+typedef float q4_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int q4_u32x4 __attribute__((ext_vector_type(4)));
+union Q4A { q4_u32x4 raw; q4_bf16x8 v; };
+union Q4B { q4_u32x4 raw[2]; q4_bf16x8 h[2]; q4_bf16x16 v; };
+
+__host__ __device__ constexpr int q4_dense_codes(int t) { return t * t / 2; }
+__host__ __device__ constexpr int q4_sparse_codes(int t) { return t * t / 4; }
+__host__ __device__ constexpr int q4_sparse_pos(int t) { return t * t / 8; }
+__host__ __device__ constexpr int q4_round_up(int b) { return (b + kGranule - 1) / kGranule * kGranule; }
+__host__ __device__ constexpr int q4_dense_tile(int t) { return q4_round_up(q4_dense_codes(t) + 2 * t); }
+__host__ __device__ constexpr int q4_sparse_tile(int t) { return q4_round_up(q4_sparse_codes(t) + q4_sparse_pos(t) + 2 * t); }
+
+__device__ __forceinline__ float q4_bf16_to_float(uint32_t bits) { return __uint_as_float(bits << 16); }
+
+// 4-bit code of w for scale s (s > 0), as a nibble
+__device__ __forceinline__ uint32_t q4_code(uint16_t w_bits, float s) {
+    float r = rintf(__fdiv_rn(q4_bf16_to_float(w_bits), s));
+    r = fminf(fmaxf(r, -7.0f), 7.0f);
+    return (uint32_t)((int)r) & 0xFu;
+}
+
+// 8 codes of a dword -> 8 bf16 values bf16(q s), element e from bits [4e+3 : 4e]
+__device__ __forceinline__ q4_u32x4 q4_dequant8(uint32_t codes, float s) {
+    q4_u32x4 out;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int q0 = ((int)(codes << (28 - 8 * p))) >> 28, q1 = ((int)(codes << (24 - 8 * p))) >> 28;
+        out[p] = bf16_rne_bits((float)q0 * s) | (bf16_rne_bits((float)q1 * s) << 16);
+    }
+    return out;
+}
+
+__device__ __forceinline__ bool q4_nonzero(uint16_t h) { return (h & 0x7FFFu) != 0; }
+
+// One workgroup per tile: scales, then codes (and, for a 2:4 tile, the kept positions of the unquantized weights).
+__global__ __launch_bounds__(256) void pack4_kernel(const uint16_t* __restrict__ W, int64_t K, const uint32_t* __restrict__ table, int Tk,
+                                                    int tile, uint8_t* __restrict__ payload, int* __restrict__ err) {
+    __shared__ float sc[128];
+    const int t = blockIdx.x;
+    const int tn = t / Tk, tk = t % Tk;
+    const uint32_t e = table[t];
+    const bool sparse = entry_sparse(e);
+    uint8_t* base = payload + entry_offset(e);
+    const int64_t n0 = (int64_t)tn * tile, k0 = (int64_t)tk * tile;
+    const int KPT = tile / kStepCols;
+    uint16_t* scales = reinterpret_cast<uint16_t*>(base + (sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) : q4_dense_codes(tile)));
+    for (int r = threadIdx.x; r < tile; r += blockDim.x) {
+        const uint16_t* row = W + (n0 + r) * K + k0;
+        uint32_t amax = 0;   // |w| compares like its bit pattern
+        for (int k = 0; k < tile; k += 8) {
+            union { q4_u32x4 v; uint16_t h[8]; } in;
+            in.v = *reinterpret_cast<const q4_u32x4*>(row + k);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { const uint32_t a = in.h[i] & 0x7FFFu; amax = a > amax ? a : amax; }
+        }
+        const uint32_t sb = bf16_rne_bits(__fdiv_rn(q4_bf16_to_float(amax), 7.0f));
+        scales[r] = (uint16_t)sb;
+        sc[r] = q4_bf16_to_float(sb);
+    }
+    __syncthreads();
+    if (!sparse) {
+        const int nchunks = tile * tile / 16;   // one lane of one fragment: 16 elements -> 2 dwords
+        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+            const int lane = c & 63, sj = c >> 6;
+            const int j = sj % KPT, s = sj / KPT, i = lane & 15, q = lane >> 4;
+            const float scl = sc[16 * s + i];
+            uint32_t d[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                union { q4_u32x4 v; uint16_t hh[8]; } in;
+                in.v = *reinterpret_cast<const q4_u32x4*>(W + (n0 + 16 * s + i) * K + k0 + 64 * j + 32 * h + 8 * q);
+                uint32_t w = 0;
+#pragma unroll
+                for (int el = 0; el < 8; ++el) w |= (scl > 0.f ? q4_code(in.hh[el], scl) : 0u) << (4 * el);
+                d[h] = w;
+            }
+            *reinterpret_cast<uint2*>(base + (size_t)c * 8) = uint2{d[0], d[1]};
+        }
+    } else {
+        const int nchunks = tile * tile / 16;   // one lane of one fragment: 16 elements -> 8 kept codes
+        uint16_t* meta = reinterpret_cast<uint16_t*>(base + q4_sparse_codes(tile));
+        bool ok = true;
+        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+            const int lane = c & 63, sj = c >> 6;
+            const int j = sj % KPT, s = sj / KPT, i = lane & 15, qa = lane >> 4;
+            const float scl = sc[16 * s + i];
+            union { q4_u32x4 v[2]; uint16_t h[16]; } in;
+            const uint16_t* src = W + (n0 + 16 * s + i) * K + k0 + 64 * j + 16 * qa;
+            in.v[0] = *reinterpret_cast<const q4_u32x4*>(src);
+            in.v[1] = *reinterpret_cast<const q4_u32x4*>(src + 8);
+            uint32_t codes = 0, idx = 0;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                // kept positions: the nonzeros, padded with the lowest-index zeros (the rule of the bf16 packer)
+                bool keep[4];
+                int nnz = 0;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) { keep[p] = q4_nonzero(in.h[4 * g + p]); nnz += keep[p] ? 1 : 0; }
+                if (nnz > 2) ok = false;
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    if (!keep[p] && nnz < 2) { keep[p] = true; ++nnz; }
+                int p0 = -1, p1 = -1;
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    if (keep[p]) { if (p0 < 0) p0 = p; else if (p1 < 0) p1 = p; }
+                if (p1 < 0) { p0 = 0; p1 = 1; }
+                const uint32_t c0 = scl > 0.f ? q4_code(in.h[4 * g + p0], scl) : 0u, c1 = scl > 0.f ? q4_code(in.h[4 * g + p1], scl) : 0u;
+                codes |= (c0 | (c1 << 4)) << (8 * g);
+                idx |= (uint32_t)(p0 | (p1 << 2)) << (4 * g);
+            }
+            *reinterpret_cast<uint32_t*>(base + (size_t)c * 4) = codes;
+            meta[(s * 64 + lane) * KPT + j] = (uint16_t)idx;
+        }
+        if (!ok) atomicOr(err, 1);
+    }
+}
+
+// The inverse: the dequantized bf16 matrix and / or the codes (int8, 0 at dropped positions) and scales in matrix order.
+__global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table, int Tk, int tile,
+                                                      int64_t K, uint16_t* __restrict__ W_deq, int8_t* __restrict__ codes_out,
+                                                      uint16_t* __restrict__ scales_out) {
+    const int t = blockIdx.x;
+    const int tn = t / Tk, tk = t % Tk;
+    const uint32_t e = table[t];
+    const bool sparse = entry_sparse(e);
+    const uint8_t* base = payload + entry_offset(e);
+    const int64_t n0 = (int64_t)tn * tile, k0 = (int64_t)tk * tile;
+    const int KPT = tile / kStepCols;
+    const uint16_t* scales = reinterpret_cast<const uint16_t*>(base + (sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) : q4_dense_codes(tile)));
+    if (scales_out)
+        for (int r = threadIdx.x; r < tile; r += blockDim.x) scales_out[(n0 + r) * Tk + tk] = scales[r];
+    const int nchunks = tile * tile / 16;
+    const uint16_t* meta = reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(tile));
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+        const int lane = c & 63, sj = c >> 6;
+        const int j = sj % KPT, s = sj / KPT, i = lane & 15, q = lane >> 4;
+        const float scl = q4_bf16_to_float(scales[16 * s + i]);
+        int qv[16];
+        int64_t kk[16];
+        if (!sparse) {
+            const uint2 d = *reinterpret_cast<const uint2*>(base + (size_t)c * 8);
+#pragma unroll
+            for (int el = 0; el < 8; ++el) {
+                qv[el] = ((int)(d.x << (28 - 4 * el))) >> 28;
+                qv[8 + el] = ((int)(d.y << (28 - 4 * el))) >> 28;
+                kk[el] = 64 * j + 8 * q + el;
+                kk[8 + el] = 64 * j + 32 + 8 * q + el;
+            }
+        } else {
+            const uint32_t d = *reinterpret_cast<const uint32_t*>(base + (size_t)c * 4);
+            const uint32_t idx = meta[(s * 64 + lane) * KPT + j];
+#pragma unroll
+            for (int el = 0; el < 16; ++el) { qv[el] = 0; kk[el] = 64 * j + 16 * q + el; }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int p0 = (idx >> (4 * g)) & 3, p1 = (idx >> (4 * g + 2)) & 3;
+                const int c0 = ((int)(d << (28 - 8 * g))) >> 28, c1 = ((int)(d << (24 - 8 * g))) >> 28;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    if (p == p0) qv[4 * g + p] = c0;
+                    if (p == p1) qv[4 * g + p] = c1;
+                }
+            }
+        }
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            const int64_t at = (n0 + 16 * s + i) * K + k0 + kk[el];
+            if (W_deq) W_deq[at] = (uint16_t)bf16_rne_bits((float)qv[el] * scl);
+            if (codes_out) codes_out[at] = (int8_t)qv[el];
+        }
+    }
+}
+
+// Up to 16 rows of X against the 4-bit weight.  KW = blockDim.x / 64 wavefronts take contiguous runs of 64-column steps.
+template <int TILE>
+__global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
+                                                       const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
+                                                       float* __restrict__ Y, int64_t N) {
+    constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
+    __shared__ q4_f32x4 red[16][64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), KW = blockDim.x >> 6;
+    const int strip = blockIdx.x, tn = strip / SPT, s = strip % SPT;
+    const int col = lane & 15, q = lane >> 4;
+    const bool xvalid = col < rows;
+    const int total = Tk * KPT, per = (total + KW - 1) / KW;
+    const int begin = w * per, end = begin + per < total ? begin + per : total;
+    const uint16_t* xrow = X + (m0 + (xvalid ? col : 0)) * K + 8 * q;
+    q4_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int step = begin; step < end; ++step) {
+        const int tk = step / KPT, j = step % KPT;
+        const uint32_t e = __builtin_amdgcn_readfirstlane(table[(int64_t)tn * Tk + tk]);
+        const uint8_t* base = payload + entry_offset(e);
+        Q4B b;
+        b.raw[0] = q4_u32x4{0u, 0u, 0u, 0u};
+        b.raw[1] = q4_u32x4{0u, 0u, 0u, 0u};
+        if (xvalid) {
+            b.raw[0] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols);
+            b.raw[1] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
+        }
+        if (!entry_sparse(e)) {
+            const float scl = q4_bf16_to_float(*reinterpret_cast<const uint16_t*>(base + q4_dense_codes(TILE) + (16 * s + col) * 2));
+            const uint2 d = *reinterpret_cast<const uint2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
+            Q4A a0, a1;
+            a0.raw = q4_dequant8(d.x, scl);
+            a1.raw = q4_dequant8(d.y, scl);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, b.h[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, b.h[1], acc, 0, 0, 0);
+        } else {
+            const float scl = q4_bf16_to_float(
+                *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + q4_sparse_pos(TILE) + (16 * s + col) * 2));
+            const uint32_t d = *reinterpret_cast<const uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
+            const uint32_t idx = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
+            Q4A a;
+            a.raw = q4_dequant8(d, scl);
+            acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b.v, acc, (int)idx, 0, 0);
+        }
+    }
+    red[w][lane] = acc;
+    __syncthreads();
+    if (w == 0) {
+        q4_f32x4 sum = red[0][lane];
+        for (int i = 1; i < KW; ++i) {
+            const q4_f32x4 v = red[i][lane];
+            sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+        }
+        if (xvalid) *reinterpret_cast<q4_f32x4*>(Y + (m0 + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
+    }
+}
+
+}  // namespace patch
+
+using namespace patch;
+
+struct patch_packed4 {
+    int64_t N = 0, K = 0;
+    int tile = 0, Tn = 0, Tk = 0;
+    int64_t n_sparse = 0;
+    size_t algorithmic_bytes = 0;   // codes + positions + scales, without alignment padding
+    size_t payload_bytes = 0;
+    uint8_t* d_payload = nullptr;
+    uint32_t* d_table = nullptr;
+    int n_cus = 256;
+};
+
+static bool q4_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" {
+
+void patch_free4(patch_packed4* P) {
+    if (!P) return;
+    if (P->d_payload) (void)hipFree(P->d_payload);
+    if (P->d_table) (void)hipFree(P->d_table);
+    delete P;
+}
+
+patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream, patch_packed4** out) {
+    if (!W_hat || !tile_map || !out || N <= 0 || K <= 0) return PATCH_ERR_ARG;
+    if ((tile != 64 && tile != 128) || N % tile || K % tile || N / tile > (1 << 20) || K / tile > (1 << 20)) return PATCH_ERR_SHAPE;
+    if (!q4_aligned16(W_hat)) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    patch_packed4* P = new (std::nothrow) patch_packed4();
+    if (!P) return PATCH_ERR_ALLOC;
+    P->N = N; P->K = K; P->tile = tile;
+    P->Tn = (int)(N / tile); P->Tk = (int)(K / tile);
+    const size_t T = (size_t)P->Tn * (size_t)P->Tk;
+    std::vector<uint32_t> table;
+    try { table.resize(T); } catch (...) { delete P; return PATCH_ERR_ALLOC; }
+    uint64_t off = 0;
+    for (size_t i = 0; i < T; ++i) {
+        const bool sparse = tile_map[i] == 0;
+        table[i] = make_entry(off, sparse);
+        off += sparse ? q4_sparse_tile(tile) : q4_dense_tile(tile);
+        P->algorithmic_bytes += sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) + 2 * tile : q4_dense_codes(tile) + 2 * tile;
+        if (sparse) ++P->n_sparse;
+    }
+    P->payload_bytes = off;
+    if ((off / kGranule) >> 31) { delete P; return PATCH_ERR_SHAPE; }
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        patch_note_hip_error((int)hipGetLastError());
+        delete P;
+        return PATCH_ERR_HIP;
+    }
+    P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    int* d_err = nullptr;
+    const bool ok = hipMalloc(&P->d_payload, P->payload_bytes) == hipSuccess && hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
+                    hipMalloc(&d_err, sizeof(int)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (d_err) (void)hipFree(d_err);
+        patch_free4(P);
+        return PATCH_ERR_ALLOC;
+    }
+    hipError_t e = hipMemcpyAsync(P->d_table, table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
+    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload, 0, P->payload_bytes, s);   // alignment padding reads as zero
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(pack4_kernel, dim3((unsigned)T), dim3(256), 0, s, static_cast<const uint16_t*>(W_hat), K, P->d_table, P->Tk, tile,
+                           P->d_payload, d_err);
+        e = hipGetLastError();
+    }
+    int h_err = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);   // also keeps the host table alive until the copy is done
+    (void)hipFree(d_err);
+    if (e != hipSuccess) {
+        patch_note_hip_error((int)e);
+        patch_free4(P);
+        return PATCH_ERR_HIP;
+    }
+    if (h_err) {
+        patch_free4(P);
+        return PATCH_ERR_NOT_24;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream) {
+    if (!P || (!W_deq && !codes && !scales)) return PATCH_ERR_ARG;
+    if ((W_deq && !q4_aligned16(W_deq)) || (scales && (reinterpret_cast<uintptr_t>(scales) & 1u))) return PATCH_ERR_ARG;
+    hipLaunchKernelGGL(unpack4_kernel, dim3((unsigned)(P->Tn * P->Tk)), dim3(256), 0, static_cast<hipStream_t>(stream), P->d_payload, P->d_table,
+                       P->Tk, P->tile, P->K, static_cast<uint16_t*>(W_deq), static_cast<int8_t*>(codes), static_cast<uint16_t*>(scales));
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
+    return PATCH_OK;
+}
+
+patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream) {
+    if (!X || !P || !Y || M < 0) return PATCH_ERR_ARG;
+    if (!q4_aligned16(X) || !q4_aligned16(Y)) return PATCH_ERR_ARG;
+    if (M == 0) return PATCH_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int total = P->Tk * (P->tile / kStepCols);
+    // wavefronts per workgroup: about 8 steps each, enough workgroups x wavefronts to fill the chip, at most 16
+    int kw = (total + 7) / 8;
+    if (kw > 16) kw = 16;
+    if (kw < 1) kw = 1;
+    const dim3 grid((unsigned)(P->N / 16)), block((unsigned)(kw * 64));
+    for (int64_t m0 = 0; m0 < M; m0 += 16) {
+        const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
+        if (P->tile == 128)
+            hipLaunchKernelGGL(decode4_kernel<128>, grid, block, 0, s, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload,
+                               P->d_table, static_cast<float*>(Y), P->N);
+        else
+            hipLaunchKernelGGL(decode4_kernel<64>, grid, block, 0, s, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload,
+                               P->d_table, static_cast<float*>(Y), P->N);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
+    return PATCH_OK;
+}
+
+size_t patch_packed4_bytes(const patch_packed4* P) { return P ? P->algorithmic_bytes : 0; }
+
+patch_status patch_packed4_dims(const patch_packed4* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles) {
+    if (!P) return PATCH_ERR_ARG;
+    if (N) *N = P->N;
+    if (K) *K = P->K;
+    if (tile) *tile = P->tile;
+    if (n_sparse_tiles) *n_sparse_tiles = P->n_sparse;
+    return PATCH_OK;
+}
+
+}  // extern "C"

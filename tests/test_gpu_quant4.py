@@ -1,0 +1,151 @@
+"""GPU parity of the 4-bit weight-only storage (Section 5.2, "Quantization") through the C ABI against the oracle.
+Codes, scales and the dequantized weight: bit-exact (the rounding decisions are taken in fp32 on both sides: a correctly
+rounded division, a rounding to the nearest integer with ties to even, one rounding of the exact product to bf16).
+Product: against the fp64 oracle product of the oracle's own dequantized weight, with the same relative and
+element-wise bars as the bf16 path (the matrix instructions and the accumulation are the same)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2509_23410_amd import binding as B, synth
+from test_gpu_parity import bits_of, check_elements, row_norms, stream, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    B.lib()
+    return torch.device("cuda:0")
+
+
+class Prepared4:
+    def __init__(self, c, dev, W_hat_o=None):
+        self.c, self.dev = c, dev
+        self.W_hat_o = oracle.apply_mask(c.W, c.tile_map, c.mask24, c.tile) if W_hat_o is None else W_hat_o
+        self.codes_o, self.scales_o = oracle.quantize4(self.W_hat_o, c.tile)
+        self.W_deq_o = oracle.dequantize4(self.codes_o, self.scales_o, c.tile)
+        self.W_hat = to_dev_bf16(self.W_hat_o, dev)
+        self.P = B.patch_pack4(self.W_hat, c.N, c.K, c.tile_map, c.tile, stream())
+
+    def unpack(self):
+        c = self.c
+        W_deq = torch.full((c.N, c.K), float("nan"), device=self.dev, dtype=torch.bfloat16)
+        codes = torch.full((c.N, c.K), 99, device=self.dev, dtype=torch.int8)
+        scales = torch.full((c.N, c.K // c.tile), float("nan"), device=self.dev, dtype=torch.bfloat16)
+        B.patch_unpack4(self.P, W_deq, codes, scales, stream())
+        torch.cuda.synchronize()
+        return bits_of(W_deq), codes.cpu().numpy(), bits_of(scales)
+
+    def gemm(self, X_bits):
+        M = X_bits.shape[0]
+        X = to_dev_bf16(X_bits, self.dev)
+        Y = torch.full((M, self.c.N), float("nan"), device=self.dev, dtype=torch.float32)
+        B.patch_gemm4(X, M, self.P, Y, stream())
+        torch.cuda.synchronize()
+        return Y.cpu().numpy()
+
+    def oracle_gemm(self, X_bits):
+        c = self.c
+        vals, meta = oracle.pack(self.W_deq_o, c.tile_map, c.tile)
+        return oracle.gemm(X_bits, vals, meta, c.N, c.K, c.tile_map, c.tile)
+
+
+CASES = [
+    # name, N, K, tile, f, list of M
+    ("tiny", 512, 512, 64, 0.5, [1, 16]),
+    ("t64_odd", 192, 320, 64, 0.4, [3, 5, 40]),
+    ("t128_mixed", 384, 640, 128, 0.5, [1, 16, 33]),
+    ("qwen_896_f0", 896, 896, 128, 0.0, [1]),
+    ("qwen_896_f1", 896, 896, 128, 1.0, [7]),
+    ("qwen_up", 4864, 896, 128, 0.5, [1]),
+    ("qwen_down", 896, 4864, 128, 0.5, [1, 16]),
+]
+
+
+@pytest.mark.parametrize("name,N,K,t,f,Ms", CASES)
+def test_quantize_pack_unpack_and_product(dev, name, N, K, t, f, Ms):
+    print(f"case {name} N={N} K={K} tile={t} f={f}", flush=True)
+    c = synth.make_case(name, N, K, max(Ms), t, f, seed=21)
+    p = Prepared4(c, dev)
+    W_deq, codes, scales = p.unpack()
+    assert np.array_equal(scales, p.scales_o)
+    assert np.array_equal(codes, p.codes_o)
+    assert np.array_equal(W_deq, p.W_deq_o)
+    a, b, s = oracle.packed4_sizes(N, K, t, c.tile_map)
+    assert p.P.nbytes == a + b + s
+    ns = int((c.tile_map == 0).sum())
+    assert p.P.dims() == (N, K, t, ns)
+    wn = row_norms(p.W_deq_o)
+    for M in Ms:
+        print(f"  product M={M}", flush=True)
+        Xb = c.X[:M]
+        check_elements(p.gemm(Xb), p.oracle_gemm(Xb), row_norms(Xb), wn, K, f"4-bit {name} M={M}")
+    p.P.close()
+
+
+def test_special_rows_ties_and_rejection(dev):
+    """An all-zero row (scale 0, codes 0), a row whose largest weight is negative, weights at exact half steps
+    (ties go to the even code), and groups with fewer than two nonzeros in a 2:4 tile."""
+    N = K = 128
+    t = 64
+    rng = np.random.default_rng(5)
+    W = synth.f32_to_bf16_bits(rng.standard_normal((N, K)).astype(np.float32) * 0.02)
+    tm = np.array([[1, 0], [0, 1]], np.uint8)
+    m24 = np.zeros((N, K), np.uint8)
+    m24[:, 0::4] = 1
+    m24[:, 3::4] = 1
+    W_hat = oracle.apply_mask(W, tm, m24, t)
+    W_hat[3, :] = 0                                                  # whole row zero (both tiles)
+    W_hat[5, :64] = synth.f32_to_bf16_bits(np.full(64, -0.0, np.float32))   # negative zeros: scale 0
+    halves = np.zeros(64, np.float32)
+    halves[:29] = np.arange(-14, 15, dtype=np.float32) * 0.25       # scale exactly 0.5: every odd multiple is a tie
+    W_hat[9, :64] = synth.f32_to_bf16_bits(halves)
+    W_hat[70, 0:8] = synth.f32_to_bf16_bits(np.array([3.5, 0, 0, -1.75, 0, 0, 0, 0.25], np.float32))   # sparse tile, thin groups
+    W_hat[70, 8:64] = 0
+    X = synth.f32_to_bf16_bits(rng.standard_normal((8, K)).astype(np.float32))
+    c = synth.Case("special", N, K, 8, t, 0.5, 5, X, W, tm, m24)
+    p = Prepared4(c, dev, W_hat_o=W_hat)
+    W_deq, codes, scales = p.unpack()
+    assert np.array_equal(scales, p.scales_o) and np.array_equal(codes, p.codes_o) and np.array_equal(W_deq, p.W_deq_o)
+    assert (scales[3] == 0).all() and (codes[3] == 0).all() and scales[5, 0] == 0
+    assert scales[9, 0] == 0x3F00 and list(codes[9, :5]) == [-7, -6, -6, -6, -5]       # -7, -6.5, -6, -5.5, -5
+    check_elements(p.gemm(c.X), p.oracle_gemm(c.X), row_norms(c.X), row_norms(p.W_deq_o), K, "4-bit special")
+    p.P.close()
+    with pytest.raises(B.PatchError) as e:
+        B.patch_pack4(to_dev_bf16(W, dev), N, K, tm, t, stream())    # unmasked weights in a 2:4 tile
+    assert e.value.status == B.ERR_NOT_24
+    for bad_N, bad_t, bad_tm in ((100, t, tm), (N, 32, np.ones((4, 4), np.uint8))):
+        with pytest.raises(B.PatchError) as e:
+            B.patch_pack4(to_dev_bf16(W, dev), bad_N, K, bad_tm, bad_t, stream())
+        assert e.value.status == B.ERR_SHAPE
+
+
+def test_full_size_decode_shape_sampled(dev):
+    """4096 x 4096, half the tiles 2:4, tile 128, M = 1 and 16: storage bit-exact on sampled rows, the product on sampled outputs."""
+    N = K = 4096
+    t = 128
+    c = synth.make_case("llama7b_attn_q4", N, K, 16, t, 0.5, seed=23)
+    W_hat_o = oracle.apply_mask(c.W, c.tile_map, c.mask24, t)
+    p = Prepared4(c, dev, W_hat_o=W_hat_o)
+    W_deq, codes, scales = p.unpack()
+    assert np.array_equal(scales, p.scales_o) and np.array_equal(codes, p.codes_o) and np.array_equal(W_deq, p.W_deq_o)
+    a, b, s = oracle.packed4_sizes(N, K, t, c.tile_map)
+    assert p.P.nbytes == a + b + s
+    rng = np.random.default_rng(9)
+    wn = row_norms(p.W_deq_o)
+    for M in (1, 16):
+        Xb = c.X[:M]
+        Y = p.gemm(Xb)
+        assert np.isfinite(Y).all()
+        mn = np.stack([rng.integers(0, M, 4096), rng.integers(0, N, 4096)], axis=1).astype(np.int64)
+        ref = oracle.gemm_points(Xb, p.W_deq_o, mn)
+        got = Y[mn[:, 0], mn[:, 1]].astype(np.float64)
+        bound = 2.0 * np.sqrt(K) * 2.0 ** -24 * row_norms(Xb)[mn[:, 0]] * wn[mn[:, 1]]
+        d = np.abs(got - ref)
+        print(f"  4-bit full size M={M}: max err/bound={float((d / bound).max()):.3f}", flush=True)
+        assert (d <= bound).all()
+        assert np.linalg.norm(got - ref) <= 2e-5 * np.linalg.norm(ref)
+    p.P.close()
