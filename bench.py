@@ -136,7 +136,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,qwen")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,qwen,q4")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -450,6 +450,39 @@ def main():
         out["decode_fused_qkv"] = dict(rows=fused, note="three 4096x4096 projections sharing X in one patch_gemm_many launch, rotating packed copies")
         out["decode"] = dict(workload="llama7b_attn_decode 4096x4096 tile128", peak_GBps=PEAK_HBM_GBS, rows=dec,
                              note="us = median of 5 batches of back-to-back launches over rotating packed copies (HBM-resident)")
+
+    # ------------------------------------------------------------------ decode from the 4-bit weight-only storage (Section 5.2)
+    if "q4" not in skip:
+        qrows = []
+        for name, N_, K_ in (("attn", 4096, 4096), ("gate", 11008, 4096), ("down", 4096, 11008)):
+            for fd in (0.0, 0.5):
+                cq = synth.make_case("llama7b_q4_" + name, N_, K_, 16, t, fd, seed=0)
+                W_hat, Pb = masked_packed(cq)
+                P4 = B.patch_pack4(W_hat, N_, K_, cq.tile_map, t, stream)
+                R4 = max(2, int(np.ceil(1.1e9 / P4.nbytes)))
+                Rb = max(2, int(np.ceil(1.1e9 / Pb.nbytes)))
+                P4s = [P4] + [B.patch_pack4(W_hat, N_, K_, cq.tile_map, t, stream) for _ in range(R4 - 1)]
+                Pbs = [Pb] + [B.patch_pack(W_hat, N_, K_, cq.tile_map, t, stream) for _ in range(Rb - 1)]
+                Xq = dev_bf16(cq.X)
+                Yq4 = torch.empty((16, N_), device=dev, dtype=torch.float32)
+                for Mq in (1, 16):
+                    f4 = lambda i, Mq=Mq: B.patch_gemm4(Xq, Mq, P4s[i % R4], Yq4, stream)
+                    fb = lambda i, Mq=Mq: B.patch_gemm(Xq, Mq, Pbs[i % Rb], Yq4, stream)
+                    nl = max(1, args.decode_launches // 2)
+                    timed(f4, 20)
+                    us4 = sorted(timed(f4, nl) / nl for _ in range(5))[2] * 1e6
+                    timed(fb, 20)
+                    usb = sorted(timed(fb, nl) / nl for _ in range(5))[2] * 1e6
+                    gbs = P4.nbytes / (us4 * 1e-6) / 1e9
+                    qrows.append(dict(shape=[N_, K_], f=fd, M=Mq, us=round(us4, 3), GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4),
+                                      packed_MB=round(P4.nbytes / 1e6, 3), copies=R4, us_bf16_storage=round(usb, 3),
+                                      speedup_vs_bf16_storage=round(usb / us4, 3),
+                                      bytes_vs_dense_bf16=round(P4.nbytes / (2.0 * N_ * K_), 4)))
+                for P_ in P4s + Pbs:
+                    P_.close()
+                del W_hat
+        out["decode_q4"] = dict(rows=qrows, note="patch_gemm4: 4-bit codes + bf16 scale per row of a tile (+ 2:4 positions), dequantized in "
+                                "registers; rotating packed copies (HBM-resident); us_bf16_storage = patch_gemm on the same pruned weight")
 
     # ------------------------------------------------------------------ measured ceilings (kernels of this library)
     if "ceilings" not in skip:

@@ -54,13 +54,18 @@ __device__ __forceinline__ uint32_t q4_code(uint16_t w_bits, float s) {
     return (uint32_t)((int)r) & 0xFu;
 }
 
-// 8 codes of a dword -> 8 bf16 values bf16(q s), element e from bits [4e+3 : 4e]
+// 8 codes of a dword -> 8 bf16 values bf16(q s), element e from bits [4e+3 : 4e].  q s is exact in fp32 (4 x 8 bits);
+// the conversion of a float pair to bf16 rounds to nearest, ties to even (v_cvt_pk_bf16_f32).
+typedef __bf16 q4_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float q4_f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ q4_u32x4 q4_dequant8(uint32_t codes, float s) {
     q4_u32x4 out;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int q0 = ((int)(codes << (28 - 8 * p))) >> 28, q1 = ((int)(codes << (24 - 8 * p))) >> 28;
-        out[p] = bf16_rne_bits((float)q0 * s) | (bf16_rne_bits((float)q1 * s) << 16);
+        const int q0 = __builtin_amdgcn_sbfe((int)codes, 8 * p, 4), q1 = __builtin_amdgcn_sbfe((int)codes, 8 * p + 4, 4);
+        const q4_f32x2 f = {(float)q0 * s, (float)q1 * s};
+        const q4_bf16x2 r = __builtin_convertvector(f, q4_bf16x2);
+        out[p] = *reinterpret_cast<const uint32_t*>(&r);
     }
     return out;
 }
@@ -207,60 +212,156 @@ __global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict_
     }
 }
 
-// Up to 16 rows of X against the 4-bit weight.  KW = blockDim.x / 64 wavefronts take contiguous runs of 64-column steps.
-template <int TILE>
+// Up to 16 rows of X against the 4-bit weight.  A workgroup owns R consecutive strips of 16 features; its KW =
+// blockDim.x / 64 wavefronts take contiguous runs of 64-column steps.  A wavefront loads the X operand of a step once
+// and uses it for all R strips (at 4 bits per weight X is the larger stream, so this reuse is what bounds the traffic),
+// works in batches of kQ4Batch steps - table entries, then every load of the batch, then the arithmetic - and issues
+// the next batch's loads before it consumes the current one.  Two batch buffers alternate; no copies.
+constexpr int kQ4Batch = 2;
+constexpr int kQ4MaxR = 3;
+
+template <int R>
+struct Q4Batch {
+    uint32_t e[kQ4Batch][R];
+    uint2 d[kQ4Batch][R];      // dense: both dwords; 2:4: x = codes, y = positions
+    uint32_t sc[kQ4Batch][R];  // scale bits
+    q4_u32x4 x[kQ4Batch][2];
+};
+
+template <int R>
+struct Q4Strips {
+    int64_t row0[R];   // first table entry of the strip's tile row
+    int s[R];          // strip within the tile
+};
+
+// Steps past the wavefront's run repeat its last step (in bounds; discarded by q4_compute).
+template <int TILE, int R>
+__device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, const uint32_t* __restrict__ table,
+                                         const uint8_t* __restrict__ payload, const uint16_t* xrow, bool xvalid, int lane, int step0, int last) {
+    constexpr int KPT = TILE / kStepCols;
+    const int col = lane & 15;
+#pragma unroll
+    for (int i = 0; i < kQ4Batch; ++i) {
+        const int step = step0 + i < last ? step0 + i : last;
+#pragma unroll
+        for (int r = 0; r < R; ++r) b.e[i][r] = __builtin_amdgcn_readfirstlane(table[st.row0[r] + step / KPT]);
+    }
+#pragma unroll
+    for (int i = 0; i < kQ4Batch; ++i) {
+        const int step = step0 + i < last ? step0 + i : last;
+        const int j = step % KPT;
+        b.x[i][0] = q4_u32x4{0u, 0u, 0u, 0u};
+        b.x[i][1] = q4_u32x4{0u, 0u, 0u, 0u};
+        if (xvalid) {
+            b.x[i][0] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols);
+            b.x[i][1] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint8_t* base = payload + entry_offset(b.e[i][r]);
+            const int s = st.s[r];
+            if (!entry_sparse(b.e[i][r])) {
+                b.sc[i][r] = *reinterpret_cast<const uint16_t*>(base + q4_dense_codes(TILE) + (16 * s + col) * 2);
+                b.d[i][r] = *reinterpret_cast<const uint2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
+            } else {
+                b.sc[i][r] = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + q4_sparse_pos(TILE) + (16 * s + col) * 2);
+                b.d[i][r].x = *reinterpret_cast<const uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
+                b.d[i][r].y = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
+            }
+        }
+    }
+}
+
+template <int R>
+__device__ __forceinline__ void q4_compute(const Q4Batch<R>& b, q4_f32x4 (&acc)[R], int step0, int end) {
+#pragma unroll
+    for (int i = 0; i < kQ4Batch; ++i) {
+        if (step0 + i >= end) break;   // uniform
+        Q4B x;
+        x.raw[0] = b.x[i][0];
+        x.raw[1] = b.x[i][1];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float scl = q4_bf16_to_float(b.sc[i][r]);
+            if (!entry_sparse(b.e[i][r])) {
+                Q4A a0, a1;
+                a0.raw = q4_dequant8(b.d[i][r].x, scl);
+                a1.raw = q4_dequant8(b.d[i][r].y, scl);
+                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, x.h[0], acc[r], 0, 0, 0);
+                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, x.h[1], acc[r], 0, 0, 0);
+            } else {
+                Q4A a;
+                a.raw = q4_dequant8(b.d[i][r].x, scl);
+                acc[r] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, x.v, acc[r], (int)b.d[i][r].y, 0, 0);
+            }
+        }
+    }
+}
+
+template <int TILE, int R>
 __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
                                                        const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
                                                        float* __restrict__ Y, int64_t N) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
-    __shared__ q4_f32x4 red[16][64];
+    __shared__ q4_f32x4 red[R][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), KW = blockDim.x >> 6;
-    const int strip = blockIdx.x, tn = strip / SPT, s = strip % SPT;
+    const int n_strips = (int)(N / kStripRows), strip0 = blockIdx.x * R;
     const int col = lane & 15, q = lane >> 4;
     const bool xvalid = col < rows;
     const int total = Tk * KPT, per = (total + KW - 1) / KW;
     const int begin = w * per, end = begin + per < total ? begin + per : total;
     const uint16_t* xrow = X + (m0 + (xvalid ? col : 0)) * K + 8 * q;
-    q4_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int step = begin; step < end; ++step) {
-        const int tk = step / KPT, j = step % KPT;
-        const uint32_t e = __builtin_amdgcn_readfirstlane(table[(int64_t)tn * Tk + tk]);
-        const uint8_t* base = payload + entry_offset(e);
-        Q4B b;
-        b.raw[0] = q4_u32x4{0u, 0u, 0u, 0u};
-        b.raw[1] = q4_u32x4{0u, 0u, 0u, 0u};
-        if (xvalid) {
-            b.raw[0] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols);
-            b.raw[1] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
-        }
-        if (!entry_sparse(e)) {
-            const float scl = q4_bf16_to_float(*reinterpret_cast<const uint16_t*>(base + q4_dense_codes(TILE) + (16 * s + col) * 2));
-            const uint2 d = *reinterpret_cast<const uint2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
-            Q4A a0, a1;
-            a0.raw = q4_dequant8(d.x, scl);
-            a1.raw = q4_dequant8(d.y, scl);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, b.h[0], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, b.h[1], acc, 0, 0, 0);
-        } else {
-            const float scl = q4_bf16_to_float(
-                *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + q4_sparse_pos(TILE) + (16 * s + col) * 2));
-            const uint32_t d = *reinterpret_cast<const uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
-            const uint32_t idx = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
-            Q4A a;
-            a.raw = q4_dequant8(d, scl);
-            acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b.v, acc, (int)idx, 0, 0);
+    Q4Strips<R> st;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int strip = strip0 + r < n_strips ? strip0 + r : n_strips - 1;   // a strip past the end repeats the last one (not stored)
+        st.row0[r] = (int64_t)(strip / SPT) * Tk;
+        st.s[r] = strip % SPT;
+    }
+    q4_f32x4 acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = q4_f32x4{0.f, 0.f, 0.f, 0.f};
+    if (begin < end) {
+        Q4Batch<R> b0, b1;
+        q4_loads<TILE, R>(b0, st, table, payload, xrow, xvalid, lane, begin, end - 1);
+        for (int step0 = begin; step0 < end; step0 += 2 * kQ4Batch) {
+            const bool have1 = step0 + kQ4Batch < end, have2 = step0 + 2 * kQ4Batch < end;   // uniform
+            if (have1) q4_loads<TILE, R>(b1, st, table, payload, xrow, xvalid, lane, step0 + kQ4Batch, end - 1);
+            q4_compute<R>(b0, acc, step0, end);
+            if (have2) q4_loads<TILE, R>(b0, st, table, payload, xrow, xvalid, lane, step0 + 2 * kQ4Batch, end - 1);
+            if (have1) q4_compute<R>(b1, acc, step0 + kQ4Batch, end);
         }
     }
-    red[w][lane] = acc;
+#pragma unroll
+    for (int r = 0; r < R; ++r) red[r][w][lane] = acc[r];
     __syncthreads();
-    if (w == 0) {
-        q4_f32x4 sum = red[0][lane];
+    // wavefront r adds up strip r in wavefront order (R <= the number of wavefronts is checked by the launcher)
+    if (w < R && strip0 + w < n_strips) {
+        q4_f32x4 sum = red[w][0][lane];
         for (int i = 1; i < KW; ++i) {
-            const q4_f32x4 v = red[i][lane];
+            const q4_f32x4 v = red[w][i][lane];
             sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
-        if (xvalid) *reinterpret_cast<q4_f32x4*>(Y + (m0 + col) * N + (int64_t)strip * 16 + 4 * q) = sum;
+        if (xvalid) *reinterpret_cast<q4_f32x4*>(Y + (m0 + col) * N + (int64_t)(strip0 + w) * 16 + 4 * q) = sum;
+    }
+}
+
+template <int TILE, int R>
+static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint32_t* table, float* Y,
+                           int64_t N, int kw, hipStream_t s) {
+    const int n_strips = (int)(N / kStripRows);
+    hipLaunchKernelGGL((decode4_kernel<TILE, R>), dim3((unsigned)((n_strips + R - 1) / R)), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk,
+                       payload, table, Y, N);
+}
+
+template <int TILE>
+static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint32_t* table,
+                             float* Y, int64_t N, int kw, hipStream_t s) {
+    switch (R) {
+        case 1: launch_decode4<TILE, 1>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
+        case 2: launch_decode4<TILE, 2>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
+        default: launch_decode4<TILE, 3>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
     }
 }
 
@@ -370,19 +471,23 @@ patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void*
     if (M == 0) return PATCH_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int total = P->Tk * (P->tile / kStepCols);
-    // wavefronts per workgroup: about 8 steps each, enough workgroups x wavefronts to fill the chip, at most 16
-    int kw = (total + 7) / 8;
+    // wavefronts per workgroup: about 4 steps each, at least one per strip, at most 16
+    int kw = (total + 3) / 4;
     if (kw > 16) kw = 16;
-    if (kw < 1) kw = 1;
-    const dim3 grid((unsigned)(P->N / 16)), block((unsigned)(kw * 64));
+    if (kw < kQ4MaxR) kw = kQ4MaxR;
+    // strips per workgroup: one workgroup per compute unit when the weight has more strips than that, at most 3
+    const int n_strips = (int)(P->N / kStripRows);
+    int R = (n_strips + P->n_cus - 1) / P->n_cus;
+    if (R > kQ4MaxR) R = kQ4MaxR;
+    if (R < 1) R = 1;
     for (int64_t m0 = 0; m0 < M; m0 += 16) {
         const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
         if (P->tile == 128)
-            hipLaunchKernelGGL(decode4_kernel<128>, grid, block, 0, s, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload,
-                               P->d_table, static_cast<float*>(Y), P->N);
+            launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_table, static_cast<float*>(Y),
+                                  P->N, kw, s);
         else
-            hipLaunchKernelGGL(decode4_kernel<64>, grid, block, 0, s, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload,
-                               P->d_table, static_cast<float*>(Y), P->N);
+            launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_table, static_cast<float*>(Y),
+                                 P->N, kw, s);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }

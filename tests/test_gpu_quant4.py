@@ -62,6 +62,9 @@ CASES = [
     ("qwen_896_f1", 896, 896, 128, 1.0, [7]),
     ("qwen_up", 4864, 896, 128, 0.5, [1]),
     ("qwen_down", 896, 4864, 128, 0.5, [1, 16]),
+    # more strips than compute units: several strips per workgroup, the last workgroup short of strips
+    ("wide_t128_three_strips", 8320, 256, 128, 0.5, [1, 16]),
+    ("wide_t64_three_strips", 8384, 192, 64, 0.5, [5]),
 ]
 
 
@@ -83,6 +86,21 @@ def test_quantize_pack_unpack_and_product(dev, name, N, K, t, f, Ms):
         print(f"  product M={M}", flush=True)
         Xb = c.X[:M]
         check_elements(p.gemm(Xb), p.oracle_gemm(Xb), row_norms(Xb), wn, K, f"4-bit {name} M={M}")
+    p.P.close()
+
+
+@pytest.mark.parametrize("t,f", [(64, 0.5), (128, 0.5), (128, 1.0)])
+def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
+    """X = identity: every output is one product with 1.0 plus zeros, so Y must equal the dequantized weight bit for
+    bit - the in-kernel dequantization (codes, signs, scale, rounding) checked element by element."""
+    N, K = 384, 512
+    c = synth.make_case("identity", N, K, 1, t, f, seed=22)
+    p = Prepared4(c, dev)
+    X = synth.f32_to_bf16_bits(np.eye(K, dtype=np.float32))
+    Y = p.gemm(X)                                        # K rows: K / 16 passes over the weight
+    want = synth.bf16_bits_to_f32(p.W_deq_o).T
+    assert np.array_equal(Y.view(np.uint32) & 0x7FFFFFFF, want.view(np.uint32) & 0x7FFFFFFF) or np.array_equal(Y, want)
+    assert np.array_equal(Y, want)                       # values (a zero's sign aside)
     p.P.close()
 
 
