@@ -9,11 +9,13 @@
 // Layout (tiles row-major, each on a 256-byte granule, table entry = offset / 256 << 1 | is 2:4, as for bf16):
 //   dense tile : code fragments in (strip, K-step) order, 512 B each: lane l holds two dwords, the 8 codes of
 //                W[row0 + l % 16][k0 + 8 (l / 16) + e] and those 32 columns further (the two operands of
-//                v_mfma_f32_16x16x32_bf16), code e in bits [4e+3 : 4e], two's complement;
-//                then the tile's `tile` scales (bf16, row order)
+//                v_mfma_f32_16x16x32_bf16), code e in bits [4e+3 : 4e], two's complement
 //   2:4 tile   : code fragments of 256 B: lane l holds the 8 kept codes of W[row0 + l % 16][k0 + 16 (l / 16) .. + 15]
 //                (the operand of v_smfmac_f32_16x16x64_bf16); then the positions, uint16 [strip][lane][K-step] as in the
-//                bf16 layout; then the scales
+//                bf16 layout
+//   scales     : an array of their own, bf16 [strip of 16 rows][tile column][row in strip]: the scales a strip needs
+//                along K are contiguous and no cache line is shared between strips (strips of one tile run in
+//                workgroups on different XCDs; inside the tile every line of scales was fetched by four L2s)
 // The product kernel dequantizes in registers (8 codes -> 8 bf16 with integer rounding) and then runs the same matrix
 // instructions as the bf16 decode kernel: one workgroup per strip of 16 features, its wavefronts split K, partial sums
 // meet in LDS in wavefront order (bit-reproducible).  It is the decode-shaped path only - up to 16 rows per pass over
@@ -42,8 +44,10 @@ __host__ __device__ constexpr int q4_dense_codes(int t) { return t * t / 2; }
 __host__ __device__ constexpr int q4_sparse_codes(int t) { return t * t / 4; }
 __host__ __device__ constexpr int q4_sparse_pos(int t) { return t * t / 8; }
 __host__ __device__ constexpr int q4_round_up(int b) { return (b + kGranule - 1) / kGranule * kGranule; }
-__host__ __device__ constexpr int q4_dense_tile(int t) { return q4_round_up(q4_dense_codes(t) + 2 * t); }
-__host__ __device__ constexpr int q4_sparse_tile(int t) { return q4_round_up(q4_sparse_codes(t) + q4_sparse_pos(t) + 2 * t); }
+__host__ __device__ constexpr int q4_dense_tile(int t) { return q4_round_up(q4_dense_codes(t)); }
+__host__ __device__ constexpr int q4_sparse_tile(int t) { return q4_round_up(q4_sparse_codes(t) + q4_sparse_pos(t)); }
+// scale of row r (0..15) of strip `strip` (over the whole matrix) for tile column tk
+__host__ __device__ constexpr int64_t q4_scale_index(int64_t strip, int Tk, int tk, int r) { return (strip * Tk + tk) * 16 + r; }
 
 __device__ __forceinline__ float q4_bf16_to_float(uint32_t bits) { return __uint_as_float(bits << 16); }
 
@@ -74,7 +78,8 @@ __device__ __forceinline__ bool q4_nonzero(uint16_t h) { return (h & 0x7FFFu) !=
 
 // One workgroup per tile: scales, then codes (and, for a 2:4 tile, the kept positions of the unquantized weights).
 __global__ __launch_bounds__(256) void pack4_kernel(const uint16_t* __restrict__ W, int64_t K, const uint32_t* __restrict__ table, int Tk,
-                                                    int tile, uint8_t* __restrict__ payload, int* __restrict__ err) {
+                                                    int tile, uint8_t* __restrict__ payload, uint16_t* __restrict__ scales,
+                                                    int* __restrict__ err) {
     __shared__ float sc[128];
     const int t = blockIdx.x;
     const int tn = t / Tk, tk = t % Tk;
@@ -82,8 +87,7 @@ __global__ __launch_bounds__(256) void pack4_kernel(const uint16_t* __restrict__
     const bool sparse = entry_sparse(e);
     uint8_t* base = payload + entry_offset(e);
     const int64_t n0 = (int64_t)tn * tile, k0 = (int64_t)tk * tile;
-    const int KPT = tile / kStepCols;
-    uint16_t* scales = reinterpret_cast<uint16_t*>(base + (sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) : q4_dense_codes(tile)));
+    const int KPT = tile / kStepCols, SPT = tile / kStripRows;
     for (int r = threadIdx.x; r < tile; r += blockDim.x) {
         const uint16_t* row = W + (n0 + r) * K + k0;
         uint32_t amax = 0;   // |w| compares like its bit pattern
@@ -94,7 +98,7 @@ __global__ __launch_bounds__(256) void pack4_kernel(const uint16_t* __restrict__
             for (int i = 0; i < 8; ++i) { const uint32_t a = in.h[i] & 0x7FFFu; amax = a > amax ? a : amax; }
         }
         const uint32_t sb = bf16_rne_bits(__fdiv_rn(q4_bf16_to_float(amax), 7.0f));
-        scales[r] = (uint16_t)sb;
+        scales[q4_scale_index((int64_t)tn * SPT + r / 16, Tk, tk, r % 16)] = (uint16_t)sb;
         sc[r] = q4_bf16_to_float(sb);
     }
     __syncthreads();
@@ -157,8 +161,9 @@ __global__ __launch_bounds__(256) void pack4_kernel(const uint16_t* __restrict__
 }
 
 // The inverse: the dequantized bf16 matrix and / or the codes (int8, 0 at dropped positions) and scales in matrix order.
-__global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table, int Tk, int tile,
-                                                      int64_t K, uint16_t* __restrict__ W_deq, int8_t* __restrict__ codes_out,
+__global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
+                                                      const uint32_t* __restrict__ table, int Tk, int tile, int64_t K,
+                                                      uint16_t* __restrict__ W_deq, int8_t* __restrict__ codes_out,
                                                       uint16_t* __restrict__ scales_out) {
     const int t = blockIdx.x;
     const int tn = t / Tk, tk = t % Tk;
@@ -166,16 +171,16 @@ __global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict_
     const bool sparse = entry_sparse(e);
     const uint8_t* base = payload + entry_offset(e);
     const int64_t n0 = (int64_t)tn * tile, k0 = (int64_t)tk * tile;
-    const int KPT = tile / kStepCols;
-    const uint16_t* scales = reinterpret_cast<const uint16_t*>(base + (sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) : q4_dense_codes(tile)));
+    const int KPT = tile / kStepCols, SPT = tile / kStripRows;
     if (scales_out)
-        for (int r = threadIdx.x; r < tile; r += blockDim.x) scales_out[(n0 + r) * Tk + tk] = scales[r];
+        for (int r = threadIdx.x; r < tile; r += blockDim.x)
+            scales_out[(n0 + r) * Tk + tk] = scales[q4_scale_index((int64_t)tn * SPT + r / 16, Tk, tk, r % 16)];
     const int nchunks = tile * tile / 16;
     const uint16_t* meta = reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(tile));
     for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
         const int lane = c & 63, sj = c >> 6;
         const int j = sj % KPT, s = sj / KPT, i = lane & 15, q = lane >> 4;
-        const float scl = q4_bf16_to_float(scales[16 * s + i]);
+        const float scl = q4_bf16_to_float(scales[q4_scale_index((int64_t)tn * SPT + s, Tk, tk, i)]);
         int qv[16];
         int64_t kk[16];
         if (!sparse) {
@@ -230,8 +235,9 @@ struct Q4Batch {
 
 template <int R>
 struct Q4Strips {
-    int64_t row0[R];   // first table entry of the strip's tile row
-    int s[R];          // strip within the tile
+    int64_t row0[R];          // first table entry of the strip's tile row
+    int s[R];                 // strip within the tile
+    const uint16_t* scl[R];   // this lane's scale of the strip for tile column 0 (the next column is 16 scales on)
 };
 
 // Steps past the wavefront's run repeat its last step (in bounds; discarded by q4_compute).
@@ -239,7 +245,6 @@ template <int TILE, int R>
 __device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, const uint32_t* __restrict__ table,
                                          const uint8_t* __restrict__ payload, const uint16_t* xrow, bool xvalid, int lane, int step0, int last) {
     constexpr int KPT = TILE / kStepCols;
-    const int col = lane & 15;
 #pragma unroll
     for (int i = 0; i < kQ4Batch; ++i) {
         const int step = step0 + i < last ? step0 + i : last;
@@ -260,11 +265,10 @@ __device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, c
         for (int r = 0; r < R; ++r) {
             const uint8_t* base = payload + entry_offset(b.e[i][r]);
             const int s = st.s[r];
+            b.sc[i][r] = st.scl[r][(step / KPT) * 16];
             if (!entry_sparse(b.e[i][r])) {
-                b.sc[i][r] = *reinterpret_cast<const uint16_t*>(base + q4_dense_codes(TILE) + (16 * s + col) * 2);
                 b.d[i][r] = *reinterpret_cast<const uint2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
             } else {
-                b.sc[i][r] = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + q4_sparse_pos(TILE) + (16 * s + col) * 2);
                 b.d[i][r].x = *reinterpret_cast<const uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
                 b.d[i][r].y = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
             }
@@ -300,8 +304,8 @@ __device__ __forceinline__ void q4_compute(const Q4Batch<R>& b, q4_f32x4 (&acc)[
 
 template <int TILE, int R>
 __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
-                                                       const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                       float* __restrict__ Y, int64_t N) {
+                                                       const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
+                                                       const uint32_t* __restrict__ table, float* __restrict__ Y, int64_t N) {
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
     __shared__ q4_f32x4 red[R][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -318,6 +322,7 @@ __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restric
         const int strip = strip0 + r < n_strips ? strip0 + r : n_strips - 1;   // a strip past the end repeats the last one (not stored)
         st.row0[r] = (int64_t)(strip / SPT) * Tk;
         st.s[r] = strip % SPT;
+        st.scl[r] = scales + q4_scale_index(strip, Tk, 0, col);
     }
     q4_f32x4 acc[R];
 #pragma unroll
@@ -348,20 +353,20 @@ __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restric
 }
 
 template <int TILE, int R>
-static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint32_t* table, float* Y,
-                           int64_t N, int kw, hipStream_t s) {
+static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint16_t* scales,
+                           const uint32_t* table, float* Y, int64_t N, int kw, hipStream_t s) {
     const int n_strips = (int)(N / kStripRows);
     hipLaunchKernelGGL((decode4_kernel<TILE, R>), dim3((unsigned)((n_strips + R - 1) / R)), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk,
-                       payload, table, Y, N);
+                       payload, scales, table, Y, N);
 }
 
 template <int TILE>
-static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint32_t* table,
-                             float* Y, int64_t N, int kw, hipStream_t s) {
+static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint16_t* scales,
+                             const uint32_t* table, float* Y, int64_t N, int kw, hipStream_t s) {
     switch (R) {
-        case 1: launch_decode4<TILE, 1>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
-        case 2: launch_decode4<TILE, 2>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
-        default: launch_decode4<TILE, 3>(X, m0, rows, K, Tk, payload, table, Y, N, kw, s); break;
+        case 1: launch_decode4<TILE, 1>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
+        case 2: launch_decode4<TILE, 2>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
+        default: launch_decode4<TILE, 3>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
     }
 }
 
@@ -375,7 +380,8 @@ struct patch_packed4 {
     int64_t n_sparse = 0;
     size_t algorithmic_bytes = 0;   // codes + positions + scales, without alignment padding
     size_t payload_bytes = 0;
-    uint8_t* d_payload = nullptr;
+    uint8_t* d_payload = nullptr;   // codes and positions
+    uint16_t* d_scales = nullptr;   // N x Tk bf16, strip-major
     uint32_t* d_table = nullptr;
     int n_cus = 256;
 };
@@ -387,6 +393,7 @@ extern "C" {
 void patch_free4(patch_packed4* P) {
     if (!P) return;
     if (P->d_payload) (void)hipFree(P->d_payload);
+    if (P->d_scales) (void)hipFree(P->d_scales);
     if (P->d_table) (void)hipFree(P->d_table);
     delete P;
 }
@@ -423,7 +430,7 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
     P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     int* d_err = nullptr;
     const bool ok = hipMalloc(&P->d_payload, P->payload_bytes) == hipSuccess && hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
-                    hipMalloc(&d_err, sizeof(int)) == hipSuccess;
+                    hipMalloc(&P->d_scales, (size_t)N * P->Tk * sizeof(uint16_t)) == hipSuccess && hipMalloc(&d_err, sizeof(int)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         if (d_err) (void)hipFree(d_err);
@@ -435,7 +442,7 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
     if (e == hipSuccess) e = hipMemsetAsync(P->d_payload, 0, P->payload_bytes, s);   // alignment padding reads as zero
     if (e == hipSuccess) {
         hipLaunchKernelGGL(pack4_kernel, dim3((unsigned)T), dim3(256), 0, s, static_cast<const uint16_t*>(W_hat), K, P->d_table, P->Tk, tile,
-                           P->d_payload, d_err);
+                           P->d_payload, P->d_scales, d_err);
         e = hipGetLastError();
     }
     int h_err = 0;
@@ -458,8 +465,8 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
 patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream) {
     if (!P || (!W_deq && !codes && !scales)) return PATCH_ERR_ARG;
     if ((W_deq && !q4_aligned16(W_deq)) || (scales && (reinterpret_cast<uintptr_t>(scales) & 1u))) return PATCH_ERR_ARG;
-    hipLaunchKernelGGL(unpack4_kernel, dim3((unsigned)(P->Tn * P->Tk)), dim3(256), 0, static_cast<hipStream_t>(stream), P->d_payload, P->d_table,
-                       P->Tk, P->tile, P->K, static_cast<uint16_t*>(W_deq), static_cast<int8_t*>(codes), static_cast<uint16_t*>(scales));
+    hipLaunchKernelGGL(unpack4_kernel, dim3((unsigned)(P->Tn * P->Tk)), dim3(256), 0, static_cast<hipStream_t>(stream), P->d_payload, P->d_scales,
+                       P->d_table, P->Tk, P->tile, P->K, static_cast<uint16_t*>(W_deq), static_cast<int8_t*>(codes), static_cast<uint16_t*>(scales));
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
     return PATCH_OK;
@@ -483,11 +490,11 @@ patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void*
     for (int64_t m0 = 0; m0 < M; m0 += 16) {
         const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
         if (P->tile == 128)
-            launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_table, static_cast<float*>(Y),
-                                  P->N, kw, s);
+            launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_scales, P->d_table,
+                                  static_cast<float*>(Y), P->N, kw, s);
         else
-            launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_table, static_cast<float*>(Y),
-                                 P->N, kw, s);
+            launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_scales, P->d_table,
+                                 static_cast<float*>(Y), P->N, kw, s);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
