@@ -63,7 +63,24 @@ def test_argument_errors_without_device():
     assert L.patch_gemm_static(fake, 1, 0, fake, 0) == B.ERR_ARG
     assert L.patch_probe_matrix_rate(2, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
     assert L.patch_probe_stream_read(fake, 1024, 1, 100, fake, 1 << 20, 0) == B.ERR_ARG
+    # 4-bit storage
+    assert L.patch_pack4(0, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack4(fake, 128, 128, 0, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack4(fake, 128, 128, tm.ctypes.data, 64, 0, None) == B.ERR_ARG
+    assert L.patch_pack4(fake, 128, 128, tm.ctypes.data, 32, 0, ctypes.byref(out)) == B.ERR_SHAPE
+    assert L.patch_pack4(fake, 128, 100, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_SHAPE
+    assert L.patch_pack4(fake + 2, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG  # misaligned
+    assert out.value is None
+    assert L.patch_gemm4(fake, 1, 0, fake, 0) == B.ERR_ARG
+    assert L.patch_gemm4(0, 1, fake, fake, 0) == B.ERR_ARG
+    assert L.patch_gemm4(fake, -1, fake, fake, 0) == B.ERR_ARG
+    assert L.patch_unpack4(0, fake, None, None, 0) == B.ERR_ARG
+    assert L.patch_packed4_bytes(0) == 0
+    assert L.patch_packed4_dims(0, None, None, None, None) == B.ERR_ARG
+    L.patch_free4(0)
     L.patch_free(0)
+    with pytest.raises(B.PatchError):
+        B.patch_pack4(fake, 128, 128, np.ones(3, np.uint8), 64)
     with pytest.raises(B.PatchError):
         B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)
 
