@@ -57,16 +57,19 @@ def _keep_top2(torch, W):
     return keep
 
 
-def stack_13b(torch, B, synth, dev, stream, timed, t):
+def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 512, 4096)):
     """The 13B decoder stack: 40 layers x {q, k, v, o 5120 x 5120; gate, up 13824 x 5120; down 5120 x 13824}, one 2:4
-    tile fraction per layer drawn U[0, 1), every GEMM with its own X, M in {1, 512, 4096}; time = sum over the layers.
+    tile fraction per layer drawn U[0, 1) - or, with per_matrix, the fractions of synth.matrix_fractions (key / value
+    dense, MLP heavy, middle blocks heavy; global target 0.5) - every GEMM with its own X; time = sum over the layers.
     A layer runs as four launches (q / k / v share X, gate / up share X).  Weights are packed layer by layer and freed;
     they are drawn on the device (N(0, 0.02^2), magnitude 2:4 mask) - the parity tests cover these shapes with the
     host-drawn inputs.  Every layer is also run with an all-dense map of the same weights."""
     H, F = 5120, 13824
     shapes = [("q", H, H), ("k", H, H), ("v", H, H), ("o", H, H), ("gate", F, H), ("up", F, H), ("down", H, F)]
-    fr = synth.layer_fractions(0, 40)
-    Ms = (1, 512, 4096)
+    if per_matrix:
+        fr = synth.matrix_fractions(40, [N_ * K_ for _, N_, K_ in shapes], 0.5)
+    else:
+        fr = np.repeat(synth.layer_fractions(0, 40)[:, None], len(shapes), axis=1)
     gen = torch.Generator(device=dev)
     gen.manual_seed(13)
     xH = torch.randn(4096, H, device=dev, generator=gen).to(torch.bfloat16)
@@ -84,9 +87,9 @@ def stack_13b(torch, B, synth, dev, stream, timed, t):
         B.patch_gemm(xF, M_, L["down"], y["down"], stream, workspace=ws)
 
     for li in range(40):
-        f = float(fr[li])
         layer, dense = {}, {}
-        for name, N_, K_ in shapes:
+        for mi, (name, N_, K_) in enumerate(shapes):
+            f = float(fr[li, mi])
             W = (torch.randn(N_, K_, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
             keep = _keep_top2(torch, W)
             tm = synth.tile_map(li, N_ // t, K_ // t, f, "stack13b", name)
@@ -97,7 +100,7 @@ def stack_13b(torch, B, synth, dev, stream, timed, t):
             packed_bytes += layer[name].nbytes
             dense_bytes += dense[name].nbytes
             del W, keep, W_hat
-        row = dict(layer=li, f=round(f, 3))
+        row = dict(layer=li, f=[round(float(v), 3) for v in fr[li]] if per_matrix else round(float(fr[li, 0]), 3))
         for M_ in Ms:
             reps = 10 if M_ == 1 else 4 if M_ == 512 else 2
             for key, L in (("mix", layer), ("dense", dense)):
@@ -110,11 +113,12 @@ def stack_13b(torch, B, synth, dev, stream, timed, t):
             for P_ in L.values():
                 P_.close()
     layer_flop = sum(2.0 * N_ * K_ for _, N_, K_ in shapes)            # per row of X
-    f_mean = float(np.mean(fr))
+    mat_flop = np.array([2.0 * N_ * K_ for _, N_, K_ in shapes])
+    f_mean = float((fr * mat_flop[None, :]).sum() / (mat_flop.sum() * 40))   # parameter-weighted
     rows = []
     for M_ in Ms:
         secs = tot[M_]["mix"]
-        issued = sum(layer_flop * M_ * (2.0 - float(f)) / 2.0 for f in fr)
+        issued = float((mat_flop[None, :] * M_ * (2.0 - fr) / 2.0).sum())
         r_ = dict(M=M_, ms_total=round(secs * 1e3, 3), ms_total_all_dense=round(tot[M_]["dense"] * 1e3, 3),
                   speedup_vs_all_dense=round(tot[M_]["dense"] / secs, 4),
                   dense_equiv_TFLOPs=round(40 * layer_flop * M_ / secs / 1e12, 1),
@@ -122,7 +126,8 @@ def stack_13b(torch, B, synth, dev, stream, timed, t):
                   GBps_compressed=round(packed_bytes / secs / 1e9, 1), frac_hbm_peak=round(packed_bytes / secs / 1e9 / PEAK_HBM_GBS, 4))
         rows.append(r_)
     return dict(layers=40, launches_per_layer=4, packed_GB=round(packed_bytes / 1e9, 3), dense_GB=round(dense_bytes / 1e9, 3),
-                f_mean=round(f_mean, 4), rows=rows, per_layer=per_layer,
+                f_mean=round(f_mean, 4), fractions="per (layer, matrix): synth.matrix_fractions" if per_matrix else "one per layer, U[0, 1)",
+                rows=rows, per_layer=per_layer,
                 note="time = sum over the 40 layers of the layer's four launches (q/k/v fused, o, gate/up fused, down), each layer "
                      "timed on its own after two warm-up passes with a caller workspace; frac_mfma_peak = issued matrix flops "
                      "(flop-weighted over the layers' fractions) / time / 2.5 PFLOP/s, the bound at M = 4096; frac_hbm_peak = "
@@ -136,7 +141,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,qwen,q4")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -578,6 +583,8 @@ def main():
     # ------------------------------------------------------------------ 13B decoder stack
     if "stack" not in skip:
         out["stack_13b"] = stack_13b(torch, B, synth, dev, stream, timed, t)
+        if "alloc" not in skip:
+            out["stack_13b_per_matrix"] = stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=True)
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None

@@ -143,3 +143,27 @@ def mask_logits(seed: int, N: int, K: int, tile: int, *tags):
 def layer_fractions(seed: int, n_layers: int = 40) -> np.ndarray:
     """One 2:4-tile fraction per decoder layer, U[0, 1) (non-uniform allocation across layers)."""
     return _rng(seed, "layer_fractions", n_layers).random(n_layers)
+
+
+MATRICES = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+def matrix_fractions(n_layers: int, params, target: float = 0.5) -> np.ndarray:
+    """2:4-tile fraction per (decoder layer, matrix), shape (n_layers, 7) in the order of MATRICES: a stand-in for the
+    allocation the paper reports for a global sparsity target (Section 5, "Sparsity allocation", and the appendix with
+    the per-matrix distributions; the figures' values are not reproduced, only their ordering): over depth the middle
+    blocks take most of the sparsity, the first blocks less and the deepest blocks least; inside a block key and
+    value stay dense, the output projection is pruned moderately, the query projection the most of the attention
+    matrices, and gate / up / down take the bulk.  `params` = weights per matrix in the same order; the fractions are
+    scaled so that their parameter-weighted mean is `target` (clipped to [0, 1])."""
+    x = (np.arange(n_layers) + 0.5) / n_layers
+    depth = np.sin(np.pi * x) * (1.0 - 0.5 * x)
+    share = np.array([0.8, 0.0, 0.0, 0.4, 1.2, 1.2, 1.2])
+    raw = depth[:, None] * share[None, :]
+    w = np.asarray(params, dtype=np.float64)[None, :]
+    lo, hi = 0.0, 64.0
+    for _ in range(80):                     # bisection on the scale: the clipped mean is monotone in it
+        c = 0.5 * (lo + hi)
+        mean = float((np.clip(c * raw, 0.0, 1.0) * w).sum() / (w.sum() * n_layers))
+        lo, hi = (c, hi) if mean < target else (lo, c)
+    return np.clip(0.5 * (lo + hi) * raw, 0.0, 1.0)

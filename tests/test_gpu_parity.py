@@ -402,6 +402,32 @@ def test_13b_layer_shapes_prefill_4096(dev, li, N, K):
     p.P.close()
 
 
+def test_13b_fused_qkv_with_per_matrix_fractions(dev):
+    """The allocation the paper reports inside a block (Section 5, "Sparsity allocation": key / value dense, query
+    pruned the most of the attention matrices) on the 13B attention shapes: q / k / v of a middle layer with the
+    fractions of synth.matrix_fractions, sharing X in one launch per pass, at M = 1, 16 and 512."""
+    H, F = 5120, 13824
+    fr = synth.matrix_fractions(40, [H * H] * 4 + [F * H] * 3, 0.5)[15]
+    assert fr[0] > 0.5 and fr[1] == 0 and fr[2] == 0
+    cases = [synth.make_case(f"alloc_{n}", H, H, 512, 128, float(fr[i]), seed=31) for i, n in enumerate(("q", "k", "v"))]
+    X = cases[0].X
+    preps = [Prepared(c, dev) for c in cases]
+    Xd = to_dev_bf16(X, dev)
+    ws = torch.empty(8 * 512 * H, device=dev, dtype=torch.float32)
+    rng = np.random.default_rng(15)
+    for M, kw in ((1, dict()), (16, dict()), (512, dict()), (512, dict(workspace=ws))):
+        print(f"13B q/k/v fused f={[round(float(v), 2) for v in fr[:3]]} M={M} workspace={'workspace' in kw}", flush=True)
+        if "workspace" in kw:
+            ws.fill_(float("nan"))
+        Ys = [torch.full((M, H), float("nan"), device=dev, dtype=torch.float32) for _ in cases]
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), **kw)
+        torch.cuda.synchronize()
+        for p, c, Y in zip(preps, cases, Ys):
+            _sampled_checks(p, c, X[:M], Y.cpu().numpy(), rng, n_points=1024, n_rows=8, what=f"13B fused {c.name} M={M}")
+    for p in preps:
+        p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
