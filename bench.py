@@ -486,6 +486,51 @@ def main():
                 for P_ in P4s + Pbs:
                     P_.close()
                 del W_hat
+        # one 7B decoder layer from the 4-bit storage at M = 1: q/k/v fused, o, gate/up fused, down (4 launches), rotating
+        # over copies of the layer; beside it the single launches of the same seven weights
+        q4layer = []
+        for fd in (0.0, 0.5):
+            shapes7 = [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o", 4096, 4096),
+                       ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
+            copies, nbytes = 12, 0
+            layer = [dict() for _ in range(copies)]
+            for name, N_, K_ in shapes7:
+                cl = synth.make_case("llama7b_layer_" + name, N_, K_, 1, t, fd, seed=0)
+                W_hat, P0 = masked_packed(cl)
+                P0.close()
+                for ci in range(copies):
+                    layer[ci][name] = B.patch_pack4(W_hat, N_, K_, cl.tile_map, t, stream)
+                nbytes += layer[0][name].nbytes
+                del W_hat
+            x4 = dev_bf16(synth.make_case("llama7b_layer_x", 128, 4096, 1, t, 0.0, seed=1).X)
+            x11 = dev_bf16(synth.make_case("llama7b_layer_x2", 128, 11008, 1, t, 0.0, seed=2).X)
+            y = {n: torch.empty((1, N_), device=dev, dtype=torch.float32) for n, N_, _ in shapes7}
+
+            def layer4(L):
+                B.patch_gemm4_many(x4, 1, [L["q"], L["k"], L["v"]], [y["q"], y["k"], y["v"]], stream)
+                B.patch_gemm4(x4, 1, L["o"], y["o"], stream)
+                B.patch_gemm4_many(x4, 1, [L["gate"], L["up"]], [y["gate"], y["up"]], stream)
+                B.patch_gemm4(x11, 1, L["down"], y["down"], stream)
+
+            def layer4_single(L):
+                for n in ("q", "k", "v", "o", "gate", "up"):
+                    B.patch_gemm4(x4, 1, L[n], y[n], stream)
+                B.patch_gemm4(x11, 1, L["down"], y["down"], stream)
+
+            res = {}
+            for label, fn in (("fused", layer4), ("single", layer4_single)):
+                run = lambda i, fn=fn: fn(layer[i % copies])
+                timed(run, 24)
+                res[label] = sorted(timed(run, 120) / 120 for _ in range(3))[1] * 1e6
+            q4layer.append(dict(f=fd, M=1, packed_MB=round(nbytes / 1e6, 1), copies=copies, us_4_launches=round(res["fused"], 2),
+                                us_7_launches=round(res["single"], 2), GBps=round(nbytes / (res["fused"] * 1e-6) / 1e9, 1),
+                                frac_hbm=round(nbytes / (res["fused"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
+            for L in layer:
+                for P_ in L.values():
+                    P_.close()
+        out["decode_q4_layer_7b"] = dict(rows=q4layer, note="the seven projections of one 7B decoder layer from the 4-bit storage at "
+                                         "M = 1, per layer: q/k/v and gate/up in one launch each (patch_gemm4_many) against seven "
+                                         "single launches; rotating over copies of the layer (> 1 GB)")
         out["decode_q4"] = dict(rows=qrows, note="patch_gemm4: 4-bit codes + bf16 scale per row of a tile (+ 2:4 positions), dequantized in "
                                 "registers; rotating packed copies (HBM-resident); us_bf16_storage = patch_gemm on the same pruned weight")
 

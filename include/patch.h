@@ -280,6 +280,9 @@ patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_
  *   patch_gemm4    Y[m, n] = sum_k X[m, k] * bf16(q s)[n, k]: X DEVICE M x K bf16, Y DEVICE M x N fp32, both 16-byte
  *                  aligned; asynchronous, allocates nothing, bit-reproducible.  Decode-shaped: the weight is streamed
  *                  once per 16 rows of X; for prefill shapes dequantize once (patch_unpack4) and patch_pack the result
+ *   patch_gemm4_many  up to PATCH_MAX_MANY weights with the same K and tile against one X in one launch per 16 rows
+ *                  (q / k / v, gate / up): Y[i] is M x N_i fp32; bit-equal to the single calls; PATCH_ERR_SHAPE when K
+ *                  or tile differ
  *   patch_unpack4  any of: W_deq (DEVICE, N x K bf16, 16-byte aligned) = bf16(q s), 0 at pruned positions; codes
  *                  (DEVICE, N x K int8, 0 at pruned positions); scales (DEVICE, N x (K / tile) bf16); NULL = not wanted
  *   patch_packed4_bytes  codes + positions + scales, without alignment padding
@@ -289,6 +292,7 @@ typedef struct patch_packed4 patch_packed4;
 patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
                          patch_packed4** out);
 patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream);
+patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* const* P, void* const* Y, int count, void* stream);
 patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream);
 size_t patch_packed4_bytes(const patch_packed4* P);
 patch_status patch_packed4_dims(const patch_packed4* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles);

@@ -21,7 +21,7 @@ EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_tune_all",
     "patch_tune_bucket", "patch_tune_table_create", "patch_tune_table_destroy", "patch_tune_table_size", "patch_tune_table_put",
     "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
-    "patch_pack4", "patch_gemm4", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
+    "patch_pack4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -100,6 +100,8 @@ def lib() -> ctypes.CDLL:
         L.patch_pack4.restype = ci
         L.patch_gemm4.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm4.restype = ci
+        L.patch_gemm4_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
+        L.patch_gemm4_many.restype = ci
         L.patch_unpack4.argtypes = [vp, vp, vp, vp, vp]
         L.patch_unpack4.restype = ci
         L.patch_packed4_bytes.argtypes = [vp]
@@ -389,6 +391,16 @@ def patch_pack4(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> 
 
 def patch_gemm4(X, M: int, P: Packed4, Y, stream: int = 0) -> None:
     _check(lib().patch_gemm4(_ptr(X), M, P.handle, _ptr(Y), stream), "patch_gemm4")
+
+
+def patch_gemm4_many(X, M: int, Ps, Ys, stream: int = 0) -> None:
+    """Several 4-bit weights (same K, same tile) against one X in one launch per 16 rows."""
+    n = len(Ps)
+    if n != len(Ys):
+        raise PatchError(ERR_ARG, "patch_gemm4_many: as many outputs as weights")
+    hp = (ctypes.c_void_p * n)(*[p.handle for p in Ps])
+    yp = (ctypes.c_void_p * n)(*[_ptr(y) for y in Ys])
+    _check(lib().patch_gemm4_many(_ptr(X), M, hp, yp, n, stream), "patch_gemm4_many")
 
 
 def patch_unpack4(P: Packed4, W_deq=None, codes=None, scales=None, stream: int = 0) -> None:

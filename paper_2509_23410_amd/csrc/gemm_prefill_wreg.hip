@@ -490,14 +490,18 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     // a step with one dense and one 2:4 tile row lasts as long as a dense one).
     // With an odd number of tile rows the last block has no second row (-1): its wavefronts copy X and meet the
     // barriers like the others, read the first row's weights (valid addresses) and multiply nothing.
-    const int32_t* pairs = reinterpret_cast<const int32_t*>(table) + (N / TILE) * (int64_t)Tk_all;
+    // (read through the constant address space: a scalar load; the table pointer came out of scalar selects, after
+    // which the compiler no longer knows its address space and would use flat vector loads)
+    const __attribute__((address_space(4))) int32_t* pairs =
+        reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(reinterpret_cast<uintptr_t>(table)) + (N / TILE) * (int64_t)Tk_all;
     const int row0 = pairs[2 * bn], row1 = pairs[2 * bn + 1];
     const bool live = tr == 0 || row1 >= 0;
     const int64_t nrow = (int64_t)__builtin_amdgcn_readfirstlane((tr == 0 || row1 < 0) ? row0 : row1) * TILE;  // first feature of this wavefront's tile row
     // this workgroup's K slice, in tiles: to the rest of the kernel it is a product with a shorter K
     const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
     const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
-    const uint32_t* trow = table + (nrow / TILE) * Tk_all + t_begin;
+    const __attribute__((address_space(1))) uint32_t* trow =
+        reinterpret_cast<const __attribute__((address_space(1))) uint32_t*>(reinterpret_cast<uintptr_t>(table)) + (nrow / TILE) * Tk_all + t_begin;
 
     // ---- per-lane sources of the X copy: wavefront w copies the 1 KB pieces w, w+4, ..., w+28 of the 32 KB stage.
     // LDS chunk c (16 bytes) = row c / 8, physical chunk c % 8, which holds logical chunk (c % 8) ^ ((row / 2) % 8):

@@ -18,7 +18,8 @@
 //                workgroups on different XCDs; inside the tile every line of scales was fetched by four L2s)
 // The product kernel dequantizes in registers (8 codes -> 8 bf16 with integer rounding) and then runs the same matrix
 // instructions as the bf16 decode kernel: one workgroup per strip of 16 features, its wavefronts split K, partial sums
-// meet in LDS in wavefront order (bit-reproducible).  It is the decode-shaped path only - up to 16 rows per pass over
+// meet in LDS in wavefront order (bit-reproducible); several weights sharing X run as one launch (patch_gemm4_many).
+// It is the decode-shaped path only - up to 16 rows per pass over
 // the weight; for prefill shapes dequantize once (patch_unpack4) and pack the result as bf16.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -37,6 +38,7 @@ typedef __bf16 q4_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 q4_bf16x16 __attribute__((ext_vector_type(16)));
 typedef float q4_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int q4_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int q4_u32x2 __attribute__((ext_vector_type(2)));
 union Q4A { q4_u32x4 raw; q4_bf16x8 v; };
 union Q4B { q4_u32x4 raw[2]; q4_bf16x8 h[2]; q4_bf16x16 v; };
 
@@ -228,28 +230,38 @@ constexpr int kQ4MaxR = 3;
 template <int R>
 struct Q4Batch {
     uint32_t e[kQ4Batch][R];
-    uint2 d[kQ4Batch][R];      // dense: both dwords; 2:4: x = codes, y = positions
+    q4_u32x2 d[kQ4Batch][R];   // dense: both dwords; 2:4: [0] = codes, [1] = positions
     uint32_t sc[kQ4Batch][R];  // scale bits
     q4_u32x4 x[kQ4Batch][2];
 };
 
+// The product kernel's pointers carry their address space: the weight pointers reach it inside a by-value struct and
+// pass through scalar selects, after which the compiler no longer knows that they are global (it then emits flat
+// loads) nor that the table is not written by the kernel (it then reads entries with vector loads).  Table entries
+// are read through the constant address space (scalar loads), everything else through the global one.
+#define PATCH_Q4_GLOBAL __attribute__((address_space(1)))
+#define PATCH_Q4_CONST __attribute__((address_space(4)))
+typedef const PATCH_Q4_CONST uint32_t* q4_table_ptr;
+typedef const PATCH_Q4_GLOBAL uint8_t* q4_bytes_ptr;
+typedef const PATCH_Q4_GLOBAL uint16_t* q4_u16_ptr;
+
 template <int R>
 struct Q4Strips {
-    int64_t row0[R];          // first table entry of the strip's tile row
+    q4_table_ptr row[R];      // table entries of the strip's tile row
+    q4_bytes_ptr pay[R];      // payload of the strip's weight
     int s[R];                 // strip within the tile
-    const uint16_t* scl[R];   // this lane's scale of the strip for tile column 0 (the next column is 16 scales on)
+    q4_u16_ptr scl[R];        // this lane's scale of the strip for tile column 0 (the next column is 16 scales on)
 };
 
 // Steps past the wavefront's run repeat its last step (in bounds; discarded by q4_compute).
 template <int TILE, int R>
-__device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, const uint32_t* __restrict__ table,
-                                         const uint8_t* __restrict__ payload, const uint16_t* xrow, bool xvalid, int lane, int step0, int last) {
+__device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, q4_u16_ptr xrow, bool xvalid, int lane, int step0, int last) {
     constexpr int KPT = TILE / kStepCols;
 #pragma unroll
     for (int i = 0; i < kQ4Batch; ++i) {
         const int step = step0 + i < last ? step0 + i : last;
 #pragma unroll
-        for (int r = 0; r < R; ++r) b.e[i][r] = __builtin_amdgcn_readfirstlane(table[st.row0[r] + step / KPT]);
+        for (int r = 0; r < R; ++r) b.e[i][r] = st.row[r][step / KPT];
     }
 #pragma unroll
     for (int i = 0; i < kQ4Batch; ++i) {
@@ -258,19 +270,19 @@ __device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, c
         b.x[i][0] = q4_u32x4{0u, 0u, 0u, 0u};
         b.x[i][1] = q4_u32x4{0u, 0u, 0u, 0u};
         if (xvalid) {
-            b.x[i][0] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols);
-            b.x[i][1] = *reinterpret_cast<const q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
+            b.x[i][0] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow + (int64_t)step * kStepCols);
+            b.x[i][1] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const uint8_t* base = payload + entry_offset(b.e[i][r]);
+            q4_bytes_ptr base = st.pay[r] + entry_offset(b.e[i][r]);
             const int s = st.s[r];
             b.sc[i][r] = st.scl[r][(step / KPT) * 16];
             if (!entry_sparse(b.e[i][r])) {
-                b.d[i][r] = *reinterpret_cast<const uint2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
+                b.d[i][r] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x2*>(base + (size_t)(s * KPT + j) * 512 + lane * 8);
             } else {
-                b.d[i][r].x = *reinterpret_cast<const uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
-                b.d[i][r].y = *reinterpret_cast<const uint16_t*>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
+                b.d[i][r][0] = *reinterpret_cast<const PATCH_Q4_GLOBAL uint32_t*>(base + (size_t)(s * KPT + j) * 256 + lane * 4);
+                b.d[i][r][1] = *reinterpret_cast<q4_u16_ptr>(base + q4_sparse_codes(TILE) + ((s * 64 + lane) * KPT + j) * 2);
             }
         }
     }
@@ -289,52 +301,124 @@ __device__ __forceinline__ void q4_compute(const Q4Batch<R>& b, q4_f32x4 (&acc)[
             const float scl = q4_bf16_to_float(b.sc[i][r]);
             if (!entry_sparse(b.e[i][r])) {
                 Q4A a0, a1;
-                a0.raw = q4_dequant8(b.d[i][r].x, scl);
-                a1.raw = q4_dequant8(b.d[i][r].y, scl);
+                a0.raw = q4_dequant8(b.d[i][r][0], scl);
+                a1.raw = q4_dequant8(b.d[i][r][1], scl);
                 acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, x.h[0], acc[r], 0, 0, 0);
                 acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, x.h[1], acc[r], 0, 0, 0);
             } else {
                 Q4A a;
-                a.raw = q4_dequant8(b.d[i][r].x, scl);
-                acc[r] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, x.v, acc[r], (int)b.d[i][r].y, 0, 0);
+                a.raw = q4_dequant8(b.d[i][r][0], scl);
+                acc[r] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, x.v, acc[r], (int)b.d[i][r][1], 0, 0);
             }
         }
     }
 }
 
-template <int TILE, int R>
-__global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
-                                                       const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
-                                                       const uint32_t* __restrict__ table, float* __restrict__ Y, int64_t N) {
+// Up to MAXC 4-bit weights that share one X (same K, same tile) in one launch.  The launch numbers the 16-feature strips
+// across all weights (first[i] = first strip of weight i, total = their number); a workgroup takes R consecutive
+// strips, which may belong to two weights.
+template <int MAXC>
+struct Q4Set {
+    static constexpr int kMax = MAXC;
+    const uint8_t* payload[MAXC];
+    const uint16_t* scales[MAXC];
+    const uint32_t* table[MAXC];
+    float* Y[MAXC];
+    int64_t N[MAXC];
+    int first[MAXC];
+    int count, total;
+};
+
+// A set of one: 40 bytes of kernel arguments.
+struct Q4One {
+    const uint8_t* payload;
+    const uint16_t* scales;
+    const uint32_t* table;
+    float* Y;
+    int64_t N;
+};
+
+struct Q4Weight {
+    uint64_t payload, scales, table, Y;
+    int64_t N;
+    int first;
+};
+
+// The weight that strip g of the launch belongs to (g uniform): scalar selects over the candidates, so that every
+// pointer stays in scalar registers.
+template <typename SetT>
+__device__ __forceinline__ Q4Weight q4_weight_of(const SetT& set, int g) {
+    Q4Weight wt;
+    if constexpr (sizeof(SetT) == sizeof(Q4One)) {
+        wt = Q4Weight{reinterpret_cast<uint64_t>(set.payload), reinterpret_cast<uint64_t>(set.scales), reinterpret_cast<uint64_t>(set.table),
+                      reinterpret_cast<uint64_t>(set.Y), set.N, 0};
+    } else {
+        wt = Q4Weight{reinterpret_cast<uint64_t>(set.payload[0]), reinterpret_cast<uint64_t>(set.scales[0]),
+                      reinterpret_cast<uint64_t>(set.table[0]), reinterpret_cast<uint64_t>(set.Y[0]), set.N[0], 0};
+#pragma unroll
+        for (int i = 1; i < SetT::kMax; ++i) {
+            const bool here = i < set.count && g >= set.first[i];
+            wt.payload = here ? reinterpret_cast<uint64_t>(set.payload[i]) : wt.payload;
+            wt.scales = here ? reinterpret_cast<uint64_t>(set.scales[i]) : wt.scales;
+            wt.table = here ? reinterpret_cast<uint64_t>(set.table[i]) : wt.table;
+            wt.Y = here ? reinterpret_cast<uint64_t>(set.Y[i]) : wt.Y;
+            wt.N = here ? set.N[i] : wt.N;
+            wt.first = here ? set.first[i] : wt.first;
+        }
+    }
+    return wt;
+}
+
+// Every kernel argument is requested in the kernel's first instructions and waited for once (the compiler otherwise
+// fetches an argument where it is first used, e.g. behind a branch: one more, if short, round trip before the first
+// weight load).  What costs far more is losing the address spaces (see PATCH_Q4_GLOBAL above): with flat loads and
+// table entries read by vector loads the same launch took 8.0 us instead of 6.2.
+#define PATCH_Q4_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
+
+template <int TILE, int R, typename SetT>
+__global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk, int KW,
+                                                       const SetT set) {
+    constexpr bool kOne = sizeof(SetT) == sizeof(Q4One);
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
     __shared__ q4_f32x4 red[R][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), KW = blockDim.x >> 6;
-    const int n_strips = (int)(N / kStripRows), strip0 = blockIdx.x * R;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // of KW wavefronts: an argument (the launch size is a hidden one, fetched apart)
     const int col = lane & 15, q = lane >> 4;
-    const bool xvalid = col < rows;
-    const int total = Tk * KPT, per = (total + KW - 1) / KW;
-    const int begin = w * per, end = begin + per < total ? begin + per : total;
-    const uint16_t* xrow = X + (m0 + (xvalid ? col : 0)) * K + 8 * q;
+    int total_strips;
+    if constexpr (kOne) total_strips = (int)(set.N / kStripRows);
+    else total_strips = set.total;
+    const int g0 = (int)blockIdx.x * R;
     Q4Strips<R> st;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int strip = strip0 + r < n_strips ? strip0 + r : n_strips - 1;   // a strip past the end repeats the last one (not stored)
-        st.row0[r] = (int64_t)(strip / SPT) * Tk;
+        const int g = g0 + r < total_strips ? g0 + r : total_strips - 1;   // a strip past the end repeats the last one (not stored)
+        const Q4Weight wt = q4_weight_of(set, g);
+        PATCH_Q4_ARGS_NOW("s"(wt.payload), "s"(wt.scales), "s"(wt.table), "s"(wt.first));
+        const int strip = g - wt.first;
+        st.row[r] = reinterpret_cast<q4_table_ptr>(wt.table) + (int64_t)(strip / SPT) * Tk;
+        st.pay[r] = reinterpret_cast<q4_bytes_ptr>(wt.payload);
         st.s[r] = strip % SPT;
-        st.scl[r] = scales + q4_scale_index(strip, Tk, 0, col);
+        st.scl[r] = reinterpret_cast<q4_u16_ptr>(wt.scales) + q4_scale_index(strip, Tk, 0, col);
     }
+    // the strip this wavefront adds up and stores at the end (wavefronts 0 .. R - 1)
+    const int gw = g0 + (w < R ? w : 0);
+    const Q4Weight wy = q4_weight_of(set, gw < total_strips ? gw : total_strips - 1);
+    PATCH_Q4_ARGS_NOW("s"(X), "s"(m0), "s"(rows), "s"(K), "s"(Tk), "s"(KW), "s"(wy.Y), "s"(wy.N), "s"(wy.first));
+    const bool xvalid = col < rows;
+    const int total = Tk * KPT, per = (total + KW - 1) / KW;
+    const int begin = w * per, end = begin + per < total ? begin + per : total;
+    q4_u16_ptr xrow = reinterpret_cast<q4_u16_ptr>(reinterpret_cast<uintptr_t>(X)) + (m0 + (xvalid ? col : 0)) * K + 8 * q;
     q4_f32x4 acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = q4_f32x4{0.f, 0.f, 0.f, 0.f};
     if (begin < end) {
         Q4Batch<R> b0, b1;
-        q4_loads<TILE, R>(b0, st, table, payload, xrow, xvalid, lane, begin, end - 1);
+        q4_loads<TILE, R>(b0, st, xrow, xvalid, lane, begin, end - 1);
         for (int step0 = begin; step0 < end; step0 += 2 * kQ4Batch) {
             const bool have1 = step0 + kQ4Batch < end, have2 = step0 + 2 * kQ4Batch < end;   // uniform
-            if (have1) q4_loads<TILE, R>(b1, st, table, payload, xrow, xvalid, lane, step0 + kQ4Batch, end - 1);
+            if (have1) q4_loads<TILE, R>(b1, st, xrow, xvalid, lane, step0 + kQ4Batch, end - 1);
             q4_compute<R>(b0, acc, step0, end);
-            if (have2) q4_loads<TILE, R>(b0, st, table, payload, xrow, xvalid, lane, step0 + 2 * kQ4Batch, end - 1);
+            if (have2) q4_loads<TILE, R>(b0, st, xrow, xvalid, lane, step0 + 2 * kQ4Batch, end - 1);
             if (have1) q4_compute<R>(b1, acc, step0 + kQ4Batch, end);
         }
     }
@@ -342,31 +426,29 @@ __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restric
     for (int r = 0; r < R; ++r) red[r][w][lane] = acc[r];
     __syncthreads();
     // wavefront r adds up strip r in wavefront order (R <= the number of wavefronts is checked by the launcher)
-    if (w < R && strip0 + w < n_strips) {
+    if (w < R && gw < total_strips) {
         q4_f32x4 sum = red[w][0][lane];
         for (int i = 1; i < KW; ++i) {
             const q4_f32x4 v = red[w][i][lane];
             sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
-        if (xvalid) *reinterpret_cast<q4_f32x4*>(Y + (m0 + col) * N + (int64_t)(strip0 + w) * 16 + 4 * q) = sum;
+        PATCH_Q4_GLOBAL float* Yg = reinterpret_cast<PATCH_Q4_GLOBAL float*>(wy.Y);
+        if (xvalid) *reinterpret_cast<PATCH_Q4_GLOBAL q4_f32x4*>(Yg + (m0 + col) * wy.N + (int64_t)(gw - wy.first) * 16 + 4 * q) = sum;
     }
 }
 
-template <int TILE, int R>
-static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint16_t* scales,
-                           const uint32_t* table, float* Y, int64_t N, int kw, hipStream_t s) {
-    const int n_strips = (int)(N / kStripRows);
-    hipLaunchKernelGGL((decode4_kernel<TILE, R>), dim3((unsigned)((n_strips + R - 1) / R)), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk,
-                       payload, scales, table, Y, N);
+template <int TILE, int R, typename SetT>
+static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw, hipStream_t s) {
+    hipLaunchKernelGGL((decode4_kernel<TILE, R, SetT>), dim3((unsigned)groups), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk, kw, set);
 }
 
-template <int TILE>
-static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const uint8_t* payload, const uint16_t* scales,
-                             const uint32_t* table, float* Y, int64_t N, int kw, hipStream_t s) {
+template <int TILE, typename SetT>
+static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw,
+                             hipStream_t s) {
     switch (R) {
-        case 1: launch_decode4<TILE, 1>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
-        case 2: launch_decode4<TILE, 2>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
-        default: launch_decode4<TILE, 3>(X, m0, rows, K, Tk, payload, scales, table, Y, N, kw, s); break;
+        case 1: launch_decode4<TILE, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
+        case 2: launch_decode4<TILE, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
+        default: launch_decode4<TILE, 3, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
     }
 }
 
@@ -472,33 +554,76 @@ patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, voi
     return PATCH_OK;
 }
 
-patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream) {
-    if (!X || !P || !Y || M < 0) return PATCH_ERR_ARG;
-    if (!q4_aligned16(X) || !q4_aligned16(Y)) return PATCH_ERR_ARG;
+patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* const* P, void* const* Y, int count, void* stream) {
+    if (!X || !P || !Y || M < 0 || count < 1 || count > PATCH_MAX_MANY) return PATCH_ERR_ARG;
+    static_assert(PATCH_MAX_MANY == kMaxMany, "header and kernels disagree");
+    if (!q4_aligned16(X)) return PATCH_ERR_ARG;
+    for (int i = 0; i < count; ++i) {
+        if (!P[i] || !Y[i] || !q4_aligned16(Y[i])) return PATCH_ERR_ARG;
+        if (P[i]->K != P[0]->K || P[i]->tile != P[0]->tile) return PATCH_ERR_SHAPE;
+    }
     if (M == 0) return PATCH_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int total = P->Tk * (P->tile / kStepCols);
+    const patch_packed4* P0 = P[0];
+    const int total = P0->Tk * (P0->tile / kStepCols);
     // wavefronts per workgroup: about 4 steps each, at least one per strip, at most 16
     int kw = (total + 3) / 4;
     if (kw > 16) kw = 16;
     if (kw < kQ4MaxR) kw = kQ4MaxR;
-    // strips per workgroup: one workgroup per compute unit when the weight has more strips than that, at most 3
-    const int n_strips = (int)(P->N / kStripRows);
-    int R = (n_strips + P->n_cus - 1) / P->n_cus;
+    // strips per workgroup: one workgroup per compute unit when the weights have more strips than that, at most 3
+    int64_t n_strips = 0;
+    for (int i = 0; i < count; ++i) n_strips += P[i]->N / kStripRows;
+    int R = (int)((n_strips + P0->n_cus - 1) / P0->n_cus);
     if (R > kQ4MaxR) R = kQ4MaxR;
     if (R < 1) R = 1;
-    for (int64_t m0 = 0; m0 < M; m0 += 16) {
-        const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
-        if (P->tile == 128)
-            launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_scales, P->d_table,
-                                  static_cast<float*>(Y), P->N, kw, s);
-        else
-            launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P->K, P->Tk, P->d_payload, P->d_scales, P->d_table,
-                                 static_cast<float*>(Y), P->N, kw, s);
+    int first[kMaxMany], total_strips = 0;
+    for (int i = 0; i < count; ++i) {
+        first[i] = total_strips;
+        total_strips += (int)(P[i]->N / kStripRows);
+    }
+    const int groups = (total_strips + R - 1) / R;
+    // more workgroups than compute units: half the wavefronts each, so that two workgroups share a compute unit (its
+    // registers hold 16 of these wavefronts) instead of running one after the other
+    if (groups > P0->n_cus && kw > 8) kw = 8;
+    auto run = [&](const auto& set) {
+        for (int64_t m0 = 0; m0 < M; m0 += 16) {
+            const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
+            if (P0->tile == 128) launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
+            else launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
+        }
+    };
+    auto fill = [&](auto& set) {
+        for (int i = 0; i < count; ++i) {
+            set.payload[i] = P[i]->d_payload;
+            set.scales[i] = P[i]->d_scales;
+            set.table[i] = P[i]->d_table;
+            set.Y[i] = static_cast<float*>(Y[i]);
+            set.N[i] = P[i]->N;
+            set.first[i] = first[i];
+        }
+        set.count = count;
+        set.total = total_strips;
+    };
+    // the fewer kernel arguments the better: a set of one, of up to three (q / k / v, gate / up), of up to eight
+    if (count == 1) {
+        run(Q4One{P0->d_payload, P0->d_scales, P0->d_table, static_cast<float*>(Y[0]), P0->N});
+    } else if (count <= 3) {
+        Q4Set<3> set = {};
+        fill(set);
+        run(set);
+    } else {
+        Q4Set<kMaxMany> set = {};
+        fill(set);
+        run(set);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
     return PATCH_OK;
+}
+
+patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream) {
+    if (!P || !Y) return PATCH_ERR_ARG;
+    return patch_gemm4_many(X, M, &P, &Y, 1, stream);
 }
 
 size_t patch_packed4_bytes(const patch_packed4* P) { return P ? P->algorithmic_bytes : 0; }

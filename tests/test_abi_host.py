@@ -74,6 +74,9 @@ def test_argument_errors_without_device():
     assert L.patch_gemm4(fake, 1, 0, fake, 0) == B.ERR_ARG
     assert L.patch_gemm4(0, 1, fake, fake, 0) == B.ERR_ARG
     assert L.patch_gemm4(fake, -1, fake, fake, 0) == B.ERR_ARG
+    assert L.patch_gemm4_many(fake, 1, two, two, 2, 0) == B.ERR_ARG   # null handles
+    assert L.patch_gemm4_many(fake, 1, two, two, 0, 0) == B.ERR_ARG   # count out of range
+    assert L.patch_gemm4_many(fake, 1, two, two, 9, 0) == B.ERR_ARG
     assert L.patch_unpack4(0, fake, None, None, 0) == B.ERR_ARG
     assert L.patch_packed4_bytes(0) == 0
     assert L.patch_packed4_dims(0, None, None, None, None) == B.ERR_ARG

@@ -104,6 +104,34 @@ def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
     p.P.close()
 
 
+def test_weights_sharing_x_in_one_launch(dev):
+    """patch_gemm4_many: weights of different N and maps against one X, bit-equal to the single calls (same wavefront
+    split of K, same order of the partial sums) and within the bound of the oracle; K or tile mismatch rejected."""
+    K, t = 1024, 128
+    cases = [synth.make_case(f"many4_{i}", N, K, 40, t, f, seed=24) for i, (N, f) in enumerate([(512, 0.5), (128, 1.0), (4480, 0.0), (384, 0.7)])]
+    X = cases[0].X
+    preps = [Prepared4(c, dev) for c in cases]
+    Xd = to_dev_bf16(X, dev)
+    for M in (1, 16, 40):
+        print(f"4-bit many M={M}", flush=True)
+        Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+        B.patch_gemm4_many(Xd, M, [p.P for p in preps], Ys, stream())
+        torch.cuda.synchronize()
+        for p, c, Y in zip(preps, cases, Ys):
+            single = torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32)
+            B.patch_gemm4(Xd, M, p.P, single, stream())
+            torch.cuda.synchronize()
+            assert torch.equal(Y, single), "fused launch differs from the single call"
+            check_elements(Y.cpu().numpy(), p.oracle_gemm(X[:M]), row_norms(X[:M]), row_norms(p.W_deq_o), K, f"4-bit many {c.name} M={M}")
+    other = Prepared4(synth.make_case("many4_k", 128, 512, 4, t, 0.5, seed=25), dev)
+    with pytest.raises(B.PatchError) as e:
+        B.patch_gemm4_many(Xd, 1, [preps[0].P, other.P], [torch.empty((1, 512), device=dev), torch.empty((1, 128), device=dev)], stream())
+    assert e.value.status == B.ERR_SHAPE
+    other.P.close()
+    for p in preps:
+        p.P.close()
+
+
 def test_special_rows_ties_and_rejection(dev):
     """An all-zero row (scale 0, codes 0), a row whose largest weight is negative, weights at exact half steps
     (ties go to the even code), and groups with fewer than two nonzeros in a 2:4 tile."""
