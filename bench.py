@@ -17,7 +17,10 @@ Also reported on the same JSON line:
   ceilings      measured ceilings from kernels of this library (register-resident loops of the two matrix
                 instructions, streaming reads) and the vendor dense GEMM on the same shapes (context)
   stack_13b     the 13B decoder stack: 40 layers x 7 matrices, one 2:4 fraction per layer drawn U[0,1),
-                M in {1, 512, 4096}, time = sum over the layers
+                M in {1, 512, 4096}, time = sum over the layers; stack_13b_per_matrix: the same with a fraction
+                per (layer, matrix) that follows the allocation the paper reports (key / value dense, MLP heavy)
+  decode_q4     decode from the 4-bit weight-only storage (7B shapes, M = 1 and 16) beside the bf16 storage;
+                decode_q4_layer_7b: one 7B decoder layer from it in four launches
   qwen_0p5b     the 0.5B-scale layer set (launch-latency-bound)
   cpu_baseline  the CPU oracle timed on a bounded sample of the headline workload
 
