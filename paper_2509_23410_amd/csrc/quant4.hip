@@ -219,20 +219,21 @@ __global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict_
     }
 }
 
-// Up to 16 rows of X against the 4-bit weight.  A workgroup owns R consecutive strips of 16 features; its KW =
-// blockDim.x / 64 wavefronts take contiguous runs of 64-column steps.  A wavefront loads the X operand of a step once
+// Up to 16 RB rows of X (RB = 1, 2 or 4 blocks of 16 rows) against the 4-bit weight in one pass over it.  A workgroup
+// owns R consecutive strips of 16 features (the registers hold R x RB accumulators and RB X operands per step: R <= 3
+// with one row block, R <= 2 with more); its KW wavefronts take contiguous runs of 64-column steps.  A wavefront loads the X operand of a step once
 // and uses it for all R strips (at 4 bits per weight X is the larger stream, so this reuse is what bounds the traffic),
-// works in batches of kQ4Batch steps - table entries, then every load of the batch, then the arithmetic - and issues
+// works in batches of NB steps (2; 1 when RB > 1) - table entries, then every load of the batch, then the arithmetic - and issues
 // the next batch's loads before it consumes the current one.  Two batch buffers alternate; no copies.
-constexpr int kQ4Batch = 2;
 constexpr int kQ4MaxR = 3;
+constexpr int kQ4Rows = 64;   // rows of X per launch at most
 
-template <int R>
+template <int R, int RB, int NB>
 struct Q4Batch {
-    uint32_t e[kQ4Batch][R];
-    q4_u32x2 d[kQ4Batch][R];   // dense: both dwords; 2:4: [0] = codes, [1] = positions
-    uint32_t sc[kQ4Batch][R];  // scale bits
-    q4_u32x4 x[kQ4Batch][2];
+    uint32_t e[NB][R];
+    q4_u32x2 d[NB][R];         // dense: both dwords; 2:4: [0] = codes, [1] = positions
+    uint32_t sc[NB][R];        // scale bits
+    q4_u32x4 x[NB][RB][2];
 };
 
 // The product kernel's pointers carry their address space: the weight pointers reach it inside a by-value struct and
@@ -254,24 +255,28 @@ struct Q4Strips {
 };
 
 // Steps past the wavefront's run repeat its last step (in bounds; discarded by q4_compute).
-template <int TILE, int R>
-__device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, q4_u16_ptr xrow, bool xvalid, int lane, int step0, int last) {
+template <int TILE, int R, int RB, int NB>
+__device__ __forceinline__ void q4_loads(Q4Batch<R, RB, NB>& b, const Q4Strips<R>& st, const q4_u16_ptr (&xrow)[RB], const bool (&xvalid)[RB],
+                                         int lane, int step0, int last) {
     constexpr int KPT = TILE / kStepCols;
 #pragma unroll
-    for (int i = 0; i < kQ4Batch; ++i) {
+    for (int i = 0; i < NB; ++i) {
         const int step = step0 + i < last ? step0 + i : last;
 #pragma unroll
         for (int r = 0; r < R; ++r) b.e[i][r] = st.row[r][step / KPT];
     }
 #pragma unroll
-    for (int i = 0; i < kQ4Batch; ++i) {
+    for (int i = 0; i < NB; ++i) {
         const int step = step0 + i < last ? step0 + i : last;
         const int j = step % KPT;
-        b.x[i][0] = q4_u32x4{0u, 0u, 0u, 0u};
-        b.x[i][1] = q4_u32x4{0u, 0u, 0u, 0u};
-        if (xvalid) {
-            b.x[i][0] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow + (int64_t)step * kStepCols);
-            b.x[i][1] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow + (int64_t)step * kStepCols + 32);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            b.x[i][rb][0] = q4_u32x4{0u, 0u, 0u, 0u};
+            b.x[i][rb][1] = q4_u32x4{0u, 0u, 0u, 0u};
+            if (xvalid[rb]) {
+                b.x[i][rb][0] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow[rb] + (int64_t)step * kStepCols);
+                b.x[i][rb][1] = *reinterpret_cast<const PATCH_Q4_GLOBAL q4_u32x4*>(xrow[rb] + (int64_t)step * kStepCols + 32);
+            }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -288,14 +293,11 @@ __device__ __forceinline__ void q4_loads(Q4Batch<R>& b, const Q4Strips<R>& st, q
     }
 }
 
-template <int R>
-__device__ __forceinline__ void q4_compute(const Q4Batch<R>& b, q4_f32x4 (&acc)[R], int step0, int end) {
+template <int R, int RB, int NB>
+__device__ __forceinline__ void q4_compute(const Q4Batch<R, RB, NB>& b, q4_f32x4 (&acc)[R][RB], int step0, int end) {
 #pragma unroll
-    for (int i = 0; i < kQ4Batch; ++i) {
+    for (int i = 0; i < NB; ++i) {
         if (step0 + i >= end) break;   // uniform
-        Q4B x;
-        x.raw[0] = b.x[i][0];
-        x.raw[1] = b.x[i][1];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float scl = q4_bf16_to_float(b.sc[i][r]);
@@ -303,12 +305,24 @@ __device__ __forceinline__ void q4_compute(const Q4Batch<R>& b, q4_f32x4 (&acc)[
                 Q4A a0, a1;
                 a0.raw = q4_dequant8(b.d[i][r][0], scl);
                 a1.raw = q4_dequant8(b.d[i][r][1], scl);
-                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, x.h[0], acc[r], 0, 0, 0);
-                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, x.h[1], acc[r], 0, 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    Q4B x;
+                    x.raw[0] = b.x[i][rb][0];
+                    x.raw[1] = b.x[i][rb][1];
+                    acc[r][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.v, x.h[0], acc[r][rb], 0, 0, 0);
+                    acc[r][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.v, x.h[1], acc[r][rb], 0, 0, 0);
+                }
             } else {
                 Q4A a;
                 a.raw = q4_dequant8(b.d[i][r][0], scl);
-                acc[r] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, x.v, acc[r], (int)b.d[i][r][1], 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    Q4B x;
+                    x.raw[0] = b.x[i][rb][0];
+                    x.raw[1] = b.x[i][rb][1];
+                    acc[r][rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, x.v, acc[r][rb], (int)b.d[i][r][1], 0, 0);
+                }
             }
         }
     }
@@ -375,12 +389,17 @@ __device__ __forceinline__ Q4Weight q4_weight_of(const SetT& set, int g) {
 // table entries read by vector loads the same launch took 8.0 us instead of 6.2.
 #define PATCH_Q4_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
 
-template <int TILE, int R, typename SetT>
-__global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk, int KW,
+// wavefronts per workgroup at most: 16, or 8 with four or more accumulators and X operands of several row blocks
+// (whose registers do not fit 16 times into a compute unit)
+constexpr int q4_max_waves(int R, int RB) { return RB == 4 || R * RB > 4 || (RB == 2 && R > 1) ? 8 : 16; }
+
+template <int TILE, int R, int RB, typename SetT>
+__global__ __launch_bounds__(64 * q4_max_waves(R, RB)) void decode4_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk, int KW,
                                                        const SetT set) {
     constexpr bool kOne = sizeof(SetT) == sizeof(Q4One);
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
-    __shared__ q4_f32x4 red[R][16][64];
+    constexpr int NB = RB > 1 ? 1 : 2;   // steps per batch
+    __shared__ q4_f32x4 red[R * RB][q4_max_waves(R, RB)][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // of KW wavefronts: an argument (the launch size is a hidden one, fetched apart)
     const int col = lane & 15, q = lane >> 4;
@@ -400,56 +419,71 @@ __global__ __launch_bounds__(1024) void decode4_kernel(const uint16_t* __restric
         st.s[r] = strip % SPT;
         st.scl[r] = reinterpret_cast<q4_u16_ptr>(wt.scales) + q4_scale_index(strip, Tk, 0, col);
     }
-    // the strip this wavefront adds up and stores at the end (wavefronts 0 .. R - 1)
-    const int gw = g0 + (w < R ? w : 0);
+    // the (strip, row block) this wavefront adds up and stores at the end (wavefronts 0 .. R RB - 1)
+    const int wr = w < R * RB ? w / RB : 0, wrb = w % RB;
+    const int gw = g0 + wr;
     const Q4Weight wy = q4_weight_of(set, gw < total_strips ? gw : total_strips - 1);
     PATCH_Q4_ARGS_NOW("s"(X), "s"(m0), "s"(rows), "s"(K), "s"(Tk), "s"(KW), "s"(wy.Y), "s"(wy.N), "s"(wy.first));
-    const bool xvalid = col < rows;
     const int total = Tk * KPT, per = (total + KW - 1) / KW;
     const int begin = w * per, end = begin + per < total ? begin + per : total;
-    q4_u16_ptr xrow = reinterpret_cast<q4_u16_ptr>(reinterpret_cast<uintptr_t>(X)) + (m0 + (xvalid ? col : 0)) * K + 8 * q;
-    q4_f32x4 acc[R];
+    bool xvalid[RB];
+    q4_u16_ptr xrow[RB];
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = q4_f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < RB; ++rb) {
+        xvalid[rb] = 16 * rb + col < rows;
+        xrow[rb] = reinterpret_cast<q4_u16_ptr>(reinterpret_cast<uintptr_t>(X)) + (m0 + (xvalid[rb] ? 16 * rb + col : 0)) * K + 8 * q;
+    }
+    q4_f32x4 acc[R][RB];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) acc[r][rb] = q4_f32x4{0.f, 0.f, 0.f, 0.f};
     if (begin < end) {
-        Q4Batch<R> b0, b1;
-        q4_loads<TILE, R>(b0, st, xrow, xvalid, lane, begin, end - 1);
-        for (int step0 = begin; step0 < end; step0 += 2 * kQ4Batch) {
-            const bool have1 = step0 + kQ4Batch < end, have2 = step0 + 2 * kQ4Batch < end;   // uniform
-            if (have1) q4_loads<TILE, R>(b1, st, xrow, xvalid, lane, step0 + kQ4Batch, end - 1);
-            q4_compute<R>(b0, acc, step0, end);
-            if (have2) q4_loads<TILE, R>(b0, st, xrow, xvalid, lane, step0 + 2 * kQ4Batch, end - 1);
-            if (have1) q4_compute<R>(b1, acc, step0 + kQ4Batch, end);
+        Q4Batch<R, RB, NB> b0, b1;
+        q4_loads<TILE, R, RB, NB>(b0, st, xrow, xvalid, lane, begin, end - 1);
+        for (int step0 = begin; step0 < end; step0 += 2 * NB) {
+            const bool have1 = step0 + NB < end, have2 = step0 + 2 * NB < end;   // uniform
+            if (have1) q4_loads<TILE, R, RB, NB>(b1, st, xrow, xvalid, lane, step0 + NB, end - 1);
+            q4_compute<R, RB, NB>(b0, acc, step0, end);
+            if (have2) q4_loads<TILE, R, RB, NB>(b0, st, xrow, xvalid, lane, step0 + 2 * NB, end - 1);
+            if (have1) q4_compute<R, RB, NB>(b1, acc, step0 + NB, end);
         }
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) red[r][w][lane] = acc[r];
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) red[r * RB + rb][w][lane] = acc[r][rb];
     __syncthreads();
-    // wavefront r adds up strip r in wavefront order (R <= the number of wavefronts is checked by the launcher)
-    if (w < R && gw < total_strips) {
+    // wavefront w < R RB adds up (strip w / RB, row block w % RB) in wavefront order (the launcher keeps KW >= R RB)
+    if (w < R * RB && gw < total_strips) {
         q4_f32x4 sum = red[w][0][lane];
         for (int i = 1; i < KW; ++i) {
             const q4_f32x4 v = red[w][i][lane];
             sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
         }
         PATCH_Q4_GLOBAL float* Yg = reinterpret_cast<PATCH_Q4_GLOBAL float*>(wy.Y);
-        if (xvalid) *reinterpret_cast<PATCH_Q4_GLOBAL q4_f32x4*>(Yg + (m0 + col) * wy.N + (int64_t)(gw - wy.first) * 16 + 4 * q) = sum;
+        if (16 * wrb + col < rows)
+            *reinterpret_cast<PATCH_Q4_GLOBAL q4_f32x4*>(Yg + (m0 + 16 * wrb + col) * wy.N + (int64_t)(gw - wy.first) * 16 + 4 * q) = sum;
     }
 }
 
-template <int TILE, int R, typename SetT>
+template <int TILE, int R, int RB, typename SetT>
 static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw, hipStream_t s) {
-    hipLaunchKernelGGL((decode4_kernel<TILE, R, SetT>), dim3((unsigned)groups), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk, kw, set);
+    hipLaunchKernelGGL((decode4_kernel<TILE, R, RB, SetT>), dim3((unsigned)groups), dim3((unsigned)(kw * 64)), 0, s, X, m0, rows, K, Tk, kw,
+                       set);
 }
 
+// up to 3 strips per workgroup with one block of 16 rows, up to 2 with RB = 2 / 4 row blocks
 template <int TILE, typename SetT>
-static void launch_decode4_r(int R, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw,
+static void launch_decode4_r(int R, int RB, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw,
                              hipStream_t s) {
-    switch (R) {
-        case 1: launch_decode4<TILE, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
-        case 2: launch_decode4<TILE, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
-        default: launch_decode4<TILE, 3, SetT>(X, m0, rows, K, Tk, set, groups, kw, s); break;
-    }
+    if (RB == 4 && R == 1) launch_decode4<TILE, 1, 4, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else if (RB == 4) launch_decode4<TILE, 2, 4, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else if (RB == 2 && R == 1) launch_decode4<TILE, 1, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else if (RB == 2) launch_decode4<TILE, 2, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else if (R == 1) launch_decode4<TILE, 1, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else if (R == 2) launch_decode4<TILE, 2, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+    else launch_decode4<TILE, 3, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
 }
 
 }  // namespace patch
@@ -566,30 +600,31 @@ patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* con
     hipStream_t s = static_cast<hipStream_t>(stream);
     const patch_packed4* P0 = P[0];
     const int total = P0->Tk * (P0->tile / kStepCols);
-    // wavefronts per workgroup: about 4 steps each, at least one per strip, at most 16
-    int kw = (total + 3) / 4;
-    if (kw > 16) kw = 16;
-    if (kw < kQ4MaxR) kw = kQ4MaxR;
-    // strips per workgroup: one workgroup per compute unit when the weights have more strips than that, at most 3
-    int64_t n_strips = 0;
-    for (int i = 0; i < count; ++i) n_strips += P[i]->N / kStripRows;
-    int R = (int)((n_strips + P0->n_cus - 1) / P0->n_cus);
-    if (R > kQ4MaxR) R = kQ4MaxR;
-    if (R < 1) R = 1;
     int first[kMaxMany], total_strips = 0;
     for (int i = 0; i < count; ++i) {
         first[i] = total_strips;
         total_strips += (int)(P[i]->N / kStripRows);
     }
-    const int groups = (total_strips + R - 1) / R;
-    // more workgroups than compute units: half the wavefronts each, so that two workgroups share a compute unit (its
-    // registers hold 16 of these wavefronts) instead of running one after the other
-    if (groups > P0->n_cus && kw > 8) kw = 8;
+    // One launch per pass of up to 64 rows.  A pass of at most 16 rows: R strips per workgroup - one workgroup per
+    // compute unit when the weights have more strips than that, at most 3.  A longer pass: 2 or 4 row blocks, R at most 2.
     auto run = [&](const auto& set) {
-        for (int64_t m0 = 0; m0 < M; m0 += 16) {
-            const int rows = (int)(M - m0 < 16 ? M - m0 : 16);
-            if (P0->tile == 128) launch_decode4_r<128>(R, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
-            else launch_decode4_r<64>(R, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
+        for (int64_t m0 = 0; m0 < M; m0 += kQ4Rows) {
+            const int rows = (int)(M - m0 < kQ4Rows ? M - m0 : kQ4Rows);
+            const int RB = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
+            int R = (total_strips + P0->n_cus - 1) / P0->n_cus;
+            if (R > (RB > 1 ? 2 : kQ4MaxR)) R = RB > 1 ? 2 : kQ4MaxR;
+            if (R < 1) R = 1;
+            const int groups = (total_strips + R - 1) / R;
+            // wavefronts per workgroup: about 4 steps each, at least one per (strip, row block), at most 16; with more
+            // workgroups than compute units half of that, so that two workgroups share a compute unit (its registers
+            // hold 16 of these wavefronts) instead of running one after the other
+            int kw = (total + 3) / 4;
+            if (kw > q4_max_waves(R, RB)) kw = q4_max_waves(R, RB);
+            if (groups > P0->n_cus && kw > 8) kw = 8;
+            if (kw < R * RB) kw = R * RB;
+            if (kw < 4) kw = 4;
+            if (P0->tile == 128) launch_decode4_r<128>(R, RB, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
+            else launch_decode4_r<64>(R, RB, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
         }
     };
     auto fill = [&](auto& set) {
