@@ -286,6 +286,10 @@ patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_
  *                  workgroups); PATCH_ERR_SHAPE when K or tile differ
  *   patch_unpack4  any of: W_deq (DEVICE, N x K bf16, 16-byte aligned) = bf16(q s), 0 at pruned positions; codes
  *                  (DEVICE, N x K int8, 0 at pruned positions); scales (DEVICE, N x (K / tile) bf16); NULL = not wanted
+ *   patch_pack_from4  the dequantized weight bf16(q s) packed for patch_gemm (the prefill path of a 4-bit model:
+ *                  dequantize once, then every prefill kernel runs unchanged): patch_unpack4 into a temporary N x K
+ *                  bf16 buffer, patch_pack with the tile map P4 was built with; synchronises `stream`; *out is the
+ *                  caller's to free (patch_free); PATCH_ERR_ALLOC when the temporary does not fit
  *   patch_packed4_bytes  codes + positions + scales, without alignment padding
  * Errors as for their bf16 counterparts.
  */
@@ -295,6 +299,7 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
 patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream);
 patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* const* P, void* const* Y, int count, void* stream);
 patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream);
+patch_status patch_pack_from4(const patch_packed4* P4, void* stream, patch_packed** out);
 size_t patch_packed4_bytes(const patch_packed4* P);
 patch_status patch_packed4_dims(const patch_packed4* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles);
 void patch_free4(patch_packed4* P);

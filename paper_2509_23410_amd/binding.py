@@ -21,7 +21,7 @@ EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_tune_all",
     "patch_tune_bucket", "patch_tune_table_create", "patch_tune_table_destroy", "patch_tune_table_size", "patch_tune_table_put",
     "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
-    "patch_pack4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
+    "patch_pack4", "patch_pack_from4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
@@ -100,6 +100,8 @@ def lib() -> ctypes.CDLL:
         L.patch_pack4.restype = ci
         L.patch_gemm4.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm4.restype = ci
+        L.patch_pack_from4.argtypes = [vp, vp, ctypes.POINTER(vp)]
+        L.patch_pack_from4.restype = ci
         L.patch_gemm4_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
         L.patch_gemm4_many.restype = ci
         L.patch_unpack4.argtypes = [vp, vp, vp, vp, vp]
@@ -387,6 +389,13 @@ def patch_pack4(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> 
     out = ctypes.c_void_p(0)
     _check(lib().patch_pack4(_ptr(W_hat), N, K, tm.ctypes.data, tile, stream, ctypes.byref(out)), "patch_pack4")
     return Packed4(out.value)
+
+
+def patch_pack_from4(P4: Packed4, stream: int = 0) -> Packed:
+    """The dequantized weight of a 4-bit storage packed for ``patch_gemm`` (dequantize once for prefill)."""
+    out = ctypes.c_void_p(0)
+    _check(lib().patch_pack_from4(P4.handle, stream, ctypes.byref(out)), "patch_pack_from4")
+    return Packed(out.value)
 
 
 def patch_gemm4(X, M: int, P: Packed4, Y, stream: int = 0) -> None:

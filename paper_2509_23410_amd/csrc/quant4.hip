@@ -499,6 +499,7 @@ struct patch_packed4 {
     uint8_t* d_payload = nullptr;   // codes and positions
     uint16_t* d_scales = nullptr;   // N x Tk bf16, strip-major
     uint32_t* d_table = nullptr;
+    std::vector<uint8_t> tile_map;  // host copy, 1 = dense
     int n_cus = 256;
 };
 
@@ -525,10 +526,11 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
     P->Tn = (int)(N / tile); P->Tk = (int)(K / tile);
     const size_t T = (size_t)P->Tn * (size_t)P->Tk;
     std::vector<uint32_t> table;
-    try { table.resize(T); } catch (...) { delete P; return PATCH_ERR_ALLOC; }
+    try { table.resize(T); P->tile_map.resize(T); } catch (...) { delete P; return PATCH_ERR_ALLOC; }
     uint64_t off = 0;
     for (size_t i = 0; i < T; ++i) {
         const bool sparse = tile_map[i] == 0;
+        P->tile_map[i] = sparse ? 0 : 1;
         table[i] = make_entry(off, sparse);
         off += sparse ? q4_sparse_tile(tile) : q4_dense_tile(tile);
         P->algorithmic_bytes += sparse ? q4_sparse_codes(tile) + q4_sparse_pos(tile) + 2 * tile : q4_dense_codes(tile) + 2 * tile;
@@ -659,6 +661,21 @@ patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* con
 patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream) {
     if (!P || !Y) return PATCH_ERR_ARG;
     return patch_gemm4_many(X, M, &P, &Y, 1, stream);
+}
+
+patch_status patch_pack_from4(const patch_packed4* P4, void* stream, patch_packed** out) {
+    if (!P4 || !out) return PATCH_ERR_ARG;
+    uint16_t* W_deq = nullptr;
+    if (hipMalloc(&W_deq, (size_t)P4->N * (size_t)P4->K * sizeof(uint16_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        return PATCH_ERR_ALLOC;
+    }
+    patch_status st = patch_unpack4(P4, W_deq, nullptr, nullptr, stream);
+    // patch_pack runs on the same stream behind the dequantization and waits for the stream before it returns
+    if (st == PATCH_OK) st = patch_pack(W_deq, P4->N, P4->K, P4->tile_map.data(), P4->tile, stream, out);
+    else (void)hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    (void)hipFree(W_deq);
+    return st;
 }
 
 size_t patch_packed4_bytes(const patch_packed4* P) { return P ? P->algorithmic_bytes : 0; }

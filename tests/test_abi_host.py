@@ -78,6 +78,8 @@ def test_argument_errors_without_device():
     assert L.patch_gemm4_many(fake, 1, two, two, 0, 0) == B.ERR_ARG   # count out of range
     assert L.patch_gemm4_many(fake, 1, two, two, 9, 0) == B.ERR_ARG
     assert L.patch_unpack4(0, fake, None, None, 0) == B.ERR_ARG
+    assert L.patch_pack_from4(0, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_pack_from4(fake, 0, None) == B.ERR_ARG
     assert L.patch_packed4_bytes(0) == 0
     assert L.patch_packed4_dims(0, None, None, None, None) == B.ERR_ARG
     L.patch_free4(0)

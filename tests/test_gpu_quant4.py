@@ -104,6 +104,30 @@ def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
     p.P.close()
 
 
+@pytest.mark.parametrize("N,K,t,f,M", [(512, 512, 64, 0.5, 70), (768, 640, 128, 0.5, 300)])
+def test_dequantize_once_for_prefill(dev, N, K, t, f, M):
+    """patch_pack_from4: the bf16 packing of the dequantized weight - its canonical export bit-equal to the oracle's
+    packing of the oracle's dequantized weight, the prefill product within the bound, and the decode-shaped 4-bit
+    product of the same rows within the bound of the same reference."""
+    c = synth.make_case("from4", N, K, M, t, f, seed=26)
+    p = Prepared4(c, dev)
+    P = B.patch_pack_from4(p.P, stream())
+    vals_o, meta_o = oracle.pack(p.W_deq_o, c.tile_map, t)
+    vals, meta = B.patch_export_canonical(P)
+    assert np.array_equal(vals, vals_o) and np.array_equal(meta, meta_o)
+    assert P.dims() == (N, K, t, int((c.tile_map == 0).sum())) and np.array_equal(P.tile_map(), c.tile_map)
+    Yo = oracle.gemm(c.X, vals_o, meta_o, N, K, c.tile_map, t)
+    X = to_dev_bf16(c.X, dev)
+    Y = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+    B.patch_gemm(X, M, P, Y, stream(), path=B.PATH_PREFILL)
+    torch.cuda.synchronize()
+    xn, wn = row_norms(c.X), row_norms(p.W_deq_o)
+    check_elements(Y.cpu().numpy(), Yo, xn, wn, K, f"prefill from 4-bit N={N} M={M}")
+    check_elements(p.gemm(c.X), Yo, xn, wn, K, f"4-bit product N={N} M={M}")
+    P.close()
+    p.P.close()
+
+
 def test_weights_sharing_x_in_one_launch(dev):
     """patch_gemm4_many: weights of different N and maps against one X, within the bound of the oracle and - at these
     sizes and up to 16 rows, where the single and the fused launches split K over the same number of wavefronts -
