@@ -158,6 +158,72 @@ def test_weights_sharing_x_in_one_launch(dev):
         p.P.close()
 
 
+def test_hip_graph_replay_matches_eager(dev):
+    """The 4-bit product allocates nothing, never synchronises and records no memset: a HIP graph captured over a single
+    launch, a pass of 40 rows and a fused launch replays bit-equal to the eager results, several times, with eager
+    work between the replays."""
+    K, t = 1024, 128
+    cases = [synth.make_case(f"graph4_{i}", N, K, 40, t, f, seed=27) for i, (N, f) in enumerate([(768, 0.5), (256, 1.0)])]
+    preps = [Prepared4(c, dev) for c in cases]
+    X = to_dev_bf16(cases[0].X, dev)
+
+    def run(st, outs):
+        B.patch_gemm4(X, 1, preps[0].P, outs[0], st)
+        B.patch_gemm4(X, 40, preps[0].P, outs[1], st)
+        B.patch_gemm4_many(X, 16, [p.P for p in preps], [outs[2], outs[3]], st)
+
+    shapes = [(1, 768), (40, 768), (16, 768), (16, 256)]
+    eager = [torch.full(sh, float("nan"), device=dev, dtype=torch.float32) for sh in shapes]
+    run(stream(), eager)                              # also the warm-up every kernel needs before a capture
+    torch.cuda.synchronize()
+    outs = [torch.full_like(Y, float("nan")) for Y in eager]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run(side.cuda_stream, outs)
+    for rep in range(3):
+        for Y in outs:
+            Y.fill_(float("nan"))
+        assert np.isfinite(preps[1].gemm(cases[0].X[:7])).all()   # eager work (and a synchronisation) between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (Y, E) in enumerate(zip(outs, eager)):
+            assert torch.equal(Y, E), f"replay {rep}: output {i} differs from the eager launch"
+    check_elements(outs[1].cpu().numpy(), preps[0].oracle_gemm(cases[0].X), row_norms(cases[0].X), row_norms(preps[0].W_deq_o), K, "graph replay, 40 rows")
+    for p in preps:
+        p.P.close()
+
+
+def test_13b_shapes_sampled(dev):
+    """The 13B stack's gate projection (13824 x 5120: three strips per workgroup, fewer workgroups than compute units'
+    worth of strips) and down projection (5120 x 13824: 216 steps over 16 wavefronts) from the 4-bit storage at M = 1, 16
+    and 48: storage bit-exact, sampled outputs against the definition on the oracle's dequantized weight."""
+    fr = synth.layer_fractions(0, 40)
+    for li, (N, K) in [(17, (13824, 5120)), (29, (5120, 13824))]:
+        f = float(fr[li])
+        print(f"4-bit 13B layer {li} N={N} K={K} f={f:.3f}", flush=True)
+        c = synth.make_case(f"l13b_q4_{li}", N, K, 48, 128, f, seed=28)
+        p = Prepared4(c, dev)
+        W_deq, codes, scales = p.unpack()
+        assert np.array_equal(scales, p.scales_o) and np.array_equal(codes, p.codes_o) and np.array_equal(W_deq, p.W_deq_o)
+        del W_deq, codes, scales
+        rng = np.random.default_rng(li)
+        wn = row_norms(p.W_deq_o)
+        for M in (1, 16, 48):
+            Xb = c.X[:M]
+            Y = p.gemm(Xb)
+            assert np.isfinite(Y).all()
+            mn = np.stack([rng.integers(0, M, 2048), rng.integers(0, N, 2048)], axis=1).astype(np.int64)
+            ref = oracle.gemm_points(Xb, p.W_deq_o, mn)
+            got = Y[mn[:, 0], mn[:, 1]].astype(np.float64)
+            bound = 2.0 * np.sqrt(K) * 2.0 ** -24 * row_norms(Xb)[mn[:, 0]] * wn[mn[:, 1]]
+            d = np.abs(got - ref)
+            print(f"  4-bit 13B {N}x{K} M={M}: max err/bound={float((d / bound).max()):.3f}", flush=True)
+            assert (d <= bound).all() and np.linalg.norm(got - ref) <= 2e-5 * np.linalg.norm(ref)
+        p.P.close()
+
+
 def test_special_rows_ties_and_rejection(dev):
     """An all-zero row (scale 0, codes 0), a row whose largest weight is negative, weights at exact half steps
     (ties go to the even code), and groups with fewer than two nonzeros in a 2:4 tile."""
