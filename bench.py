@@ -546,12 +546,15 @@ def main():
         best_rate = {}
         for label, ops in (("random_operands", torch.randn(B.PROBE_OPERAND_BYTES // 2, device=dev).to(torch.bfloat16)),
                            ("zero_operands", torch.zeros(B.PROBE_OPERAND_BYTES // 2, device=dev, dtype=torch.bfloat16))):
-            for kind, name, flop in ((0, "dense_mfma_16x16x32_bf16", 16384.0), (1, "sparse_smfmac_16x16x64_bf16", 32768.0)):
+            for kind, name, flop in ((0, "dense_mfma_16x16x32_bf16", 16384.0), (1, "sparse_smfmac_16x16x64_bf16", 32768.0),
+                                     (2, "dense_mfma_32x32x16_bf16_unused_shape", 16384.0), (3, "sparse_smfmac_32x32x32_bf16_unused_shape", 32768.0)):
+                if kind >= 2 and label != "random_operands":
+                    continue
                 for wps in (1, 2):      # wavefronts per SIMD
                     fn = lambda _i, kind=kind, ops=ops, wps=wps: B.patch_probe_matrix_rate(kind, ops, wps * n_cus, iters, res, stream)
                     timed(fn, 2)
                     t_best = min(timed(fn, 3) / 3 for _ in range(3))
-                    rate = round(wps * n_cus * 4 * iters * 16 * flop / t_best / 1e12, 1)
+                    rate = round(wps * n_cus * 4 * iters * 16 * flop / t_best / 1e12, 1)   # a round is 16 x flop for every kind
                     ceil[f"{name}_{label}_{wps}_per_simd_TFLOPs"] = rate
                     best_rate[(kind, label)] = max(best_rate.get((kind, label), 0.0), rate)
         P_d, P_s = best_rate[(0, "random_operands")], best_rate[(1, "random_operands")]

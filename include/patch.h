@@ -311,7 +311,9 @@ void patch_free4(patch_packed4* P);
  *   patch_probe_matrix_rate  `workgroups` workgroups of 4 wavefronts each run `iters` rounds of 16 independent matrix
  *                            instructions on register operands: kind 0 = v_mfma_f32_16x16x32_bf16 (16384 flop each),
  *                            kind 1 = v_smfmac_f32_16x16x64_bf16 (32768 dense-equivalent flop each).  Total instructions
- *                            = workgroups * 4 * iters * 16.  operands: DEVICE, 16-byte aligned, at least
+ *                            = workgroups * 4 * iters * 16.  kind 2 = v_mfma_f32_32x32x16_bf16 (32768 flop) and kind 3 =
+ *                            v_smfmac_f32_32x32x32_bf16 (65536 dense-equivalent flop), the 32 x 32 shapes the product
+ *                            kernels do not use: rounds of 8, i.e. the same flops per round.  operands: DEVICE, 16-byte aligned, at least
  *                            PATCH_PROBE_OPERAND_BYTES of bf16 data (random data gives the rate under realistic
  *                            switching activity; zeros give the clock-unconstrained rate); out: DEVICE,
  *                            workgroups * 256 floats (keeps the results alive).

@@ -1,6 +1,7 @@
 // Measured ceilings of the part, for the roofline figures the benchmark prints next to the product kernels:
 //   matrix_rate_kernel  register-resident loops of the two matrix instructions the product kernels use
-//                       (v_mfma_f32_16x16x32_bf16, v_smfmac_f32_16x16x64_bf16), no memory traffic inside the loop
+//                       (v_mfma_f32_16x16x32_bf16, v_smfmac_f32_16x16x64_bf16) and of their 32 x 32 shapes, no memory
+//                       traffic inside the loop
 //   stream_read_kernel  128-bit streaming read of a buffer (the HBM bound of the decode path)
 // They compute nothing of the method; the caller times them with events on the stream it passes.
 #include <hip/hip_runtime.h>
@@ -22,6 +23,10 @@ union ClB { cl_u32x4 raw[2]; cl_bf16x8 h[2]; cl_bf16x16 v; };
 // `operands` (the caller fills it with random bf16 so that consecutive instructions see different data: the clock
 // under matrix load depends on how many bits toggle) and runs `iters` rounds of 16 independent instructions.
 // KIND 0: dense 16x16x32, 16384 flop per instruction; KIND 1: 2:4 16x16x64, 32768 dense-equivalent flop.
+// KIND 2 / 3: the 32 x 32 shapes of the same two instructions (v_mfma_f32_32x32x16_bf16, 32768 flop, and
+// v_smfmac_f32_32x32x32_bf16, 65536 dense-equivalent flop; 8 per round on four 16-register accumulators, two
+// consecutive instructions sharing the B operand): half the operand registers read per flop - the product kernels do not
+// use them (their layout is built on the 16 x 16 shapes); the figure says what that choice costs under the power limit.
 template <int KIND>
 __global__ __launch_bounds__(256) void matrix_rate_kernel(const cl_u32x4* __restrict__ operands, int iters, float* __restrict__ out) {
     const int tid = threadIdx.x;
@@ -59,8 +64,24 @@ __global__ __launch_bounds__(256) void matrix_rate_kernel(const cl_u32x4* __rest
 // instruction issued at about 60 % of this rate)
 #define PATCH_CL_D(J, A, BH) "v_mfma_f32_16x16x32_bf16 a[4*" #J ":4*" #J "+3], %[a" #A "], %[b" #BH "], a[4*" #J ":4*" #J "+3]\n\t"
 #define PATCH_CL_S(J, A, B_) "v_smfmac_f32_16x16x64_bf16 a[4*" #J ":4*" #J "+3], %[a" #A "], %[b" #B_ "], %[i" #A "]\n\t"
+#define PATCH_CL_D32(J, A, BH) "v_mfma_f32_32x32x16_bf16 a[16*" #J ":16*" #J "+15], %[a" #A "], %[b" #BH "], a[16*" #J ":16*" #J "+15]\n\t"
+#define PATCH_CL_S32(J, A, B_) "v_smfmac_f32_32x32x32_bf16 a[16*" #J ":16*" #J "+15], %[a" #A "], %[b" #B_ "], %[i" #A "]\n\t"
     for (int it = 0; it < iters; ++it) {
-        if (KIND == 0) {
+        if (KIND == 2) {
+            asm volatile(PATCH_CL_D32(0, 0, 00) PATCH_CL_D32(1, 1, 00) PATCH_CL_D32(2, 2, 11) PATCH_CL_D32(3, 3, 11)
+                         PATCH_CL_D32(0, 0, 20) PATCH_CL_D32(1, 1, 20) PATCH_CL_D32(2, 2, 31) PATCH_CL_D32(3, 3, 31)
+                         :
+                         : [a0] "v"(a[0].v), [a1] "v"(a[1].v), [a2] "v"(a[2].v), [a3] "v"(a[3].v), [b00] "v"(b[0].h[0]),
+                           [b11] "v"(b[1].h[1]), [b20] "v"(b[2].h[0]), [b31] "v"(b[3].h[1])
+                         : PATCH_CL_CLOBBER);
+        } else if (KIND == 3) {
+            asm volatile(PATCH_CL_S32(0, 0, 0) PATCH_CL_S32(1, 1, 0) PATCH_CL_S32(2, 2, 1) PATCH_CL_S32(3, 3, 1)
+                         PATCH_CL_S32(0, 0, 2) PATCH_CL_S32(1, 1, 2) PATCH_CL_S32(2, 2, 3) PATCH_CL_S32(3, 3, 3)
+                         :
+                         : [a0] "v"(a[0].v), [a1] "v"(a[1].v), [a2] "v"(a[2].v), [a3] "v"(a[3].v), [b0] "v"(b[0].v), [b1] "v"(b[1].v),
+                           [b2] "v"(b[2].v), [b3] "v"(b[3].v), [i0] "v"(idx[0]), [i1] "v"(idx[1]), [i2] "v"(idx[2]), [i3] "v"(idx[3])
+                         : PATCH_CL_CLOBBER);
+        } else if (KIND == 0) {
             asm volatile(PATCH_CL_D(0, 0, 00) PATCH_CL_D(1, 1, 00) PATCH_CL_D(2, 2, 00) PATCH_CL_D(3, 3, 00)
                          PATCH_CL_D(4, 0, 11) PATCH_CL_D(5, 1, 11) PATCH_CL_D(6, 2, 11) PATCH_CL_D(7, 3, 11)
                          PATCH_CL_D(8, 0, 20) PATCH_CL_D(9, 1, 20) PATCH_CL_D(10, 2, 20) PATCH_CL_D(11, 3, 20)
@@ -96,6 +117,8 @@ __global__ __launch_bounds__(256) void matrix_rate_kernel(const cl_u32x4* __rest
 #undef PATCH_CL_READ
 #undef PATCH_CL_D
 #undef PATCH_CL_S
+#undef PATCH_CL_D32
+#undef PATCH_CL_S32
 #undef PATCH_CL_ZERO4
 #undef PATCH_CL_CLOBBER
 }
@@ -126,16 +149,18 @@ extern "C" {
 
 patch_status patch_probe_matrix_rate(int kind, const void* operands, size_t operand_bytes, int workgroups, int iters, void* out,
                                      size_t out_bytes, void* stream) {
-    if (!operands || !out || workgroups < 1 || workgroups > 65536 || iters < 1 || (kind != 0 && kind != 1)) return PATCH_ERR_ARG;
+    if (!operands || !out || workgroups < 1 || workgroups > 65536 || iters < 1 || kind < 0 || kind > 3) return PATCH_ERR_ARG;
     if ((reinterpret_cast<uintptr_t>(operands) & 15u) || (reinterpret_cast<uintptr_t>(out) & 3u)) return PATCH_ERR_ARG;
     if (operand_bytes < PATCH_PROBE_OPERAND_BYTES || out_bytes < (size_t)workgroups * 256 * sizeof(float)) return PATCH_ERR_SIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (kind == 0)
-        hipLaunchKernelGGL(patch::matrix_rate_kernel<0>, dim3(workgroups), dim3(256), 0, s, static_cast<const patch::cl_u32x4*>(operands), iters,
-                           static_cast<float*>(out));
-    else
-        hipLaunchKernelGGL(patch::matrix_rate_kernel<1>, dim3(workgroups), dim3(256), 0, s, static_cast<const patch::cl_u32x4*>(operands), iters,
-                           static_cast<float*>(out));
+    const patch::cl_u32x4* ops = static_cast<const patch::cl_u32x4*>(operands);
+    float* o = static_cast<float*>(out);
+    switch (kind) {
+        case 0: hipLaunchKernelGGL(patch::matrix_rate_kernel<0>, dim3(workgroups), dim3(256), 0, s, ops, iters, o); break;
+        case 1: hipLaunchKernelGGL(patch::matrix_rate_kernel<1>, dim3(workgroups), dim3(256), 0, s, ops, iters, o); break;
+        case 2: hipLaunchKernelGGL(patch::matrix_rate_kernel<2>, dim3(workgroups), dim3(256), 0, s, ops, iters, o); break;
+        default: hipLaunchKernelGGL(patch::matrix_rate_kernel<3>, dim3(workgroups), dim3(256), 0, s, ops, iters, o); break;
+    }
     return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
 }
 

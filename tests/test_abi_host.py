@@ -61,7 +61,7 @@ def test_argument_errors_without_device():
     assert L.patch_tune(fake, 1, 0, fake, None, 0, None, 5, None, None) == B.ERR_ARG
     assert L.patch_tune_all(fake, 1, 0, fake, None, 0, None, 5, None, 0, None) == B.ERR_ARG
     assert L.patch_gemm_static(fake, 1, 0, fake, 0) == B.ERR_ARG
-    assert L.patch_probe_matrix_rate(2, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_probe_matrix_rate(4, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
     assert L.patch_probe_stream_read(fake, 1024, 1, 100, fake, 1 << 20, 0) == B.ERR_ARG
     # 4-bit storage
     assert L.patch_pack4(0, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
