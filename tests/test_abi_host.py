@@ -186,3 +186,26 @@ def test_kernels_with_untracked_loads_do_not_spill(source, kernel):
         assert get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory"
         assert get("VGPRs") <= 256 and get("AGPRs") == 0, name
     assert seen >= 4, f"expected several instantiations of {kernel}, saw {seen}"
+
+
+def test_no_flat_memory_instructions(tmp_path):
+    """Every pointer the kernels dereference is device memory.  A pointer that reached a kernel inside a by-value struct
+    or through scalar selects loses its address space unless the code restores it; the compiler then emits flat
+    instructions (and reads read-only tables with vector loads), which cost the 4-bit decode launch a quarter of its
+    time.  The generated assembly of every source must contain none."""
+    import subprocess
+    from paper_2509_23410_amd import build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    for src in build.sources():
+        out = tmp_path / (os.path.basename(src) + ".s")
+        cmd = [hipcc, *[f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")], "-S", "--cuda-device-only",
+               "-I", os.path.join(ROOT, "include"), "-I", build.CSRC, "-o", str(out), src]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert r.returncode == 0, r.stdout[-2000:]
+        text = out.read_text()
+        flat = [l.strip() for l in text.splitlines() if re.match(r"\s+flat_(load|store|atomic)", l)]
+        assert not flat, f"{os.path.basename(src)}: {len(flat)} flat instructions, e.g. {flat[0]}"
+        if os.path.basename(src) == "quant4.hip":
+            # table entries of the 4-bit product kernel come through scalar loads
+            body = re.search(r"^_ZN5patch14decode4_kernelILi128ELi1ELi1ENS_5Q4OneE.*?^\.Lfunc_end", text, re.S | re.M)
+            assert body and len(re.findall(r"\bs_load_dword\b", body.group(0))) >= 2
