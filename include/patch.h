@@ -61,8 +61,8 @@ typedef struct {
                  /* workspace a part-filled last round of at most half the chip is split on its own), */
                  /* 1 = no split.  Never more slices than the workspace holds: without one, no split. */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
-                 /* 2 = 256 x 256 LDS-staged kernel, 3 = 256 x 256 weights-in-registers kernel (the      */
-                 /* default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
+                 /* 2 = 256 x 256 LDS-staged kernel (the default for tile 64), 3 = 256 x 256 weights-in- */
+                 /* registers kernel (the default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
                  /* features per wavefront (its split_k = K chunks over `workspace`, 0 = auto; the       */
                  /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 5120, and */
@@ -163,7 +163,7 @@ patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, 
  *   prefill path, tile 128: the execution tiles 256 x 256 with one wavefront per SIMD (default), 256 x 256 with two
  *     (variant 2) and the small 128 x 128 tile (variant 1; Appendix O reports that small execution tiles under-use
  *     the matrix units - it is timed so that the report shows it), and the K-split counts the workspace allows;
- *   prefill path, tile 64: the 128 x 128 kernel.
+ *   prefill path, tile 64: the 256 x 256 LDS-staged kernel (default) and the small 128 x 128 tile.
  *   X, Y       as for patch_gemm (Y is overwritten several times; after patch_tune it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1

@@ -390,7 +390,8 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
             for (int sk : {2, 3, 4, 6, 8, 12, 16})
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 2 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
     } else {
-        add(PATCH_PATH_PREFILL, 1, 1, false);
+        add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, two wavefronts per SIMD (the tile-64 default)
+        add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
     }
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));

@@ -160,22 +160,25 @@ __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restr
 }
 
 // ------------------------------------------------------------------------------------------------------
-// Main prefill kernel (tile = 128): 256 features x 256 rows per workgroup, 8 wavefronts, 64-column K-steps,
-// LDS double buffer filled by direct global->LDS loads.
+// LDS-staged prefill kernel (tile = 128 or 64): 256 features x 256 rows per workgroup, 8 wavefronts, 64-column
+// K-steps, LDS double buffer filled by direct global->LDS loads.
 //
-//   wavefront w < 4 : tile row 0 of the block (features 0..127),   rows 64 w .. 64 w + 63
-//   wavefront w >= 4: tile row 1 of the block (features 128..255), rows 64 (w-4) ..
-// The two wavefronts that share a SIMD (w and w + 4) thus always own DIFFERENT tile rows, so every SIMD
+//   wavefront w < 4 : features 0..127 of the block,   rows 64 w .. 64 w + 63
+//   wavefront w >= 4: features 128..255 of the block, rows 64 (w-4) ..
+// With tile 128 the two wavefronts that share a SIMD (w and w + 4) always own DIFFERENT tile rows, so every SIMD
 // carries cost(tile row 0) + cost(tile row 1) matrix cycles per K-step whatever the tile types are: the
-// dense/2:4 mix cannot unbalance the workgroup between two barriers.
+// dense/2:4 mix cannot unbalance the workgroup between two barriers.  With tile 64 a wavefront's 128 features
+// are two tile rows (its 32-feature blocks 0-1 and 2-3), each with its own type, and every K-step is a new tile.
 //
-// LDS per stage: weight fragments [tile row][strip][2048 B] (a 2:4 strip uses the first 1024 B), X tile
-// 256 rows x 128 B with the XOR swizzle of xs_off(); plus the position words of the current 2:4 tiles.
+// LDS per stage: weight fragments [strip of the block][2048 B] (a 2:4 strip uses the first 1024 B), X tile
+// 256 rows x 128 B with the XOR swizzle of xs_off(); plus the position words of the current 2:4 tiles
+// (tile 128: 2 KB per tile row, kept for the tile's two K-steps in a buffer chosen by the tile's parity;
+// tile 64: 512 B per tile row in a 1 KB slot, per stage).
 // ------------------------------------------------------------------------------------------------------
 constexpr int kPfBN = 256, kPfBM = 256;
 constexpr int kPfAStage = 2 * 8 * kDenseFragBytes;   // 32 KB
 constexpr int kPfBStage = kPfBM * 128;               // 32 KB
-constexpr int kPfMetaBuf = 2 * 2048;                 // two tile rows x 2 KB of position words (tile 128)
+constexpr int kPfMetaBuf = 2 * 2048;                 // position words: two tile rows x 2 KB (tile 128), four x 1 KB (tile 64)
 constexpr int kPfLds = 2 * kPfAStage + 2 * kPfBStage + 2 * kPfMetaBuf;
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -214,18 +217,32 @@ __device__ __forceinline__ void mma_step(f32x16& c0, f32x16& c1, const bf16x8& a
         : "scc");
 }
 
-__global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
-                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                           int Tk, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
-    constexpr int TILE = 128, KPT = 2;
+// Table entries of the (up to four) tile rows of a block at one K-step.  Plain members, never indexed at run time: an
+// array that is indexed by a wavefront-dependent value lives in scratch memory, and anything that makes the register
+// allocator spill or copy around the matrix instructions of mma_step (which it cannot see) stores accumulators that
+// are still being written.  tests/test_abi_host.py checks that the kernel uses no scratch memory at all.
+struct PfEntries {
+    uint32_t v0, v1, v2, v3;
+};
+
+template <int TILE>
+__global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
+                                                          const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
+                                                          int Tk, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
+    constexpr int KPT = TILE / kStepCols;        // K-steps per tile: 2 or 1
+    constexpr int SPT = TILE / kStripRows;       // strips per tile: 8 or 4
+    constexpr int NR = kPfBN / TILE;             // tile rows per block: 2 or 4
+    constexpr int WR = NR / 2;                   // tile rows per wavefront: 1 or 2
+    constexpr int ESZ = 2 * KPT;                 // bytes of position bits per lane and strip
+    constexpr int MROW = TILE == 128 ? 2048 : 1024;   // LDS bytes per tile row of position words
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    uint8_t* const As = lds;                                  // [stage][tile row][strip][2048]
+    uint8_t* const As = lds;                                  // [stage][strip of the block][2048]
     uint8_t* const Bs = lds + 2 * kPfAStage;                  // [stage][256 rows][128 B] swizzled
-    uint8_t* const Ms = lds + 2 * kPfAStage + 2 * kPfBStage;  // [tile parity][tile row][2048]
+    uint8_t* const Ms = lds + 2 * kPfAStage + 2 * kPfBStage;  // [buffer][tile row][MROW]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = w >> 2, wm = w & 3;  // tile row of the block, 64-row group
+    const int r = w >> 2, wm = w & 3;  // 128-feature half of the block, 64-row group
 
     // ---- block -> (n, m) tile of the output.  Consecutive blocks go to different XCDs (hardware round-robin),
     // each with its own L2, so every XCD gets a contiguous run of the tile order below, and that order walks
@@ -256,12 +273,12 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         }
     }
     const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * kPfBM;
-    const bool row_live = n0 + 128 * r < N;  // N is a multiple of 128, not necessarily of 256
-    const int tn = (int)(n0 / TILE) + (row_live ? r : 0);
-    const uint32_t* trow0 = table + (int64_t)(n0 / TILE) * Tk;
-    const bool two_rows = n0 + 128 < N;
-    const uint32_t* trow1 = trow0 + (two_rows ? Tk : 0);
-    const uint32_t* trow_mine = table + (int64_t)tn * Tk;
+    // N is a multiple of the tile, not necessarily of 256: the last block has `live` tile rows.  Table rows of
+    // the others alias the last live one (valid addresses); their weights are not copied and nothing of theirs is stored.
+    const int live = (int)((N - n0) / TILE) < NR ? (int)((N - n0) / TILE) : NR;
+    const uint32_t* trow[NR];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) trow[i] = table + ((int64_t)(n0 / TILE) + (i < live ? i : live - 1)) * Tk;
 
     // ---- per-lane source pointers for the X tile copy: wavefront w copies 1 KB pieces w, w+8, w+16, w+24
     const uint8_t* xsrc[4];
@@ -274,25 +291,45 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8);
     }
 
-    // Fill one LDS stage with K-step ks; e0 / e1 are the table entries of the two tile rows at that step.
-    auto prefetch = [&](int ks, int stage, uint32_t e0, uint32_t e1) {
-        const int tk = ks >> 1, j = ks & 1;
-        // weights: wavefront w copies strip w of both tile rows
+    // Fill one LDS stage with K-step ks; e[i] = table entry of tile row i of the block at that step.
+    auto prefetch = [&](int ks, int stage, const PfEntries e) {
+        const int tk = ks / KPT, j = ks % KPT;
+        // weights: wavefront w copies strips w and w + 8 of the block's 16
 #pragma unroll
-        for (int rr = 0; rr < 2; ++rr) {
-            if (rr == 1 && !two_rows) break;
-            const uint32_t e = rr ? e1 : e0;
-            const uint8_t* tb = payload + entry_offset(e);
-            uint8_t* dst = As + stage * kPfAStage + (rr * 8 + w) * kDenseFragBytes;
-            if (entry_sparse(e)) {
-                g2l16(tb + (size_t)(w * KPT + j) * kSparseFragBytes + lane * 16, dst);
-                if (j == 0 && w < 2) {  // the tile's 2 KB of position words, once per tile
-                    g2l16(tb + sparse_vals_bytes(TILE) + w * 1024 + lane * 16, Ms + (tk & 1) * kPfMetaBuf + rr * 2048 + w * 1024);
-                }
+        for (int h = 0; h < 2; ++h) {
+            // strip w + 8 h of the block: tile row h (tile 128) or r + 2 h (tile 64) - a choice between two entries at most
+            const int sidx = w + 8 * h, tr = sidx / SPT, st = sidx % SPT;
+            if (tr >= live) continue;
+            const uint32_t ev = TILE == 128 ? (h ? e.v1 : e.v0) : (h ? (r ? e.v3 : e.v2) : (r ? e.v1 : e.v0));
+            const uint8_t* tb = payload + entry_offset(ev);
+            uint8_t* dst = As + stage * kPfAStage + sidx * kDenseFragBytes;
+            if (entry_sparse(ev)) {
+                g2l16(tb + (size_t)(st * KPT + j) * kSparseFragBytes + lane * 16, dst);
             } else {
-                const uint8_t* f = tb + (size_t)(w * KPT + j) * kDenseFragBytes + lane * 16;
+                const uint8_t* f = tb + (size_t)(st * KPT + j) * kDenseFragBytes + lane * 16;
                 g2l16(f, dst);
                 g2l16(f + 1024, dst + 1024);
+            }
+        }
+        // position words of the 2:4 tiles
+        if constexpr (TILE == 128) {
+            // 2 KB per tile, once per tile (its first K-step), by wavefronts 0 and 1
+            if (j == 0 && w < 2) {
+#pragma unroll
+                for (int rr = 0; rr < NR; ++rr) {
+                    const uint32_t ev = rr ? e.v1 : e.v0;
+                    if (rr < live && entry_sparse(ev))
+                        g2l16(payload + entry_offset(ev) + sparse_vals_bytes(TILE) + w * 1024 + lane * 16,
+                              Ms + (tk & 1) * kPfMetaBuf + rr * MROW + w * 1024);
+                }
+            }
+        } else {
+            // 512 B per tile, every step, tile row w by wavefront w (the copy moves 1 KB: the second half is the
+            // head of the next tile or the zeroed slack behind the payload, and lands in the unused half of the slot)
+            if (w < NR && w < live) {
+                const uint32_t ev01 = (w & 1) ? e.v1 : e.v0, ev23 = (w & 1) ? e.v3 : e.v2;
+                const uint32_t ev = (w & 2) ? ev23 : ev01;
+                if (entry_sparse(ev)) g2l16(payload + entry_offset(ev) + sparse_vals_bytes(TILE) + lane * 16, Ms + stage * kPfMetaBuf + w * MROW);
             }
         }
         // X tile
@@ -309,23 +346,23 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
     const int i32 = lane & 31, q = lane >> 5;
-    // LDS byte offsets of this lane inside a strip's fragment; a 32-feature block a covers strips 2a, 2a+1
+    // LDS byte offsets of this lane inside a strip's fragment; a 32-feature block a covers strips 2a, 2a+1 of the
+    // wavefront's eight
     const int lane_frag = ((i32 >> 4) * kDenseFragBytes) + (16 * q + (i32 & 15)) * 16;
-    const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * 4;
-    // One K-step: wait for the stage, refill the other one, multiply.  e_mine: table entry of this wavefront's
-    // tile at step ks; (pf_ks, pf_e0, pf_e1): the step to fetch into the idle stage and its entries.
-    auto step = [&](int ks, uint32_t e_mine, int pf_ks, uint32_t pf_e0, uint32_t pf_e1) {
+    const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * ESZ;
+    // One K-step: wait for the stage, refill the other one, multiply.  e_mine[i]: table entry of this wavefront's
+    // i-th tile row at step ks; (pf_ks, pf_e): the step to fetch into the idle stage and its entries.
+    auto step = [&](int ks, uint32_t e_mine0, uint32_t e_mine1, int pf_ks, const PfEntries pf_e) {
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        prefetch(pf_ks, stage ^ 1, pf_e0, pf_e1);
-        const int tk = ks >> 1, j = ks & 1;
-        const int sp = (int)(e_mine & 1u);
+        prefetch(pf_ks, stage ^ 1, pf_e);
+        const int tk = ks / KPT, j = ks % KPT;
         const uint8_t* as = As + stage * kPfAStage + r * 8 * kDenseFragBytes + lane_frag;
         const uint8_t* bs = Bs + stage * kPfBStage;
-        const uint8_t* ms = Ms + (tk & 1) * kPfMetaBuf + r * 2048 + lane_meta;
-        // half-step u of a strip: 2:4 fragment half at u * 512, dense operand pair at u * 1024 and + 512
-        const int ustride = sp ? 512 : 1024;
+        // position words of block a: tile 128: tile row r of buffer tk & 1, strips 2a, 2a+1 of the tile's eight;
+        // tile 64: tile row 2 r + a / 2 of this stage's buffer, strips 2 (a % 2), + 1 of the tile's four
+        const uint8_t* ms = Ms + (TILE == 128 ? (tk & 1) : stage) * kPfMetaBuf + lane_meta;
 
         // X fragments as 8-register pairs: a 2:4 instruction takes a pair, a dense one either half
         B16 xb[2][2];
@@ -343,9 +380,15 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         uint32_t fpw[3];
         auto fetch = [&](int pos, int buf) {
             const int a = pos >> 1, u = pos & 1;
+            const int sp = (int)((WR == 1 || a < 2 ? e_mine0 : e_mine1) & 1u);
+            // half-step u of a strip: 2:4 fragment half at u * 512, dense operand pair at u * 1024 and + 512
+            const int ustride = sp ? 512 : 1024;
             fa0[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride);
             fa1[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride + 512);
-            fpw[buf] = *reinterpret_cast<const uint32_t*>(ms + a * 2 * 64 * 4 + u * 32 * 4);
+            if constexpr (TILE == 128)
+                fpw[buf] = *reinterpret_cast<const uint32_t*>(ms + r * MROW + a * 2 * 64 * ESZ + u * 32 * ESZ);
+            else
+                fpw[buf] = *reinterpret_cast<const uint16_t*>(ms + (2 * r + (a >> 1)) * MROW + (a & 1) * 2 * 64 * ESZ + u * 32 * ESZ);
         };
         fetch(0, 0);
         fetch(1, 1);
@@ -353,59 +396,81 @@ __global__ __launch_bounds__(512) void prefill_kernel_t128(const uint16_t* __res
         for (int pos = 0; pos < 8; ++pos) {
             if (pos + 2 < 8) fetch(pos + 2, (pos + 2) % 3);
             const int a = pos >> 1, u = pos & 1, buf = pos % 3;
-            const int idx = (int)(fpw[buf] >> (16 * j));
+            const int sp = (int)((WR == 1 || a < 2 ? e_mine0 : e_mine1) & 1u);
+            const int idx = TILE == 128 ? (int)(fpw[buf] >> (16 * j)) : (int)fpw[buf];
             mma_step(acc[a][0], acc[a][1], fa0[buf].v, fa1[buf].v, xb[0][u], xb[1][u], idx, sp);
         }
     };
 
     // Table entries are read one tile ahead of their first use, so no step starts by waiting for a scalar load.
-    uint32_t e0 = trow0[0], e1 = trow1[0], em = trow_mine[0];
-    prefetch(0, 0, e0, e1);
+    auto entries = [&](int tk) {
+        PfEntries t;
+        t.v0 = trow[0][tk];
+        t.v1 = trow[1][tk];
+        t.v2 = trow[NR > 2 ? 2 : 0][tk];
+        t.v3 = trow[NR > 2 ? 3 : 0][tk];
+        return t;
+    };
+    PfEntries e = entries(0);
+    prefetch(0, 0, e);
     for (int tk = 0; tk < Tk; ++tk) {
-        const int tkn = (tk + 1 < Tk) ? tk + 1 : tk;
-        const uint32_t e0n = trow0[tkn], e1n = trow1[tkn], emn = trow_mine[tkn];
-        step(2 * tk, em, 2 * tk + 1, e0, e1);
-        // the very last step re-fetches itself into the idle stage: no branch around the loads
-        step(2 * tk + 1, em, (tk + 1 < Tk) ? 2 * tk + 2 : 2 * tk + 1, e0n, e1n);
-        e0 = e0n; e1 = e1n; em = emn;
+        // (the very last step re-fetches itself into the idle stage: no branch around the loads; en = e there)
+        const int more = tk + 1 < Tk ? 1 : 0;
+        const PfEntries en = entries(tk + more);
+        // this wavefront's tile rows: r (tile 128), 2 r and 2 r + 1 (tile 64)
+        const uint32_t em0 = WR == 1 ? (r ? e.v1 : e.v0) : (r ? e.v2 : e.v0), em1 = r ? e.v3 : e.v1;
+        if constexpr (KPT == 2) {
+            step(2 * tk, em0, em1, 2 * tk + 1, e);
+            step(2 * tk + 1, em0, em1, 2 * tk + 1 + more, en);
+        } else {
+            step(tk, em0, em1, tk + more, en);
+        }
+        e = en;
     }
 
     // the idle-stage loads of the last step must land before this workgroup's LDS can be handed on
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // rows of the block past N computed on whatever was in LDS; nothing of theirs is stored
-    if (!row_live) return;
     // the last matrix instructions may still be writing their accumulators: 16-pass results need up to 18 wait
     // states before another unit may read them
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     // acc[a][b][i]: feature n0 + 128 r + 32 a + 8 (i/4) + 4 q + i%4, row m0 + 64 wm + 32 b + i32
+    // (blocks of the last feature block past N computed on whatever was in LDS; nothing of theirs is stored)
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int64_t m = m0 + 64 * wm + 32 * b + i32;
         if (m >= M) continue;
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a) {
+            if (n0 + 128 * r + 32 * a >= N) continue;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
                 store4(Y, m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q, v, ybf16);
             }
+        }
     }
 }
 
-// Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_t128;
-// tile 64 -> prefill_kernel_v0.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_t128, 3 prefill_kernel_wreg
+// Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds;
+// tile 64 -> prefill_kernel_lds.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds, 3 prefill_kernel_wreg
 // (each falling back to the default choice where it does not apply).
+template <int TILE>
+static void launch_prefill_lds(const GemmArgs& a, hipStream_t stream) {
+    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE>),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+    (void)granted;
+    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kPfBM - 1) / kPfBM);
+    const int nblk = tiles_n * tiles_m;
+    const int grid = ((nblk + 7) / 8) * 8;
+    hipLaunchKernelGGL(prefill_kernel_lds<TILE>, dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, tiles_n,
+                       tiles_m, a.Y, a.ybf16);
+}
+
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream) {
     if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, split_k, stream); return; }
-    if (a.tile == 128 && variant != 1) {
-        static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_t128),
-                                                              hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
-        (void)granted;
-        const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kPfBM - 1) / kPfBM);
-        const int nblk = tiles_n * tiles_m;
-        const int grid = ((nblk + 7) / 8) * 8;
-        hipLaunchKernelGGL(prefill_kernel_t128, dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk,
-                           tiles_n, tiles_m, a.Y, a.ybf16);
+    if (variant != 1) {
+        if (a.tile == 128) launch_prefill_lds<128>(a, stream);
+        else launch_prefill_lds<64>(a, stream);
         return;
     }
     dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);

@@ -161,11 +161,15 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
     assert re.search(r"\.agpr_count:\s+256", text)
 
 
-@pytest.mark.parametrize("source,kernel", [("gemm_decode.hip", "decode_kernel"), ("gemm_mid.hip", "mid_kernel")])
-def test_kernels_with_untracked_loads_do_not_spill(source, kernel):
+@pytest.mark.parametrize("source,kernel,at_least", [("gemm_decode.hip", "decode_kernel", 4), ("gemm_mid.hip", "mid_kernel", 4),
+                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2)])
+def test_kernels_with_untracked_loads_do_not_spill(source, kernel, at_least):
     """decode_kernel and mid_kernel issue their loads from asm statements and wait for them in a later one; until
     that wait the destinations must stay where the loads write them.  A spill (or any scratch use) of such a register
-    would store a value that is still in flight, so every instantiation must report none."""
+    would store a value that is still in flight, so every instantiation must report none.  prefill_kernel_lds issues its
+    matrix instructions from asm statements: a spill or a scratch copy of an accumulator behind one of them would store
+    a value the matrix pipe is still writing (seen once: a duplicated loop body made the register allocator spill
+    accumulators, and some outputs came out wrong now and then)."""
     import subprocess
     from paper_2509_23410_amd import build
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -185,7 +189,7 @@ def test_kernels_with_untracked_loads_do_not_spill(source, kernel):
         assert get("VGPRs Spill") == 0 and get("SGPRs Spill") == 0, f"{name} spills"
         assert get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory"
         assert get("VGPRs") <= 256 and get("AGPRs") == 0, name
-    assert seen >= 4, f"expected several instantiations of {kernel}, saw {seen}"
+    assert seen >= at_least, f"expected several instantiations of {kernel}, saw {seen}"
 
 
 def test_no_flat_memory_instructions(tmp_path):

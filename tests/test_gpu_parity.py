@@ -428,6 +428,26 @@ def test_13b_fused_qkv_with_per_matrix_fractions(dev):
         p.P.close()
 
 
+@pytest.mark.parametrize("N,K,M,f", [(2112, 1088, 700, 0.6), (320, 2048, 257, 1.0), (576, 64, 300, 0.5), (1024, 1024, 512, 0.0)])
+def test_tile64_prefill(dev, N, K, M, f):
+    """Mask tile 64 on the 256 x 256 prefill kernel: every K-step a new tile, two tile rows per wavefront, feature counts
+    that leave one to three tile rows in the last block, a single K-step, ragged M; the small kernel beside it, the bf16
+    output, and repeated launches bit-equal (a spilled accumulator once made a few outputs differ from run to run)."""
+    print(f"tile 64 prefill N={N} K={K} M={M} f={f}", flush=True)
+    c = synth.make_case("t64_prefill", N, K, M, 64, f, seed=12)
+    p = Prepared(c, dev)
+    Yo = p.oracle_gemm(c.X)
+    Y = p.gemm(c.X, path=B.PATH_PREFILL)
+    p.check(c.X, Y, Yo, f"tile 64 {N}x{K} M={M}")
+    for rep in range(3):
+        assert np.array_equal(p.gemm(c.X, path=B.PATH_PREFILL), Y), "launches of one configuration must be bit-equal"
+    p.check(c.X, p.gemm(c.X, path=B.PATH_PREFILL, variant=1), Yo, "tile 64, small kernel")
+    Mr = M - 70
+    assert np.array_equal(p.gemm(c.X[:Mr], path=B.PATH_PREFILL), Y[:Mr]), "rows must not depend on how many rows follow them"
+    check_bf16(p.gemm_bf16(c.X, path=B.PATH_PREFILL), Yo, row_norms(c.X), p.wn, K, "tile 64 bf16 output")
+    p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
