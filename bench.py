@@ -21,6 +21,7 @@ Also reported on the same JSON line:
                 per (layer, matrix) that follows the allocation the paper reports (key / value dense, MLP heavy)
   decode_q4     decode from the 4-bit weight-only storage (7B shapes, M = 1 and 16) beside the bf16 storage;
                 decode_q4_layer_7b: one 7B decoder layer from it in four launches
+  prefill_tile64  the two MLP projections with mask tile 64 (the paper's other tile size)
   qwen_0p5b     the 0.5B-scale layer set (launch-latency-bound)
   cpu_baseline  the CPU oracle timed on a bounded sample of the headline workload
 
@@ -144,7 +145,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4,tile64")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -302,6 +303,27 @@ def main():
                                       note="median of three interleaved rounds of 10 launches each")
         for P_f in Pf:
             P_f.close()
+
+    # ------------------------------------------------------------------ mask tile 64 (the paper's other tile size) on the same projections
+    if "tile64" not in skip:
+        rows64 = []
+        for name, N_, K_ in (("gate", 11008, 4096), ("down", 4096, 11008)):
+            us_f = {}
+            for ff in (0.0, 0.6, 1.0):
+                c64 = synth.make_case("llama7b_mlp_t64_" + name, N_, K_, M, 64, ff, seed=0)
+                W_hat64, P64 = masked_packed(c64)
+                X64 = layers[0]["X"] if K_ == 4096 else layers[2]["X"]
+                Y64 = layers[0]["Y"] if N_ == 11008 else layers[2]["Y"]
+                fn = lambda _i: B.patch_gemm(X64, M, P64, Y64, stream)
+                settle(fn, batch=10, max_batches=8)
+                us_f[ff] = sorted(timed(fn, 10) / 10 for _ in range(3))[1] * 1e6
+                P64.close()
+                del W_hat64
+            rows64.append(dict(shape=[N_, K_], M=M, tile=64, us_f0=round(us_f[0.0], 1), us_f06=round(us_f[0.6], 1), us_f1=round(us_f[1.0], 1),
+                               dense_equiv_TFLOPs_f06=round(2.0 * M * N_ * K_ / us_f[0.6] / 1e6, 1),
+                               speedup_f06_over_all_dense=round(us_f[0.0] / us_f[0.6], 3), speedup_f1_over_all_dense=round(us_f[0.0] / us_f[1.0], 3)))
+        out["prefill_tile64"] = dict(rows=rows64, note="mask tile 64 x 64 on prefill_kernel_lds<64> (256 x 256 workgroup tiles, LDS-staged); "
+                                     "the headline uses mask tile 128 on prefill_kernel_wreg")
 
     # ------------------------------------------------------------------ mid M: 13B layer shapes at M = 512, 7B MLP at M = 2048
     if "mid" not in skip:
