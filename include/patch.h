@@ -55,10 +55,11 @@ typedef struct {
     int path;    /* patch_path                                                                      */
     int split_k; /* decode: K slices (one wavefront each) per workgroup whose fp32 partials are     */
                  /* reduced in slice order; rounded down to a power of two in 1..16, 0 = auto.       */
-                 /* prefill (tile 128): K slices per output tile, one workgroup each, whose partial  */
+                 /* prefill: K slices per output tile, one workgroup each, whose partial             */
                  /* products go to `workspace` and are summed in slice order by a second launch;     */
                  /* 0 = auto (1 unless the tile grid would leave a third of the chip idle; with a    */
-                 /* workspace a part-filled last round of at most half the chip is split on its own), */
+                 /* workspace a part-filled last round of at most half the chip is split on its own - */
+                 /* tile 128 only),                                                                   */
                  /* 1 = no split.  Never more slices than the workspace holds: without one, no split. */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
                  /* 2 = 256 x 256 LDS-staged kernel (the default for tile 64), 3 = 256 x 256 weights-in- */

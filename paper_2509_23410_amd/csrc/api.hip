@@ -392,6 +392,10 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
     } else {
         add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, two wavefronts per SIMD (the tile-64 default)
         add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
+        const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+        if (workspace)
+            for (int sk : {2, 3, 4, 6, 8})
+                if ((size_t)sk * per_slice <= workspace_bytes && sk * 4 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
     }
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
@@ -537,8 +541,11 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
         if (!use_mid_kernel(rows, variant, split_k, chunks, a.N / 64) || chunks < 2) return 0;
         return (size_t)chunks * (size_t)rows * (size_t)P->N * sizeof(float);
     }
-    if (variant != 0 && variant != 3) return 0;
-    if (!prefill_wreg_supports(a)) return 0;
+    if (variant == 1) return 0;
+    if (variant == 2 || !prefill_wreg_supports(a)) {   // the LDS-staged kernel: whole-launch K split only
+        const int sl = prefill_lds_split(a, split_k);
+        return sl > 1 ? (size_t)sl * (size_t)M * (size_t)P->N * sizeof(float) : 0;
+    }
     const int s = prefill_wreg_split(a, split_k);
     if (s > 1) return (size_t)s * (size_t)M * (size_t)P->N * sizeof(float);
     if (split_k != 0) return 0;

@@ -225,10 +225,12 @@ struct PfEntries {
     uint32_t v0, v1, v2, v3;
 };
 
-template <int TILE>
+// SPLIT: K cut into gridDim.y slices of whole tiles, one workgroup each; slice y writes its partial product (fp32) to
+// Y + y M N - a workspace - and wr_reduce sums the slices in order.
+template <int TILE, bool SPLIT>
 __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
-                                                          int Tk, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
+                                                          int Tk_all, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
     constexpr int KPT = TILE / kStepCols;        // K-steps per tile: 2 or 1
     constexpr int SPT = TILE / kStripRows;       // strips per tile: 8 or 4
     constexpr int NR = kPfBN / TILE;             // tile rows per block: 2 or 4
@@ -276,9 +278,12 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
     // N is a multiple of the tile, not necessarily of 256: the last block has `live` tile rows.  Table rows of
     // the others alias the last live one (valid addresses); their weights are not copied and nothing of theirs is stored.
     const int live = (int)((N - n0) / TILE) < NR ? (int)((N - n0) / TILE) : NR;
+    // this workgroup's K slice, in tiles: to the rest of the kernel it is a product with a shorter K
+    const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
+    const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
     const uint32_t* trow[NR];
 #pragma unroll
-    for (int i = 0; i < NR; ++i) trow[i] = table + ((int64_t)(n0 / TILE) + (i < live ? i : live - 1)) * Tk;
+    for (int i = 0; i < NR; ++i) trow[i] = table + ((int64_t)(n0 / TILE) + (i < live ? i : live - 1)) * Tk_all + t_begin;
 
     // ---- per-lane source pointers for the X tile copy: wavefront w copies 1 KB pieces w, w+8, w+16, w+24
     const uint8_t* xsrc[4];
@@ -288,7 +293,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
         const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
         int64_t row = m0 + m;
         if (row >= M) row = M - 1;                     // rows past M: any valid row, their outputs are not stored
-        xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8);
+        xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8 + (int64_t)t_begin * TILE);
     }
 
     // Fill one LDS stage with K-step ks; e[i] = table entry of tile row i of the block at that step.
@@ -445,32 +450,63 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                store4(Y, m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q, v, ybf16);
+                // partial products stay fp32; their sum is rounded by the reduction
+                store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q, v, SPLIT ? 0 : ybf16);
             }
         }
     }
+}
+
+// K slices per output tile of the LDS-staged kernel: as prefill_wreg_split, each slice at least 512 columns long.
+int prefill_lds_split(const GemmArgs& a, int requested) {
+    const int tiles = (int)(((a.N + kPfBN - 1) / kPfBN) * ((a.M + kPfBM - 1) / kPfBM));
+    const int min_tiles = 512 / a.tile;
+    int s = requested;
+    if (s <= 0) {
+        s = 1;
+        if (tiles < (a.n_cus * 2) / 3) {
+            s = a.n_cus / tiles;
+            if (s > a.Tk / min_tiles) s = a.Tk / min_tiles;
+            if (s > 8) s = 8;
+        }
+    }
+    if (s > a.Tk) s = a.Tk;
+    const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
+    const size_t fit = (a.ws && per_slice) ? a.ws_bytes / per_slice : 0;
+    if ((size_t)s > fit) s = (int)fit;
+    return s < 2 ? 1 : s;
 }
 
 // Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds;
 // tile 64 -> prefill_kernel_lds.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds, 3 prefill_kernel_wreg
 // (each falling back to the default choice where it does not apply).
 template <int TILE>
-static void launch_prefill_lds(const GemmArgs& a, hipStream_t stream) {
-    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE>),
-                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
-    (void)granted;
+static void launch_prefill_lds(const GemmArgs& a, int split_k, hipStream_t stream) {
+    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, false>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, true>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+    (void)granted0;
+    (void)granted1;
     const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kPfBM - 1) / kPfBM);
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    hipLaunchKernelGGL(prefill_kernel_lds<TILE>, dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk, tiles_n,
-                       tiles_m, a.Y, a.ybf16);
+    const int split = prefill_lds_split(a, split_k);
+    if (split == 1) {
+        hipLaunchKernelGGL((prefill_kernel_lds<TILE, false>), dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
+                           a.Tk, tiles_n, tiles_m, a.Y, a.ybf16);
+    } else {
+        hipLaunchKernelGGL((prefill_kernel_lds<TILE, true>), dim3(grid, split), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload,
+                           a.table, a.Tk, tiles_n, tiles_m, a.ws, 0);
+        wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, a.ybf16, stream);
+    }
 }
 
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream) {
     if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, split_k, stream); return; }
     if (variant != 1) {
-        if (a.tile == 128) launch_prefill_lds<128>(a, stream);
-        else launch_prefill_lds<64>(a, stream);
+        if (a.tile == 128) launch_prefill_lds<128>(a, split_k, stream);
+        else launch_prefill_lds<64>(a, split_k, stream);
         return;
     }
     dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);

@@ -445,6 +445,16 @@ def test_tile64_prefill(dev, N, K, M, f):
     Mr = M - 70
     assert np.array_equal(p.gemm(c.X[:Mr], path=B.PATH_PREFILL), Y[:Mr]), "rows must not depend on how many rows follow them"
     check_bf16(p.gemm_bf16(c.X, path=B.PATH_PREFILL), Yo, row_norms(c.X), p.wn, K, "tile 64 bf16 output")
+    # K split over workgroups (partial products in a poisoned caller workspace, summed in slice order)
+    ws = torch.empty(8 * M * N, device=dev, dtype=torch.float32)
+    need = B.patch_gemm_workspace_bytes(M, p.P, path=B.PATH_PREFILL)
+    print(f"  tile 64: automatic split wants {need} workspace bytes", flush=True)
+    for kw in (dict(workspace=ws), dict(workspace=ws, split_k=3), dict(workspace=ws, split_k=8)):
+        if kw.get("split_k", 0) > K // 64:
+            continue
+        Ys = p.gemm(c.X, path=B.PATH_PREFILL, **kw)
+        p.check(c.X, Ys, Yo, f"tile 64 split_k={kw.get('split_k', 0)}")
+        assert np.array_equal(p.gemm(c.X, path=B.PATH_PREFILL, **kw), Ys)
     p.P.close()
 
 
