@@ -213,3 +213,58 @@ def test_no_flat_memory_instructions(tmp_path):
             # table entries of the 4-bit product kernel come through scalar loads
             body = re.search(r"^_ZN5patch14decode4_kernelILi128ELi1ELi1ENS_5Q4OneE.*?^\.Lfunc_end", text, re.S | re.M)
             assert body and len(re.findall(r"\bs_load_dword\b", body.group(0))) >= 2
+
+
+def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path):
+    """prefill_kernel_lds issues its matrix instructions from asm statements, so the compiler does not know that an
+    accumulator is still being written when the statement ends (the hardware does not interlock a read of it either).
+    From the first of those statements to the wait states in front of the output stage no compiler-generated instruction
+    may touch an accumulator register: no copy, no spill, no reuse."""
+    import subprocess
+    from paper_2509_23410_amd import build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = tmp_path / "gemm_prefill.s"
+    cmd = [hipcc, *[f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")], "-S", "--cuda-device-only",
+           "-I", os.path.join(ROOT, "include"), "-I", build.CSRC, "-o", str(out), os.path.join(build.CSRC, "gemm_prefill.hip")]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout[-2000:]
+    text = out.read_text()
+    bodies = re.findall(r"^(_ZN5patch18prefill_kernel_lds\w+):.*?\n(.*?)^\.Lfunc_end", text, re.S | re.M)
+    assert len(bodies) >= 4, [b[0] for b in bodies]
+
+    def regs(tok):
+        out_ = set()
+        for g in re.finditer(r"\bv\[(\d+):(\d+)\]", tok):
+            out_.update(range(int(g.group(1)), int(g.group(2)) + 1))
+        for g in re.finditer(r"\bv(\d+)\b", tok):
+            out_.add(int(g.group(1)))
+        return out_
+
+    for name, body in bodies:
+        lines = body.splitlines()
+        acc, inasm, first, last = set(), False, None, None
+        for i, line in enumerate(lines):
+            if "#ASMSTART" in line:
+                inasm = True
+            elif "#ASMEND" in line:
+                inasm = False
+            elif inasm and re.match(r"\s+v_s?mfmac?_", line):
+                acc |= regs(line.split(",")[0])
+                first = i if first is None else first
+                last = i
+        assert len(acc) == 128 and first is not None, (name, len(acc))     # 8 accumulator tiles of 16 registers
+        # ... and up to the wait states the kernel itself puts before its output stage reads the accumulators
+        end = next(i for i in range(last, len(lines)) if "s_nop 15" in lines[i])
+        inasm = False
+        for i, line in enumerate(lines[:end]):
+            if "#ASMSTART" in line:
+                inasm = True
+                continue
+            if "#ASMEND" in line:
+                inasm = False
+                continue
+            code = line.split(";")[0]
+            if i < first or inasm or not code.strip() or code.strip().startswith(".") or code.strip().endswith(":"):
+                continue
+            touched = regs(code) & acc
+            assert not touched, f"{name}: compiler instruction touches accumulator registers {sorted(touched)[:4]}: {line.strip()}"
