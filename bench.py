@@ -643,15 +643,20 @@ def main():
                 Xq = dev_bf16(cq.X)
                 Yq = torch.empty((64, N_), device=dev, dtype=torch.float32)
                 r_ = dict(shape=[N_, K_], f=fd, packed_MB=round(Pq.nbytes / 1e6, 2))
+                wsq = torch.empty(8 * 64 * N_, device=dev, dtype=torch.float32)
                 for Mq in (1, 64):
                     fn = lambda _i, Mq=Mq: B.patch_gemm(Xq, Mq, Pq, Yq, stream)
                     timed(fn, 20)
                     r_[f"us_M{Mq}"] = round(sorted(timed(fn, 200) / 200 for _ in range(3))[1] * 1e6, 2)
+                fn = lambda _i: B.patch_gemm(Xq, 64, Pq, Yq, stream, workspace=wsq)
+                timed(fn, 20)
+                r_["us_M64_with_workspace"] = round(sorted(timed(fn, 200) / 200 for _ in range(3))[1] * 1e6, 2)
                 rows.append(r_)
                 Pq.close()
                 del W_hat, Xq, Yq
         out["qwen_0p5b"] = dict(rows=rows, note="0.5B-scale set, tile 128, cache-resident (1.6 - 8.7 MB): bounded by launch latency "
-                                "(an empty launch is in ceilings.empty_launch_us), not by a roofline")
+                                "(an empty launch is in ceilings.empty_launch_us), not by a roofline; with a caller workspace the "
+                                "64-row pass over a weight of few features splits K over otherwise idle compute units")
 
     # ------------------------------------------------------------------ 13B decoder stack
     if "stack" not in skip:

@@ -66,7 +66,7 @@ typedef struct {
                  /* registers kernel (the default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
                  /* features per wavefront (its split_k = K chunks over `workspace`, 0 = auto; the       */
-                 /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 5120, and */
+                 /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 4608, and */
                  /* for 12 .. 16 rows when N >= 10240).  A variant that does not apply falls back to the */
                  /* default.                                                                             */
     void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for launches that split K   */

@@ -287,9 +287,9 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
 
 // A pass on the decode path runs the 64-features-per-wavefront kernel (gemm_mid.hip) when asked for (variant 4) or,
 // by default, when it can fill the chip and X is a large part of the traffic:
-//   17 .. 64 rows: with K-chunks over a workspace, or with at least 80 groups of 64 features (measured at M = 32,
+//   17 .. 64 rows: with K-chunks over a workspace, or with at least 72 groups of 64 features (measured at M = 32,
 //     unsplit: 4096 x 4096, 64 groups, 19.6 us against 12.9 for the strip kernel; 5120 x 5120, 80 groups, 24.1
-//     against 25.2; 13824 x 5120 25.7 against 46.3);
+//     against 25.2; 13824 x 5120 25.7 against 46.3; at M = 64: 4864 x 896, 76 groups, 9.1 against 10.5);
 //   12 .. 16 rows: with at least 160 groups (M = 16: 11008 x 4096 17.9 us against 19.9, 13824 x 5120 22.4 against
 //     29.8; M = 8: 18.2 against 15.9 and 22.9 against 24.3; 4096 x 4096: the strip kernel at every M <= 16).
 //     (a set of three 4096 x 4096 weights, 192 groups: from 8 rows, 20.0 us against 20.5; equal at M = 1)
@@ -297,7 +297,7 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
     if (variant == 4) return true;
     if (variant != 0 || split_k != 0) return false;
     if (rows <= 16) return rows >= (set ? 8 : 12) && groups >= 160;
-    return mid_chunks > 1 || groups >= 80;
+    return mid_chunks > 1 || groups >= 72;
 }
 
 // Measured crossovers between decode-path passes (up to 64 rows each; every pass streams the whole weight) and the
