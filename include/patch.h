@@ -43,10 +43,10 @@ typedef enum {
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
  * once per pass: 16-feature strips per workgroup for few rows, 64 features per wavefront for more rows where that
- * fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 16 always; with a
- * workspace for at least two slices (see patch_gemm_opts) up to M = 64 (tile 64, which has no split prefill: 192);
- * without one up to M = 128 for N >= 5120, else up to M = 192 for weights below 64 MB and M = 64 above; prefill
- * beyond. */
+ * fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 64 always; beyond, with a
+ * workspace for at least two slices (see patch_gemm_opts) prefill, whose K split then fills the chip; without one
+ * the cheaper of repeated passes and one unsplit prefill launch by an estimate from the launch geometry (passes up to
+ * M = 192 at 4096 x 4096, up to M = 128 from 5120 features, further for long-K weights of few features). */
 typedef enum { PATCH_PATH_AUTO = 0, PATCH_PATH_DECODE = 1, PATCH_PATH_PREFILL = 2 } patch_path;
 
 /* Schedule options (the knobs the paper's Appendix A leaves to an autotuner: tile shape and

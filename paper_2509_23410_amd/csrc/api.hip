@@ -309,13 +309,25 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
 //     5120 x 13824   passes 27.8 / 36.8 / 72.5    split prefill 42.1 / 43.0 / 45.9
 //   without one the prefill grid is too small to fill the chip (66 - 93 us on these shapes) and the passes cost
 //     4096 x 4096 12.9 / 20.7 / 41.2 (strip kernel), 5120 x 5120 24.1 / 32.9 / 66.1, 13824 x 5120 25.7 / 34.8 / 70.3.
+// Without a workspace the choice is an estimate of both sides from the launch geometry (fitted to the same
+// measurements; it reproduces the crossovers above - M = 192 at 4096 x 4096, 128 from 5120 features - and also holds
+// for long-K weights of few features such as 4096 x 11008, where 16 output tiles run 172 steps each: 144 us, against
+// 45 us for a 64-row pass):
+//   unsplit prefill launch  rounds x 64-column steps x 1.0 us (tile 64 on the LDS-staged kernel: 1.45 us)
+//   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256))
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
     const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
-    const bool small = P->payload_bytes < ((size_t)64 << 20);
     if (M <= 16) return PATCH_PATH_DECODE;
-    if (ws) return (M <= kDecodeRows || P->tile != 128) && M <= 192 ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
-    if (P->N / 64 >= 80) return M <= 128 ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
-    return M <= (small ? 192 : 64) ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (ws) return M <= kDecodeRows ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
+    if (M <= kDecodeRows) return PATCH_PATH_DECODE;
+    const double steps = (double)P->K / 64.0;
+    const int64_t tiles = ((P->N + 255) / 256) * ((M + 255) / 256);
+    const double rounds = (double)((tiles + P->n_cus - 1) / P->n_cus);
+    const double prefill_us = rounds * steps * (P->tile == 128 ? 1.0 : 1.45);
+    const double groups = (double)(P->N / 64);
+    const double pass_us = steps * 0.3 * (1.0 + 0.4 * (groups < 256.0 ? groups / 256.0 : 1.0));
+    const double passes = (double)((M + kDecodeRows - 1) / kDecodeRows);
+    return passes * pass_us < prefill_us ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
 }
 
 patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void* Y, void* stream, const patch_gemm_opts* opts) {
