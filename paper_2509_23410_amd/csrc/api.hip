@@ -590,8 +590,8 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
     if (opts && opts->workspace && split_k == 0) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     if (path == PATCH_PATH_PREFILL && count > 1 && (variant == 0 || variant == 3) && split_k <= 1 && prefill_wreg_supports(a)) {
-        // one launch over the feature blocks of all weights - unless the blocks are so few that splitting K pays
-        // (then one split launch per weight, below)
+        // one launch over the feature blocks of all weights (with a workspace and few blocks: K in slices over the
+        // whole set, see launch_prefill_wreg_set)
         int blocks = 0;
         WeightSet set = {};
         for (int i = 0; i < count; ++i) {
@@ -604,13 +604,9 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
         }
         set.count = count;
         set.units = blocks;
-        const int64_t tiles = (int64_t)blocks * ((M + 255) / 256);
-        const bool have_ws = opts && opts->workspace && split_k == 0;
-        if (!have_ws || tiles >= (a.n_cus * 2) / 3) {
-            launch_prefill_wreg_set(a, set, s);
-            HIP_TRY(hipGetLastError());
-            return PATCH_OK;
-        }
+        launch_prefill_wreg_set(a, set, s);
+        HIP_TRY(hipGetLastError());
+        return PATCH_OK;
     }
     if (path == PATCH_PATH_PREFILL || count == 1) {
         patch_gemm_opts o = {path, split_k, variant, opts ? opts->workspace : nullptr, opts ? opts->workspace_bytes : 0, a.ybf16};

@@ -375,6 +375,30 @@ __global__ __launch_bounds__(256) void wr_reduce_kernel(const wr_f32x4* __restri
     }
 }
 
+// The same for a set of weights in one launch: blockIdx.y = weight; its slices lie one behind the other at ws[y].
+struct WrReduceSet {
+    const float* ws[kMaxMany];
+    float* Y[kMaxMany];
+    size_t n4[kMaxMany];
+};
+__global__ __launch_bounds__(256) void wr_reduce_set_kernel(const WrReduceSet set, int slices, int ybf16) {
+    const int y = blockIdx.y;
+    const wr_f32x4* ws = reinterpret_cast<const wr_f32x4*>(set.ws[0]);
+    float* Y = set.Y[0];
+    size_t n4 = set.n4[0];
+#pragma unroll
+    for (int i = 1; i < kMaxMany; ++i)
+        if (y == i) { ws = reinterpret_cast<const wr_f32x4*>(set.ws[i]); Y = set.Y[i]; n4 = set.n4[i]; }
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+        wr_f32x4 acc = ws[i];
+        for (int s = 1; s < slices; ++s) {
+            const wr_f32x4 v = ws[(size_t)s * n4 + i];
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        store4(Y, (int64_t)(4 * i), acc, ybf16);
+    }
+}
+
 __device__ __forceinline__ uint64_t wr_uniform64(uint64_t v) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return ((uint64_t)hi << 32) | lo;
@@ -855,6 +879,38 @@ void launch_prefill_wreg_set(const GemmArgs& a, const WeightSet& set, hipStream_
     wr_grant_lds();
     const int tiles_m = (int)((a.M + kWrBM - 1) / kWrBM);
     const int nblk = set.units * tiles_m;
+    // A set whose tile grid covers less than about two thirds of the chip (q / k / v of a 13B layer at M = 512: 120
+    // tiles): K in slices over the whole set in ONE launch - slice y of weight i writes its partial product to the
+    // workspace region of that weight - and one reduction launch over all weights.  (One split launch and one
+    // reduction per weight took 126 us on that set.)
+    if (a.ws && nblk < (a.n_cus * 2) / 3) {
+        int64_t out_floats = 0;
+        for (int i = 0; i < set.count; ++i) out_floats += a.M * set.N[i];
+        int split = a.n_cus / nblk;
+        if (split > a.Tk / 4) split = a.Tk / 4;
+        if (split > 8) split = 8;
+        const size_t fit = out_floats ? a.ws_bytes / ((size_t)out_floats * sizeof(float)) : 0;
+        if ((size_t)split > fit) split = (int)fit;
+        if (split >= 2) {
+            WeightSet part = set;
+            WrReduceSet red = {};
+            size_t off = 0, n4_max = 0;
+            for (int i = 0; i < set.count; ++i) {
+                part.Y[i] = a.ws + off;
+                red.ws[i] = a.ws + off;
+                red.Y[i] = set.Y[i];
+                red.n4[i] = (size_t)a.M * (size_t)set.N[i] / 4;
+                if (red.n4[i] > n4_max) n4_max = red.n4[i];
+                off += (size_t)split * (size_t)a.M * (size_t)set.N[i];
+            }
+            hipLaunchKernelGGL(prefill_kernel_wreg<1>, dim3(((nblk + 7) / 8) * 8, split), dim3(256), kWrLds, stream, a.X, a.M, a.K, a.Tk,
+                               set.units, tiles_m, 0, nblk, part, 0);
+            const size_t blocks = (n4_max + 255) / 256;
+            hipLaunchKernelGGL(wr_reduce_set_kernel, dim3((unsigned)(blocks < 2048 ? blocks : 2048), (unsigned)set.count), dim3(256), 0, stream,
+                               red, split, a.ybf16);
+            return;
+        }
+    }
     int tail = 0;
     const int tail_split = prefill_wreg_tail_of(nblk, a, &tail);   // 1 without a.ws
     if (tail_split > 1) {

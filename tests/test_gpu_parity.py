@@ -506,13 +506,27 @@ def test_gemm_many_matches_single_calls(dev):
             torch.cuda.synchronize()
             assert torch.equal(Y, single), "fused launch differs from the single call"
             p.check(X[:M], Y.cpu().numpy(), None, f"many M={M}")
-    # with a workspace the few output tiles of this set are better split: one split launch per weight
-    ws = torch.full((8 * 40 * 512,), float("nan"), device=dev, dtype=torch.float32)
-    Ys = [torch.full((40, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
-    B.patch_gemm_many(Xd, 40, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, workspace=ws)
+    # with a workspace the few output tiles of this set are split in K: one launch over the set, slices in the
+    # (poisoned) workspace, one reduction launch; repeated launches bit-equal
+    for M in (40, 300):
+        ws = torch.full((8 * M * 1024,), float("nan"), device=dev, dtype=torch.float32)
+        Ys = [torch.full((M, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, workspace=ws)
+        torch.cuda.synchronize()
+        first = [Y.clone() for Y in Ys]
+        for p, Y in zip(preps, Ys):
+            p.check(X[:M], Y.cpu().numpy(), None, f"many, K slices over the set, M={M}")
+        ws.fill_(float("nan"))
+        B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, workspace=ws)
+        torch.cuda.synchronize()
+        assert all(torch.equal(a_, b_) for a_, b_ in zip(first, Ys))
+    # a workspace too small for two slices of the set: the unsplit launch
+    ws = torch.full((300 * 1024,), float("nan"), device=dev, dtype=torch.float32)
+    Ys = [torch.full((300, c.N), float("nan"), device=dev, dtype=torch.float32) for c in cases]
+    B.patch_gemm_many(Xd, 300, [p.P for p in preps], Ys, stream(), path=B.PATH_PREFILL, workspace=ws)
     torch.cuda.synchronize()
     for p, Y in zip(preps, Ys):
-        p.check(X[:40], Y.cpu().numpy(), None, "many, split launches")
+        p.check(X[:300], Y.cpu().numpy(), None, "many, small workspace")
     other = Prepared(synth.make_case("manyk", 128, 512, 4, t, 0.5, seed=21), dev)
     with pytest.raises(B.PatchError):   # K differs
         B.patch_gemm_many(Xd, 1, [preps[0].P, other.P],
