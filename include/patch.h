@@ -281,7 +281,7 @@ patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_
  *   patch_gemm4    Y[m, n] = sum_k X[m, k] * bf16(q s)[n, k]: X DEVICE M x K bf16, Y DEVICE M x N fp32, both 16-byte
  *                  aligned; asynchronous, allocates nothing, bit-reproducible.  Decode-shaped: the weight is streamed
  *                  once per 64 rows of X; for prefill shapes dequantize once (patch_unpack4) and patch_pack the result
- *   patch_gemm4_many  up to PATCH_MAX_MANY weights with the same K and tile against one X in one launch per 16 rows
+ *   patch_gemm4_many  up to PATCH_MAX_MANY weights with the same K and tile against one X in one launch per 64 rows
  *                  (q / k / v, gate / up): Y[i] is M x N_i fp32; bit-reproducible, and equal to the single calls up to
  *                  the order of the fp32 partial sums (the split of K over wavefronts depends on the number of
  *                  workgroups); PATCH_ERR_SHAPE when K or tile differ

@@ -17,10 +17,10 @@
 //                along K are contiguous and no cache line is shared between strips (strips of one tile run in
 //                workgroups on different XCDs; inside the tile every line of scales was fetched by four L2s)
 // The product kernel dequantizes in registers (8 codes -> 8 bf16 with integer rounding) and then runs the same matrix
-// instructions as the bf16 decode kernel: one workgroup per strip of 16 features, its wavefronts split K, partial sums
-// meet in LDS in wavefront order (bit-reproducible); several weights sharing X run as one launch (patch_gemm4_many).
-// It is the decode-shaped path only - up to 16 rows per pass over
-// the weight; for prefill shapes dequantize once (patch_unpack4) and pack the result as bf16.
+// instructions as the bf16 decode kernel: a workgroup owns one to three strips of 16 features, its wavefronts split K,
+// partial sums meet in LDS in wavefront order (bit-reproducible); several weights sharing X run as one launch
+// (patch_gemm4_many).  It is the decode-shaped path only - up to 64 rows of X (one, two or four blocks of 16) per pass
+// over the weight; for prefill shapes dequantize once and pack the result as bf16 (patch_pack_from4).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -221,10 +221,11 @@ __global__ __launch_bounds__(256) void unpack4_kernel(const uint8_t* __restrict_
 
 // Up to 16 RB rows of X (RB = 1, 2 or 4 blocks of 16 rows) against the 4-bit weight in one pass over it.  A workgroup
 // owns R consecutive strips of 16 features (the registers hold R x RB accumulators and RB X operands per step: R <= 3
-// with one row block, R <= 2 with more); its KW wavefronts take contiguous runs of 64-column steps.  A wavefront loads the X operand of a step once
-// and uses it for all R strips (at 4 bits per weight X is the larger stream, so this reuse is what bounds the traffic),
-// works in batches of NB steps (2; 1 when RB > 1) - table entries, then every load of the batch, then the arithmetic - and issues
-// the next batch's loads before it consumes the current one.  Two batch buffers alternate; no copies.
+// with one row block, R <= 2 with more); its KW wavefronts take contiguous runs of 64-column steps.  A wavefront loads
+// the X operand of a step once and uses it for all R strips (at 4 bits per weight X is the larger stream, so this
+// reuse is what bounds the traffic), works in batches of NB steps (2; 1 when RB > 1) - table entries, then every load
+// of the batch, then the arithmetic - and issues the next batch's loads before it consumes the current one.  Two batch
+// buffers alternate; no copies.
 constexpr int kQ4MaxR = 3;
 constexpr int kQ4Rows = 64;   // rows of X per launch at most
 
@@ -399,7 +400,8 @@ __global__ __launch_bounds__(64 * q4_max_waves(R, RB)) void decode4_kernel(const
     constexpr bool kOne = sizeof(SetT) == sizeof(Q4One);
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
     constexpr int NB = RB > 1 ? 1 : 2;   // steps per batch
-    __shared__ q4_f32x4 red[R * RB][q4_max_waves(R, RB)][64];
+    constexpr int CH = R * RB < 8 ? R * RB : 8;   // items per round of the final reduction
+    __shared__ q4_f32x4 red[CH][q4_max_waves(R, RB)][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // of KW wavefronts: an argument (the launch size is a hidden one, fetched apart)
     const int col = lane & 15, q = lane >> 4;
@@ -419,11 +421,12 @@ __global__ __launch_bounds__(64 * q4_max_waves(R, RB)) void decode4_kernel(const
         st.s[r] = strip % SPT;
         st.scl[r] = reinterpret_cast<q4_u16_ptr>(wt.scales) + q4_scale_index(strip, Tk, 0, col);
     }
-    // the (strip, row block) this wavefront adds up and stores at the end (wavefronts 0 .. R RB - 1)
-    const int wr = w < R * RB ? w / RB : 0, wrb = w % RB;
-    const int gw = g0 + wr;
-    const Q4Weight wy = q4_weight_of(set, gw < total_strips ? gw : total_strips - 1);
-    PATCH_Q4_ARGS_NOW("s"(X), "s"(m0), "s"(rows), "s"(K), "s"(Tk), "s"(KW), "s"(wy.Y), "s"(wy.N), "s"(wy.first));
+    // the first (strip, row block) this wavefront adds up and stores at the end (it takes items w, w + KW, ...)
+    {
+        const int gw = g0 + (w < R * RB ? w / RB : 0);
+        const Q4Weight wy = q4_weight_of(set, gw < total_strips ? gw : total_strips - 1);
+        PATCH_Q4_ARGS_NOW("s"(X), "s"(m0), "s"(rows), "s"(K), "s"(Tk), "s"(KW), "s"(wy.Y), "s"(wy.N), "s"(wy.first));
+    }
     const int total = Tk * KPT, per = (total + KW - 1) / KW;
     const int begin = w * per, end = begin + per < total ? begin + per : total;
     bool xvalid[RB];
@@ -449,21 +452,30 @@ __global__ __launch_bounds__(64 * q4_max_waves(R, RB)) void decode4_kernel(const
             if (have1) q4_compute<R, RB, NB>(b1, acc, step0 + NB, end);
         }
     }
+    // Partial sums meet in LDS, CH (strip, row block) items at a time (all of them unless R RB > 8): wavefront w adds
+    // up the items w, w + KW, ... of the chunk in wavefront order and stores them.
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int c0 = 0; c0 < R * RB; c0 += CH) {
+        if (c0 > 0) __syncthreads();
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) red[r * RB + rb][w][lane] = acc[r][rb];
-    __syncthreads();
-    // wavefront w < R RB adds up (strip w / RB, row block w % RB) in wavefront order (the launcher keeps KW >= R RB)
-    if (w < R * RB && gw < total_strips) {
-        q4_f32x4 sum = red[w][0][lane];
-        for (int i = 1; i < KW; ++i) {
-            const q4_f32x4 v = red[w][i][lane];
-            sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                if (r * RB + rb >= c0 && r * RB + rb < c0 + CH) red[r * RB + rb - c0][w][lane] = acc[r][rb];
+        __syncthreads();
+        for (int i0 = w; i0 < CH && c0 + i0 < R * RB; i0 += KW) {
+            const int item = c0 + i0, gw = g0 + item / RB, wrb = item % RB;
+            if (gw >= total_strips) break;
+            const Q4Weight wy = q4_weight_of(set, gw);
+            q4_f32x4 sum = red[i0][0][lane];
+            for (int i = 1; i < KW; ++i) {
+                const q4_f32x4 v = red[i0][i][lane];
+                sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+            }
+            PATCH_Q4_GLOBAL float* Yg = reinterpret_cast<PATCH_Q4_GLOBAL float*>(wy.Y);
+            if (16 * wrb + col < rows)
+                *reinterpret_cast<PATCH_Q4_GLOBAL q4_f32x4*>(Yg + (m0 + 16 * wrb + col) * wy.N + (int64_t)(gw - wy.first) * 16 + 4 * q) = sum;
         }
-        PATCH_Q4_GLOBAL float* Yg = reinterpret_cast<PATCH_Q4_GLOBAL float*>(wy.Y);
-        if (16 * wrb + col < rows)
-            *reinterpret_cast<PATCH_Q4_GLOBAL q4_f32x4*>(Yg + (m0 + 16 * wrb + col) * wy.N + (int64_t)(gw - wy.first) * 16 + 4 * q) = sum;
     }
 }
 
@@ -473,17 +485,38 @@ static void launch_decode4(const uint16_t* X, int64_t m0, int rows, int64_t K, i
                        set);
 }
 
-// up to 3 strips per workgroup with one block of 16 rows, up to 2 with RB = 2 / 4 row blocks
+// up to 3 strips per workgroup with one or four blocks of 16 rows, up to 4 with two
 template <int TILE, typename SetT>
 static void launch_decode4_r(int R, int RB, const uint16_t* X, int64_t m0, int rows, int64_t K, int Tk, const SetT& set, int groups, int kw,
                              hipStream_t s) {
-    if (RB == 4 && R == 1) launch_decode4<TILE, 1, 4, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else if (RB == 4) launch_decode4<TILE, 2, 4, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else if (RB == 2 && R == 1) launch_decode4<TILE, 1, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else if (RB == 2) launch_decode4<TILE, 2, 2, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else if (R == 1) launch_decode4<TILE, 1, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else if (R == 2) launch_decode4<TILE, 2, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
-    else launch_decode4<TILE, 3, 1, SetT>(X, m0, rows, K, Tk, set, groups, kw, s);
+#define PATCH_Q4_CASE(r, rb) \
+    if (R == r && RB == rb) return launch_decode4<TILE, r, rb, SetT>(X, m0, rows, K, Tk, set, groups, kw, s)
+    PATCH_Q4_CASE(1, 1); PATCH_Q4_CASE(2, 1); PATCH_Q4_CASE(3, 1);
+    PATCH_Q4_CASE(1, 2); PATCH_Q4_CASE(2, 2); PATCH_Q4_CASE(3, 2); PATCH_Q4_CASE(4, 2);
+    PATCH_Q4_CASE(1, 4); PATCH_Q4_CASE(2, 4); PATCH_Q4_CASE(3, 4);
+#undef PATCH_Q4_CASE
+}
+
+// Strips per workgroup for a pass of `rows` rows over `strips` strips: the R that minimises an estimate of the pass,
+//     rounds(workgroups) x (x + R),
+// in units of one strip's share of a wavefront's work.  x is what a workgroup spends on its X operands (it loads all of
+// X whatever R is; fitted: 0.15 + 0.045 rows up to 16 rows, 1.7 for 32, 4.5 for 64 - at 4 bits per weight 64 rows of X
+// are 16 times a strip's codes); rounds = workgroups / compute units, rounded up while at most two rounds are resident at
+// once (then the busiest compute unit decides), with half a round for the tail beyond.  More strips per workgroup
+// share X further but must not leave compute units idle: 688 strips on 256 units run as 230 workgroups of 3 (one
+// round) rather than 344 of 2.  R <= 3 (one or four row blocks) or 4 (two): what the registers hold.
+static int q4_strips_per_group(int strips, int n_cus, int rows) {
+    const int max_r = rows > 16 && rows <= 32 ? 4 : kQ4MaxR;
+    const double x = rows <= 16 ? 0.15 + 0.045 * rows : rows <= 32 ? 1.7 : 4.5;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int r = 1; r <= max_r; ++r) {
+        const int groups = (strips + r - 1) / r;
+        const double rounds = groups <= 2 * n_cus ? (double)((groups + n_cus - 1) / n_cus) : (double)groups / n_cus + 0.5;
+        const double cost = rounds * (x + r);
+        if (r == 1 || cost <= best_cost) { best = r; best_cost = cost; }
+    }
+    return best;
 }
 
 }  // namespace patch
@@ -607,23 +640,19 @@ patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* con
         first[i] = total_strips;
         total_strips += (int)(P[i]->N / kStripRows);
     }
-    // One launch per pass of up to 64 rows.  A pass of at most 16 rows: R strips per workgroup - one workgroup per
-    // compute unit when the weights have more strips than that, at most 3.  A longer pass: 2 or 4 row blocks, R at most 2.
+    // One launch per pass of up to 64 rows (1, 2 or 4 blocks of 16), R strips per workgroup (q4_strips_per_group).
     auto run = [&](const auto& set) {
         for (int64_t m0 = 0; m0 < M; m0 += kQ4Rows) {
             const int rows = (int)(M - m0 < kQ4Rows ? M - m0 : kQ4Rows);
             const int RB = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
-            int R = (total_strips + P0->n_cus - 1) / P0->n_cus;
-            if (R > (RB > 1 ? 2 : kQ4MaxR)) R = RB > 1 ? 2 : kQ4MaxR;
-            if (R < 1) R = 1;
+            const int R = q4_strips_per_group(total_strips, P0->n_cus, rows);
             const int groups = (total_strips + R - 1) / R;
-            // wavefronts per workgroup: about 4 steps each, at least one per (strip, row block), at most 16; with more
+            // wavefronts per workgroup: about 4 steps each, at least 4, at most 16 (8 with many registers); with more
             // workgroups than compute units half of that, so that two workgroups share a compute unit (its registers
             // hold 16 of these wavefronts) instead of running one after the other
             int kw = (total + 3) / 4;
             if (kw > q4_max_waves(R, RB)) kw = q4_max_waves(R, RB);
             if (groups > P0->n_cus && kw > 8) kw = 8;
-            if (kw < R * RB) kw = R * RB;
             if (kw < 4) kw = 4;
             if (P0->tile == 128) launch_decode4_r<128>(R, RB, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);
             else launch_decode4_r<64>(R, RB, static_cast<const uint16_t*>(X), m0, rows, P0->K, P0->Tk, set, groups, kw, s);

@@ -65,6 +65,9 @@ CASES = [
     # more strips than compute units: several strips per workgroup, the last workgroup short of strips
     ("wide_t128_three_strips", 8320, 256, 128, 0.5, [1, 16, 20, 40]),
     ("wide_t64_three_strips", 8384, 192, 64, 0.5, [5, 33, 64]),
+    # 864 / 868 strips: two strips per workgroup up to 16 rows and at 64, four at 17 .. 32 rows
+    ("wide_t128_four_strips", 13824, 256, 128, 0.5, [8, 24, 32, 64]),
+    ("wide_t64_four_strips", 13888, 192, 64, 0.6, [16, 32]),
 ]
 
 
@@ -196,9 +199,8 @@ def test_hip_graph_replay_matches_eager(dev):
 
 
 def test_13b_shapes_sampled(dev):
-    """The 13B stack's gate projection (13824 x 5120: three strips per workgroup, fewer workgroups than compute units'
-    worth of strips) and down projection (5120 x 13824: 216 steps over 16 wavefronts) from the 4-bit storage at M = 1, 16
-    and 48: storage bit-exact, sampled outputs against the definition on the oracle's dequantized weight."""
+    """The 13B stack's gate projection (13824 x 5120: 864 strips, several per workgroup) and down projection
+    (5120 x 13824: 216 steps over 16 wavefronts) from the 4-bit storage at M = 1, 16 and 48: storage bit-exact, sampled outputs against the definition on the oracle's dequantized weight."""
     fr = synth.layer_fractions(0, 40)
     for li, (N, K) in [(17, (13824, 5120)), (29, (5120, 13824))]:
         f = float(fr[li])
