@@ -43,7 +43,8 @@ typedef enum {
 
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
  * once per pass: 16-feature strips per workgroup for few rows, 64 features per wavefront for more rows where that
- * fills the chip), PREFILL in 256-row tiles.  AUTO (measured crossovers): decode up to M = 64 always; beyond, with a
+ * fills the chip), PREFILL in blocks of 256 rows (128 where an estimate of both says so: few rows, or a weight of
+ * few feature blocks that would otherwise need a deep K split).  AUTO (measured crossovers): decode up to M = 64 always; beyond, with a
  * workspace for at least two slices (see patch_gemm_opts) prefill, whose K split then fills the chip; without one
  * the cheaper of repeated passes and one unsplit prefill launch by an estimate from the launch geometry (passes up to
  * M = 192 at 4096 x 4096, up to M = 128 from 5120 features, further for long-K weights of few features). */
@@ -63,7 +64,9 @@ typedef struct {
                  /* 1 = no split.  Never more slices than the workspace holds: without one, no split. */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
                  /* 2 = 256 x 256 LDS-staged kernel (the default for tile 64), 3 = 256 x 256 weights-in- */
-                 /* registers kernel (the default for tile 128 where K <= 32768 and M K 2 < 4 GB).  Decode: 2 / 3 = 8 / 4     */
+                 /* registers kernel (the default for tile 128 where K <= 32768 and M K 2 < 4 GB), 4 = the  */
+                 /* LDS-staged kernel with blocks of 256 features x 128 rows (the default, with no split  */
+                 /* requested, where estimated faster: up to a few hundred rows).  Decode: 2 / 3 = 8 / 4  */
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
                  /* features per wavefront (its split_k = K chunks over `workspace`, 0 = auto; the       */
                  /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 4608, and */
@@ -164,7 +167,8 @@ patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, 
  *   prefill path, tile 128: the execution tiles 256 x 256 with one wavefront per SIMD (default), 256 x 256 with two
  *     (variant 2) and the small 128 x 128 tile (variant 1; Appendix O reports that small execution tiles under-use
  *     the matrix units - it is timed so that the report shows it), and the K-split counts the workspace allows;
- *   prefill path, tile 64: the 256 x 256 LDS-staged kernel (default) and the small 128 x 128 tile.
+ *   prefill path, tile 64: the 256 x 256 LDS-staged kernel (default) and the small 128 x 128 tile, K-split counts;
+ *   prefill path, M <= 4096, both tiles: blocks of 256 features x 128 rows (variant 4), unsplit and split.
  *   X, Y       as for patch_gemm (Y is overwritten several times; after patch_tune it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1

@@ -392,11 +392,12 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
                     if ((size_t)sk * per_slice <= workspace_bytes && sk <= P->Tk) add(PATCH_PATH_DECODE, sk, 4, true);
         }
     }
+    const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+    const int tiles_per_slice = 512 / P->tile;   // K slices of at least 512 columns
     if (P->tile == 128) {
         add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, one wavefront per SIMD
         add(PATCH_PATH_PREFILL, 1, 2, false);   // 256 x 256, two wavefronts per SIMD
         add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
-        const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
         if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic: may split a part-filled last round only
         if (workspace)
             for (int sk : {2, 3, 4, 6, 8, 12, 16})
@@ -404,10 +405,16 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
     } else {
         add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, two wavefronts per SIMD (the tile-64 default)
         add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
-        const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+        if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic
         if (workspace)
             for (int sk : {2, 3, 4, 6, 8})
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 4 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
+    }
+    if (M <= 4096) {   // 256 features x 128 rows per workgroup: beyond a few thousand rows never ahead
+        add(PATCH_PATH_PREFILL, 1, 4, false);
+        if (workspace)
+            for (int sk : {2, 3, 4, 6, 8})
+                if ((size_t)sk * per_slice <= workspace_bytes && sk * tiles_per_slice <= P->Tk) add(PATCH_PATH_PREFILL, sk, 4, true);
     }
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
@@ -554,8 +561,12 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
         return (size_t)chunks * (size_t)rows * (size_t)P->N * sizeof(float);
     }
     if (variant == 1) return 0;
-    if (variant == 2 || !prefill_wreg_supports(a)) {   // the LDS-staged kernel: whole-launch K split only
-        const int sl = prefill_lds_split(a, split_k);
+    if (variant == 0 && split_k == 0) {
+        int split128 = 1;
+        if (prefill_prefers_128_rows(a, &split128)) return split128 > 1 ? (size_t)split128 * (size_t)M * (size_t)P->N * sizeof(float) : 0;
+    }
+    if (variant == 2 || variant == 4 || !prefill_wreg_supports(a)) {   // the LDS-staged kernel: whole-launch K split only
+        const int sl = prefill_lds_split(a, split_k, variant == 4 ? 128 : 256);
         return sl > 1 ? (size_t)sl * (size_t)M * (size_t)P->N * sizeof(float) : 0;
     }
     const int s = prefill_wreg_split(a, split_k);

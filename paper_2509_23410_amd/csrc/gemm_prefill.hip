@@ -177,9 +177,9 @@ __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restr
 // ------------------------------------------------------------------------------------------------------
 constexpr int kPfBN = 256, kPfBM = 256;
 constexpr int kPfAStage = 2 * 8 * kDenseFragBytes;   // 32 KB
-constexpr int kPfBStage = kPfBM * 128;               // 32 KB
 constexpr int kPfMetaBuf = 2 * 2048;                 // position words: two tile rows x 2 KB (tile 128), four x 1 KB (tile 64)
-constexpr int kPfLds = 2 * kPfAStage + 2 * kPfBStage + 2 * kPfMetaBuf;
+__host__ __device__ constexpr int pf_xstage(int bm) { return bm * 128; }   // X tile of a stage: 32 or 16 KB
+__host__ __device__ constexpr int pf_lds_bytes(int bm) { return 2 * (kPfAStage + pf_xstage(bm)) + 2 * kPfMetaBuf; }   // 136 / 104 KB
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -227,24 +227,30 @@ struct PfEntries {
 
 // SPLIT: K cut into gridDim.y slices of whole tiles, one workgroup each; slice y writes its partial product (fp32) to
 // Y + y M N - a workspace - and wr_reduce sums the slices in order.
-template <int TILE, bool SPLIT>
+template <int TILE, bool SPLIT, int BM>
 __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                           const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
                                                           int Tk_all, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
     constexpr int KPT = TILE / kStepCols;        // K-steps per tile: 2 or 1
     constexpr int SPT = TILE / kStripRows;       // strips per tile: 8 or 4
     constexpr int NR = kPfBN / TILE;             // tile rows per block: 2 or 4
-    constexpr int WR = NR / 2;                   // tile rows per wavefront: 1 or 2
+    constexpr int NA = BM / 64;                  // 32-feature blocks per wavefront: 4 (128 features) or 2 (64)
+    constexpr int WR = NA * 32 > TILE ? 2 : 1;   // tile rows per wavefront: 2 only for 128 features of tile 64
     constexpr int ESZ = 2 * KPT;                 // bytes of position bits per lane and strip
     constexpr int MROW = TILE == 128 ? 2048 : 1024;   // LDS bytes per tile row of position words
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    uint8_t* const As = lds;                                  // [stage][strip of the block][2048]
-    uint8_t* const Bs = lds + 2 * kPfAStage;                  // [stage][256 rows][128 B] swizzled
-    uint8_t* const Ms = lds + 2 * kPfAStage + 2 * kPfBStage;  // [buffer][tile row][MROW]
+    constexpr int NS = 2, XSTAGE = pf_xstage(BM);
+    uint8_t* const As = lds;                                      // [stage][strip of the block][2048]
+    uint8_t* const Bs = lds + NS * kPfAStage;                     // [stage][BM rows][128 B] swizzled
+    uint8_t* const Ms = lds + NS * kPfAStage + NS * XSTAGE;       // [buffer][tile row][MROW]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = w >> 2, wm = w & 3;  // 128-feature half of the block, 64-row group
+    // BM = 256: wavefront = 128-feature half of the block x one of four 64-row groups; BM = 128: 64-feature quarter x
+    // one of two 64-row groups
+    const int w4 = w >> 2;                                  // strip w of the block lies in its 128-feature half w4
+    const int fo = BM == 256 ? 128 * (w >> 2) : 64 * (w >> 1);   // first feature of the wavefront inside the block
+    const int wm = BM == 256 ? (w & 3) : (w & 1);
 
     // ---- block -> (n, m) tile of the output.  Consecutive blocks go to different XCDs (hardware round-robin),
     // each with its own L2, so every XCD gets a contiguous run of the tile order below, and that order walks
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
             bm = (tiles_m / GM) * GM + rem % gm;
         }
     }
-    const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * kPfBM;
+    const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * BM;
     // N is a multiple of the tile, not necessarily of 256: the last block has `live` tile rows.  Table rows of
     // the others alias the last live one (valid addresses); their weights are not copied and nothing of theirs is stored.
     const int live = (int)((N - n0) / TILE) < NR ? (int)((N - n0) / TILE) : NR;
@@ -285,10 +291,11 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
 #pragma unroll
     for (int i = 0; i < NR; ++i) trow[i] = table + ((int64_t)(n0 / TILE) + (i < live ? i : live - 1)) * Tk_all + t_begin;
 
-    // ---- per-lane source pointers for the X tile copy: wavefront w copies 1 KB pieces w, w+8, w+16, w+24
-    const uint8_t* xsrc[4];
+    // ---- per-lane source pointers for the X tile copy: wavefront w copies 1 KB pieces w, w+8 (, w+16, w+24)
+    constexpr int XP = BM / 64;
+    const uint8_t* xsrc[XP];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < XP; ++i) {
         const int c = (w + 8 * i) * 64 + lane;       // physical 16-byte chunk of the tile
         const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
         int64_t row = m0 + m;
@@ -302,10 +309,10 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
         // weights: wavefront w copies strips w and w + 8 of the block's 16
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            // strip w + 8 h of the block: tile row h (tile 128) or r + 2 h (tile 64) - a choice between two entries at most
+            // strip w + 8 h of the block: tile row h (tile 128) or w4 + 2 h (tile 64) - a choice between two entries at most
             const int sidx = w + 8 * h, tr = sidx / SPT, st = sidx % SPT;
             if (tr >= live) continue;
-            const uint32_t ev = TILE == 128 ? (h ? e.v1 : e.v0) : (h ? (r ? e.v3 : e.v2) : (r ? e.v1 : e.v0));
+            const uint32_t ev = TILE == 128 ? (h ? e.v1 : e.v0) : (h ? (w4 ? e.v3 : e.v2) : (w4 ? e.v1 : e.v0));
             const uint8_t* tb = payload + entry_offset(ev);
             uint8_t* dst = As + stage * kPfAStage + sidx * kDenseFragBytes;
             if (entry_sparse(ev)) {
@@ -339,12 +346,12 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
         }
         // X tile
 #pragma unroll
-        for (int i = 0; i < 4; ++i) g2l16(xsrc[i] + (size_t)ks * 128, Bs + stage * kPfBStage + (w + 8 * i) * 1024);
+        for (int i = 0; i < XP; ++i) g2l16(xsrc[i] + (size_t)ks * 128, Bs + stage * XSTAGE + (w + 8 * i) * 1024);
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[NA][2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -352,21 +359,23 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
 
     const int i32 = lane & 31, q = lane >> 5;
     // LDS byte offsets of this lane inside a strip's fragment; a 32-feature block a covers strips 2a, 2a+1 of the
-    // wavefront's eight
+    // wavefront's eight (four)
     const int lane_frag = ((i32 >> 4) * kDenseFragBytes) + (16 * q + (i32 & 15)) * 16;
     const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * ESZ;
     // One K-step: wait for the stage, refill the other one, multiply.  e_mine[i]: table entry of this wavefront's
     // i-th tile row at step ks; (pf_ks, pf_e): the step to fetch into the idle stage and its entries.
+    // (A third stage, fetched two steps ahead with counted waits, was no faster with blocks of 128 rows: the step is
+    // bound by LDS reads, not by the latency of the loads.)
     auto step = [&](int ks, uint32_t e_mine0, uint32_t e_mine1, int pf_ks, const PfEntries pf_e) {
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         prefetch(pf_ks, stage ^ 1, pf_e);
         const int tk = ks / KPT, j = ks % KPT;
-        const uint8_t* as = As + stage * kPfAStage + r * 8 * kDenseFragBytes + lane_frag;
-        const uint8_t* bs = Bs + stage * kPfBStage;
-        // position words of block a: tile 128: tile row r of buffer tk & 1, strips 2a, 2a+1 of the tile's eight;
-        // tile 64: tile row 2 r + a / 2 of this stage's buffer, strips 2 (a % 2), + 1 of the tile's four
+        const uint8_t* as = As + stage * kPfAStage + (fo / kStripRows) * kDenseFragBytes + lane_frag;
+        const uint8_t* bs = Bs + stage * XSTAGE;
+        // position words of block a (features fo + 32 a ..): tile row (fo + 32 a) / TILE of the block, in buffer
+        // tk & 1 (tile 128) or this stage's (tile 64); strips ((fo + 32 a) % TILE) / 16, + 1 of the tile
         const uint8_t* ms = Ms + (TILE == 128 ? (tk & 1) : stage) * kPfMetaBuf + lane_meta;
 
         // X fragments as 8-register pairs: a 2:4 instruction takes a pair, a dense one either half
@@ -390,16 +399,16 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
             const int ustride = sp ? 512 : 1024;
             fa0[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride);
             fa1[buf].raw = *reinterpret_cast<const u32x4*>(as + a * 2 * kDenseFragBytes + u * ustride + 512);
-            if constexpr (TILE == 128)
-                fpw[buf] = *reinterpret_cast<const uint32_t*>(ms + r * MROW + a * 2 * 64 * ESZ + u * 32 * ESZ);
-            else
-                fpw[buf] = *reinterpret_cast<const uint16_t*>(ms + (2 * r + (a >> 1)) * MROW + (a & 1) * 2 * 64 * ESZ + u * 32 * ESZ);
+            const int f = fo + 32 * a;
+            const uint8_t* pw = ms + (f / TILE) * MROW + ((f % TILE) / kStripRows) * 64 * ESZ + u * 32 * ESZ;
+            if constexpr (TILE == 128) fpw[buf] = *reinterpret_cast<const uint32_t*>(pw);
+            else fpw[buf] = *reinterpret_cast<const uint16_t*>(pw);
         };
         fetch(0, 0);
         fetch(1, 1);
 #pragma unroll
-        for (int pos = 0; pos < 8; ++pos) {
-            if (pos + 2 < 8) fetch(pos + 2, (pos + 2) % 3);
+        for (int pos = 0; pos < 2 * NA; ++pos) {
+            if (pos + 2 < 2 * NA) fetch(pos + 2, (pos + 2) % 3);
             const int a = pos >> 1, u = pos & 1, buf = pos % 3;
             const int sp = (int)((WR == 1 || a < 2 ? e_mine0 : e_mine1) & 1u);
             const int idx = TILE == 128 ? (int)(fpw[buf] >> (16 * j)) : (int)fpw[buf];
@@ -422,8 +431,17 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
         // (the very last step re-fetches itself into the idle stage: no branch around the loads; en = e there)
         const int more = tk + 1 < Tk ? 1 : 0;
         const PfEntries en = entries(tk + more);
-        // this wavefront's tile rows: r (tile 128), 2 r and 2 r + 1 (tile 64)
-        const uint32_t em0 = WR == 1 ? (r ? e.v1 : e.v0) : (r ? e.v2 : e.v0), em1 = r ? e.v3 : e.v1;
+        // this wavefront's tile rows.  128 features: w4 (tile 128), 2 w4 and 2 w4 + 1 (tile 64); 64 features: w4 (tile
+        // 128), w / 2 (tile 64)
+        uint32_t em0, em1;
+        if constexpr (BM == 256) {
+            em0 = WR == 1 ? (w4 ? e.v1 : e.v0) : (w4 ? e.v2 : e.v0);
+            em1 = w4 ? e.v3 : e.v1;
+        } else {
+            const uint32_t lo = (w & 2) ? e.v1 : e.v0, hi = (w & 2) ? e.v3 : e.v2;
+            em0 = TILE == 128 ? (w4 ? e.v1 : e.v0) : (w4 ? hi : lo);
+            em1 = em0;
+        }
         if constexpr (KPT == 2) {
             step(2 * tk, em0, em1, 2 * tk + 1, e);
             step(2 * tk + 1, em0, em1, 2 * tk + 1 + more, en);
@@ -438,28 +456,28 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
     // the last matrix instructions may still be writing their accumulators: 16-pass results need up to 18 wait
     // states before another unit may read them
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-    // acc[a][b][i]: feature n0 + 128 r + 32 a + 8 (i/4) + 4 q + i%4, row m0 + 64 wm + 32 b + i32
+    // acc[a][b][i]: feature n0 + fo + 32 a + 8 (i/4) + 4 q + i%4, row m0 + 64 wm + 32 b + i32
     // (blocks of the last feature block past N computed on whatever was in LDS; nothing of theirs is stored)
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int64_t m = m0 + 64 * wm + 32 * b + i32;
         if (m >= M) continue;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            if (n0 + 128 * r + 32 * a >= N) continue;
+        for (int a = 0; a < NA; ++a) {
+            if (n0 + fo + 32 * a >= N) continue;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
                 // partial products stay fp32; their sum is rounded by the reduction
-                store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + 128 * r + 32 * a + 8 * g + 4 * q, v, SPLIT ? 0 : ybf16);
+                store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + fo + 32 * a + 8 * g + 4 * q, v, SPLIT ? 0 : ybf16);
             }
         }
     }
 }
 
 // K slices per output tile of the LDS-staged kernel: as prefill_wreg_split, each slice at least 512 columns long.
-int prefill_lds_split(const GemmArgs& a, int requested) {
-    const int tiles = (int)(((a.N + kPfBN - 1) / kPfBN) * ((a.M + kPfBM - 1) / kPfBM));
+int prefill_lds_split(const GemmArgs& a, int requested, int bm) {
+    const int tiles = (int)(((a.N + kPfBN - 1) / kPfBN) * ((a.M + bm - 1) / bm));
     const int min_tiles = 512 / a.tile;
     int s = requested;
     if (s <= 0) {
@@ -477,36 +495,84 @@ int prefill_lds_split(const GemmArgs& a, int requested) {
     return s < 2 ? 1 : s;
 }
 
-// Kernel choice.  variant 0 (default): tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds;
-// tile 64 -> prefill_kernel_lds.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds, 3 prefill_kernel_wreg
-// (each falling back to the default choice where it does not apply).
-template <int TILE>
+// Blocks of 128 rows or of 256?  Few rows leave most of a 256-row block empty, and a weight of few feature blocks
+// fills the chip only through a deep K split, whose partial products are written and read again.  Both sides are
+// estimated from measured rates:
+//     us = rounds x K-steps per workgroup x t_step + 3 + (split > 1 ? 3 + (2 split + 1) M N 4 B / 5.5 TB/s : 0)
+// with t_step = 1.0 us (weights-in-registers kernel), 1.45 (LDS-staged, 256 rows), 0.85 (LDS-staged, 128 rows: bound
+// by LDS reads - a wavefront's 64 x 64 outputs reuse an operand half as often as 128 x 64).  The 256-row side takes the
+// split its launcher would take; the 128-row side its best split of at most 8 slices of at least 512 columns that the
+// workspace holds.  Returns true, and the split, when 128 rows are estimated at least 3 % faster.
+static double pf_estimate(const GemmArgs& a, int blocks, int split, double t_step) {
+    const int rounds = (blocks * split + a.n_cus - 1) / a.n_cus;
+    const int steps = ((a.Tk + split - 1) / split) * (a.tile / kStepCols);
+    double us = rounds * steps * t_step + 3.0;
+    if (split > 1) us += 3.0 + (2.0 * split + 1.0) * (double)a.M * (double)a.N * 4.0 / 5.5e6;
+    return us;
+}
+
+bool prefill_prefers_128_rows(const GemmArgs& a, int* split) {
+    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN);
+    const int b256 = tiles_n * (int)((a.M + 255) / 256), b128 = tiles_n * (int)((a.M + 127) / 128);
+    const bool wreg = a.tile == 128 && prefill_wreg_supports(a);
+    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 1.0 : 1.45);
+    const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
+    const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
+    const int longest = a.Tk * a.tile / 512;
+    double best = 0.0;
+    *split = 1;
+    for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
+        const double us = pf_estimate(a, b128, sp, 0.85);
+        if (sp == 1 || us < best) { best = us; *split = sp; }
+    }
+    return best < 0.97 * us256;
+}
+
+// Kernel choice.  variant 0 (default): prefill_kernel_lds with blocks of 128 rows where prefill_prefers_128_rows says so
+// (no split requested); else tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds with blocks
+// of 256 rows.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds (256 rows), 3 prefill_kernel_wreg, 4
+// prefill_kernel_lds with 128 rows (each falling back to the default choice where it does not apply).
+template <int TILE, int BM>
 static void launch_prefill_lds(const GemmArgs& a, int split_k, hipStream_t stream) {
-    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, false>),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
-    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, true>),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+    constexpr int kLds = pf_lds_bytes(BM);
+    static const hipError_t granted0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, false, BM>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    static const hipError_t granted1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel_lds<TILE, true, BM>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     (void)granted0;
     (void)granted1;
-    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kPfBM - 1) / kPfBM);
+    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + BM - 1) / BM);
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    const int split = prefill_lds_split(a, split_k);
+    const int split = prefill_lds_split(a, split_k, BM);
     if (split == 1) {
-        hipLaunchKernelGGL((prefill_kernel_lds<TILE, false>), dim3(grid), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
-                           a.Tk, tiles_n, tiles_m, a.Y, a.ybf16);
+        hipLaunchKernelGGL((prefill_kernel_lds<TILE, false, BM>), dim3(grid), dim3(512), kLds, stream, a.X, a.M, a.N, a.K, a.payload,
+                           a.table, a.Tk, tiles_n, tiles_m, a.Y, a.ybf16);
     } else {
-        hipLaunchKernelGGL((prefill_kernel_lds<TILE, true>), dim3(grid, split), dim3(512), kPfLds, stream, a.X, a.M, a.N, a.K, a.payload,
+        hipLaunchKernelGGL((prefill_kernel_lds<TILE, true, BM>), dim3(grid, split), dim3(512), kLds, stream, a.X, a.M, a.N, a.K, a.payload,
                            a.table, a.Tk, tiles_n, tiles_m, a.ws, 0);
         wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, a.ybf16, stream);
     }
 }
 
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream) {
+    if (variant == 0 && split_k == 0) {
+        int split128 = 1;
+        if (prefill_prefers_128_rows(a, &split128)) {
+            if (a.tile == 128) launch_prefill_lds<128, 128>(a, split128, stream);
+            else launch_prefill_lds<64, 128>(a, split128, stream);
+            return;
+        }
+    }
     if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, split_k, stream); return; }
+    if (variant == 4) {   // the LDS-staged kernel with blocks of 128 rows
+        if (a.tile == 128) launch_prefill_lds<128, 128>(a, split_k, stream);
+        else launch_prefill_lds<64, 128>(a, split_k, stream);
+        return;
+    }
     if (variant != 1) {
-        if (a.tile == 128) launch_prefill_lds<128>(a, split_k, stream);
-        else launch_prefill_lds<64>(a, split_k, stream);
+        if (a.tile == 128) launch_prefill_lds<128, 256>(a, split_k, stream);
+        else launch_prefill_lds<64, 256>(a, split_k, stream);
         return;
     }
     dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);

@@ -74,7 +74,9 @@ void wr_reduce(const float* ws, size_t n4, int slices, float* Y, int ybf16, hipS
 void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t stream);
 bool prefill_wreg_supports(const GemmArgs& a);                  // tile 128, K <= 32768, M * K * 2 < 4 GB
 int prefill_wreg_split(const GemmArgs& a, int requested);       // K slices per output tile the launch will use
-int prefill_lds_split(const GemmArgs& a, int requested);        // the same for the LDS-staged kernel (tile 64; variant 2)
+int prefill_lds_split(const GemmArgs& a, int requested, int bm = 256);   // the same for the LDS-staged kernel with blocks of bm rows
+// whether the default choice (variant 0, no split requested) is the LDS-staged kernel with blocks of 128 rows, and its split
+bool prefill_prefers_128_rows(const GemmArgs& a, int* split);
 // K slices for the last *tail tiles of an unsplit launch with a part-filled last round (needs a.ws); 1 = none
 int prefill_wreg_tail(const GemmArgs& a, int* tail);
 int prefill_wreg_tail_of(int tiles, const GemmArgs& a, int* tail);   // the same for a given tile count (sets of weights)

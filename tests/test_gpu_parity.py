@@ -458,6 +458,36 @@ def test_tile64_prefill(dev, N, K, M, f):
     p.P.close()
 
 
+@pytest.mark.parametrize("t,N,K,M,f", [(64, 2112, 1088, 700, 0.6), (64, 320, 2048, 257, 1.0), (64, 576, 64, 130, 0.5),
+                                       (128, 2176, 1152, 700, 0.6), (128, 384, 2048, 100, 1.0), (128, 1024, 1024, 512, 0.0),
+                                       (128, 640, 128, 129, 0.5)])
+def test_prefill_blocks_of_128_rows(dev, t, N, K, M, f):
+    """The LDS-staged prefill kernel with blocks of 128 rows of X (a wavefront = 64 features x 64 rows): both mask tiles,
+    feature counts that leave part of the last block empty, ragged M, one K-step, K split over a poisoned workspace,
+    bf16 output, repeated launches bit-equal, rows independent of the rows behind them."""
+    print(f"128-row blocks tile={t} N={N} K={K} M={M} f={f}", flush=True)
+    c = synth.make_case("pf128", N, K, M, t, f, seed=14)
+    p = Prepared(c, dev)
+    Yo = p.oracle_gemm(c.X)
+    kw = dict(path=B.PATH_PREFILL, variant=4)
+    Y = p.gemm(c.X, **kw)
+    p.check(c.X, Y, Yo, f"128-row blocks tile {t} {N}x{K} M={M}")
+    for rep in range(3):
+        assert np.array_equal(p.gemm(c.X, **kw), Y), "launches of one configuration must be bit-equal"
+    Mr = M - 70
+    assert np.array_equal(p.gemm(c.X[:Mr], **kw), Y[:Mr]), "rows must not depend on how many rows follow them"
+    check_bf16(p.gemm_bf16(c.X, **kw), Yo, row_norms(c.X), p.wn, K, "128-row blocks, bf16 output")
+    ws = torch.empty(8 * M * N, device=dev, dtype=torch.float32)
+    for more in (dict(workspace=ws), dict(workspace=ws, split_k=3), dict(workspace=ws, split_k=8)):
+        if more.get("split_k", 0) > K // t:
+            continue
+        ws.fill_(float("nan"))
+        Ys = p.gemm(c.X, **kw, **more)
+        p.check(c.X, Ys, Yo, f"128-row blocks split_k={more.get('split_k', 0)}")
+        assert np.array_equal(p.gemm(c.X, **kw, **more), Ys)
+    p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
@@ -611,7 +641,7 @@ def test_tune_report_table_and_small_execution_tile(dev):
     for sch, us in rep:
         print(f"  candidate {sch}: {us:.1f} us", flush=True)
     pre = {sch["variant"]: us for sch, us in rep if sch["path"] == B.PATH_PREFILL and sch["split_k"] == 1}
-    assert set(pre) == {0, 1, 2}, "the three execution tiles of the prefill path must all be timed"
+    assert set(pre) == {0, 1, 2, 4}, "the four execution tiles of the prefill path must all be timed"
     assert pre[1] > pre[0], f"128 x 128 execution tile {pre[1]:.1f} us is not slower than 256 x 256 {pre[0]:.1f} us"
     assert all(sch["path"] == B.PATH_PREFILL for sch, _ in rep), "decode passes are no contenders at M = 2048"
     rep1 = B.patch_tune_all(X, 1, p.P, Y, stream=stream(), reps=5)
@@ -643,7 +673,7 @@ def test_prefill_long_k(dev):
     p.P.close()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
 def test_prefill_kernel_variants(dev, variant):
     """Every prefill kernel variant (patch_gemm_opts.variant) against the oracle: odd tile-row count (N % 256 = 128),
     ragged M, K of several tiles, all-dense / mixed / all-2:4 maps."""

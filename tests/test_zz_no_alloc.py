@@ -52,13 +52,14 @@ def test_static_scratch_refuses_oversized_schedules():
     dev = torch.device("cuda:0")
     st = torch.cuda.current_stream().cuda_stream
     N = K = 5120
-    c = synth.make_case("static_big", N, K, 512, 128, 0.0, seed=52, with_mask=False)
+    M = 1024
+    c = synth.make_case("static_big", N, K, M, 128, 0.0, seed=52, with_mask=False)
     P = B.patch_pack(_dev_bf16(c.W, dev), N, K, np.ones_like(c.tile_map), 128, st)
     X = _dev_bf16(c.X, dev)
-    assert B.patch_gemm_workspace_bytes(512, P) > B.STATIC_SCRATCH_BYTES
-    Y = torch.full((512, N), 3.0, device=dev, dtype=torch.float32)
+    assert B.patch_gemm_workspace_bytes(M, P) > B.STATIC_SCRATCH_BYTES
+    Y = torch.full((M, N), 3.0, device=dev, dtype=torch.float32)
     with pytest.raises(B.PatchError) as e:
-        B.patch_gemm_static(X, 512, P, Y, st)
+        B.patch_gemm_static(X, M, P, Y, st)
     assert e.value.status == B.ERR_SIZE
     torch.cuda.synchronize()
     assert bool((Y == 3.0).all()), "a refused call must not launch anything"
