@@ -313,7 +313,8 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
 // measurements; it reproduces the crossovers above - M = 192 at 4096 x 4096, 128 from 5120 features - and also holds
 // for long-K weights of few features such as 4096 x 11008, where 16 output tiles run 172 steps each: 144 us, against
 // 45 us for a 64-row pass):
-//   unsplit prefill launch  rounds x 64-column steps x 1.0 us (tile 64 on the LDS-staged kernel: 1.45 us)
+//   unsplit prefill launch  rounds x 64-column steps x 1.0 us (tile 64 on the LDS-staged kernel: 1.45 us), or with
+//                           blocks of 128 rows x 0.85 us, whichever is less (launch_prefill makes the same choice)
 //   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256))
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
     const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
@@ -323,7 +324,10 @@ static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* op
     const double steps = (double)P->K / 64.0;
     const int64_t tiles = ((P->N + 255) / 256) * ((M + 255) / 256);
     const double rounds = (double)((tiles + P->n_cus - 1) / P->n_cus);
-    const double prefill_us = rounds * steps * (P->tile == 128 ? 1.0 : 1.45);
+    const int64_t tiles128 = ((P->N + 255) / 256) * ((M + 127) / 128);   // blocks of 128 rows: 0.85 us per step
+    const double us128 = (double)((tiles128 + P->n_cus - 1) / P->n_cus) * steps * 0.85;
+    const double us256 = rounds * steps * (P->tile == 128 ? 1.0 : 1.45);
+    const double prefill_us = us128 < us256 ? us128 : us256;
     const double groups = (double)(P->N / 64);
     const double pass_us = steps * 0.3 * (1.0 + 0.4 * (groups < 256.0 ? groups / 256.0 : 1.0));
     const double passes = (double)((M + kDecodeRows - 1) / kDecodeRows);
