@@ -364,8 +364,11 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
     const int lane_meta = ((i32 >> 4) * 64 + 16 * q + (i32 & 15)) * ESZ;
     // One K-step: wait for the stage, refill the other one, multiply.  e_mine[i]: table entry of this wavefront's
     // i-th tile row at step ks; (pf_ks, pf_e): the step to fetch into the idle stage and its entries.
-    // (A third stage, fetched two steps ahead with counted waits, was no faster with blocks of 128 rows: the step is
-    // bound by LDS reads, not by the latency of the loads.)
+    // (With blocks of 128 rows no single unit bounds the step - counters: LDS busy a third of the cycles, matrix pipes
+    // a third; leaving out the matrix instructions, the global -> LDS loads or the LDS reads saves 18 %, 30 % or 12 %
+    // of it.  The largest piece is the global -> LDS path: 48 KB per step take about 0.75 us.  A third stage fetched two
+    // steps ahead with counted waits, and a third stage with the X fragments of the next step read between this step's
+    // matrix instructions, both measured 3 - 8 % slower than this loop.)
     auto step = [&](int ks, uint32_t e_mine0, uint32_t e_mine1, int pf_ks, const PfEntries pf_e) {
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -499,8 +502,8 @@ int prefill_lds_split(const GemmArgs& a, int requested, int bm) {
 // fills the chip only through a deep K split, whose partial products are written and read again.  Both sides are
 // estimated from measured rates:
 //     us = rounds x K-steps per workgroup x t_step + 3 + (split > 1 ? 3 + (2 split + 1) M N 4 B / 5.5 TB/s : 0)
-// with t_step = 1.0 us (weights-in-registers kernel), 1.45 (LDS-staged, 256 rows), 0.85 (LDS-staged, 128 rows: bound
-// by LDS reads - a wavefront's 64 x 64 outputs reuse an operand half as often as 128 x 64).  The 256-row side takes the
+// with t_step = 1.0 us (weights-in-registers kernel), 1.45 (LDS-staged, 256 rows), 0.85 (LDS-staged, 128 rows: more
+// than half of a 256-row step, see the note at the step loop).  The 256-row side takes the
 // split its launcher would take; the 128-row side its best split of at most 8 slices of at least 512 columns that the
 // workspace holds.  Returns true, and the split, when 128 rows are estimated at least 3 % faster.
 static double pf_estimate(const GemmArgs& a, int blocks, int split, double t_step) {
