@@ -610,6 +610,22 @@ def main():
         fn = lambda i: B.patch_probe_stream_read(big.data_ptr(), 16, 1, 64, sink, stream)
         timed(fn, 20)
         ceil["empty_launch_us"] = round(sorted(timed(fn, 200) / 200 for _ in range(5))[2] * 1e6, 2)
+        # what one compute unit fetches per K-step of the LDS-staged prefill kernels, on its own: 48 KB rounds (or 24 KB
+        # rounds, one or two in flight) by 8 wavefronts; every workgroup on its own cache-resident chunk, or walking 48 MB
+        fill = dict()
+        rounds = 256
+        empty_us = ceil["empty_launch_us"]
+        for label, wg, chunks in (("cache_resident_all_cus", n_cus, n_cus), ("streaming_16_workgroups", 16, 1024), ("streaming_all_cus", n_cus, 1024)):
+            for kind, name, kb in ((0, "global_to_lds_48KB", 48), (2, "global_to_registers_48KB", 48), (4, "global_to_lds_24KB", 24),
+                                   (3, "global_to_lds_24KB_two_in_flight", 24)):
+                fn = lambda _i, kind=kind, wg=wg, chunks=chunks: B.patch_probe_lds_fill(kind, big, chunks * 48 * 1024, wg, rounds, sink, stream)
+                timed(fn, 2)
+                per_round = (min(timed(fn, 5) / 5 for _ in range(3)) * 1e6 - empty_us) / rounds
+                fill[f"{name}_{label}"] = dict(us_per_round=round(per_round, 3), GBps_per_cu=round(kb * 1024 / per_round / 1e3, 1))
+        ceil["cu_fetch"] = fill
+        ceil["cu_fetch_note"] = ("a round = every wavefront of a workgroup of 8 issues its 1 KB pieces, waits for them and meets the others at a "
+                                 "barrier; the per-compute-unit rate is the same with one or two rounds in flight, so it is a throughput, not "
+                                 "a latency: it bounds a K-step of the kernels that stage both operands (48 KB with blocks of 128 rows)")
         del big, sink
         # vendor dense GEMM (bf16 output) on the headline shapes, for context: same macro tile class, same part
         vend = []

@@ -311,7 +311,7 @@ void patch_free4(patch_packed4* P);
 
 /*
  * Measurement probes (this project's; no passage of the paper): kernels that run nothing of the method, for the
- * measured ceilings the benchmark prints beside the product kernels.  Both are asynchronous on `stream` and
+ * measured ceilings the benchmark prints beside the product kernels.  All are asynchronous on `stream` and
  * allocate nothing; the caller times them with events.
  *   patch_probe_matrix_rate  `workgroups` workgroups of 4 wavefronts each run `iters` rounds of 16 independent matrix
  *                            instructions on register operands: kind 0 = v_mfma_f32_16x16x32_bf16 (16384 flop each),
@@ -325,6 +325,14 @@ void patch_free4(patch_packed4* P);
  *   patch_probe_stream_read  reads `bytes` (16-byte aligned, multiple of 16) at src with 128-bit loads, grid-stride
  *                            over workgroups x threads (threads a multiple of 64, at most 1024); out: DEVICE,
  *                            workgroups * threads 32-bit words.
+ *   patch_probe_lds_fill     `workgroups` workgroups of 8 wavefronts each fetch 48 KB per round (six 1 KB pieces per
+ *                            wavefront, then a wait and a barrier: the fetch pattern of a K-step of the LDS-staged
+ *                            prefill kernel) for `rounds` rounds, walking over the floor(bytes / 48 KB) chunks of src
+ *                            (16-byte aligned): kind 0 = global -> LDS directly, kind 1 = global -> registers -> LDS,
+ *                            kind 2 = global -> registers only; kind 4 = as 0 with rounds of 24 KB (three pieces per
+ *                            wavefront) into alternating halves of the buffer, kind 3 = as 4 but waiting only for the
+ *                            round before the one just issued (two rounds in flight).  out: DEVICE, workgroups * 512
+ *                            32-bit words.
  * Errors: PATCH_ERR_ARG, PATCH_ERR_SIZE (a buffer too small), PATCH_ERR_HIP.
  */
 #define PATCH_PROBE_OPERAND_BYTES ((size_t)12 * 256 * 16)
@@ -332,6 +340,8 @@ patch_status patch_probe_matrix_rate(int kind, const void* operands, size_t oper
                                      size_t out_bytes, void* stream);
 patch_status patch_probe_stream_read(const void* src, size_t bytes, int workgroups, int threads, void* out, size_t out_bytes,
                                      void* stream);
+patch_status patch_probe_lds_fill(int kind, const void* src, size_t bytes, int workgroups, int rounds, void* out, size_t out_bytes,
+                                  void* stream);
 
 void patch_free(patch_packed* P);
 const char* patch_strerror(patch_status s);

@@ -143,6 +143,59 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const cl_u32x4* __res
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = fold;
 }
 
+
+// A workgroup of 8 wavefronts fetches 48 KB per round - what a K-step of the LDS-staged prefill kernel with blocks of
+// 128 rows fetches - in six 1 KB pieces per wavefront, waits for them and meets at a barrier, `rounds` times over
+// a window of `chunks` 48 KB chunks of src (chunk = (workgroup + round * workgroups) % chunks).
+//   KIND 0: global -> LDS directly (global_load_lds, 16 bytes per lane)
+//   KIND 1: global -> registers (128-bit loads) -> LDS (ds_write_b128)
+//   KIND 2: global -> registers only, folded into one word
+//   KIND 4: as 0 with rounds of half a chunk (three pieces per wavefront) into alternating halves of the buffer
+//   KIND 3: as 4, but a round waits only for the round before it (two rounds in flight)
+// One word per thread that depends on what was fetched goes to `out`.
+template <int KIND>
+__global__ __launch_bounds__(512) void lds_fill_kernel(const uint8_t* __restrict__ src, unsigned chunks, int rounds, uint32_t* __restrict__ out) {
+    constexpr int kChunk = 48 * 1024;
+    __shared__ __attribute__((aligned(16))) uint8_t buf[kChunk];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t fold = 0;
+    for (int r = 0; r < rounds; ++r) {
+        const unsigned c = (unsigned)(((size_t)blockIdx.x + (size_t)r * gridDim.x) % chunks);
+        const uint8_t* g = src + (size_t)c * kChunk + (size_t)(w * 6) * 1024 + lane * 16;
+        if constexpr (KIND == 0) {
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i * 1024),
+                                                 (__attribute__((address_space(3))) void*)(buf + (w * 6 + i) * 1024), 16, 0, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else if constexpr (KIND == 3 || KIND == 4) {
+            // half a chunk per round into alternating halves of the buffer; KIND 3 waits for the round before this one
+            // only (two rounds in flight), KIND 4 for this one
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i * 1024),
+                                                 (__attribute__((address_space(3))) void*)(buf + ((r & 1) * 24 + w * 3 + i) * 1024), 16, 0, 0);
+            if constexpr (KIND == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            cl_u32x4 v[6];
+#pragma unroll
+            for (int i = 0; i < 6; ++i) v[i] = *reinterpret_cast<const cl_u32x4*>(g + i * 1024);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                if constexpr (KIND == 1) *reinterpret_cast<cl_u32x4*>(buf + (w * 6 + i) * 1024 + lane * 16) = v[i];
+                else fold ^= v[i][0] ^ v[i][1] ^ v[i][2] ^ v[i][3];
+            }
+        }
+        __syncthreads();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if constexpr (KIND != 2) fold = *reinterpret_cast<const uint32_t*>(buf + ((tid * 4 + 64) % kChunk));
+    out[(size_t)blockIdx.x * 512 + tid] = fold;
+}
+
 }  // namespace patch
 
 extern "C" {
@@ -171,6 +224,26 @@ patch_status patch_probe_stream_read(const void* src, size_t bytes, int workgrou
     if (out_bytes < (size_t)workgroups * threads * sizeof(uint32_t)) return PATCH_ERR_SIZE;
     hipLaunchKernelGGL(patch::stream_read_kernel, dim3(workgroups), dim3(threads), 0, static_cast<hipStream_t>(stream),
                        static_cast<const patch::cl_u32x4*>(src), bytes / 16, static_cast<uint32_t*>(out));
+    return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
+}
+
+patch_status patch_probe_lds_fill(int kind, const void* src, size_t bytes, int workgroups, int rounds, void* out, size_t out_bytes,
+                                  void* stream) {
+    if (!src || !out || kind < 0 || kind > 4 || workgroups < 1 || workgroups > 65536 || rounds < 1) return PATCH_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(out) & 3u)) return PATCH_ERR_ARG;
+    const size_t chunks = bytes / (48 * 1024);
+    if (chunks < 1 || chunks > 0xFFFFFFFFu) return PATCH_ERR_SIZE;
+    if (out_bytes < (size_t)workgroups * 512 * sizeof(uint32_t)) return PATCH_ERR_SIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* p = static_cast<const uint8_t*>(src);
+    uint32_t* o = static_cast<uint32_t*>(out);
+    switch (kind) {
+        case 0: hipLaunchKernelGGL(patch::lds_fill_kernel<0>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
+        case 1: hipLaunchKernelGGL(patch::lds_fill_kernel<1>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
+        case 2: hipLaunchKernelGGL(patch::lds_fill_kernel<2>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
+        case 3: hipLaunchKernelGGL(patch::lds_fill_kernel<3>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
+        default: hipLaunchKernelGGL(patch::lds_fill_kernel<4>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
+    }
     return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
 }
 

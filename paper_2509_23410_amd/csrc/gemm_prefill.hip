@@ -366,9 +366,11 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
     // i-th tile row at step ks; (pf_ks, pf_e): the step to fetch into the idle stage and its entries.
     // (With blocks of 128 rows no single unit bounds the step - counters: LDS busy a third of the cycles, matrix pipes
     // a third; leaving out the matrix instructions, the global -> LDS loads or the LDS reads saves 18 %, 30 % or 12 %
-    // of it.  The largest piece is the global -> LDS path: 48 KB per step take about 0.75 us.  A third stage fetched two
-    // steps ahead with counted waits, and a third stage with the X fragments of the next step read between this step's
-    // matrix instructions, both measured 3 - 8 % slower than this loop.)
+    // of it.  The largest piece is the global -> LDS path: a compute unit fetches a step's 48 KB in 0.53 us when they
+    // hit in L2 and in 0.76 us when they come from HBM (patch_probe_lds_fill), the same with one or two rounds in
+    // flight - a rate, not a latency.  Accordingly a third stage fetched two steps ahead with counted waits, and a third
+    // stage with the X fragments of the next step read between this step's matrix instructions, both measured 3 - 8 %
+    // slower than this loop.)
     auto step = [&](int ks, uint32_t e_mine0, uint32_t e_mine1, int pf_ks, const PfEntries pf_e) {
         const int stage = ks & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

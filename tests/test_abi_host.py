@@ -63,6 +63,9 @@ def test_argument_errors_without_device():
     assert L.patch_gemm_static(fake, 1, 0, fake, 0) == B.ERR_ARG
     assert L.patch_probe_matrix_rate(4, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
     assert L.patch_probe_stream_read(fake, 1024, 1, 100, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_probe_lds_fill(5, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_probe_lds_fill(0, fake, 1000, 1, 1, fake, 1 << 20, 0) == B.ERR_SIZE        # less than one 48 KB chunk
+    assert L.patch_probe_lds_fill(0, fake, 1 << 20, 4, 1, fake, 1024, 0) == B.ERR_SIZE        # out too small
     # 4-bit storage
     assert L.patch_pack4(0, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
     assert L.patch_pack4(fake, 128, 128, 0, 64, 0, ctypes.byref(out)) == B.ERR_ARG
