@@ -232,8 +232,9 @@ def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path):
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert r.returncode == 0, r.stdout[-2000:]
     text = out.read_text()
-    bodies = re.findall(r"^(_ZN5patch18prefill_kernel_lds\w+):.*?\n(.*?)^\.Lfunc_end", text, re.S | re.M)
-    assert len(bodies) >= 8, [b[0] for b in bodies]      # tile 128 / 64 x whole / split x blocks of 256 / 128 rows
+    bodies = re.findall(r"^(_ZN5patch1[89]prefill_kernel_(?:lds|areg)\w+):.*?\n(.*?)^\.Lfunc_end", text, re.S | re.M)
+    # prefill_kernel_lds: tile 128 / 64 x whole / split x blocks of 256 / 128 rows; prefill_kernel_areg: whole / split
+    assert len(bodies) >= 10, [b[0] for b in bodies]
 
     def regs(tok):
         out_ = set()
@@ -256,7 +257,7 @@ def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path):
                     since.setdefault(r, i)
                 last = i
         # 8 accumulator tiles of 16 registers with blocks of 256 rows (template argument Li256E), 4 with 128
-        want = 128 if name.endswith("Li256EEEvPKtlllPKhPKjiiiPfi") else 64
+        want = 128 if name.endswith("Li256EEEvPKtlllPKhPKjiiiPfi") else 64      # prefill_kernel_areg: 4 tiles
         assert len(since) == want and last is not None, (name, len(since))
         # ... and up to the wait states the kernel itself puts before its output stage reads the accumulators.  A tile
         # that no matrix instruction has written yet is still a constant (zero) to the compiler, which may keep other

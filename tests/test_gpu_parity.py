@@ -462,14 +462,26 @@ def test_tile64_prefill(dev, N, K, M, f):
                                        (128, 2176, 1152, 700, 0.6), (128, 384, 2048, 100, 1.0), (128, 1024, 1024, 512, 0.0),
                                        (128, 640, 128, 129, 0.5)])
 def test_prefill_blocks_of_128_rows(dev, t, N, K, M, f):
+    _blocks_of_128_rows(dev, t, N, K, M, f, 4)
+
+
+@pytest.mark.parametrize("N,K,M,f", [(2176, 1152, 700, 0.6), (384, 2048, 100, 1.0), (1024, 1024, 512, 0.0), (640, 128, 129, 0.5),
+                                     (4224, 512, 300, 0.3)])
+def test_prefill_128_rows_weights_in_registers(dev, N, K, M, f):
+    """Blocks of 128 rows with the weight fragments loaded straight into registers (mask tile 128): the same cases and
+    checks as the LDS-staged kernel, plus a weight of 33 tile rows."""
+    _blocks_of_128_rows(dev, 128, N, K, M, f, 5)
+
+
+def _blocks_of_128_rows(dev, t, N, K, M, f, variant):
     """The LDS-staged prefill kernel with blocks of 128 rows of X (a wavefront = 64 features x 64 rows): both mask tiles,
     feature counts that leave part of the last block empty, ragged M, one K-step, K split over a poisoned workspace,
     bf16 output, repeated launches bit-equal, rows independent of the rows behind them."""
-    print(f"128-row blocks tile={t} N={N} K={K} M={M} f={f}", flush=True)
+    print(f"128-row blocks variant={variant} tile={t} N={N} K={K} M={M} f={f}", flush=True)
     c = synth.make_case("pf128", N, K, M, t, f, seed=14)
     p = Prepared(c, dev)
     Yo = p.oracle_gemm(c.X)
-    kw = dict(path=B.PATH_PREFILL, variant=4)
+    kw = dict(path=B.PATH_PREFILL, variant=variant)
     Y = p.gemm(c.X, **kw)
     p.check(c.X, Y, Yo, f"128-row blocks tile {t} {N}x{K} M={M}")
     for rep in range(3):
@@ -641,7 +653,7 @@ def test_tune_report_table_and_small_execution_tile(dev):
     for sch, us in rep:
         print(f"  candidate {sch}: {us:.1f} us", flush=True)
     pre = {sch["variant"]: us for sch, us in rep if sch["path"] == B.PATH_PREFILL and sch["split_k"] == 1}
-    assert set(pre) == {0, 1, 2, 4}, "the four execution tiles of the prefill path must all be timed"
+    assert set(pre) == {0, 1, 2, 4, 5}, "every execution tile of the prefill path must be timed"
     assert pre[1] > pre[0], f"128 x 128 execution tile {pre[1]:.1f} us is not slower than 256 x 256 {pre[0]:.1f} us"
     assert all(sch["path"] == B.PATH_PREFILL for sch, _ in rep), "decode passes are no contenders at M = 2048"
     rep1 = B.patch_tune_all(X, 1, p.P, Y, stream=stream(), reps=5)
@@ -673,7 +685,7 @@ def test_prefill_long_k(dev):
     p.P.close()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
 def test_prefill_kernel_variants(dev, variant):
     """Every prefill kernel variant (patch_gemm_opts.variant) against the oracle: odd tile-row count (N % 256 = 128),
     ragged M, K of several tiles, all-dense / mixed / all-2:4 maps."""
