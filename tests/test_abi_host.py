@@ -165,7 +165,7 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
 
 
 @pytest.mark.parametrize("source,kernel,at_least", [("gemm_decode.hip", "decode_kernel", 4), ("gemm_mid.hip", "mid_kernel", 4),
-                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2)])
+                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2), ("gemm_prefill.hip", "prefill_kernel_areg", 2)])
 def test_kernels_with_untracked_loads_do_not_spill(source, kernel, at_least):
     """decode_kernel and mid_kernel issue their loads from asm statements and wait for them in a later one; until
     that wait the destinations must stay where the loads write them.  A spill (or any scratch use) of such a register
