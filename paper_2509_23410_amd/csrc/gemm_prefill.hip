@@ -704,15 +704,17 @@ int prefill_lds_split(const GemmArgs& a, int requested, int bm) {
 // fills the chip only through a deep K split, whose partial products are written and read again.  Both sides are
 // estimated from measured rates:
 //     us = rounds x K-steps per workgroup x t_step + 3 + (split > 1 ? 3 + (2 split + 1) M N 4 B / 5.5 TB/s : 0)
-// with t_step = 1.0 us (weights-in-registers kernel), 1.45 (LDS-staged, 256 rows), and for 128 rows 0.70 (mask tile 128:
-// prefill_kernel_areg) or 0.85 (mask tile 64: LDS-staged; more than half of a 256-row step, see the note at its step
-// loop).  The 256-row side takes the
+// A step is slower the fuller the chip (shared L2 bandwidth, power): t_step = t0 + t1 x min(1, workgroups / compute
+// units), with (t0, t1) = (0.93, 0.25) us for the weights-in-registers kernel of 256 rows, (1.30, 0.15) LDS-staged with
+// 256 rows, (0.67, 0.18) prefill_kernel_areg (128 rows, mask tile 128), (0.80, 0.13) LDS-staged with 128 rows (mask
+// tile 64; more than half of a 256-row step, see the note at its step loop).  The 256-row side takes the
 // split its launcher would take; the 128-row side its best split of at most 8 slices of at least 512 columns that the
 // workspace holds.  Returns true, and the split, when 128 rows are estimated at least 3 % faster.
-static double pf_estimate(const GemmArgs& a, int blocks, int split, double t_step) {
+static double pf_estimate(const GemmArgs& a, int blocks, int split, double t0, double t1) {
     const int rounds = (blocks * split + a.n_cus - 1) / a.n_cus;
     const int steps = ((a.Tk + split - 1) / split) * (a.tile / kStepCols);
-    double us = rounds * steps * t_step + 3.0;
+    const double fill = blocks * split < a.n_cus ? (double)(blocks * split) / a.n_cus : 1.0;
+    double us = rounds * steps * (t0 + t1 * fill) + 3.0;
     if (split > 1) us += 3.0 + (2.0 * split + 1.0) * (double)a.M * (double)a.N * 4.0 / 5.5e6;
     return us;
 }
@@ -721,14 +723,15 @@ bool prefill_prefers_128_rows(const GemmArgs& a, int* split) {
     const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN);
     const int b256 = tiles_n * (int)((a.M + 255) / 256), b128 = tiles_n * (int)((a.M + 127) / 128);
     const bool wreg = a.tile == 128 && prefill_wreg_supports(a);
-    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 1.0 : 1.45);
+    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 0.93 : 1.30,
+                                     wreg ? 0.25 : 0.15);
     const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
     const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
     const int longest = a.Tk * a.tile / 512;
     double best = 0.0;
     *split = 1;
     for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
-        const double us = pf_estimate(a, b128, sp, a.tile == 128 ? 0.70 : 0.85);
+        const double us = pf_estimate(a, b128, sp, a.tile == 128 ? 0.67 : 0.80, a.tile == 128 ? 0.18 : 0.13);
         if (sp == 1 || us < best) { best = us; *split = sp; }
     }
     return best < 0.97 * us256;
