@@ -714,6 +714,7 @@ def test_random_shapes_and_schedules(dev):
         p = Prepared(c, dev)
         Yo = p.oracle_gemm(c.X)
         scheds = [dict(), dict(path=B.PATH_DECODE), dict(path=B.PATH_PREFILL), dict(path=B.PATH_PREFILL, variant=1 if t == 64 else 2),
+                  dict(path=B.PATH_PREFILL, variant=4), dict(path=B.PATH_PREFILL, variant=5, workspace=ws),
                   dict(workspace=ws), dict(path=B.PATH_PREFILL, workspace=ws, split_k=int(rng.integers(2, 5))),
                   dict(path=B.PATH_DECODE, split_k=int(rng.integers(1, 9)))]
         for kw in scheds:
