@@ -314,7 +314,7 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
 // for long-K weights of few features such as 4096 x 11008, where 16 output tiles run 172 steps each: 144 us, against
 // 45 us for a 64-row pass):
 //   unsplit prefill launch  rounds x 64-column steps x 1.0 us (tile 64 on the LDS-staged kernel: 1.45 us), or with
-//                           blocks of 128 rows x 0.70 us (tile 64: 0.85), whichever is less (launch_prefill makes the
+//                           blocks of 128 rows x 0.70 us (tile 64: 0.75), whichever is less (launch_prefill makes the
 //                           same choice)
 //   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256))
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
@@ -325,8 +325,8 @@ static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* op
     const double steps = (double)P->K / 64.0;
     const int64_t tiles = ((P->N + 255) / 256) * ((M + 255) / 256);
     const double rounds = (double)((tiles + P->n_cus - 1) / P->n_cus);
-    const int64_t tiles128 = ((P->N + 255) / 256) * ((M + 127) / 128);   // blocks of 128 rows: 0.70 / 0.85 us per step
-    const double us128 = (double)((tiles128 + P->n_cus - 1) / P->n_cus) * steps * (P->tile == 128 ? 0.70 : 0.85);
+    const int64_t tiles128 = ((P->N + 255) / 256) * ((M + 127) / 128);   // blocks of 128 rows: 0.70 / 0.75 us per step
+    const double us128 = (double)((tiles128 + P->n_cus - 1) / P->n_cus) * steps * (P->tile == 128 ? 0.70 : 0.75);
     const double us256 = rounds * steps * (P->tile == 128 ? 1.0 : 1.45);
     const double prefill_us = us128 < us256 ? us128 : us256;
     const double groups = (double)(P->N / 64);
@@ -411,6 +411,7 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 2 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
     } else {
         add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, two wavefronts per SIMD (the tile-64 default)
+        add(PATCH_PATH_PREFILL, 1, 6, false);   // 256 x 256 with the weights in registers
         add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
         if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic
         if (workspace)
@@ -418,8 +419,7 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 4 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
     }
     if (M <= 4096) {   // 256 features x 128 rows per workgroup: beyond a few thousand rows never ahead
-        for (int v : {4, 5}) {   // LDS-staged; weights in registers (mask tile 128 only)
-            if (v == 5 && P->tile != 128) continue;
+        for (int v : {4, 5}) {   // LDS-staged; weights in registers
             add(PATCH_PATH_PREFILL, 1, v, false);
             if (workspace)
                 for (int sk : {2, 3, 4, 6, 8})
@@ -575,7 +575,7 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
         int split128 = 1;
         if (prefill_prefers_128_rows(a, &split128)) return split128 > 1 ? (size_t)split128 * (size_t)M * (size_t)P->N * sizeof(float) : 0;
     }
-    if (variant == 2 || variant == 4 || variant == 5 || !prefill_wreg_supports(a)) {   // whole-launch K split only
+    if (variant == 2 || variant == 4 || variant == 5 || (variant == 6 && a.tile == 64) || !prefill_wreg_supports(a)) {   // whole-launch K split only
         const int sl = prefill_lds_split(a, split_k, variant == 4 || variant == 5 ? 128 : 256);
         return sl > 1 ? (size_t)sl * (size_t)M * (size_t)P->N * sizeof(float) : 0;
     }

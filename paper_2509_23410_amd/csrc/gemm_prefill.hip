@@ -481,23 +481,24 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
 }
 
 // ------------------------------------------------------------------------------------------------------
-// Mask tile 128, blocks of 256 features x 128 rows, weights straight into registers ("areg").
+// Blocks of 256 features x BM rows with the weights straight into registers ("areg"): BM = 128 on both mask tiles (the
+// 128-row kernel of the default choice), BM = 256 on mask tile 64 (variant 6).
 //
-// The LDS-staged kernel with 128-row blocks is bound by what a compute unit can fetch per K-step (48 KB), and the
-// global -> LDS path is the slower way in (patch_probe_lds_fill).  Here only X goes that way (16 KB per step, two LDS
-// stages); a wavefront owns 32 features x ALL 128 rows, so its weight fragments are its own: each lane loads its
-// 16-byte pieces of the stored fragments (the gather the LDS kernel does with LDS reads) from global memory into
-// registers one step ahead, by ordinary loads the compiler tracks.  No weight byte is fetched twice and none passes
-// through LDS; the position dwords of a 2:4 tile (both K-steps in one dword) are loaded once per tile.
-//   wavefront w : features 32 w .. 32 w + 31 of the block (tile row w / 4, strips 2 (w % 4), + 1 of that tile)
-//   a step      : 4 positions (half-step u, row-block pair) of mma_step, X fragments read from LDS two positions ahead
+// The LDS-staged kernel is bound by what a compute unit can fetch per K-step, and the global -> LDS path is the
+// slower way in (patch_probe_lds_fill).  Here only X goes that way (BM x 128 bytes per step, two LDS stages); a
+// wavefront owns 32 features x ALL BM rows, so its weight fragments are its own: each lane loads its 16-byte pieces of
+// the stored fragments (the gather the LDS kernel does with LDS reads) from global memory into registers one step
+// ahead, by ordinary loads the compiler tracks, into two buffers that alternate (no copy).  No weight byte is fetched
+// twice and none passes through LDS.  Mask tile 128: the two buffers are a tile's two K-steps, and the position dwords
+// of a 2:4 tile (both K-steps in one dword) are loaded once per tile.  Mask tile 64: every step is a tile; steps go
+// in pairs.
+//   wavefront w : features 32 w .. 32 w + 31 of the block: tile row 32 w / TILE, two strips of that tile
+//   a step      : BM / 32 positions (half-step u, pair of 32-row blocks) of mma_step, X fragments read from LDS two
+//                 positions ahead
 // ------------------------------------------------------------------------------------------------------
-constexpr int kArBM = 128;
-constexpr int kArStage = kArBM * 128;     // 16 KB
-constexpr int kArLds = 2 * kArStage;
-
 typedef const __attribute__((address_space(1))) u32x4* ar_g16_t;
 typedef const __attribute__((address_space(1))) uint32_t* ar_g4_t;
+typedef const __attribute__((address_space(1))) uint16_t* ar_g2_t;
 
 // One step's weight operands of a wavefront.  Plain members, and the same member for the same use whatever the tile
 // type (an array indexed by the type lands in scratch memory): half-step 0 multiplies (h0a, h0b), half-step 1
@@ -506,16 +507,19 @@ struct ArWeights {
     A8 h0a, h0b, h1a, h1b;
 };
 
-template <bool SPLIT>
+template <int TILE, int BM, bool SPLIT>
 __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                            const uint8_t* __restrict__ payload, const uint32_t* __restrict__ table,
                                                            int Tk_all, int tiles_n, int tiles_m, float* __restrict__ Y, int ybf16) {
-    constexpr int TILE = 128;
+    constexpr int KPT = TILE / kStepCols;  // K-steps per tile: 2 or 1
+    constexpr int NB = BM / 32;            // 32-row blocks: 4 or 8
+    constexpr int XP = BM / 64;            // 1 KB pieces of the X tile per wavefront
+    constexpr int kArStage = BM * 128;     // 16 or 32 KB
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int w4 = w >> 2;                 // tile row of the block this wavefront's features lie in
     const int fo = 32 * w;                 // first feature of the wavefront inside the block
+    const int w4 = fo / TILE;              // tile row of the block this wavefront's features lie in
     // block -> (n, m) as in prefill_kernel_lds: one contiguous run of the grouped order per XCD
     const int nblk = tiles_n * tiles_m;
     int bid = blockIdx.x;
@@ -540,18 +544,18 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
             bm = (tiles_m / GM) * GM + rem % gm;
         }
     }
-    const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * kArBM;
-    // N is a multiple of 128, not necessarily of 256: a wavefront of a missing second tile row works on the first
+    const int64_t n0 = (int64_t)bn * kPfBN, m0 = (int64_t)bm * BM;
+    // N is a multiple of the tile, not necessarily of 256: a wavefront of a missing tile row works on the last live
     // one's weights (valid addresses) and stores nothing
-    const int live = (int)((N - n0) / TILE) < 2 ? (int)((N - n0) / TILE) : 2;
+    const int live = (int)((N - n0) / TILE) < kPfBN / TILE ? (int)((N - n0) / TILE) : kPfBN / TILE;
     const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
     const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
     const uint32_t* trow = table + ((int64_t)(n0 / TILE) + (w4 < live ? w4 : live - 1)) * Tk_all + t_begin;
 
-    // X tile copy: wavefront w copies 1 KB pieces w and w + 8 of the 16
-    const uint8_t* xsrc[2];
+    // X tile copy: wavefront w copies 1 KB pieces w, w + 8, ...
+    const uint8_t* xsrc[XP];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < XP; ++i) {
         const int c = (w + 8 * i) * 64 + lane;
         const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
         int64_t row = m0 + m;
@@ -560,18 +564,18 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
     }
     auto load_x = [&](int ks, int stage) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) g2l16(xsrc[i] + (size_t)ks * 128, lds + stage * kArStage + (w + 8 * i) * 1024);
+        for (int i = 0; i < XP; ++i) g2l16(xsrc[i] + (size_t)ks * 128, lds + stage * kArStage + (w + 8 * i) * 1024);
     };
 
     const int i32 = lane & 31, q = lane >> 5;
-    // this lane's piece of a stored fragment: strip 2 (w % 4) + i32 / 16 of the tile, fragment lane 16 q + i32 % 16
-    const int strip = 2 * (w & 3) + (i32 >> 4);
+    // this lane's piece of a stored fragment: strip (32 w % TILE) / 16 + i32 / 16 of the tile, fragment lane 16 q + i32 % 16
+    const int strip = (fo % TILE) / kStripRows + (i32 >> 4);
     const int flane = 16 * q + (i32 & 15);
     // one step's weights: tile entry e, K-step j of the tile
     auto load_w = [&](ArWeights& d, uint32_t e, int j) {
         const bool sp = entry_sparse(e);
         // the fragment of (strip, K-step j): 1 KB (2:4: halves of 512 B) or 2 KB (dense: two operands per half of 1 KB)
-        const uint8_t* f = payload + entry_offset(e) + (size_t)(strip * 2 + j) * (sp ? kSparseFragBytes : kDenseFragBytes) + flane * 16;
+        const uint8_t* f = payload + entry_offset(e) + (size_t)(strip * KPT + j) * (sp ? kSparseFragBytes : kDenseFragBytes) + flane * 16;
         d.h0a.raw = *(ar_g16_t)(f);
         d.h1a.raw = *(ar_g16_t)(f + (sp ? 512 : 1024));
         if (!sp) {
@@ -579,18 +583,24 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
             d.h1b.raw = *(ar_g16_t)(f + 1536);
         }
     };
-    // the position dwords (both K-steps) of a 2:4 tile for half-steps 0 and 1: fragment lanes flane and flane + 32
+    // the position words of a 2:4 tile for half-steps 0 and 1 (fragment lanes flane and flane + 32): mask tile 128 a
+    // dword holding both K-steps, mask tile 64 a 16-bit word
     auto load_pos = [&](uint32_t& d0, uint32_t& d1, uint32_t e) {
         if (entry_sparse(e)) {
-            const uint8_t* pb = payload + entry_offset(e) + sparse_vals_bytes(TILE) + (size_t)(strip * 64 + flane) * 4;
-            d0 = *(ar_g4_t)(pb);
-            d1 = *(ar_g4_t)(pb + 32 * 4);
+            const uint8_t* pb = payload + entry_offset(e) + sparse_vals_bytes(TILE) + (size_t)(strip * 64 + flane) * (2 * KPT);
+            if constexpr (KPT == 2) {
+                d0 = *(ar_g4_t)(pb);
+                d1 = *(ar_g4_t)(pb + 32 * 4);
+            } else {
+                d0 = *(ar_g2_t)(pb);
+                d1 = *(ar_g2_t)(pb + 32 * 2);
+            }
         }
     };
 
-    f32x16 acc[4];
+    f32x16 acc[NB];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 
@@ -603,10 +613,10 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
     };
     auto step_mma = [&](int ks, const ArWeights& wc, uint32_t p0, uint32_t p1, int sp, int j) {
         const uint8_t* bs = lds + (ks & 1) * kArStage;
-        // position p = (half-step p / 2, row blocks 2 (p % 2) and + 1); X fragments two positions ahead
+        // position p = (half-step p / (NB / 2), row blocks 2 (p % (NB / 2)) and + 1); X fragments two positions ahead
         B16 xa[3], xb[3];
         auto fetch = [&](int p, int buf) {
-            const int u = p >> 1, b0 = 2 * (p & 1);
+            const int u = p / (NB / 2), b0 = 2 * (p % (NB / 2));
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 xa[buf].raw[c] = *reinterpret_cast<const u32x4*>(bs + xs_off(32 * b0 + i32, 2 * (2 * u + c) + q));
@@ -616,44 +626,74 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
         fetch(0, 0);
         fetch(1, 1);
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            if (p + 2 < 4) fetch(p + 2, (p + 2) % 3);
-            const int u = p >> 1, b0 = 2 * (p & 1), buf = p % 3;
+        for (int p = 0; p < NB; ++p) {
+            if (p + 2 < NB) fetch(p + 2, (p + 2) % 3);
+            const int u = p / (NB / 2), b0 = 2 * (p % (NB / 2)), buf = p % 3;
             mma_step(acc[b0], acc[b0 + 1], u ? wc.h1a.v : wc.h0a.v, u ? wc.h1b.v : wc.h0b.v, xa[buf], xb[buf], (int)((u ? p1 : p0) >> (16 * j)), sp);
         }
     };
 
-    ArWeights w0, w1;            // weights of the even / odd step of a tile
-    uint32_t p0 = 0u, p1 = 0u, pn0 = 0u, pn1 = 0u;
-    uint32_t e = trow[0];
-    load_x(0, 0);
-    load_w(w0, e, 0);
-    load_pos(pn0, pn1, e);
-    __builtin_assume(Tk > 0);        // every K slice holds at least one tile (prefill_lds_split)
-    for (int tk = 0; tk < Tk; ++tk) {
-        const int more = tk + 1 < Tk ? 1 : 0;
-        const uint32_t en = trow[tk + more];
-        const int sp = (int)(e & 1u);
-        step_begin(2 * tk, 2 * tk + 1);
-        // this tile's position dwords were loaded a step ago into (pn0, pn1) and have landed.  They are taken over here by
-        // an opaque copy: a plain assignment becomes a copy on the loop's back edge, right behind the loads it then
-        // has to wait for
-        asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3" : "=&v"(p0), "=&v"(p1) : "v"(pn0), "v"(pn1));
-        load_w(w1, e, 1);
-        step_mma(2 * tk, w0, p0, p1, sp, 0);
-        // (the very last step fetches its own X again and the first step's weights of its own tile: no branch)
-        step_begin(2 * tk + 1, 2 * tk + 1 + more);
-        load_w(w0, en, 0);
-        load_pos(pn0, pn1, en);
-        step_mma(2 * tk + 1, w1, p0, p1, sp, 1);
-        e = en;
+    if constexpr (KPT == 2) {
+        ArWeights w0, w1;            // weights of the even / odd step of a tile
+        uint32_t p0 = 0u, p1 = 0u, pn0 = 0u, pn1 = 0u;
+        uint32_t e = trow[0];
+        load_x(0, 0);
+        load_w(w0, e, 0);
+        load_pos(pn0, pn1, e);
+        __builtin_assume(Tk > 0);        // every K slice holds at least one tile (prefill_lds_split)
+        for (int tk = 0; tk < Tk; ++tk) {
+            const int more = tk + 1 < Tk ? 1 : 0;
+            const uint32_t en = trow[tk + more];
+            const int sp = (int)(e & 1u);
+            step_begin(2 * tk, 2 * tk + 1);
+            // this tile's position dwords were loaded a step ago into (pn0, pn1) and have landed.  They are taken over here by
+            // an opaque copy: a plain assignment becomes a copy on the loop's back edge, right behind the loads it then
+            // has to wait for
+            asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3" : "=&v"(p0), "=&v"(p1) : "v"(pn0), "v"(pn1));
+            load_w(w1, e, 1);
+            step_mma(2 * tk, w0, p0, p1, sp, 0);
+            // (the very last step fetches its own X again and the first step's weights of its own tile: no branch)
+            step_begin(2 * tk + 1, 2 * tk + 1 + more);
+            load_w(w0, en, 0);
+            load_pos(pn0, pn1, en);
+            step_mma(2 * tk + 1, w1, p0, p1, sp, 1);
+            e = en;
+        }
+    } else {
+        // Mask tile 64: every step is a tile of its own.  Steps go in pairs (the buffers w0 / w1 alternate without a
+        // copy), table entries are read two steps ahead; past the end the last step is fetched again (no branch around
+        // the loads), and the second step of the last pair is skipped when the count is odd.
+        const int S = Tk;
+        ArWeights w0, w1;
+        uint32_t a0 = 0u, a1 = 0u, b0_ = 0u, b1_ = 0u;   // position words of w0 / w1
+        uint32_t e0 = trow[0], e1 = trow[S > 1 ? 1 : 0];
+        load_x(0, 0);
+        load_w(w0, e0, 0);
+        load_pos(a0, a1, e0);
+        __builtin_assume(S > 0);
+        for (int s_ = 0; s_ < S; s_ += 2) {
+            const int s1 = s_ + 1 < S ? s_ + 1 : S - 1, s2 = s_ + 2 < S ? s_ + 2 : S - 1, s3 = s_ + 3 < S ? s_ + 3 : S - 1;
+            const uint32_t e2 = trow[s2], e3 = trow[s3];
+            step_begin(s_, s1);
+            load_w(w1, e1, 0);
+            load_pos(b0_, b1_, e1);
+            step_mma(s_, w0, a0, a1, (int)(e0 & 1u), 0);
+            if (s_ + 1 < S) {
+                step_begin(s_ + 1, s2);
+                load_w(w0, e2, 0);
+                load_pos(a0, a1, e2);
+                step_mma(s_ + 1, w1, b0_, b1_, (int)(e1 & 1u), 0);
+            }
+            e0 = e2;
+            e1 = e3;
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32
     if (w4 < live) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < NB; ++b) {
             const int64_t m = m0 + 32 * b + i32;
             if (m >= M) continue;
 #pragma unroll
@@ -665,17 +705,19 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
     }
 }
 
+template <int TILE, int BM>
 static void launch_prefill_areg(const GemmArgs& a, int split_k, hipStream_t stream) {
-    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + kArBM - 1) / kArBM);
+    constexpr int kLds = 2 * BM * 128;    // 32 or 64 KB
+    const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN), tiles_m = (int)((a.M + BM - 1) / BM);
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    const int split = prefill_lds_split(a, split_k, kArBM);
+    const int split = prefill_lds_split(a, split_k, BM);
     if (split == 1) {
-        hipLaunchKernelGGL((prefill_kernel_areg<false>), dim3(grid), dim3(512), kArLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table, a.Tk,
-                           tiles_n, tiles_m, a.Y, a.ybf16);
+        hipLaunchKernelGGL((prefill_kernel_areg<TILE, BM, false>), dim3(grid), dim3(512), kLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
+                           a.Tk, tiles_n, tiles_m, a.Y, a.ybf16);
     } else {
-        hipLaunchKernelGGL((prefill_kernel_areg<true>), dim3(grid, split), dim3(512), kArLds, stream, a.X, a.M, a.N, a.K, a.payload, a.table,
-                           a.Tk, tiles_n, tiles_m, a.ws, 0);
+        hipLaunchKernelGGL((prefill_kernel_areg<TILE, BM, true>), dim3(grid, split), dim3(512), kLds, stream, a.X, a.M, a.N, a.K, a.payload,
+                           a.table, a.Tk, tiles_n, tiles_m, a.ws, 0);
         wr_reduce(a.ws, (size_t)a.M * (size_t)a.N / 4, split, a.Y, a.ybf16, stream);
     }
 }
@@ -705,9 +747,9 @@ int prefill_lds_split(const GemmArgs& a, int requested, int bm) {
 // estimated from measured rates:
 //     us = rounds x K-steps per workgroup x t_step + 3 + (split > 1 ? 3 + (2 split + 1) M N 4 B / 5.5 TB/s : 0)
 // A step is slower the fuller the chip (shared L2 bandwidth, power): t_step = t0 + t1 x min(1, workgroups / compute
-// units), with (t0, t1) = (0.93, 0.25) us for the weights-in-registers kernel of 256 rows, (1.30, 0.15) LDS-staged with
-// 256 rows, (0.67, 0.18) prefill_kernel_areg (128 rows, mask tile 128), (0.80, 0.13) LDS-staged with 128 rows (mask
-// tile 64; more than half of a 256-row step, see the note at its step loop).  The 256-row side takes the
+// units), with (t0, t1) = (0.90, 0.35) us for the weights-in-registers kernel of 256 rows, (1.31, 0.37) LDS-staged with
+// 256 rows, and for prefill_kernel_areg with 128 rows (0.70, 0.24) on mask tile 128, (0.75, 0.22) on mask tile 64 (fitted
+// to unsplit launches of 16 and of 256 workgroups at f = 0.6).  The 256-row side takes the
 // split its launcher would take; the 128-row side its best split of at most 8 slices of at least 512 columns that the
 // workspace holds.  Returns true, and the split, when 128 rows are estimated at least 3 % faster.
 static double pf_estimate(const GemmArgs& a, int blocks, int split, double t0, double t1) {
@@ -723,25 +765,25 @@ bool prefill_prefers_128_rows(const GemmArgs& a, int* split) {
     const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN);
     const int b256 = tiles_n * (int)((a.M + 255) / 256), b128 = tiles_n * (int)((a.M + 127) / 128);
     const bool wreg = a.tile == 128 && prefill_wreg_supports(a);
-    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 0.93 : 1.30,
-                                     wreg ? 0.25 : 0.15);
+    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 0.90 : 1.31,
+                                     wreg ? 0.35 : 0.37);
     const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
     const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
     const int longest = a.Tk * a.tile / 512;
     double best = 0.0;
     *split = 1;
     for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
-        const double us = pf_estimate(a, b128, sp, a.tile == 128 ? 0.67 : 0.80, a.tile == 128 ? 0.18 : 0.13);
+        const double us = pf_estimate(a, b128, sp, a.tile == 128 ? 0.70 : 0.75, a.tile == 128 ? 0.24 : 0.22);
         if (sp == 1 || us < best) { best = us; *split = sp; }
     }
     return best < 0.97 * us256;
 }
 
-// Kernel choice.  variant 0 (default): blocks of 128 rows where prefill_prefers_128_rows says so (no split requested) -
-// prefill_kernel_areg for mask tile 128, prefill_kernel_lds<64, ., 128> for mask tile 64; else tile 128 ->
-// prefill_kernel_wreg where its limits hold, else prefill_kernel_lds with blocks of 256 rows.  variant 1 forces
-// prefill_kernel_v0, 2 prefill_kernel_lds (256 rows), 3 prefill_kernel_wreg, 4 prefill_kernel_lds with 128 rows, 5
-// prefill_kernel_areg (mask tile 64: as 4); each falls back to the default choice where it does not apply.
+// Kernel choice.  variant 0 (default): prefill_kernel_areg with blocks of 128 rows where prefill_prefers_128_rows says so
+// (no split requested); else tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds with blocks
+// of 256 rows.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds (256 rows), 3 prefill_kernel_wreg, 4
+// prefill_kernel_lds with 128 rows, 5 prefill_kernel_areg with 128 rows, 6 prefill_kernel_areg with 256 rows (mask tile
+// 64 only); each falls back to the default choice where it does not apply.
 template <int TILE, int BM>
 static void launch_prefill_lds(const GemmArgs& a, int split_k, hipStream_t stream) {
     constexpr int kLds = pf_lds_bytes(BM);
@@ -769,14 +811,19 @@ void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t str
     if (variant == 0 && split_k == 0) {
         int split128 = 1;
         if (prefill_prefers_128_rows(a, &split128)) {
-            if (a.tile == 128) launch_prefill_areg(a, split128, stream);
-            else launch_prefill_lds<64, 128>(a, split128, stream);
+            if (a.tile == 128) launch_prefill_areg<128, 128>(a, split128, stream);
+            else launch_prefill_areg<64, 128>(a, split128, stream);
             return;
         }
     }
     if (a.tile == 128 && (variant == 0 || variant == 3) && prefill_wreg_supports(a)) { launch_prefill_wreg(a, split_k, stream); return; }
-    if (variant == 5 && a.tile == 128) { launch_prefill_areg(a, split_k, stream); return; }   // 128 rows, weights in registers
-    if (variant == 4 || variant == 5) {   // the LDS-staged kernel with blocks of 128 rows
+    if (variant == 5) {   // 128 rows, weights in registers
+        if (a.tile == 128) launch_prefill_areg<128, 128>(a, split_k, stream);
+        else launch_prefill_areg<64, 128>(a, split_k, stream);
+        return;
+    }
+    if (variant == 6 && a.tile == 64) { launch_prefill_areg<64, 256>(a, split_k, stream); return; }   // 256 rows, weights in registers
+    if (variant == 4) {   // the LDS-staged kernel with blocks of 128 rows
         if (a.tile == 128) launch_prefill_lds<128, 128>(a, split_k, stream);
         else launch_prefill_lds<64, 128>(a, split_k, stream);
         return;

@@ -465,12 +465,16 @@ def test_prefill_blocks_of_128_rows(dev, t, N, K, M, f):
     _blocks_of_128_rows(dev, t, N, K, M, f, 4)
 
 
-@pytest.mark.parametrize("N,K,M,f", [(2176, 1152, 700, 0.6), (384, 2048, 100, 1.0), (1024, 1024, 512, 0.0), (640, 128, 129, 0.5),
-                                     (4224, 512, 300, 0.3)])
-def test_prefill_128_rows_weights_in_registers(dev, N, K, M, f):
-    """Blocks of 128 rows with the weight fragments loaded straight into registers (mask tile 128): the same cases and
-    checks as the LDS-staged kernel, plus a weight of 33 tile rows."""
-    _blocks_of_128_rows(dev, 128, N, K, M, f, 5)
+@pytest.mark.parametrize("variant,t,N,K,M,f", [
+    (5, 128, 2176, 1152, 700, 0.6), (5, 128, 384, 2048, 100, 1.0), (5, 128, 1024, 1024, 512, 0.0), (5, 128, 640, 128, 129, 0.5),
+    (5, 128, 4224, 512, 300, 0.3),
+    (5, 64, 2112, 1088, 700, 0.6), (5, 64, 320, 2048, 257, 1.0), (5, 64, 576, 64, 130, 0.5), (5, 64, 1024, 1024, 512, 0.0), (5, 64, 192, 448, 100, 0.5),
+    (6, 64, 2112, 1088, 700, 0.6), (6, 64, 320, 2048, 257, 1.0), (6, 64, 576, 64, 130, 0.5), (6, 64, 1024, 1024, 512, 0.0), (6, 64, 192, 448, 100, 0.5)])
+def test_prefill_weights_in_registers(dev, variant, t, N, K, M, f):
+    """prefill_kernel_areg - weight fragments loaded straight into registers, X through LDS: blocks of 128 rows (variant 5)
+    on both mask tiles and of 256 rows (variant 6) on mask tile 64; the cases and checks of the LDS-staged kernel, a
+    weight of 33 tile rows, odd and even tile counts along K (mask tile 64 takes its steps in pairs)."""
+    _blocks_of_128_rows(dev, t, N, K, M, f, variant)
 
 
 def _blocks_of_128_rows(dev, t, N, K, M, f, variant):
@@ -685,7 +689,7 @@ def test_prefill_long_k(dev):
     p.P.close()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 def test_prefill_kernel_variants(dev, variant):
     """Every prefill kernel variant (patch_gemm_opts.variant) against the oracle: odd tile-row count (N % 256 = 128),
     ragged M, K of several tiles, all-dense / mixed / all-2:4 maps."""
