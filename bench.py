@@ -349,7 +349,8 @@ def main():
             del W_hat, Xm, Ym, ws
         out["mid_m"] = dict(rows=rows, note="patch_gemm, automatic path; with a workspace the launch splits K over otherwise idle "
                                             "compute units (partials summed in slice order): M <= 64 one decode-path pass with 64 "
-                                            "features per wavefront, beyond that the prefill kernel")
+                                            "features per wavefront (from 33 rows on weights of at least 10240 features the prefill "
+                                            "kernel with 128-row blocks), beyond that the prefill kernels")
 
     # ------------------------------------------------------------------ decode: 7B attention projection
     if "decode" not in skip:

@@ -44,7 +44,8 @@ typedef enum {
 /* Which kernel family patch_gemm_ex uses.  DECODE handles M in passes of up to 64 rows (the weight is streamed
  * once per pass: 16-feature strips per workgroup for few rows, 64 features per wavefront for more rows where that
  * fills the chip), PREFILL in blocks of 256 rows (128 where an estimate of both says so: few rows, or a weight of
- * few feature blocks that would otherwise need a deep K split).  AUTO (measured crossovers): decode up to M = 64 always; beyond, with a
+ * few feature blocks that would otherwise need a deep K split).  AUTO (measured crossovers): decode up to M = 64 (with a
+ * workspace, a single weight of at least 10240 features goes to prefill from M = 33); beyond, with a
  * workspace for at least two slices (see patch_gemm_opts) prefill, whose K split then fills the chip; without one
  * the cheaper of repeated passes and one unsplit prefill launch by an estimate from the launch geometry (passes up to
  * M = 192 at 4096 x 4096, up to M = 128 from 5120 features, further for long-K weights of few features). */

@@ -317,9 +317,14 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
 //                           blocks of 128 rows x 0.70 us (tile 64: 0.75), whichever is less (launch_prefill makes the
 //                           same choice)
 //   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256))
-static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts) {
+static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts, bool single = true) {
     const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
     if (M <= 16) return PATCH_PATH_DECODE;
+    // With a workspace, 33 .. 64 rows and a single weight of at least 160 feature groups (10240 features: the pass then
+    // runs unsplit on the 64-features-per-wavefront kernel): the split prefill launch with 128-row blocks is ahead, e.g.
+    // M = 33 / 64: 11008 x 4096 20.7 / 23.0 us against 21.2 / 26.6, 32000 x 4096 36.8 / 39.8 against 43.5 / 54.1 (8192 x
+    // 4096 breaks even at 64 rows; 4096 features and fewer stay on the pass).
+    if (ws && single && M > 32 && M <= kDecodeRows && P->N / 64 >= 160) return PATCH_PATH_PREFILL;
     if (ws) return M <= kDecodeRows ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
     if (M <= kDecodeRows) return PATCH_PATH_DECODE;
     const double steps = (double)P->K / 64.0;
@@ -600,7 +605,7 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     if (opts) { path = opts->path; split_k = opts->split_k; variant = opts->variant; }
     if (path < PATCH_PATH_AUTO || path > PATCH_PATH_PREFILL || split_k < 0 || split_k > 16 || variant < 0) return PATCH_ERR_ARG;
     if (M == 0) return PATCH_OK;
-    if (path == PATCH_PATH_AUTO) path = auto_path(M, P[0], opts);
+    if (path == PATCH_PATH_AUTO) path = auto_path(M, P[0], opts, count == 1);
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs a = {};
     a.X = static_cast<const uint16_t*>(X);
