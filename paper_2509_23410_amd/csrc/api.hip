@@ -316,7 +316,9 @@ static bool use_mid_kernel(int rows, int variant, int split_k, int mid_chunks, i
 //   unsplit prefill launch  rounds x 64-column steps x 1.0 us (tile 64 on the LDS-staged kernel: 1.45 us), or with
 //                           blocks of 128 rows x 0.70 us (tile 64: 0.75), whichever is less (launch_prefill makes the
 //                           same choice)
-//   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256))
+//   pass of up to 64 rows   steps x 0.3 us x (1 + 0.4 min(1, feature groups / 256)) x max(1, feature groups / 256)
+// From 33 rows on the same estimate also decides a single pass against an unsplit prefill launch: only weights wider
+// than the chip change side (65536 x 4096 at M = 64: 109 us in a pass, 90 us on the 128-row prefill kernel).
 static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* opts, bool single = true) {
     const bool ws = opts && opts->workspace && opts->workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
     if (M <= 16) return PATCH_PATH_DECODE;
@@ -326,7 +328,7 @@ static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* op
     // 4096 breaks even at 64 rows; 4096 features and fewer stay on the pass).
     if (ws && single && M > 32 && M <= kDecodeRows && P->N / 64 >= 160) return PATCH_PATH_PREFILL;
     if (ws) return M <= kDecodeRows ? PATCH_PATH_DECODE : PATCH_PATH_PREFILL;
-    if (M <= kDecodeRows) return PATCH_PATH_DECODE;
+    if (M <= 32 || (M <= kDecodeRows && !single)) return PATCH_PATH_DECODE;
     const double steps = (double)P->K / 64.0;
     const int64_t tiles = ((P->N + 255) / 256) * ((M + 255) / 256);
     const double rounds = (double)((tiles + P->n_cus - 1) / P->n_cus);
@@ -335,7 +337,8 @@ static int auto_path(int64_t M, const patch_packed* P, const patch_gemm_opts* op
     const double us256 = rounds * steps * (P->tile == 128 ? 1.0 : 1.45);
     const double prefill_us = us128 < us256 ? us128 : us256;
     const double groups = (double)(P->N / 64);
-    const double pass_us = steps * 0.3 * (1.0 + 0.4 * (groups < 256.0 ? groups / 256.0 : 1.0));
+    // (a weight of more feature groups than the chip takes at once - 65536 features - costs that many times more)
+    const double pass_us = steps * 0.3 * (1.0 + 0.4 * (groups < 256.0 ? groups / 256.0 : 1.0)) * (groups > 256.0 ? groups / 256.0 : 1.0);
     // a last pass of r < 64 rows costs about (1 + r / 64) / 2 of a full one (11008 x 4096: 12.8 us for 1 row, 26.7 for 64)
     const int64_t full = M / kDecodeRows, rest = M % kDecodeRows;
     const double passes = (double)full + (rest ? 0.5 + 0.5 * (double)rest / kDecodeRows : 0.0);
