@@ -322,7 +322,7 @@ def main():
             rows64.append(dict(shape=[N_, K_], M=M, tile=64, us_f0=round(us_f[0.0], 1), us_f06=round(us_f[0.6], 1), us_f1=round(us_f[1.0], 1),
                                dense_equiv_TFLOPs_f06=round(2.0 * M * N_ * K_ / us_f[0.6] / 1e6, 1),
                                speedup_f06_over_all_dense=round(us_f[0.0] / us_f[0.6], 3), speedup_f1_over_all_dense=round(us_f[0.0] / us_f[1.0], 3)))
-        out["prefill_tile64"] = dict(rows=rows64, note="mask tile 64 x 64 on prefill_kernel_lds<64> (256 x 256 workgroup tiles, LDS-staged); "
+        out["prefill_tile64"] = dict(rows=rows64, note="mask tile 64 x 64 on prefill_kernel_areg<64, 256> (256 x 256 workgroup tiles, weights straight into registers); "
                                      "the headline uses mask tile 128 on prefill_kernel_wreg")
 
     # ------------------------------------------------------------------ mid M: 13B layer shapes at M = 512, 7B MLP at M = 2048

@@ -64,10 +64,11 @@ typedef struct {
                  /* tile 128 only),                                                                   */
                  /* 1 = no split.  Never more slices than the workspace holds: without one, no split. */
     int variant; /* kernel variant within the path, 0 = default.  Prefill: 1 = simple 128 x 128 kernel, */
-                 /* 2 = 256 x 256 LDS-staged kernel (the default for tile 64), 3 = 256 x 256 weights-in- */
+                 /* 2 = 256 x 256 LDS-staged kernel (tile 128 beyond the limits of 3), 3 = 256 x 256 weights-in- */
                  /* registers kernel (the default for tile 128 where K <= 32768 and M K 2 < 4 GB), 4 = the  */
                  /* LDS-staged kernel with blocks of 256 features x 128 rows, 5 = blocks of 128 rows with  */
-                 /* the weights loaded straight into registers, 6 = the same with 256 rows (tile 64 only). */
+                 /* the weights loaded straight into registers, 6 = the same with 256 rows (tile 64 only:  */
+                 /* its 256-row default).                                                                  */
                  /* Blocks of 128 rows (5) are the default, with no split requested, where estimated       */
                  /* faster (up to a few hundred rows).  Decode: 2 / 3 = 8 / 4                              */
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
@@ -170,9 +171,9 @@ patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, 
  *   prefill path, tile 128: the execution tiles 256 x 256 with one wavefront per SIMD (default), 256 x 256 with two
  *     (variant 2) and the small 128 x 128 tile (variant 1; Appendix O reports that small execution tiles under-use
  *     the matrix units - it is timed so that the report shows it), and the K-split counts the workspace allows;
- *   prefill path, tile 64: the 256 x 256 LDS-staged kernel (default) and the small 128 x 128 tile, K-split counts;
- *   prefill path, M <= 4096: blocks of 256 features x 128 rows (variants 4 and 5), unsplit and split; tile 64 also
- *     256 rows with the weights in registers (variant 6).
+ *   prefill path, tile 64: 256 x 256 with the weights in registers (default), LDS-staged (variant 2), the small
+ *     128 x 128 tile, K-split counts;
+ *   prefill path, M <= 4096: blocks of 256 features x 128 rows (variants 4 and 5), unsplit and split.
  *   X, Y       as for patch_gemm (Y is overwritten several times; after patch_tune it holds the product)
  *   workspace  DEVICE scratch for split launches or NULL (then only unsplit candidates), caller-owned
  *   reps       timed launches per candidate after two warm-up launches (HIP events on `stream`); >= 1

@@ -418,8 +418,8 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
             for (int sk : {2, 3, 4, 6, 8, 12, 16})
                 if ((size_t)sk * per_slice <= workspace_bytes && sk * 2 <= P->Tk) add(PATCH_PATH_PREFILL, sk, 0, true);
     } else {
-        add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256, two wavefronts per SIMD (the tile-64 default)
-        add(PATCH_PATH_PREFILL, 1, 6, false);   // 256 x 256 with the weights in registers
+        add(PATCH_PATH_PREFILL, 1, 0, false);   // 256 x 256 with the weights in registers (the tile-64 default)
+        add(PATCH_PATH_PREFILL, 1, 2, false);   // 256 x 256 LDS-staged
         add(PATCH_PATH_PREFILL, 1, 1, false);   // 128 x 128: the small execution tile
         if (workspace) add(PATCH_PATH_PREFILL, 0, 0, true);   // automatic
         if (workspace)
@@ -583,7 +583,7 @@ size_t patch_gemm_workspace_bytes(int64_t M, const patch_packed* P, const patch_
         int split128 = 1;
         if (prefill_prefers_128_rows(a, &split128)) return split128 > 1 ? (size_t)split128 * (size_t)M * (size_t)P->N * sizeof(float) : 0;
     }
-    if (variant == 2 || variant == 4 || variant == 5 || (variant == 6 && a.tile == 64) || !prefill_wreg_supports(a)) {   // whole-launch K split only
+    if (variant == 2 || variant == 4 || variant == 5 || (variant == 6 && a.tile == 64) || !prefill_wreg_supports(a)) {   // whole-launch K split only (same for both 256-row kernels)
         const int sl = prefill_lds_split(a, split_k, variant == 4 || variant == 5 ? 128 : 256);
         return sl > 1 ? (size_t)sl * (size_t)M * (size_t)P->N * sizeof(float) : 0;
     }

@@ -482,7 +482,7 @@ __global__ __launch_bounds__(512) void prefill_kernel_lds(const uint16_t* __rest
 
 // ------------------------------------------------------------------------------------------------------
 // Blocks of 256 features x BM rows with the weights straight into registers ("areg"): BM = 128 on both mask tiles (the
-// 128-row kernel of the default choice), BM = 256 on mask tile 64 (variant 6).
+// 128-row kernel of the default choice), BM = 256 on mask tile 64 (its 256-row kernel; variant 6).
 //
 // The LDS-staged kernel is bound by what a compute unit can fetch per K-step, and the global -> LDS path is the
 // slower way in (patch_probe_lds_fill).  Here only X goes that way (BM x 128 bytes per step, two LDS stages); a
@@ -747,8 +747,8 @@ int prefill_lds_split(const GemmArgs& a, int requested, int bm) {
 // estimated from measured rates:
 //     us = rounds x K-steps per workgroup x t_step + 3 + (split > 1 ? 3 + (2 split + 1) M N 4 B / 5.5 TB/s : 0)
 // A step is slower the fuller the chip (shared L2 bandwidth, power): t_step = t0 + t1 x min(1, workgroups / compute
-// units), with (t0, t1) = (0.90, 0.35) us for the weights-in-registers kernel of 256 rows, (1.31, 0.37) LDS-staged with
-// 256 rows, and for prefill_kernel_areg with 128 rows (0.70, 0.24) on mask tile 128, (0.75, 0.22) on mask tile 64 (fitted
+// units), with (t0, t1) = (0.90, 0.35) us for prefill_kernel_wreg, (1.26, 0.33) for the 256-row kernels of mask tile 64
+// and of long K, and for prefill_kernel_areg with 128 rows (0.70, 0.24) on mask tile 128, (0.75, 0.22) on mask tile 64 (fitted
 // to unsplit launches of 16 and of 256 workgroups at f = 0.6).  The 256-row side takes the
 // split its launcher would take; the 128-row side its best split of at most 8 slices of at least 512 columns that the
 // workspace holds.  Returns true, and the split, when 128 rows are estimated at least 3 % faster.
@@ -765,8 +765,8 @@ bool prefill_prefers_128_rows(const GemmArgs& a, int* split) {
     const int tiles_n = (int)((a.N + kPfBN - 1) / kPfBN);
     const int b256 = tiles_n * (int)((a.M + 255) / 256), b128 = tiles_n * (int)((a.M + 127) / 128);
     const bool wreg = a.tile == 128 && prefill_wreg_supports(a);
-    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 0.90 : 1.31,
-                                     wreg ? 0.35 : 0.37);
+    const double us256 = pf_estimate(a, b256, wreg ? prefill_wreg_split(a, 0) : prefill_lds_split(a, 0, 256), wreg ? 0.90 : 1.26,
+                                     wreg ? 0.35 : 0.33);
     const size_t per_slice = (size_t)a.M * (size_t)a.N * sizeof(float);
     const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
     const int longest = a.Tk * a.tile / 512;
@@ -780,10 +780,10 @@ bool prefill_prefers_128_rows(const GemmArgs& a, int* split) {
 }
 
 // Kernel choice.  variant 0 (default): prefill_kernel_areg with blocks of 128 rows where prefill_prefers_128_rows says so
-// (no split requested); else tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds with blocks
-// of 256 rows.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds (256 rows), 3 prefill_kernel_wreg, 4
-// prefill_kernel_lds with 128 rows, 5 prefill_kernel_areg with 128 rows, 6 prefill_kernel_areg with 256 rows (mask tile
-// 64 only); each falls back to the default choice where it does not apply.
+// (no split requested); else 256 rows: tile 128 -> prefill_kernel_wreg where its limits hold, else prefill_kernel_lds;
+// tile 64 -> prefill_kernel_areg.  variant 1 forces prefill_kernel_v0, 2 prefill_kernel_lds (256 rows), 3
+// prefill_kernel_wreg, 4 prefill_kernel_lds with 128 rows, 5 prefill_kernel_areg with 128 rows, 6 prefill_kernel_areg
+// with 256 rows (mask tile 64 only); each falls back to the default choice where it does not apply.
 template <int TILE, int BM>
 static void launch_prefill_lds(const GemmArgs& a, int split_k, hipStream_t stream) {
     constexpr int kLds = pf_lds_bytes(BM);
@@ -822,7 +822,7 @@ void launch_prefill(const GemmArgs& a, int variant, int split_k, hipStream_t str
         else launch_prefill_areg<64, 128>(a, split_k, stream);
         return;
     }
-    if (variant == 6 && a.tile == 64) { launch_prefill_areg<64, 256>(a, split_k, stream); return; }   // 256 rows, weights in registers
+    if ((variant == 0 || variant == 6) && a.tile == 64) { launch_prefill_areg<64, 256>(a, split_k, stream); return; }   // 256 rows
     if (variant == 4) {   // the LDS-staged kernel with blocks of 128 rows
         if (a.tile == 128) launch_prefill_lds<128, 128>(a, split_k, stream);
         else launch_prefill_lds<64, 128>(a, split_k, stream);
