@@ -559,6 +559,32 @@ def main():
                                          "single launches; rotating over copies of the layer (> 1 GB)")
         out["decode_q4"] = dict(rows=qrows, note="patch_gemm4: 4-bit codes + bf16 scale per row of a tile (+ 2:4 positions), dequantized in "
                                 "registers; rotating packed copies (HBM-resident); us_bf16_storage = patch_gemm on the same pruned weight")
+        # the prefill-shaped product from the same 4-bit storage (patch_gemm4_ex), beside 64-row passes and the bf16 storage
+        prow = []
+        for name, N_, K_ in (("attn", 4096, 4096), ("gate", 11008, 4096)):
+            cq = synth.make_case("llama7b_q4p_" + name, N_, K_, 2048, t, 0.5, seed=0)
+            W_hat, Pb = masked_packed(cq)
+            P4 = B.patch_pack4(W_hat, N_, K_, cq.tile_map, t, stream)
+            Xq = dev_bf16(cq.X)
+            Yq = torch.empty((2048, N_), device=dev, dtype=torch.float32)
+            wsq = torch.empty(8 * 512 * N_, device=dev, dtype=torch.float32)
+            for Mq in (128, 512, 2048):
+                fns = (("us_passes_of_64_rows", lambda i: B.patch_gemm4_many(Xq, Mq, [P4], [Yq], stream)),
+                       ("us", lambda i: B.patch_gemm4(Xq, Mq, P4, Yq, stream)),
+                       ("us_with_workspace", lambda i: B.patch_gemm4(Xq, Mq, P4, Yq, stream, workspace=wsq)),
+                       ("us_bf16_storage_with_workspace", lambda i: B.patch_gemm(Xq, Mq, Pb, Yq, stream, workspace=wsq)))
+                row = dict(shape=[N_, K_], M=Mq, f=0.5, packed_MB=round(P4.nbytes / 1e6, 2), bf16_packed_MB=round(Pb.nbytes / 1e6, 2))
+                for key, fn in fns:
+                    n_ = 20 if Mq <= 512 else 5
+                    timed(fn, n_)
+                    row[key] = round(min(timed(fn, n_) / n_ for _ in range(3)) * 1e6, 1)
+                row["dense_equiv_TFLOPs_with_workspace"] = round(2.0 * Mq * N_ * K_ / (row["us_with_workspace"] * 1e-6) / 1e12, 1)
+                prow.append(row)
+            P4.close(); Pb.close()
+            del W_hat, Xq, Yq, wsq
+        out["prefill_q4"] = dict(rows=prow, note="patch_gemm4_ex on mask tile 128: the weight stays in 4 bits (read once per 128 rows of X, "
+                                 "dequantized in registers); passes = the decode-shaped kernel repeated per 64 rows; bf16 storage = "
+                                 "patch_gemm on the bf16 packing of the same pruned weight (4 x the bytes)")
 
     # ------------------------------------------------------------------ measured ceilings (kernels of this library)
     if "ceilings" not in skip:

@@ -290,6 +290,14 @@ patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_
  *   patch_gemm4    Y[m, n] = sum_k X[m, k] * bf16(q s)[n, k]: X DEVICE M x K bf16, Y DEVICE M x N fp32, both 16-byte
  *                  aligned; asynchronous, allocates nothing, bit-reproducible.  Decode-shaped: the weight is streamed
  *                  once per 64 rows of X; for prefill shapes dequantize once (patch_unpack4) and patch_pack the result
+ *   patch_gemm4_ex  the same product with an optional caller workspace (DEVICE, 16-byte aligned, or NULL; used when it
+ *                  holds at least two slices of M x N fp32).  Mask tile 128 has a prefill-shaped kernel that reads the
+ *                  4-bit weight once per 128 rows of X and dequantizes in registers (no bf16 copy of the weight); with a
+ *                  workspace it splits K over workgroups (partial sums in the workspace, summed in slice order).  It is
+ *                  taken where an estimate of both sides puts it ahead of passes of up to 64 rows (with a workspace
+ *                  from about 65 rows, from 48 on wide weights; without one from a few hundred rows, from 129 on wide
+ *                  weights); otherwise, and for mask tile 64, passes as patch_gemm4 (= patch_gemm4_ex without a
+ *                  workspace).  Launches that may run concurrently need distinct workspaces
  *   patch_gemm4_many  up to PATCH_MAX_MANY weights with the same K and tile against one X in one launch per 64 rows
  *                  (q / k / v, gate / up): Y[i] is M x N_i fp32; bit-reproducible, and equal to the single calls up to
  *                  the order of the fp32 partial sums (the split of K over wavefronts depends on the number of
@@ -307,6 +315,8 @@ typedef struct patch_packed4 patch_packed4;
 patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
                          patch_packed4** out);
 patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream);
+patch_status patch_gemm4_ex(const void* X, int64_t M, const patch_packed4* P, void* Y, void* workspace, size_t workspace_bytes,
+                            void* stream);
 patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* const* P, void* const* Y, int count, void* stream);
 patch_status patch_unpack4(const patch_packed4* P, void* W_deq, void* codes, void* scales, void* stream);
 patch_status patch_pack_from4(const patch_packed4* P4, void* stream, patch_packed** out);

@@ -23,7 +23,7 @@ EXPORTS = [
     "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
     "patch_pack4", "patch_pack_from4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
-    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
+    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_gemm4_ex", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
 
@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.patch_pack4.restype = ci
         L.patch_gemm4.argtypes = [vp, i64, vp, vp, vp]
         L.patch_gemm4.restype = ci
+        L.patch_gemm4_ex.argtypes = [vp, i64, vp, vp, vp, sz, vp]
+        L.patch_gemm4_ex.restype = ci
         L.patch_pack_from4.argtypes = [vp, vp, ctypes.POINTER(vp)]
         L.patch_pack_from4.restype = ci
         L.patch_gemm4_many.argtypes = [vp, i64, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp]
@@ -400,8 +402,13 @@ def patch_pack_from4(P4: Packed4, stream: int = 0) -> Packed:
     return Packed(out.value)
 
 
-def patch_gemm4(X, M: int, P: Packed4, Y, stream: int = 0) -> None:
-    _check(lib().patch_gemm4(_ptr(X), M, P.handle, _ptr(Y), stream), "patch_gemm4")
+def patch_gemm4(X, M: int, P: Packed4, Y, stream: int = 0, workspace=None) -> None:
+    """Y = X . bf16(q s)^T from the 4-bit storage; with a workspace tensor: patch_gemm4_ex (K split for prefill shapes)."""
+    if workspace is None:
+        _check(lib().patch_gemm4(_ptr(X), M, P.handle, _ptr(Y), stream), "patch_gemm4")
+    else:
+        _check(lib().patch_gemm4_ex(_ptr(X), M, P.handle, _ptr(Y), _ptr(workspace), workspace.numel() * workspace.element_size(), stream),
+               "patch_gemm4_ex")
 
 
 def patch_gemm4_many(X, M: int, Ps, Ys, stream: int = 0) -> None:

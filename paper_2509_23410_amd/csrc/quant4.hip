@@ -19,8 +19,9 @@
 // The product kernel dequantizes in registers (8 codes -> 8 bf16 with integer rounding) and then runs the same matrix
 // instructions as the bf16 decode kernel: a workgroup owns one to three strips of 16 features, its wavefronts split K,
 // partial sums meet in LDS in wavefront order (bit-reproducible); several weights sharing X run as one launch
-// (patch_gemm4_many).  It is the decode-shaped path only - up to 64 rows of X (one, two or four blocks of 16) per pass
-// over the weight; for prefill shapes dequantize once and pack the result as bf16 (patch_pack_from4).
+// (patch_gemm4_many).  That kernel takes up to 64 rows of X (one, two or four blocks of 16) per pass over the weight;
+// for more rows mask tile 128 has a prefill-shaped kernel that keeps the weight in 4 bits (prefill4_kernel below,
+// patch_gemm4_ex), and any weight can be dequantized once and packed as bf16 (patch_pack_from4).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -31,6 +32,7 @@
 #include "epilogue.h"
 #include "kernels.h"
 #include "layout.h"
+#include "prefill_parts.h"
 
 namespace patch {
 
@@ -519,6 +521,201 @@ static int q4_strips_per_group(int strips, int n_cus, int rows) {
     return best;
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Prefill-shaped product from the 4-bit storage (mask tile 128): the structure of prefill_kernel_areg - blocks of 256
+// features x 128 rows, a wavefront owns 32 features x all 128 rows, X through two LDS stages - with the weight operands
+// dequantized in registers.  A lane loads the codes of its pieces of the stored fragments one step ahead (dense: two
+// 8-byte loads, fragment lanes fl and fl + 32, each holding the codes of both half-steps; 2:4: two 4-byte loads), the
+// scale of its row once per tile and the position dwords once per tile; at the top of a step the codes of that step
+// become bf16 operands (q4_dequant8) and the step runs as in the bf16 kernel.  The weight is read once per 128 rows of
+// X, at 4 bits per kept weight, and no bf16 copy of it exists anywhere.
+// ------------------------------------------------------------------------------------------------------
+constexpr int kP4BN = 256, kP4BM = 128;
+constexpr int kP4Stage = kP4BM * 128;      // 16 KB
+constexpr int kP4Lds = 2 * kP4Stage;
+
+typedef const __attribute__((address_space(1))) uint32_t* p4_g4_t;
+typedef const __attribute__((address_space(1))) uint16_t* p4_g2_t;
+typedef const __attribute__((address_space(1))) q4_u32x2* p4_g8_t;
+
+// One step's codes of a wavefront.  Named by use (an array indexed by the tile type would live in scratch memory):
+// half-step u multiplies the operands dequantized from (a_u, b_u); a 2:4 tile uses a_0 and a_1 only.
+struct P4Codes {
+    uint32_t a0, a1, b0, b1;
+};
+
+template <bool SPLIT>
+__global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
+                                                       const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
+                                                       const uint32_t* __restrict__ table, int Tk_all, int tiles_n, int tiles_m,
+                                                       float* __restrict__ Y) {
+    constexpr int TILE = 128;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fo = 32 * w;                 // first feature of the wavefront inside the block
+    const int w4 = fo / TILE;              // tile row of the block its features lie in
+    // block -> (n, m): one contiguous run of the grouped order (4 row blocks x all feature blocks) per XCD
+    const int nblk = tiles_n * tiles_m;
+    int bid = blockIdx.x;
+    {
+        const int per = (nblk + 7) / 8;
+        const int x = bid & 7, i = bid >> 3;
+        const int t = x * per + i;
+        bid = (i < per && t < nblk) ? t : -1;
+    }
+    if (bid < 0) return;
+    int bn, bm;
+    {
+        constexpr int GM = 4;
+        const int full = (tiles_m / GM) * GM * tiles_n;
+        if (bid < full) {
+            const int g = bid / (GM * tiles_n), rem = bid % (GM * tiles_n);
+            bn = rem / GM;
+            bm = g * GM + rem % GM;
+        } else {
+            const int gm = tiles_m % GM, rem = bid - full;
+            bn = rem / gm;
+            bm = (tiles_m / GM) * GM + rem % gm;
+        }
+    }
+    const int64_t n0 = (int64_t)bn * kP4BN, m0 = (int64_t)bm * kP4BM;
+    // N is a multiple of 128, not necessarily of 256: a wavefront of a missing second tile row works on the first one's
+    // weights (valid addresses) and stores nothing
+    const int live = (int)((N - n0) / TILE) < 2 ? (int)((N - n0) / TILE) : 2;
+    const int trw = w4 < live ? w4 : live - 1;
+    const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
+    const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
+    const uint32_t* trow = table + ((int64_t)(n0 / TILE) + trw) * Tk_all + t_begin;
+
+    const uint8_t* xsrc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = (w + 8 * i) * 64 + lane;
+        const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
+        int64_t row = m0 + m;
+        if (row >= M) row = M - 1;
+        xsrc[i] = reinterpret_cast<const uint8_t*>(X + row * K + pl * 8 + (int64_t)t_begin * TILE);
+    }
+    auto load_x = [&](int ks, int stage) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) g2l16(xsrc[i] + (size_t)ks * 128, lds + stage * kP4Stage + (w + 8 * i) * 1024);
+    };
+
+    const int i32 = lane & 31, q = lane >> 5;
+    // this lane's pieces: strip (32 w % 128) / 16 + i32 / 16 of the tile, fragment lanes fl and fl + 32
+    const int strip = (fo % TILE) / 16 + (i32 >> 4);
+    const int fl = 16 * q + (i32 & 15);
+    // scale of the lane's row for the first tile of this K slice; the next tile's is 16 scales on
+    const uint16_t* sc = scales + q4_scale_index(((n0 + (int64_t)trw * TILE) / 16) + strip, Tk_all, t_begin, i32 & 15);
+    auto load_codes = [&](P4Codes& d, uint32_t e, int j) {
+        const uint8_t* tb = payload + entry_offset(e);
+        if (entry_sparse(e)) {
+            const uint8_t* f = tb + (size_t)(strip * 2 + j) * 256;
+            d.a0 = *(p4_g4_t)(f + fl * 4);
+            d.a1 = *(p4_g4_t)(f + (fl + 32) * 4);
+        } else {
+            const uint8_t* f = tb + (size_t)(strip * 2 + j) * 512;
+            const q4_u32x2 lo = *(p4_g8_t)(f + fl * 8), hi = *(p4_g8_t)(f + (fl + 32) * 8);
+            d.a0 = lo[0];
+            d.a1 = lo[1];
+            d.b0 = hi[0];
+            d.b1 = hi[1];
+        }
+    };
+    // per tile: the position dwords (both K-steps) of fragment lanes fl and fl + 32, and the scale
+    auto load_tile = [&](uint32_t& d0, uint32_t& d1, uint32_t& scl, uint32_t e, int tk) {
+        scl = *(p4_g2_t)(sc + (size_t)tk * 16);
+        if (entry_sparse(e)) {
+            const uint8_t* pb = payload + entry_offset(e) + q4_sparse_codes(TILE) + (size_t)(strip * 64 + fl) * 4;
+            d0 = *(p4_g4_t)(pb);
+            d1 = *(p4_g4_t)(pb + 32 * 4);
+        }
+    };
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+
+    auto step_begin = [&](int ks, int pf_ks) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        load_x(pf_ks, (ks & 1) ^ 1);
+    };
+    auto step_mma = [&](int ks, const P4Codes& c, uint32_t p0, uint32_t p1, uint32_t sbits, int sp, int j) {
+        const float scl = q4_bf16_to_float(sbits);
+        A8 h0a, h0b, h1a, h1b;
+        h0a.raw = q4_dequant8(c.a0, scl);
+        h1a.raw = q4_dequant8(c.a1, scl);
+        h0b.raw = h0a.raw;                                 // a 2:4 step does not use the second operands
+        h1b.raw = h1a.raw;
+        if (!sp) {
+            h0b.raw = q4_dequant8(c.b0, scl);
+            h1b.raw = q4_dequant8(c.b1, scl);
+        }
+        const uint8_t* bs = lds + (ks & 1) * kP4Stage;
+        B16 xa[3], xb[3];
+        auto fetch = [&](int p, int buf) {
+            const int u = p >> 1, b0 = 2 * (p & 1);
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                xa[buf].raw[cc] = *reinterpret_cast<const u32x4*>(bs + xs_off(32 * b0 + i32, 2 * (2 * u + cc) + q));
+                xb[buf].raw[cc] = *reinterpret_cast<const u32x4*>(bs + xs_off(32 * (b0 + 1) + i32, 2 * (2 * u + cc) + q));
+            }
+        };
+        fetch(0, 0);
+        fetch(1, 1);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p + 2 < 4) fetch(p + 2, (p + 2) % 3);
+            const int u = p >> 1, b0 = 2 * (p & 1), buf = p % 3;
+            mma_step(acc[b0], acc[b0 + 1], u ? h1a.v : h0a.v, u ? h1b.v : h0b.v, xa[buf], xb[buf], (int)((u ? p1 : p0) >> (16 * j)), sp);
+        }
+    };
+
+    P4Codes c0, c1;              // codes of the even / odd step of a tile
+    c0.b0 = c0.b1 = c1.b0 = c1.b1 = 0u;
+    uint32_t p0 = 0u, p1 = 0u, sb = 0u, pn0 = 0u, pn1 = 0u, sbn = 0u;
+    uint32_t e = trow[0];
+    load_x(0, 0);
+    load_codes(c0, e, 0);
+    load_tile(pn0, pn1, sbn, e, 0);
+    __builtin_assume(Tk > 0);
+    for (int tk = 0; tk < Tk; ++tk) {
+        const int more = tk + 1 < Tk ? 1 : 0;
+        const uint32_t en = trow[tk + more];
+        const int sp = (int)(e & 1u);
+        step_begin(2 * tk, 2 * tk + 1);
+        // this tile's position dwords and scale were loaded a step ago and have landed; an opaque copy, so that it does
+        // not become a copy on the loop's back edge right behind the loads
+        asm volatile("v_mov_b32 %0, %3\n\tv_mov_b32 %1, %4\n\tv_mov_b32 %2, %5" : "=&v"(p0), "=&v"(p1), "=&v"(sb) : "v"(pn0), "v"(pn1), "v"(sbn));
+        load_codes(c1, e, 1);
+        step_mma(2 * tk, c0, p0, p1, sb, sp, 0);
+        step_begin(2 * tk + 1, 2 * tk + 1 + more);
+        load_codes(c0, en, 0);
+        load_tile(pn0, pn1, sbn, en, tk + more);
+        step_mma(2 * tk + 1, c1, p0, p1, sb, sp, 1);
+        e = en;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32
+    if (w4 < live) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t m = m0 + 32 * b + i32;
+            if (m >= M) continue;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v = {acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]};
+                store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + fo + 8 * g + 4 * q, v, 0);
+            }
+        }
+    }
+}
+
 }  // namespace patch
 
 using namespace patch;
@@ -688,8 +885,76 @@ patch_status patch_gemm4_many(const void* X, int64_t M, const patch_packed4* con
 }
 
 patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void* Y, void* stream) {
-    if (!P || !Y) return PATCH_ERR_ARG;
-    return patch_gemm4_many(X, M, &P, &Y, 1, stream);
+    return patch_gemm4_ex(X, M, P, Y, nullptr, 0, stream);
+}
+
+// Passes of up to 64 rows (the decode-shaped kernel) or the prefill-shaped kernel (mask tile 128 only)?  Both sides are
+// estimated from measured rates, as for the bf16 kernels:
+//   pass of r rows   rounds x (x(r) + R) x 0.05 us x 64-column steps, the terms of q4_strips_per_group (a workgroup
+//                    loads all of X whatever R is); 64 rows: 4096^2 17.8 us, 11008 x 4096 21.9, 13824 x 5120 44.5
+//   prefill kernel   rounds x steps per workgroup x (0.95 + 0.4 fill) us + 3, fill = min(1, workgroups / compute units)
+//                    (the dequantization makes its step 0.3 - 0.4 us longer than the bf16 kernel's), + for a split
+//                    3 + (2 split + 1) M N 4 B / 5.5 TB/s; splits of at most 8 slices of at least 512 columns
+// Returns the split to launch the prefill kernel with, or 0 for passes.
+static double q4_pass_us(int strips, int n_cus, int rows, int steps) {
+    const int R = q4_strips_per_group(strips, n_cus, rows);
+    const int groups = (strips + R - 1) / R;
+    const double x = rows <= 16 ? 0.15 + 0.045 * rows : rows <= 32 ? 1.7 : 1.7 + 2.8 * (rows - 32) / 32.0;   // 4.5 at 64 rows
+    const double rounds = groups <= 2 * n_cus ? (double)((groups + n_cus - 1) / n_cus) : (double)groups / n_cus + 0.5;
+    return rounds * (x + R) * 0.05 * steps;
+}
+
+static int q4_prefill_split(int64_t M, const patch_packed4* P, const GemmArgs& a) {
+    if (P->tile != 128 || M <= 16) return 0;
+    const int steps = P->Tk * 2, strips = (int)(P->N / 16);
+    const int64_t full = M / kQ4Rows;
+    const int rest = (int)(M % kQ4Rows);
+    const double passes_us = (double)full * q4_pass_us(strips, P->n_cus, kQ4Rows, steps) + (rest ? q4_pass_us(strips, P->n_cus, rest, steps) : 0.0);
+    const int blocks = (int)((P->N + kP4BN - 1) / kP4BN) * (int)((M + kP4BM - 1) / kP4BM);
+    const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
+    const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
+    const int longest = P->Tk * P->tile / 512;
+    int best_split = 1;
+    double best = 0.0;
+    for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
+        const int wgs = blocks * sp;
+        const int rounds = (wgs + P->n_cus - 1) / P->n_cus;
+        const double fill = wgs < P->n_cus ? (double)wgs / P->n_cus : 1.0;
+        double us = rounds * ((P->Tk + sp - 1) / sp) * 2 * (0.95 + 0.4 * fill) + 3.0;
+        if (sp > 1) us += 3.0 + (2.0 * sp + 1.0) * (double)per_slice / 5.5e6;
+        if (sp == 1 || us < best) { best = us; best_split = sp; }
+    }
+    return best < passes_us ? best_split : 0;
+}
+
+patch_status patch_gemm4_ex(const void* X, int64_t M, const patch_packed4* P, void* Y, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    if (!X || !P || !Y || M < 0) return PATCH_ERR_ARG;
+    if (!q4_aligned16(X) || !q4_aligned16(Y) || (workspace && !q4_aligned16(workspace))) return PATCH_ERR_ARG;
+    if (M == 0) return PATCH_OK;
+    const bool ws = workspace && workspace_bytes >= 2 * (size_t)M * (size_t)P->N * sizeof(float);
+    GemmArgs a = {};
+    a.M = M; a.N = P->N; a.K = P->K;
+    a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
+    a.n_cus = P->n_cus;
+    if (ws) { a.ws = static_cast<float*>(workspace); a.ws_bytes = workspace_bytes; }
+    const int split = q4_prefill_split(M, P, a);
+    if (split == 0) return patch_gemm4_many(X, M, &P, &Y, 1, stream);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int tiles_n = (int)((P->N + kP4BN - 1) / kP4BN), tiles_m = (int)((M + kP4BM - 1) / kP4BM);
+    const int grid = ((tiles_n * tiles_m + 7) / 8) * 8;
+    const uint16_t* Xp = static_cast<const uint16_t*>(X);
+    if (split == 1) {
+        hipLaunchKernelGGL((prefill4_kernel<false>), dim3(grid), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table,
+                           P->Tk, tiles_n, tiles_m, static_cast<float*>(Y));
+    } else {
+        hipLaunchKernelGGL((prefill4_kernel<true>), dim3(grid, split), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales,
+                           P->d_table, P->Tk, tiles_n, tiles_m, a.ws);
+        wr_reduce(a.ws, (size_t)M * (size_t)P->N / 4, split, static_cast<float*>(Y), 0, s);
+    }
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) { patch_note_hip_error((int)err); return PATCH_ERR_HIP; }
+    return PATCH_OK;
 }
 
 patch_status patch_pack_from4(const patch_packed4* P4, void* stream, patch_packed** out) {

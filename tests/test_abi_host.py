@@ -68,6 +68,8 @@ def test_argument_errors_without_device():
     assert L.patch_probe_lds_fill(0, fake, 1 << 20, 4, 1, fake, 1024, 0) == B.ERR_SIZE        # out too small
     # 4-bit storage
     assert L.patch_pack4(0, 128, 128, tm.ctypes.data, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+    assert L.patch_gemm4_ex(fake, 1, 0, fake, None, 0, 0) == B.ERR_ARG
+    assert L.patch_gemm4_ex(None, 1, fake, fake, None, 0, 0) == B.ERR_ARG
     assert L.patch_pack4(fake, 128, 128, 0, 64, 0, ctypes.byref(out)) == B.ERR_ARG
     assert L.patch_pack4(fake, 128, 128, tm.ctypes.data, 64, 0, None) == B.ERR_ARG
     assert L.patch_pack4(fake, 128, 128, tm.ctypes.data, 32, 0, ctypes.byref(out)) == B.ERR_SHAPE
@@ -165,7 +167,7 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
 
 
 @pytest.mark.parametrize("source,kernel,at_least", [("gemm_decode.hip", "decode_kernel", 4), ("gemm_mid.hip", "mid_kernel", 4),
-                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2), ("gemm_prefill.hip", "prefill_kernel_areg", 6)])
+                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2), ("gemm_prefill.hip", "prefill_kernel_areg", 6), ("quant4.hip", "prefill4_kernel", 2)])
 def test_kernels_with_untracked_loads_do_not_spill(source, kernel, at_least):
     """decode_kernel and mid_kernel issue their loads from asm statements and wait for them in a later one; until
     that wait the destinations must stay where the loads write them.  A spill (or any scratch use) of such a register
@@ -218,24 +220,26 @@ def test_no_flat_memory_instructions(tmp_path):
             assert body and len(re.findall(r"\bs_load_dword\b", body.group(0))) >= 2
 
 
-def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path):
-    """prefill_kernel_lds issues its matrix instructions from asm statements, so the compiler does not know that an
-    accumulator is still being written when the statement ends (the hardware does not interlock a read of it either).
-    From the first of those statements to the wait states in front of the output stage no compiler-generated instruction
-    may touch an accumulator register: no copy, no spill, no reuse."""
+@pytest.mark.parametrize("source,pattern,at_least", [
+    # prefill_kernel_lds: tile 128 / 64 x whole / split x blocks of 256 / 128 rows; prefill_kernel_areg: (128, 128), (64, 128),
+    # (64, 256) x whole / split; prefill4_kernel: whole / split
+    ("gemm_prefill.hip", r"_ZN5patch1[89]prefill_kernel_(?:lds|areg)\w+", 14), ("quant4.hip", r"_ZN5patch15prefill4_kernel\w+", 2)])
+def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path, source, pattern, at_least):
+    """The prefill kernels built on mma_step issue their matrix instructions from asm statements, so the compiler does not
+    know that an accumulator is still being written when the statement ends (the hardware does not interlock a read of
+    it either).  From the first of those statements to the wait states in front of the output stage no
+    compiler-generated instruction may touch an accumulator register: no copy, no spill, no reuse."""
     import subprocess
     from paper_2509_23410_amd import build
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = tmp_path / "gemm_prefill.s"
+    out = tmp_path / (source + ".s")
     cmd = [hipcc, *[f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")], "-S", "--cuda-device-only",
-           "-I", os.path.join(ROOT, "include"), "-I", build.CSRC, "-o", str(out), os.path.join(build.CSRC, "gemm_prefill.hip")]
+           "-I", os.path.join(ROOT, "include"), "-I", build.CSRC, "-o", str(out), os.path.join(build.CSRC, source)]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert r.returncode == 0, r.stdout[-2000:]
     text = out.read_text()
-    bodies = re.findall(r"^(_ZN5patch1[89]prefill_kernel_(?:lds|areg)\w+):.*?\n(.*?)^\.Lfunc_end", text, re.S | re.M)
-    # prefill_kernel_lds: tile 128 / 64 x whole / split x blocks of 256 / 128 rows; prefill_kernel_areg: (128, 128), (64, 128),
-    # (64, 256) x whole / split
-    assert len(bodies) >= 14, [b[0] for b in bodies]
+    bodies = re.findall(r"^(" + pattern + r"):.*?\n(.*?)^\.Lfunc_end", text, re.S | re.M)
+    assert len(bodies) >= at_least, [b[0] for b in bodies]
 
     def regs(tok):
         out_ = set()
@@ -259,7 +263,7 @@ def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path):
                 last = i
         # 8 accumulator tiles of 16 registers with blocks of 256 rows, 4 with 128 (the template argument BM)
         bm = re.search(r"prefill_kernel_ldsILi\d+ELb[01]ELi(\d+)E|prefill_kernel_aregILi\d+ELi(\d+)E", name)
-        want = 128 if (bm.group(1) or bm.group(2)) == "256" else 64
+        want = 128 if bm and (bm.group(1) or bm.group(2)) == "256" else 64      # prefill4_kernel: blocks of 128 rows
         assert len(since) == want and last is not None, (name, len(since))
         # ... and up to the wait states the kernel itself puts before its output stage reads the accumulators.  A tile
         # that no matrix instruction has written yet is still a constant (zero) to the compiler, which may keep other

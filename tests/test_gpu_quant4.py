@@ -39,11 +39,13 @@ class Prepared4:
         torch.cuda.synchronize()
         return bits_of(W_deq), codes.cpu().numpy(), bits_of(scales)
 
-    def gemm(self, X_bits):
+    def gemm(self, X_bits, workspace=None):
         M = X_bits.shape[0]
         X = to_dev_bf16(X_bits, self.dev)
         Y = torch.full((M, self.c.N), float("nan"), device=self.dev, dtype=torch.float32)
-        B.patch_gemm4(X, M, self.P, Y, stream())
+        if workspace is not None:
+            workspace.fill_(float("nan"))      # poisoned: every partial the launch reads it must have written
+        B.patch_gemm4(X, M, self.P, Y, stream(), workspace=workspace)
         torch.cuda.synchronize()
         return Y.cpu().numpy()
 
@@ -104,6 +106,29 @@ def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
     want = synth.bf16_bits_to_f32(p.W_deq_o).T
     assert np.array_equal(Y.view(np.uint32) & 0x7FFFFFFF, want.view(np.uint32) & 0x7FFFFFFF) or np.array_equal(Y, want)
     assert np.array_equal(Y, want)                       # values (a zero's sign aside)
+    p.P.close()
+
+
+@pytest.mark.parametrize("N,K,f,Ms", [(2176, 1152, 0.6, [33, 64, 65, 129, 300, 700]), (384, 2048, 1.0, [40, 100, 257]),
+                                      (1024, 1024, 0.0, [48, 128, 512]), (640, 128, 0.5, [33, 129]), (10368, 256, 0.4, [65, 130])])
+def test_prefill_shaped_product_from_4_bits(dev, N, K, f, Ms):
+    """patch_gemm4_ex on mask tile 128: the prefill-shaped kernel (weight read once per 128 rows, dequantized in
+    registers) without a workspace and with one (K split over workgroups, poisoned workspace), feature counts that
+    leave half of the last block empty, a single tile along K, ragged M, a weight of 81 tile rows; every element against
+    the oracle's product on the oracle's dequantized weight, repeated launches bit-equal (which kernel runs depends on
+    M, so rows are compared with the oracle, not across row counts)."""
+    c = synth.make_case("q4_prefill", N, K, max(Ms), 128, f, seed=29)
+    p = Prepared4(c, dev)
+    wn = row_norms(p.W_deq_o)
+    ws = torch.empty(8 * max(Ms) * N, device=dev, dtype=torch.float32)
+    for M in Ms:
+        Xb = c.X[:M]
+        Yo = p.oracle_gemm(Xb)
+        for w in (None, ws):
+            print(f"4-bit prefill-shaped N={N} K={K} f={f} M={M} workspace={w is not None}", flush=True)
+            Y = p.gemm(Xb, workspace=w)
+            check_elements(Y, Yo, row_norms(Xb), wn, K, f"4-bit prefill-shaped M={M} ws={w is not None}")
+            assert np.array_equal(p.gemm(Xb, workspace=w), Y), "launches of one configuration must be bit-equal"
     p.P.close()
 
 
