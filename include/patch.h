@@ -291,13 +291,13 @@ patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_
  *                  aligned; asynchronous, allocates nothing, bit-reproducible.  Decode-shaped: the weight is streamed
  *                  once per 64 rows of X; for prefill shapes dequantize once (patch_unpack4) and patch_pack the result
  *   patch_gemm4_ex  the same product with an optional caller workspace (DEVICE, 16-byte aligned, or NULL; used when it
- *                  holds at least two slices of M x N fp32).  Mask tile 128 has a prefill-shaped kernel that reads the
- *                  4-bit weight once per 128 rows of X and dequantizes in registers (no bf16 copy of the weight); with a
- *                  workspace it splits K over workgroups (partial sums in the workspace, summed in slice order).  It is
- *                  taken where an estimate of both sides puts it ahead of passes of up to 64 rows (with a workspace
- *                  from about 65 rows, from 48 on wide weights; without one from a few hundred rows, from 129 on wide
- *                  weights); otherwise, and for mask tile 64, passes as patch_gemm4 (= patch_gemm4_ex without a
- *                  workspace).  Launches that may run concurrently need distinct workspaces
+ *                  holds at least two slices of M x N fp32).  A prefill-shaped kernel reads the 4-bit weight once per
+ *                  128 rows of X and dequantizes in registers (no bf16 copy of the weight); with a workspace it splits K
+ *                  over workgroups (partial sums in the workspace, summed in slice order).  It is taken where an
+ *                  estimate of both sides puts it ahead of passes of up to 64 rows (with a workspace from about 65
+ *                  rows, from 48 on wide weights; without one from a few hundred rows, from 129 on wide weights);
+ *                  otherwise passes as patch_gemm4 (= patch_gemm4_ex without a workspace).  Launches that may run
+ *                  concurrently need distinct workspaces
  *   patch_gemm4_many  up to PATCH_MAX_MANY weights with the same K and tile against one X in one launch per 64 rows
  *                  (q / k / v, gate / up): Y[i] is M x N_i fp32; bit-reproducible, and equal to the single calls up to
  *                  the order of the fp32 partial sums (the split of K over wavefronts depends on the number of

@@ -522,7 +522,7 @@ static int q4_strips_per_group(int strips, int n_cus, int rows) {
 }
 
 // ------------------------------------------------------------------------------------------------------
-// Prefill-shaped product from the 4-bit storage (mask tile 128): the structure of prefill_kernel_areg - blocks of 256
+// Prefill-shaped product from the 4-bit storage: the structure of prefill_kernel_areg - blocks of 256
 // features x 128 rows, a wavefront owns 32 features x all 128 rows, X through two LDS stages - with the weight operands
 // dequantized in registers.  A lane loads the codes of its pieces of the stored fragments one step ahead (dense: two
 // 8-byte loads, fragment lanes fl and fl + 32, each holding the codes of both half-steps; 2:4: two 4-byte loads), the
@@ -544,12 +544,12 @@ struct P4Codes {
     uint32_t a0, a1, b0, b1;
 };
 
-template <bool SPLIT>
+template <int TILE, bool SPLIT>
 __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                        const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
                                                        const uint32_t* __restrict__ table, int Tk_all, int tiles_n, int tiles_m,
                                                        float* __restrict__ Y) {
-    constexpr int TILE = 128;
+    constexpr int KPT = TILE / kStepCols;      // K-steps per tile: 2 or 1
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -580,9 +580,9 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
         }
     }
     const int64_t n0 = (int64_t)bn * kP4BN, m0 = (int64_t)bm * kP4BM;
-    // N is a multiple of 128, not necessarily of 256: a wavefront of a missing second tile row works on the first one's
+    // N is a multiple of the tile, not necessarily of 256: a wavefront of a missing tile row works on the last live one's
     // weights (valid addresses) and stores nothing
-    const int live = (int)((N - n0) / TILE) < 2 ? (int)((N - n0) / TILE) : 2;
+    const int live = (int)((N - n0) / TILE) < kP4BN / TILE ? (int)((N - n0) / TILE) : kP4BN / TILE;
     const int trw = w4 < live ? w4 : live - 1;
     const int t_begin = SPLIT ? (int)((int64_t)blockIdx.y * Tk_all / gridDim.y) : 0;
     const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
@@ -603,7 +603,7 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     };
 
     const int i32 = lane & 31, q = lane >> 5;
-    // this lane's pieces: strip (32 w % 128) / 16 + i32 / 16 of the tile, fragment lanes fl and fl + 32
+    // this lane's pieces: strip (32 w % TILE) / 16 + i32 / 16 of the tile, fragment lanes fl and fl + 32
     const int strip = (fo % TILE) / 16 + (i32 >> 4);
     const int fl = 16 * q + (i32 & 15);
     // scale of the lane's row for the first tile of this K slice; the next tile's is 16 scales on
@@ -611,11 +611,11 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     auto load_codes = [&](P4Codes& d, uint32_t e, int j) {
         const uint8_t* tb = payload + entry_offset(e);
         if (entry_sparse(e)) {
-            const uint8_t* f = tb + (size_t)(strip * 2 + j) * 256;
+            const uint8_t* f = tb + (size_t)(strip * KPT + j) * 256;
             d.a0 = *(p4_g4_t)(f + fl * 4);
             d.a1 = *(p4_g4_t)(f + (fl + 32) * 4);
         } else {
-            const uint8_t* f = tb + (size_t)(strip * 2 + j) * 512;
+            const uint8_t* f = tb + (size_t)(strip * KPT + j) * 512;
             const q4_u32x2 lo = *(p4_g8_t)(f + fl * 8), hi = *(p4_g8_t)(f + (fl + 32) * 8);
             d.a0 = lo[0];
             d.a1 = lo[1];
@@ -623,13 +623,19 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
             d.b1 = hi[1];
         }
     };
-    // per tile: the position dwords (both K-steps) of fragment lanes fl and fl + 32, and the scale
+    // per tile: the position words of fragment lanes fl and fl + 32 (mask tile 128: a dword holding both K-steps; mask
+    // tile 64: 16 bits), and the scale
     auto load_tile = [&](uint32_t& d0, uint32_t& d1, uint32_t& scl, uint32_t e, int tk) {
         scl = *(p4_g2_t)(sc + (size_t)tk * 16);
         if (entry_sparse(e)) {
-            const uint8_t* pb = payload + entry_offset(e) + q4_sparse_codes(TILE) + (size_t)(strip * 64 + fl) * 4;
-            d0 = *(p4_g4_t)(pb);
-            d1 = *(p4_g4_t)(pb + 32 * 4);
+            const uint8_t* pb = payload + entry_offset(e) + q4_sparse_codes(TILE) + (size_t)(strip * 64 + fl) * (2 * KPT);
+            if constexpr (KPT == 2) {
+                d0 = *(p4_g4_t)(pb);
+                d1 = *(p4_g4_t)(pb + 32 * 4);
+            } else {
+                d0 = *(p4_g2_t)(pb);
+                d1 = *(p4_g2_t)(pb + 32 * 2);
+            }
         }
     };
 
@@ -675,29 +681,60 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
         }
     };
 
-    P4Codes c0, c1;              // codes of the even / odd step of a tile
-    c0.b0 = c0.b1 = c1.b0 = c1.b1 = 0u;
-    uint32_t p0 = 0u, p1 = 0u, sb = 0u, pn0 = 0u, pn1 = 0u, sbn = 0u;
-    uint32_t e = trow[0];
-    load_x(0, 0);
-    load_codes(c0, e, 0);
-    load_tile(pn0, pn1, sbn, e, 0);
-    __builtin_assume(Tk > 0);
-    for (int tk = 0; tk < Tk; ++tk) {
-        const int more = tk + 1 < Tk ? 1 : 0;
-        const uint32_t en = trow[tk + more];
-        const int sp = (int)(e & 1u);
-        step_begin(2 * tk, 2 * tk + 1);
-        // this tile's position dwords and scale were loaded a step ago and have landed; an opaque copy, so that it does
-        // not become a copy on the loop's back edge right behind the loads
-        asm volatile("v_mov_b32 %0, %3\n\tv_mov_b32 %1, %4\n\tv_mov_b32 %2, %5" : "=&v"(p0), "=&v"(p1), "=&v"(sb) : "v"(pn0), "v"(pn1), "v"(sbn));
-        load_codes(c1, e, 1);
-        step_mma(2 * tk, c0, p0, p1, sb, sp, 0);
-        step_begin(2 * tk + 1, 2 * tk + 1 + more);
-        load_codes(c0, en, 0);
-        load_tile(pn0, pn1, sbn, en, tk + more);
-        step_mma(2 * tk + 1, c1, p0, p1, sb, sp, 1);
-        e = en;
+    if constexpr (KPT == 2) {
+        P4Codes c0, c1;              // codes of the even / odd step of a tile
+        c0.b0 = c0.b1 = c1.b0 = c1.b1 = 0u;
+        uint32_t p0 = 0u, p1 = 0u, sb = 0u, pn0 = 0u, pn1 = 0u, sbn = 0u;
+        uint32_t e = trow[0];
+        load_x(0, 0);
+        load_codes(c0, e, 0);
+        load_tile(pn0, pn1, sbn, e, 0);
+        __builtin_assume(Tk > 0);
+        for (int tk = 0; tk < Tk; ++tk) {
+            const int more = tk + 1 < Tk ? 1 : 0;
+            const uint32_t en = trow[tk + more];
+            const int sp = (int)(e & 1u);
+            step_begin(2 * tk, 2 * tk + 1);
+            // this tile's position dwords and scale were loaded a step ago and have landed; an opaque copy, so that it does
+            // not become a copy on the loop's back edge right behind the loads
+            asm volatile("v_mov_b32 %0, %3\n\tv_mov_b32 %1, %4\n\tv_mov_b32 %2, %5" : "=&v"(p0), "=&v"(p1), "=&v"(sb) : "v"(pn0), "v"(pn1), "v"(sbn));
+            load_codes(c1, e, 1);
+            step_mma(2 * tk, c0, p0, p1, sb, sp, 0);
+            step_begin(2 * tk + 1, 2 * tk + 1 + more);
+            load_codes(c0, en, 0);
+            load_tile(pn0, pn1, sbn, en, tk + more);
+            step_mma(2 * tk + 1, c1, p0, p1, sb, sp, 1);
+            e = en;
+        }
+    } else {
+        // Mask tile 64: every step is a tile of its own, with its own scale and position words.  Steps go in pairs (the
+        // buffers alternate without a copy), table entries are read two steps ahead; past the end the last step is
+        // fetched again, and the second step of the last pair is skipped when the count is odd.
+        const int S = Tk;
+        P4Codes c0, c1;
+        c0.b0 = c0.b1 = c1.b0 = c1.b1 = 0u;
+        uint32_t a0 = 0u, a1 = 0u, as_ = 0u, b0_ = 0u, b1_ = 0u, bs_ = 0u;   // position words and scale of c0 / c1
+        uint32_t e0 = trow[0], e1 = trow[S > 1 ? 1 : 0];
+        load_x(0, 0);
+        load_codes(c0, e0, 0);
+        load_tile(a0, a1, as_, e0, 0);
+        __builtin_assume(S > 0);
+        for (int s_ = 0; s_ < S; s_ += 2) {
+            const int s1 = s_ + 1 < S ? s_ + 1 : S - 1, s2 = s_ + 2 < S ? s_ + 2 : S - 1, s3 = s_ + 3 < S ? s_ + 3 : S - 1;
+            const uint32_t e2 = trow[s2], e3 = trow[s3];
+            step_begin(s_, s1);
+            load_codes(c1, e1, 0);
+            load_tile(b0_, b1_, bs_, e1, s1);
+            step_mma(s_, c0, a0, a1, as_, (int)(e0 & 1u), 0);
+            if (s_ + 1 < S) {
+                step_begin(s_ + 1, s2);
+                load_codes(c0, e2, 0);
+                load_tile(a0, a1, as_, e2, s2);
+                step_mma(s_ + 1, c1, b0_, b1_, bs_, (int)(e1 & 1u), 0);
+            }
+            e0 = e2;
+            e1 = e3;
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
@@ -888,7 +925,7 @@ patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void*
     return patch_gemm4_ex(X, M, P, Y, nullptr, 0, stream);
 }
 
-// Passes of up to 64 rows (the decode-shaped kernel) or the prefill-shaped kernel (mask tile 128 only)?  Both sides are
+// Passes of up to 64 rows (the decode-shaped kernel) or the prefill-shaped kernel?  Both sides are
 // estimated from measured rates, as for the bf16 kernels:
 //   pass of r rows   rounds x (x(r) + R) x 0.05 us x 64-column steps, the terms of q4_strips_per_group (a workgroup
 //                    loads all of X whatever R is); 64 rows: 4096^2 17.8 us, 11008 x 4096 21.9, 13824 x 5120 44.5
@@ -905,8 +942,8 @@ static double q4_pass_us(int strips, int n_cus, int rows, int steps) {
 }
 
 static int q4_prefill_split(int64_t M, const patch_packed4* P, const GemmArgs& a) {
-    if (P->tile != 128 || M <= 16) return 0;
-    const int steps = P->Tk * 2, strips = (int)(P->N / 16);
+    if (M <= 16) return 0;
+    const int kpt = P->tile / 64, steps = P->Tk * kpt, strips = (int)(P->N / 16);
     const int64_t full = M / kQ4Rows;
     const int rest = (int)(M % kQ4Rows);
     const double passes_us = (double)full * q4_pass_us(strips, P->n_cus, kQ4Rows, steps) + (rest ? q4_pass_us(strips, P->n_cus, rest, steps) : 0.0);
@@ -920,7 +957,7 @@ static int q4_prefill_split(int64_t M, const patch_packed4* P, const GemmArgs& a
         const int wgs = blocks * sp;
         const int rounds = (wgs + P->n_cus - 1) / P->n_cus;
         const double fill = wgs < P->n_cus ? (double)wgs / P->n_cus : 1.0;
-        double us = rounds * ((P->Tk + sp - 1) / sp) * 2 * (0.95 + 0.4 * fill) + 3.0;
+        double us = rounds * ((P->Tk + sp - 1) / sp) * kpt * (0.95 + 0.4 * fill) + 3.0;
         if (sp > 1) us += 3.0 + (2.0 * sp + 1.0) * (double)per_slice / 5.5e6;
         if (sp == 1 || us < best) { best = us; best_split = sp; }
     }
@@ -944,14 +981,18 @@ patch_status patch_gemm4_ex(const void* X, int64_t M, const patch_packed4* P, vo
     const int tiles_n = (int)((P->N + kP4BN - 1) / kP4BN), tiles_m = (int)((M + kP4BM - 1) / kP4BM);
     const int grid = ((tiles_n * tiles_m + 7) / 8) * 8;
     const uint16_t* Xp = static_cast<const uint16_t*>(X);
-    if (split == 1) {
-        hipLaunchKernelGGL((prefill4_kernel<false>), dim3(grid), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table,
-                           P->Tk, tiles_n, tiles_m, static_cast<float*>(Y));
-    } else {
-        hipLaunchKernelGGL((prefill4_kernel<true>), dim3(grid, split), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales,
-                           P->d_table, P->Tk, tiles_n, tiles_m, a.ws);
-        wr_reduce(a.ws, (size_t)M * (size_t)P->N / 4, split, static_cast<float*>(Y), 0, s);
-    }
+    auto launch = [&](auto whole, auto sliced) {
+        if (split == 1) {
+            hipLaunchKernelGGL(whole, dim3(grid), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk, tiles_n,
+                               tiles_m, static_cast<float*>(Y));
+        } else {
+            hipLaunchKernelGGL(sliced, dim3(grid, split), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk,
+                               tiles_n, tiles_m, a.ws);
+            wr_reduce(a.ws, (size_t)M * (size_t)P->N / 4, split, static_cast<float*>(Y), 0, s);
+        }
+    };
+    if (P->tile == 128) launch(prefill4_kernel<128, false>, prefill4_kernel<128, true>);
+    else launch(prefill4_kernel<64, false>, prefill4_kernel<64, true>);
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) { patch_note_hip_error((int)err); return PATCH_ERR_HIP; }
     return PATCH_OK;

@@ -109,15 +109,19 @@ def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
     p.P.close()
 
 
-@pytest.mark.parametrize("N,K,f,Ms", [(2176, 1152, 0.6, [33, 64, 65, 129, 300, 700]), (384, 2048, 1.0, [40, 100, 257]),
-                                      (1024, 1024, 0.0, [48, 128, 512]), (640, 128, 0.5, [33, 129]), (10368, 256, 0.4, [65, 130])])
-def test_prefill_shaped_product_from_4_bits(dev, N, K, f, Ms):
-    """patch_gemm4_ex on mask tile 128: the prefill-shaped kernel (weight read once per 128 rows, dequantized in
+@pytest.mark.parametrize("t,N,K,f,Ms", [(128, 2176, 1152, 0.6, [33, 64, 65, 129, 300, 700]), (128, 384, 2048, 1.0, [40, 100, 257]),
+                                        (128, 1024, 1024, 0.0, [48, 128, 512]), (128, 640, 128, 0.5, [33, 129]),
+                                        (128, 10368, 256, 0.4, [65, 130]),
+                                        (64, 2112, 1088, 0.6, [33, 65, 129, 300, 700]), (64, 320, 2048, 1.0, [40, 257]),
+                                        (64, 1024, 1024, 0.0, [128, 512]), (64, 576, 64, 0.5, [129]), (64, 192, 448, 0.5, [100, 300])])
+def test_prefill_shaped_product_from_4_bits(dev, t, N, K, f, Ms):
+    """patch_gemm4_ex: the prefill-shaped kernel (weight read once per 128 rows, dequantized in
     registers) without a workspace and with one (K split over workgroups, poisoned workspace), feature counts that
-    leave half of the last block empty, a single tile along K, ragged M, a weight of 81 tile rows; every element against
+    leave part of the last block empty, a single tile along K, odd and even tile counts (mask tile 64 takes its steps in
+    pairs), ragged M, a weight of 81 tile rows; both mask tiles; every element against
     the oracle's product on the oracle's dequantized weight, repeated launches bit-equal (which kernel runs depends on
     M, so rows are compared with the oracle, not across row counts)."""
-    c = synth.make_case("q4_prefill", N, K, max(Ms), 128, f, seed=29)
+    c = synth.make_case("q4_prefill", N, K, max(Ms), t, f, seed=29)
     p = Prepared4(c, dev)
     wn = row_norms(p.W_deq_o)
     ws = torch.empty(8 * max(Ms) * N, device=dev, dtype=torch.float32)
@@ -125,7 +129,7 @@ def test_prefill_shaped_product_from_4_bits(dev, N, K, f, Ms):
         Xb = c.X[:M]
         Yo = p.oracle_gemm(Xb)
         for w in (None, ws):
-            print(f"4-bit prefill-shaped N={N} K={K} f={f} M={M} workspace={w is not None}", flush=True)
+            print(f"4-bit prefill-shaped tile={t} N={N} K={K} f={f} M={M} workspace={w is not None}", flush=True)
             Y = p.gemm(Xb, workspace=w)
             check_elements(Y, Yo, row_norms(Xb), wn, K, f"4-bit prefill-shaped M={M} ws={w is not None}")
             assert np.array_equal(p.gemm(Xb, workspace=w), Y), "launches of one configuration must be bit-equal"
