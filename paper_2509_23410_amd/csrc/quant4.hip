@@ -523,16 +523,14 @@ static int q4_strips_per_group(int strips, int n_cus, int rows) {
 
 // ------------------------------------------------------------------------------------------------------
 // Prefill-shaped product from the 4-bit storage: the structure of prefill_kernel_areg - blocks of 256
-// features x 128 rows, a wavefront owns 32 features x all 128 rows, X through two LDS stages - with the weight operands
+// features x 128 or 256 rows, a wavefront owns 32 features x all rows, X through two LDS stages - with the weight operands
 // dequantized in registers.  A lane loads the codes of its pieces of the stored fragments one step ahead (dense: two
 // 8-byte loads, fragment lanes fl and fl + 32, each holding the codes of both half-steps; 2:4: two 4-byte loads), the
 // scale of its row once per tile and the position dwords once per tile; at the top of a step the codes of that step
 // become bf16 operands (q4_dequant8) and the step runs as in the bf16 kernel.  The weight is read once per 128 rows of
 // X, at 4 bits per kept weight, and no bf16 copy of it exists anywhere.
 // ------------------------------------------------------------------------------------------------------
-constexpr int kP4BN = 256, kP4BM = 128;
-constexpr int kP4Stage = kP4BM * 128;      // 16 KB
-constexpr int kP4Lds = 2 * kP4Stage;
+constexpr int kP4BN = 256;
 
 typedef const __attribute__((address_space(1))) uint32_t* p4_g4_t;
 typedef const __attribute__((address_space(1))) uint16_t* p4_g2_t;
@@ -544,12 +542,15 @@ struct P4Codes {
     uint32_t a0, a1, b0, b1;
 };
 
-template <int TILE, bool SPLIT>
+template <int TILE, int BM, bool SPLIT>
 __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restrict__ X, int64_t M, int64_t N, int64_t K,
                                                        const uint8_t* __restrict__ payload, const uint16_t* __restrict__ scales,
                                                        const uint32_t* __restrict__ table, int Tk_all, int tiles_n, int tiles_m,
                                                        float* __restrict__ Y) {
     constexpr int KPT = TILE / kStepCols;      // K-steps per tile: 2 or 1
+    constexpr int NB = BM / 32;                // 32-row blocks: 4 or 8
+    constexpr int XP = BM / 64;                // 1 KB pieces of the X tile per wavefront
+    constexpr int kP4Stage = BM * 128;         // 16 or 32 KB
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -579,7 +580,7 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
             bm = (tiles_m / GM) * GM + rem % gm;
         }
     }
-    const int64_t n0 = (int64_t)bn * kP4BN, m0 = (int64_t)bm * kP4BM;
+    const int64_t n0 = (int64_t)bn * kP4BN, m0 = (int64_t)bm * BM;
     // N is a multiple of the tile, not necessarily of 256: a wavefront of a missing tile row works on the last live one's
     // weights (valid addresses) and stores nothing
     const int live = (int)((N - n0) / TILE) < kP4BN / TILE ? (int)((N - n0) / TILE) : kP4BN / TILE;
@@ -588,9 +589,9 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     const int Tk = SPLIT ? (int)((int64_t)(blockIdx.y + 1) * Tk_all / gridDim.y) - t_begin : Tk_all;
     const uint32_t* trow = table + ((int64_t)(n0 / TILE) + trw) * Tk_all + t_begin;
 
-    const uint8_t* xsrc[2];
+    const uint8_t* xsrc[XP];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < XP; ++i) {
         const int c = (w + 8 * i) * 64 + lane;
         const int m = c >> 3, pp = c & 7, pl = pp ^ ((m >> 1) & 7);
         int64_t row = m0 + m;
@@ -599,7 +600,7 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     }
     auto load_x = [&](int ks, int stage) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) g2l16(xsrc[i] + (size_t)ks * 128, lds + stage * kP4Stage + (w + 8 * i) * 1024);
+        for (int i = 0; i < XP; ++i) g2l16(xsrc[i] + (size_t)ks * 128, lds + stage * kP4Stage + (w + 8 * i) * 1024);
     };
 
     const int i32 = lane & 31, q = lane >> 5;
@@ -639,9 +640,9 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
         }
     };
 
-    f32x16 acc[4];
+    f32x16 acc[NB];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 
@@ -664,7 +665,7 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
         const uint8_t* bs = lds + (ks & 1) * kP4Stage;
         B16 xa[3], xb[3];
         auto fetch = [&](int p, int buf) {
-            const int u = p >> 1, b0 = 2 * (p & 1);
+            const int u = p / (NB / 2), b0 = 2 * (p % (NB / 2));
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc) {
                 xa[buf].raw[cc] = *reinterpret_cast<const u32x4*>(bs + xs_off(32 * b0 + i32, 2 * (2 * u + cc) + q));
@@ -674,9 +675,9 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
         fetch(0, 0);
         fetch(1, 1);
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            if (p + 2 < 4) fetch(p + 2, (p + 2) % 3);
-            const int u = p >> 1, b0 = 2 * (p & 1), buf = p % 3;
+        for (int p = 0; p < NB; ++p) {
+            if (p + 2 < NB) fetch(p + 2, (p + 2) % 3);
+            const int u = p / (NB / 2), b0 = 2 * (p % (NB / 2)), buf = p % 3;
             mma_step(acc[b0], acc[b0 + 1], u ? h1a.v : h0a.v, u ? h1b.v : h0b.v, xa[buf], xb[buf], (int)((u ? p1 : p0) >> (16 * j)), sp);
         }
     };
@@ -741,7 +742,7 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32
     if (w4 < live) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < NB; ++b) {
             const int64_t m = m0 + 32 * b + i32;
             if (m >= M) continue;
 #pragma unroll
@@ -929,10 +930,11 @@ patch_status patch_gemm4(const void* X, int64_t M, const patch_packed4* P, void*
 // estimated from measured rates, as for the bf16 kernels:
 //   pass of r rows   rounds x (x(r) + R) x 0.05 us x 64-column steps, the terms of q4_strips_per_group (a workgroup
 //                    loads all of X whatever R is); 64 rows: 4096^2 17.8 us, 11008 x 4096 21.9, 13824 x 5120 44.5
-//   prefill kernel   rounds x steps per workgroup x (0.95 + 0.4 fill) us + 3, fill = min(1, workgroups / compute units)
-//                    (the dequantization makes its step 0.3 - 0.4 us longer than the bf16 kernel's), + for a split
-//                    3 + (2 split + 1) M N 4 B / 5.5 TB/s; splits of at most 8 slices of at least 512 columns
-// Returns the split to launch the prefill kernel with, or 0 for passes.
+//   prefill kernel   rounds x steps per workgroup x (t0 + t1 fill) us + 3, fill = min(1, workgroups / compute units),
+//                    for blocks of 128 and of 256 rows (the dequantization makes a step 0.2 - 0.4 us longer than the
+//                    bf16 kernel's), + for a split 3 + (2 split + 1) M N 4 B / 5.5 TB/s; splits of at most 8 slices of at
+//                    least 512 columns
+// Returns the split to launch the prefill kernel with (and the block height), or 0 for passes.
 static double q4_pass_us(int strips, int n_cus, int rows, int steps) {
     const int R = q4_strips_per_group(strips, n_cus, rows);
     const int groups = (strips + R - 1) / R;
@@ -941,25 +943,32 @@ static double q4_pass_us(int strips, int n_cus, int rows, int steps) {
     return rounds * (x + R) * 0.05 * steps;
 }
 
-static int q4_prefill_split(int64_t M, const patch_packed4* P, const GemmArgs& a) {
+static int q4_prefill_split(int64_t M, const patch_packed4* P, const GemmArgs& a, int* bm_out) {
+    *bm_out = 128;
     if (M <= 16) return 0;
     const int kpt = P->tile / 64, steps = P->Tk * kpt, strips = (int)(P->N / 16);
     const int64_t full = M / kQ4Rows;
     const int rest = (int)(M % kQ4Rows);
     const double passes_us = (double)full * q4_pass_us(strips, P->n_cus, kQ4Rows, steps) + (rest ? q4_pass_us(strips, P->n_cus, rest, steps) : 0.0);
-    const int blocks = (int)((P->N + kP4BN - 1) / kP4BN) * (int)((M + kP4BM - 1) / kP4BM);
     const size_t per_slice = (size_t)M * (size_t)P->N * sizeof(float);
     const int fit = a.ws ? (int)(a.ws_bytes / per_slice < 8 ? a.ws_bytes / per_slice : 8) : 1;
     const int longest = P->Tk * P->tile / 512;
     int best_split = 1;
     double best = 0.0;
-    for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
-        const int wgs = blocks * sp;
-        const int rounds = (wgs + P->n_cus - 1) / P->n_cus;
-        const double fill = wgs < P->n_cus ? (double)wgs / P->n_cus : 1.0;
-        double us = rounds * ((P->Tk + sp - 1) / sp) * kpt * (0.95 + 0.4 * fill) + 3.0;
-        if (sp > 1) us += 3.0 + (2.0 * sp + 1.0) * (double)per_slice / 5.5e6;
-        if (sp == 1 || us < best) { best = us; best_split = sp; }
+    bool first = true;
+    for (int bm : {128, 256}) {
+        const int blocks = (int)((P->N + kP4BN - 1) / kP4BN) * (int)((M + bm - 1) / bm);
+        // a step of 256 rows dequantizes the same codes for twice the rows: 1.2 + 0.47 fill us against 0.88 + 0.2 fill
+        // (fitted to unsplit launches of 16 .. 256 workgroups); it pays once 128-row blocks would need a second round
+        const double t0 = bm == 128 ? 0.88 : 1.2, t1 = bm == 128 ? 0.2 : 0.47;
+        for (int sp = 1; sp <= 8 && (sp == 1 || (sp <= fit && sp <= longest)); ++sp) {
+            const int wgs = blocks * sp;
+            const int rounds = (wgs + P->n_cus - 1) / P->n_cus;
+            const double fill = wgs < P->n_cus ? (double)wgs / P->n_cus : 1.0;
+            double us = rounds * ((P->Tk + sp - 1) / sp) * kpt * (t0 + t1 * fill) + 3.0;
+            if (sp > 1) us += 3.0 + (2.0 * sp + 1.0) * (double)per_slice / 5.5e6;
+            if (first || us < best) { best = us; best_split = sp; *bm_out = bm; first = false; }
+        }
     }
     return best < passes_us ? best_split : 0;
 }
@@ -975,24 +984,28 @@ patch_status patch_gemm4_ex(const void* X, int64_t M, const patch_packed4* P, vo
     a.tile = P->tile; a.Tn = P->Tn; a.Tk = P->Tk;
     a.n_cus = P->n_cus;
     if (ws) { a.ws = static_cast<float*>(workspace); a.ws_bytes = workspace_bytes; }
-    const int split = q4_prefill_split(M, P, a);
+    int bm = 128;
+    const int split = q4_prefill_split(M, P, a, &bm);
     if (split == 0) return patch_gemm4_many(X, M, &P, &Y, 1, stream);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int tiles_n = (int)((P->N + kP4BN - 1) / kP4BN), tiles_m = (int)((M + kP4BM - 1) / kP4BM);
+    const int tiles_n = (int)((P->N + kP4BN - 1) / kP4BN), tiles_m = (int)((M + bm - 1) / bm);
     const int grid = ((tiles_n * tiles_m + 7) / 8) * 8;
+    const int lds_bytes = 2 * bm * 128;
     const uint16_t* Xp = static_cast<const uint16_t*>(X);
     auto launch = [&](auto whole, auto sliced) {
         if (split == 1) {
-            hipLaunchKernelGGL(whole, dim3(grid), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk, tiles_n,
+            hipLaunchKernelGGL(whole, dim3(grid), dim3(512), lds_bytes, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk, tiles_n,
                                tiles_m, static_cast<float*>(Y));
         } else {
-            hipLaunchKernelGGL(sliced, dim3(grid, split), dim3(512), kP4Lds, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk,
+            hipLaunchKernelGGL(sliced, dim3(grid, split), dim3(512), lds_bytes, s, Xp, M, P->N, P->K, P->d_payload, P->d_scales, P->d_table, P->Tk,
                                tiles_n, tiles_m, a.ws);
             wr_reduce(a.ws, (size_t)M * (size_t)P->N / 4, split, static_cast<float*>(Y), 0, s);
         }
     };
-    if (P->tile == 128) launch(prefill4_kernel<128, false>, prefill4_kernel<128, true>);
-    else launch(prefill4_kernel<64, false>, prefill4_kernel<64, true>);
+    if (P->tile == 128 && bm == 128) launch(prefill4_kernel<128, 128, false>, prefill4_kernel<128, 128, true>);
+    else if (P->tile == 128) launch(prefill4_kernel<128, 256, false>, prefill4_kernel<128, 256, true>);
+    else if (bm == 128) launch(prefill4_kernel<64, 128, false>, prefill4_kernel<64, 128, true>);
+    else launch(prefill4_kernel<64, 256, false>, prefill4_kernel<64, 256, true>);
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) { patch_note_hip_error((int)err); return PATCH_ERR_HIP; }
     return PATCH_OK;

@@ -167,7 +167,7 @@ def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
 
 
 @pytest.mark.parametrize("source,kernel,at_least", [("gemm_decode.hip", "decode_kernel", 4), ("gemm_mid.hip", "mid_kernel", 4),
-                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2), ("gemm_prefill.hip", "prefill_kernel_areg", 6), ("quant4.hip", "prefill4_kernel", 4)])
+                                                   ("gemm_prefill.hip", "prefill_kernel_lds", 2), ("gemm_prefill.hip", "prefill_kernel_areg", 6), ("quant4.hip", "prefill4_kernel", 8)])
 def test_kernels_with_untracked_loads_do_not_spill(source, kernel, at_least):
     """decode_kernel and mid_kernel issue their loads from asm statements and wait for them in a later one; until
     that wait the destinations must stay where the loads write them.  A spill (or any scratch use) of such a register
@@ -222,8 +222,8 @@ def test_no_flat_memory_instructions(tmp_path):
 
 @pytest.mark.parametrize("source,pattern,at_least", [
     # prefill_kernel_lds: tile 128 / 64 x whole / split x blocks of 256 / 128 rows; prefill_kernel_areg: (128, 128), (64, 128),
-    # (64, 256) x whole / split; prefill4_kernel: tile 128 / 64 x whole / split
-    ("gemm_prefill.hip", r"_ZN5patch1[89]prefill_kernel_(?:lds|areg)\w+", 14), ("quant4.hip", r"_ZN5patch15prefill4_kernel\w+", 4)])
+    # (64, 256) x whole / split; prefill4_kernel: tile 128 / 64 x blocks of 128 / 256 rows x whole / split
+    ("gemm_prefill.hip", r"_ZN5patch1[89]prefill_kernel_(?:lds|areg)\w+", 14), ("quant4.hip", r"_ZN5patch15prefill4_kernel\w+", 8)])
 def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path, source, pattern, at_least):
     """The prefill kernels built on mma_step issue their matrix instructions from asm statements, so the compiler does not
     know that an accumulator is still being written when the statement ends (the hardware does not interlock a read of
@@ -263,7 +263,8 @@ def test_lds_prefill_kernel_leaves_its_accumulators_alone(tmp_path, source, patt
                 last = i
         # 8 accumulator tiles of 16 registers with blocks of 256 rows, 4 with 128 (the template argument BM)
         bm = re.search(r"prefill_kernel_ldsILi\d+ELb[01]ELi(\d+)E|prefill_kernel_aregILi\d+ELi(\d+)E", name)
-        want = 128 if bm and (bm.group(1) or bm.group(2)) == "256" else 64      # prefill4_kernel: blocks of 128 rows
+        bm = bm or re.search(r"prefill4_kernelILi\d+ELi(\d+)E()", name)
+        want = 128 if (bm.group(1) or bm.group(2)) == "256" else 64
         assert len(since) == want and last is not None, (name, len(since))
         # ... and up to the wait states the kernel itself puts before its output stage reads the accumulators.  A tile
         # that no matrix instruction has written yet is still a constant (zero) to the compiler, which may keep other

@@ -111,14 +111,14 @@ def test_product_with_identity_reads_back_the_dequantized_weight(dev, t, f):
 
 @pytest.mark.parametrize("t,N,K,f,Ms", [(128, 2176, 1152, 0.6, [33, 64, 65, 129, 300, 700]), (128, 384, 2048, 1.0, [40, 100, 257]),
                                         (128, 1024, 1024, 0.0, [48, 128, 512]), (128, 640, 128, 0.5, [33, 129]),
-                                        (128, 10368, 256, 0.4, [65, 130]),
+                                        (128, 10368, 256, 0.4, [65, 130]), (128, 4224, 512, 0.5, [2100]), (64, 4160, 448, 0.5, [2100]),
                                         (64, 2112, 1088, 0.6, [33, 65, 129, 300, 700]), (64, 320, 2048, 1.0, [40, 257]),
                                         (64, 1024, 1024, 0.0, [128, 512]), (64, 576, 64, 0.5, [129]), (64, 192, 448, 0.5, [100, 300])])
 def test_prefill_shaped_product_from_4_bits(dev, t, N, K, f, Ms):
     """patch_gemm4_ex: the prefill-shaped kernel (weight read once per 128 rows, dequantized in
     registers) without a workspace and with one (K split over workgroups, poisoned workspace), feature counts that
     leave part of the last block empty, a single tile along K, odd and even tile counts (mask tile 64 takes its steps in
-    pairs), ragged M, a weight of 81 tile rows; both mask tiles; every element against
+    pairs), ragged M, a weight of 81 tile rows, row counts that take blocks of 256 rows; both mask tiles; every element against
     the oracle's product on the oracle's dequantized weight, repeated launches bit-equal (which kernel runs depends on
     M, so rows are compared with the oracle, not across row counts)."""
     c = synth.make_case("q4_prefill", N, K, max(Ms), t, f, seed=29)
