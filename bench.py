@@ -61,13 +61,16 @@ def _keep_top2(torch, W):
     return keep
 
 
-def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 512, 4096)):
+def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 512, 4096), q4=False):
     """The 13B decoder stack: 40 layers x {q, k, v, o 5120 x 5120; gate, up 13824 x 5120; down 5120 x 13824}, one 2:4
     tile fraction per layer drawn U[0, 1) - or, with per_matrix, the fractions of synth.matrix_fractions (key / value
     dense, MLP heavy, middle blocks heavy; global target 0.5) - every GEMM with its own X; time = sum over the layers.
     A layer runs as four launches (q / k / v share X, gate / up share X).  Weights are packed layer by layer and freed;
     they are drawn on the device (N(0, 0.02^2), magnitude 2:4 mask) - the parity tests cover these shapes with the
-    host-drawn inputs.  Every layer is also run with an all-dense map of the same weights."""
+    host-drawn inputs.  Every layer is also run with an all-dense map of the same weights.  With q4 the same pruned
+    weights are also stored in 4 bits (patch_pack4) and run at M = 1 (four launches: patch_gemm4_many / patch_gemm4) and
+    M = 512 (seven patch_gemm4_ex launches); a layer's 4-bit weights (about 150 MB) would stay in the last-level cache
+    between repetitions, so two consecutive layers are timed alternately (300 MB) and half of the pair's time counts."""
     H, F = 5120, 13824
     shapes = [("q", H, H), ("k", H, H), ("v", H, H), ("o", H, H), ("gate", F, H), ("up", F, H), ("down", H, F)]
     if per_matrix:
@@ -81,6 +84,7 @@ def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 5
     y = {n: torch.empty((4096, N_), device=dev, dtype=torch.float32) for n, N_, _ in shapes}
     ws = torch.empty(96 << 20, device=dev, dtype=torch.float32)     # 384 MB: room for every split the launcher picks
     tot = {M_: dict(mix=0.0, dense=0.0) for M_ in Ms}
+    tot4, bytes4, prev4 = {1: 0.0, 512: 0.0}, 0, None
     packed_bytes, dense_bytes, flop_w, ideal_s = 0, 0, 0.0, {M_: 0.0 for M_ in Ms}
     per_layer = []
 
@@ -90,8 +94,18 @@ def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 5
         B.patch_gemm_many(xH, M_, [L["gate"], L["up"]], [y["gate"], y["up"]], stream, workspace=ws)
         B.patch_gemm(xF, M_, L["down"], y["down"], stream, workspace=ws)
 
+    def layer_pass4(L4, M_):
+        if M_ == 1:
+            B.patch_gemm4_many(xH, 1, [L4["q"], L4["k"], L4["v"]], [y["q"], y["k"], y["v"]], stream)
+            B.patch_gemm4(xH, 1, L4["o"], y["o"], stream)
+            B.patch_gemm4_many(xH, 1, [L4["gate"], L4["up"]], [y["gate"], y["up"]], stream)
+            B.patch_gemm4(xF, 1, L4["down"], y["down"], stream)
+        else:
+            for name, _, K_ in shapes:
+                B.patch_gemm4(xH if K_ == H else xF, M_, L4[name], y[name], stream, workspace=ws)
+
     for li in range(40):
-        layer, dense = {}, {}
+        layer, dense, layer4 = {}, {}, {}
         for mi, (name, N_, K_) in enumerate(shapes):
             f = float(fr[li, mi])
             W = (torch.randn(N_, K_, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
@@ -101,6 +115,9 @@ def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 5
             B.patch_apply_mask(W, keep.view(N_, K_), tm, N_, K_, t, W_hat, stream)
             layer[name] = B.patch_pack(W_hat, N_, K_, tm, t, stream)
             dense[name] = B.patch_pack(W_hat, N_, K_, np.ones_like(tm), t, stream)
+            if q4:
+                layer4[name] = B.patch_pack4(W_hat, N_, K_, tm, t, stream)
+                bytes4 += layer4[name].nbytes
             packed_bytes += layer[name].nbytes
             dense_bytes += dense[name].nbytes
             del W, keep, W_hat
@@ -112,10 +129,19 @@ def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 5
                 s_ = min(timed(lambda _i: layer_pass(L, M_), reps) / reps for _ in range(2))
                 tot[M_][key] += s_
                 row[f"us_M{M_}" + ("" if key == "mix" else "_all_dense")] = round(s_ * 1e6, 1)
+        if q4 and prev4 is not None:
+            for M_ in (1, 512):
+                reps = 10 if M_ == 1 else 4
+                pair = lambda _i: (layer_pass4(prev4, M_), layer_pass4(layer4, M_))
+                timed(pair, 2)
+                s_ = min(timed(pair, reps) / reps for _ in range(2)) / 2.0
+                tot4[M_] += s_ * 40.0 / 39.0          # 39 pairs stand for 40 layers
+                row[f"us_M{M_}_q4_mean_with_previous_layer"] = round(s_ * 1e6, 1)
         per_layer.append(row)
-        for L in (layer, dense):
+        for L in (layer, dense) + ((prev4,) if prev4 is not None else ()):
             for P_ in L.values():
                 P_.close()
+        prev4 = layer4 if q4 else None
     layer_flop = sum(2.0 * N_ * K_ for _, N_, K_ in shapes)            # per row of X
     mat_flop = np.array([2.0 * N_ * K_ for _, N_, K_ in shapes])
     f_mean = float((fr * mat_flop[None, :]).sum() / (mat_flop.sum() * 40))   # parameter-weighted
@@ -129,7 +155,20 @@ def stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=False, Ms=(1, 5
                   issued_TFLOPs=round(issued / secs / 1e12, 1), frac_mfma_peak=round(issued / secs / 1e12 / PEAK_MFMA_BF16_TF, 4),
                   GBps_compressed=round(packed_bytes / secs / 1e9, 1), frac_hbm_peak=round(packed_bytes / secs / 1e9 / PEAK_HBM_GBS, 4))
         rows.append(r_)
-    return dict(layers=40, launches_per_layer=4, packed_GB=round(packed_bytes / 1e9, 3), dense_GB=round(dense_bytes / 1e9, 3),
+    extra = {}
+    if prev4 is not None:
+        for P_ in prev4.values():
+            P_.close()
+    if q4:
+        extra["q4"] = dict(packed_GB=round(bytes4 / 1e9, 3), bytes_vs_bf16_storage=round(bytes4 / packed_bytes, 4),
+                           ms_total_M1=round(tot4[1] * 1e3, 3), GBps_M1=round(bytes4 / tot4[1] / 1e9, 1),
+                           frac_hbm_peak_M1=round(bytes4 / tot4[1] / 1e9 / PEAK_HBM_GBS, 4),
+                           ms_total_M512=round(tot4[512] * 1e3, 3),
+                           dense_equiv_TFLOPs_M512=round(40 * layer_flop * 512 / tot4[512] / 1e12, 1),
+                           note="the same 40 layers from the 4-bit storage: M = 1 four launches per layer, M = 512 seven "
+                                "patch_gemm4_ex launches with the workspace; consecutive layers are timed in alternation (a "
+                                "layer's 4-bit weights alone would stay in the last-level cache) and half of the pair counts")
+    return dict(layers=40, launches_per_layer=4, packed_GB=round(packed_bytes / 1e9, 3), dense_GB=round(dense_bytes / 1e9, 3), **extra,
                 f_mean=round(f_mean, 4), fractions="per (layer, matrix): synth.matrix_fractions" if per_matrix else "one per layer, U[0, 1)",
                 rows=rows, per_layer=per_layer,
                 note="time = sum over the 40 layers of the layer's four launches (q/k/v fused, o, gate/up fused, down), each layer "
@@ -703,7 +742,7 @@ def main():
 
     # ------------------------------------------------------------------ 13B decoder stack
     if "stack" not in skip:
-        out["stack_13b"] = stack_13b(torch, B, synth, dev, stream, timed, t)
+        out["stack_13b"] = stack_13b(torch, B, synth, dev, stream, timed, t, q4="q4" not in skip)
         if "alloc" not in skip:
             out["stack_13b_per_matrix"] = stack_13b(torch, B, synth, dev, stream, timed, t, per_matrix=True)
 
