@@ -62,21 +62,30 @@ __device__ __forceinline__ uint32_t q4_code(uint16_t w_bits, float s) {
     return (uint32_t)((int)r) & 0xFu;
 }
 
-// 8 codes of a dword -> 8 bf16 values bf16(q s), element e from bits [4e+3 : 4e].  q s is exact in fp32 (4 x 8 bits);
-// the conversion of a float pair to bf16 rounds to nearest, ties to even (v_cvt_pk_bf16_f32).
+// 8 codes of a dword -> 8 bf16 values bf16(q s), element e from bits [4e+3 : 4e].  v_cvt_off_f32_i4 turns the low nibble
+// of a byte (selected by SDWA; the odd nibbles come from the dword shifted by 4) into the float q / 16 in one
+// instruction - a bit-field extract and an integer conversion otherwise; q / 16 times 16 s is q s, exact in fp32
+// (4 x 8 bits), and the conversion of a float pair to bf16 rounds to nearest, ties to even (v_cvt_pk_bf16_f32).
 typedef __bf16 q4_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float q4_f32x2 __attribute__((ext_vector_type(2)));
+#define PATCH_Q4_NIBBLE(dst, src, byte) \
+    asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_" #byte : "=v"(dst) : "v"(src))
 __device__ __forceinline__ q4_u32x4 q4_dequant8(uint32_t codes, float s) {
+    const float s16 = s * 16.0f;
+    const uint32_t odd = codes >> 4;
+    float lo[4], hi[4];
+    PATCH_Q4_NIBBLE(lo[0], codes, 0); PATCH_Q4_NIBBLE(lo[1], codes, 1); PATCH_Q4_NIBBLE(lo[2], codes, 2); PATCH_Q4_NIBBLE(lo[3], codes, 3);
+    PATCH_Q4_NIBBLE(hi[0], odd, 0); PATCH_Q4_NIBBLE(hi[1], odd, 1); PATCH_Q4_NIBBLE(hi[2], odd, 2); PATCH_Q4_NIBBLE(hi[3], odd, 3);
     q4_u32x4 out;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int q0 = __builtin_amdgcn_sbfe((int)codes, 8 * p, 4), q1 = __builtin_amdgcn_sbfe((int)codes, 8 * p + 4, 4);
-        const q4_f32x2 f = {(float)q0 * s, (float)q1 * s};
+        const q4_f32x2 f = {lo[p] * s16, hi[p] * s16};
         const q4_bf16x2 r = __builtin_convertvector(f, q4_bf16x2);
         out[p] = *reinterpret_cast<const uint32_t*>(&r);
     }
     return out;
 }
+#undef PATCH_Q4_NIBBLE
 
 __device__ __forceinline__ bool q4_nonzero(uint16_t h) { return (h & 0x7FFFu) != 0; }
 
