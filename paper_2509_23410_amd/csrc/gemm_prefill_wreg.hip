@@ -793,8 +793,8 @@ int prefill_wreg_split(const GemmArgs& a, int requested) {
 // A launch whose tile count is a little more than a multiple of the CU count ends with a part-filled round that
 // lasts as long as a full one.  With a workspace the last `tail` tiles (at most half a round) are cut into K slices
 // that fill the chip once: returns the slice count (1 = no such split) and sets *tail.  It pays when the part of a
-// round it saves outweighs writing and re-reading the partial tiles (an estimate from measured rates: 1.3 us per
-// step, 3 TB/s for the partials, 8 us for the two extra launches).
+// round it saves outweighs writing and re-reading the partial tiles (an estimate from measured rates: 0.9 - 1.25 us
+// per step depending on how full the chip is, 3 TB/s for the partials, 8 us for the two extra launches).
 int prefill_wreg_tail(const GemmArgs& a, int* tail) {
     return prefill_wreg_tail_of((int)(((a.N + kWrBN - 1) / kWrBN) * ((a.M + kWrBM - 1) / kWrBM)), a, tail);
 }
@@ -811,8 +811,11 @@ int prefill_wreg_tail_of(int tiles, const GemmArgs& a, int* tail) {
     if (s < 2) return 1;
     // after more than three full rounds the workgroups are far out of step and a part-filled round costs much less
     // than a full one (gate + up in one launch, 5.4 rounds: splitting the last 96 tiles measured 4 % slower)
-    const double round_us = 2.0 * a.Tk * 1.3 * (tiles / a.n_cus > 3 ? 0.4 : 1.0);
-    const double gain_us = round_us * (1.0 - 1.0 / s);
+    // a K-step costs 0.9 us on a nearly empty chip and 1.25 us on a full one: the part-filled round is shorter than a
+    // full round to begin with, and its slices run on a fuller chip
+    const double fill = (double)t / a.n_cus, fill_s = (double)t * s / a.n_cus;
+    const double round_us = 2.0 * a.Tk * (0.9 + 0.35 * fill) * (tiles / a.n_cus > 3 ? 0.4 : 1.0);
+    const double gain_us = round_us - 2.0 * a.Tk / s * (0.9 + 0.35 * (fill_s < 1.0 ? fill_s : 1.0)) * (tiles / a.n_cus > 3 ? 0.4 : 1.0);
     const double cost_us = 2.0 * (double)t * s * per_slot / 3.0e6 + 8.0;
     if (gain_us <= cost_us) return 1;
     *tail = t;

@@ -895,7 +895,7 @@ def test_prefill_part_filled_last_round_is_split(dev):
     """270 output tiles on 256 compute units: with a workspace the last 14 tiles are cut into K slices of their own
     (partial tiles in workspace slots, summed by a third launch).  Sampled checks against the oracle, with and
     without the workspace; rows outside the tail tiles are bit-equal between the two."""
-    N, K, M, t = 2560, 2048, 6912 - 40, 128       # 10 feature blocks x 27 row blocks (the last one ragged)
+    N, K, M, t = 2560, 4096, 6912 - 40, 128       # 10 feature blocks x 27 row blocks (the last one ragged)
     c = synth.make_case("tail", N, K, M, t, 0.5, seed=31)
     p = Prepared(c, dev)
     need = B.patch_gemm_workspace_bytes(M, p.P, path=B.PATH_PREFILL)
@@ -919,7 +919,7 @@ def test_prefill_set_with_split_last_round(dev):
     """Two weights sharing X in one prefill launch whose 270 tiles end in a part-filled round: with a workspace the
     last tiles (of both weights) are split in K; every output against the oracle on samples, and equal to the
     unsplit set launch within rounding."""
-    K, M, t = 2048, 6912 - 40, 128
+    K, M, t = 4096, 6912 - 40, 128
     cases = [synth.make_case(f"tailset{i}", N, K, M, t, f, seed=33) for i, (N, f) in enumerate([(1280, 0.5), (1280, 0.8)])]
     X = cases[0].X
     preps = [Prepared(c, dev) for c in cases]
