@@ -315,8 +315,18 @@ def main():
         for _ in range(3):
             B.patch_pack(L["W_hat"], c.N, c.K, c.tile_map, t, stream).close()
         torch.cuda.synchronize()
-        out["pack"] = dict(shape=[c.N, c.K], ms=(time.time() - tp) / 3 * 1e3,
-                           note="patch_pack wall time incl. allocation and the status read-back")
+        pack_ms = (time.time() - tp) / 3 * 1e3
+        ts = time.time()
+        saved = L["P"].serialize(stream)
+        save_ms = (time.time() - ts) * 1e3
+        ts = time.time()
+        B.patch_deserialize(saved, stream).close()
+        load_ms = (time.time() - ts) * 1e3
+        out["pack"] = dict(shape=[c.N, c.K], ms=pack_ms, saved_MB=round(saved.size / 1e6, 2), serialize_ms=round(save_ms, 1),
+                           deserialize_ms=round(load_ms, 1),
+                           note="patch_pack wall time incl. allocation and the status read-back; patch_serialize / patch_deserialize "
+                                "to and from pageable host memory, incl. the checksum over every byte")
+        del saved
 
     # ------------------------------------------------------------------ prefill time against the 2:4 tile fraction (gate projection)
     if "sweep" not in skip:

@@ -279,6 +279,26 @@ patch_status patch_packed_tile_map(const patch_packed* P, uint8_t* tile_map, siz
 patch_status patch_packed_row_order(const patch_packed* P, int32_t* order, size_t cap, size_t* count);
 
 /*
+ * A packed weight saved to and loaded from HOST memory (this project's; no passage of the paper - Appendix A compresses
+ * once per weight and tile size, these calls keep the result): header (magic, layout number, tile, N, K, sizes,
+ * checksum), the tile map, then the payload exactly as it lies in device memory.  The byte order of the payload is the
+ * library's own; the layout number changes with it and patch_deserialize refuses any other number.
+ *   patch_serialized_bytes  size of the buffer patch_serialize fills (0 for NULL)
+ *   patch_serialize    buf: HOST, at least that many bytes (else PATCH_ERR_SIZE); copies on `stream` and waits for it
+ *   patch_deserialize  buf: HOST, as written by patch_serialize; checks magic, layout number, shape, sizes against the
+ *                      tile map, map entries (0 / 1) and the checksum (FNV-1a over map and payload: about a second per
+ *                      GB) before any device work - PATCH_ERR_ARG / PATCH_ERR_SHAPE / PATCH_ERR_SIZE (buffer shorter
+ *                      than its header says); rebuilds the tables and the launch order from the tile map as patch_pack
+ *                      does, allocates, copies the payload on `stream` and waits for it.  *out: caller frees with
+ *                      patch_free; it multiplies bit-identically to the handle that was saved.
+ * patch_serialized4_bytes / patch_serialize4 / patch_deserialize4: the same for the 4-bit storage below (payload, then
+ * the scales; its own magic).
+ */
+size_t patch_serialized_bytes(const patch_packed* P);
+patch_status patch_serialize(const patch_packed* P, void* buf, size_t bytes, void* stream);
+patch_status patch_deserialize(const void* buf, size_t bytes, void* stream, patch_packed** out);
+
+/*
  * 4-bit weight-only storage of the pruned weight and its decode-shaped product (Section 5.2, "Quantization": the
  * hybrid-sparse model composed with 4-bit weight-only quantization; its table counts 4 bits per element of a dense tile
  * and 2 x 4 + 4 bits per group of four of a 2:4 tile).  The paper names no quantizer; this library's is symmetric with
@@ -323,6 +343,9 @@ patch_status patch_pack_from4(const patch_packed4* P4, void* stream, patch_packe
 size_t patch_packed4_bytes(const patch_packed4* P);
 patch_status patch_packed4_dims(const patch_packed4* P, int64_t* N, int64_t* K, int* tile, int64_t* n_sparse_tiles);
 void patch_free4(patch_packed4* P);
+size_t patch_serialized4_bytes(const patch_packed4* P);
+patch_status patch_serialize4(const patch_packed4* P, void* buf, size_t bytes, void* stream);
+patch_status patch_deserialize4(const void* buf, size_t bytes, void* stream, patch_packed4** out);
 
 /*
  * Measurement probes (this project's; no passage of the paper): kernels that run nothing of the method, for the

@@ -23,7 +23,8 @@ EXPORTS = [
     "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
     "patch_pack4", "patch_pack_from4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
-    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_gemm4_ex", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
+    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_gemm4_ex",
+    "patch_serialized_bytes", "patch_serialize", "patch_deserialize", "patch_serialized4_bytes", "patch_serialize4", "patch_deserialize4", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
 
@@ -116,6 +117,13 @@ def lib() -> ctypes.CDLL:
         L.patch_packed4_dims.restype = ci
         L.patch_free4.argtypes = [vp]
         L.patch_free4.restype = None
+        for sfx in ("", "4"):
+            getattr(L, f"patch_serialized{sfx}_bytes").argtypes = [vp]
+            getattr(L, f"patch_serialized{sfx}_bytes").restype = sz
+            getattr(L, f"patch_serialize{sfx}").argtypes = [vp, vp, sz, vp]
+            getattr(L, f"patch_serialize{sfx}").restype = ci
+            getattr(L, f"patch_deserialize{sfx}").argtypes = [vp, sz, vp, ctypes.POINTER(vp)]
+            getattr(L, f"patch_deserialize{sfx}").restype = ci
         L.patch_free.argtypes = [vp]
         L.patch_free.restype = None
         L.patch_strerror.argtypes = [ci]
@@ -196,6 +204,12 @@ class Packed:
         _check(lib().patch_packed_dims(self.handle, ctypes.byref(N), ctypes.byref(K), ctypes.byref(t), ctypes.byref(ns)),
                "patch_packed_dims")
         return int(N.value), int(K.value), int(t.value), int(ns.value)
+
+    def serialize(self, stream: int = 0) -> np.ndarray:
+        """The packed weight as host bytes (header, tile map, device payload); patch_deserialize loads it again."""
+        buf = np.empty(int(lib().patch_serialized_bytes(self.handle)), np.uint8)
+        _check(lib().patch_serialize(self.handle, buf.ctypes.data, buf.size, stream), "patch_serialize")
+        return buf
 
     def tile_map(self) -> np.ndarray:
         N, K, t, _ = self.dims()
@@ -380,10 +394,37 @@ class Packed4:
     def nbytes(self) -> int:
         return int(lib().patch_packed4_bytes(self.handle))
 
+    def serialize(self, stream: int = 0) -> np.ndarray:
+        """The 4-bit storage as host bytes (header, tile map, codes and positions, scales); patch_deserialize4 loads it."""
+        buf = np.empty(int(lib().patch_serialized4_bytes(self.handle)), np.uint8)
+        _check(lib().patch_serialize4(self.handle, buf.ctypes.data, buf.size, stream), "patch_serialize4")
+        return buf
+
     def dims(self):
         N, K, t, ns = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int64()
         _check(lib().patch_packed4_dims(self.handle, ctypes.byref(N), ctypes.byref(K), ctypes.byref(t), ctypes.byref(ns)), "patch_packed4_dims")
         return int(N.value), int(K.value), int(t.value), int(ns.value)
+
+
+def _host_bytes(buf) -> np.ndarray:
+    a = np.ascontiguousarray(np.frombuffer(buf, np.uint8) if isinstance(buf, (bytes, bytearray, memoryview)) else buf)
+    if a.dtype != np.uint8:
+        raise PatchError(ERR_ARG, "a saved weight is a uint8 buffer")
+    return a
+
+
+def patch_deserialize(buf, stream: int = 0) -> Packed:
+    a = _host_bytes(buf)
+    h = ctypes.c_void_p(0)
+    _check(lib().patch_deserialize(a.ctypes.data, a.size, stream, ctypes.byref(h)), "patch_deserialize")
+    return Packed(h.value)
+
+
+def patch_deserialize4(buf, stream: int = 0) -> "Packed4":
+    a = _host_bytes(buf)
+    h = ctypes.c_void_p(0)
+    _check(lib().patch_deserialize4(a.ctypes.data, a.size, stream, ctypes.byref(h)), "patch_deserialize4")
+    return Packed4(h.value)
 
 
 def patch_pack4(W_hat, N: int, K: int, tile_map, tile: int, stream: int = 0) -> Packed4:

@@ -14,6 +14,7 @@
 #include "../../include/patch.h"
 #include "kernels.h"
 #include "layout.h"
+#include "saved.h"
 
 using namespace patch;
 
@@ -207,14 +208,10 @@ void patch_free(patch_packed* P) {
     delete P;
 }
 
-patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
-                        patch_packed** out) {
-    if (!W_hat || !tile_map || !out) return PATCH_ERR_ARG;
-    patch_status st = check_shape(N, K, tile);
-    if (st != PATCH_OK) return st;
-    if (!aligned16(W_hat)) return PATCH_ERR_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-
+// The host side of a packed weight (tile map, offset / type table, tile-row pairs) and its device buffers, the table
+// uploaded on `s`, the payload not yet written.  Shared by patch_pack (which fills the payload from the matrix) and
+// patch_deserialize (which copies a saved one).
+static patch_status new_packed(int64_t N, int64_t K, const uint8_t* tile_map, int tile, hipStream_t s, patch_packed** out) {
     patch_packed* P = new (std::nothrow) patch_packed();
     if (!P) return PATCH_ERR_ALLOC;
     P->N = N; P->K = K; P->tile = tile;
@@ -248,29 +245,55 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     P->device = dev;
     P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-    int* d_err = nullptr;
     // a kilobyte of slack behind the payload keeps any over-read of the last tile inside the allocation
-    bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kZeroPad) == hipSuccess &&
-              hipMalloc(&P->d_table, (T + P->pairs.size()) * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&d_err, sizeof(int)) == hipSuccess;
+    const bool ok = hipMalloc(&P->d_payload, P->payload_bytes + kZeroPad) == hipSuccess &&
+                    hipMalloc(&P->d_table, (T + P->pairs.size()) * sizeof(uint32_t)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
-        if (d_err) (void)hipFree(d_err);
         patch_free(P);
         return PATCH_ERR_ALLOC;
     }
     hipError_t e = hipMemcpyAsync(P->d_table, P->table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
         e = hipMemcpyAsync(P->d_table + T, P->pairs.data(), P->pairs.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
     if (e == hipSuccess) e = hipMemsetAsync(P->d_payload + P->payload_bytes, 0, kZeroPad, s);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipStreamSynchronize(s);
+        patch_free(P);
+        return PATCH_ERR_HIP;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream,
+                        patch_packed** out) {
+    if (!W_hat || !tile_map || !out) return PATCH_ERR_ARG;
+    patch_status st = check_shape(N, K, tile);
+    if (st != PATCH_OK) return st;
+    if (!aligned16(W_hat)) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    patch_packed* P = nullptr;
+    st = new_packed(N, K, tile_map, tile, s, &P);
+    if (st != PATCH_OK) return st;
+    const size_t T = (size_t)P->Tn * (size_t)P->Tk;
+    int* d_err = nullptr;
+    if (hipMalloc(&d_err, sizeof(int)) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(s);
+        patch_free(P);
+        return PATCH_ERR_ALLOC;
+    }
+    hipError_t e = hipMemsetAsync(d_err, 0, sizeof(int), s);
     if (e == hipSuccess) {
         launch_pack(static_cast<const uint16_t*>(W_hat), K, P->d_table, (int)T, P->Tk, tile, P->d_payload, d_err, s);
         e = hipGetLastError();
     }
     int h_err = 0;
     if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    const hipError_t e_sync = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = e_sync;
     (void)hipFree(d_err);
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
@@ -280,6 +303,72 @@ patch_status patch_pack(const void* W_hat, int64_t N, int64_t K, const uint8_t* 
     if (h_err) {
         patch_free(P);
         return PATCH_ERR_NOT_24;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+// ---- a packed weight saved to and loaded from host memory (saved.h)
+size_t patch_serialized_bytes(const patch_packed* P) {
+    if (!P) return 0;
+    return saved_round(sizeof(SavedHeader)) + saved_round(P->tile_map.size()) + P->payload_bytes;
+}
+
+patch_status patch_serialize(const patch_packed* P, void* buf, size_t bytes, void* stream) {
+    if (!P || !buf) return PATCH_ERR_ARG;
+    if (bytes < patch_serialized_bytes(P)) return PATCH_ERR_SIZE;
+    uint8_t* b = static_cast<uint8_t*>(buf);
+    const size_t map_at = saved_round(sizeof(SavedHeader)), pay_at = map_at + saved_round(P->tile_map.size());
+    memset(b, 0, pay_at);
+    memcpy(b + map_at, P->tile_map.data(), P->tile_map.size());
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(b + pay_at, P->d_payload, P->payload_bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    SavedHeader h = {};
+    memcpy(h.magic, kSavedMagic16, 8);
+    h.layout = kSavedLayout;
+    h.tile = (uint32_t)P->tile;
+    h.N = P->N;
+    h.K = P->K;
+    h.map_bytes = P->tile_map.size();
+    h.payload_bytes = P->payload_bytes;
+    h.checksum = fnv1a(b + pay_at, P->payload_bytes, fnv1a(b + map_at, P->tile_map.size(), kFnvBasis));
+    memcpy(b, &h, sizeof(h));
+    return PATCH_OK;
+}
+
+patch_status patch_deserialize(const void* buf, size_t bytes, void* stream, patch_packed** out) {
+    if (!buf || !out) return PATCH_ERR_ARG;
+    if (bytes < saved_round(sizeof(SavedHeader))) return PATCH_ERR_SIZE;
+    const uint8_t* b = static_cast<const uint8_t*>(buf);
+    SavedHeader h;
+    memcpy(&h, b, sizeof(h));
+    if (memcmp(h.magic, kSavedMagic16, 8) != 0 || h.layout != kSavedLayout) return PATCH_ERR_ARG;
+    const patch_status shape = check_shape(h.N, h.K, (int)h.tile);
+    if (shape != PATCH_OK) return shape;
+    const uint64_t T = (uint64_t)(h.N / h.tile) * (uint64_t)(h.K / h.tile);
+    if (h.map_bytes != T || h.aux_bytes != 0) return PATCH_ERR_ARG;
+    const size_t map_at = saved_round(sizeof(SavedHeader)), pay_at = map_at + saved_round((size_t)T);
+    if (bytes < pay_at || h.payload_bytes > bytes - pay_at) return PATCH_ERR_SIZE;
+    for (uint64_t i = 0; i < T; ++i)
+        if (b[map_at + i] > 1) return PATCH_ERR_ARG;
+    if (fnv1a(b + pay_at, (size_t)h.payload_bytes, fnv1a(b + map_at, (size_t)T, kFnvBasis)) != h.checksum) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    patch_packed* P = nullptr;
+    const patch_status st = new_packed(h.N, h.K, b + map_at, (int)h.tile, s, &P);
+    if (st != PATCH_OK) return st;
+    if (P->payload_bytes != h.payload_bytes) {   // the map decides the size: a header that disagrees is not ours
+        (void)hipStreamSynchronize(s);
+        patch_free(P);
+        return PATCH_ERR_ARG;
+    }
+    hipError_t e = hipMemcpyAsync(P->d_payload, b + pay_at, P->payload_bytes, hipMemcpyHostToDevice, s);
+    const hipError_t e_sync = hipStreamSynchronize(s);   // the caller's buffer is free to go when the call returns
+    if (e == hipSuccess) e = e_sync;
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        patch_free(P);
+        return PATCH_ERR_HIP;
     }
     *out = P;
     return PATCH_OK;

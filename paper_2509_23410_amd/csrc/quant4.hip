@@ -24,6 +24,7 @@
 // patch_gemm4_ex), and any weight can be dequantized once and packed as bf16 (patch_pack_from4).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include <new>
 #include <vector>
@@ -33,6 +34,7 @@
 #include "kernels.h"
 #include "layout.h"
 #include "prefill_parts.h"
+#include "saved.h"
 
 namespace patch {
 
@@ -792,11 +794,9 @@ void patch_free4(patch_packed4* P) {
     delete P;
 }
 
-patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream, patch_packed4** out) {
-    if (!W_hat || !tile_map || !out || N <= 0 || K <= 0) return PATCH_ERR_ARG;
-    if ((tile != 64 && tile != 128) || N % tile || K % tile || N / tile > (1 << 20) || K / tile > (1 << 20)) return PATCH_ERR_SHAPE;
-    if (!q4_aligned16(W_hat)) return PATCH_ERR_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+// The host side of a 4-bit packed weight and its device buffers: table uploaded on `s`, payload zeroed (its alignment
+// padding reads as zero), codes and scales not yet written.  Shared by patch_pack4 and patch_deserialize4.
+static patch_status new_packed4(int64_t N, int64_t K, const uint8_t* tile_map, int tile, hipStream_t s, patch_packed4** out) {
     patch_packed4* P = new (std::nothrow) patch_packed4();
     if (!P) return PATCH_ERR_ALLOC;
     P->N = N; P->K = K; P->tile = tile;
@@ -823,18 +823,42 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
         return PATCH_ERR_HIP;
     }
     P->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    int* d_err = nullptr;
     const bool ok = hipMalloc(&P->d_payload, P->payload_bytes) == hipSuccess && hipMalloc(&P->d_table, T * sizeof(uint32_t)) == hipSuccess &&
-                    hipMalloc(&P->d_scales, (size_t)N * P->Tk * sizeof(uint16_t)) == hipSuccess && hipMalloc(&d_err, sizeof(int)) == hipSuccess;
+                    hipMalloc(&P->d_scales, (size_t)N * P->Tk * sizeof(uint16_t)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
-        if (d_err) (void)hipFree(d_err);
         patch_free4(P);
         return PATCH_ERR_ALLOC;
     }
     hipError_t e = hipMemcpyAsync(P->d_table, table.data(), T * sizeof(uint32_t), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMemsetAsync(d_err, 0, sizeof(int), s);
-    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload, 0, P->payload_bytes, s);   // alignment padding reads as zero
+    if (e == hipSuccess) e = hipMemsetAsync(P->d_payload, 0, P->payload_bytes, s);
+    const hipError_t e_sync = hipStreamSynchronize(s);   // the host table goes out of scope here
+    if (e == hipSuccess) e = e_sync;
+    if (e != hipSuccess) {
+        patch_note_hip_error((int)e);
+        patch_free4(P);
+        return PATCH_ERR_HIP;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t* tile_map, int tile, void* stream, patch_packed4** out) {
+    if (!W_hat || !tile_map || !out || N <= 0 || K <= 0) return PATCH_ERR_ARG;
+    if ((tile != 64 && tile != 128) || N % tile || K % tile || N / tile > (1 << 20) || K / tile > (1 << 20)) return PATCH_ERR_SHAPE;
+    if (!q4_aligned16(W_hat)) return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    patch_packed4* P = nullptr;
+    const patch_status st = new_packed4(N, K, tile_map, tile, s, &P);
+    if (st != PATCH_OK) return st;
+    const size_t T = (size_t)P->Tn * (size_t)P->Tk;
+    int* d_err = nullptr;
+    if (hipMalloc(&d_err, sizeof(int)) != hipSuccess) {
+        (void)hipGetLastError();
+        patch_free4(P);
+        return PATCH_ERR_ALLOC;
+    }
+    hipError_t e = hipMemsetAsync(d_err, 0, sizeof(int), s);
     if (e == hipSuccess) {
         hipLaunchKernelGGL(pack4_kernel, dim3((unsigned)T), dim3(256), 0, s, static_cast<const uint16_t*>(W_hat), K, P->d_table, P->Tk, tile,
                            P->d_payload, P->d_scales, d_err);
@@ -842,7 +866,8 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
     }
     int h_err = 0;
     if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);   // also keeps the host table alive until the copy is done
+    const hipError_t e_sync = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = e_sync;
     (void)hipFree(d_err);
     if (e != hipSuccess) {
         patch_note_hip_error((int)e);
@@ -852,6 +877,84 @@ patch_status patch_pack4(const void* W_hat, int64_t N, int64_t K, const uint8_t*
     if (h_err) {
         patch_free4(P);
         return PATCH_ERR_NOT_24;
+    }
+    *out = P;
+    return PATCH_OK;
+}
+
+// ---- the 4-bit storage saved to and loaded from host memory (saved.h): header, tile map, codes and positions, scales
+size_t patch_serialized4_bytes(const patch_packed4* P) {
+    if (!P) return 0;
+    return saved_round(sizeof(SavedHeader)) + saved_round(P->tile_map.size()) + saved_round(P->payload_bytes) +
+           (size_t)P->N * P->Tk * sizeof(uint16_t);
+}
+
+patch_status patch_serialize4(const patch_packed4* P, void* buf, size_t bytes, void* stream) {
+    if (!P || !buf) return PATCH_ERR_ARG;
+    if (bytes < patch_serialized4_bytes(P)) return PATCH_ERR_SIZE;
+    uint8_t* b = static_cast<uint8_t*>(buf);
+    const size_t scales_bytes = (size_t)P->N * P->Tk * sizeof(uint16_t);
+    const size_t map_at = saved_round(sizeof(SavedHeader)), pay_at = map_at + saved_round(P->tile_map.size());
+    const size_t sc_at = pay_at + saved_round(P->payload_bytes);
+    memset(b, 0, pay_at);
+    memset(b + pay_at + P->payload_bytes, 0, sc_at - pay_at - P->payload_bytes);
+    memcpy(b + map_at, P->tile_map.data(), P->tile_map.size());
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(b + pay_at, P->d_payload, P->payload_bytes, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(b + sc_at, P->d_scales, scales_bytes, hipMemcpyDeviceToHost, s);
+    const hipError_t e_sync = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = e_sync;
+    if (e != hipSuccess) { patch_note_hip_error((int)e); return PATCH_ERR_HIP; }
+    SavedHeader h = {};
+    memcpy(h.magic, kSavedMagic4, 8);
+    h.layout = kSavedLayout;
+    h.tile = (uint32_t)P->tile;
+    h.N = P->N;
+    h.K = P->K;
+    h.map_bytes = P->tile_map.size();
+    h.payload_bytes = P->payload_bytes;
+    h.aux_bytes = scales_bytes;
+    h.checksum = fnv1a(b + sc_at, scales_bytes, fnv1a(b + pay_at, P->payload_bytes, fnv1a(b + map_at, P->tile_map.size(), kFnvBasis)));
+    memcpy(b, &h, sizeof(h));
+    return PATCH_OK;
+}
+
+patch_status patch_deserialize4(const void* buf, size_t bytes, void* stream, patch_packed4** out) {
+    if (!buf || !out) return PATCH_ERR_ARG;
+    if (bytes < saved_round(sizeof(SavedHeader))) return PATCH_ERR_SIZE;
+    const uint8_t* b = static_cast<const uint8_t*>(buf);
+    SavedHeader h;
+    memcpy(&h, b, sizeof(h));
+    if (memcmp(h.magic, kSavedMagic4, 8) != 0 || h.layout != kSavedLayout) return PATCH_ERR_ARG;
+    if (h.N <= 0 || h.K <= 0) return PATCH_ERR_ARG;
+    if ((h.tile != 64 && h.tile != 128) || h.N % h.tile || h.K % h.tile || h.N / h.tile > (1 << 20) || h.K / h.tile > (1 << 20))
+        return PATCH_ERR_SHAPE;
+    const uint64_t Tk = (uint64_t)(h.K / h.tile), T = (uint64_t)(h.N / h.tile) * Tk;
+    if (h.map_bytes != T || h.aux_bytes != (uint64_t)h.N * Tk * sizeof(uint16_t)) return PATCH_ERR_ARG;
+    const size_t map_at = saved_round(sizeof(SavedHeader)), pay_at = map_at + saved_round((size_t)T);
+    if (bytes < pay_at || h.payload_bytes > bytes - pay_at) return PATCH_ERR_SIZE;
+    const size_t sc_at = pay_at + saved_round((size_t)h.payload_bytes);
+    if (bytes < sc_at || h.aux_bytes > bytes - sc_at) return PATCH_ERR_SIZE;
+    for (uint64_t i = 0; i < T; ++i)
+        if (b[map_at + i] > 1) return PATCH_ERR_ARG;
+    if (fnv1a(b + sc_at, (size_t)h.aux_bytes, fnv1a(b + pay_at, (size_t)h.payload_bytes, fnv1a(b + map_at, (size_t)T, kFnvBasis))) != h.checksum)
+        return PATCH_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    patch_packed4* P = nullptr;
+    const patch_status st = new_packed4(h.N, h.K, b + map_at, (int)h.tile, s, &P);
+    if (st != PATCH_OK) return st;
+    if (P->payload_bytes != h.payload_bytes) {   // the map decides the size: a header that disagrees is not ours
+        patch_free4(P);
+        return PATCH_ERR_ARG;
+    }
+    hipError_t e = hipMemcpyAsync(P->d_payload, b + pay_at, P->payload_bytes, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(P->d_scales, b + sc_at, (size_t)h.aux_bytes, hipMemcpyHostToDevice, s);
+    const hipError_t e_sync = hipStreamSynchronize(s);   // the caller's buffer is free to go when the call returns
+    if (e == hipSuccess) e = e_sync;
+    if (e != hipSuccess) {
+        patch_note_hip_error((int)e);
+        patch_free4(P);
+        return PATCH_ERR_HIP;
     }
     *out = P;
     return PATCH_OK;

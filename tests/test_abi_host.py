@@ -1,6 +1,7 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
 declares, and rejects bad arguments before any device work."""
 import ctypes
+import struct
 import os
 import re
 
@@ -93,6 +94,62 @@ def test_argument_errors_without_device():
         B.patch_pack4(fake, 128, 128, np.ones(3, np.uint8), 64)
     with pytest.raises(B.PatchError):
         B.patch_pack(fake, 128, 128, np.ones(3, np.uint8), 64)
+
+
+def _fnv1a(data: bytes, h: int = 14695981039346656037) -> int:
+    for b in data:
+        h = ((h ^ b) * 1099511628211) & 0xFFFFFFFFFFFFFFFF
+    return h
+
+
+def _saved(magic=b"PATCHPK\0", layout=1, tile=64, N=128, K=128, map_bytes=4, payload=b"\0" * 4 * 8192, aux=b"", tm=b"\1\1\1\1",
+           checksum=None, claim_payload=None):
+    """A saved-weight buffer written by hand from the documented format: 64-byte header, tile map, payload (and the
+    scales of the 4-bit storage), each part at a multiple of 64 bytes."""
+    pad = lambda b: b + b"\0" * (-len(b) % 64)
+    body = pad(tm) + (pad(payload) if aux else payload) + aux
+    cs = _fnv1a(aux, _fnv1a(payload, _fnv1a(tm))) if checksum is None else checksum
+    head = struct.pack("<8sIIqqQQQQ", magic, layout, tile, N, K, map_bytes, len(payload) if claim_payload is None else claim_payload,
+                       len(aux), cs)
+    assert len(head) == 64
+    return np.frombuffer(head + body, np.uint8).copy()
+
+
+def test_saved_weight_is_checked_on_the_host():
+    """patch_deserialize / patch_deserialize4 refuse, before any device work, everything that is not a buffer the
+    library wrote: wrong magic or layout number, impossible shapes, sizes that disagree with the tile map or with the
+    buffer, map entries other than 0 / 1, a checksum that does not match."""
+    L = B.lib()
+    out = ctypes.c_void_p(0)
+    assert L.patch_serialized_bytes(0) == 0 and L.patch_serialized4_bytes(0) == 0
+    fake = 0x1000
+    assert L.patch_serialize(0, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_serialize(fake, 0, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_serialize4(0, fake, 1 << 20, 0) == B.ERR_ARG
+    for name, magic in (("patch_deserialize", b"PATCHPK\0"), ("patch_deserialize4", b"PATCHQ4\0")):
+        fn = getattr(L, name)
+        other = b"PATCHQ4\0" if name == "patch_deserialize" else b"PATCHPK\0"
+        aux = b"\0" * (128 * 2 * 2) if name == "patch_deserialize4" else b""
+        call = lambda a, n=None: fn(a.ctypes.data, a.size if n is None else n, 0, ctypes.byref(out))
+        assert fn(0, 64, 0, ctypes.byref(out)) == B.ERR_ARG
+        good = _saved(magic=magic, aux=aux)
+        assert fn(good.ctypes.data, good.size, 0, None) == B.ERR_ARG
+        assert call(good, 63) == B.ERR_SIZE                                       # shorter than a header
+        assert call(_saved(magic=other, aux=aux)) == B.ERR_ARG                     # the other storage's buffer
+        assert call(_saved(magic=b"NOTPATCH", aux=aux)) == B.ERR_ARG
+        assert call(_saved(magic=magic, layout=2, aux=aux)) == B.ERR_ARG          # written by another layout
+        assert call(_saved(magic=magic, tile=32, aux=aux)) == B.ERR_SHAPE
+        assert call(_saved(magic=magic, N=100, aux=aux)) == B.ERR_SHAPE
+        assert call(_saved(magic=magic, N=-128, aux=aux)) == B.ERR_ARG
+        assert call(_saved(magic=magic, map_bytes=5, aux=aux)) == B.ERR_ARG       # not (N / tile) (K / tile)
+        assert call(good, good.size - 1) == B.ERR_SIZE                            # truncated
+        assert call(_saved(magic=magic, aux=aux, claim_payload=1 << 40)) == B.ERR_SIZE
+        assert call(_saved(magic=magic, aux=aux, tm=b"\1\2\1\1")) == B.ERR_ARG    # a map entry that is neither 0 nor 1
+        assert call(_saved(magic=magic, aux=aux, checksum=12345)) == B.ERR_ARG
+        flipped = good.copy()
+        flipped[-1] ^= 1
+        assert call(flipped) == B.ERR_ARG                                         # one bit of the last byte
+    assert call is not None and out.value is None
 
 
 def test_tune_table_host_logic():

@@ -504,6 +504,38 @@ def _blocks_of_128_rows(dev, t, N, K, M, f, variant):
     p.P.close()
 
 
+@pytest.mark.parametrize("t,N,K,f", [(128, 640, 512, 0.5), (64, 320, 448, 0.4), (128, 384, 256, 1.0)])
+def test_saved_weight_round_trip(dev, t, N, K, f):
+    """patch_serialize -> patch_deserialize: the loaded handle has the saved one's dimensions, tile map, launch order
+    and canonical export (bit-equal to the oracle's pack), multiplies bit-identically on the decode and the prefill
+    path, and the oracle confirms the product; a buffer with one payload bit flipped is refused."""
+    c = synth.make_case("saved", N, K, 300, t, f, seed=77)
+    p = Prepared(c, dev)
+    buf = p.P.serialize(stream())
+    assert buf.size == 64 + -(-c.tile_map.size // 64) * 64 + p.P.nbytes
+    Ys = {M: p.gemm(c.X[:M]) for M in (1, 16, 40, 300)}
+    order, dims = p.P.row_order(), p.P.dims()
+    p.P.close()                                    # the saved bytes are all that is left
+    p.P = B.patch_deserialize(buf, stream())
+    assert p.P.dims() == dims and np.array_equal(p.P.tile_map(), c.tile_map) and np.array_equal(p.P.row_order(), order)
+    vals, meta = B.patch_export_canonical(p.P)
+    assert np.array_equal(vals, p.vals_o) and np.array_equal(meta, p.meta_o)
+    for M, Y in Ys.items():
+        assert np.array_equal(p.gemm(c.X[:M]), Y), f"M={M}: the loaded weight multiplies differently"
+    p.check(c.X, p.gemm(c.X), None, "loaded weight")
+    again = p.P.serialize(stream())
+    assert np.array_equal(again, buf), "saving the loaded weight gives other bytes"
+    bad = buf.copy()
+    bad[buf.size // 2] ^= 4
+    with pytest.raises(B.PatchError) as e:
+        B.patch_deserialize(bad, stream())
+    assert e.value.status == B.ERR_ARG
+    with pytest.raises(B.PatchError) as e:
+        B.patch_deserialize(buf[:-1], stream())
+    assert e.value.status == B.ERR_SIZE
+    p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)

@@ -318,3 +318,35 @@ def test_full_size_decode_shape_sampled(dev):
         assert (d <= bound).all()
         assert np.linalg.norm(got - ref) <= 2e-5 * np.linalg.norm(ref)
     p.P.close()
+
+
+@pytest.mark.parametrize("t,N,K,f", [(128, 384, 640, 0.5), (64, 192, 320, 0.4)])
+def test_saved_4_bit_weight_round_trip(dev, t, N, K, f):
+    """patch_serialize4 -> patch_deserialize4: codes, scales and dequantized weight of the loaded handle are the
+    oracle's, its products are bit-equal to the saved handle's, a flipped bit is refused."""
+    c = synth.make_case("saved4", N, K, 130, t, f, seed=78)
+    p = Prepared4(c, dev)
+    buf = p.P.serialize(stream())
+    Ys = {M: p.gemm(c.X[:M]) for M in (1, 20, 130)}
+    ws = torch.empty(4 * 130 * N, device=dev, dtype=torch.float32)
+    Yw = p.gemm(c.X, workspace=ws)
+    dims, nbytes = p.P.dims(), p.P.nbytes
+    p.P.close()
+    p.P = B.patch_deserialize4(buf, stream())
+    assert p.P.dims() == dims and p.P.nbytes == nbytes
+    W_deq, codes, scales = p.unpack()
+    assert np.array_equal(codes, p.codes_o) and np.array_equal(scales, p.scales_o)
+    assert np.array_equal(W_deq, p.W_deq_o)
+    for M, Y in Ys.items():
+        assert np.array_equal(p.gemm(c.X[:M]), Y), f"M={M}: the loaded weight multiplies differently"
+    assert np.array_equal(p.gemm(c.X, workspace=ws), Yw)
+    assert np.array_equal(p.P.serialize(stream()), buf)
+    bad = buf.copy()
+    bad[-3] ^= 16                                  # inside the scales
+    with pytest.raises(B.PatchError) as e:
+        B.patch_deserialize4(bad, stream())
+    assert e.value.status == B.ERR_ARG
+    with pytest.raises(B.PatchError) as e:
+        B.patch_deserialize(buf, stream())          # the other storage's loader
+    assert e.value.status == B.ERR_ARG
+    p.P.close()
