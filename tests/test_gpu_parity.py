@@ -536,6 +536,54 @@ def test_saved_weight_round_trip(dev, t, N, K, f):
     p.P.close()
 
 
+def test_x_of_four_gigabytes(dev):
+    """The largest X the hand-scheduled prefill kernel takes (its lane offsets into X are 32 bits wide: M K 2 < 4 GB)
+    and the first size beyond, which must go to a kernel with 64-bit addresses.  X is a 4099-row block repeated (4099
+    does not divide the 262144 rows after which a 32-bit byte offset wraps, so a wrapped address reads another row):
+    every row of Y must be bit-equal to the row of the first period with the same X, and rows sampled at both ends, at
+    the wrap and at random are compared with the oracle."""
+    N, K, t, period = 256, 8192, 128, 4099
+    c = synth.make_case("x4g", N, K, period, t, 0.5, seed=61)
+    p = Prepared(c, dev)
+    Xs = to_dev_bf16(c.X, dev)
+    rng = np.random.default_rng(8)
+    for M, kw in ((262143, dict(path=B.PATH_PREFILL, variant=3)), (262145, dict(path=B.PATH_PREFILL, variant=3)), (262145, dict())):
+        print(f"X of {M * K * 2 / 2 ** 30:.3f} GiB, M={M} {kw}", flush=True)
+        idx = torch.arange(M, device=dev) % period
+        X = Xs[idx]
+        Y = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+        B.patch_gemm(X, M, p.P, Y, stream(), **kw)
+        torch.cuda.synchronize()
+        del X
+        assert torch.equal(Y, Y[:period][idx]), "rows with equal X differ: an address wrapped or a block was skipped"
+        rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(M - 130, M), np.arange(131072 - 4, 131072 + 4),
+                                         np.arange(262144 - 300, min(M, 262144 + 4)), rng.integers(0, M, 100)]))
+        rows = rows[rows < M]
+        Yr = Y[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        Xr = np.ascontiguousarray(c.X[rows % period])
+        check_elements(Yr, p.oracle_gemm(Xr), row_norms(Xr), p.wn, K, f"M={M} sampled rows")
+        del Y
+    p.P.close()
+
+
+@pytest.mark.parametrize("K", [16384, 16512])
+def test_longest_k_of_the_hand_scheduled_kernel(dev, K):
+    """K = 16384 is the longest the hand-scheduled prefill kernel takes (128 tiles along K: two table registers per
+    lane); K = 16512 must go to another kernel.  Full output against the oracle on every prefill variant, with and
+    without a K split, and on the decode path."""
+    N, M, t = 384, 300, 128
+    c = synth.make_case("longk", N, K, M, t, 0.5, seed=62)
+    p = Prepared(c, dev)
+    Yo = p.oracle_gemm(c.X)
+    ws = torch.empty(8 * M * N, device=dev, dtype=torch.float32)
+    for kw in (dict(), dict(workspace=ws), dict(path=B.PATH_PREFILL, variant=3), dict(path=B.PATH_PREFILL, variant=3, workspace=ws),
+               dict(path=B.PATH_PREFILL, variant=3, workspace=ws, split_k=7), dict(path=B.PATH_PREFILL, variant=5),
+               dict(path=B.PATH_PREFILL, variant=2), dict(path=B.PATH_DECODE), dict(path=B.PATH_DECODE, workspace=ws)):
+        print(f"K={K} " + str({k: v for k, v in kw.items() if k != 'workspace'}) + (" +workspace" if "workspace" in kw else ""), flush=True)
+        p.check(c.X, p.gemm(c.X, **kw), Yo, f"K={K}")
+    p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
