@@ -584,6 +584,54 @@ def test_longest_k_of_the_hand_scheduled_kernel(dev, K):
     p.P.close()
 
 
+def test_payload_beyond_four_gigabytes(dev):
+    """A packed weight whose payload is larger than 4 GB (tile offsets are stored in 256-byte granules, kernel addresses
+    are 64 bits wide): 2304 tile rows x 65 tile columns, a fifth of the tiles 2:4, 4.5 GB.  The weight is a block of
+    33 tile rows repeated (33 tile rows are not a divisor of 2^32 bytes, so a wrapped offset reads another row): every
+    column of Y must be bit-equal to the column of the first period with the same weight row, and sampled columns from
+    both ends, around the 4 GB mark and at random are compared with the oracle - on the decode kernel, the batched
+    decode kernel, the prefill kernels and after unpacking."""
+    t, Tn, Tk, per = 128, 2304, 65, 33
+    N, K, M = Tn * t, Tk * t, 300
+    c = synth.make_case("big_payload", per * t, K, M, t, 0.2, seed=63)
+    W_hat_s = oracle.apply_mask(c.W, c.tile_map, c.mask24, t)
+    vals_s, meta_s = oracle.pack(W_hat_s, c.tile_map, t)
+    ridx = torch.arange(N, device=dev) % (per * t)
+    W_hat = to_dev_bf16(W_hat_s, dev)[ridx]
+    tile_map = np.ascontiguousarray(c.tile_map[np.arange(Tn) % per])
+    P = B.patch_pack(W_hat, N, K, tile_map, t, stream())
+    assert P.nbytes > 2 ** 32, P.nbytes
+    back = torch.full((N, K), -1, device=dev, dtype=torch.int16).view(torch.bfloat16)
+    B.patch_unpack(P, back, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(back.view(torch.int16), W_hat.view(torch.int16)), "unpack differs from what was packed"
+    del back, W_hat
+    X = to_dev_bf16(c.X, dev)
+    rng = np.random.default_rng(9)
+    row_bytes = np.where(tile_map == 1, 2 * t * t, t * t + t * t // 8).sum(axis=1)
+    first_beyond = int(np.searchsorted(np.cumsum(row_bytes), 2 ** 32)) * t     # first feature whose tiles end past 4 GB
+    assert 0 < first_beyond < N - 130
+    cols = np.unique(np.concatenate([np.arange(0, 140), np.arange(N - 140, N), np.arange(first_beyond - 130, first_beyond + 130),
+                                     rng.integers(0, N, 200)]))
+    xn, wn = row_norms(c.X), row_norms(W_hat_s)
+    ws = torch.empty(2 * M * N, device=dev, dtype=torch.float32)
+    for rows, kw in ((1, dict()), (16, dict()), (48, dict()), (64, dict(workspace=ws)), (M, dict()), (M, dict(workspace=ws)),
+                     (M, dict(path=B.PATH_PREFILL, variant=5)), (M, dict(path=B.PATH_PREFILL, variant=2))):
+        print(f"payload {P.nbytes / 2 ** 30:.2f} GiB, M={rows} " + str({k: v for k, v in kw.items() if k != 'workspace'})
+              + (" +workspace" if "workspace" in kw else ""), flush=True)
+        Y = torch.full((rows, N), float("nan"), device=dev, dtype=torch.float32)
+        if "workspace" in kw:
+            ws.fill_(float("nan"))
+        B.patch_gemm(X, rows, P, Y, stream(), **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y[:, : per * t][:, ridx]), "columns with equal weight rows differ: an offset wrapped"
+        Yc = Y[:, torch.from_numpy(cols).to(dev)].cpu().numpy()
+        Yo = oracle.gemm(np.ascontiguousarray(c.X[:rows]), vals_s, meta_s, per * t, K, c.tile_map, t)[:, cols % (per * t)]
+        check_elements(Yc, Yo, xn[:rows], wn[cols % (per * t)], K, f"M={rows} sampled columns")
+        del Y
+    P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
