@@ -632,6 +632,39 @@ def test_payload_beyond_four_gigabytes(dev):
     P.close()
 
 
+def test_workspace_of_any_size_is_respected(dev):
+    """Whatever size the caller's workspace has - what patch_gemm_workspace_bytes asks for, 16 bytes less, half, one
+    slice, a page, 16 bytes - a launch writes nothing behind it (a guard region keeps its pattern) and the result is
+    the oracle's: a launch that cannot use the workspace as it is splits less or not at all."""
+    guard = 1 << 18
+    pattern = 0x7FC0BEEF
+    rng = np.random.default_rng(12)
+    for t, N, K, M, f in ((128, 640, 2048, 300, 0.5), (64, 448, 1600, 513, 0.5), (128, 1152, 768, 64, 1.0), (128, 256, 4096, 130, 0.0)):
+        c = synth.make_case("anyws", N, K, M, t, f, seed=71)
+        p = Prepared(c, dev)
+        Yo = p.oracle_gemm(c.X)
+        X = to_dev_bf16(c.X, dev)
+        xn = row_norms(c.X)
+        big = torch.empty(8 * M * N + guard, device=dev, dtype=torch.int32)
+        scheds = [dict(), dict(path=B.PATH_DECODE), dict(path=B.PATH_PREFILL), dict(path=B.PATH_PREFILL, variant=2, split_k=5),
+                  dict(path=B.PATH_PREFILL, variant=3, split_k=int(rng.integers(2, 9))), dict(path=B.PATH_PREFILL, variant=5, split_k=4),
+                  dict(path=B.PATH_PREFILL, variant=4), dict(path=B.PATH_PREFILL, variant=6, split_k=3), dict(path=B.PATH_DECODE, variant=4)]
+        for kw in scheds:
+            need = B.patch_gemm_workspace_bytes(M, p.P, **kw)
+            for nbytes in sorted({need, need - 16, need // 32 * 16, 8 * M * N * 4, 2 * M * N * 4, M * N * 4, 4096, 16}):
+                if nbytes <= 0:
+                    continue
+                n = nbytes // 4
+                big.fill_(pattern)
+                Y = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+                what = f"tile {t} {N}x{K} M={M} {kw} workspace of {nbytes} bytes (asked for: {need})"
+                B.patch_gemm(X, M, p.P, Y, stream(), workspace=big[:n].view(torch.float32), **kw)
+                torch.cuda.synchronize()
+                assert bool((big[n:] == pattern).all()), what + ": wrote behind the workspace"
+                check_elements(Y.cpu().numpy(), Yo, xn, p.wn, K, what)
+        p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)

@@ -350,3 +350,25 @@ def test_saved_4_bit_weight_round_trip(dev, t, N, K, f):
         B.patch_deserialize(buf, stream())          # the other storage's loader
     assert e.value.status == B.ERR_ARG
     p.P.close()
+
+
+def test_4_bit_product_respects_a_workspace_of_any_size(dev):
+    """patch_gemm4_ex with workspaces from 16 bytes to eight slices: nothing is written behind them and the result is the
+    oracle's (without room for two slices the launch does not split)."""
+    guard, pattern = 1 << 18, 0x7FC0BEEF
+    for t, N, K, M in ((128, 640, 2048, 300), (64, 448, 1600, 130)):
+        c = synth.make_case("anyws4", N, K, M, t, 0.5, seed=72)
+        p = Prepared4(c, dev)
+        Yo = p.oracle_gemm(c.X)
+        X = to_dev_bf16(c.X, dev)
+        xn, wn = row_norms(c.X), row_norms(p.W_deq_o)
+        big = torch.empty(8 * M * N + guard, device=dev, dtype=torch.int32)
+        for nbytes in (8 * M * N * 4, 3 * M * N * 4 + 16, 2 * M * N * 4, 2 * M * N * 4 - 16, M * N * 4, 4096, 16):
+            n = nbytes // 4
+            big.fill_(pattern)
+            Y = torch.full((M, N), float("nan"), device=dev, dtype=torch.float32)
+            B.patch_gemm4(X, M, p.P, Y, stream(), workspace=big[:n].view(torch.float32))
+            torch.cuda.synchronize()
+            assert bool((big[n:] == pattern).all()), f"workspace of {nbytes} bytes: wrote behind it"
+            check_elements(Y.cpu().numpy(), Yo, xn, wn, K, f"4-bit tile {t} workspace of {nbytes} bytes")
+        p.P.close()
