@@ -665,6 +665,39 @@ def test_workspace_of_any_size_is_respected(dev):
         p.P.close()
 
 
+def test_nothing_is_written_outside_y(dev):
+    """Y lies between two guard regions: with ragged M, a feature count that leaves part of the last block empty, fp32
+    and bf16 output, on every path and kernel variant, with and without a workspace, both guards keep their pattern
+    (a bf16 Y is half as large: a kernel that stored fp32 into it would run over its end)."""
+    guard, pattern = 1 << 16, 0x7FC0BEEF
+    ws = torch.empty(8 * 300 * 1152, device=dev, dtype=torch.float32)
+    for t, N, K, M in ((128, 1152, 512, 300), (64, 320, 448, 131), (128, 384, 1024, 49), (64, 64, 64, 1), (128, 128, 128, 257)):
+        c = synth.make_case("yguard", N, K, M, t, 0.5, seed=73)
+        p = Prepared(c, dev)
+        X = to_dev_bf16(c.X, dev)
+        Yo = p.oracle_gemm(c.X)
+        xn = row_norms(c.X)
+        scheds = [dict(), dict(workspace=ws), dict(path=B.PATH_DECODE), dict(path=B.PATH_DECODE, workspace=ws), dict(path=B.PATH_DECODE, variant=4)]
+        for v in range(0, 7):
+            scheds += [dict(path=B.PATH_PREFILL, variant=v), dict(path=B.PATH_PREFILL, variant=v, workspace=ws)]
+        for kw in scheds:
+            for bf16 in (False, True):
+                words = M * N // 2 if bf16 else M * N          # M N is even in every case but the single row of 64
+                if bf16 and (M * N) % 2:
+                    continue
+                buf = torch.full((guard + words + guard,), pattern, device=dev, dtype=torch.int32)
+                Y = buf[guard: guard + words].view(torch.bfloat16 if bf16 else torch.float32).view(M, N)
+                what = f"tile {t} {N}x{K} M={M} bf16={bf16} " + str({k: v for k, v in kw.items() if k != 'workspace'}) + (" +workspace" if "workspace" in kw else "")
+                B.patch_gemm(X, M, p.P, Y, stream(), y_bf16=bf16, **kw)
+                torch.cuda.synchronize()
+                assert bool((buf[:guard] == pattern).all()) and bool((buf[guard + words:] == pattern).all()), what + ": wrote outside Y"
+                if bf16:
+                    check_bf16(bits_of(Y), Yo, xn, p.wn, K, what)
+                else:
+                    check_elements(Y.cpu().numpy(), Yo, xn, p.wn, K, what)
+        p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
