@@ -13,6 +13,7 @@ Also reported on the same JSON line:
                 compressed weight bytes against the HBM peak, rotating over enough distinct packed copies
                 to defeat the 256 MB last-level cache
   speedup_vs_all_dense   same shapes with an all-dense tile map through the same library
+  prefill_m2048 the headline step on 2048 rows (the configuration's other row count), with its all-dense counterpart
   pack          compression throughput (one-off conversion; not part of a step)
   ceilings      measured ceilings from kernels of this library (register-resident loops of the two matrix
                 instructions, streaming reads) and the vendor dense GEMM on the same shapes (context)
@@ -184,7 +185,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4,tile64")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,half,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4,tile64")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -286,6 +287,22 @@ def main():
                      "traffic = measured HBM bytes per launch (profiles/)")
     roof["frac"] = roof["achieved"] / roof["peak"]
 
+    # ------------------------------------------------------------------ the configuration's other row count (2048 rows)
+    M2 = 2048
+    half = None
+    if "half" not in skip and M > M2:
+        def step2(_i):
+            for L in layers:
+                B.patch_gemm(L["X"], M2, L["P"], L["Y"], stream, **opts)
+
+        settle(step2)
+        timed(step2, args.warmup)
+        secs2 = timed(step2, args.steps)
+        half = dict(M=M2, ms_per_step=secs2 / args.steps * 1e3, dense_equiv_TFLOPs=dense_flop * M2 / M / (secs2 / args.steps) / 1e12,
+                    frac_mfma_peak=issued_flop * M2 / M / (secs2 / args.steps) / 1e12 / PEAK_MFMA_BF16_TF,
+                    note="the same three launches on the first 2048 rows of X (the 7B MLP prefill configuration names both row "
+                         "counts): 344 + 344 + 128 output tiles on 256 compute units, i.e. part-filled rounds")
+
     # ------------------------------------------------------------------ same shapes, all-dense tile map
     speedup = None
     if "dense" not in skip:
@@ -304,8 +321,21 @@ def main():
         dsecs = timed(dstep, args.steps)
         speedup = dsecs / secs
         out["all_dense_ms_per_step"] = dsecs / args.steps * 1e3
+        if half is not None:
+            def dstep2(_i):
+                for X, P0, Y in dl:
+                    B.patch_gemm(X, M2, P0, Y, stream, **opts)
+
+            settle(dstep2)
+            timed(dstep2, args.warmup)
+            d2 = timed(dstep2, args.steps)
+            half["all_dense_ms_per_step"] = d2 / args.steps * 1e3
+            half["speedup_vs_all_dense"] = d2 / (half["ms_per_step"] * 1e-3 * args.steps)
         for _, P0, _ in dl:
             P0.close()
+
+    if half is not None:
+        out["prefill_m2048"] = half
 
     # ------------------------------------------------------------------ pack throughput (one-off conversion)
     if "pack" not in skip:
