@@ -298,10 +298,31 @@ def main():
         settle(step2)
         timed(step2, args.warmup)
         secs2 = timed(step2, args.steps)
-        half = dict(M=M2, ms_per_step=secs2 / args.steps * 1e3, dense_equiv_TFLOPs=dense_flop * M2 / M / (secs2 / args.steps) / 1e12,
+        def step2f(_i):      # gate and up share X: one launch over both weights, then down
+            B.patch_gemm_many(layers[0]["X"], M2, [layers[0]["P"], layers[1]["P"]], [layers[0]["Y"], layers[1]["Y"]], stream, **opts)
+            B.patch_gemm(layers[2]["X"], M2, layers[2]["P"], layers[2]["Y"], stream, **opts)
+
+        settle(step2f)
+        timed(step2f, args.warmup)
+        secs2f = timed(step2f, args.steps)
+        need2 = max(B.patch_gemm_workspace_bytes(M2, layers[2]["P"]), 16)
+        ws2 = torch.empty(need2 // 4, device=dev, dtype=torch.float32)
+
+        def step2w(_i):      # and the down projection (128 tiles) with a workspace: K split over the idle half of the chip
+            B.patch_gemm_many(layers[0]["X"], M2, [layers[0]["P"], layers[1]["P"]], [layers[0]["Y"], layers[1]["Y"]], stream, **opts)
+            B.patch_gemm(layers[2]["X"], M2, layers[2]["P"], layers[2]["Y"], stream, workspace=ws2, **opts)
+
+        settle(step2w)
+        timed(step2w, args.warmup)
+        secs2w = timed(step2w, args.steps)
+        del ws2
+        half = dict(M=M2, ms_per_step=secs2 / args.steps * 1e3, ms_per_step_gate_up_in_one_launch=secs2f / args.steps * 1e3,
+                    ms_per_step_one_launch_and_workspace=secs2w / args.steps * 1e3, workspace_MB=round(need2 / 1e6, 1), dense_equiv_TFLOPs=dense_flop * M2 / M / (secs2 / args.steps) / 1e12,
                     frac_mfma_peak=issued_flop * M2 / M / (secs2 / args.steps) / 1e12 / PEAK_MFMA_BF16_TF,
                     note="the same three launches on the first 2048 rows of X (the 7B MLP prefill configuration names both row "
-                         "counts): 344 + 344 + 128 output tiles on 256 compute units, i.e. part-filled rounds")
+                         "counts): 344 + 344 + 128 output tiles on 256 compute units, i.e. part-filled rounds; gate and up in one "
+                         "launch (patch_gemm_many) are 688 tiles, three rounds instead of four; with a caller workspace the down "
+                         "projection splits K over the idle half of the chip")
 
     # ------------------------------------------------------------------ same shapes, all-dense tile map
     speedup = None
