@@ -207,10 +207,21 @@ patch_status patch_tune(const void* X, int64_t M, const patch_packed* P, void* Y
  *                         it the compressed layout - is fixed when P is packed here, and both inputs run from the one
  *                         P; the kernels' execution tiles are independent of the layout, so the second search is not
  *                         narrowed by the first.  Y must hold max(M_decode, M_prefill) x N floats.
+ *   patch_tune_table_export  the entries as plain records, for the caller to keep between processes (a tuned table
+ *                         holds for the GPU model it was timed on): *count = entries in the table; entries == NULL
+ *                         with cap 0 only asks for that number; PATCH_ERR_SIZE if cap is too small
+ *   patch_tune_table_import  stores / replaces `count` records; every record is checked first (shape, bucket a power
+ *                         of two, path, split, variant) and nothing is stored if one is bad (PATCH_ERR_ARG)
  * The table is internally locked; entries are plain values.  Errors: PATCH_ERR_ARG, PATCH_ERR_ALLOC, and those of
  * patch_tune.
  */
 typedef struct patch_tune_table patch_tune_table;
+typedef struct {
+    int64_t m_bucket, N, K, n_sparse_tiles;
+    int tile;
+    int path, split_k, variant, y_bf16;
+    int uses_workspace;   /* the schedule was timed with a workspace and needs one */
+} patch_tune_entry;
 int64_t patch_tune_bucket(int64_t M);
 patch_status patch_tune_table_create(patch_tune_table** out);
 void patch_tune_table_destroy(patch_tune_table* t);
@@ -219,6 +230,8 @@ patch_status patch_tune_table_put(patch_tune_table* t, int64_t M, int64_t N, int
                                   const patch_gemm_opts* opts);
 patch_status patch_tune_table_get(const patch_tune_table* t, int64_t M, int64_t N, int64_t K, int tile, int64_t n_sparse_tiles,
                                   void* workspace, size_t workspace_bytes, patch_gemm_opts* out);
+patch_status patch_tune_table_export(const patch_tune_table* t, patch_tune_entry* entries, size_t cap, size_t* count);
+patch_status patch_tune_table_import(patch_tune_table* t, const patch_tune_entry* entries, size_t count);
 patch_status patch_tune_layer(patch_tune_table* t, const void* X_decode, int64_t M_decode, const void* X_prefill, int64_t M_prefill,
                               const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes, void* stream, int reps);
 

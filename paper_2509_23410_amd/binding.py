@@ -20,7 +20,7 @@ PATH_AUTO, PATH_DECODE, PATH_PREFILL = 0, 1, 2
 EXPORTS = [
     "patch_hard_masks", "patch_apply_mask", "patch_pack", "patch_gemm", "patch_gemm_ex", "patch_gemm_many", "patch_gemm_static", "patch_gemm_workspace_bytes", "patch_tune", "patch_tune_all",
     "patch_tune_bucket", "patch_tune_table_create", "patch_tune_table_destroy", "patch_tune_table_size", "patch_tune_table_put",
-    "patch_tune_table_get", "patch_tune_layer", "patch_unpack",
+    "patch_tune_table_get", "patch_tune_table_export", "patch_tune_table_import", "patch_tune_layer", "patch_unpack",
     "patch_pack4", "patch_pack_from4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
     "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_gemm4_ex",
@@ -35,6 +35,12 @@ class GemmOpts(ctypes.Structure):
 
 class TuneResult(ctypes.Structure):
     _fields_ = [("opts", GemmOpts), ("us", ctypes.c_float)]
+
+
+class TuneEntry(ctypes.Structure):
+    _fields_ = [("m_bucket", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("n_sparse_tiles", ctypes.c_int64),
+                ("tile", ctypes.c_int), ("path", ctypes.c_int), ("split_k", ctypes.c_int), ("variant", ctypes.c_int),
+                ("y_bf16", ctypes.c_int), ("uses_workspace", ctypes.c_int)]
 
 
 class PatchError(RuntimeError):
@@ -78,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.patch_tune_table_put.restype = ci
         L.patch_tune_table_get.argtypes = [vp, i64, i64, i64, ci, i64, vp, sz, ctypes.POINTER(GemmOpts)]
         L.patch_tune_table_get.restype = ci
+        L.patch_tune_table_export.argtypes = [vp, ctypes.POINTER(TuneEntry), sz, ctypes.POINTER(sz)]
+        L.patch_tune_table_export.restype = ci
+        L.patch_tune_table_import.argtypes = [vp, ctypes.POINTER(TuneEntry), sz]
+        L.patch_tune_table_import.restype = ci
         L.patch_tune_layer.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, sz, vp, ci]
         L.patch_tune_layer.restype = ci
         L.patch_gemm_workspace_bytes.argtypes = [i64, vp, ctypes.POINTER(GemmOpts)]
@@ -324,6 +334,25 @@ class TuneTable:
             return None
         _check(st, "patch_tune_table_get")
         return _sched(o)
+
+    _FIELDS = ("m_bucket", "N", "K", "n_sparse_tiles", "tile", "path", "split_k", "variant", "y_bf16", "uses_workspace")
+
+    def export(self) -> list:
+        """Every entry as a plain dict (JSON-friendly), to keep a tuned table between processes."""
+        n = ctypes.c_size_t(0)
+        _check(lib().patch_tune_table_export(self.handle, None, 0, ctypes.byref(n)), "patch_tune_table_export")
+        arr = (TuneEntry * max(n.value, 1))()
+        _check(lib().patch_tune_table_export(self.handle, arr, n.value, ctypes.byref(n)), "patch_tune_table_export")
+        return [{f: int(getattr(arr[i], f)) for f in self._FIELDS} for i in range(n.value)]
+
+    def load(self, entries) -> None:
+        """Stores / replaces entries given as the dicts export() returns; nothing is stored if one of them is bad."""
+        entries = list(entries)
+        arr = (TuneEntry * max(len(entries), 1))()
+        for i, e in enumerate(entries):
+            for f in self._FIELDS:
+                setattr(arr[i], f, int(e[f]))
+        _check(lib().patch_tune_table_import(self.handle, arr, len(entries)), "patch_tune_table_import")
 
     def get_for(self, M: int, P: Packed, workspace=None):
         N, K, t, ns = P.dims()

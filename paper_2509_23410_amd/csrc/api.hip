@@ -630,6 +630,40 @@ patch_status patch_tune_table_get(const patch_tune_table* t, int64_t M, int64_t 
     return PATCH_OK;
 }
 
+patch_status patch_tune_table_export(const patch_tune_table* t, patch_tune_entry* entries, size_t cap, size_t* count) {
+    if (!t || !count || (!entries && cap)) return PATCH_ERR_ARG;
+    std::lock_guard<std::mutex> lock(t->mu);
+    *count = t->entries.size();
+    if (!entries) return PATCH_OK;          // a size query
+    if (cap < t->entries.size()) return PATCH_ERR_SIZE;
+    size_t i = 0;
+    for (const auto& kv : t->entries) {
+        const TuneKey& k = kv.first;
+        const TuneEntry& e = kv.second;
+        entries[i++] = patch_tune_entry{k.bucket, k.N, k.K, k.n_sparse, k.tile, e.path, e.split_k, e.variant, e.y_bf16, e.uses_ws ? 1 : 0};
+    }
+    return PATCH_OK;
+}
+
+patch_status patch_tune_table_import(patch_tune_table* t, const patch_tune_entry* entries, size_t count) {
+    if (!t || (!entries && count)) return PATCH_ERR_ARG;
+    // all or nothing: every entry is checked before the first is stored
+    for (size_t i = 0; i < count; ++i) {
+        const patch_tune_entry& e = entries[i];
+        if (!tune_key_ok(e.m_bucket, e.N, e.K, e.tile, e.n_sparse_tiles) || patch_tune_bucket(e.m_bucket) != e.m_bucket) return PATCH_ERR_ARG;
+        if (e.path < PATCH_PATH_AUTO || e.path > PATCH_PATH_PREFILL || e.split_k < 0 || e.split_k > 16 || e.variant < 0) return PATCH_ERR_ARG;
+    }
+    std::lock_guard<std::mutex> lock(t->mu);
+    try {
+        for (size_t i = 0; i < count; ++i) {
+            const patch_tune_entry& e = entries[i];
+            t->entries[TuneKey{e.m_bucket, e.N, e.K, e.n_sparse_tiles, e.tile}] =
+                TuneEntry{e.path, e.split_k, e.variant, e.y_bf16 ? 1 : 0, e.uses_workspace != 0};
+        }
+    } catch (...) { return PATCH_ERR_ALLOC; }
+    return PATCH_OK;
+}
+
 patch_status patch_tune_layer(patch_tune_table* t, const void* X_decode, int64_t M_decode, const void* X_prefill, int64_t M_prefill,
                               const patch_packed* P, void* Y, void* workspace, size_t workspace_bytes, void* stream, int reps) {
     if (!t || !P || !X_decode || !X_prefill || M_decode < 1 || M_prefill < 1) return PATCH_ERR_ARG;

@@ -1,6 +1,7 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
 declares, and rejects bad arguments before any device work."""
 import ctypes
+import json
 import struct
 import os
 import re
@@ -179,6 +180,35 @@ def test_tune_table_host_logic():
     assert L.patch_tune_table_put(tab.handle, 1, 4096, 4096, 128, 512, ctypes.byref(bad)) == B.ERR_ARG
     assert L.patch_tune_table_create(None) == B.ERR_ARG and L.patch_tune_table_size(None) == 0
     assert L.patch_tune_layer(None, 0x1000, 1, 0x1000, 64, None, 0x1000, None, 0, None, 3) == B.ERR_ARG
+    # export / import: plain records, all or nothing
+    saved = tab.export()
+    assert len(saved) == 3 and {e["m_bucket"] for e in saved} == {1, 64, 4096}
+    assert all(e["N"] == 4096 and e["K"] == 4096 and e["tile"] == 128 and e["n_sparse_tiles"] == 512 for e in saved)
+    assert json.loads(json.dumps(saved)) == saved
+    other = B.TuneTable()
+    other.put(1, 4096, 4096, 128, 512, path=B.PATH_PREFILL)                     # replaced by the import
+    other.put(7, 896, 896, 128, 10, path=B.PATH_DECODE)                          # kept
+    other.load(saved)
+    assert len(other) == 4 and other.get(1, 4096, 4096, 128, 512) == tab.get(1, 4096, 4096, 128, 512)
+    assert other.get(40, 4096, 4096, 128, 512, workspace=0x1000, workspace_bytes=64) == got
+    assert other.get(40, 4096, 4096, 128, 512) is None and other.get(7, 896, 896, 128, 10)["path"] == B.PATH_DECODE
+    for field, value in (("m_bucket", 3), ("m_bucket", 0), ("K", 4000), ("tile", 32), ("n_sparse_tiles", 5000), ("path", 9), ("split_k", 17), ("variant", -1)):
+        broken = [dict(e) for e in saved]
+        broken[2][field] = value
+        fresh = B.TuneTable()
+        with pytest.raises(B.PatchError) as err:
+            fresh.load(broken)
+        assert err.value.status == B.ERR_ARG and len(fresh) == 0, field       # the two good records before it were not stored
+        fresh.close()
+    n = ctypes.c_size_t(99)
+    small = (B.TuneEntry * 2)()
+    assert L.patch_tune_table_export(tab.handle, small, 2, ctypes.byref(n)) == B.ERR_SIZE and n.value == 3
+    assert L.patch_tune_table_export(tab.handle, None, 2, ctypes.byref(n)) == B.ERR_ARG
+    assert L.patch_tune_table_export(None, small, 2, ctypes.byref(n)) == B.ERR_ARG
+    assert L.patch_tune_table_export(tab.handle, small, 2, None) == B.ERR_ARG
+    assert L.patch_tune_table_import(None, small, 0) == B.ERR_ARG and L.patch_tune_table_import(tab.handle, None, 1) == B.ERR_ARG
+    assert L.patch_tune_table_import(tab.handle, None, 0) == B.OK and len(tab) == 3
+    other.close()
     tab.close()
 
 
