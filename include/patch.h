@@ -74,8 +74,10 @@ typedef struct {
                  /* K-steps per wavefront of the 16-feature-strip kernel; 4 = the kernel with 64         */
                  /* features per wavefront (its split_k = K chunks over `workspace`, 0 = auto; the       */
                  /* default for passes of 17 .. 64 rows when a workspace allows chunks or N >= 4608, and */
-                 /* for 12 .. 16 rows when N >= 10240).  A variant that does not apply falls back to the */
-                 /* default.                                                                             */
+                 /* for 12 .. 16 rows when N >= 10240); 5 / 6 = the strip kernel with two X loads per    */
+                 /* step / with one X load for several steps (up to 8 rows; the default picks 6 where at */
+                 /* least a quarter of the tiles are 2:4).  A variant that does not apply falls back to  */
+                 /* the default.                                                                         */
     void* workspace;        /* DEVICE, 16-byte aligned, caller-owned scratch for launches that split K   */
                             /* over workgroups (prefill; decode passes of 17 .. 64 rows), or NULL.  The  */
                             /* library never allocates in a product call.  Launches that may run         */
@@ -166,8 +168,8 @@ patch_status patch_gemm_static(const void* X, int64_t M, const patch_packed* P, 
  * run per layer and input shape, on the decode input first).  patch_tune_all times every candidate schedule of
  * patch_gemm_ex for this M and P on the device, on real operands; patch_tune returns the fastest.  Candidates:
  *   decode path (M <= 256): 16-feature-strip kernel with 8 or 4 K-steps per wavefront (variants 2 / 3) and 2 .. 16
- *     wavefronts per workgroup (split_k: the wavefronts-per-compute-unit dimension), the 64-features-per-wavefront
- *     kernel (variant 4) unsplit and with K chunks over the workspace;
+ *     wavefronts per workgroup (split_k: the wavefronts-per-compute-unit dimension), up to 8 rows both ways of loading
+ *     X (variants 5 / 6), the 64-features-per-wavefront kernel (variant 4) unsplit and with K chunks over the workspace;
  *   prefill path, tile 128: the execution tiles 256 x 256 with one wavefront per SIMD (default), 256 x 256 with two
  *     (variant 2) and the small 128 x 128 tile (variant 1; Appendix O reports that small execution tiles under-use
  *     the matrix units - it is timed so that the report shows it), and the K-split counts the workspace allows;

@@ -451,6 +451,7 @@ patch_status patch_gemm_ex(const void* X, int64_t M, const patch_packed* P, void
     a.payload = P->d_payload; a.table = P->d_table;
     a.Y = static_cast<float*>(Y);
     a.n_cus = P->n_cus;
+    a.sparse_pct = (int)(100 * P->n_sparse / ((int64_t)P->Tn * P->Tk));
     if (opts && opts->workspace) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }
     a.ybf16 = (opts && opts->y_bf16) ? 1 : 0;
     if (path == PATCH_PATH_DECODE) {
@@ -485,6 +486,10 @@ patch_status patch_tune_all(const void* X, int64_t M, const patch_packed* P, voi
         add(PATCH_PATH_DECODE, 0, 0, false);
         add(PATCH_PATH_DECODE, 0, 2, false);   // 8 K-steps per wavefront
         add(PATCH_PATH_DECODE, 0, 3, false);   // 4 K-steps per wavefront
+        if (M <= 8) {                          // X loads: two per step / one for several steps
+            add(PATCH_PATH_DECODE, 0, 5, false);
+            add(PATCH_PATH_DECODE, 0, 6, false);
+        }
         for (int kw : {2, 4, 8, 16})           // wavefronts per workgroup
             for (int v : {2, 3})
                 if (kw * (v == 2 ? 8 : 4) <= 2 * steps && (kw <= 8 || v == 3)) add(PATCH_PATH_DECODE, kw, v, false);
@@ -738,6 +743,15 @@ patch_status patch_gemm_many(const void* X, int64_t M, const patch_packed* const
     a.M = M; a.K = P[0]->K; a.N = P[0]->N;
     a.tile = P[0]->tile; a.Tk = P[0]->Tk;
     a.n_cus = P[0]->n_cus;
+    {
+        int64_t sparse = 0, tiles = 0;
+        for (int i = 0; i < count; ++i) {
+            if (!P[i]) return PATCH_ERR_ARG;
+            sparse += P[i]->n_sparse;
+            tiles += (int64_t)P[i]->Tn * P[i]->Tk;
+        }
+        a.sparse_pct = (int)(100 * sparse / tiles);
+    }
     a.ybf16 = (opts && opts->y_bf16) ? 1 : 0;
     if (opts && opts->workspace && !aligned16(opts->workspace)) return PATCH_ERR_ARG;
     if (opts && opts->workspace && split_k == 0) { a.ws = static_cast<float*>(opts->workspace); a.ws_bytes = opts->workspace_bytes; }

@@ -36,13 +36,55 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
+// dst[lane] = v[lane + S] within each row of 16 lanes (S = 0 .. 15): a DPP row rotation (row_ror:n delivers
+// src[lane - n], measured), one instruction per dword.
+template <int S>
+__device__ __forceinline__ u32x4 rows_up(u32x4 v) {
+    if constexpr (S == 0) return v;
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v[i], 0x120 + ((16 - S) & 15), 0xF, 0xF, false);
+    return r;
+}
+__device__ __forceinline__ u32x4 rows_up(u32x4 v, int s) {   // s is a constant once the caller's loop is unrolled
+    switch (s) {
+        case 1: return rows_up<1>(v);
+        case 2: return rows_up<2>(v);
+        case 3: return rows_up<3>(v);
+        case 4: return rows_up<4>(v);
+        case 5: return rows_up<5>(v);
+        case 6: return rows_up<6>(v);
+        case 7: return rows_up<7>(v);
+        case 8: return rows_up<8>(v);
+        case 9: return rows_up<9>(v);
+        case 10: return rows_up<10>(v);
+        case 11: return rows_up<11>(v);
+        case 12: return rows_up<12>(v);
+        case 13: return rows_up<13>(v);
+        case 14: return rows_up<14>(v);
+        case 15: return rows_up<15>(v);
+        default: return v;
+    }
+}
+
 // RB = blocks of 16 rows of X per launch (1, 2 or 4): the weights are streamed once for up to 64 rows.
 // SetT = DecodeSet (up to 8 weights sharing X) or WeightOne (a single weight: short kernel arguments, no selection).
-template <int TILE, int NK, int MAXW, int RB, typename SetT>
+// XR = 16: every step loads its two X operands with two instructions, in the lanes the matrix instruction reads
+//      them from (16 columns = rows of X, 4 lane groups = 8 elements of K each).
+// XR = 1, 2, 4, 8 (at most XR rows, RB = 1): with few rows most of those lanes are idle, and a load instruction costs
+//      its turn in the memory pipeline however few lanes it has.  The 16 columns then hold 16 / XR operands of XR rows
+//      each - column c = operand c / XR (K-step (c / XR) / 2 of the load, half (c / XR) % 2), row c % XR - so one
+//      instruction fetches X for 8 / XR steps, and each step rotates its two operands down to columns 0 .. XR - 1
+//      (four DPP moves each).  Columns XR .. 15 of the product are then other steps' leftovers; they are never stored.
+template <int TILE, int NK, int MAXW, int RB, typename SetT, int XR = 16>
 __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __restrict__ X, int64_t m0, int rows, int64_t K, int Tk,
                                                            const SetT set, int ybf16) {
     constexpr bool kOne = sizeof(SetT) == sizeof(WeightOne);
     constexpr int KPT = TILE / kStepCols, SPT = TILE / kStripRows;
+    constexpr bool kWide = XR < 16;
+    static_assert(!kWide || RB == 1, "several steps per X load: one row block only");
+    constexpr int SPL = kWide ? 8 / XR : 1;               // steps served by one X load
+    constexpr int NL = kWide ? (NK + SPL - 1) / SPL : 1;   // X loads per pass
     __shared__ f32x4 red[MAXW][RB][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -94,6 +136,11 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
     // lanes whose column is a row of X; the other lanes never load X and never store
     const uint64_t xmask = __builtin_amdgcn_ballot_w64(xvalid);
 
+    // several steps per load: this lane's operand (step xs of the load, half xh) and row xr
+    const int xcw = col / (kWide ? XR : 16), xr = col % (kWide ? XR : 16);
+    const int xs = xcw >> 1;
+    const uint32_t voffxw = (uint32_t)(((xr < rows ? xr : 0) * K + xs * kStepCols + (xcw & 1) * 32 + 8 * q) * 2);
+
     // the same for the further row blocks (RB > 1)
     uint32_t voffx_r[RB];
     uint64_t xmask_r[RB];
@@ -127,8 +174,29 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         // K) is jumped over by a scalar branch inside the block and leaves the zero its destination was initialised
         // with (issuing it with an empty EXEC mask instead still costs an instruction's turn in the memory pipeline:
         // all-2:4 maps at M = 1 went from 6.5 to 6.0 us on 4096 x 4096 and from 13.4 to 11.6 us on 11008 x 4096); X is loaded by the lanes that have a row only.
-        u32x4 a[NK][2], b[NK][RB][2];
+        u32x4 a[NK][2], b[kWide ? 1 : NK][RB][2], xl[NL];
         uint32_t idx[NK];
+        // several steps per X load: these loads go first, so that they are the oldest in flight and their operands
+        // can be moved into place while the weights are still on their way.  Lanes whose step lies past the end of K
+        // or whose row does not exist are masked out and keep their zero; nothing is issued when no lane is left.
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            xl[i] = u32x4{0u, 0u, 0u, 0u};
+            if constexpr (kWide) {
+                const uint64_t xm = __builtin_amdgcn_ballot_w64(xr < rows && i * SPL + xs < n);
+                uint64_t saved;
+                asm volatile(
+                    "s_mov_b64 %[sv], exec\n\t"
+                    "s_mov_b64 exec, %[xm]\n\t"
+                    "s_cbranch_execz 1f\n\t"
+                    "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"
+                    "1:\n\t"
+                    "s_mov_b64 exec, %[sv]"
+                    : [x0] "+v"(xl[i]), [sv] "=&s"(saved)
+                    : [vx] "v"(voffxw), [sbx] "s"(xbase + (size_t)(base + i * SPL) * (kStepCols * 2)), [xm] "s"(xm)
+                    : "memory");
+            }
+        }
 #pragma unroll
         for (int g = 0; g < NK; ++g) {
             const int k = (g < n) ? base + g : base;
@@ -146,8 +214,7 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
             uint32_t vi = 0;
             uint64_t saved;
 // One step's loads.  LDM is the mnemonic of the positions load (16 or 32 bits per lane).
-#define PATCH_DECODE_STEP_LOADS(LDM)                                                                              \
-    asm volatile(                                                                                                 \
+#define PATCH_DECODE_WEIGHT_LOADS(LDM)                                                                            \
         "s_cmp_eq_u32 %[kind], 0\n\t"                                                                             \
         "s_cbranch_scc1 3f\n\t"                                                                                   \
         "global_load_dwordx4 %[v0], %[vo], %[sb0] nt\n\t"                                                         \
@@ -158,7 +225,10 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         "s_cmp_eq_u32 %[mkind], 2\n\t"                                                                            \
         "s_cbranch_scc0 2f\n\t"                                                                                   \
         LDM " %[vi], %[vm], %[sbm] nt\n\t"                                                                        \
-        "2:\n\t"                                                                                                  \
+        "2:\n\t"
+#define PATCH_DECODE_STEP_LOADS(LDM)                                                                              \
+    asm volatile(                                                                                                 \
+        PATCH_DECODE_WEIGHT_LOADS(LDM)                                                                            \
         "s_mov_b64 %[sv], exec\n\t"                                                                               \
         "s_mov_b64 exec, %[xm]\n\t"                                                                               \
         "global_load_dwordx4 %[x0], %[vx], %[sbx]\n\t"                                                            \
@@ -169,14 +239,29 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         : [vo] "v"(voff), [vm] "v"(voffm), [vx] "v"(voffx), [sb0] "s"(sb0), [sbm] "s"(sbm), [sbx] "s"(sbx),       \
           [kind] "s"(kind), [mkind] "s"(mkind), [xm] "s"(xmask)                                                   \
         : "memory", "scc")
-            if constexpr (KPT == 2) { PATCH_DECODE_STEP_LOADS("global_load_dword"); }
-            else { PATCH_DECODE_STEP_LOADS("global_load_ushort"); }
+// The same without X (several steps per X load: issued ahead of the steps).
+#define PATCH_DECODE_STEP_LOADS_W(LDM)                                                                            \
+    asm volatile(                                                                                                 \
+        PATCH_DECODE_WEIGHT_LOADS(LDM)                                                                            \
+        "3:"                                                                                                       \
+        : [v0] "+v"(v0), [v1] "+v"(v1), [vi] "+v"(vi)                                                             \
+        : [vo] "v"(voff), [vm] "v"(voffm), [sb0] "s"(sb0), [sbm] "s"(sbm), [kind] "s"(kind), [mkind] "s"(mkind)   \
+        : "memory", "scc")
+            if constexpr (kWide) {
+                if constexpr (KPT == 2) { PATCH_DECODE_STEP_LOADS_W("global_load_dword"); }
+                else { PATCH_DECODE_STEP_LOADS_W("global_load_ushort"); }
+            } else {
+                if constexpr (KPT == 2) { PATCH_DECODE_STEP_LOADS("global_load_dword"); }
+                else { PATCH_DECODE_STEP_LOADS("global_load_ushort"); }
+                b[g][0][0] = x0;
+                b[g][0][1] = x1;
+            }
 #undef PATCH_DECODE_STEP_LOADS
+#undef PATCH_DECODE_STEP_LOADS_W
+#undef PATCH_DECODE_WEIGHT_LOADS
             a[g][0] = v0;
             a[g][1] = v1;
             idx[g] = vi;
-            b[g][0][0] = x0;
-            b[g][0][1] = x1;
             // X of the further row blocks: same step, same scalar base, the block's own lanes and rows
 #pragma unroll
             for (int rb = 1; rb < RB; ++rb) {
@@ -197,13 +282,30 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
         }
         // ---- wait for the loads (the compiler does not know about them), then tie every destination to this
         // point so that no use can be scheduled above the wait
+        u32x4 bw[kWide ? NK : 1][2];
+        if constexpr (kWide) {
+            // every live step has issued at least one weight load since: once no more than NK loads are outstanding
+            // the X loads (the oldest) have landed.  Their operands move into place under the weights' latency.
+            if (n == NK) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NK) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < NL; ++i) asm volatile("" : "+v"(xl[i]));
+#pragma unroll
+            for (int g = 0; g < NK; ++g) {
+                bw[g][0] = rows_up(xl[g / SPL], 2 * (g % SPL) * XR);
+                bw[g][1] = rows_up(xl[g / SPL], (2 * (g % SPL) + 1) * XR);
+                asm volatile("" : "+v"(bw[g][0]), "+v"(bw[g][1]));
+            }
+        }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int g = 0; g < NK; ++g)
         {
             asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(idx[g]));
+            if constexpr (!kWide) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(b[g][rb][0]), "+v"(b[g][rb][1]));
+                for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(b[g][rb][0]), "+v"(b[g][rb][1]));
+            }
         }
 
 #pragma unroll
@@ -218,8 +320,13 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
                     BFrag bb;
-                    bb.raw[0] = b[g][rb][0];
-                    bb.raw[1] = b[g][rb][1];
+                    if constexpr (kWide) {
+                        bb.raw[0] = bw[g][0];
+                        bb.raw[1] = bw[g][1];
+                    } else {
+                        bb.raw[0] = b[g][rb][0];
+                        bb.raw[1] = b[g][rb][1];
+                    }
                     if (sp) {
                         acc[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0.v, bb.v, acc[rb], (int)pos, 0, 0);
                     } else {
@@ -249,21 +356,30 @@ __global__ __launch_bounds__(MAXW * 64) void decode_kernel(const uint16_t* __res
 }
 
 template <int TILE, typename SetT>
-static void launch_decode_s(const GemmArgs& a, const SetT& set, int units, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
+static void launch_decode_s(const GemmArgs& a, const SetT& set, int units, int64_t m0, int rows, int nk, int kw, int xr, hipStream_t stream) {
     dim3 grid((unsigned)units), block((unsigned)(kw * 64));
     if (rows > 32) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 4, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
     else if (rows > 16) hipLaunchKernelGGL((decode_kernel<TILE, 4, 8, 2, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
-    else if (nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
-    else hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    else if (xr == 16 && nk == 8) hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    else if (xr == 16) hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1, SetT>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+#define PATCH_DECODE_WIDE(XR_)                                                                                                               \
+    else if (xr == XR_ && nk == 8)                                                                                                           \
+        hipLaunchKernelGGL((decode_kernel<TILE, 8, 8, 1, SetT, XR_>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);       \
+    else if (xr == XR_)                                                                                                                      \
+        hipLaunchKernelGGL((decode_kernel<TILE, 4, 16, 1, SetT, XR_>), grid, block, 0, stream, a.X, m0, rows, a.K, a.Tk, set, a.ybf16);
+    PATCH_DECODE_WIDE(1)
+    PATCH_DECODE_WIDE(4)
+    PATCH_DECODE_WIDE(8)
+#undef PATCH_DECODE_WIDE
 }
 
 template <int TILE>
-static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, hipStream_t stream) {
+static void launch_decode_t(const GemmArgs& a, const DecodeSet& set, int64_t m0, int rows, int nk, int kw, int xr, hipStream_t stream) {
     if (set.count == 1) {
         const WeightOne one = {set.payload[0], set.table[0], set.Y[0], set.N[0]};
-        launch_decode_s<TILE>(a, one, set.units, m0, rows, nk, kw, stream);
+        launch_decode_s<TILE>(a, one, set.units, m0, rows, nk, kw, xr, stream);
     } else {
-        launch_decode_s<TILE>(a, set, set.units, m0, rows, nk, kw, stream);
+        launch_decode_s<TILE>(a, set, set.units, m0, rows, nk, kw, xr, stream);
     }
 }
 
@@ -309,8 +425,14 @@ int launch_decode_set(const GemmArgs& a, const DecodeSet& set, int64_t m0, int r
     int kw = split_k > 0 ? split_k : kw_default > 0 ? kw_default : (total + nk - 1) / nk;
     if (kw > maxw) kw = maxw;
     if (kw < 1) kw = 1;
-    if (a.tile == 128) launch_decode_t<128>(a, set, m0, rows, nk, kw, stream);
-    else launch_decode_t<64>(a, set, m0, rows, nk, kw, stream);
+    // up to 8 rows: X of several steps per load instruction where 2:4 tiles are at least a quarter of the map (on an
+    // all-dense map the X loads are a small part of the instructions and the two schedules measured equal within the
+    // noise, at 5 .. 8 rows the old one 2 - 3 % ahead; all-2:4 maps gain 3 - 13 %, half-2:4 maps 0 - 6 %).  Variant 5
+    // keeps the two loads per step, variant 6 asks for the new schedule whatever the map.
+    const bool wide = rows <= 8 && variant != 5 && (variant == 6 || a.sparse_pct >= 25);
+    const int xr = !wide ? 16 : rows == 1 ? 1 : rows <= 4 ? 4 : 8;
+    if (a.tile == 128) launch_decode_t<128>(a, set, m0, rows, nk, kw, xr, stream);
+    else launch_decode_t<64>(a, set, m0, rows, nk, kw, xr, stream);
     return kw;
 }
 

@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void prefill_kernel_v0(const uint16_t* __restr
 // (tile 128: 2 KB per tile row, kept for the tile's two K-steps in a buffer chosen by the tile's parity;
 // tile 64: 512 B per tile row in a 1 KB slot, per stage).
 // ------------------------------------------------------------------------------------------------------
-constexpr int kPfBN = 256, kPfBM = 256;
+constexpr int kPfBN = 256;
 constexpr int kPfAStage = 2 * 8 * kDenseFragBytes;   // 32 KB
 constexpr int kPfMetaBuf = 2 * 2048;                 // position words: two tile rows x 2 KB (tile 128), four x 1 KB (tile 64)
 __host__ __device__ constexpr int pf_xstage(int bm) { return bm * 128; }   // X tile of a stage: 32 or 16 KB

@@ -29,6 +29,7 @@ struct GemmArgs {
     size_t ws_bytes = 0;
     int n_cus;
     int ybf16 = 0;          // nonzero: Y (and every Y of a set) is bf16, the accumulator rounded to nearest even
+    int sparse_pct = 0;     // share of 2:4 tiles in the weight (all weights of a set), per cent: a hint for schedules
 };
 
 // Up to kMaxMany weights that share one X (same K, same tile), multiplied in one launch.  The launch numbers its

@@ -698,6 +698,46 @@ def test_nothing_is_written_outside_y(dev):
         p.P.close()
 
 
+@pytest.mark.parametrize("t,N,K", [(128, 384, 640), (64, 192, 320), (64, 128, 64), (128, 256, 2176)])
+def test_decode_x_load_schedules(dev, t, N, K):
+    """Up to 8 rows the strip kernel loads X either with two instructions per step (variant 5) or with one instruction
+    for 8, 2 or 1 steps (variant 6: the operands of 1, up to 4, up to 8 rows side by side in the 16 operand columns,
+    rotated into place per step).  Both against the oracle and bit-equal to each other (the same products summed in the
+    same order), on all-dense, mixed and all-2:4 maps, K-step counts that leave the last pass of a wavefront part empty,
+    forced wavefront counts, bf16 output, and weights sharing X in one launch."""
+    for f in (0.0, 0.5, 1.0):
+        c = synth.make_case("xsched", N, K, 8, t, f, seed=81)
+        p = Prepared(c, dev)
+        for M in range(1, 9):
+            Yo = p.oracle_gemm(c.X[:M])
+            print(f"tile {t} {N}x{K} f={f} M={M}", flush=True)
+            Y5 = p.gemm(c.X[:M], path=B.PATH_DECODE, variant=5)
+            Y6 = p.gemm(c.X[:M], path=B.PATH_DECODE, variant=6)
+            p.check(c.X[:M], Y6, Yo, f"one X load for several steps, M={M}")
+            assert np.array_equal(Y5, Y6), "the two X-load schedules differ"
+            assert np.array_equal(p.gemm(c.X[:M]), Y6), "the default schedule differs"
+            for kw in (1, 3, 16):
+                Yk = p.gemm(c.X[:M], path=B.PATH_DECODE, variant=6, split_k=kw)
+                p.check(c.X[:M], Yk, Yo, f"M={M}, {kw} wavefronts")
+                assert np.array_equal(Yk, p.gemm(c.X[:M], path=B.PATH_DECODE, variant=5, split_k=kw))
+            check_bf16(p.gemm_bf16(c.X[:M], path=B.PATH_DECODE, variant=6), Yo, row_norms(c.X[:M]), p.wn, K, f"bf16 M={M}")
+        p.P.close()
+    # two weights sharing X (different fractions: the set's overall share decides the default schedule)
+    cases = [synth.make_case(f"xsched_set{i}", N, K, 8, t, f, seed=82 + i) for i, f in enumerate((0.2, 0.9))]
+    preps = [Prepared(c, dev) for c in cases]
+    X = cases[0].X
+    Xd = to_dev_bf16(X, dev)
+    for M in (1, 3, 8):
+        for v in (0, 5, 6):
+            Ys = [torch.full((M, N), float("nan"), device=dev, dtype=torch.float32) for _ in cases]
+            B.patch_gemm_many(Xd, M, [p.P for p in preps], Ys, stream(), path=B.PATH_DECODE, variant=v)
+            torch.cuda.synchronize()
+            for p, Y in zip(preps, Ys):
+                p.check(X[:M], Y.cpu().numpy(), None, f"set, M={M}, variant {v}")
+    for p in preps:
+        p.P.close()
+
+
 def test_mid_m_paths_agree(dev):
     """M around the decode / prefill crossover: both paths must give the oracle's result."""
     c = synth.make_case("mid", 1024, 768, 300, 128, 0.5, seed=9)
