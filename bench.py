@@ -14,6 +14,7 @@ Also reported on the same JSON line:
                 to defeat the 256 MB last-level cache
   speedup_vs_all_dense   same shapes with an all-dense tile map through the same library
   prefill_m2048 the headline step on 2048 rows (the configuration's other row count), with its all-dense counterpart
+  prefill_bf16_out  the headline step with bf16 output (half the bytes stored; beside the headline, not instead of it)
   pack          compression throughput (one-off conversion; not part of a step)
   ceilings      measured ceilings from kernels of this library (register-resident loops of the two matrix
                 instructions, streaming reads) and the vendor dense GEMM on the same shapes (context)
@@ -185,7 +186,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=4096, help="rows of X for the headline prefill workload")
     ap.add_argument("--f", type=float, default=0.6, help="fraction of 2:4 tiles of the headline workload")
-    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,half,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4,tile64")
+    ap.add_argument("--skip", default="", help="comma list of sections to skip: decode,dense,half,bf16out,cpu,pack,mid,sweep,layer,ceilings,stack,alloc,qwen,q4,tile64")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--decode-launches", type=int, default=200)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -357,6 +358,25 @@ def main():
 
     if half is not None:
         out["prefill_m2048"] = half
+
+    # ------------------------------------------------------------------ the headline step with bf16 output (half the stores)
+    if "bf16out" not in skip:
+        Yb = [torch.empty((M, L["c"].N), device=dev, dtype=torch.bfloat16) for L in layers]
+
+        def bstep(_i):
+            for L, Y16 in zip(layers, Yb):
+                B.patch_gemm(L["X"], M, L["P"], Y16, stream, y_bf16=True, **opts)
+
+        settle(bstep)
+        timed(bstep, args.warmup)
+        bsecs = timed(bstep, args.steps)
+        out["prefill_bf16_out"] = dict(M=M, ms_per_step=bsecs / args.steps * 1e3, dense_equiv_TFLOPs=dense_flop / (bsecs / args.steps) / 1e12,
+                                       frac_mfma_peak=issued_flop / (bsecs / args.steps) / 1e12 / PEAK_MFMA_BF16_TF,
+                                       speedup_vs_fp32_output=secs / bsecs,
+                                       note="the headline step with the accumulator rounded to bf16 in the output stage (patch_gemm_opts.y_bf16): "
+                                            "the store burst at the end of every round of tiles is half as long; not the headline, whose Y is "
+                                            "fp32 (a bf16 Y alone is outside the 1e-3 bar against the fp64 oracle)")
+        del Yb
 
     # ------------------------------------------------------------------ pack throughput (one-off conversion)
     if "pack" not in skip:

@@ -11,8 +11,8 @@ typedef float ep_f32x4 __attribute__((ext_vector_type(4)));
 // bf16 bit pattern of an fp32 value, round to nearest even; a NaN stays a (quiet) NaN
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
     const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const uint32_t nan = (u >> 16) | 0x40u, rne = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;   // both computed: a select, no branch
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? nan : rne;
 }
 
 typedef unsigned int ep_u32x2 __attribute__((ext_vector_type(2)));

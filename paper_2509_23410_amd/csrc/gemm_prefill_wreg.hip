@@ -42,7 +42,9 @@ typedef float wr_f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWrBN = 256, kWrBM = 256;
 constexpr int kWrStage = kWrBM * 128;   // 256 rows of X x 64 columns, swizzled
-constexpr int kWrLds = 4 * kWrStage;    // 128 KB
+constexpr int kWrRing = 4 * kWrStage;   // 128 KB: the four X stages
+constexpr int kWrOut = 4096;            // per wavefront: 16 rows x 64 features fp32 of the output stage
+constexpr int kWrLds = kWrRing + 4 * kWrOut;   // 144 KB
 
 typedef __attribute__((address_space(3))) void* wr_lptr_t;
 
@@ -735,30 +737,52 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
     // workgroup's LDS and registers can be handed on; the last matrix instructions may still be writing
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory", PATCH_WR_CLOBBER);
 
-    // accumulator (s, cb), register r: feature nrow + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col
+    // accumulator (s, cb), register r: feature nrow + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col.
+    // Stored from there, one instruction writes 16 rows x 64 bytes (half cache lines); a compute unit then takes about
+    // 10 us for its 256 KB however idle the memory is, and longer for a bf16 Y (quarter lines).  So every column block
+    // (16 rows x this wavefront's 64 features) is turned through 4 KB of LDS of the wavefront's own, behind the X ring
+    // (no barrier: a wavefront's LDS instructions execute in order): written as it lies in the registers, read back
+    // as 4 rows x 256 contiguous bytes per instruction.  16-byte chunk c of row r sits at chunk c ^ r: the 16 lanes
+    // that write one chunk column, and the 16 that read one row, each touch all 64 banks once.
     if (live) {
+        uint8_t* const stg = lds + kWrRing + w * kWrOut;
+        const int rr = lane >> 4, ch = lane & 15;   // as a reader: row rr of every four, chunk ch = features 4 ch .. 4 ch + 3
 #define PATCH_WR_READ(S, CB)                                                                                       \
     asm volatile("v_accvgpr_read_b32 %0, a[4*(16*" #S "+" #CB ")+0]\n\tv_accvgpr_read_b32 %1, a[4*(16*" #S "+" #CB ")+1]\n\t" \
                  "v_accvgpr_read_b32 %2, a[4*(16*" #S "+" #CB ")+2]\n\tv_accvgpr_read_b32 %3, a[4*(16*" #S "+" #CB ")+3]"       \
                  : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]))
+#define PATCH_WR_STAGE(S, CB)                                                                                      \
+    PATCH_WR_READ(S, CB);                                                                                          \
+    *reinterpret_cast<wr_f32x4*>(stg + col * 256 + (((4 * S + q) ^ col) << 4)) = wr_f32x4{v[0], v[1], v[2], v[3]};
 #define PATCH_WR_STORE(CB, SET, NSET)                                                                              \
     {                                                                                                              \
-        const int64_t m = m0 + 16 * CB + col;                                                                      \
-        /* element offset of this lane's first four features: a workspace slot (MODE 2), a workspace slice (MODE 1), Y */ \
-        const int64_t ye = MODE == 2 ? ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + col) * kWrBN + 128 * tr + 64 * sh + 4 * q \
-                                     : (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * q;      \
-        const int yb = MODE == 0 ? ybf16 : 0; /* partial products stay fp32; their sum is rounded by the reduction */  \
         float v[4];                                                                                                \
-        PATCH_WR_READ(0, CB);                                                                                      \
-        if (MODE == 2 || m < M) store4(Y, ye, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                               \
-        PATCH_WR_READ(1, CB);                                                                                      \
-        if (MODE == 2 || m < M) store4(Y, ye + 16, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
-        PATCH_WR_READ(2, CB);                                                                                      \
-        if (MODE == 2 || m < M) store4(Y, ye + 32, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
-        PATCH_WR_READ(3, CB);                                                                                      \
-        if (MODE == 2 || m < M) store4(Y, ye + 48, wr_f32x4{v[0], v[1], v[2], v[3]}, yb);                          \
+        PATCH_WR_STAGE(0, CB) PATCH_WR_STAGE(1, CB) PATCH_WR_STAGE(2, CB) PATCH_WR_STAGE(3, CB)                    \
+        wr_f32x4 o[4];                                                                                             \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) { /* all four reads before the first store waits for one */  \
+            const int r = 4 * j + rr;                                                                              \
+            o[j] = *reinterpret_cast<const wr_f32x4*>(stg + r * 256 + ((ch ^ r) << 4));                            \
+        }                                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                            \
+            const int r = 4 * j + rr; /* row inside the column block */                                            \
+            const int64_t m = m0 + 16 * CB + r;                                                                    \
+            /* element offset of this lane's four features: a workspace slot (MODE 2), a workspace slice (MODE 1), Y */ \
+            const int64_t ye = MODE == 2 ? ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + r) * kWrBN + 128 * tr + 64 * sh + 4 * ch \
+                                         : (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * ch;     \
+            if (MODE == 2 || m < M) store4(Y, ye, o[j], YB);                                                       \
+        }                                                                                                          \
     }
-        PATCH_WR_16(PATCH_WR_STORE)
+        // (the bf16 choice is taken once, not per store: MODE 1 / 2 write fp32 partial products, their sum is rounded by the reduction)
+        if (MODE == 0 && ybf16) {
+#define YB 1
+            PATCH_WR_16(PATCH_WR_STORE)
+#undef YB
+        } else {
+#define YB 0
+            PATCH_WR_16(PATCH_WR_STORE)
+#undef YB
+        }
+#undef PATCH_WR_STAGE
 #undef PATCH_WR_STORE
 #undef PATCH_WR_READ
     }
