@@ -641,38 +641,15 @@ __global__ __launch_bounds__(512) void prefill_kernel_areg(const uint16_t* __res
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-    // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32.  Stored from there, an instruction would
-    // write 32 rows x 32 bytes (quarter cache lines), which a compute unit's store path takes at a fraction of its
-    // rate (the output stage of prefill_kernel_wreg has the measurements).  The X stages are free once every
-    // wavefront has left the loop: each block of 32 rows x the wavefront's 32 features is turned through 4 KB of
-    // them - written as it lies in the registers, read back as 8 rows x 128 contiguous bytes per instruction; a
-    // wavefront's LDS instructions execute in order, so only the one barrier is needed.  16-byte chunk c of row r
-    // sits at chunk c ^ (r / 2 % 8): two rows fill the 64 banks, and sixteen lanes that write one chunk of sixteen
-    // rows, or read two whole rows, touch every bank once.
+    // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32.  The X stages are free once every wavefront
+    // has left the loop: each block of 32 rows is turned through 4 KB of them and stored in whole rows
+    // (store_block_rows).
     __syncthreads();
     if (w4 < live) {
-        uint8_t* const stg = lds + w * 4096;
-        const int rr = lane >> 3, ch = lane & 7;   // as a reader: row rr of every eight, chunk ch = features 4 ch .. 4 ch + 3
-        const int yb = SPLIT ? 0 : ybf16;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 v = {acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]};
-                *reinterpret_cast<f32x4*>(stg + i32 * 128 + ((((2 * g + q) ^ (i32 >> 1)) & 7) << 4)) = v;
-            }
-            f32x4 o[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int r = 8 * j + rr;
-                o[j] = *reinterpret_cast<const f32x4*>(stg + r * 128 + (((ch ^ (r >> 1)) & 7) << 4));
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int64_t m = m0 + 32 * b + 8 * j + rr;
-                if (m < M) store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + fo + 4 * ch, o[j], yb);
-            }
-        }
+        for (int b = 0; b < NB; ++b)
+            store_block_rows(lds + w * 4096, acc[b], lane, Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + (m0 + 32 * b) * N + n0 + fo, N,
+                             M - (m0 + 32 * b), SPLIT ? 0 : ybf16);
     }
 }
 

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "epilogue.h"
+
 namespace patch {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -56,6 +58,37 @@ __device__ __forceinline__ void mma_step(f32x16& c0, f32x16& c1, const bf16x8& a
         : [a0] "v"(a0), [a1] "v"(a1), [b0] "v"(b0.v), [b1] "v"(b1.v), [b0lo] "v"(b0.h[0]), [b0hi] "v"(b0.h[1]),
           [b1lo] "v"(b1.h[0]), [b1hi] "v"(b1.h[1]), [idx] "v"(idx), [sp] "s"(sparse)
         : "scc");
+}
+
+// Output of one 32-row block of a wavefront's 32 features.  acc[i]: feature 8 (i / 4) + 4 q + i % 4, row i32 (lane =
+// 32 q + i32).  Stored from there, an instruction would write 32 rows x 32 bytes (quarter cache lines), which a
+// compute unit's store path takes at a fraction of its rate (the output stage of prefill_kernel_wreg has the
+// measurements).  The block is turned through 4 KB of LDS of the wavefront's own (`stg`) - written as it lies in the
+// registers, read back as 8 rows x 128 contiguous bytes per instruction; a wavefront's LDS instructions execute in
+// order, so no barrier lies between the two.  16-byte chunk c of row r sits at chunk c ^ (r / 2 % 8): two rows fill
+// the 64 banks, and sixteen lanes that write one chunk of sixteen rows, or read two whole rows, touch every bank once.
+// `elem` = element offset of (row 0 of the block, first feature of the wavefront) in Y, `rows` = rows of the block
+// that exist (the others are not stored).
+__device__ __forceinline__ void store_block_rows(uint8_t* stg, const f32x16& acc, int lane, float* Y, int64_t elem, int64_t N,
+                                                 int64_t rows, int ybf16) {
+    const int i32 = lane & 31, q = lane >> 5;
+    const int rr = lane >> 3, ch = lane & 7;   // as a reader: row rr of every eight, chunk ch = features 4 ch .. 4 ch + 3
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 v = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+        *reinterpret_cast<f32x4*>(stg + i32 * 128 + ((((2 * g + q) ^ (i32 >> 1)) & 7) << 4)) = v;
+    }
+    f32x4 o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = 8 * j + rr;
+        o[j] = *reinterpret_cast<const f32x4*>(stg + r * 128 + (((ch ^ (r >> 1)) & 7) << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = 8 * j + rr;
+        if (r < rows) store4(Y, elem + (int64_t)r * N + 4 * ch, o[j], ybf16);
+    }
 }
 
 }  // namespace patch

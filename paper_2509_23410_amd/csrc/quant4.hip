@@ -750,18 +750,15 @@ __global__ __launch_bounds__(512) void prefill4_kernel(const uint16_t* __restric
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-    // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32
+    // acc[b][i]: feature n0 + fo + 8 (i/4) + 4 q + i%4, row m0 + 32 b + i32.  The X stages are free once every wavefront
+    // has left the loop: each block of 32 rows is turned through 4 KB of them and stored in whole rows
+    // (store_block_rows).
+    __syncthreads();
     if (w4 < live) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int64_t m = m0 + 32 * b + i32;
-            if (m >= M) continue;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 v = {acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]};
-                store4(Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + m * N + n0 + fo + 8 * g + 4 * q, v, 0);
-            }
-        }
+        for (int b = 0; b < NB; ++b)
+            store_block_rows(lds + w * 4096, acc[b], lane, Y, (SPLIT ? (int64_t)blockIdx.y * M * N : 0) + (m0 + 32 * b) * N + n0 + fo, N,
+                             M - (m0 + 32 * b), 0);
     }
 }
 
