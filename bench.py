@@ -774,6 +774,24 @@ def main():
                                  "barrier; the per-compute-unit rate is the same with one or two rounds in flight, so it is a throughput, not "
                                  "a latency: it bounds a K-step of the kernels that stage both operands (48 KB with blocks of 128 rows)")
         del big, sink
+        # the output stage of the prefill kernel on its own: one workgroup per 256 x 256 tile of a 4096 x 11008 output
+        # (688 tiles, the gate projection's grid) and of a 1536 x 11008 one (258 tiles: one round and two stragglers, whose
+        # time is what a compute unit needs when nothing else is storing), two Y buffers in alternation
+        st = dict()
+        for bf in (False, True):
+            Ys = [torch.empty((4096, 11008), device=dev, dtype=torch.bfloat16 if bf else torch.float32) for _ in range(2)]
+            for rows_ in (4096, 1536):
+                for pat, pname in ((0, "16_rows_x_%d_bytes" % (32 if bf else 64)), (1, "4_rows_x_%d_bytes" % (128 if bf else 256))):
+                    fn = lambda i, pat=pat, bf=bf, rows_=rows_: B.patch_probe_store_tiles(pat, bf, Ys[i & 1], rows_, 11008, stream)
+                    timed(fn, 6)
+                    t_ = sorted(timed(fn, 40) / 40 for _ in range(3))[1]
+                    st[f"{'bf16' if bf else 'fp32'}_{rows_ // 256 * 43}_tiles_{pname}_us"] = round(t_ * 1e6, 1)
+            del Ys
+        ceil["store_tiles"] = st
+        ceil["store_tiles_note"] = ("stores only, 4 wavefronts x 64 store instructions per tile: 16 rows x 64 bytes per instruction is the "
+                                    "accumulator layout stored as it lies, 4 rows x 256 bytes the same data after a turn through LDS (what the "
+                                    "prefill kernels do); 688 tiles = 2.7 rounds of the chip, bound by the HBM write rate in either pattern "
+                                    "for fp32; 258 tiles = one round and two stragglers, and bf16: the row pattern is the faster one")
         # vendor dense GEMM (bf16 output) on the headline shapes, for context: same macro tile class, same part
         vend = []
         for name, N_, K_ in (("gate", 11008, 4096), ("down", 4096, 11008)):

@@ -386,6 +386,12 @@ patch_status patch_deserialize4(const void* buf, size_t bytes, void* stream, pat
  *                            wavefront) into alternating halves of the buffer, kind 3 = as 4 but waiting only for the
  *                            round before the one just issued (two rounds in flight).  out: DEVICE, workgroups * 512
  *                            32-bit words.
+ *   patch_probe_store_tiles  stores only: one workgroup of 4 wavefronts per 256 x 256 tile of a row-major M x N
+ *                            matrix Y (DEVICE, 16-byte aligned, y_bytes >= M * N * 4, or * 2 with bf16; M and N multiples
+ *                            of 256), 64 store instructions per wavefront as in the output stage of the prefill kernel:
+ *                            pattern 0 = 16 rows x 64 bytes per instruction (the accumulator layout stored as it lies),
+ *                            pattern 1 = 4 rows x 256 contiguous bytes (after a turn through LDS); with bf16 half the
+ *                            bytes per lane.  The values written are arbitrary.
  * Errors: PATCH_ERR_ARG, PATCH_ERR_SIZE (a buffer too small), PATCH_ERR_HIP.
  */
 #define PATCH_PROBE_OPERAND_BYTES ((size_t)12 * 256 * 16)
@@ -395,6 +401,7 @@ patch_status patch_probe_stream_read(const void* src, size_t bytes, int workgrou
                                      void* stream);
 patch_status patch_probe_lds_fill(int kind, const void* src, size_t bytes, int workgroups, int rounds, void* out, size_t out_bytes,
                                   void* stream);
+patch_status patch_probe_store_tiles(int pattern, int bf16, void* Y, size_t y_bytes, int64_t M, int64_t N, void* stream);
 
 void patch_free(patch_packed* P);
 const char* patch_strerror(patch_status s);

@@ -3,6 +3,7 @@
 //                       (v_mfma_f32_16x16x32_bf16, v_smfmac_f32_16x16x64_bf16) and of their 32 x 32 shapes, no memory
 //                       traffic inside the loop
 //   stream_read_kernel  128-bit streaming read of a buffer (the HBM bound of the decode path)
+//   store_tiles_kernel  the output stage of a prefill workgroup on its own, in two store patterns
 // They compute nothing of the method; the caller times them with events on the stream it passes.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -196,6 +197,33 @@ __global__ __launch_bounds__(512) void lds_fill_kernel(const uint8_t* __restrict
     out[(size_t)blockIdx.x * 512 + tid] = fold;
 }
 
+// Stores only: workgroup t of 4 wavefronts writes output tile t (256 rows x 256 features of a row-major M x N matrix,
+// tiles along N first) the way a prefill workgroup's output stage does, 64 store instructions per wavefront.
+//   PAT 0: 16 rows x 16 bytes-per-lane quarters of 64 bytes - the accumulator layout of the 16 x 16 matrix instruction
+//          stored as it lies (lane = row % 16 + 16 * (four features))
+//   PAT 1: 4 rows x the wavefront's 64 features contiguous - the same data after a turn through LDS
+// BF16: two bytes per element (8 bytes per lane) instead of four (16 bytes per lane).
+typedef unsigned int cl_u32x2 __attribute__((ext_vector_type(2)));
+template <int PAT, int BF16>
+__global__ __launch_bounds__(256) void store_tiles_kernel(void* __restrict__ Y, long N, int tiles_n) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long m0 = 256L * (blockIdx.x / tiles_n), n0 = 256L * (blockIdx.x % tiles_n);
+    cl_f32x4 v = {(float)lane, (float)w, (float)blockIdx.x, 1.0f};
+    for (int j = 0; j < 64; ++j) {
+        long m, n;
+        if (PAT == 0) { m = m0 + 16 * (j >> 2) + (lane & 15); n = n0 + 64 * w + 16 * (j & 3) + 4 * (lane >> 4); }
+        else { m = m0 + 4 * j + (lane >> 4); n = n0 + 64 * w + 4 * (lane & 15); }
+        v[3] += 1.0f;
+        if (BF16) {
+            const cl_u32x2 p = {(__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u),
+                                (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u)};
+            *reinterpret_cast<cl_u32x2*>(static_cast<uint16_t*>(Y) + m * N + n) = p;
+        } else {
+            *reinterpret_cast<cl_f32x4*>(static_cast<float*>(Y) + m * N + n) = v;
+        }
+    }
+}
+
 }  // namespace patch
 
 extern "C" {
@@ -244,6 +272,21 @@ patch_status patch_probe_lds_fill(int kind, const void* src, size_t bytes, int w
         case 3: hipLaunchKernelGGL(patch::lds_fill_kernel<3>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
         default: hipLaunchKernelGGL(patch::lds_fill_kernel<4>, dim3(workgroups), dim3(512), 0, s, p, (unsigned)chunks, rounds, o); break;
     }
+    return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
+}
+
+patch_status patch_probe_store_tiles(int pattern, int bf16, void* Y, size_t y_bytes, int64_t M, int64_t N, void* stream) {
+    if (!Y || pattern < 0 || pattern > 1 || M < 256 || N < 256 || M % 256 || N % 256) return PATCH_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(Y) & 15u) return PATCH_ERR_ARG;
+    const int64_t tiles = (M / 256) * (N / 256);
+    if (tiles > (1 << 20)) return PATCH_ERR_ARG;
+    if (y_bytes < (size_t)M * (size_t)N * (bf16 ? 2 : 4)) return PATCH_ERR_SIZE;   // every tile lies inside M x N
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int tn = (int)(N / 256);
+    if (pattern == 0 && !bf16) hipLaunchKernelGGL((patch::store_tiles_kernel<0, 0>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
+    else if (pattern == 0) hipLaunchKernelGGL((patch::store_tiles_kernel<0, 1>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
+    else if (!bf16) hipLaunchKernelGGL((patch::store_tiles_kernel<1, 0>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
+    else hipLaunchKernelGGL((patch::store_tiles_kernel<1, 1>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
     return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
 }
 
