@@ -1210,3 +1210,19 @@ def test_hip_graph_replay_matches_eager(dev):
             assert torch.equal(Y, E), f"replay {rep}: M={M} differs from the eager launch"
     p.check(c.X, outs[2].cpu().numpy(), None, "graph replay, split prefill")
     p.P.close()
+
+
+def test_store_probe_stays_inside_its_matrix(dev):
+    """patch_probe_store_tiles (the output stage's stores on their own, timed by bench.py's ceilings section) writes
+    every element of its M x N matrix and nothing outside it, in both store patterns and both element sizes."""
+    M, N = 512, 768
+    for bf16 in (False, True):
+        dt = torch.bfloat16 if bf16 else torch.float32
+        guard = 4096
+        for pattern in (0, 1):
+            buf = torch.full((guard + M * N + guard,), -7.0, device=dev, dtype=dt)   # the probe writes values >= 0 only
+            Y = buf[guard:guard + M * N]
+            B.patch_probe_store_tiles(pattern, bf16, Y, M, N, stream())
+            torch.cuda.synchronize()
+            assert bool((buf[:guard] == -7.0).all()) and bool((buf[guard + M * N:] == -7.0).all()), "wrote outside Y"
+            assert bool((Y >= 0).all()), f"pattern {pattern}, bf16 {bf16}: elements left unwritten"
