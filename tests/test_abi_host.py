@@ -217,44 +217,47 @@ def test_tune_table_host_logic():
 
 
 def test_wreg_kernel_keeps_named_registers_to_itself(tmp_path):
-    """prefill_kernel_wreg addresses a[0:255], v[64:230] and s[80:95] by name inside its asm statements (the whole step
-    loop is one statement); the code the compiler generates around them must not touch those registers, nor m0
-    (written by the asm for LDS-DMA)."""
+    """prefill_kernel_wreg addresses a[0:255] and v[64:251] by name inside its asm statements (the whole step loop is one
+    statement); between those statements weight loads, LDS reads and LDS-DMA are in flight into these registers, so the
+    code the compiler generates around them must not touch them, nor m0 (written by the asm for LDS-DMA), and must not
+    spill a vector register (a spill could move a value the asm owns).  The scalar registers the loop names (s74 - s97)
+    are initialised and consumed inside the one loop statement, which declares them clobbered: the compiler may use them
+    elsewhere.  v252 - v255 belong to nobody.  Every instantiation is checked."""
     import re
     from paper_2509_23410_amd import build
     text = open(build.device_asm("gemm_prefill_wreg.hip", str(tmp_path / "wreg.s"))).read()
-    m = re.search(r"^_ZN5patch19prefill_kernel_wreg\w*:[^\n]*\n(.*?)s_endpgm", text, re.S | re.M)
-    assert m, "kernel not found in the assembly"
-    inasm, max_v, max_s, n_asm = False, -1, -1, 0
-    for line in m.group(1).splitlines():
-        if "#ASMSTART" in line:
-            inasm, n_asm = True, n_asm + 1
-            continue
-        if "#ASMEND" in line:
-            inasm = False
-            continue
-        code = line.split(";")[0]
-        if inasm or not code.strip() or code.strip().startswith("."):
-            continue
-        assert not re.search(r"\ba\[?\d", code) and "accvgpr" not in code, f"compiler touched an accumulation register: {line}"
-        assert not re.search(r"\bm0\b", code), f"compiler uses m0: {line}"
-        for g in re.finditer(r"\bv(\d+)\b", code):
-            max_v = max(max_v, int(g.group(1)))
-        for g in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
-            max_v = max(max_v, int(g.group(2)))
-        for g in re.finditer(r"\bs(\d+)\b", code):
-            max_s = max(max_s, int(g.group(1)))
-        for g in re.finditer(r"\bs\[(\d+):(\d+)\]", code):
-            max_s = max(max_s, int(g.group(2)))
-    assert n_asm > 40, "inline asm markers missing from the assembly"
-    assert 0 <= max_v < 64, f"compiler allocated v{max_v}, inside the range the asm owns"
-    assert 0 <= max_s < 80, f"compiler allocated s{max_s}, inside the range the asm owns"
-    loop = re.search(r"WR_D0_\d+:(.*?)WR_END_\d+:", m.group(1), re.S)
-    assert loop and "#ASMEND" not in loop.group(1), "the step loop must be a single asm statement"
-    meta = re.search(r"\.name:\s+_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
-    spills = re.search(r"_ZN5patch19prefill_kernel_wreg.*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
-    assert (meta or spills) and int((meta or spills).group(1)) == 0
-    assert re.search(r"\.agpr_count:\s+256", text)
+    bodies = list(re.finditer(r"^(_ZN5patch19prefill_kernel_wreg\w*):[^\n]*\n(.*?)^\.Lfunc_end\d+:", text, re.S | re.M))
+    assert len(bodies) == 3, "expected the instantiations <0>, <1>, <2>"
+    for m in bodies:
+        name = m.group(1)
+        inasm, n_asm = False, 0
+        for line in m.group(2).splitlines():
+            if "#ASMSTART" in line:
+                inasm, n_asm = True, n_asm + 1
+                continue
+            if "#ASMEND" in line:
+                inasm = False
+                continue
+            code = line.split(";")[0]
+            if inasm or not code.strip() or code.strip().startswith("."):
+                continue
+            assert not re.search(r"\ba\[?\d", code) and "accvgpr" not in code, f"{name}: compiler touched an accumulation register: {line}"
+            assert not re.search(r"\bm0\b", code), f"{name}: compiler uses m0: {line}"
+            used = [int(g.group(1)) for g in re.finditer(r"\bv(\d+)\b", code)]
+            for g in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
+                used += [int(g.group(1)), int(g.group(2))]
+            for v in used:
+                assert v < 64 or v > 251, f"{name}: compiler allocated v{v}, inside the range the asm owns: {line}"
+        assert n_asm > 40, f"{name}: inline asm markers missing from the assembly"
+        loop = re.search(r"WR_D0_\d+:(.*?)WR_END_\d+:", m.group(2), re.S)
+        assert loop and "#ASMEND" not in loop.group(1), f"{name}: the step loop must be a single asm statement"
+    metas = re.findall(r"\.name:\s+(_ZN5patch19prefill_kernel_wreg\w*)\n(?:(?!\.name:).)*?\.vgpr_spill_count:\s+(\d+)", text, re.S)
+    if not metas:   # older metadata order: spill count first
+        metas = [(n, c) for c, n in re.findall(r"\.vgpr_spill_count:\s+(\d+)(?:(?!\.vgpr_spill_count:).)*?\.name:\s+(_ZN5patch19prefill_kernel_wreg\w*)", text, re.S)]
+    assert len(metas) == 3, f"kernel metadata not found: {metas}"
+    for n, c in metas:
+        assert int(c) == 0, f"{n}: {c} vector registers spilled"
+    assert len(re.findall(r"\.agpr_count:\s+256", text)) >= 3
 
 
 @pytest.mark.parametrize("source,kernel,at_least", [("gemm_decode.hip", "decode_kernel", 4), ("gemm_mid.hip", "mid_kernel", 4),
