@@ -374,8 +374,9 @@ def main():
                                        frac_mfma_peak=issued_flop / (bsecs / args.steps) / 1e12 / PEAK_MFMA_BF16_TF,
                                        speedup_vs_fp32_output=secs / bsecs,
                                        note="the headline step with the accumulator rounded to bf16 in the output stage (patch_gemm_opts.y_bf16): "
-                                            "the store burst at the end of every round of tiles is half as long; not the headline, whose Y is "
-                                            "fp32 (a bf16 Y alone is outside the 1e-3 bar against the fp64 oracle)")
+                                            "half the bytes stored, a few per cent at most since the output stage stores whole rows (ceilings."
+                                            "store_tiles has the stores on their own); not the headline, whose Y is fp32 (a bf16 Y alone is "
+                                            "outside the 1e-3 bar against the fp64 oracle)")
         del Yb
 
     # ------------------------------------------------------------------ pack throughput (one-off conversion)
