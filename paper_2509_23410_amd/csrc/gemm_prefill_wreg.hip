@@ -739,7 +739,8 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
 
     // accumulator (s, cb), register r: feature nrow + 16 (4 sh + s) + 4 q + r, row m0 + 16 cb + col.
     // Stored from there, one instruction writes 16 rows x 64 bytes (half cache lines); a compute unit then takes about
-    // 10 us for its 256 KB however idle the memory is, and longer for a bf16 Y (quarter lines).  So every column block
+    // 7 us for its 256 KB however idle the memory is, and a bf16 Y (quarter lines) is bound by the pattern, not by its
+    // bytes (patch_probe_store_tiles runs both patterns on their own).  So every column block
     // (16 rows x this wavefront's 64 features) is turned through 4 KB of LDS of the wavefront's own, behind the X ring
     // (no barrier: a wavefront's LDS instructions execute in order): written as it lies in the registers, read back
     // as 4 rows x 256 contiguous bytes per instruction.  16-byte chunk c of row r sits at chunk c ^ r: the 16 lanes
@@ -769,18 +770,18 @@ __global__ __launch_bounds__(256) void prefill_kernel_wreg(const uint16_t* __res
             /* element offset of this lane's four features: a workspace slot (MODE 2), a workspace slice (MODE 1), Y */ \
             const int64_t ye = MODE == 2 ? ((int64_t)(bid - t0) * gridDim.y + blockIdx.y) * (kWrBM * kWrBN) + (16 * CB + r) * kWrBN + 128 * tr + 64 * sh + 4 * ch \
                                          : (MODE == 1 ? (int64_t)blockIdx.y * M * N : 0) + m * N + nrow + 64 * sh + 4 * ch;     \
-            if (MODE == 2 || m < M) store4(Y, ye, o[j], YB);                                                       \
+            if (MODE == 2 || m < M) store4(Y, ye, o[j], PATCH_WR_YB);                                                       \
         }                                                                                                          \
     }
         // (the bf16 choice is taken once, not per store: MODE 1 / 2 write fp32 partial products, their sum is rounded by the reduction)
         if (MODE == 0 && ybf16) {
-#define YB 1
+#define PATCH_WR_YB 1
             PATCH_WR_16(PATCH_WR_STORE)
-#undef YB
+#undef PATCH_WR_YB
         } else {
-#define YB 0
+#define PATCH_WR_YB 0
             PATCH_WR_16(PATCH_WR_STORE)
-#undef YB
+#undef PATCH_WR_YB
         }
 #undef PATCH_WR_STAGE
 #undef PATCH_WR_STORE
