@@ -793,6 +793,16 @@ def main():
                     st[f"{'bf16' if bf else 'fp32'}_{rows_ // 256 * 43}_tiles_{pname}_us"] = round(t_ * 1e6, 1)
             del Ys
         ceil["store_tiles"] = st
+        # LDS read rate of a compute unit with four wavefronts (the prefill kernel's X fragments): 128 KB per 64-column step
+        lout = torch.empty(n_cus * 256, device=dev, dtype=torch.float32)
+        l_iters = 20000
+        fn = lambda _i: B.patch_probe_lds_read(n_cus, l_iters, lout, stream)
+        timed(fn, 2)
+        t_ = min(timed(fn, 3) / 3 for _ in range(3))
+        ceil["lds_read_GBps_per_cu_4_wavefronts"] = round(l_iters * 32768 / t_ / 1e9, 1)
+        ceil["lds_read_note"] = ("conflict-free ds_read_b128, 8 in flight per wavefront, one workgroup of 4 wavefronts per compute unit, no "
+                                 "other work (the clock is not held down by matrix instructions as it is in the product kernels)")
+        del lout
         ceil["store_tiles_note"] = ("stores only, 4 wavefronts x 64 store instructions per tile: 16 rows x 64 bytes per instruction is the "
                                     "accumulator layout stored as it lies, 4 rows x 256 bytes the same data after a turn through LDS (what the "
                                     "prefill kernels do); 688 tiles = 2.7 rounds of the chip, bound by the HBM write rate in either pattern "

@@ -392,6 +392,9 @@ patch_status patch_deserialize4(const void* buf, size_t bytes, void* stream, pat
  *                            pattern 0 = 16 rows x 64 bytes per instruction (the accumulator layout stored as it lies),
  *                            pattern 1 = 4 rows x 256 contiguous bytes (after a turn through LDS); with bf16 half the
  *                            bytes per lane.  The values written are arbitrary.
+ *   patch_probe_lds_read     LDS reads only: `workgroups` workgroups of 4 wavefronts, each wavefront reading its own
+ *                            8 KB of LDS with conflict-free 128-bit reads, 8 in flight, `iters` times (bytes per
+ *                            workgroup = iters * 32 KB).  out: DEVICE, workgroups * 256 floats.
  * Errors: PATCH_ERR_ARG, PATCH_ERR_SIZE (a buffer too small), PATCH_ERR_HIP.
  */
 #define PATCH_PROBE_OPERAND_BYTES ((size_t)12 * 256 * 16)
@@ -402,6 +405,7 @@ patch_status patch_probe_stream_read(const void* src, size_t bytes, int workgrou
 patch_status patch_probe_lds_fill(int kind, const void* src, size_t bytes, int workgroups, int rounds, void* out, size_t out_bytes,
                                   void* stream);
 patch_status patch_probe_store_tiles(int pattern, int bf16, void* Y, size_t y_bytes, int64_t M, int64_t N, void* stream);
+patch_status patch_probe_lds_read(int workgroups, int iters, void* out, size_t out_bytes, void* stream);
 
 void patch_free(patch_packed* P);
 const char* patch_strerror(patch_status s);

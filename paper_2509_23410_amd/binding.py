@@ -23,7 +23,7 @@ EXPORTS = [
     "patch_tune_table_get", "patch_tune_table_export", "patch_tune_table_import", "patch_tune_layer", "patch_unpack",
     "patch_pack4", "patch_pack_from4", "patch_gemm4", "patch_gemm4_many", "patch_unpack4", "patch_packed4_bytes", "patch_packed4_dims", "patch_free4",
     "patch_canonical_sizes", "patch_export_canonical", "patch_packed_bytes", "patch_table_bytes", "patch_packed_dims",
-    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_probe_store_tiles", "patch_gemm4_ex",
+    "patch_packed_tile_map", "patch_packed_row_order", "patch_probe_matrix_rate", "patch_probe_stream_read", "patch_probe_lds_fill", "patch_probe_store_tiles", "patch_probe_lds_read", "patch_gemm4_ex",
     "patch_serialized_bytes", "patch_serialize", "patch_deserialize", "patch_serialized4_bytes", "patch_serialize4", "patch_deserialize4", "patch_free", "patch_strerror", "patch_last_hip_error", "patch_version",
 ]
 
@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
         L.patch_probe_lds_fill.restype = ci
         L.patch_probe_store_tiles.argtypes = [ci, ci, vp, sz, i64, i64, vp]
         L.patch_probe_store_tiles.restype = ci
+        L.patch_probe_lds_read.argtypes = [ci, ci, vp, sz, vp]
+        L.patch_probe_lds_read.restype = ci
         L.patch_pack4.argtypes = [vp, i64, i64, vp, ci, vp, ctypes.POINTER(vp)]
         L.patch_pack4.restype = ci
         L.patch_gemm4.argtypes = [vp, i64, vp, vp, vp]
@@ -517,6 +519,11 @@ def patch_probe_lds_fill(kind: int, src, nbytes: int, workgroups: int, rounds: i
     """The 48 KB-per-round fetch pattern of the LDS-staged prefill kernel on its own (see include/patch.h)."""
     _check(lib().patch_probe_lds_fill(kind, _ptr(src), nbytes, workgroups, rounds, _ptr(out), out.numel() * out.element_size(), stream),
            "patch_probe_lds_fill")
+
+
+def patch_probe_lds_read(workgroups: int, iters: int, out, stream: int = 0) -> None:
+    """Conflict-free 128-bit LDS reads by workgroups of 4 wavefronts, iters * 32 KB per workgroup (see include/patch.h)."""
+    _check(lib().patch_probe_lds_read(workgroups, iters, _ptr(out), out.numel() * out.element_size(), stream), "patch_probe_lds_read")
 
 
 def patch_probe_store_tiles(pattern: int, bf16: bool, Y, M: int, N: int, stream: int = 0) -> None:

@@ -4,6 +4,7 @@
 //                       traffic inside the loop
 //   stream_read_kernel  128-bit streaming read of a buffer (the HBM bound of the decode path)
 //   store_tiles_kernel  the output stage of a prefill workgroup on its own, in two store patterns
+//   lds_read_kernel     what four wavefronts of a compute unit read from LDS (the X fragments of the prefill kernels)
 // They compute nothing of the method; the caller times them with events on the stream it passes.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -224,6 +225,30 @@ __global__ __launch_bounds__(256) void store_tiles_kernel(void* __restrict__ Y, 
     }
 }
 
+// LDS reads only: a workgroup of 4 wavefronts (one per SIMD, as in the 256 x 256 prefill kernel), each reading its own
+// 8 KB of a 32 KB buffer with ds_read_b128 - 64 lanes x 16 contiguous bytes, conflict-free - eight reads in flight,
+// `iters` times.  Bytes per workgroup = iters * 8 * 1 KB * 4.
+__global__ __launch_bounds__(256) void lds_read_kernel(int iters, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) float buf[8192];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < 8192; i += 256) buf[i] = (float)i;
+    __syncthreads();
+    const uint32_t a = (uint32_t)(size_t)((__attribute__((address_space(3))) void*)buf) + (tid & 63) * 16 + (tid >> 6) * 8192;
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        cl_f32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+        asm volatile(
+            "ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:1024\n\tds_read_b128 %2, %8 offset:2048\n\tds_read_b128 %3, %8 offset:3072\n\t"
+            "ds_read_b128 %4, %8 offset:4096\n\tds_read_b128 %5, %8 offset:5120\n\tds_read_b128 %6, %8 offset:6144\n\tds_read_b128 %7, %8 offset:7168\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+            : "v"(a)
+            : "memory");
+        acc += r0[0] + r1[0] + r2[0] + r3[0] + r4[0] + r5[0] + r6[0] + r7[0];
+    }
+    out[(size_t)blockIdx.x * 256 + tid] = acc;
+}
+
 }  // namespace patch
 
 extern "C" {
@@ -287,6 +312,14 @@ patch_status patch_probe_store_tiles(int pattern, int bf16, void* Y, size_t y_by
     else if (pattern == 0) hipLaunchKernelGGL((patch::store_tiles_kernel<0, 1>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
     else if (!bf16) hipLaunchKernelGGL((patch::store_tiles_kernel<1, 0>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
     else hipLaunchKernelGGL((patch::store_tiles_kernel<1, 1>), dim3((unsigned)tiles), dim3(256), 0, s, Y, (long)N, tn);
+    return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
+}
+
+patch_status patch_probe_lds_read(int workgroups, int iters, void* out, size_t out_bytes, void* stream) {
+    if (!out || workgroups < 1 || workgroups > 65536 || iters < 1) return PATCH_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(out) & 3u) return PATCH_ERR_ARG;
+    if (out_bytes < (size_t)workgroups * 256 * sizeof(float)) return PATCH_ERR_SIZE;
+    hipLaunchKernelGGL(patch::lds_read_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters, static_cast<float*>(out));
     return hipGetLastError() == hipSuccess ? PATCH_OK : PATCH_ERR_HIP;
 }
 

@@ -68,6 +68,8 @@ def test_argument_errors_without_device():
     assert L.patch_probe_lds_fill(5, fake, 1 << 20, 1, 1, fake, 1 << 20, 0) == B.ERR_ARG
     assert L.patch_probe_lds_fill(0, fake, 1000, 1, 1, fake, 1 << 20, 0) == B.ERR_SIZE        # less than one 48 KB chunk
     assert L.patch_probe_lds_fill(0, fake, 1 << 20, 4, 1, fake, 1024, 0) == B.ERR_SIZE        # out too small
+    assert L.patch_probe_lds_read(0, 10, fake, 1 << 20, 0) == B.ERR_ARG
+    assert L.patch_probe_lds_read(4, 10, fake, 4 * 256 * 4 - 1, 0) == B.ERR_SIZE              # out too small
     assert L.patch_probe_store_tiles(2, 0, fake, 1 << 30, 256, 256, 0) == B.ERR_ARG           # no such pattern
     assert L.patch_probe_store_tiles(0, 0, fake, 1 << 30, 256, 300, 0) == B.ERR_ARG           # N not a multiple of 256
     assert L.patch_probe_store_tiles(0, 0, fake, 256 * 256 * 4 - 1, 256, 256, 0) == B.ERR_SIZE  # Y smaller than M x N fp32
