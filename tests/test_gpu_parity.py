@@ -1226,3 +1226,18 @@ def test_store_probe_stays_inside_its_matrix(dev):
             torch.cuda.synchronize()
             assert bool((buf[:guard] == -7.0).all()) and bool((buf[guard + M * N:] == -7.0).all()), "wrote outside Y"
             assert bool((Y >= 0).all()), f"pattern {pattern}, bf16 {bf16}: elements left unwritten"
+
+
+def test_lds_read_probe_runs(dev):
+    """patch_probe_lds_read (bench.py's ceilings section): every lane sums the first float of its eight 16-byte pieces per
+    pass over a buffer filled with buf[i] = i, so its result is known exactly."""
+    wgs, iters = 8, 3
+    out = torch.full((wgs * 256,), -1.0, device=dev, dtype=torch.float32)
+    B.patch_probe_lds_read(wgs, iters, out, stream())
+    torch.cuda.synchronize()
+    lane = torch.arange(256, device=dev) % 64
+    wave = torch.arange(256, device=dev) // 64
+    first = (lane * 16 + wave * 8192) // 4                       # float index of the lane's first piece
+    per_pass = sum((first + o // 4).float() for o in range(0, 8192, 1024))
+    expect = (per_pass * iters).repeat(wgs)
+    assert torch.equal(out, expect)
